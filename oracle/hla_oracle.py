@@ -1,0 +1,311 @@
+"""CPU oracle for non-causal Hadamard Linear Attention (HLA), fp64, numpy.
+
+TEST INFRASTRUCTURE ONLY.  This file defines what the GPU library must compute; it is
+deliberately plain and slow.  It shares no code with the HIP path and must never be imported by
+the product package: only tests, the smoke check and the bench's cpu_baseline leg call it.
+
+Every function works on ONE attention unit (one sequence of one head) with 2-D float64 arrays;
+`hla_operator_forward/backward` loop such units over batch, heads and packed sequences.
+
+Notation follows the paper: N tokens, head dim d, feature dim d_phi, Hadamard degree F,
+D = d_phi**F.  qf = phi_q(Q) is [N, d_phi]; kfs = [phi_k1(K), ..., phi_kF(K)], each [N, d_phi];
+v is [N, d].
+
+Pins (tests/test_oracle_*.py): brute force == factorized; F=1 == textbook linear attention;
+d_phi=1, identical-key, one-hot and N=1 closed forms; row normalisation; convexity; permutation
+invariance; homogeneity (rational-function form); the sequential state update; Lemma 4.1; GELU
+against tabulated normal-CDF values; both backward routes against central finite differences.
+No function here is "parity unpinned".
+"""
+from __future__ import annotations
+
+import math
+import string
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+from scipy.special import erf as _erf
+
+F64 = np.float64
+
+
+# --------------------------------------------------------------------------------------------
+# Feature maps phi (App. A.1; Alg. 1 Step 4): Linear(d->d) -> GELU -> Linear(d->d_phi) -> ReLU
+# --------------------------------------------------------------------------------------------
+def gelu_erf(h: np.ndarray) -> np.ndarray:
+    """Exact GELU: h * Phi(h), Phi the standard normal CDF = (1 + erf(h/sqrt 2)) / 2."""
+    h = np.asarray(h, dtype=F64)
+    return h * 0.5 * (1.0 + _erf(h / math.sqrt(2.0)))
+
+
+def gelu_erf_grad(h: np.ndarray) -> np.ndarray:
+    """d/dh [h Phi(h)] = Phi(h) + h * pdf(h), pdf the standard normal density."""
+    h = np.asarray(h, dtype=F64)
+    cdf = 0.5 * (1.0 + _erf(h / math.sqrt(2.0)))
+    pdf = np.exp(-0.5 * h * h) / math.sqrt(2.0 * math.pi)
+    return cdf + h * pdf
+
+
+def phi_forward(x, W1, b1, W2, b2):
+    """phi(x) = max(GELU(x W1 + b1) W2 + b2, 0)  (App. A.1: two linear layers, GELU between,
+    ReLU after; weights act from the right, W1 is [d, d], W2 is [d, d_phi]).
+
+    Returns (features [N, d_phi], pre-activation h [N, d], pre-ReLU u [N, d_phi])."""
+    x = np.asarray(x, dtype=F64)
+    h = x @ np.asarray(W1, F64) + np.asarray(b1, F64)
+    g = gelu_erf(h)
+    u = g @ np.asarray(W2, F64) + np.asarray(b2, F64)
+    return np.maximum(u, 0.0), h, u
+
+
+def phi_backward(dfeat, x, W1, b1, W2, b2):
+    """Gradient of a scalar loss w.r.t. x given its gradient w.r.t. phi(x) (chain rule through
+    ReLU, the second linear layer, GELU and the first linear layer of App. A.1)."""
+    _, h, u = phi_forward(x, W1, b1, W2, b2)
+    du = np.asarray(dfeat, F64) * (u > 0.0)
+    dg = du @ np.asarray(W2, F64).T
+    dh = dg * gelu_erf_grad(h)
+    return dh @ np.asarray(W1, F64).T
+
+
+# --------------------------------------------------------------------------------------------
+# Outer-product feature tensors (Sec. 4.2, definition of T_q and T_k before Theorem 4.2)
+# --------------------------------------------------------------------------------------------
+def outer_features(feats: Sequence[np.ndarray]) -> np.ndarray:
+    """Per token n: feats[0][n] (x) feats[1][n] (x) ... flattened to length d_phi**F, slot f of
+    the outer product belonging to feats[f] (first slot slowest, as the listings' einsum
+    'bhsd,bhse,bhsf->bhsdef' followed by a flatten)."""
+    n = feats[0].shape[0]
+    t = np.asarray(feats[0], F64)
+    for f in feats[1:]:
+        t = (t[:, :, None] * np.asarray(f, F64)[:, None, :]).reshape(n, -1)
+    return t
+
+
+# --------------------------------------------------------------------------------------------
+# Forward
+# --------------------------------------------------------------------------------------------
+def hla_bruteforce(qf, kfs, v, eps: float):
+    """The plain definition (Eq. 'hla' + row normalisation of Sec. 4.2), O(N^2):
+    A_ij = prod_f <qf_i, kf_f,j>,  eta_i = sum_j A_ij,  o_i = sum_j A_ij v_j / (eta_i + eps)."""
+    qf = np.asarray(qf, F64)
+    v = np.asarray(v, F64)
+    A = np.ones((qf.shape[0], v.shape[0]), dtype=F64)
+    for kf in kfs:
+        A = A * (qf @ np.asarray(kf, F64).T)
+    eta = A.sum(axis=1)
+    o = (A @ v) / (eta + eps)[:, None]
+    return o, A, eta
+
+
+def hla_state(kfs, v):
+    """Key-side state of Theorem 4.2: context C = T_k (x)_1 V  [D, d] and the key-feature sum
+    z = sum_j T_k,j  [D] that the normaliser eta contracts against."""
+    Tk = outer_features(kfs)
+    v = np.asarray(v, F64)
+    return Tk.T @ v, Tk.sum(axis=0)
+
+
+def hla_factorized(qf, kfs, v, eps: float):
+    """The paper's linear-time scheme (Theorem 4.2, normaliser eta of Sec. 4.2; same steps as
+    the listings for 2 and 3 factors, any F): C, z from the keys; T_q from the queries;
+    num_i = T_q,i . C, eta_i = T_q,i . z, o_i = num_i / (eta_i + eps)."""
+    C, z = hla_state(kfs, v)
+    Tq = outer_features([qf] * len(kfs))
+    eta = Tq @ z
+    o = (Tq @ C) / (eta + eps)[:, None]
+    return o, C, z, eta
+
+
+def hla_sequential_state(kfs, v):
+    """Token-by-token update C^i = C^{i-1} + T_k,i (Kronecker) v_i (Sec. 4.4, sequential
+    updates); returns the final (C^N, z^N).  Python loop: small inputs only."""
+    kfs = [np.asarray(k, F64) for k in kfs]
+    v = np.asarray(v, F64)
+    D = kfs[0].shape[1] ** len(kfs)
+    C = np.zeros((D, v.shape[1]), F64)
+    z = np.zeros(D, F64)
+    for i in range(v.shape[0]):
+        t = outer_features([k[i:i + 1] for k in kfs])[0]
+        C += np.outer(t, v[i])
+        z += t
+    return C, z
+
+
+# --------------------------------------------------------------------------------------------
+# Backward (the paper leaves this to autograd; derived from the factorized form)
+# --------------------------------------------------------------------------------------------
+def _slot_gradient(dT: np.ndarray, feats: Sequence[np.ndarray], slot: int) -> np.ndarray:
+    """Given dT [N, d_phi, ..., d_phi] (gradient w.r.t. the outer product of `feats`), return
+    the gradient w.r.t. feats[slot] holding the other factors fixed:
+    out[n, a] = sum over the other indices of dT[n, .., a at `slot`, ..] * prod_{f != slot} feats[f][n, .]"""
+    F = len(feats)
+    letters = string.ascii_lowercase[:F]
+    operands = [dT]
+    spec = ["n" + letters]
+    for f in range(F):
+        if f != slot:
+            operands.append(np.asarray(feats[f], F64))
+            spec.append("n" + letters[f])
+    return np.einsum(",".join(spec) + "->n" + letters[slot], *operands)
+
+
+def hla_backward_factorized(qf, kfs, v, do, eps: float):
+    """Gradients of L = sum(O * dO) through the factorized form.  With den_i = eta_i + eps,
+    g_i = dO_i / den_i, s_i = -<dO_i, o_i> / den_i:
+      dT_q,i = C g_i + s_i z;   dC = sum_i T_q,i (x) g_i;   dz = sum_i s_i T_q,i;
+      dT_k,j = dC v_j + dz;     dv_j = dC^T T_k,j;
+    and every feature vector collects the gradient of each outer-product slot it fills.
+    Returns (dqf [N,d_phi], [dkf_1..dkf_F], dv [N,d])."""
+    qf = np.asarray(qf, F64)
+    kfs = [np.asarray(k, F64) for k in kfs]
+    v = np.asarray(v, F64)
+    do = np.asarray(do, F64)
+    F = len(kfs)
+    n, dp = qf.shape
+    o, C, z, eta = hla_factorized(qf, kfs, v, eps)
+    den = eta + eps
+    g = do / den[:, None]
+    s = -(do * o).sum(axis=1) / den
+    Tq = outer_features([qf] * F)
+    Tk = outer_features(kfs)
+    dTq = g @ C.T + s[:, None] * z[None, :]
+    dC = Tq.T @ g
+    dz = Tq.T @ s
+    dTk = v @ dC.T + dz[None, :]
+    dv = Tk @ dC
+    shape = (n,) + (dp,) * F
+    dTq = dTq.reshape(shape)
+    dTk = dTk.reshape((v.shape[0],) + (dp,) * F)
+    dqf = np.zeros_like(qf)
+    for slot in range(F):
+        dqf += _slot_gradient(dTq, [qf] * F, slot)
+    dkfs = [_slot_gradient(dTk, kfs, slot) for slot in range(F)]
+    return dqf, dkfs, dv
+
+
+def hla_backward_bruteforce(qf, kfs, v, do, eps: float):
+    """Same gradients through the explicit N x N matrix (independent route):
+    dA_ij = <g_i, v_j> + s_i;  with P^f_ij = <qf_i, kf_f,j>,  dP^f = dA * prod_{f' != f} P^f';
+    dqf = sum_f dP^f kf_f;  dkf_f = dP^f^T qf;  dv = A^T g."""
+    qf = np.asarray(qf, F64)
+    kfs = [np.asarray(k, F64) for k in kfs]
+    v = np.asarray(v, F64)
+    do = np.asarray(do, F64)
+    o, A, eta = hla_bruteforce(qf, kfs, v, eps)
+    den = eta + eps
+    g = do / den[:, None]
+    s = -(do * o).sum(axis=1) / den
+    dA = g @ v.T + s[:, None]
+    P = [qf @ k.T for k in kfs]
+    dqf = np.zeros_like(qf)
+    dkfs = []
+    for f in range(len(kfs)):
+        others = np.ones_like(A)
+        for f2 in range(len(kfs)):
+            if f2 != f:
+                others = others * P[f2]
+        dP = dA * others
+        dqf += dP @ kfs[f]
+        dkfs.append(dP.T @ qf)
+    dv = A.T @ g
+    return dqf, dkfs, dv
+
+
+# --------------------------------------------------------------------------------------------
+# Whole operator over batch / heads / packed sequences (Alg. 1 Steps 4-5)
+# --------------------------------------------------------------------------------------------
+class PhiWeights:
+    """Weights of one feature map: W1 [d,d], b1 [d], W2 [d,d_phi], b2 [d_phi]; shared by all
+    heads (App. A.1 sizes the first layer by the head dimension)."""
+
+    def __init__(self, W1, b1, W2, b2):
+        self.W1 = np.asarray(W1, F64)
+        self.b1 = np.asarray(b1, F64)
+        self.W2 = np.asarray(W2, F64)
+        self.b2 = np.asarray(b2, F64)
+
+    def astuple(self):
+        return self.W1, self.b1, self.W2, self.b2
+
+
+def _units(B: int, N: int, cu_seqlens: Optional[Sequence[int]]):
+    """(batch index, first token, one-past-last token) of every independent sequence."""
+    if cu_seqlens is None:
+        return [(b, 0, N) for b in range(B)]
+    if B != 1:
+        raise ValueError("packed input needs B == 1")
+    cu = list(cu_seqlens)
+    return [(0, cu[s], cu[s + 1]) for s in range(len(cu) - 1)]
+
+
+def _features(Q, K, lo, hi, b, h, F, d_phi, phi: Optional[Sequence[PhiWeights]]):
+    if phi is None:  # features handed in: Q is [.., d_phi], K is [.., F*d_phi] factor-major
+        qf = np.asarray(Q[b, h, lo:hi], F64)
+        kk = np.asarray(K[b, h, lo:hi], F64)
+        kfs = [kk[:, f * d_phi:(f + 1) * d_phi] for f in range(F)]
+    else:
+        qf = phi_forward(Q[b, h, lo:hi], *phi[0].astuple())[0]
+        kfs = [phi_forward(K[b, h, lo:hi], *phi[1 + f].astuple())[0] for f in range(F)]
+    return qf, kfs
+
+
+def hla_operator_forward(Q, K, V, F: int, d_phi: int, eps: float,
+                         phi: Optional[Sequence[PhiWeights]] = None,
+                         cu_seqlens: Optional[Sequence[int]] = None,
+                         route: str = "factorized") -> np.ndarray:
+    """O [B,H,N,d] for Q,K,V [B,H,N,*].  `phi` = [phi_q, phi_k1..phi_kF] or None when Q and K
+    already hold features.  Sequences (batch entries, or the packed ranges of cu_seqlens) never
+    share state."""
+    B, H, N = V.shape[:3]
+    O = np.zeros(V.shape, F64)
+    for (b, lo, hi) in _units(B, N, cu_seqlens):
+        if hi == lo:
+            continue
+        for h in range(H):
+            qf, kfs = _features(Q, K, lo, hi, b, h, F, d_phi, phi)
+            v = np.asarray(V[b, h, lo:hi], F64)
+            if route == "factorized":
+                O[b, h, lo:hi] = hla_factorized(qf, kfs, v, eps)[0]
+            elif route == "bruteforce":
+                O[b, h, lo:hi] = hla_bruteforce(qf, kfs, v, eps)[0]
+            else:
+                raise ValueError(route)
+    return O
+
+
+def hla_operator_backward(Q, K, V, dO, F: int, d_phi: int, eps: float,
+                          phi: Optional[Sequence[PhiWeights]] = None,
+                          cu_seqlens: Optional[Sequence[int]] = None,
+                          route: str = "factorized"):
+    """(dQ, dK, dV) with the shapes of Q, K, V for L = sum(O * dO).  With feature maps, dK sums
+    the contributions of the F key maps (they all read the same K)."""
+    B, H, N = V.shape[:3]
+    dQ = np.zeros(Q.shape, F64)
+    dK = np.zeros(K.shape, F64)
+    dV = np.zeros(V.shape, F64)
+    bwd = hla_backward_factorized if route == "factorized" else hla_backward_bruteforce
+    for (b, lo, hi) in _units(B, N, cu_seqlens):
+        if hi == lo:
+            continue
+        for h in range(H):
+            qf, kfs = _features(Q, K, lo, hi, b, h, F, d_phi, phi)
+            v = np.asarray(V[b, h, lo:hi], F64)
+            dqf, dkfs, dv = bwd(qf, kfs, v, dO[b, h, lo:hi], eps)
+            dV[b, h, lo:hi] = dv
+            if phi is None:
+                dQ[b, h, lo:hi] = dqf
+                dK[b, h, lo:hi] = np.concatenate(dkfs, axis=1)
+            else:
+                dQ[b, h, lo:hi] = phi_backward(dqf, Q[b, h, lo:hi], *phi[0].astuple())
+                acc = np.zeros((hi - lo, K.shape[-1]), F64)
+                for f in range(F):
+                    acc += phi_backward(dkfs[f], K[b, h, lo:hi], *phi[1 + f].astuple())
+                dK[b, h, lo:hi] = acc
+    return dQ, dK, dV
+
+
+def hla_bruteforce_rows(qf_rows, kfs, v, eps: float) -> np.ndarray:
+    """Brute-force outputs for a subset of query rows against ALL keys: O(rows * N).  Used to
+    spot-check full-size problems against the plain definition."""
+    return hla_bruteforce(qf_rows, kfs, v, eps)[0]

@@ -1,0 +1,130 @@
+"""Pins for the oracle's backward: central finite differences of the forward (which is itself
+pinned in test_oracle_forward.py), agreement of the two independent gradient routes, and
+structural facts (scale invariance => <dq, q> = 0; linearity in V)."""
+import numpy as np
+import pytest
+
+from oracle import hla_oracle as orc
+
+
+def _loss_feats(q, ks, v, do, eps):
+    return float((orc.hla_bruteforce(q, ks, v, eps)[0] * do).sum())
+
+
+def _fd(fun, x, h=1e-6):
+    g = np.zeros_like(x)
+    it = np.nditer(x, flags=["multi_index"])
+    for _ in it:
+        i = it.multi_index
+        old = x[i]
+        x[i] = old + h
+        fp = fun()
+        x[i] = old - h
+        fm = fun()
+        x[i] = old
+        g[i] = (fp - fm) / (2 * h)
+    return g
+
+
+@pytest.mark.parametrize("F,dp", [(1, 5), (2, 4), (3, 3), (3, 6)])
+def test_feature_level_backward_against_finite_differences(F, dp):
+    rng = np.random.default_rng(30 + F * 10 + dp)
+    n, d, eps = 7, 3, 1e-3
+    q = np.abs(rng.standard_normal((n, dp))) + 0.2
+    ks = [np.abs(rng.standard_normal((n, dp))) + 0.2 for _ in range(F)]
+    v = rng.standard_normal((n, d))
+    do = rng.standard_normal((n, d))
+    for route in (orc.hla_backward_factorized, orc.hla_backward_bruteforce):
+        dq, dks, dv = route(q, ks, v, do, eps)
+        f = lambda: _loss_feats(q, ks, v, do, eps)
+        np.testing.assert_allclose(dq, _fd(f, q), rtol=2e-7, atol=1e-8)
+        for a in range(F):
+            np.testing.assert_allclose(dks[a], _fd(f, ks[a]), rtol=2e-7, atol=1e-8)
+        np.testing.assert_allclose(dv, _fd(f, v), rtol=2e-7, atol=1e-8)
+
+
+@pytest.mark.parametrize("F,dp", [(2, 12), (3, 6)])
+def test_backward_routes_agree(F, dp):
+    rng = np.random.default_rng(40 + F)
+    n, d = 50, 8
+    q = np.abs(rng.standard_normal((n, dp)))
+    ks = [np.abs(rng.standard_normal((n, dp))) for _ in range(F)]
+    v = rng.standard_normal((n, d))
+    do = rng.standard_normal((n, d))
+    a = orc.hla_backward_factorized(q, ks, v, do, 1e-6)
+    b = orc.hla_backward_bruteforce(q, ks, v, do, 1e-6)
+    np.testing.assert_allclose(a[0], b[0], rtol=1e-9, atol=1e-12)
+    for x, y in zip(a[1], b[1]):
+        np.testing.assert_allclose(x, y, rtol=1e-9, atol=1e-12)
+    np.testing.assert_allclose(a[2], b[2], rtol=1e-9, atol=1e-12)
+
+
+def test_scale_invariance_makes_query_gradient_orthogonal():
+    # eps = 0: the output does not change when a query's features are rescaled, so the gradient
+    # has no component along the features; the same holds for each key map scaled as a whole.
+    rng = np.random.default_rng(50)
+    n, dp, d, F = 20, 6, 5, 3
+    q = np.abs(rng.standard_normal((n, dp)))
+    ks = [np.abs(rng.standard_normal((n, dp))) for _ in range(F)]
+    v = rng.standard_normal((n, d))
+    do = rng.standard_normal((n, d))
+    dq, dks, dv = orc.hla_backward_factorized(q, ks, v, do, 0.0)
+    scale = np.abs(dq).max() * np.abs(q).max()
+    assert np.abs((dq * q).sum(1)).max() <= 1e-12 * scale * dp
+    for f in range(F):
+        assert abs((dks[f] * ks[f]).sum()) <= 1e-10 * np.abs(dks[f]).sum() * np.abs(ks[f]).max()
+    # linear in V: dV does not depend on V, and <dV, V> = L
+    dv2 = orc.hla_backward_factorized(q, ks, 3.0 * v + 1.0, do, 0.0)[2]
+    np.testing.assert_allclose(dv2, dv, rtol=1e-11, atol=1e-13)
+    L = _loss_feats(q, ks, v, do, 0.0)
+    assert abs((dv * v).sum() - L) <= 1e-11 * max(1.0, abs(L))
+
+
+def test_phi_backward_against_finite_differences():
+    rng = np.random.default_rng(51)
+    n, d, dp = 5, 6, 4
+    x = rng.standard_normal((n, d))
+    W1, b1 = rng.standard_normal((d, d)), rng.standard_normal(d)
+    W2, b2 = rng.standard_normal((d, dp)), rng.standard_normal(dp)
+    w = rng.standard_normal((n, dp))
+    f = lambda: float((orc.phi_forward(x, W1, b1, W2, b2)[0] * w).sum())
+    dx = orc.phi_backward(w, x, W1, b1, W2, b2)
+    np.testing.assert_allclose(dx, _fd(f, x), rtol=1e-6, atol=1e-8)
+    # clipped features pass no gradient
+    feat = orc.phi_forward(x, W1, b1, W2, b2)[0]
+    assert (feat == 0).any()
+    w0 = np.where(feat == 0, w, 0.0)
+    assert np.all(orc.phi_backward(w0, x, W1, b1, W2, b2) == 0.0)
+
+
+@pytest.mark.parametrize("packed", [False, True])
+def test_operator_backward_with_feature_maps_against_finite_differences(packed):
+    rng = np.random.default_rng(52)
+    B, H, N, d, F, dp = (1, 2, 9, 4, 3, 3) if packed else (2, 1, 5, 4, 3, 3)
+    cu = [0, 4, 9] if packed else None
+    Q, K, V, dO = (rng.standard_normal((B, H, N, d)) for _ in range(4))
+    phi = [orc.PhiWeights(rng.standard_normal((d, d)), 0.3 * rng.standard_normal(d),
+                          rng.standard_normal((d, dp)), rng.standard_normal(dp) + 1.5)
+           for _ in range(1 + F)]
+    eps = 1e-4
+    f = lambda: float((orc.hla_operator_forward(Q, K, V, F, dp, eps, phi=phi, cu_seqlens=cu,
+                                                route="bruteforce") * dO).sum())
+    for route in ("factorized", "bruteforce"):
+        dQ, dK, dV = orc.hla_operator_backward(Q, K, V, dO, F, dp, eps, phi=phi, cu_seqlens=cu,
+                                               route=route)
+        np.testing.assert_allclose(dQ, _fd(f, Q), rtol=2e-6, atol=2e-8)
+        np.testing.assert_allclose(dK, _fd(f, K), rtol=2e-6, atol=2e-8)
+        np.testing.assert_allclose(dV, _fd(f, V), rtol=2e-6, atol=2e-8)
+
+
+def test_operator_backward_feature_level_layout():
+    # K gradients come back factor-major in the last dim, matching the input layout
+    rng = np.random.default_rng(53)
+    B, H, N, d, F, dp = 1, 2, 6, 3, 2, 3
+    Q = np.abs(rng.standard_normal((B, H, N, dp))) + 0.1
+    K = np.abs(rng.standard_normal((B, H, N, F * dp))) + 0.1
+    V, dO = rng.standard_normal((B, H, N, d)), rng.standard_normal((B, H, N, d))
+    f = lambda: float((orc.hla_operator_forward(Q, K, V, F, dp, 1e-5) * dO).sum())
+    dQ, dK, dV = orc.hla_operator_backward(Q, K, V, dO, F, dp, 1e-5)
+    np.testing.assert_allclose(dK, _fd(f, K), rtol=1e-6, atol=1e-8)
+    np.testing.assert_allclose(dQ, _fd(f, Q), rtol=1e-6, atol=1e-8)
