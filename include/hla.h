@@ -1,0 +1,155 @@
+/*
+ * libhla — non-causal Hadamard Linear Attention (HLA) for AMD MI355X (gfx950).
+ *
+ * The operator (paper Sec. 4.1, Eq. "hla"; normaliser and factorized evaluation Sec. 4.2,
+ * Theorem 4.2; feature maps App. A.1 and Alg. 1 Steps 4-5):
+ *
+ *     A_ij  = prod_{f=1..F} < phi_q(q_i), phi_kf(k_j) >          (Hadamard product of F score matrices)
+ *     eta_i = sum_j A_ij
+ *     o_i   = sum_j A_ij v_j / (eta_i + eps)
+ *
+ * evaluated in O(N) through the key-side state  C = sum_j T_k,j (x) v_j,  z = sum_j T_k,j  with
+ * T_k,j = phi_k1(k_j) (x) ... (x) phi_kF(k_j), and the query-side contraction with
+ * T_q,i = phi_q(q_i) (x) ... (x) phi_q(q_i).  The N x N matrix is never formed.
+ *
+ * Plain C ABI: no C++ or torch types cross this boundary.  Unless stated otherwise every
+ * tensor pointer is a DEVICE pointer owned by the caller; the library owns only the handle and
+ * the workspace inside it.  All work is enqueued on the HIP stream passed in; no entry point
+ * synchronises the device except hla_create / hla_destroy.  Failures are returned as codes;
+ * nothing is printed and nothing is thrown.  A handle must not be used from two streams or two
+ * host threads at the same time.
+ */
+#ifndef HLA_H_
+#define HLA_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct hla_handle hla_handle; /* opaque, library-owned */
+
+typedef enum {
+  HLA_OK = 0,
+  HLA_ERR_INVALID_ARG = 1, /* null pointer, negative size, bad cu_seqlens, size above the handle's maxima */
+  HLA_ERR_UNSUPPORTED = 2, /* (F, d_phi, d, dtype, strides) combination no kernel covers */
+  HLA_ERR_ALLOC = 3,       /* hipMalloc / host allocation failed */
+  HLA_ERR_HIP = 4,         /* a HIP runtime call failed (launch, copy) */
+  HLA_ERR_STATE = 5        /* call order: backward without weights, weights in PHI_NONE mode, ... */
+} hla_status;
+
+/* I/O element type of Q, K, V, O, dO, dQ, dK, dV and of the feature-map weights.  Accumulation
+ * and the key-side state are always fp32 (the paper does not fix a precision). */
+typedef enum { HLA_F32 = 0, HLA_BF16 = 1 } hla_dtype;
+
+/* HLA_PHI_MLP : Q and K hold raw head vectors [.., d]; the library applies the feature maps of
+ *               App. A.1 (Linear d->d, exact erf GELU, Linear d->d_phi, ReLU) — Alg. 1 Step 4.
+ * HLA_PHI_NONE: Q holds phi_q(Q) [.., d_phi] and K holds [phi_k1(K) | ... | phi_kF(K)]
+ *               [.., F*d_phi] (factor-major inside the last dim), as the paper's listings for 2
+ *               and 3 factors take them.  Features are expected >= 0 (Sec. 4.2); not checked. */
+typedef enum { HLA_PHI_MLP = 0, HLA_PHI_NONE = 1 } hla_phi_mode;
+
+/* Which kernels serve the handle.  AUTO picks the MFMA path when the configuration has one. */
+typedef enum {
+  HLA_PATH_AUTO = 0,
+  HLA_PATH_GENERIC = 1, /* fp32 vector-ALU kernels over the literal d_phi^F state; any supported shape */
+  HLA_PATH_MFMA = 2     /* bf16 matrix-core kernels; HLA_ERR_UNSUPPORTED if the shape has none */
+} hla_kernel_path;
+
+typedef struct {
+  int32_t head_dim;      /* d: 32, 64 or 128 (width of V, and of raw Q/K in PHI_MLP mode) */
+  int32_t feature_dim;   /* d_phi: paper uses 6 with F=3 and 12 with F=2 (App. A.1) */
+  int32_t degree;        /* F, number of Hadamard factors: 1..4; d_phi^F <= 256 */
+  float eps;             /* added to eta in the denominator, as in the paper's listings */
+  int32_t io_dtype;      /* hla_dtype */
+  int32_t phi_mode;      /* hla_phi_mode */
+  int32_t kernel_path;   /* hla_kernel_path */
+  int32_t max_heads;     /* largest H any call will pass */
+  int64_t max_tokens;    /* largest B*N (tokens per head, all batch rows / packed sequences) */
+  int32_t max_seqs;      /* largest number of independent sequences (B, or num_seqs when packed) */
+} hla_config;
+
+/* Weights of one feature map, device pointers in io_dtype, row-major, applied from the right:
+ * h = x W1 + b1 (W1 [d, d]), u = GELU(h) W2 + b2 (W2 [d, d_phi]), phi(x) = max(u, 0).
+ * A head stride of 0 shares that array across heads (the default reading of App. A.1: the first
+ * layer is sized by the head dimension); otherwise head h's copy starts at ptr + h * stride. */
+typedef struct {
+  const void* W1;
+  const void* b1;
+  const void* W2;
+  const void* b2;
+  int64_t head_stride_W1; /* elements; 0 = shared across heads */
+  int64_t head_stride_b1;
+  int64_t head_stride_W2;
+  int64_t head_stride_b2;
+} hla_phi_weights;
+
+/* Strided view of a [B, H, N, width] tensor; the innermost dim is contiguous.  Strides in
+ * elements.  The MFMA path additionally needs ptr and all strides 16-byte aligned. */
+typedef struct {
+  void* ptr;
+  int64_t stride_b;
+  int64_t stride_h;
+  int64_t stride_n;
+} hla_tensor;
+
+/* Create a handle and its device workspace (saved features, key-side state, partial sums) on
+ * the current HIP device.  Synchronous.  On failure *out is NULL. */
+hla_status hla_create(const hla_config* config, hla_handle** out);
+
+/* PHI_MLP only: register the 1+F feature maps in the order phi_q, phi_k1, .., phi_kF.  The
+ * library repacks them into its own workspace on `hip_stream`; the caller may free its copies
+ * once that stream work has completed.  Must be called again if the weights change. */
+hla_status hla_set_phi_weights(hla_handle* h, const hla_phi_weights* maps, int32_t num_maps,
+                               void* hip_stream);
+
+/* Forward (Alg. 1 Steps 4-5).  Q, K, V, O are [B, H, N, *] views (widths per phi_mode; V and O
+ * are [.., d]).  Dense batch: cu_seqlens = NULL, num_seqs ignored, every batch row is one
+ * sequence.  Packed: cu_seqlens is a HOST array of num_seqs+1 non-decreasing token offsets with
+ * cu_seqlens[0] = 0 and cu_seqlens[num_seqs] = N, B must be 1; sequence s owns tokens
+ * [cu[s], cu[s+1]) and shares no state with the others.  Empty sequences and N = 0 are legal and
+ * write nothing.  Keeps the features, the state and the denominators in the handle for a
+ * following hla_backward.  Output rows whose eta is 0 are 0/(0+eps) = 0. */
+hla_status hla_forward(hla_handle* h, int32_t B, int32_t H, int32_t N, const int32_t* cu_seqlens,
+                       int32_t num_seqs, hla_tensor Q, hla_tensor K, hla_tensor V, hla_tensor O,
+                       void* hip_stream);
+
+/* Backward of L = sum(O * dO) w.r.t. Q, K, V (the paper relies on autograd; the formulas follow
+ * from Theorem 4.2: g_i = dO_i/den_i, s_i = -<dO_i,o_i>/den_i, dT_q,i = C g_i + s_i z,
+ * dC = sum_i T_q,i (x) g_i, dz = sum_i s_i T_q,i, dT_k,j = dC v_j + dz, dv_j = dC^T T_k,j, then the
+ * chain rule through the outer products and, in PHI_MLP mode, the feature maps; dK sums the F
+ * key maps).  Must follow an hla_forward on the same handle with the same B, H, N, cu_seqlens,
+ * Q, K, V (HLA_ERR_STATE otherwise); O is that forward's output.  dQ, dK, dV have the shapes of
+ * Q, K, V and are fully overwritten. */
+hla_status hla_backward(hla_handle* h, int32_t B, int32_t H, int32_t N, const int32_t* cu_seqlens,
+                        int32_t num_seqs, hla_tensor Q, hla_tensor K, hla_tensor V, hla_tensor O,
+                        hla_tensor dO, hla_tensor dQ, hla_tensor dK, hla_tensor dV,
+                        void* hip_stream);
+
+/* Release the workspace.  Synchronises the device first.  NULL is accepted. */
+hla_status hla_destroy(hla_handle* h);
+
+/* Static, human-readable name of a status code. */
+const char* hla_status_string(hla_status s);
+
+/* Which path serves the handle: HLA_PATH_GENERIC or HLA_PATH_MFMA (never AUTO); -1 for NULL. */
+int32_t hla_active_path(const hla_handle* h);
+
+/* Per-kernel timing for bench harnesses.  While enabled, every kernel the handle launches is
+ * bracketed by a pair of HIP events on the caller's stream.  Enabling (or re-enabling) clears the
+ * accumulated records; at most HLA_PROFILE_MAX_RECORDS launches are recorded, later ones run
+ * untimed. */
+#define HLA_PROFILE_MAX_RECORDS 8192
+hla_status hla_profile_enable(hla_handle* h, int32_t on);
+
+/* Synchronises on the recorded events, then reports per distinct kernel: its name (static
+ * string), the summed duration in milliseconds and the number of launches.  Writes at most `cap`
+ * entries to each non-NULL HOST array and returns the number of distinct kernels recorded. */
+int32_t hla_profile_read(hla_handle* h, int32_t cap, const char** names, double* total_ms,
+                         int64_t* launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HLA_H_ */

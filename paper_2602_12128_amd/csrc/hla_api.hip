@@ -1,0 +1,394 @@
+// C-ABI entry points of libhla: argument validation, workspace ownership, token tables, path
+// dispatch and per-kernel event timing.  No arithmetic of the method lives here.
+#include <algorithm>
+#include <cstring>
+#include <new>
+
+#include "hla_handle.h"
+
+namespace hla {
+
+// ---- profiler ---------------------------------------------------------------------------------
+const char* Profiler::begin(const char* name, hipStream_t s) {
+  if (!on || n_used >= static_cast<size_t>(HLA_PROFILE_MAX_RECORDS)) return nullptr;
+  if (n_used == records.size()) {
+    ProfileRecord r{name, nullptr, nullptr};
+    if (hipEventCreate(&r.start) != hipSuccess) return nullptr;
+    if (hipEventCreate(&r.stop) != hipSuccess) {
+      (void)hipEventDestroy(r.start);
+      return nullptr;
+    }
+    records.push_back(r);
+  }
+  records[n_used].name = name;
+  (void)hipEventRecord(records[n_used].start, s);
+  pending = true;
+  return name;
+}
+void Profiler::end(hipStream_t s) {
+  if (!pending) return;
+  (void)hipEventRecord(records[n_used].stop, s);
+  ++n_used;
+  pending = false;
+}
+void Profiler::clear_records() {
+  n_used = 0;
+  pending = false;
+}
+void Profiler::destroy() {
+  for (auto& r : records) {
+    (void)hipEventDestroy(r.start);
+    (void)hipEventDestroy(r.stop);
+  }
+  records.clear();
+  n_used = 0;
+}
+
+// ---- token tables -----------------------------------------------------------------------------
+static void build_table_host(const hla_handle* hd, int32_t bs, std::vector<BlockEnt>* ents,
+                             std::vector<int32_t>* seq_off) {
+  const int nseq = static_cast<int>(hd->cu_host.size()) - 1;
+  ents->clear();
+  seq_off->assign(nseq + 1, 0);
+  for (int s = 0; s < nseq; ++s) {
+    (*seq_off)[s] = static_cast<int32_t>(ents->size());
+    const int32_t lo = hd->sig_packed ? hd->cu_host[s] : 0;
+    const int32_t hi = hd->sig_packed ? hd->cu_host[s + 1] : hd->sig_N;
+    for (int32_t t0 = lo; t0 < hi; t0 += bs)
+      ents->push_back(BlockEnt{hd->sig_packed ? 0 : s, s, t0, std::min(t0 + bs, hi)});
+  }
+  (*seq_off)[nseq] = static_cast<int32_t>(ents->size());
+}
+
+hla_status get_table(hla_handle* hd, int32_t block_tokens, hipStream_t s, hla_token_table** out) {
+  auto it = hd->tables.find(block_tokens);
+  if (it == hd->tables.end()) return HLA_ERR_STATE;  // block size not planned at create
+  hla_token_table& t = it->second;
+  if (!t.valid) {
+    std::vector<BlockEnt> ents;
+    std::vector<int32_t> seq_off;
+    build_table_host(hd, block_tokens, &ents, &seq_off);
+    if (static_cast<int64_t>(ents.size()) > t.capacity) return HLA_ERR_INVALID_ARG;
+    // pageable source: the runtime stages it before returning, so the vectors may die here
+    if (!ents.empty())
+      HLA_HIP_TRY(hipMemcpyAsync(t.dev, ents.data(), ents.size() * sizeof(BlockEnt),
+                                 hipMemcpyHostToDevice, s));
+    HLA_HIP_TRY(hipMemcpyAsync(t.seq_off_dev, seq_off.data(), seq_off.size() * sizeof(int32_t),
+                               hipMemcpyHostToDevice, s));
+    t.count = static_cast<int32_t>(ents.size());
+    t.valid = true;
+  }
+  *out = &t;
+  return HLA_OK;
+}
+
+}  // namespace hla
+
+using namespace hla;
+
+namespace {
+
+template <typename T>
+hla_status dev_alloc(T** p, size_t count) {
+  *p = nullptr;
+  if (count == 0) count = 1;
+  return hipMalloc(reinterpret_cast<void**>(p), count * sizeof(T)) == hipSuccess ? HLA_OK
+                                                                                : HLA_ERR_ALLOC;
+}
+
+void free_all(hla_handle* hd) {
+  (void)hipFree(hd->feat);
+  (void)hipFree(hd->dfeat);
+  (void)hipFree(hd->den);
+  (void)hipFree(hd->yhat);
+  (void)hipFree(hd->state);
+  (void)hipFree(hd->dstate);
+  (void)hipFree(hd->partial);
+  (void)hipFree(hd->path_ws);
+  (void)hipFree(hd->w_f32);
+  for (auto& kv : hd->tables) {
+    (void)hipFree(kv.second.dev);
+    (void)hipFree(kv.second.seq_off_dev);
+  }
+  hd->prof.destroy();
+}
+
+int64_t ipow(int64_t b, int e) {
+  int64_t r = 1;
+  for (int i = 0; i < e; ++i) r *= b;
+  return r;
+}
+
+// Validates the shape arguments shared by forward and backward and refreshes the table signature.
+hla_status prepare_call(hla_handle* hd, int32_t B, int32_t H, int32_t N, const int32_t* cu,
+                        int32_t num_seqs, bool* empty, int32_t* nseq_eff) {
+  if (hd == nullptr) return HLA_ERR_INVALID_ARG;
+  if (B < 0 || H < 0 || N < 0) return HLA_ERR_INVALID_ARG;
+  const bool packed = cu != nullptr;
+  if (packed) {
+    if (B != 1 || num_seqs < 0) return HLA_ERR_INVALID_ARG;
+    if (cu[0] != 0 || cu[num_seqs] != N) return HLA_ERR_INVALID_ARG;
+    for (int s = 0; s < num_seqs; ++s)
+      if (cu[s + 1] < cu[s]) return HLA_ERR_INVALID_ARG;
+  }
+  const int32_t nseq = packed ? num_seqs : B;
+  *nseq_eff = nseq;
+  *empty = (B == 0 || H == 0 || N == 0 || nseq == 0);
+  if (H > hd->cfg.max_heads || nseq > hd->cfg.max_seqs ||
+      static_cast<int64_t>(B) * N > hd->cfg.max_tokens)
+    return HLA_ERR_INVALID_ARG;
+  // table signature
+  bool same = hd->sig_B == B && hd->sig_N == N && hd->sig_packed == packed;
+  if (same && packed) {
+    same = static_cast<int32_t>(hd->cu_host.size()) == num_seqs + 1 &&
+           std::memcmp(hd->cu_host.data(), cu, sizeof(int32_t) * (num_seqs + 1)) == 0;
+  }
+  if (!same) {
+    hd->sig_B = B;
+    hd->sig_N = N;
+    hd->sig_packed = packed;
+    if (packed) {
+      hd->cu_host.assign(cu, cu + num_seqs + 1);
+    } else {
+      hd->cu_host.assign(static_cast<size_t>(B) + 1, 0);
+    }
+    for (auto& kv : hd->tables) kv.second.valid = false;
+  }
+  hd->g.B = B;
+  hd->g.H = H;
+  hd->g.N = N;
+  return HLA_OK;
+}
+
+bool bad_view(const hla_tensor& t) { return t.ptr == nullptr; }
+
+}  // namespace
+
+extern "C" {
+
+const char* hla_status_string(hla_status s) {
+  switch (s) {
+    case HLA_OK: return "HLA_OK";
+    case HLA_ERR_INVALID_ARG: return "HLA_ERR_INVALID_ARG";
+    case HLA_ERR_UNSUPPORTED: return "HLA_ERR_UNSUPPORTED";
+    case HLA_ERR_ALLOC: return "HLA_ERR_ALLOC";
+    case HLA_ERR_HIP: return "HLA_ERR_HIP";
+    case HLA_ERR_STATE: return "HLA_ERR_STATE";
+  }
+  return "HLA_ERR_UNKNOWN";
+}
+
+hla_status hla_create(const hla_config* c, hla_handle** out) {
+  if (out == nullptr) return HLA_ERR_INVALID_ARG;
+  *out = nullptr;
+  if (c == nullptr) return HLA_ERR_INVALID_ARG;
+  if (c->max_heads <= 0 || c->max_tokens <= 0 || c->max_seqs <= 0) return HLA_ERR_INVALID_ARG;
+  if (c->io_dtype != HLA_F32 && c->io_dtype != HLA_BF16) return HLA_ERR_INVALID_ARG;
+  if (c->phi_mode != HLA_PHI_MLP && c->phi_mode != HLA_PHI_NONE) return HLA_ERR_INVALID_ARG;
+  if (c->kernel_path < HLA_PATH_AUTO || c->kernel_path > HLA_PATH_MFMA) return HLA_ERR_INVALID_ARG;
+  if (!(c->eps >= 0.0f)) return HLA_ERR_INVALID_ARG;
+  if (c->head_dim != 32 && c->head_dim != 64 && c->head_dim != 128) return HLA_ERR_UNSUPPORTED;
+  if (c->degree < 1 || c->degree > 4 || c->feature_dim < 1) return HLA_ERR_UNSUPPORTED;
+  if (c->feature_dim > 256 || ipow(c->feature_dim, c->degree) > 256) return HLA_ERR_UNSUPPORTED;
+  if (static_cast<int64_t>(c->max_heads) * c->max_tokens >= (1ll << 31)) return HLA_ERR_UNSUPPORTED;
+
+  hla_handle* hd = new (std::nothrow) hla_handle();
+  if (hd == nullptr) return HLA_ERR_ALLOC;
+  hd->cfg = *c;
+  hd->g = Geom{};
+  hd->g.d = c->head_dim;
+  hd->g.dphi = c->feature_dim;
+  hd->g.F = c->degree;
+  hd->g.D = static_cast<int32_t>(ipow(c->feature_dim, c->degree));
+  hd->g.nfeat = (1 + c->degree) * c->feature_dim;
+  hd->g.eps = c->eps;
+  hd->max_th = static_cast<int64_t>(c->max_heads) * c->max_tokens;
+  hd->max_units = c->max_seqs * c->max_heads;
+
+  const bool mfma_ok = mfma_supported(*c);
+  if (c->kernel_path == HLA_PATH_MFMA && !mfma_ok) {
+    delete hd;
+    return HLA_ERR_UNSUPPORTED;
+  }
+  hd->path = (c->kernel_path == HLA_PATH_GENERIC || !mfma_ok) ? HLA_PATH_GENERIC : HLA_PATH_MFMA;
+
+  hla_status st = hd->path == HLA_PATH_MFMA ? mfma_workspace_plan(hd) : generic_workspace_plan(hd);
+  // allocate what the plan asked for
+  if (st == HLA_OK) st = dev_alloc(&hd->feat, hd->max_th * hd->g.nfeat);
+  if (st == HLA_OK) st = dev_alloc(&hd->dfeat, hd->max_th * hd->g.nfeat);
+  if (st == HLA_OK) st = dev_alloc(&hd->den, hd->max_th);
+  if (st == HLA_OK) st = dev_alloc(&hd->yhat, hd->yhat_floats);
+  if (st == HLA_OK) st = dev_alloc(&hd->state, hd->max_units * hd->state_stride);
+  if (st == HLA_OK) st = dev_alloc(&hd->dstate, hd->max_units * hd->state_stride);
+  if (st == HLA_OK) st = dev_alloc(&hd->partial, hd->max_chunks * c->max_heads * hd->state_stride);
+  if (st == HLA_OK && hd->path_ws_bytes > 0) {
+    char* p = nullptr;
+    st = dev_alloc(&p, hd->path_ws_bytes);
+    hd->path_ws = p;
+  }
+  if (st == HLA_OK && c->phi_mode == HLA_PHI_MLP) {
+    const int64_t per_map = static_cast<int64_t>(c->head_dim) * c->head_dim + c->head_dim +
+                            static_cast<int64_t>(c->head_dim) * c->feature_dim + c->feature_dim;
+    st = dev_alloc(&hd->w_f32, per_map * (1 + c->degree) * c->max_heads);
+  }
+  for (auto& kv : hd->tables) {
+    if (st != HLA_OK) break;
+    hla_token_table& t = kv.second;
+    t.block_tokens = kv.first;
+    t.capacity = (c->max_tokens + kv.first - 1) / kv.first + c->max_seqs;
+    st = dev_alloc(&t.dev, t.capacity);
+    if (st == HLA_OK) st = dev_alloc(&t.seq_off_dev, c->max_seqs + 1);
+  }
+  if (st != HLA_OK) {
+    free_all(hd);
+    delete hd;
+    return st;
+  }
+  if (hipDeviceSynchronize() != hipSuccess) {
+    free_all(hd);
+    delete hd;
+    return HLA_ERR_HIP;
+  }
+  *out = hd;
+  return HLA_OK;
+}
+
+hla_status hla_destroy(hla_handle* hd) {
+  if (hd == nullptr) return HLA_OK;
+  (void)hipDeviceSynchronize();
+  free_all(hd);
+  delete hd;
+  return HLA_OK;
+}
+
+int32_t hla_active_path(const hla_handle* hd) { return hd == nullptr ? -1 : hd->path; }
+
+hla_status hla_set_phi_weights(hla_handle* hd, const hla_phi_weights* maps, int32_t num_maps,
+                               void* hip_stream) {
+  if (hd == nullptr || maps == nullptr) return HLA_ERR_INVALID_ARG;
+  if (hd->cfg.phi_mode != HLA_PHI_MLP) return HLA_ERR_STATE;
+  if (num_maps != 1 + hd->cfg.degree) return HLA_ERR_INVALID_ARG;
+  for (int m = 0; m < num_maps; ++m)
+    if (!maps[m].W1 || !maps[m].b1 || !maps[m].W2 || !maps[m].b2) return HLA_ERR_INVALID_ARG;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  HLA_TRY(convert_weights_to_f32(hd, maps, s));
+  HLA_TRY(hd->path == HLA_PATH_MFMA ? mfma_set_weights(hd, s) : generic_set_weights(hd, s));
+  hd->have_weights = true;
+  hd->have_forward = false;
+  return HLA_OK;
+}
+
+hla_status hla_forward(hla_handle* hd, int32_t B, int32_t H, int32_t N, const int32_t* cu_seqlens,
+                       int32_t num_seqs, hla_tensor Q, hla_tensor K, hla_tensor V, hla_tensor O,
+                       void* hip_stream) {
+  bool empty = false;
+  int32_t nseq = 0;
+  HLA_TRY(prepare_call(hd, B, H, N, cu_seqlens, num_seqs, &empty, &nseq));
+  hd->have_forward = false;
+  if (hd->cfg.phi_mode == HLA_PHI_MLP && !hd->have_weights) return HLA_ERR_STATE;
+  if (!empty && (bad_view(Q) || bad_view(K) || bad_view(V) || bad_view(O)))
+    return HLA_ERR_INVALID_ARG;
+  hla_call_args a{};
+  a.B = B;
+  a.H = H;
+  a.N = N;
+  a.num_seqs = nseq;
+  a.packed = cu_seqlens != nullptr;
+  a.Q = make_view(Q);
+  a.K = make_view(K);
+  a.V = make_view(V);
+  a.O = make_view(O);
+  a.stream = static_cast<hipStream_t>(hip_stream);
+  if (!empty) HLA_TRY(hd->path == HLA_PATH_MFMA ? mfma_forward(hd, a) : generic_forward(hd, a));
+  hd->have_forward = true;
+  hd->fw_B = B;
+  hd->fw_H = H;
+  hd->fw_N = N;
+  hd->fw_packed = a.packed;
+  hd->fw_cu = hd->cu_host;
+  hd->fw_Q = Q.ptr;
+  hd->fw_K = K.ptr;
+  hd->fw_V = V.ptr;
+  return HLA_OK;
+}
+
+hla_status hla_backward(hla_handle* hd, int32_t B, int32_t H, int32_t N, const int32_t* cu_seqlens,
+                        int32_t num_seqs, hla_tensor Q, hla_tensor K, hla_tensor V, hla_tensor O,
+                        hla_tensor dO, hla_tensor dQ, hla_tensor dK, hla_tensor dV,
+                        void* hip_stream) {
+  bool empty = false;
+  int32_t nseq = 0;
+  if (hd == nullptr) return HLA_ERR_INVALID_ARG;
+  // The tables and the saved features belong to the last forward: check before touching them.
+  {
+    const bool packed = cu_seqlens != nullptr;
+    bool same = hd->have_forward && hd->fw_B == B && hd->fw_H == H && hd->fw_N == N &&
+                hd->fw_packed == packed && hd->fw_Q == Q.ptr && hd->fw_K == K.ptr &&
+                hd->fw_V == V.ptr;
+    if (same && packed) {
+      same = num_seqs >= 0 && static_cast<int32_t>(hd->fw_cu.size()) == num_seqs + 1 &&
+             std::memcmp(hd->fw_cu.data(), cu_seqlens, sizeof(int32_t) * (num_seqs + 1)) == 0;
+    }
+    if (!same) return HLA_ERR_STATE;
+  }
+  HLA_TRY(prepare_call(hd, B, H, N, cu_seqlens, num_seqs, &empty, &nseq));
+  if (empty) return HLA_OK;
+  if (bad_view(Q) || bad_view(K) || bad_view(V) || bad_view(O) || bad_view(dO) || bad_view(dQ) ||
+      bad_view(dK) || bad_view(dV))
+    return HLA_ERR_INVALID_ARG;
+  hla_call_args a{};
+  a.B = B;
+  a.H = H;
+  a.N = N;
+  a.num_seqs = nseq;
+  a.packed = cu_seqlens != nullptr;
+  a.Q = make_view(Q);
+  a.K = make_view(K);
+  a.V = make_view(V);
+  a.O = make_view(O);
+  a.dO = make_view(dO);
+  a.dQ = make_view(dQ);
+  a.dK = make_view(dK);
+  a.dV = make_view(dV);
+  a.stream = static_cast<hipStream_t>(hip_stream);
+  return hd->path == HLA_PATH_MFMA ? mfma_backward(hd, a) : generic_backward(hd, a);
+}
+
+hla_status hla_profile_enable(hla_handle* hd, int32_t on) {
+  if (hd == nullptr) return HLA_ERR_INVALID_ARG;
+  hd->prof.on = on != 0;
+  hd->prof.clear_records();
+  return HLA_OK;
+}
+
+int32_t hla_profile_read(hla_handle* hd, int32_t cap, const char** names, double* total_ms,
+                         int64_t* launches) {
+  if (hd == nullptr) return 0;
+  std::vector<const char*> uniq;
+  std::vector<double> ms;
+  std::vector<int64_t> cnt;
+  for (size_t i = 0; i < hd->prof.n_used; ++i) {
+    ProfileRecord& r = hd->prof.records[i];
+    if (hipEventSynchronize(r.stop) != hipSuccess) continue;
+    float t = 0.f;
+    if (hipEventElapsedTime(&t, r.start, r.stop) != hipSuccess) continue;
+    size_t k = 0;
+    for (; k < uniq.size(); ++k)
+      if (uniq[k] == r.name || std::strcmp(uniq[k], r.name) == 0) break;
+    if (k == uniq.size()) {
+      uniq.push_back(r.name);
+      ms.push_back(0.0);
+      cnt.push_back(0);
+    }
+    ms[k] += t;
+    cnt[k] += 1;
+  }
+  for (size_t k = 0; k < uniq.size() && static_cast<int32_t>(k) < cap; ++k) {
+    if (names) names[k] = uniq[k];
+    if (total_ms) total_ms[k] = ms[k];
+    if (launches) launches[k] = cnt[k];
+  }
+  return static_cast<int32_t>(uniq.size());
+}
+
+}  // extern "C"

@@ -1,0 +1,612 @@
+// Generic path: fp32 vector-ALU kernels over the literal d_phi^F feature tensor (no matrix
+// cores, no algebraic compression).  Serves fp32 I/O, unusual (F, d_phi) and acts as an
+// independent GPU cross-check of the MFMA path.  Throughput is not a goal here.
+//
+// With the augmented state  Chat = [C | z]  ([D, d+1]) and augmented per-token rows
+// vhat_j = [v_j | 1], ghat_i = [dO_i/den_i | -<dO_i,o_i>/den_i] every step is one of three
+// shapes (Theorem 4.2 and its derivatives):
+//   accumulate : Chat  = sum_j T_j (x) yhat_j            (state; d state with T_q, ghat)
+//   contract   : out_i = T_i . Chat                       (query side; dV with T_k, dChat)
+//   dtensor    : dT_i  = Chat yhat_i, then the chain rule through the outer product
+#include <cmath>
+
+#include "hla_handle.h"
+
+namespace hla {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kChunk = 1024;      // tokens per partial state
+constexpr int kAccTile = 8;       // tokens staged per step of accumulate
+constexpr int kMaxRows = 128;     // accumulator rows per thread in accumulate: D*d/256 <= 128
+constexpr int kTokPerThread = 4;  // contract: tokens per thread
+constexpr int kDtTile = 8;        // dtensor: tokens per block
+constexpr int kPhiTile = 16;      // feature maps: tokens per block
+constexpr int kMaxF = 4;
+
+__device__ __forceinline__ float gelu_erf(float h) {
+  return h * 0.5f * (1.0f + erff(h * 0.70710678118654752440f));
+}
+__device__ __forceinline__ float gelu_erf_grad(float h) {
+  const float cdf = 0.5f * (1.0f + erff(h * 0.70710678118654752440f));
+  const float pdf = 0.39894228040143267794f * expf(-0.5f * h * h);
+  return cdf + h * pdf;
+}
+
+// Slot offsets into a feature row: query tensors use phi_q in every slot, key tensors use map f.
+__device__ __forceinline__ int slot_offset(bool query, int slot, int dphi) {
+  return query ? 0 : (1 + slot) * dphi;
+}
+
+// Entry `Di` of the outer product of one token's features (first slot slowest).
+__device__ __forceinline__ float outer_entry(const float* frow, bool query, int Di, int F,
+                                             int dphi) {
+  float p = 1.0f;
+  for (int s = F - 1; s >= 0; --s) {
+    const int a = Di % dphi;
+    Di /= dphi;
+    p *= frow[slot_offset(query, s, dphi) + a];
+  }
+  return p;
+}
+
+// ---- weights / features I/O -------------------------------------------------------------------
+template <typename T>
+__global__ void k_convert_weights(const T* __restrict__ src, int64_t head_stride, float* dst,
+                                  int count, int heads_w) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  const int hw = blockIdx.y;
+  if (i < count && hw < heads_w) dst[static_cast<int64_t>(hw) * count + i] = to_float(src[hw * head_stride + i]);
+}
+
+// PHI_NONE: copy caller-provided features into the fp32 feature workspace.
+template <typename T>
+__global__ void k_feat_import(Geom g, View Q, View K, float* __restrict__ feat) {
+  const int64_t idx = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  const int64_t total = static_cast<int64_t>(g.B) * g.H * g.N * g.nfeat;
+  if (idx >= total) return;
+  const int j = static_cast<int>(idx % g.nfeat);
+  const int64_t th = idx / g.nfeat;
+  const int n = static_cast<int>(th % g.N);
+  const int h = static_cast<int>((th / g.N) % g.H);
+  const int b = static_cast<int>(th / (static_cast<int64_t>(g.N) * g.H));
+  feat[idx] = j < g.dphi ? to_float(Q.row<const T>(b, h, n)[j])
+                         : to_float(K.row<const T>(b, h, n)[j - g.dphi]);
+}
+
+// PHI_NONE: feature gradients are the answer; store them in the I/O dtype.
+template <typename T>
+__global__ void k_dfeat_export(Geom g, const float* __restrict__ dfeat, View dQ, View dK) {
+  const int64_t idx = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  const int64_t total = static_cast<int64_t>(g.B) * g.H * g.N * g.nfeat;
+  if (idx >= total) return;
+  const int j = static_cast<int>(idx % g.nfeat);
+  const int64_t th = idx / g.nfeat;
+  const int n = static_cast<int>(th % g.N);
+  const int h = static_cast<int>((th / g.N) % g.H);
+  const int b = static_cast<int>(th / (static_cast<int64_t>(g.N) * g.H));
+  if (j < g.dphi)
+    dQ.row<T>(b, h, n)[j] = from_float<T>(dfeat[idx]);
+  else
+    dK.row<T>(b, h, n)[j - g.dphi] = from_float<T>(dfeat[idx]);
+}
+
+// ---- feature maps (App. A.1) ------------------------------------------------------------------
+// grid (ceil(N/kPhiTile), H, B), block d threads.  Thread j owns hidden unit j.
+template <typename T>
+__global__ void k_phi_forward(Geom g, PhiF32 w, View Q, View K, float* __restrict__ feat) {
+  extern __shared__ float smem[];
+  const int d = g.d, dphi = g.dphi;
+  float* xs = smem;                 // [kPhiTile][d]
+  float* gs = smem + kPhiTile * d;  // [kPhiTile][d]
+  const int j = threadIdx.x;
+  const int n0 = blockIdx.x * kPhiTile, h = blockIdx.y, b = blockIdx.z;
+  const int nt = min(kPhiTile, g.N - n0);
+  const int hw = w.heads_w == 1 ? 0 : h;
+  for (int m = 0; m <= g.F; ++m) {
+    if (m <= 1) {
+      __syncthreads();
+      const View& X = m == 0 ? Q : K;
+      for (int t = 0; t < kPhiTile; ++t)
+        xs[t * d + j] = t < nt ? to_float(X.row<const T>(b, h, n0 + t)[j]) : 0.0f;
+      __syncthreads();
+    }
+    const int64_t mh = static_cast<int64_t>(m) * w.heads_w + hw;
+    const float* W1 = w.W1 + mh * d * d;
+    const float* W2 = w.W2 + mh * d * dphi;
+    float acc[kPhiTile];
+#pragma unroll
+    for (int t = 0; t < kPhiTile; ++t) acc[t] = 0.0f;
+    for (int i = 0; i < d; ++i) {
+      const float wv = W1[i * d + j];
+#pragma unroll
+      for (int t = 0; t < kPhiTile; ++t) acc[t] += xs[t * d + i] * wv;
+    }
+    const float bias = w.b1[mh * d + j];
+#pragma unroll
+    for (int t = 0; t < kPhiTile; ++t) gs[t * d + j] = gelu_erf(acc[t] + bias);
+    __syncthreads();
+    for (int idx = j; idx < nt * dphi; idx += d) {
+      const int t = idx / dphi, c = idx % dphi;
+      float u = w.b2[mh * dphi + c];
+      for (int jj = 0; jj < d; ++jj) u += gs[t * d + jj] * W2[jj * dphi + c];
+      feat[g.th(b, h, n0 + t) * g.nfeat + m * dphi + c] = fmaxf(u, 0.0f);
+    }
+    __syncthreads();
+  }
+}
+
+// Input gradients through the feature maps; hidden activations are recomputed.  dK sums the F
+// key maps.  Thread j owns hidden unit j and input coordinate j.
+template <typename T>
+__global__ void k_phi_backward(Geom g, PhiF32 w, View Q, View K, const float* __restrict__ feat,
+                               const float* __restrict__ dfeat, View dQ, View dK) {
+  extern __shared__ float smem[];
+  const int d = g.d, dphi = g.dphi;
+  float* xs = smem;                   // [kPhiTile][d]
+  float* dhs = xs + kPhiTile * d;     // [kPhiTile][d]
+  float* dus = dhs + kPhiTile * d;    // [kPhiTile][dphi]
+  const int j = threadIdx.x;
+  const int n0 = blockIdx.x * kPhiTile, h = blockIdx.y, b = blockIdx.z;
+  const int nt = min(kPhiTile, g.N - n0);
+  const int hw = w.heads_w == 1 ? 0 : h;
+  float dx[kPhiTile];
+  for (int m = 0; m <= g.F; ++m) {
+    if (m <= 1) {
+      __syncthreads();
+      const View& X = m == 0 ? Q : K;
+      for (int t = 0; t < kPhiTile; ++t)
+        xs[t * d + j] = t < nt ? to_float(X.row<const T>(b, h, n0 + t)[j]) : 0.0f;
+#pragma unroll
+      for (int t = 0; t < kPhiTile; ++t) dx[t] = 0.0f;
+    }
+    __syncthreads();
+    for (int idx = j; idx < kPhiTile * dphi; idx += d) {
+      const int t = idx / dphi, c = idx % dphi;
+      float du = 0.0f;
+      if (t < nt) {
+        const int64_t o = g.th(b, h, n0 + t) * g.nfeat + m * dphi + c;
+        du = feat[o] > 0.0f ? dfeat[o] : 0.0f;  // ReLU passes gradient only where it was open
+      }
+      dus[idx] = du;
+    }
+    __syncthreads();
+    const int64_t mh = static_cast<int64_t>(m) * w.heads_w + hw;
+    const float* W1 = w.W1 + mh * d * d;
+    const float* W2 = w.W2 + mh * d * dphi;
+    float acc[kPhiTile];
+#pragma unroll
+    for (int t = 0; t < kPhiTile; ++t) acc[t] = 0.0f;
+    for (int i = 0; i < d; ++i) {
+      const float wv = W1[i * d + j];
+#pragma unroll
+      for (int t = 0; t < kPhiTile; ++t) acc[t] += xs[t * d + i] * wv;
+    }
+    const float bias = w.b1[mh * d + j];
+#pragma unroll
+    for (int t = 0; t < kPhiTile; ++t) {
+      float dg = 0.0f;
+      for (int c = 0; c < dphi; ++c) dg += dus[t * dphi + c] * W2[j * dphi + c];
+      dhs[t * d + j] = dg * gelu_erf_grad(acc[t] + bias);
+    }
+    __syncthreads();
+    for (int jj = 0; jj < d; ++jj) {
+      const float wv = W1[j * d + jj];  // dx_j = sum_jj dh_jj W1[j][jj]
+#pragma unroll
+      for (int t = 0; t < kPhiTile; ++t) dx[t] += dhs[t * d + jj] * wv;
+    }
+    if (m == 0 || m == g.F) {
+      const View& dX = m == 0 ? dQ : dK;
+      for (int t = 0; t < nt; ++t) dX.row<T>(b, h, n0 + t)[j] = from_float<T>(dx[t]);
+    }
+  }
+}
+
+// ---- accumulate: partial Chat = sum over a chunk of tokens of T (x) yhat -----------------------
+// YIO = true : yhat_j = [V_j | 1] read from the caller's V (I/O dtype, strided)
+// YIO = false: yhat_i read from the dense fp32 scratch [th][d+1]
+// grid (chunks, H), block 256.  Thread (r, c): column c, rows r + k*R with R = 256/d.
+template <typename T, bool YIO>
+__global__ void k_accumulate(Geom g, const BlockEnt* __restrict__ chunks,
+                             const float* __restrict__ feat, bool query, View Y,
+                             const float* __restrict__ ydense, float* __restrict__ partial,
+                             int64_t state_stride) {
+  extern __shared__ float smem[];
+  const int d = g.d, D = g.D;
+  const int R = kThreads / d;
+  const int nrows = (D + R - 1) / R;
+  const int Dpad = nrows * R;
+  float* ts = smem;                    // [kAccTile][Dpad]
+  float* ys = ts + kAccTile * Dpad;    // [kAccTile][d+1]
+  float* fs = ys + kAccTile * (d + 1); // [kAccTile][nfeat]
+  const BlockEnt e = chunks[blockIdx.x];
+  const int h = blockIdx.y;
+  const int tid = threadIdx.x;
+  const int c = tid % d, r = tid / d;
+  float acc[kMaxRows];
+#pragma unroll
+  for (int k = 0; k < kMaxRows; ++k) acc[k] = 0.0f;
+  float zacc = 0.0f;
+  for (int n0 = e.t0; n0 < e.t1; n0 += kAccTile) {
+    const int nt = min(kAccTile, e.t1 - n0);
+    __syncthreads();
+    for (int idx = tid; idx < kAccTile * g.nfeat; idx += kThreads) {
+      const int t = idx / g.nfeat;
+      fs[idx] = t < nt ? feat[g.th(e.b, h, n0 + t) * g.nfeat + idx % g.nfeat] : 0.0f;
+    }
+    for (int idx = tid; idx < kAccTile * (d + 1); idx += kThreads) {
+      const int t = idx / (d + 1), cc = idx % (d + 1);
+      float y = 0.0f;
+      if (t < nt) {
+        if (YIO)
+          y = cc < d ? to_float(Y.row<const T>(e.b, h, n0 + t)[cc]) : 1.0f;
+        else
+          y = ydense[g.th(e.b, h, n0 + t) * (d + 1) + cc];
+      }
+      ys[idx] = y;
+    }
+    __syncthreads();
+    for (int idx = tid; idx < kAccTile * Dpad; idx += kThreads) {
+      const int t = idx / Dpad, Di = idx % Dpad;
+      ts[idx] = Di < D ? outer_entry(fs + t * g.nfeat, query, Di, g.F, g.dphi) : 0.0f;
+    }
+    __syncthreads();
+    for (int t = 0; t < nt; ++t) {
+      const float yv = ys[t * (d + 1) + c];
+      const float* trow = ts + t * Dpad + r;
+#pragma unroll
+      for (int k = 0; k < kMaxRows; ++k)
+        if (k < nrows) acc[k] += trow[k * R] * yv;
+      if (tid < D) zacc += ts[t * Dpad + tid] * ys[t * (d + 1) + d];
+    }
+  }
+  float* out = partial + (static_cast<int64_t>(blockIdx.x) * g.H + h) * state_stride;
+#pragma unroll
+  for (int k = 0; k < kMaxRows; ++k) {
+    const int Di = r + k * R;
+    if (k < nrows && Di < D) out[Di * (d + 1) + c] = acc[k];
+  }
+  if (tid < D) out[tid * (d + 1) + d] = zacc;
+}
+
+// Sum the partial states of each (sequence, head) in chunk order (deterministic).
+// grid (num_seqs, H), block 256.
+__global__ void k_reduce(Geom g, const int32_t* __restrict__ seq_chunk_off,
+                         const float* __restrict__ partial, float* __restrict__ state,
+                         int64_t state_stride, int count) {
+  const int s = blockIdx.x, h = blockIdx.y;
+  const int c0 = seq_chunk_off[s], c1 = seq_chunk_off[s + 1];
+  float* out = state + (static_cast<int64_t>(s) * g.H + h) * state_stride;
+  for (int i = threadIdx.x; i < count; i += blockDim.x) {
+    float a = 0.0f;
+    for (int ch = c0; ch < c1; ++ch) a += partial[(static_cast<int64_t>(ch) * g.H + h) * state_stride + i];
+    out[i] = a;
+  }
+}
+
+// ---- contract: out_i = T_i . M -----------------------------------------------------------------
+// QUERY = true : T = T_q, M = Chat; writes O = num / (eta + eps) and den = eta + eps
+// QUERY = false: T = T_k, M = dChat; writes dV = first d columns
+// grid (tiles, H), block 256; tile = kTokPerThread * R tokens; thread (r, c) owns column c of
+// tokens r + k*R.
+template <typename T, bool QUERY>
+__global__ void k_contract(Geom g, const BlockEnt* __restrict__ tiles,
+                           const float* __restrict__ feat, const float* __restrict__ M,
+                           int64_t state_stride, View Out, float* __restrict__ den) {
+  extern __shared__ float smem[];
+  const int d = g.d, D = g.D;
+  const int R = kThreads / d;
+  const int tile = kTokPerThread * R;
+  float* ts = smem;             // [tile][D]
+  float* fs = ts + tile * D;    // [tile][nfeat]
+  float* etas = fs + tile * g.nfeat;  // [tile]
+  const BlockEnt e = tiles[blockIdx.x];
+  const int h = blockIdx.y;
+  const int tid = threadIdx.x;
+  const int c = tid % d, r = tid / d;
+  const int nt = e.t1 - e.t0;
+  const float* Mu = M + (static_cast<int64_t>(e.seq) * g.H + h) * state_stride;
+  for (int idx = tid; idx < tile * g.nfeat; idx += kThreads) {
+    const int t = idx / g.nfeat;
+    fs[idx] = t < nt ? feat[g.th(e.b, h, e.t0 + t) * g.nfeat + idx % g.nfeat] : 0.0f;
+  }
+  __syncthreads();
+  for (int idx = tid; idx < tile * D; idx += kThreads) {
+    const int t = idx / D, Di = idx % D;
+    ts[idx] = outer_entry(fs + t * g.nfeat, QUERY, Di, g.F, g.dphi);
+  }
+  __syncthreads();
+  float acc[kTokPerThread];
+#pragma unroll
+  for (int k = 0; k < kTokPerThread; ++k) acc[k] = 0.0f;
+  for (int Di = 0; Di < D; ++Di) {
+    const float mv = Mu[Di * (d + 1) + c];
+#pragma unroll
+    for (int k = 0; k < kTokPerThread; ++k) acc[k] += ts[(k * R + r) * D + Di] * mv;
+  }
+  if (QUERY) {
+    if (tid < tile) {
+      float eta = 0.0f;
+      for (int Di = 0; Di < D; ++Di) eta += ts[tid * D + Di] * Mu[Di * (d + 1) + d];
+      etas[tid] = eta + g.eps;
+      if (tid < nt) den[g.th(e.b, h, e.t0 + tid)] = eta + g.eps;
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int k = 0; k < kTokPerThread; ++k) {
+    const int t = k * R + r;
+    if (t < nt) {
+      const float o = QUERY ? acc[k] / etas[t] : acc[k];
+      Out.row<T>(e.b, h, e.t0 + t)[c] = from_float<T>(o);
+    }
+  }
+}
+
+// ghat_i = [dO_i / den_i | -<dO_i, o_i> / den_i]   (one block row of d threads per token)
+// grid (ceil(N/R), H, B), block 256.
+template <typename T>
+__global__ void k_backward_prep(Geom g, View dO, View O, const float* __restrict__ den,
+                                float* __restrict__ yhat) {
+  __shared__ float red[kThreads];
+  const int d = g.d;
+  const int R = kThreads / d;
+  const int c = threadIdx.x % d, r = threadIdx.x / d;
+  const int n = blockIdx.x * R + r, h = blockIdx.y, b = blockIdx.z;
+  const bool live = n < g.N;
+  float go = 0.0f, dn = 1.0f, dot = 0.0f;
+  if (live) {
+    dn = den[g.th(b, h, n)];
+    go = to_float(dO.row<const T>(b, h, n)[c]);
+    dot = go * to_float(O.row<const T>(b, h, n)[c]);
+  }
+  red[threadIdx.x] = dot;
+  __syncthreads();
+  for (int s = d / 2; s > 0; s >>= 1) {
+    if (c < s) red[threadIdx.x] += red[threadIdx.x + s];
+    __syncthreads();
+  }
+  if (live) {
+    float* y = yhat + g.th(b, h, n) * (d + 1);
+    y[c] = go / dn;
+    if (c == 0) y[d] = -red[r * d] / dn;
+  }
+}
+
+// ---- dtensor: dT_i = M yhat_i, then gradients of the outer-product slots -----------------------
+// QUERY = true : M = Chat, yhat = ghat (dense scratch), slots all phi_q -> dfeat[.., 0:dphi] (summed)
+// QUERY = false: M = dChat, yhat = [V | 1] (caller's V), slot f -> dfeat[.., (1+f)*dphi : ..]
+// grid (tiles of kDtTile, H), block 256 (needs D <= 256).
+template <typename T, bool QUERY>
+__global__ void k_dtensor(Geom g, const BlockEnt* __restrict__ tiles,
+                          const float* __restrict__ feat, const float* __restrict__ M,
+                          int64_t state_stride, View Y, const float* __restrict__ ydense,
+                          float* __restrict__ dfeat) {
+  extern __shared__ float smem[];
+  const int d = g.d, D = g.D, dphi = g.dphi, F = g.F;
+  float* ys = smem;                       // [kDtTile][d+1]
+  float* fs = ys + kDtTile * (d + 1);     // [kDtTile][nfeat]
+  float* dts = fs + kDtTile * g.nfeat;    // [kDtTile][D]
+  const BlockEnt e = tiles[blockIdx.x];
+  const int h = blockIdx.y;
+  const int tid = threadIdx.x;
+  const int nt = e.t1 - e.t0;
+  const float* Mu = M + (static_cast<int64_t>(e.seq) * g.H + h) * state_stride;
+  for (int idx = tid; idx < kDtTile * g.nfeat; idx += kThreads) {
+    const int t = idx / g.nfeat;
+    fs[idx] = t < nt ? feat[g.th(e.b, h, e.t0 + t) * g.nfeat + idx % g.nfeat] : 0.0f;
+  }
+  for (int idx = tid; idx < kDtTile * (d + 1); idx += kThreads) {
+    const int t = idx / (d + 1), cc = idx % (d + 1);
+    float y = 0.0f;
+    if (t < nt) {
+      if (QUERY)
+        y = ydense[g.th(e.b, h, e.t0 + t) * (d + 1) + cc];
+      else
+        y = cc < d ? to_float(Y.row<const T>(e.b, h, e.t0 + t)[cc]) : 1.0f;
+    }
+    ys[idx] = y;
+  }
+  __syncthreads();
+  if (tid < D) {
+    float dt[kDtTile];
+#pragma unroll
+    for (int t = 0; t < kDtTile; ++t) dt[t] = 0.0f;
+    const float* mrow = Mu + tid * (d + 1);
+    for (int cc = 0; cc <= d; ++cc) {
+      const float mv = mrow[cc];
+#pragma unroll
+      for (int t = 0; t < kDtTile; ++t) dt[t] += mv * ys[t * (d + 1) + cc];
+    }
+#pragma unroll
+    for (int t = 0; t < kDtTile; ++t) dts[t * D + tid] = dt[t];
+  }
+  __syncthreads();
+  // gradient of slot s, coordinate a, token t: sum over entries whose digit s equals a of
+  // dT[entry] * product of the other slots' features
+  const int nout = QUERY ? kDtTile * dphi : kDtTile * F * dphi;
+  for (int idx = tid; idx < nout; idx += kThreads) {
+    int t, s_lo, s_hi, a;
+    if (QUERY) {
+      t = idx / dphi;
+      a = idx % dphi;
+      s_lo = 0;
+      s_hi = F;
+    } else {
+      t = idx / (F * dphi);
+      s_lo = (idx / dphi) % F;
+      s_hi = s_lo + 1;
+      a = idx % dphi;
+    }
+    if (t >= nt) continue;
+    const float* frow = fs + t * g.nfeat;
+    float grad = 0.0f;
+    for (int s = s_lo; s < s_hi; ++s) {
+      for (int Di = 0; Di < D; ++Di) {
+        int rem = Di;
+        float p = 1.0f;
+        bool hit = false;
+        for (int sl = F - 1; sl >= 0; --sl) {
+          const int dig = rem % dphi;
+          rem /= dphi;
+          if (sl == s)
+            hit = dig == a;
+          else
+            p *= frow[slot_offset(QUERY, sl, dphi) + dig];
+        }
+        if (hit) grad += dts[t * D + Di] * p;
+      }
+    }
+    const int col = QUERY ? a : (1 + s_lo) * dphi + a;
+    dfeat[g.th(e.b, h, e.t0 + t) * g.nfeat + col] = grad;
+  }
+}
+
+template <typename T>
+hla_status forward_t(hla_handle* hd, const hla_call_args& a) {
+  Geom g = hd->g;
+  hipStream_t s = a.stream;
+  const int d = g.d;
+  const int R = kThreads / d;
+  if (hd->cfg.phi_mode == HLA_PHI_NONE) {
+    const int64_t total = static_cast<int64_t>(g.B) * g.H * g.N * g.nfeat;
+    HLA_TRY(launch(hd, "generic_feat_import", k_feat_import<T>, dim3((total + 255) / 256), dim3(256),
+                   0, s, g, a.Q, a.K, hd->feat));
+  } else {
+    const size_t sh = 2 * kPhiTile * d * sizeof(float);
+    HLA_TRY(launch(hd, "generic_phi_forward", k_phi_forward<T>,
+                   dim3((g.N + kPhiTile - 1) / kPhiTile, g.H, g.B), dim3(d), sh, s, g, hd->phi, a.Q,
+                   a.K, hd->feat));
+  }
+  hla_token_table *chunks = nullptr, *tiles = nullptr;
+  HLA_TRY(get_table(hd, kChunk, s, &chunks));
+  HLA_TRY(get_table(hd, kTokPerThread * R, s, &tiles));
+  const int nrows = (g.D + R - 1) / R;
+  const size_t sh_acc = (kAccTile * nrows * R + kAccTile * (d + 1) + kAccTile * g.nfeat) * sizeof(float);
+  HLA_TRY(launch(hd, "generic_state_accumulate", k_accumulate<T, true>, dim3(chunks->count, g.H),
+                 dim3(kThreads), sh_acc, s, g, chunks->dev, hd->feat, false, a.V,
+                 static_cast<const float*>(nullptr), hd->partial, hd->state_stride));
+  HLA_TRY(launch(hd, "generic_state_reduce", k_reduce, dim3(a.num_seqs, g.H), dim3(256), 0, s, g,
+                 chunks->seq_off_dev, hd->partial, hd->state, hd->state_stride, g.D * (d + 1)));
+  const int tile = kTokPerThread * R;
+  const size_t sh_c = (static_cast<size_t>(tile) * g.D + tile * g.nfeat + tile) * sizeof(float);
+  HLA_TRY(launch(hd, "generic_query_contract", k_contract<T, true>, dim3(tiles->count, g.H),
+                 dim3(kThreads), sh_c, s, g, tiles->dev, hd->feat, hd->state, hd->state_stride, a.O,
+                 hd->den));
+  return HLA_OK;
+}
+
+template <typename T>
+hla_status backward_t(hla_handle* hd, const hla_call_args& a) {
+  Geom g = hd->g;
+  hipStream_t s = a.stream;
+  const int d = g.d;
+  const int R = kThreads / d;
+  hla_token_table *chunks = nullptr, *tiles = nullptr, *dtt = nullptr;
+  HLA_TRY(get_table(hd, kChunk, s, &chunks));
+  HLA_TRY(get_table(hd, kTokPerThread * R, s, &tiles));
+  HLA_TRY(get_table(hd, kDtTile, s, &dtt));
+  HLA_TRY(launch(hd, "generic_backward_prep", k_backward_prep<T>, dim3((g.N + R - 1) / R, g.H, g.B),
+                 dim3(kThreads), 0, s, g, a.dO, a.O, hd->den, hd->yhat));
+  const int nrows = (g.D + R - 1) / R;
+  const size_t sh_acc = (kAccTile * nrows * R + kAccTile * (d + 1) + kAccTile * g.nfeat) * sizeof(float);
+  HLA_TRY(launch(hd, "generic_dstate_accumulate", k_accumulate<T, false>, dim3(chunks->count, g.H),
+                 dim3(kThreads), sh_acc, s, g, chunks->dev, hd->feat, true, a.V, hd->yhat, hd->partial,
+                 hd->state_stride));
+  HLA_TRY(launch(hd, "generic_dstate_reduce", k_reduce, dim3(a.num_seqs, g.H), dim3(256), 0, s, g,
+                 chunks->seq_off_dev, hd->partial, hd->dstate, hd->state_stride, g.D * (d + 1)));
+  const size_t sh_dt = (kDtTile * (d + 1) + kDtTile * g.nfeat + static_cast<size_t>(kDtTile) * g.D) * sizeof(float);
+  HLA_TRY(launch(hd, "generic_dquery_features", k_dtensor<T, true>, dim3(dtt->count, g.H),
+                 dim3(kThreads), sh_dt, s, g, dtt->dev, hd->feat, hd->state, hd->state_stride, a.V,
+                 hd->yhat, hd->dfeat));
+  HLA_TRY(launch(hd, "generic_dkey_features", k_dtensor<T, false>, dim3(dtt->count, g.H),
+                 dim3(kThreads), sh_dt, s, g, dtt->dev, hd->feat, hd->dstate, hd->state_stride, a.V,
+                 static_cast<const float*>(nullptr), hd->dfeat));
+  const int tile = kTokPerThread * R;
+  const size_t sh_c = (static_cast<size_t>(tile) * g.D + tile * g.nfeat + tile) * sizeof(float);
+  HLA_TRY(launch(hd, "generic_dvalue_contract", k_contract<T, false>, dim3(tiles->count, g.H),
+                 dim3(kThreads), sh_c, s, g, tiles->dev, hd->feat, hd->dstate, hd->state_stride, a.dV,
+                 static_cast<float*>(nullptr)));
+  if (hd->cfg.phi_mode == HLA_PHI_NONE) {
+    const int64_t total = static_cast<int64_t>(g.B) * g.H * g.N * g.nfeat;
+    HLA_TRY(launch(hd, "generic_dfeat_export", k_dfeat_export<T>, dim3((total + 255) / 256),
+                   dim3(256), 0, s, g, hd->dfeat, a.dQ, a.dK));
+  } else {
+    const size_t sh = (2 * kPhiTile * d + kPhiTile * g.dphi) * sizeof(float);
+    HLA_TRY(launch(hd, "generic_phi_backward", k_phi_backward<T>,
+                   dim3((g.N + kPhiTile - 1) / kPhiTile, g.H, g.B), dim3(d), sh, s, g, hd->phi, a.Q,
+                   a.K, hd->feat, hd->dfeat, a.dQ, a.dK));
+  }
+  return HLA_OK;
+}
+
+}  // namespace
+
+hla_status generic_workspace_plan(hla_handle* hd) {
+  const Geom& g = hd->g;
+  if (g.F > kMaxF || g.D > kThreads) return HLA_ERR_UNSUPPORTED;
+  const int R = kThreads / g.d;
+  if ((g.D + R - 1) / R > kMaxRows) return HLA_ERR_UNSUPPORTED;
+  if (kPhiTile * g.dphi > 64 * 1024) return HLA_ERR_UNSUPPORTED;
+  hd->state_stride = static_cast<int64_t>(g.D) * (g.d + 1);
+  hd->max_chunks = (hd->cfg.max_tokens + kChunk - 1) / kChunk + hd->cfg.max_seqs;
+  hd->yhat_floats = hd->max_th * (g.d + 1);
+  hd->tables[kChunk];
+  hd->tables[kTokPerThread * R];
+  hd->tables[kDtTile];
+  // shared-memory budgets (64 KiB static+dynamic without opting in)
+  const size_t tile = kTokPerThread * R;
+  const size_t sh_c = (tile * g.D + tile * g.nfeat + tile) * sizeof(float);
+  if (sh_c > 64 * 1024) return HLA_ERR_UNSUPPORTED;
+  return HLA_OK;
+}
+
+hla_status convert_weights_to_f32(hla_handle* hd, const hla_phi_weights* maps, hipStream_t s) {
+  const Geom& g = hd->g;
+  const int nm = 1 + g.F;
+  bool shared = true;
+  for (int m = 0; m < nm; ++m)
+    shared = shared && maps[m].head_stride_W1 == 0 && maps[m].head_stride_b1 == 0 &&
+             maps[m].head_stride_W2 == 0 && maps[m].head_stride_b2 == 0;
+  const int hw = shared ? 1 : hd->cfg.max_heads;
+  const int64_t nW1 = static_cast<int64_t>(g.d) * g.d, nb1 = g.d, nW2 = static_cast<int64_t>(g.d) * g.dphi,
+                nb2 = g.dphi;
+  float* W1 = hd->w_f32;
+  float* b1 = W1 + nm * hw * nW1;
+  float* W2 = b1 + nm * hw * nb1;
+  float* b2 = W2 + nm * hw * nW2;
+  hd->phi = PhiF32{W1, b1, W2, b2, hw};
+  for (int m = 0; m < nm; ++m) {
+    struct Item {
+      const void* src;
+      int64_t stride;
+      float* dst;
+      int64_t count;
+    } items[4] = {{maps[m].W1, maps[m].head_stride_W1, W1 + m * hw * nW1, nW1},
+                  {maps[m].b1, maps[m].head_stride_b1, b1 + m * hw * nb1, nb1},
+                  {maps[m].W2, maps[m].head_stride_W2, W2 + m * hw * nW2, nW2},
+                  {maps[m].b2, maps[m].head_stride_b2, b2 + m * hw * nb2, nb2}};
+    for (const Item& it : items) {
+      dim3 grid(static_cast<unsigned>((it.count + 255) / 256), hw);
+      if (hd->cfg.io_dtype == HLA_F32)
+        HLA_TRY(launch(hd, "convert_weights", k_convert_weights<float>, grid, dim3(256), 0, s,
+                       static_cast<const float*>(it.src), it.stride, it.dst, static_cast<int>(it.count), hw));
+      else
+        HLA_TRY(launch(hd, "convert_weights", k_convert_weights<bf16_t>, grid, dim3(256), 0, s,
+                       static_cast<const bf16_t*>(it.src), it.stride, it.dst, static_cast<int>(it.count), hw));
+    }
+  }
+  return HLA_OK;
+}
+
+hla_status generic_set_weights(hla_handle*, hipStream_t) { return HLA_OK; }
+
+hla_status generic_forward(hla_handle* hd, const hla_call_args& a) {
+  return hd->cfg.io_dtype == HLA_F32 ? forward_t<float>(hd, a) : forward_t<bf16_t>(hd, a);
+}
+
+hla_status generic_backward(hla_handle* hd, const hla_call_args& a) {
+  return hd->cfg.io_dtype == HLA_F32 ? backward_t<float>(hd, a) : backward_t<bf16_t>(hd, a);
+}
+
+}  // namespace hla

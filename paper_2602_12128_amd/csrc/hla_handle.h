@@ -1,0 +1,108 @@
+// The library-owned handle behind the opaque hla_handle of include/hla.h (internal).
+#ifndef HLA_HANDLE_H_
+#define HLA_HANDLE_H_
+
+#include <map>
+#include <vector>
+
+#include "hla_common.h"
+
+// One table of token runs for a given block size; rebuilt when (B, N, cu_seqlens) changes.
+struct hla_token_table {
+  int32_t block_tokens = 0;
+  hla::BlockEnt* dev = nullptr;     // capacity entries
+  int32_t* seq_off_dev = nullptr;   // [max_seqs+1] first block of each sequence
+  int64_t capacity = 0;
+  int32_t count = 0;                // valid entries for the current shape
+  bool valid = false;
+};
+
+struct hla_call_args {
+  int32_t B, H, N;
+  int32_t num_seqs;                // effective number of sequences (B when dense)
+  bool packed;
+  hla::View Q, K, V, O, dO, dQ, dK, dV;
+  hipStream_t stream;
+};
+
+struct hla_handle {
+  hla_config cfg;
+  int32_t path;                    // HLA_PATH_GENERIC or HLA_PATH_MFMA
+  hla::Geom g;                     // d, dphi, F, D, nfeat, eps filled at create; B,H,N per call
+  int64_t max_th;                  // max_heads * max_tokens
+  int32_t max_units;               // max_seqs * max_heads
+
+  // device workspace
+  float* feat = nullptr;           // [max_th][nfeat]   features saved by forward
+  float* dfeat = nullptr;          // [max_th][nfeat]   feature gradients
+  float* den = nullptr;            // [max_th]          eta + eps saved by forward
+  float* yhat = nullptr;           // path-specific per-token scratch, yhat_floats long
+  int64_t yhat_floats = 0;
+  float* state = nullptr;          // [max_units][state_stride]
+  float* dstate = nullptr;         // [max_units][state_stride]
+  float* partial = nullptr;        // [max_chunks * max_heads][state_stride]
+  int64_t state_stride = 0;        // floats per (sequence, head) state
+  int64_t max_chunks = 0;
+  void* path_ws = nullptr;         // extra path-owned device memory (repacked weights, bf16 state)
+  size_t path_ws_bytes = 0;
+
+  // feature-map weights, fp32 copies (both paths keep them; the MFMA path adds packed bf16)
+  float* w_f32 = nullptr;
+  hla::PhiF32 phi{};
+  bool have_weights = false;
+
+  // token tables keyed by block size
+  std::map<int32_t, hla_token_table> tables;
+  std::vector<int32_t> cu_host;    // shape signature of the tables (effective cu, B rows if dense)
+  int32_t sig_B = -1, sig_N = -1;
+  bool sig_packed = false;
+
+  // signature of the last forward, checked by backward
+  bool have_forward = false;
+  int32_t fw_B = 0, fw_H = 0, fw_N = 0;
+  bool fw_packed = false;
+  std::vector<int32_t> fw_cu;
+  const void *fw_Q = nullptr, *fw_K = nullptr, *fw_V = nullptr;
+
+  hla::Profiler prof;
+};
+
+namespace hla {
+
+// Ensure the table for `block_tokens` matches the current call shape; uploads on `s` if stale.
+hla_status get_table(hla_handle* hd, int32_t block_tokens, hipStream_t s, hla_token_table** out);
+
+template <typename... KArgs, typename... Args>
+inline hla_status launch(hla_handle* hd, const char* name, void (*kernel)(KArgs...), dim3 grid,
+                         dim3 block, size_t shmem, hipStream_t s, Args... args) {
+  if (grid.x == 0 || grid.y == 0 || grid.z == 0) return HLA_OK;
+  hd->prof.begin(name, s);
+  kernel<<<grid, block, shmem, s>>>(static_cast<KArgs>(args)...);
+  hd->prof.end(s);
+  return hipGetLastError() == hipSuccess ? HLA_OK : HLA_ERR_HIP;
+}
+
+// Path entry points (hla_generic.hip / hla_mfma.hip).
+hla_status generic_workspace_plan(hla_handle* hd);
+hla_status generic_set_weights(hla_handle* hd, hipStream_t s);
+hla_status generic_forward(hla_handle* hd, const hla_call_args& a);
+hla_status generic_backward(hla_handle* hd, const hla_call_args& a);
+
+bool mfma_supported(const hla_config& c);
+hla_status mfma_workspace_plan(hla_handle* hd);
+hla_status mfma_set_weights(hla_handle* hd, hipStream_t s);
+hla_status mfma_forward(hla_handle* hd, const hla_call_args& a);
+hla_status mfma_backward(hla_handle* hd, const hla_call_args& a);
+
+// Shared helper kernels' host wrappers (hla_generic.hip).
+hla_status convert_weights_to_f32(hla_handle* hd, const hla_phi_weights* maps, hipStream_t s);
+
+}  // namespace hla
+
+#define HLA_TRY(expr)                   \
+  do {                                  \
+    hla_status _s = (expr);             \
+    if (_s != HLA_OK) return _s;        \
+  } while (0)
+
+#endif  // HLA_HANDLE_H_
