@@ -225,6 +225,8 @@ hla_status hla_create(const hla_config* c, hla_handle** out) {
     char* p = nullptr;
     st = dev_alloc(&p, hd->path_ws_bytes);
     hd->path_ws = p;
+    // padding entries of packed operands are never written afterwards and must read as zero
+    if (st == HLA_OK && hipMemset(p, 0, hd->path_ws_bytes) != hipSuccess) st = HLA_ERR_HIP;
   }
   if (st == HLA_OK && c->phi_mode == HLA_PHI_MLP) {
     const int64_t per_map = static_cast<int64_t>(c->head_dim) * c->head_dim + c->head_dim +

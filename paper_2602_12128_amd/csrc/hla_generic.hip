@@ -463,21 +463,44 @@ __global__ void k_dtensor(Geom g, const BlockEnt* __restrict__ tiles,
 }
 
 template <typename T>
+hla_status features_in_t(hla_handle* hd, const hla_call_args& a) {
+  Geom g = hd->g;
+  hipStream_t s = a.stream;
+  const int d = g.d;
+  if (hd->cfg.phi_mode == HLA_PHI_NONE) {
+    const int64_t total = static_cast<int64_t>(g.B) * g.H * g.N * g.nfeat;
+    return launch(hd, "generic_feat_import", k_feat_import<T>, dim3((total + 255) / 256), dim3(256),
+                  0, s, g, a.Q, a.K, hd->feat);
+  }
+  const size_t sh = 2 * kPhiTile * d * sizeof(float);
+  return launch(hd, "generic_phi_forward", k_phi_forward<T>,
+                dim3((g.N + kPhiTile - 1) / kPhiTile, g.H, g.B), dim3(d), sh, s, g, hd->phi, a.Q, a.K,
+                hd->feat);
+}
+
+template <typename T>
+hla_status features_out_t(hla_handle* hd, const hla_call_args& a) {
+  Geom g = hd->g;
+  hipStream_t s = a.stream;
+  const int d = g.d;
+  if (hd->cfg.phi_mode == HLA_PHI_NONE) {
+    const int64_t total = static_cast<int64_t>(g.B) * g.H * g.N * g.nfeat;
+    return launch(hd, "generic_dfeat_export", k_dfeat_export<T>, dim3((total + 255) / 256), dim3(256),
+                  0, s, g, hd->dfeat, a.dQ, a.dK);
+  }
+  const size_t sh = (2 * kPhiTile * d + kPhiTile * g.dphi) * sizeof(float);
+  return launch(hd, "generic_phi_backward", k_phi_backward<T>,
+                dim3((g.N + kPhiTile - 1) / kPhiTile, g.H, g.B), dim3(d), sh, s, g, hd->phi, a.Q, a.K,
+                hd->feat, hd->dfeat, a.dQ, a.dK);
+}
+
+template <typename T>
 hla_status forward_t(hla_handle* hd, const hla_call_args& a) {
   Geom g = hd->g;
   hipStream_t s = a.stream;
   const int d = g.d;
   const int R = kThreads / d;
-  if (hd->cfg.phi_mode == HLA_PHI_NONE) {
-    const int64_t total = static_cast<int64_t>(g.B) * g.H * g.N * g.nfeat;
-    HLA_TRY(launch(hd, "generic_feat_import", k_feat_import<T>, dim3((total + 255) / 256), dim3(256),
-                   0, s, g, a.Q, a.K, hd->feat));
-  } else {
-    const size_t sh = 2 * kPhiTile * d * sizeof(float);
-    HLA_TRY(launch(hd, "generic_phi_forward", k_phi_forward<T>,
-                   dim3((g.N + kPhiTile - 1) / kPhiTile, g.H, g.B), dim3(d), sh, s, g, hd->phi, a.Q,
-                   a.K, hd->feat));
-  }
+  HLA_TRY(features_in_t<T>(hd, a));
   hla_token_table *chunks = nullptr, *tiles = nullptr;
   HLA_TRY(get_table(hd, kChunk, s, &chunks));
   HLA_TRY(get_table(hd, kTokPerThread * R, s, &tiles));
@@ -527,17 +550,7 @@ hla_status backward_t(hla_handle* hd, const hla_call_args& a) {
   HLA_TRY(launch(hd, "generic_dvalue_contract", k_contract<T, false>, dim3(tiles->count, g.H),
                  dim3(kThreads), sh_c, s, g, tiles->dev, hd->feat, hd->dstate, hd->state_stride, a.dV,
                  static_cast<float*>(nullptr)));
-  if (hd->cfg.phi_mode == HLA_PHI_NONE) {
-    const int64_t total = static_cast<int64_t>(g.B) * g.H * g.N * g.nfeat;
-    HLA_TRY(launch(hd, "generic_dfeat_export", k_dfeat_export<T>, dim3((total + 255) / 256),
-                   dim3(256), 0, s, g, hd->dfeat, a.dQ, a.dK));
-  } else {
-    const size_t sh = (2 * kPhiTile * d + kPhiTile * g.dphi) * sizeof(float);
-    HLA_TRY(launch(hd, "generic_phi_backward", k_phi_backward<T>,
-                   dim3((g.N + kPhiTile - 1) / kPhiTile, g.H, g.B), dim3(d), sh, s, g, hd->phi, a.Q,
-                   a.K, hd->feat, hd->dfeat, a.dQ, a.dK));
-  }
-  return HLA_OK;
+  return features_out_t<T>(hd, a);
 }
 
 }  // namespace
@@ -600,6 +613,15 @@ hla_status convert_weights_to_f32(hla_handle* hd, const hla_phi_weights* maps, h
 }
 
 hla_status generic_set_weights(hla_handle*, hipStream_t) { return HLA_OK; }
+
+// Features in (feature maps, or import of caller-provided features) and feature gradients out
+// (through the maps, or exported as they are); shared with the MFMA path.
+hla_status generic_features_in(hla_handle* hd, const hla_call_args& a) {
+  return hd->cfg.io_dtype == HLA_F32 ? features_in_t<float>(hd, a) : features_in_t<bf16_t>(hd, a);
+}
+hla_status generic_features_out(hla_handle* hd, const hla_call_args& a) {
+  return hd->cfg.io_dtype == HLA_F32 ? features_out_t<float>(hd, a) : features_out_t<bf16_t>(hd, a);
+}
 
 hla_status generic_forward(hla_handle* hd, const hla_call_args& a) {
   return hd->cfg.io_dtype == HLA_F32 ? forward_t<float>(hd, a) : forward_t<bf16_t>(hd, a);

@@ -87,6 +87,8 @@ hla_status generic_workspace_plan(hla_handle* hd);
 hla_status generic_set_weights(hla_handle* hd, hipStream_t s);
 hla_status generic_forward(hla_handle* hd, const hla_call_args& a);
 hla_status generic_backward(hla_handle* hd, const hla_call_args& a);
+hla_status generic_features_in(hla_handle* hd, const hla_call_args& a);
+hla_status generic_features_out(hla_handle* hd, const hla_call_args& a);
 
 bool mfma_supported(const hla_config& c);
 hla_status mfma_workspace_plan(hla_handle* hd);

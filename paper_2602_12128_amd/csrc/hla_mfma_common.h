@@ -1,0 +1,263 @@
+// Device helpers for the matrix-core (MFMA) path on gfx950: operand types, MFMA wrappers with
+// their lane layouts, LDS transpose reads, wave-level LDS ordering, and the compile-time tables
+// of the symmetric (monomial) form of the degree-3 feature tensor.
+#ifndef HLA_MFMA_COMMON_H_
+#define HLA_MFMA_COMMON_H_
+
+#include <type_traits>
+#include <utility>
+
+#include "hla_common.h"
+
+namespace hla {
+namespace mf {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kWave = 64;
+
+// ---- v_mfma_f32_32x32x16_bf16 ---------------------------------------------------------------
+// D[32x32] += A[32x16] * B[16x32].  Lane l = (r, g) with r = l % 32, g = l / 32:
+//   A operand: row r,   k = 8g .. 8g+7      (8 bf16 = 4 VGPRs)
+//   B operand: col r,   k = 8g .. 8g+7
+//   D: column r; register i (0..15) holds row 8*(i/4) + 4*g + (i%4).
+// The contraction only needs A and B to agree on what k-slot (g, j) means, so kernels are free
+// to map k-slots to tokens / channels / monomials in whatever order suits their loads.
+__device__ __forceinline__ f32x16 mfma32(u32x4 a, u32x4 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
+                                                 __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+__device__ __forceinline__ int d_row(int i, int g) { return 8 * (i / 4) + 4 * g + (i % 4); }
+
+// two fp32 -> packed bf16 pair (lo = a, hi = b), round-to-nearest-even
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  bf16x2 v;
+  v[0] = static_cast<__bf16>(a);
+  v[1] = static_cast<__bf16>(b);
+  return __builtin_bit_cast(uint32_t, v);
+}
+__device__ __forceinline__ float bf16_lo(uint32_t p) { return __uint_as_float(p << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t p) { return __uint_as_float(p & 0xffff0000u); }
+
+// ---- ds_read_b64_tr_b16 ---------------------------------------------------------------------
+// Within each group of 16 lanes the 16 x (4 bf16) values are treated as a 4 x 16 matrix whose row
+// j is supplied by lanes 4j..4j+3 (4 elements each); lane n of the group receives column n.
+// With a row-major [k][n] tile in LDS, lane L passing the address of (row k0 + L/4, cols
+// n0 + 4*(L%4) .. +3) receives (k0..k0+3, n0 + L): four consecutive k for one n, which is half of
+// an MFMA operand whose contraction index runs along the tile's rows.
+__device__ __forceinline__ u32x2 lds_read_tr16(const void* lds_ptr) {
+  typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
+  s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(lds_ptr));
+  return __builtin_bit_cast(u32x2, v);
+}
+
+// Orders this wave's earlier LDS writes before its later LDS reads by other lanes of the same
+// wave (no s_barrier: waves of a workgroup run independent pipelines over private LDS regions).
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// value held by the lane 32 away (the other half of a (token, g) lane pair)
+__device__ __forceinline__ float partner32(float v) { return __shfl_xor(v, 32, 64); }
+
+template <int I, int N, class Fn>
+__device__ __forceinline__ void static_for(Fn&& f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for<I + 1, N>(f);
+  }
+}
+
+// ---- symmetric form of the degree-3 feature tensor -------------------------------------------
+// T_q = q (x) q (x) q is symmetric, so contracting it with the state only sees the state summed
+// over index permutations.  Both sides are therefore kept over the C(dphi+2, 3) monomials
+// {x <= y <= z}:   query feature  Qm[m] = q_x q_y q_z,
+//                  key feature    S[m]  = sum over distinct orderings (a,b,c) of (x,y,z) of
+//                                         k1_a k2_b k3_c,
+// and  sum_D T_q[D] C[D,:] = sum_m Qm[m] Csym[m,:]  with  Csym = sum_j S_j (x) v_j  exactly.
+//
+// Index reversal a -> dphi-1-a maps monomials to monomials without fixed points when dphi is
+// even, so they split into NS = NM/2 mirror pairs.  A token is served by two lanes (g = 0, 1):
+// lane g = 0 evaluates the pair's first member from the features as they are, lane g = 1 runs
+// the SAME instructions on the reversed feature vector and thereby evaluates the mirror member.
+// "Slot" s (0..NS-1, padded to SP) names a pair; (g, s) names a monomial.
+struct Tri {
+  int x, y, z;
+};
+constexpr int sym3_num_mono(int dp) { return dp * (dp + 1) * (dp + 2) / 6; }
+constexpr Tri sym3_mono(int dp, int m) {
+  int c = 0;
+  for (int x = 0; x < dp; ++x)
+    for (int y = x; y < dp; ++y)
+      for (int z = y; z < dp; ++z) {
+        if (c == m) return Tri{x, y, z};
+        ++c;
+      }
+  return Tri{-1, -1, -1};
+}
+constexpr int sym3_canon(int dp, Tri t) {
+  int c = 0;
+  for (int x = 0; x < dp; ++x)
+    for (int y = x; y < dp; ++y)
+      for (int z = y; z < dp; ++z) {
+        if (x == t.x && y == t.y && z == t.z) return c;
+        ++c;
+      }
+  return -1;
+}
+constexpr Tri sym3_mirror(int dp, Tri t) { return Tri{dp - 1 - t.z, dp - 1 - t.y, dp - 1 - t.x}; }
+// s-th monomial (in canonical order) that precedes its own mirror image
+constexpr Tri sym3_slot(int dp, int s) {
+  int c = 0;
+  for (int m = 0; m < sym3_num_mono(dp); ++m) {
+    const Tri t = sym3_mono(dp, m);
+    if (m < sym3_canon(dp, sym3_mirror(dp, t))) {
+      if (c == s) return t;
+      ++c;
+    }
+  }
+  return Tri{-1, -1, -1};
+}
+// canonical monomial index served by (g, s); -1 for padding slots
+constexpr int sym3_slot_canon(int dp, int g, int s) {
+  if (s >= sym3_num_mono(dp) / 2) return -1;
+  const Tri t = sym3_slot(dp, s);
+  return g == 0 ? sym3_canon(dp, t) : sym3_canon(dp, sym3_mirror(dp, t));
+}
+
+template <int DP>
+struct Sym3 {
+  static_assert(DP % 2 == 0, "mirror pairing needs an even feature dim");
+  static constexpr int NM = sym3_num_mono(DP);   // monomials
+  static constexpr int NS = NM / 2;              // mirror pairs (slots actually used)
+  static constexpr int SP = (NS + 15) / 16 * 16; // slots per lane half, padded
+  static constexpr int MP = 2 * SP;              // rows of the padded symmetric state
+};
+
+// Query monomials of this lane's slots from its (possibly reversed) features.
+template <int DP>
+__device__ __forceinline__ void query_monomials(const float (&q)[DP], float (&qm)[Sym3<DP>::SP]) {
+  static_for<0, Sym3<DP>::SP>([&](auto S) {
+    constexpr int s = decltype(S)::value;
+    if constexpr (s < Sym3<DP>::NS) {
+      constexpr Tri t = sym3_slot(DP, s);
+      qm[s] = (q[t.x] * q[t.y]) * q[t.z];
+    } else {
+      qm[s] = 0.0f;
+    }
+  });
+}
+
+// dq[a] += sum_s dm[s] * d(q_x q_y q_z)/dq_a  (one term per position, which also covers
+// repeated indices).
+template <int DP>
+__device__ __forceinline__ void query_monomials_grad(const float (&q)[DP],
+                                                     const float (&dm)[Sym3<DP>::SP],
+                                                     float (&dq)[DP]) {
+  static_for<0, Sym3<DP>::NS>([&](auto S) {
+    constexpr int s = decltype(S)::value;
+    constexpr Tri t = sym3_slot(DP, s);
+    dq[t.x] += dm[s] * (q[t.y] * q[t.z]);
+    dq[t.y] += dm[s] * (q[t.x] * q[t.z]);
+    dq[t.z] += dm[s] * (q[t.x] * q[t.y]);
+  });
+}
+
+// Distinct orderings of a monomial, enumerated at compile time.
+struct Perm3 {
+  int n;
+  int a[6], b[6], c[6];
+};
+constexpr Perm3 sym3_perms(Tri t) {
+  Perm3 p{0, {0, 0, 0, 0, 0, 0}, {0, 0, 0, 0, 0, 0}, {0, 0, 0, 0, 0, 0}};
+  const int v[3] = {t.x, t.y, t.z};
+  const int idx[6][3] = {{0, 1, 2}, {0, 2, 1}, {1, 0, 2}, {1, 2, 0}, {2, 0, 1}, {2, 1, 0}};
+  for (int k = 0; k < 6; ++k) {
+    const int a = v[idx[k][0]], b = v[idx[k][1]], c = v[idx[k][2]];
+    bool dup = false;
+    for (int e = 0; e < p.n; ++e) dup = dup || (p.a[e] == a && p.b[e] == b && p.c[e] == c);
+    if (!dup) {
+      p.a[p.n] = a;
+      p.b[p.n] = b;
+      p.c[p.n] = c;
+      ++p.n;
+    }
+  }
+  return p;
+}
+
+// Key monomial feature of one monomial: S = sum over distinct orderings of k1_a k2_b k3_c.
+template <int DP, int X, int Y, int Z>
+__device__ __forceinline__ float key_monomial(const float (&k1)[DP], const float (&k2)[DP],
+                                              const float (&k3)[DP]) {
+  constexpr Perm3 p = sym3_perms(Tri{X, Y, Z});
+  float acc = 0.0f;
+  static_for<0, p.n>([&](auto E) {
+    constexpr int e = decltype(E)::value;
+    acc += k1[p.a[e]] * (k2[p.b[e]] * k3[p.c[e]]);
+  });
+  return acc;
+}
+
+// All NM key monomials in canonical order (one lane serves one token).
+template <int DP>
+__device__ __forceinline__ void key_monomials_all(const float (&k1)[DP], const float (&k2)[DP],
+                                                  const float (&k3)[DP],
+                                                  float (&sm)[Sym3<DP>::NM]) {
+  static_for<0, Sym3<DP>::NM>([&](auto M) {
+    constexpr int m = decltype(M)::value;
+    constexpr Tri t = sym3_mono(DP, m);
+    sm[m] = key_monomial<DP, t.x, t.y, t.z>(k1, k2, k3);
+  });
+}
+
+// Key monomials of this lane's slots (features possibly reversed).
+template <int DP>
+__device__ __forceinline__ void key_monomials_slots(const float (&k1)[DP], const float (&k2)[DP],
+                                                    const float (&k3)[DP],
+                                                    float (&sm)[Sym3<DP>::SP]) {
+  static_for<0, Sym3<DP>::SP>([&](auto S) {
+    constexpr int s = decltype(S)::value;
+    if constexpr (s < Sym3<DP>::NS) {
+      constexpr Tri t = sym3_slot(DP, s);
+      sm[s] = key_monomial<DP, t.x, t.y, t.z>(k1, k2, k3);
+    } else {
+      sm[s] = 0.0f;
+    }
+  });
+}
+
+// Chain rule of key_monomials_slots: every distinct ordering (a,b,c) of slot s feeds
+// dk1[a] += ds * k2_b k3_c, dk2[b] += ds * k1_a k3_c, dk3[c] += ds * k1_a k2_b.
+template <int DP>
+__device__ __forceinline__ void key_monomials_grad(const float (&k1)[DP], const float (&k2)[DP],
+                                                   const float (&k3)[DP],
+                                                   const float (&ds)[Sym3<DP>::SP],
+                                                   float (&dk1)[DP], float (&dk2)[DP],
+                                                   float (&dk3)[DP]) {
+  static_for<0, Sym3<DP>::NS>([&](auto S) {
+    constexpr int s = decltype(S)::value;
+    constexpr Tri t = sym3_slot(DP, s);
+    constexpr Perm3 p = sym3_perms(t);
+    static_for<0, p.n>([&](auto E) {
+      constexpr int e = decltype(E)::value;
+      dk1[p.a[e]] += ds[s] * (k2[p.b[e]] * k3[p.c[e]]);
+      dk2[p.b[e]] += ds[s] * (k1[p.a[e]] * k3[p.c[e]]);
+      dk3[p.c[e]] += ds[s] * (k1[p.a[e]] * k2[p.b[e]]);
+    });
+  });
+}
+
+}  // namespace mf
+}  // namespace hla
+
+#endif  // HLA_MFMA_COMMON_H_

@@ -1,0 +1,84 @@
+"""GPU parity of the MFMA (bf16 matrix-core) path against the CPU oracle through the C ABI, on
+inputs that span several tiles, chunks and ragged tails, plus packed sequences."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2602_12128_amd as hla
+from paper_2602_12128_amd import workloads as wl
+from tests import parity_utils as pu
+
+pytestmark = pytest.mark.gpu
+
+BWD = False
+
+
+@pytest.mark.parametrize("d,N,kind", [
+    (128, 64, "halfnormal"),
+    (128, 1000, "lognormal"),
+    (64, 777, "halfnormal"),
+    (128, 2500, "sparse"),
+    (64, 33, "lognormal"),
+    (128, 1, "halfnormal"),
+])
+def test_feature_level_bf16(d, N, kind):
+    t = wl.make_feature_inputs(300 + N, 2, 3, N, d, 3, 6, torch.bfloat16, kind=kind)
+    bwd = BWD and N > 1
+    gpu = pu.run_gpu(t, 3, 6, 1e-6, path=hla.HLA_PATH_MFMA, backward=bwd)
+    assert gpu["_path"] == hla.HLA_PATH_MFMA
+    ref = pu.run_oracle(t, 3, 6, 1e-6, backward=bwd)
+    pu.assert_parity(gpu, ref, 2e-2, f"mfma features d={d} N={N} {kind}")
+
+
+@pytest.mark.parametrize("d,N,b2", [(128, 700, 2.0), (64, 1300, 0.5), (128, 95, 1.0)])
+def test_feature_maps_bf16(d, N, b2):
+    t, phi = wl.make_raw_inputs(400 + N, 1, 2, N, d, 3, 6, torch.bfloat16, b2_mean=b2)
+    gpu = pu.run_gpu(t, 3, 6, 1e-6, phi=phi, path=hla.HLA_PATH_MFMA, backward=BWD)
+    ref = pu.run_oracle(t, 3, 6, 1e-6, phi=phi, backward=BWD)
+    pu.assert_parity(gpu, ref, 2e-2, f"mfma phi d={d} N={N} b2={b2}")
+
+
+def test_packed_sequences_no_leak_bf16():
+    cu = [0, 100, 100, 1500, 1501, 2600]
+    t = wl.make_feature_inputs(12, 1, 2, cu[-1], 128, 3, 6, torch.bfloat16)
+    gpu = pu.run_gpu(t, 3, 6, 1e-6, cu_seqlens=cu, path=hla.HLA_PATH_MFMA, backward=BWD)
+    ref = pu.run_oracle(t, 3, 6, 1e-6, cu_seqlens=cu, backward=BWD)
+    # the single-token sequence [1500,1501) has O(eps) feature gradients: compare it apart
+    keep = np.ones(cu[-1], bool)
+    keep[1500] = False
+    pu.assert_parity({k: v[:, :, keep] for k, v in gpu.items() if k != "_path"},
+                     {k: v[:, :, keep] for k, v in ref.items()}, 2e-2, "mfma packed")
+    np.testing.assert_allclose(pu.to_np(gpu["O"])[:, :, 1500], ref["O"][:, :, 1500], rtol=2e-2, atol=1e-3)
+    t2 = {k: v.clone() for k, v in t.items()}
+    t2["K"][:, :, :100] += 0.5
+    t2["V"][:, :, :100] -= 1.0
+    gpu2 = pu.run_gpu(t2, 3, 6, 1e-6, cu_seqlens=cu, path=hla.HLA_PATH_MFMA, backward=BWD)
+    for k in gpu:
+        if k != "_path":
+            assert torch.equal(gpu[k][:, :, 100:], gpu2[k][:, :, 100:]), k
+    assert not torch.equal(gpu["O"][:, :, :100], gpu2["O"][:, :, :100])
+
+
+def test_mfma_matches_generic_path_and_is_repeatable():
+    t = wl.make_feature_inputs(13, 2, 2, 900, 128, 3, 6, torch.bfloat16, kind="lognormal")
+    a = pu.run_gpu(t, 3, 6, 1e-6, path=hla.HLA_PATH_MFMA, backward=BWD)
+    b = pu.run_gpu(t, 3, 6, 1e-6, path=hla.HLA_PATH_MFMA, backward=BWD)
+    c = pu.run_gpu(t, 3, 6, 1e-6, path=hla.HLA_PATH_GENERIC, backward=BWD)
+    for k in a:
+        if k == "_path":
+            continue
+        assert torch.equal(a[k], b[k]), f"{k} not bit-reproducible"
+        assert pu.max_rel_err(pu.to_np(a[k]), pu.to_np(c[k])) < 2e-2, k
+
+
+def test_unsupported_shapes_fall_back_or_report():
+    # AUTO falls back to the generic kernels when the MFMA path has none; forcing MFMA reports it
+    h = hla.HLA(head_dim=32, feature_dim=6, degree=3, io_dtype=hla.HLA_BF16,
+                phi_mode=hla.HLA_PHI_NONE, max_heads=1, max_tokens=8, max_seqs=1)
+    assert h.active_path == hla.HLA_PATH_GENERIC
+    h.destroy()
+    with pytest.raises(hla.HLAError) as e:
+        hla.HLA(head_dim=128, feature_dim=12, degree=2, io_dtype=hla.HLA_BF16,
+                phi_mode=hla.HLA_PHI_NONE, kernel_path=hla.HLA_PATH_MFMA, max_heads=1,
+                max_tokens=8, max_seqs=1)
+    assert e.value.code == 2
