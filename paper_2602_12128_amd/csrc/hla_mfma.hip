@@ -345,16 +345,426 @@ __global__ __launch_bounds__(kThreads) void k_query(Geom g, const BlockEnt* __re
   }
 }
 
+// Canonical monomial served by (g, slot); -1 for padding slots.
+struct CanonMap {
+  int8_t canon[2][32];
+};
+template <int DP>
+CanonMap make_canon_map() {
+  CanonMap cm{};
+  for (int g = 0; g < 2; ++g)
+    for (int s = 0; s < 32; ++s) cm.canon[g][s] = static_cast<int8_t>(sym3_slot_canon(DP, g, s));
+  return cm;
+}
+
+// Stage a [32 tokens x D] bf16 tile row-major into LDS with coalesced 16-byte loads; rows at or
+// beyond t1 are zero.  Row stride `stride` bytes.
+template <int D>
+__device__ __forceinline__ void stage_tile32(const View& X, int b, int h, int n0, int t1, int lane,
+                                             unsigned char* dst, int stride) {
+  constexpr int PIECES = D / 8;
+  constexpr int RPL = 64 / PIECES;
+  constexpr int NLD = 32 / RPL;
+  const int prow = lane / PIECES, pcol = lane % PIECES;
+#pragma unroll
+  for (int i = 0; i < NLD; ++i) {
+    const int row = i * RPL + prow;
+    const int n = n0 + row;
+    u32x4 v;
+    v[0] = v[1] = v[2] = v[3] = 0u;
+    if (n < t1) v = *reinterpret_cast<const u32x4*>(X.row<const bf16_t>(b, h, n) + pcol * 8);
+    *reinterpret_cast<u32x4*>(dst + row * stride + pcol * 16) = v;
+  }
+}
+
+// ---- k_bwd_query ------------------------------------------------------------------------------
+template <int D>
+struct BwdQSmem {
+  static constexpr int kRow = D * 2 + 32;       // bytes per token row of the dO (-> g) and O tiles
+  static constexpr int kTile = 32 * kRow;
+  static constexpr int kQStride = 64 * 2 + 32;  // bytes per token row of the Qm tile (64 slot columns)
+  static constexpr int kQBytes = 32 * kQStride;
+  static constexpr int kWaveBytes = 2 * kTile + kQBytes;
+  static constexpr int kRedBytes = (64 * D + 64) * 4;
+  static constexpr int kTotal = kWaves * kWaveBytes > kRedBytes ? kWaves * kWaveBytes : kRedBytes;
+};
+
+// grid (chunks, H), block 256.  Per 32-token tile and lane (token r, slot half gl):
+//   g = dO/den, s = -<dO,o>/den;  dM^T = Csym g^T (+ s z)  -> chain rule to d(phi_q) ;
+//   dCsym += Qm^T g (contraction over the tile's tokens), dzsym += s Qm.
+// The chunk's dCsym/dzsym are summed over the four waves in wave order and written as a partial
+// with canonical monomial rows.
+template <int DP, int D>
+__global__ __launch_bounds__(kThreads) void k_bwd_query(
+    Geom g, const BlockEnt* __restrict__ chunks, const float* __restrict__ feat,
+    const float* __restrict__ den, const unsigned char* __restrict__ ops, View dO, View O,
+    float* __restrict__ dfeat, float* __restrict__ partial, int64_t partial_stride, CanonMap cm) {
+  using SY = Sym3<DP>;
+  using SL = StateLayout<DP, D>;
+  using SM = BwdQSmem<D>;
+  constexpr int SP = SY::SP;
+  constexpr int NCB = D / 32, NKD = D / 16;
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  unsigned char* gs = smem + wave * SM::kWaveBytes;
+  unsigned char* os = gs + SM::kTile;
+  unsigned char* qs = os + SM::kTile;
+  const BlockEnt e = chunks[blockIdx.x];
+  const int h = blockIdx.y;
+  const int r = lane % 32, gl = lane / 32;
+  const int L = lane % 16, q = lane / 16;
+  const int64_t u = static_cast<int64_t>(e.seq) * g.H + h;
+  const u32x4* opB = reinterpret_cast<const u32x4*>(ops + u * SL::kOpBytes + SL::kOpElems * 2);
+  const float* zslot = reinterpret_cast<const float*>(ops + u * SL::kOpBytes + 2 * SL::kOpElems * 2) + gl * SP;
+  u32x4 a_mo[2][NKD];
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+    for (int ks = 0; ks < NKD; ++ks) a_mo[rb][ks] = opB[(rb * NKD + ks) * 64 + lane];
+  float z[SP];
+#pragma unroll
+  for (int s = 0; s < SP; ++s) z[s] = zslot[s];
+
+  f32x16 dC[2][NCB];
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) dC[rb][cb][i] = 0.0f;
+  float dzacc[SP];
+#pragma unroll
+  for (int s = 0; s < SP; ++s) dzacc[s] = 0.0f;
+
+  for (int n0 = e.t0 + wave * 32; n0 < e.t1; n0 += kWaves * 32) {
+    stage_tile32<D>(dO, e.b, h, n0, e.t1, lane, gs, SM::kRow);
+    stage_tile32<D>(O, e.b, h, n0, e.t1, lane, os, SM::kRow);
+    wave_lds_sync();
+    const int n = n0 + r;
+    const bool live = n < e.t1;
+    const int64_t th = g.th(e.b, h, live ? n : e.t0);
+    const float inv = live ? 1.0f / den[th] : 0.0f;
+    u32x4 dov[NKD];
+    float dot = 0.0f;
+#pragma unroll
+    for (int ks = 0; ks < NKD; ++ks) {
+      dov[ks] = *reinterpret_cast<const u32x4*>(gs + r * SM::kRow + (16 * ks + 8 * gl) * 2);
+      const u32x4 ov = *reinterpret_cast<const u32x4*>(os + r * SM::kRow + (16 * ks + 8 * gl) * 2);
+#pragma unroll
+      for (int p = 0; p < 4; ++p)
+        dot += bf16_lo(dov[ks][p]) * bf16_lo(ov[p]) + bf16_hi(dov[ks][p]) * bf16_hi(ov[p]);
+    }
+    dot += partner32(dot);
+    const float si = -dot * inv;
+    f32x16 dM[2];
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) dM[rb][i] = 0.0f;
+#pragma unroll
+    for (int ks = 0; ks < NKD; ++ks) {
+      u32x4 gv;
+#pragma unroll
+      for (int p = 0; p < 4; ++p)
+        gv[p] = pack_bf16(bf16_lo(dov[ks][p]) * inv, bf16_hi(dov[ks][p]) * inv);
+      *reinterpret_cast<u32x4*>(gs + r * SM::kRow + (16 * ks + 8 * gl) * 2) = gv;  // dO tile becomes g tile
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb) dM[rb] = mfma32(a_mo[rb][ks], gv, dM[rb]);
+    }
+    float qf[DP];
+    if (live) {
+      const float* f = feat + th * g.nfeat;
+#pragma unroll
+      for (int c = 0; c < DP; ++c) qf[c] = f[gl ? DP - 1 - c : c];
+    } else {
+#pragma unroll
+      for (int c = 0; c < DP; ++c) qf[c] = 0.0f;
+    }
+    float qm[SP];
+    query_monomials<DP>(qf, qm);
+#pragma unroll
+    for (int p4 = 0; p4 < SP / 8; ++p4) {
+      u32x4 w;
+#pragma unroll
+      for (int p = 0; p < 4; ++p) {
+        const int s = 8 * p4 + 2 * p;
+        w[p] = pack_bf16(qm[s], qm[s + 1]);
+        dzacc[s] += si * bf16_lo(w[p]);
+        dzacc[s + 1] += si * bf16_hi(w[p]);
+      }
+      *reinterpret_cast<u32x4*>(qs + r * SM::kQStride + (32 * gl + 8 * p4) * 2) = w;
+    }
+    float dm[SP];
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) dm[16 * rb + i] = dM[rb][i] + si * z[16 * rb + i];
+    float dq[DP];
+#pragma unroll
+    for (int c = 0; c < DP; ++c) dq[c] = 0.0f;
+    query_monomials_grad<DP>(qf, dm, dq);
+    float other[DP];
+#pragma unroll
+    for (int c = 0; c < DP; ++c) other[c] = partner32(dq[c]);
+    if (live && gl == 0) {
+#pragma unroll
+      for (int c = 0; c < DP; ++c) dfeat[th * g.nfeat + c] = dq[c] + other[DP - 1 - c];
+    }
+    wave_lds_sync();
+    // dCsym[(g,s) rows x D] += Qm^T[64 x 32 tokens] g[32 tokens x D]
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      const int krow = 16 * ks + 8 * gl + L / 4;
+      u32x4 a[2];
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb) {
+        const unsigned char* p = qs + krow * SM::kQStride + (32 * rb + 16 * (q % 2) + 4 * (L % 4)) * 2;
+        const u32x2 lo = lds_read_tr16(p);
+        const u32x2 hi = lds_read_tr16(p + 4 * SM::kQStride);
+        a[rb][0] = lo[0];
+        a[rb][1] = lo[1];
+        a[rb][2] = hi[0];
+        a[rb][3] = hi[1];
+      }
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb) {
+        const unsigned char* p = gs + krow * SM::kRow + (32 * cb + 16 * (q % 2) + 4 * (L % 4)) * 2;
+        const u32x2 lo = lds_read_tr16(p);
+        const u32x2 hi = lds_read_tr16(p + 4 * SM::kRow);
+        u32x4 b;
+        b[0] = lo[0];
+        b[1] = lo[1];
+        b[2] = hi[0];
+        b[3] = hi[1];
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) dC[rb][cb] = mfma32(a[rb], b, dC[rb][cb]);
+      }
+    }
+    wave_lds_sync();
+  }
+  // dz: sum over the 32 token lanes of each half
+#pragma unroll
+  for (int s = 0; s < SP; ++s) {
+    float v = dzacc[s];
+#pragma unroll
+    for (int m = 1; m < 32; m <<= 1) v += __shfl_xor(v, m, 64);
+    dzacc[s] = v;
+  }
+  float* red = reinterpret_cast<float*>(smem);
+  __syncthreads();
+  for (int i = threadIdx.x; i < 64 * D + 64; i += kThreads) red[i] = 0.0f;
+  for (int w = 0; w < kWaves; ++w) {
+    __syncthreads();
+    if (wave == w) {
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int row = 32 * rb + d_row(i, gl);  // = 32 g' + s' : column of the Qm tile
+          const int m = cm.canon[row / 32][row % 32];
+          if (m >= 0) {
+#pragma unroll
+            for (int cb = 0; cb < NCB; ++cb) red[m * D + 32 * cb + r] += dC[rb][cb][i];
+          }
+        }
+      }
+      if (r == 0) {
+#pragma unroll
+        for (int s = 0; s < SP; ++s) {
+          const int m = cm.canon[gl][s];
+          if (m >= 0) red[64 * D + m] += dzacc[s];
+        }
+      }
+    }
+  }
+  __syncthreads();
+  float* out = partial + (static_cast<int64_t>(blockIdx.x) * g.H + h) * partial_stride;
+  for (int i = threadIdx.x; i < 64 * D + 64; i += kThreads) out[i] = red[i];
+}
+
+// ---- k_bwd_key --------------------------------------------------------------------------------
+template <int D>
+struct BwdKSmem {
+  static constexpr int kRow = D * 2 + 32;
+  static constexpr int kWaveBytes = 32 * kRow;
+  static constexpr int kTotal = kWaves * kWaveBytes;
+};
+
+// grid (blocks of kQueryBlock tokens, H), block 256.  Per 32-token tile and lane (token r, gl):
+//   dS^T = dCsym V^T (+ dzsym) -> chain rule to d(phi_k1..3);  dV^T = dCsym^T S^T.
+template <int DP, int D>
+__global__ __launch_bounds__(kThreads) void k_bwd_key(Geom g, const BlockEnt* __restrict__ blocks,
+                                                      const float* __restrict__ feat,
+                                                      const unsigned char* __restrict__ dops, View V,
+                                                      float* __restrict__ dfeat, View dV) {
+  using SY = Sym3<DP>;
+  using SL = StateLayout<DP, D>;
+  using SM = BwdKSmem<D>;
+  constexpr int SP = SY::SP, MP = SY::MP;
+  constexpr int NRB = D / 32, NKS = MP / 16, NKD = D / 16;
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  unsigned char* vs = smem + wave * SM::kWaveBytes;
+  const int r = lane % 32, gl = lane / 32;
+  const BlockEnt e = blocks[blockIdx.x];
+  const int h = blockIdx.y;
+  const int64_t u = static_cast<int64_t>(e.seq) * g.H + h;
+  const u32x4* opA = reinterpret_cast<const u32x4*>(dops + u * SL::kOpBytes);
+  const u32x4* opB = reinterpret_cast<const u32x4*>(dops + u * SL::kOpBytes + SL::kOpElems * 2);
+  const float* dzslot = reinterpret_cast<const float*>(dops + u * SL::kOpBytes + 2 * SL::kOpElems * 2) + gl * SP;
+  u32x4 a_ch[NRB][NKS], a_mo[2][NKD];
+#pragma unroll
+  for (int rb = 0; rb < NRB; ++rb)
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) a_ch[rb][ks] = opA[(rb * NKS + ks) * 64 + lane];
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+    for (int ks = 0; ks < NKD; ++ks) a_mo[rb][ks] = opB[(rb * NKD + ks) * 64 + lane];
+  float dz[SP];
+#pragma unroll
+  for (int s = 0; s < SP; ++s) dz[s] = dzslot[s];
+
+  for (int n0 = e.t0 + wave * 32; n0 < e.t1; n0 += kWaves * 32) {
+    stage_tile32<D>(V, e.b, h, n0, e.t1, lane, vs, SM::kRow);
+    wave_lds_sync();
+    const int n = n0 + r;
+    const bool live = n < e.t1;
+    const int64_t th = g.th(e.b, h, live ? n : e.t0);
+    f32x16 dS[2];
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) dS[rb][i] = 0.0f;
+#pragma unroll
+    for (int ks = 0; ks < NKD; ++ks) {
+      const u32x4 bv = *reinterpret_cast<const u32x4*>(vs + r * SM::kRow + (16 * ks + 8 * gl) * 2);
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb) dS[rb] = mfma32(a_mo[rb][ks], bv, dS[rb]);
+    }
+    float k1[DP], k2[DP], k3[DP];
+    if (live) {
+      const float* f = feat + th * g.nfeat + DP;
+#pragma unroll
+      for (int c = 0; c < DP; ++c) {
+        const int cc = gl ? DP - 1 - c : c;
+        k1[c] = f[cc];
+        k2[c] = f[DP + cc];
+        k3[c] = f[2 * DP + cc];
+      }
+    } else {
+#pragma unroll
+      for (int c = 0; c < DP; ++c) k1[c] = k2[c] = k3[c] = 0.0f;
+    }
+    {
+      float ds[SP];
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) ds[16 * rb + i] = dS[rb][i] + dz[16 * rb + i];
+      float dk1[DP], dk2[DP], dk3[DP];
+#pragma unroll
+      for (int c = 0; c < DP; ++c) dk1[c] = dk2[c] = dk3[c] = 0.0f;
+      key_monomials_grad<DP>(k1, k2, k3, ds, dk1, dk2, dk3);
+      float o1[DP], o2[DP], o3[DP];
+#pragma unroll
+      for (int c = 0; c < DP; ++c) {
+        o1[c] = partner32(dk1[c]);
+        o2[c] = partner32(dk2[c]);
+        o3[c] = partner32(dk3[c]);
+      }
+      if (live && gl == 0) {
+        float* df = dfeat + th * g.nfeat + DP;
+#pragma unroll
+        for (int c = 0; c < DP; ++c) {
+          df[c] = dk1[c] + o1[DP - 1 - c];
+          df[DP + c] = dk2[c] + o2[DP - 1 - c];
+          df[2 * DP + c] = dk3[c] + o3[DP - 1 - c];
+        }
+      }
+    }
+    float sm[SP];
+    key_monomials_slots<DP>(k1, k2, k3, sm);
+    f32x16 acc[NRB];
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[rb][i] = 0.0f;
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) {
+      u32x4 b;
+#pragma unroll
+      for (int p = 0; p < 4; ++p) b[p] = pack_bf16(sm[8 * ks + 2 * p], sm[8 * ks + 2 * p + 1]);
+#pragma unroll
+      for (int rb = 0; rb < NRB; ++rb) acc[rb] = mfma32(a_ch[rb][ks], b, acc[rb]);
+    }
+    if (live) {
+      bf16_t* orow = dV.row<bf16_t>(e.b, h, n);
+#pragma unroll
+      for (int rb = 0; rb < NRB; ++rb)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          u32x2 w;
+          w[0] = pack_bf16(acc[rb][4 * q4], acc[rb][4 * q4 + 1]);
+          w[1] = pack_bf16(acc[rb][4 * q4 + 2], acc[rb][4 * q4 + 3]);
+          *reinterpret_cast<u32x2*>(orow + 32 * rb + 8 * q4 + 4 * gl) = w;
+        }
+    }
+    wave_lds_sync();
+  }
+}
+
+inline int pick_chunk(const Geom& g, int num_seqs) {
+  // smallest power of two >= 256 that keeps the grid at or under ~3 workgroups per CU
+  int chunk = 256;
+  const int64_t tokens = static_cast<int64_t>(g.B) * g.N;
+  while ((tokens / chunk + num_seqs) * g.H > 768 && chunk < (1 << 20)) chunk *= 2;
+  return chunk;
+}
+
+template <typename K>
+hla_status allow_big_lds(K kernel, int bytes) {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, bytes) == hipSuccess
+             ? HLA_OK
+             : HLA_ERR_HIP;
+}
+
+template <int DP, int D>
+hla_status backward_core(hla_handle* hd, const hla_call_args& a) {
+  using SL = StateLayout<DP, D>;
+  Geom g = hd->g;
+  hipStream_t s = a.stream;
+  const int chunk = pick_chunk(g, a.num_seqs);
+  hla_token_table *chunks = nullptr, *qblocks = nullptr;
+  HLA_TRY(get_table(hd, chunk, s, &chunks));
+  HLA_TRY(get_table(hd, kQueryBlock, s, &qblocks));
+  static bool attr_set = false;
+  if (!attr_set) {
+    HLA_TRY(allow_big_lds(&k_bwd_query<DP, D>, BwdQSmem<D>::kTotal));
+    HLA_TRY(allow_big_lds(&k_bwd_key<DP, D>, BwdKSmem<D>::kTotal));
+    attr_set = true;
+  }
+  unsigned char* ops = static_cast<unsigned char*>(hd->path_ws);
+  unsigned char* dops = ops + SL::kOpBytes * hd->max_units;
+  HLA_TRY(launch(hd, "mfma_bwd_query", k_bwd_query<DP, D>, dim3(chunks->count, g.H), dim3(kThreads),
+                 BwdQSmem<D>::kTotal, s, g, chunks->dev, hd->feat, hd->den, ops, a.dO, a.O, hd->dfeat,
+                 hd->partial, SL::kF32, make_canon_map<DP>()));
+  HLA_TRY(launch(hd, "mfma_dstate_reduce", k_reduce<DP, D>, dim3(a.num_seqs, g.H, kReduceSlices),
+                 dim3(256), 0, s, g, chunks->seq_off_dev, hd->partial, SL::kF32, hd->dstate, dops,
+                 make_slot_map<DP>()));
+  HLA_TRY(launch(hd, "mfma_bwd_key", k_bwd_key<DP, D>, dim3(qblocks->count, g.H), dim3(kThreads),
+                 BwdKSmem<D>::kTotal, s, g, qblocks->dev, hd->feat, dops, a.V, hd->dfeat, a.dV));
+  return HLA_OK;
+}
+
 template <int DP, int D>
 hla_status forward_core(hla_handle* hd, const hla_call_args& a) {
   using SL = StateLayout<DP, D>;
   using SM = StateSmem<D>;
   Geom g = hd->g;
   hipStream_t s = a.stream;
-  // chunk size: smallest power of two >= 256 that keeps the grid at or under ~3 workgroups per CU
-  int chunk = 256;
-  const int64_t tokens = static_cast<int64_t>(g.B) * g.N;
-  while ((tokens / chunk + a.num_seqs) * g.H > 768 && chunk < (1 << 20)) chunk *= 2;
+  const int chunk = pick_chunk(g, a.num_seqs);
   hla_token_table *chunks = nullptr, *qblocks = nullptr;
   HLA_TRY(get_table(hd, chunk, s, &chunks));
   HLA_TRY(get_table(hd, kQueryBlock, s, &qblocks));
@@ -413,6 +823,14 @@ hla_status mfma_forward(hla_handle* hd, const hla_call_args& a) {
   return forward_core<6, 64>(hd, a);
 }
 
-hla_status mfma_backward(hla_handle*, const hla_call_args&) { return HLA_ERR_UNSUPPORTED; }
+hla_status mfma_backward(hla_handle* hd, const hla_call_args& a) {
+  if (!aligned16(a.V) || !aligned16(a.O) || !aligned16(a.dO) || !aligned16(a.dV))
+    return HLA_ERR_UNSUPPORTED;
+  if (hd->g.d == 128)
+    HLA_TRY((backward_core<6, 128>(hd, a)));
+  else
+    HLA_TRY((backward_core<6, 64>(hd, a)));
+  return generic_features_out(hd, a);
+}
 
 }  // namespace hla

@@ -10,7 +10,7 @@ from tests import parity_utils as pu
 
 pytestmark = pytest.mark.gpu
 
-BWD = False
+BWD = True
 
 
 @pytest.mark.parametrize("d,N,kind", [
