@@ -1,0 +1,179 @@
+#!/usr/bin/env python3
+"""Throughput of the HLA hot path (feature maps -> key-side state -> query contraction, and
+the matching backward) on one MI355X, on synthetic video-DiT-shaped inputs.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3] [--features]
+
+A step is one forward + backward of the whole path over the configuration's batch, inputs
+resident in HBM.  Prints ONE JSON line: tokens/s (all heads of a token count once), the nominal
+TFLOP/s, a `roofline` object for the kernel that takes the most time (HIP-event durations taken
+inside the library around every launch) and a `cpu_baseline` object (the fp64 oracle timed on
+this host's cores over a bounded sample of the same workload).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=3, help="BASELINE configuration 2..5 (default 3)")
+    ap.add_argument("--features", action="store_true",
+                    help="feature-level interface (Q,K already phi-mapped): times the core alone")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--path", choices=["auto", "generic", "mfma"], default="auto")
+    return ap.parse_args()
+
+
+def cpu_baseline(w, phi, backward, features):
+    """Oracle (as it stands) on a bounded sample: the first heads of batch row / sequence 0."""
+    import numpy as np
+    import torch
+
+    from oracle import hla_oracle as orc
+    from tests import parity_utils as pu
+
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    H = w.H
+    n_seq = w.N if w.cu_seqlens is None else w.cu_seqlens[1] - w.cu_seqlens[0]
+    # about 2.5 s per 32760-token head on 8 cores: take enough heads for ~10 s
+    heads = max(1, min(H, int(round(4 * 32760 / max(n_seq, 1)))))
+    sl = (slice(0, 1), slice(0, heads), slice(0, n_seq))
+    t = {k: pu.to_np(v[sl]) for k, v in w.tensors.items()}
+    ophi = None if features else pu.oracle_phi(phi)
+    t0 = time.perf_counter()
+    orc.hla_operator_forward(t["Q"], t["K"], t["V"], w.F, w.d_phi, w.eps, phi=ophi)
+    if backward:
+        orc.hla_operator_backward(t["Q"], t["K"], t["V"], t["dO"], w.F, w.d_phi, w.eps, phi=ophi)
+    dt = time.perf_counter() - t0
+    # whole-job rate: a token counts once all H heads are done
+    value = n_seq / (dt * H / heads)
+    return {"value": value, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{heads} of {H} heads of one {n_seq}-token sequence, "
+                      f"{'fwd+bwd' if backward else 'fwd'}, fp64 numpy, {dt:.1f} s"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    import paper_2602_12128_amd as hla
+    from paper_2602_12128_amd import flops
+    from paper_2602_12128_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    hla.load_library()
+    dev = torch.device("cuda:0")
+    w = wl.make_workload(args.config)
+    backward = w.backward
+    phi = w.phi
+    if args.features:
+        ft = wl.make_feature_inputs(w.seed, w.B, w.H, w.N, w.d, w.F, w.d_phi, w.dtype)
+        w.tensors["Q"], w.tensors["K"] = ft["Q"], ft["K"]
+        phi = None
+    t = {k: v.to(dev) for k, v in w.tensors.items()}
+    nseq = w.B if w.cu_seqlens is None else len(w.cu_seqlens) - 1
+    path = {"auto": hla.HLA_PATH_AUTO, "generic": hla.HLA_PATH_GENERIC, "mfma": hla.HLA_PATH_MFMA}[args.path]
+    h = hla.HLA(head_dim=w.d, feature_dim=w.d_phi, degree=w.F, eps=w.eps,
+                io_dtype=hla.HLA_F32 if w.dtype == torch.float32 else hla.HLA_BF16,
+                phi_mode=hla.HLA_PHI_NONE if phi is None else hla.HLA_PHI_MLP, kernel_path=path,
+                max_heads=w.H, max_tokens=w.B * w.N, max_seqs=nseq)
+    if phi is not None:
+        h.set_phi_weights([{k: v.to(dev) for k, v in m.items()} for m in phi])
+    O = torch.empty_like(t["V"])
+    grads = [torch.empty_like(t[k]) for k in ("Q", "K", "V")] if backward else None
+
+    def step():
+        h.forward(t["Q"], t["K"], t["V"], O, cu_seqlens=w.cu_seqlens)
+        if backward:
+            h.backward(t["Q"], t["K"], t["V"], O, t["dO"], *grads, cu_seqlens=w.cu_seqlens)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = 1e3 * elapsed / args.steps
+
+    # per-kernel durations: the same K steps again with the library's event pairs switched on
+    h.profile_enable(True)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    prof = h.profile_read()
+    h.profile_enable(False)
+    kernels = {p["kernel"]: {"avg_us": 1e3 * p["total_ms"] / p["launches"],
+                             "launches_per_step": p["launches"] / args.steps} for p in prof}
+    sum_us = sum(k["avg_us"] * k["launches_per_step"] for k in kernels.values())
+
+    tokens = w.N * w.B
+    th = w.token_heads
+    tok_s = tokens / (elapsed / args.steps)
+    fl = flops.path_flops(w.d, w.d_phi, w.F, backward, phi is not None) * th
+    by = flops.path_bytes(w.d, w.d_phi, w.F, backward, phi is not None) * th
+    tflops = fl / (elapsed / args.steps) / 1e12
+
+    roofline = None
+    if kernels:
+        dom = max(kernels, key=lambda k: kernels[k]["avg_us"] * kernels[k]["launches_per_step"])
+        model = flops.kernel_model(dom, w.d, w.d_phi, w.F)
+        if model is not None:
+            kb, kf, bound = model
+            peak, unit = flops.PEAKS[bound]
+            dur = kernels[dom]["avg_us"] * 1e-6
+            achieved = (kb * th / dur / 1e9) if bound == "hbm" else (kf * th / dur / 1e12)
+            roofline = {"kernel": dom, "bound": bound, "achieved": achieved, "peak": peak,
+                        "unit": unit, "frac": achieved / peak, "traffic": None,
+                        "avg_launch_us": kernels[dom]["avg_us"],
+                        "algorithmic_bytes_per_launch": kb * th,
+                        "nominal_flops_per_launch": kf * th}
+
+    out = {
+        "metric": "HLA fwd+bwd tokens/s" if backward else "HLA fwd tokens/s",
+        "value": tok_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if w.dtype == torch.bfloat16 else "f32",
+        "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "H": w.H, "N": w.N, "d": w.d, "F": w.F,
+                   "d_phi": w.d_phi, "phi": "mlp" if phi is not None else "none",
+                   "packed_seqs": nseq if w.cu_seqlens else 0,
+                   "path": "mfma" if h.active_path == hla.HLA_PATH_MFMA else "generic"},
+        "tflops_nominal": tflops,
+        "mfma_peak_frac_nominal": tflops / 2500.0,
+        "hbm_frac_whole_path": by / (elapsed / args.steps) / 8e12,
+        "kernels_us": {k: round(v["avg_us"] * v["launches_per_step"], 2) for k, v in kernels.items()},
+        "kernels_sum_us": round(sum_us, 2),
+        "roofline": roofline,
+    }
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(w, phi, backward, args.features)
+    h.destroy()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -83,11 +83,30 @@ def run_oracle(tensors, F, d_phi, eps, phi=None, cu_seqlens=None, backward=True,
     return out
 
 
-def assert_parity(gpu, ref, tol, what=""):
+def relu_kink_masks(tensors, phi, F, band):
+    """Token masks (True = compare) for dQ and dK.  The ReLU of the feature maps makes the
+    gradient discontinuous where a pre-activation u crosses zero; a token whose |u| is within
+    the arithmetic's error `band` of zero may take the other branch on the GPU (which decides in
+    its own precision), so its gradient row is compared only through the finiteness check."""
+    ophi = oracle_phi(phi)
+    Q, K = to_np(tensors["Q"]), to_np(tensors["K"])
+    uq = np.abs(orc.phi_forward(Q, *ophi[0].astuple())[2]).min(-1)
+    uk = np.minimum.reduce([np.abs(orc.phi_forward(K, *ophi[1 + f].astuple())[2]).min(-1)
+                            for f in range(F)])
+    return {"dQ": uq > band, "dK": uk > band}
+
+
+def assert_parity(gpu, ref, tol, what="", row_masks=None):
     errs = {}
     for k, r in ref.items():
         g = to_np(gpu[k])
         assert np.isfinite(g).all(), f"{what}: {k} has non-finite entries"
+        if row_masks is not None and k in row_masks:
+            m = row_masks[k]
+            assert m.mean() > 0.8, f"{what}: kink band excludes too many rows of {k}"
+            scale = np.abs(r).max()
+            errs[k] = float(np.abs(g - r)[m].max() / scale) if m.any() else 0.0
+            continue
         errs[k] = max_rel_err(g, r)
     msg = ", ".join(f"{k}={e:.2e}" for k, e in errs.items())
     print(f"[parity] {what}: {msg} (tol {tol:g})", flush=True)
