@@ -136,6 +136,17 @@ const char* hla_status_string(hla_status s);
 /* Which path serves the handle: HLA_PATH_GENERIC or HLA_PATH_MFMA (never AUTO); -1 for NULL. */
 int32_t hla_active_path(const hla_handle* h);
 
+/* Intermediate results of the last forward / backward, for tests of the individual steps:
+ *   HLA_WS_FEATURES      [B*H*N][(1+F)*d_phi] fp32: phi_q, then phi_k1..phi_kF of every token-head
+ *                        (Alg. 1 Step 4), row index (b*H + h)*N + n
+ *   HLA_WS_FEATURE_GRADS same layout: gradient w.r.t. those features (after hla_backward)
+ *   HLA_WS_DENOMINATORS  [B*H*N] fp32: eta + eps (Sec. 4.2 normaliser)
+ * Copies `count` floats to the HOST buffer `host_dst` after synchronising `hip_stream`.  count
+ * above what the last call produced is HLA_ERR_INVALID_ARG. */
+typedef enum { HLA_WS_FEATURES = 0, HLA_WS_FEATURE_GRADS = 1, HLA_WS_DENOMINATORS = 2 } hla_workspace_kind;
+hla_status hla_read_workspace(hla_handle* h, int32_t kind, float* host_dst, int64_t count,
+                              void* hip_stream);
+
 /* Per-kernel timing for bench harnesses.  While enabled, every kernel the handle launches is
  * bracketed by a pair of HIP events on the caller's stream.  Enabling (or re-enabling) clears the
  * accumulated records; at most HLA_PROFILE_MAX_RECORDS launches are recorded, later ones run

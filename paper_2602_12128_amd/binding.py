@@ -22,7 +22,9 @@ HLA_PATH_AUTO, HLA_PATH_GENERIC, HLA_PATH_MFMA = 0, 1, 2
 EXPORTS = (
     "hla_create", "hla_set_phi_weights", "hla_forward", "hla_backward", "hla_destroy",
     "hla_status_string", "hla_active_path", "hla_profile_enable", "hla_profile_read",
+    "hla_read_workspace",
 )
+HLA_WS_FEATURES, HLA_WS_FEATURE_GRADS, HLA_WS_DENOMINATORS = 0, 1, 2
 
 
 class hla_config(C.Structure):
@@ -88,6 +90,8 @@ def load_library() -> C.CDLL:
     lib.hla_profile_read.argtypes = [H, C.c_int32, C.POINTER(C.c_char_p), C.POINTER(C.c_double),
                                      C.POINTER(C.c_int64)]
     lib.hla_profile_read.restype = C.c_int32
+    lib.hla_read_workspace.argtypes = [H, C.c_int32, C.POINTER(C.c_float), C.c_int64, C.c_void_p]
+    lib.hla_read_workspace.restype = C.c_int
     _lib = lib
     return lib
 
@@ -185,6 +189,15 @@ class HLA:
         _check(self._lib.hla_backward(self._h, B, H, N, cu, ns, _view(Q), _view(K), _view(V),
                                       _view(O), _view(dO), _view(dQ), _view(dK), _view(dV),
                                       _stream_ptr(stream)), "hla_backward")
+
+    # -- hla_read_workspace
+    def read_workspace(self, kind: int, count: int, stream=None):
+        """Returns a numpy float32 array of `count` values of the requested intermediate."""
+        import numpy as np
+        out = np.empty(count, dtype=np.float32)
+        _check(self._lib.hla_read_workspace(self._h, kind, out.ctypes.data_as(C.POINTER(C.c_float)),
+                                            count, _stream_ptr(stream)), "hla_read_workspace")
+        return out
 
     # -- hla_profile_enable / hla_profile_read
     def profile_enable(self, on: bool):

@@ -356,6 +356,26 @@ hla_status hla_backward(hla_handle* hd, int32_t B, int32_t H, int32_t N, const i
   return hd->path == HLA_PATH_MFMA ? mfma_backward(hd, a) : generic_backward(hd, a);
 }
 
+hla_status hla_read_workspace(hla_handle* hd, int32_t kind, float* host_dst, int64_t count,
+                              void* hip_stream) {
+  if (hd == nullptr || host_dst == nullptr || count < 0) return HLA_ERR_INVALID_ARG;
+  if (!hd->have_forward) return HLA_ERR_STATE;
+  const int64_t th = static_cast<int64_t>(hd->fw_B) * hd->fw_H * hd->fw_N;
+  const float* src = nullptr;
+  int64_t avail = 0;
+  switch (kind) {
+    case HLA_WS_FEATURES: src = hd->feat; avail = th * hd->g.nfeat; break;
+    case HLA_WS_FEATURE_GRADS: src = hd->dfeat; avail = th * hd->g.nfeat; break;
+    case HLA_WS_DENOMINATORS: src = hd->den; avail = th; break;
+    default: return HLA_ERR_INVALID_ARG;
+  }
+  if (count > avail) return HLA_ERR_INVALID_ARG;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  HLA_HIP_TRY(hipStreamSynchronize(s));
+  if (count > 0) HLA_HIP_TRY(hipMemcpy(host_dst, src, count * sizeof(float), hipMemcpyDeviceToHost));
+  return HLA_OK;
+}
+
 hla_status hla_profile_enable(hla_handle* hd, int32_t on) {
   if (hd == nullptr) return HLA_ERR_INVALID_ARG;
   hd->prof.on = on != 0;

@@ -45,6 +45,7 @@ struct hla_handle {
   int64_t max_chunks = 0;
   void* path_ws = nullptr;         // extra path-owned device memory (repacked weights, bf16 state)
   size_t path_ws_bytes = 0;
+  size_t w_packed_off = 0;         // byte offset of the MFMA path's packed feature-map weights in path_ws
 
   // feature-map weights, fp32 copies (both paths keep them; the MFMA path adds packed bf16)
   float* w_f32 = nullptr;
@@ -95,6 +96,12 @@ hla_status mfma_workspace_plan(hla_handle* hd);
 hla_status mfma_set_weights(hla_handle* hd, hipStream_t s);
 hla_status mfma_forward(hla_handle* hd, const hla_call_args& a);
 hla_status mfma_backward(hla_handle* hd, const hla_call_args& a);
+
+// Feature maps on matrix cores (hla_mfma_phi.hip).
+size_t mfma_phi_packed_bytes(const hla_handle* hd);
+hla_status mfma_phi_set_weights(hla_handle* hd, hipStream_t s);
+hla_status mfma_phi_forward(hla_handle* hd, const hla_call_args& a);
+hla_status mfma_phi_backward(hla_handle* hd, const hla_call_args& a);
 
 // Shared helper kernels' host wrappers (hla_generic.hip).
 hla_status convert_weights_to_f32(hla_handle* hd, const hla_phi_weights* maps, hipStream_t s);

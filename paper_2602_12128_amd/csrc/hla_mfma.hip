@@ -357,26 +357,6 @@ CanonMap make_canon_map() {
   return cm;
 }
 
-// Stage a [32 tokens x D] bf16 tile row-major into LDS with coalesced 16-byte loads; rows at or
-// beyond t1 are zero.  Row stride `stride` bytes.
-template <int D>
-__device__ __forceinline__ void stage_tile32(const View& X, int b, int h, int n0, int t1, int lane,
-                                             unsigned char* dst, int stride) {
-  constexpr int PIECES = D / 8;
-  constexpr int RPL = 64 / PIECES;
-  constexpr int NLD = 32 / RPL;
-  const int prow = lane / PIECES, pcol = lane % PIECES;
-#pragma unroll
-  for (int i = 0; i < NLD; ++i) {
-    const int row = i * RPL + prow;
-    const int n = n0 + row;
-    u32x4 v;
-    v[0] = v[1] = v[2] = v[3] = 0u;
-    if (n < t1) v = *reinterpret_cast<const u32x4*>(X.row<const bf16_t>(b, h, n) + pcol * 8);
-    *reinterpret_cast<u32x4*>(dst + row * stride + pcol * 16) = v;
-  }
-}
-
 // ---- k_bwd_query ------------------------------------------------------------------------------
 template <int D>
 struct BwdQSmem {
@@ -809,16 +789,23 @@ hla_status mfma_workspace_plan(hla_handle* hd) {
   // per unit: opA + opB (bf16) + zslot, for the state and for its gradient
   const int64_t op_bytes = 2 * MP * g.d * 2 + 2 * SP * 4;
   hd->path_ws_bytes = static_cast<size_t>(2 * op_bytes * hd->max_units);
+  hd->w_packed_off = hd->path_ws_bytes;
+  if (hd->cfg.phi_mode == HLA_PHI_MLP) hd->path_ws_bytes += mfma_phi_packed_bytes(hd);
   for (int sz = 256; sz <= (1 << 20); sz *= 2) hd->tables[sz];
   hd->tables[kQueryBlock];
   return HLA_OK;
 }
 
-hla_status mfma_set_weights(hla_handle*, hipStream_t) { return HLA_OK; }
+hla_status mfma_set_weights(hla_handle* hd, hipStream_t s) { return mfma_phi_set_weights(hd, s); }
 
 hla_status mfma_forward(hla_handle* hd, const hla_call_args& a) {
   if (!aligned16(a.V) || !aligned16(a.O)) return HLA_ERR_UNSUPPORTED;
-  HLA_TRY(generic_features_in(hd, a));
+  if (hd->cfg.phi_mode == HLA_PHI_MLP) {
+    if (!aligned16(a.Q) || !aligned16(a.K)) return HLA_ERR_UNSUPPORTED;
+    HLA_TRY(mfma_phi_forward(hd, a));
+  } else {
+    HLA_TRY(generic_features_in(hd, a));
+  }
   if (hd->g.d == 128) return forward_core<6, 128>(hd, a);
   return forward_core<6, 64>(hd, a);
 }
@@ -830,6 +817,11 @@ hla_status mfma_backward(hla_handle* hd, const hla_call_args& a) {
     HLA_TRY((backward_core<6, 128>(hd, a)));
   else
     HLA_TRY((backward_core<6, 64>(hd, a)));
+  if (hd->cfg.phi_mode == HLA_PHI_MLP) {
+    if (!aligned16(a.Q) || !aligned16(a.K) || !aligned16(a.dQ) || !aligned16(a.dK))
+      return HLA_ERR_UNSUPPORTED;
+    return mfma_phi_backward(hd, a);
+  }
   return generic_features_out(hd, a);
 }
 

@@ -69,6 +69,26 @@ __device__ __forceinline__ void wave_lds_sync() {
 // value held by the lane 32 away (the other half of a (token, g) lane pair)
 __device__ __forceinline__ float partner32(float v) { return __shfl_xor(v, 32, 64); }
 
+// Stage a [32 tokens x D] bf16 tile row-major into LDS with coalesced 16-byte loads; rows at or
+// beyond t1 are zero.  Row stride `stride` bytes.
+template <int D>
+__device__ __forceinline__ void stage_tile32(const View& X, int b, int h, int n0, int t1, int lane,
+                                             unsigned char* dst, int stride) {
+  constexpr int PIECES = D / 8;
+  constexpr int RPL = 64 / PIECES;
+  constexpr int NLD = 32 / RPL;
+  const int prow = lane / PIECES, pcol = lane % PIECES;
+#pragma unroll
+  for (int i = 0; i < NLD; ++i) {
+    const int row = i * RPL + prow;
+    const int n = n0 + row;
+    u32x4 v;
+    v[0] = v[1] = v[2] = v[3] = 0u;
+    if (n < t1) v = *reinterpret_cast<const u32x4*>(X.row<const bf16_t>(b, h, n) + pcol * 8);
+    *reinterpret_cast<u32x4*>(dst + row * stride + pcol * 16) = v;
+  }
+}
+
 template <int I, int N, class Fn>
 __device__ __forceinline__ void static_for(Fn&& f) {
   if constexpr (I < N) {

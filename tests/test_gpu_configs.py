@@ -15,7 +15,7 @@ pytestmark = pytest.mark.gpu
 
 # |pre-ReLU| below this is within the GPU feature maps' rounding error of the kink (see
 # parity_utils.relu_kink_masks); such rows are excluded from the dQ/dK comparison.
-KINK_BAND = 1e-4
+KINK_BAND = 1e-2
 
 
 def _head_slice(tensors, heads):
