@@ -61,8 +61,22 @@ static void build_table_host(const hla_handle* hd, int32_t bs, std::vector<Block
 }
 
 hla_status get_table(hla_handle* hd, int32_t block_tokens, hipStream_t s, hla_token_table** out) {
+  if (block_tokens <= 0) return HLA_ERR_INVALID_ARG;
   auto it = hd->tables.find(block_tokens);
-  if (it == hd->tables.end()) return HLA_ERR_STATE;  // block size not planned at create
+  if (it == hd->tables.end()) {
+    // a block size first seen with this call shape: its (small) table is allocated once and kept
+    hla_token_table nt;
+    nt.block_tokens = block_tokens;
+    nt.capacity = (hd->cfg.max_tokens + block_tokens - 1) / block_tokens + hd->cfg.max_seqs;
+    if (hipMalloc(reinterpret_cast<void**>(&nt.dev), nt.capacity * sizeof(BlockEnt)) != hipSuccess)
+      return HLA_ERR_ALLOC;
+    if (hipMalloc(reinterpret_cast<void**>(&nt.seq_off_dev),
+                  (hd->cfg.max_seqs + 1) * sizeof(int32_t)) != hipSuccess) {
+      (void)hipFree(nt.dev);
+      return HLA_ERR_ALLOC;
+    }
+    it = hd->tables.emplace(block_tokens, nt).first;
+  }
   hla_token_table& t = it->second;
   if (!t.valid) {
     std::vector<BlockEnt> ents;

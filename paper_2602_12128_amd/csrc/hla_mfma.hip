@@ -18,7 +18,8 @@ using namespace mf;
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
 constexpr int kQueryBlock = 1024;  // tokens per workgroup in token-parallel kernels
-constexpr int kReduceSlices = 8;
+constexpr int kChunkTarget = 240;   // workgroups aimed at by the chunked (token-contraction) kernels
+constexpr int kReduceSlices = 32;  // row slices of the state per (sequence, head) in k_reduce
 
 // Where canonical monomial m sits among the (g, slot) pairs.
 struct SlotMap {
@@ -74,11 +75,6 @@ __global__ __launch_bounds__(kThreads) void k_state(Geom g, const BlockEnt* __re
   using SM = StateSmem<D>;
   static_assert(SY::MP == 64, "state kernel is laid out for a 64-row padded state");
   constexpr int NCB = D / 32;      // column blocks of the state
-  constexpr int NVL = D * 2 / 16 * 64 / 64;  // 16-byte pieces per token row = D/8
-  constexpr int PIECES = D / 8;    // 16-byte pieces per row
-  constexpr int ROWS_PER_LD = 64 / PIECES;   // token rows covered by one wave-wide 16 B load
-  constexpr int NLD = 64 / ROWS_PER_LD;      // loads per 64-token tile
-  (void)NVL;
   extern __shared__ __align__(16) unsigned char smem[];
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
   unsigned char* vs = smem + wave * SM::kWaveBytes;
@@ -102,34 +98,34 @@ __global__ __launch_bounds__(kThreads) void k_state(Geom g, const BlockEnt* __re
   u32x4 ones;
   ones[0] = ones[1] = ones[2] = ones[3] = 0x3f803f80u;  // bf16 1.0 pairs
 
-  const int prow = lane / PIECES, pcol = lane % PIECES;
-  for (int n0 = e.t0 + wave * 64; n0 < e.t1; n0 += kWaves * 64) {
-    // ---- V tile: coalesced 16-byte loads, rows beyond the chunk are zero
+  // the next sub-tile's V rows and key features are fetched while the current one is consumed
+  TileRegs<D, 64> vt;
+  float kf[3 * DP];
+  auto fetch = [&](int n0) {
+    fetch_tile<D, 64>(V, e.b, h, n0, e.t1, lane, vt);
+    const int n = n0 + lane;
+    if (n < e.t1) {
+      const float* f = feat + g.th(e.b, h, n) * g.nfeat + DP;
 #pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-      const int row = i * ROWS_PER_LD + prow;
-      const int n = n0 + row;
-      u32x4 v;
-      v[0] = v[1] = v[2] = v[3] = 0u;
-      if (n < e.t1) v = *reinterpret_cast<const u32x4*>(V.row<const bf16_t>(e.b, h, n) + pcol * 8);
-      *reinterpret_cast<u32x4*>(vs + row * SM::kVStride + pcol * 16) = v;
+      for (int a = 0; a < 3 * DP; ++a) kf[a] = f[a];
+    } else {
+#pragma unroll
+      for (int a = 0; a < 3 * DP; ++a) kf[a] = 0.0f;
     }
+  };
+  if (e.t0 + wave * 64 < e.t1) fetch(e.t0 + wave * 64);
+  for (int n0 = e.t0 + wave * 64; n0 < e.t1; n0 += kWaves * 64) {
+    put_tile<D, 64>(vt, lane, vs, SM::kVStride);
     // ---- key monomials of token n0 + lane (all NM, canonical order), as bf16 row of the S tile
     {
       float k1[DP], k2[DP], k3[DP];
-      const int n = n0 + lane;
-      if (n < e.t1) {
-        const float* f = feat + g.th(e.b, h, n) * g.nfeat + DP;
 #pragma unroll
-        for (int a = 0; a < DP; ++a) {
-          k1[a] = f[a];
-          k2[a] = f[DP + a];
-          k3[a] = f[2 * DP + a];
-        }
-      } else {
-#pragma unroll
-        for (int a = 0; a < DP; ++a) k1[a] = k2[a] = k3[a] = 0.0f;
+      for (int a = 0; a < DP; ++a) {
+        k1[a] = kf[a];
+        k2[a] = kf[DP + a];
+        k3[a] = kf[2 * DP + a];
       }
+      if (n0 + kWaves * 64 < e.t1) fetch(n0 + kWaves * 64);
       float sm[SY::NM];
       key_monomials_all<DP>(k1, k2, k3, sm);
       uint32_t packed[32];
@@ -223,7 +219,7 @@ __global__ void k_reduce(Geom g, const int32_t* __restrict__ seq_chunk_off,
                          float* __restrict__ state, unsigned char* __restrict__ ops, SlotMap sm) {
   using SL = StateLayout<DP, D>;
   constexpr int MP = SL::MP, SP = SL::SP;
-  constexpr int CW = D / kReduceSlices;  // channels per slice
+  constexpr int RW = MP / kReduceSlices;  // state rows per slice: RW * D consecutive floats
   const int s = blockIdx.x, h = blockIdx.y, sl = blockIdx.z;
   const int c0 = seq_chunk_off[s], c1 = seq_chunk_off[s + 1];
   const int64_t u = static_cast<int64_t>(s) * g.H + h;
@@ -231,8 +227,8 @@ __global__ void k_reduce(Geom g, const int32_t* __restrict__ seq_chunk_off,
   uint16_t* opA = reinterpret_cast<uint16_t*>(ops + u * SL::kOpBytes);
   uint16_t* opB = opA + SL::kOpElems;
   float* zslot = reinterpret_cast<float*>(opB + SL::kOpElems);
-  for (int idx = threadIdx.x; idx < MP * CW; idx += blockDim.x) {
-    const int m = idx / CW, c = sl * CW + idx % CW;
+  for (int idx = threadIdx.x; idx < RW * D; idx += blockDim.x) {
+    const int m = sl * RW + idx / D, c = idx % D;
     float a = 0.0f;
     for (int ch = c0; ch < c1; ++ch)
       a += partial[(static_cast<int64_t>(ch) * g.H + h) * partial_stride + m * D + c];
@@ -695,11 +691,14 @@ __global__ __launch_bounds__(kThreads) void k_bwd_key(Geom g, const BlockEnt* __
 }
 
 inline int pick_chunk(const Geom& g, int num_seqs) {
-  // smallest power of two >= 256 that keeps the grid at or under ~3 workgroups per CU
-  int chunk = 256;
-  const int64_t tokens = static_cast<int64_t>(g.B) * g.N;
-  while ((tokens / chunk + num_seqs) * g.H > 768 && chunk < (1 << 20)) chunk *= 2;
-  return chunk;
+  // About one workgroup per compute unit over all (sequence, head) units (the kernels hold one
+  // workgroup per CU), in multiples of the 256 tokens a workgroup consumes per round.  With the
+  // mean sequence length L and c chunks wanted per unit: chunks * H <= kChunkTarget + units.
+  const int units = num_seqs * g.H > 0 ? num_seqs * g.H : 1;
+  const int per_unit = kChunkTarget / units > 0 ? kChunkTarget / units : 1;
+  const int64_t mean_len = (static_cast<int64_t>(g.B) * g.N + num_seqs - 1) / (num_seqs > 0 ? num_seqs : 1);
+  const int64_t chunk = ((mean_len + per_unit - 1) / per_unit + 255) / 256 * 256;
+  return static_cast<int>(chunk < 256 ? 256 : chunk);
 }
 
 template <typename K>
@@ -782,16 +781,14 @@ hla_status mfma_workspace_plan(hla_handle* hd) {
   const Geom& g = hd->g;
   const int64_t MP = 64, SP = 32;
   hd->state_stride = MP * g.d + MP;
-  // forward_core keeps chunks * H <= 768 unless the sequences alone exceed that
-  hd->max_chunks = (768 + hd->cfg.max_heads - 1) / hd->cfg.max_heads + hd->cfg.max_seqs +
-                   hd->cfg.max_tokens / (1 << 20) + 2;
+  // pick_chunk keeps chunks * H <= kChunkTarget + num_seqs * H
+  hd->max_chunks = (kChunkTarget + hd->cfg.max_heads - 1) / hd->cfg.max_heads + hd->cfg.max_seqs + 1;
   hd->yhat_floats = 1;
   // per unit: opA + opB (bf16) + zslot, for the state and for its gradient
   const int64_t op_bytes = 2 * MP * g.d * 2 + 2 * SP * 4;
   hd->path_ws_bytes = static_cast<size_t>(2 * op_bytes * hd->max_units);
   hd->w_packed_off = hd->path_ws_bytes;
   if (hd->cfg.phi_mode == HLA_PHI_MLP) hd->path_ws_bytes += mfma_phi_packed_bytes(hd);
-  for (int sz = 256; sz <= (1 << 20); sz *= 2) hd->tables[sz];
   hd->tables[kQueryBlock];
   return HLA_OK;
 }

@@ -89,6 +89,38 @@ __device__ __forceinline__ void stage_tile32(const View& X, int b, int h, int n0
   }
 }
 
+// The same staging split in two so that the global loads of the NEXT tile can be in flight while
+// the current tile is being consumed: fetch_tile issues the loads into registers, put_tile writes
+// them to LDS.  ROWS = tokens per tile (32 or 64).
+template <int D, int ROWS>
+struct TileRegs {
+  static constexpr int PIECES = D / 8;        // 16-byte pieces per token row
+  static constexpr int RPL = 64 / PIECES;     // rows covered by one wave-wide load
+  static constexpr int NLD = ROWS / RPL;      // loads per tile
+  u32x4 v[NLD];
+};
+template <int D, int ROWS>
+__device__ __forceinline__ void fetch_tile(const View& X, int b, int h, int n0, int t1, int lane,
+                                           TileRegs<D, ROWS>& t) {
+  using T = TileRegs<D, ROWS>;
+  const int prow = lane / T::PIECES, pcol = lane % T::PIECES;
+#pragma unroll
+  for (int i = 0; i < T::NLD; ++i) {
+    const int n = n0 + i * T::RPL + prow;
+    t.v[i][0] = t.v[i][1] = t.v[i][2] = t.v[i][3] = 0u;
+    if (n < t1) t.v[i] = *reinterpret_cast<const u32x4*>(X.row<const bf16_t>(b, h, n) + pcol * 8);
+  }
+}
+template <int D, int ROWS>
+__device__ __forceinline__ void put_tile(const TileRegs<D, ROWS>& t, int lane, unsigned char* dst,
+                                         int stride) {
+  using T = TileRegs<D, ROWS>;
+  const int prow = lane / T::PIECES, pcol = lane % T::PIECES;
+#pragma unroll
+  for (int i = 0; i < T::NLD; ++i)
+    *reinterpret_cast<u32x4*>(dst + (i * T::RPL + prow) * stride + pcol * 16) = t.v[i];
+}
+
 template <int I, int N, class Fn>
 __device__ __forceinline__ void static_for(Fn&& f) {
   if constexpr (I < N) {

@@ -155,21 +155,29 @@ __device__ __forceinline__ void first_layer(const unsigned char* wm, const u32x4
 #pragma unroll
       for (int e = 0; e < 4; ++e) acc[rb][4 * q4 + e] = bv[e];
     }
-#pragma unroll
-  for (int ks = 0; ks < D / 16; ++ks) {
+  // A operands are fetched one k-step ahead of the MFMAs that consume them
+  auto fetch = [&](int ks, u32x4(&a)[D / 32]) {
     const int krow = 16 * ks + 8 * gl + L / 4;  // input channel (row of W1) this lane addresses
 #pragma unroll
     for (int rb = 0; rb < D / 32; ++rb) {
       const int col = 32 * rb + 16 * (q % 2) + 4 * (L % 4);
       const u32x2 lo = lds_read_tr16(wm + SM::w1_off(krow, col));
       const u32x2 hi = lds_read_tr16(wm + SM::w1_off(krow + 4, col));
-      u32x4 a;
-      a[0] = lo[0];
-      a[1] = lo[1];
-      a[2] = hi[0];
-      a[3] = hi[1];
-      acc[rb] = mfma32(a, xb[ks], acc[rb]);
+      a[rb][0] = lo[0];
+      a[rb][1] = lo[1];
+      a[rb][2] = hi[0];
+      a[rb][3] = hi[1];
     }
+  };
+  u32x4 a[2][D / 32];
+  fetch(0, a[0]);
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ++ks) {
+    if (ks + 1 < D / 16) fetch(ks + 1, a[(ks + 1) & 1]);
+    __builtin_amdgcn_sched_barrier(0);  // keep the next step's LDS reads ahead of this step's MFMAs
+#pragma unroll
+    for (int rb = 0; rb < D / 32; ++rb) acc[rb] = mfma32(a[ks & 1][rb], xb[ks], acc[rb]);
+    __builtin_amdgcn_sched_barrier(0);
   }
 }
 
@@ -309,21 +317,28 @@ __global__ __launch_bounds__(kThreads) void k_phi_bwd(Geom g, View X,
           }
       }
       // dx^T[in x tok] += W1[in x hidden] dh^T: A rows = input channels, plain reads of the W1 copy
-#pragma unroll
-      for (int ks2 = 0; ks2 < NKS; ++ks2) {
+      auto fetch = [&](int ks2, u32x4(&a)[NRB]) {
         const int ncol = 32 * (ks2 / 2) + 16 * (ks2 % 2) + 4 * gl;  // hidden units ncol..+3 and ncol+8..+11
 #pragma unroll
         for (int rb = 0; rb < NRB; ++rb) {
           const int row = 32 * rb + r;
           const u32x2 lo = *reinterpret_cast<const u32x2*>(wm + SM::w1_off(row, ncol));
           const u32x2 hi = *reinterpret_cast<const u32x2*>(wm + SM::w1_off(row, ncol + 8));
-          u32x4 a;
-          a[0] = lo[0];
-          a[1] = lo[1];
-          a[2] = hi[0];
-          a[3] = hi[1];
-          dx[rb] = mfma32(a, dhb[ks2], dx[rb]);
+          a[rb][0] = lo[0];
+          a[rb][1] = lo[1];
+          a[rb][2] = hi[0];
+          a[rb][3] = hi[1];
         }
+      };
+      u32x4 aw[2][NRB];
+      fetch(0, aw[0]);
+#pragma unroll
+      for (int ks2 = 0; ks2 < NKS; ++ks2) {
+        if (ks2 + 1 < NKS) fetch(ks2 + 1, aw[(ks2 + 1) & 1]);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb) dx[rb] = mfma32(aw[ks2 & 1][rb], dhb[ks2], dx[rb]);
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
     if (live) {

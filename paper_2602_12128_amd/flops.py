@@ -70,13 +70,17 @@ def attention_layer_tflops(tokens: int, kind: str, width: int = 1536, heads: int
 def kernel_model(name: str, d: int, d_phi: int, F: int, e: int = 2):
     D = d_phi ** F
     qf, kf = 4 * d_phi, 4 * F * d_phi
+    lin = 2 * d * d + 2 * d * d_phi            # one feature map forward
+    lin_b = 4 * d * d + 2 * d * d_phi          # one feature map backward (recompute + input grad)
     m = {
-        "mfma_phi_forward": (2 * d * e + qf + kf, phi_forward_flops(d, d_phi, F), "mfma"),
+        "mfma_phi_forward_q": (d * e + qf, lin, "mfma"),
+        "mfma_phi_forward_k": (d * e + kf, F * lin, "mfma"),
         "mfma_state": (d * e + kf, 2 * D * d + D, "hbm"),
         "mfma_query": (qf + d * e + 4, 2 * D * d + 2 * D, "hbm"),
         "mfma_bwd_query": (2 * d * e + qf + 4 + qf, 4 * D * d, "hbm"),
         "mfma_bwd_key": (d * e + kf + d * e + kf, 4 * D * d, "hbm"),
-        "mfma_phi_backward": (2 * d * e + 2 * (qf + kf) + 2 * d * e, phi_backward_flops(d, d_phi, F), "mfma"),
+        "mfma_phi_backward_q": (2 * d * e + 2 * qf, lin_b, "mfma"),
+        "mfma_phi_backward_k": (2 * d * e + 2 * kf, F * lin_b, "mfma"),
         "generic_phi_forward": (2 * d * e + qf + kf, phi_forward_flops(d, d_phi, F), "alu"),
         "generic_phi_backward": (2 * d * e + 2 * (qf + kf) + 2 * d * e, phi_backward_flops(d, d_phi, F), "alu"),
     }
