@@ -732,8 +732,8 @@ hla_status backward_core(hla_handle* hd, const hla_call_args& a) {
   HLA_TRY(launch(hd, "mfma_dstate_reduce", k_reduce<DP, D>, dim3(a.num_seqs, g.H, kReduceSlices),
                  dim3(256), 0, s, g, chunks->seq_off_dev, hd->partial, SL::kF32, hd->dstate, dops,
                  make_slot_map<DP>()));
-  HLA_TRY(launch(hd, "mfma_bwd_key", k_bwd_key<DP, D>, dim3(qblocks->count, g.H), dim3(kThreads),
-                 BwdKSmem<D>::kTotal, s, g, qblocks->dev, hd->feat, dops, a.V, hd->dfeat, a.dV));
+  HLA_TRY(launch(hd, "mfma_bwd_key", k_bwd_key<DP, D>, dim3(chunks->count, g.H), dim3(kThreads),
+                 BwdKSmem<D>::kTotal, s, g, chunks->dev, hd->feat, dops, a.V, hd->dfeat, a.dV));
   return HLA_OK;
 }
 

@@ -8,7 +8,7 @@
 //   u^T[d_phi x 32]  = W2^T g^T      B = GELU(hidden) packed straight from the accumulators
 // and backward   dg^T = W2 du^T,  dh = dg * GELU'(hidden),  dx^T = W1 dh^T  (A = the same LDS copy
 // of W1, plain reads).  The weights of a head stay resident in LDS for the workgroup's lifetime;
-// each wave streams its own 32-token tiles through a private staging buffer.
+// each wave streams its own 32-token tiles, loading them from global memory in operand order.
 #include "hla_handle.h"
 #include "hla_mfma_common.h"
 
@@ -17,9 +17,14 @@ namespace {
 
 using namespace mf;
 
-constexpr int kThreads = 256;
-constexpr int kWaves = kThreads / kWave;
 constexpr int kDP = 6;
+// waves per workgroup of the query-map and key-map kernels
+#ifndef HLA_PHI_WAVES_Q
+#define HLA_PHI_WAVES_Q 8
+#endif
+#ifndef HLA_PHI_WAVES_K
+#define HLA_PHI_WAVES_K 4
+#endif
 
 // ---- GELU on the vector ALU ------------------------------------------------------------------
 // x * Phi(x) with Phi(x) - 1/2 = t * P(t^2), t = clamp(x, +-4)/4: degree-7 minimax fit of the
@@ -103,40 +108,52 @@ __global__ void k_pack_phi(PhiF32 w, int dphi, unsigned char* __restrict__ out) 
 // ---- LDS layout ---------------------------------------------------------------------------------
 // W1 is kept row-major with its 16-byte chunks XOR-swizzled by the row, so that both the
 // transpose reads (4 consecutive rows, same columns) and the plain reads (32 consecutive rows,
-// same columns) spread over the banks without padding.
+// same columns) spread over the banks without padding.  LDS holds weights only: every lane loads
+// its token's input channels straight from global memory in operand order.
 template <int D>
 struct PhiSmem {
   static constexpr int kChunks = D / 8;               // 16-byte chunks per W1 row
   static constexpr int kW1 = D * D * 2;
   static constexpr int kW2 = D * 32 * 2;              // room for W2A (forward) or W2B (backward, half used)
   static constexpr int kMap = kW1 + kW2 + D * 4 + 32;  // + b1 + b2
-  static constexpr int kRow = D * 2 + 16;             // staging row stride
-  static constexpr int kStage = 32 * kRow;
-  static constexpr int total(int nmaps) { return nmaps * kMap + kWaves * kStage; }
+  static constexpr int total(int nmaps) { return nmaps * kMap; }
   __device__ static __forceinline__ int w1_off(int row, int col) {
     return row * (D * 2) + ((((col >> 3) ^ row) & (kChunks - 1)) << 4) + ((col & 7) << 1);
   }
 };
 
+// Copy one (map, head) block of packed weights into LDS (all threads of the workgroup).
 template <int D, bool BACKWARD>
-__device__ __forceinline__ void load_weights(unsigned char* smem, const unsigned char* wpk, int nmaps) {
+__device__ __forceinline__ void load_weights(unsigned char* dst, const unsigned char* src) {
   using SM = PhiSmem<D>;
   using PK = Packed<D>;
-  for (int m = 0; m < nmaps; ++m) {
-    const unsigned char* src = wpk + static_cast<int64_t>(m) * PK::kBytes;  // maps of one head are adjacent
-    unsigned char* dst = smem + m * SM::kMap;
-    for (int i = threadIdx.x; i < D * SM::kChunks; i += kThreads) {
-      const int row = i / SM::kChunks, ch = i % SM::kChunks;
-      *reinterpret_cast<u32x4*>(dst + SM::w1_off(row, ch * 8)) =
-          *reinterpret_cast<const u32x4*>(src + PK::kW1 + i * 16);
-    }
-    const int w2_bytes = BACKWARD ? D * 16 * 2 : D * 32 * 2;
-    const unsigned char* w2 = src + (BACKWARD ? PK::kW2B : PK::kW2A);
-    for (int i = threadIdx.x; i < w2_bytes / 16; i += kThreads)
-      *reinterpret_cast<u32x4*>(dst + SM::kW1 + i * 16) = *reinterpret_cast<const u32x4*>(w2 + i * 16);
-    for (int i = threadIdx.x; i < D + 8; i += kThreads)
-      *reinterpret_cast<float*>(dst + SM::kW1 + SM::kW2 + i * 4) =
-          *reinterpret_cast<const float*>(src + PK::kB1 + i * 4);
+  const int nthreads = blockDim.x;
+  for (int i = threadIdx.x; i < D * SM::kChunks; i += nthreads) {
+    const int row = i / SM::kChunks, ch = i % SM::kChunks;
+    *reinterpret_cast<u32x4*>(dst + SM::w1_off(row, ch * 8)) =
+        *reinterpret_cast<const u32x4*>(src + PK::kW1 + i * 16);
+  }
+  const int w2_bytes = BACKWARD ? D * 16 * 2 : D * 32 * 2;
+  const unsigned char* w2 = src + (BACKWARD ? PK::kW2B : PK::kW2A);
+  for (int i = threadIdx.x; i < w2_bytes / 16; i += nthreads)
+    *reinterpret_cast<u32x4*>(dst + SM::kW1 + i * 16) = *reinterpret_cast<const u32x4*>(w2 + i * 16);
+  for (int i = threadIdx.x; i < D + 8; i += nthreads)
+    *reinterpret_cast<float*>(dst + SM::kW1 + SM::kW2 + i * 4) =
+        *reinterpret_cast<const float*>(src + PK::kB1 + i * 4);
+}
+
+// The lane's share of its token's input vector as B operands: k-slot (ks, gl, j) is channel
+// 16 ks + 8 gl + j, i.e. one 16-byte piece per k-step.  Tokens at or beyond N read as zero.
+template <int D>
+__device__ __forceinline__ void load_x(const View& X, int b, int h, int n, int N, int gl,
+                                       u32x4 (&x)[D / 16]) {
+  if (n < N) {
+    const bf16_t* row = X.row<const bf16_t>(b, h, n);
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) x[ks] = *reinterpret_cast<const u32x4*>(row + 16 * ks + 8 * gl);
+  } else {
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) x[ks][0] = x[ks][1] = x[ks][2] = x[ks][3] = 0u;
   }
 }
 
@@ -182,13 +199,14 @@ __device__ __forceinline__ void first_layer(const unsigned char* wm, const u32x4
 }
 
 // ---- forward ------------------------------------------------------------------------------------
-// grid (G, H, B), block 256.  Maps map0 .. map0+NMAPS-1 of the head are applied to X; features go
-// to the fp32 feature workspace.
-template <int D, int NMAPS>
-__global__ __launch_bounds__(kThreads) void k_phi_fwd(Geom g, View X,
-                                                      const unsigned char* __restrict__ wpk,
-                                                      int heads_w, int nmaps_total, int map0,
-                                                      float* __restrict__ feat) {
+// grid (G, H, B), block WAVES*64.  Maps map0 .. map0+NMAPS-1 of the head are applied to X; the
+// features go to the fp32 feature workspace.  Wave w of the grid serves 32-token tiles
+// w, w + (total waves), ..; the next tile's inputs are loaded while the current one is computed.
+template <int D, int NMAPS, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void k_phi_fwd(Geom g, View X,
+                                                        const unsigned char* __restrict__ wpk,
+                                                        int heads_w, int map0,
+                                                        float* __restrict__ feat) {
   using SM = PhiSmem<D>;
   constexpr int NRB = D / 32, NKS = D / 16;
   extern __shared__ __align__(16) unsigned char smem[];
@@ -196,24 +214,19 @@ __global__ __launch_bounds__(kThreads) void k_phi_fwd(Geom g, View X,
   const int r = lane % 32, gl = lane / 32;
   const int h = blockIdx.y, b = blockIdx.z;
   const int hw = heads_w == 1 ? 0 : h;
-  // packed blocks are ordered [map][head]
-  for (int m = 0; m < NMAPS; ++m)
+  for (int m = 0; m < NMAPS; ++m)  // packed blocks are ordered [map][head]
     load_weights<D, false>(smem + m * SM::kMap,
-                           wpk + (static_cast<int64_t>(map0 + m) * heads_w + hw) * Packed<D>::kBytes, 1);
-  (void)nmaps_total;
+                           wpk + (static_cast<int64_t>(map0 + m) * heads_w + hw) * Packed<D>::kBytes);
   __syncthreads();
-  unsigned char* stage = smem + NMAPS * SM::kMap + wave * SM::kStage;
   const int ntiles = (g.N + 31) / 32;
-  for (int tile = blockIdx.x * kWaves + wave; tile < ntiles; tile += gridDim.x * kWaves) {
-    const int n0 = tile * 32;
-    stage_tile32<D>(X, b, h, n0, g.N, lane, stage, SM::kRow);
-    wave_lds_sync();
-    u32x4 xb[NKS];
-#pragma unroll
-    for (int ks = 0; ks < NKS; ++ks)
-      xb[ks] = *reinterpret_cast<const u32x4*>(stage + r * SM::kRow + (16 * ks + 8 * gl) * 2);
-    const int n = n0 + r;
+  const int stride = gridDim.x * WAVES;
+  int tile = blockIdx.x * WAVES + wave;
+  u32x4 xb[NKS], xn[NKS];
+  if (tile < ntiles) load_x<D>(X, b, h, tile * 32 + r, g.N, gl, xb);
+  for (; tile < ntiles; tile += stride) {
+    const int n = tile * 32 + r;
     const bool live = n < g.N;
+    if (tile + stride < ntiles) load_x<D>(X, b, h, (tile + stride) * 32 + r, g.N, gl, xn);
 #pragma unroll
     for (int m = 0; m < NMAPS; ++m) {
       const unsigned char* wm = smem + m * SM::kMap;
@@ -242,19 +255,20 @@ __global__ __launch_bounds__(kThreads) void k_phi_fwd(Geom g, View X,
           if (4 * gl + i < kDP) f[i] = fmaxf(u[i] + b2[4 * gl + i], 0.0f);
       }
     }
-    wave_lds_sync();
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) xb[ks] = xn[ks];
   }
 }
 
 // ---- backward -----------------------------------------------------------------------------------
-// grid (G, H, B), block 256.  dX = sum over the NMAPS maps of W1 (GELU'(h) * (W2 du)), with
+// grid (G, H, B), block WAVES*64.  dX = sum over the NMAPS maps of W1 (GELU'(h) * (W2 du)), with
 // du = d(feature) where the ReLU was open.  Hidden activations are recomputed.
-template <int D, int NMAPS>
-__global__ __launch_bounds__(kThreads) void k_phi_bwd(Geom g, View X,
-                                                      const unsigned char* __restrict__ wpk,
-                                                      int heads_w, int map0,
-                                                      const float* __restrict__ feat,
-                                                      const float* __restrict__ dfeat, View dX) {
+template <int D, int NMAPS, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void k_phi_bwd(Geom g, View X,
+                                                        const unsigned char* __restrict__ wpk,
+                                                        int heads_w, int map0,
+                                                        const float* __restrict__ feat,
+                                                        const float* __restrict__ dfeat, View dX) {
   using SM = PhiSmem<D>;
   constexpr int NRB = D / 32, NKS = D / 16;
   extern __shared__ __align__(16) unsigned char smem[];
@@ -264,20 +278,32 @@ __global__ __launch_bounds__(kThreads) void k_phi_bwd(Geom g, View X,
   const int hw = heads_w == 1 ? 0 : h;
   for (int m = 0; m < NMAPS; ++m)
     load_weights<D, true>(smem + m * SM::kMap,
-                          wpk + (static_cast<int64_t>(map0 + m) * heads_w + hw) * Packed<D>::kBytes, 1);
+                          wpk + (static_cast<int64_t>(map0 + m) * heads_w + hw) * Packed<D>::kBytes);
   __syncthreads();
-  unsigned char* stage = smem + NMAPS * SM::kMap + wave * SM::kStage;
   const int ntiles = (g.N + 31) / 32;
-  for (int tile = blockIdx.x * kWaves + wave; tile < ntiles; tile += gridDim.x * kWaves) {
-    const int n0 = tile * 32;
-    stage_tile32<D>(X, b, h, n0, g.N, lane, stage, SM::kRow);
-    wave_lds_sync();
-    u32x4 xb[NKS];
-#pragma unroll
-    for (int ks = 0; ks < NKS; ++ks)
-      xb[ks] = *reinterpret_cast<const u32x4*>(stage + r * SM::kRow + (16 * ks + 8 * gl) * 2);
-    const int n = n0 + r;
+  const int stride = gridDim.x * WAVES;
+  int tile = blockIdx.x * WAVES + wave;
+  u32x4 xb[NKS], xn[NKS];
+  if (tile < ntiles) load_x<D>(X, b, h, tile * 32 + r, g.N, gl, xb);
+  for (; tile < ntiles; tile += stride) {
+    const int n = tile * 32 + r;
     const bool live = n < g.N;
+    if (tile + stride < ntiles) load_x<D>(X, b, h, (tile + stride) * 32 + r, g.N, gl, xn);
+    // du^T as B operand of one 16-slot step: slot (gl, j) is feature 8gl + j (only gl = 0 is used)
+    u32x4 dub[NMAPS];
+#pragma unroll
+    for (int m = 0; m < NMAPS; ++m) {
+      dub[m][0] = dub[m][1] = dub[m][2] = dub[m][3] = 0u;
+      if (live && gl == 0) {
+        const int64_t o = g.th(b, h, n) * g.nfeat + (map0 + m) * kDP;
+        float du[8];
+#pragma unroll
+        for (int a = 0; a < 8; ++a)
+          du[a] = (a < kDP && feat[o + (a < kDP ? a : 0)] > 0.0f) ? dfeat[o + (a < kDP ? a : 0)] : 0.0f;
+#pragma unroll
+        for (int p = 0; p < 4; ++p) dub[m][p] = pack_bf16(du[2 * p], du[2 * p + 1]);
+      }
+    }
     f32x16 dx[NRB];
 #pragma unroll
     for (int rb = 0; rb < NRB; ++rb)
@@ -286,17 +312,6 @@ __global__ __launch_bounds__(kThreads) void k_phi_bwd(Geom g, View X,
 #pragma unroll
     for (int m = 0; m < NMAPS; ++m) {
       const unsigned char* wm = smem + m * SM::kMap;
-      // du^T as B operand of one 16-slot step: slot (gl, j) is feature 8gl + j
-      u32x4 dub;
-      dub[0] = dub[1] = dub[2] = dub[3] = 0u;
-      if (live && gl == 0) {
-        const int64_t o = g.th(b, h, n) * g.nfeat + (map0 + m) * kDP;
-        float du[8];
-#pragma unroll
-        for (int a = 0; a < 8; ++a) du[a] = (a < kDP && feat[o + (a < kDP ? a : 0)] > 0.0f) ? dfeat[o + (a < kDP ? a : 0)] : 0.0f;
-#pragma unroll
-        for (int p = 0; p < 4; ++p) dub[p] = pack_bf16(du[2 * p], du[2 * p + 1]);
-      }
       f32x16 acc[NRB];
       first_layer<D>(wm, xb, lane, acc);
       u32x4 dhb[NKS];
@@ -306,7 +321,7 @@ __global__ __launch_bounds__(kThreads) void k_phi_bwd(Geom g, View X,
 #pragma unroll
         for (int i = 0; i < 16; ++i) dg[i] = 0.0f;
         const u32x4 a2 = *reinterpret_cast<const u32x4*>(wm + SM::kW1 + (rb * 64 + lane) * 16);
-        dg = mfma32(a2, dub, dg);
+        dg = mfma32(a2, dub[m], dg);
 #pragma unroll
         for (int half = 0; half < 2; ++half)
 #pragma unroll
@@ -353,7 +368,8 @@ __global__ __launch_bounds__(kThreads) void k_phi_bwd(Geom g, View X,
           *reinterpret_cast<u32x2*>(orow + 32 * rb + 8 * q4 + 4 * gl) = w;
         }
     }
-    wave_lds_sync();
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) xb[ks] = xn[ks];
   }
 }
 
@@ -365,14 +381,16 @@ hla_status allow_lds(K kernel, int bytes) {
              : HLA_ERR_HIP;
 }
 
-int grid_x(const Geom& g) {
+int grid_x(const Geom& g, int waves) {
   // about one workgroup per compute unit in total, at least one per (batch row, head)
   const int units = g.B * g.H;
-  const int tiles = (g.N + 32 * kWaves - 1) / (32 * kWaves);
-  int gx = (256 + units - 1) / units;
+  const int tiles = (g.N + 32 * waves - 1) / (32 * waves);
+  int gx = 256 / units;  // rounding down keeps the whole grid resident in one round
   if (gx > tiles) gx = tiles;
   return gx < 1 ? 1 : gx;
 }
+
+constexpr int kWavesQ = HLA_PHI_WAVES_Q, kWavesK = HLA_PHI_WAVES_K;
 
 template <int D>
 hla_status forward_t(hla_handle* hd, const hla_call_args& a) {
@@ -381,15 +399,14 @@ hla_status forward_t(hla_handle* hd, const hla_call_args& a) {
   const unsigned char* wpk = static_cast<const unsigned char*>(hd->path_ws) + hd->w_packed_off;
   static bool attr = false;
   if (!attr) {
-    HLA_TRY(allow_lds(&k_phi_fwd<D, 1>, SM::total(1)));
-    HLA_TRY(allow_lds(&k_phi_fwd<D, 3>, SM::total(3)));
+    HLA_TRY(allow_lds(&k_phi_fwd<D, 1, kWavesQ>, SM::total(1)));
+    HLA_TRY(allow_lds(&k_phi_fwd<D, 3, kWavesK>, SM::total(3)));
     attr = true;
   }
-  const dim3 grid(grid_x(g), g.H, g.B);
-  HLA_TRY(launch(hd, "mfma_phi_forward_q", k_phi_fwd<D, 1>, grid, dim3(kThreads), SM::total(1), a.stream,
-                 g, a.Q, wpk, hd->phi.heads_w, 4, 0, hd->feat));
-  HLA_TRY(launch(hd, "mfma_phi_forward_k", k_phi_fwd<D, 3>, grid, dim3(kThreads), SM::total(3), a.stream,
-                 g, a.K, wpk, hd->phi.heads_w, 4, 1, hd->feat));
+  HLA_TRY(launch(hd, "mfma_phi_forward_q", k_phi_fwd<D, 1, kWavesQ>, dim3(grid_x(g, kWavesQ), g.H, g.B),
+                 dim3(kWavesQ * 64), SM::total(1), a.stream, g, a.Q, wpk, hd->phi.heads_w, 0, hd->feat));
+  HLA_TRY(launch(hd, "mfma_phi_forward_k", k_phi_fwd<D, 3, kWavesK>, dim3(grid_x(g, kWavesK), g.H, g.B),
+                 dim3(kWavesK * 64), SM::total(3), a.stream, g, a.K, wpk, hd->phi.heads_w, 1, hd->feat));
   return HLA_OK;
 }
 
@@ -400,15 +417,16 @@ hla_status backward_t(hla_handle* hd, const hla_call_args& a) {
   const unsigned char* wpk = static_cast<const unsigned char*>(hd->path_ws) + hd->w_packed_off;
   static bool attr = false;
   if (!attr) {
-    HLA_TRY(allow_lds(&k_phi_bwd<D, 1>, SM::total(1)));
-    HLA_TRY(allow_lds(&k_phi_bwd<D, 3>, SM::total(3)));
+    HLA_TRY(allow_lds(&k_phi_bwd<D, 1, kWavesQ>, SM::total(1)));
+    HLA_TRY(allow_lds(&k_phi_bwd<D, 3, kWavesK>, SM::total(3)));
     attr = true;
   }
-  const dim3 grid(grid_x(g), g.H, g.B);
-  HLA_TRY(launch(hd, "mfma_phi_backward_q", k_phi_bwd<D, 1>, grid, dim3(kThreads), SM::total(1), a.stream,
-                 g, a.Q, wpk, hd->phi.heads_w, 0, hd->feat, hd->dfeat, a.dQ));
-  HLA_TRY(launch(hd, "mfma_phi_backward_k", k_phi_bwd<D, 3>, grid, dim3(kThreads), SM::total(3), a.stream,
-                 g, a.K, wpk, hd->phi.heads_w, 1, hd->feat, hd->dfeat, a.dK));
+  HLA_TRY(launch(hd, "mfma_phi_backward_q", k_phi_bwd<D, 1, kWavesQ>, dim3(grid_x(g, kWavesQ), g.H, g.B),
+                 dim3(kWavesQ * 64), SM::total(1), a.stream, g, a.Q, wpk, hd->phi.heads_w, 0, hd->feat,
+                 hd->dfeat, a.dQ));
+  HLA_TRY(launch(hd, "mfma_phi_backward_k", k_phi_bwd<D, 3, kWavesK>, dim3(grid_x(g, kWavesK), g.H, g.B),
+                 dim3(kWavesK * 64), SM::total(3), a.stream, g, a.K, wpk, hd->phi.heads_w, 1, hd->feat,
+                 hd->dfeat, a.dK));
   return HLA_OK;
 }
 
