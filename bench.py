@@ -32,8 +32,22 @@ def parse():
     ap.add_argument("--features", action="store_true",
                     help="feature-level interface (Q,K already phi-mapped): times the core alone")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--calib-copy-mib", type=int, default=0,
+                    help="before the warm-up, run one device-to-device copy of this many MiB: the "
+                         "known-size kernel that scales rocprofv3's FETCH_SIZE / WRITE_SIZE")
     ap.add_argument("--path", choices=["auto", "generic", "mfma"], default="auto")
     return ap.parse_args()
+
+
+def measured_traffic(workload: str, kernel: str):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary of this
+    workload (profiles/hbm_traffic_<workload>.json, written by profile_tools.py), or None."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.json")
+    try:
+        t = json.load(open(path)).get(kernel)
+        return None if t is None else t["read_bytes"] + t["write_bytes"]
+    except (OSError, ValueError, KeyError):
+        return None
 
 
 def cpu_baseline(w, phi, backward, features):
@@ -109,6 +123,12 @@ def main():
         if backward:
             h.backward(t["Q"], t["K"], t["V"], O, t["dO"], *grads, cu_seqlens=w.cu_seqlens)
 
+    if args.calib_copy_mib > 0:
+        src = torch.zeros(args.calib_copy_mib * 2 ** 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -147,7 +167,7 @@ def main():
             dur = kernels[dom]["avg_us"] * 1e-6
             achieved = (kb * th / dur / 1e9) if bound == "hbm" else (kf * th / dur / 1e12)
             roofline = {"kernel": dom, "bound": bound, "achieved": achieved, "peak": peak,
-                        "unit": unit, "frac": achieved / peak, "traffic": None,
+                        "unit": unit, "frac": achieved / peak, "traffic": measured_traffic(w.name, dom),
                         "avg_launch_us": kernels[dom]["avg_us"],
                         "algorithmic_bytes_per_launch": kb * th,
                         "nominal_flops_per_launch": kf * th}
