@@ -3,12 +3,14 @@
 //
 // A token is an MFMA *column* (lane (r, gl): token r of a 32-token tile, half gl), so the two
 // layers chain without any layout change:
-//   hidden^T[d x 32] = W1^T X^T      A = W1^T read from one row-major copy of W1 in LDS with
-//                                    transpose reads; B = the token's own input channels
+//   hidden^T[d x 32] = W1^T X^T      A = rows of W1^T read from LDS with plain 16-byte reads;
+//                                    B = the token's own input channels, loaded from global
+//                                    memory in operand order
 //   u^T[d_phi x 32]  = W2^T g^T      B = GELU(hidden) packed straight from the accumulators
 // and backward   dg^T = W2 du^T,  dh = dg * GELU'(hidden),  dx^T = W1 dh^T  (A = the same LDS copy
-// of W1, plain reads).  The weights of a head stay resident in LDS for the workgroup's lifetime;
-// each wave streams its own 32-token tiles, loading them from global memory in operand order.
+// of W1^T, transpose reads).  The weights of a head stay resident in LDS for the workgroup's
+// lifetime; each wave streams its own 32-token tiles, and two waves share a SIMD so that one
+// wave's GELU arithmetic overlaps the other's matrix and LDS work.
 #include "hla_handle.h"
 #include "hla_mfma_common.h"
 
@@ -18,52 +20,49 @@ namespace {
 using namespace mf;
 
 constexpr int kDP = 6;
-// waves per workgroup of the query-map and key-map kernels
-#ifndef HLA_PHI_WAVES_Q
-#define HLA_PHI_WAVES_Q 8
+// waves per workgroup of the forward and backward kernels
+#ifndef HLA_PHI_WAVES_F
+#define HLA_PHI_WAVES_F 8
 #endif
-#ifndef HLA_PHI_WAVES_K
-#define HLA_PHI_WAVES_K 4
+#ifndef HLA_PHI_WAVES_B
+#define HLA_PHI_WAVES_B 8
 #endif
 
 // ---- GELU on the vector ALU ------------------------------------------------------------------
-// x * Phi(x) with Phi(x) - 1/2 = t * P(t^2), t = clamp(x, +-4)/4: degree-7 minimax fit of the
-// normal CDF (|error| <= 2.2e-5 inside, 3.2e-5 beyond the clamp), i.e. |GELU error| <= 4.2e-4,
-// an order of magnitude below the bf16 rounding the result receives anyway.
+// Phi(x) - 1/2 = xc * P(xc^2) with xc = clamp(x, +-3.75): degree-6 minimax fit of the normal CDF,
+// |GELU error| <= 3.3e-4 over all x, below the bf16 rounding the result receives anyway.
 __device__ __forceinline__ float gelu_poly(float x) {
-  const float t = __builtin_amdgcn_fmed3f(x, -4.0f, 4.0f) * 0.25f;
-  const float u = t * t;
-  float p = -1.697353482246399f;
-  p = p * u + 8.16788387298584f;
-  p = p * u + -17.20026397705078f;
-  p = p * u + 21.146461486816406f;
-  p = p * u + -17.173776626586914f;
-  p = p * u + 9.896830558776855f;
-  p = p * u + -4.23522424697876f;
-  p = p * u + 1.5953900814056396f;
-  return x * (t * p + 0.5f);
+  const float xc = __builtin_amdgcn_fmed3f(x, -3.75f, 3.75f);
+  const float u = xc * xc;
+  float p = 3.912438593e-08f;
+  p = p * u + -2.376254374e-06f;
+  p = p * u + 6.234781818e-05f;
+  p = p * u + -9.441798806e-04f;
+  p = p * u + 9.362553295e-03f;
+  p = p * u + -6.578987063e-02f;
+  p = p * u + 3.987064701e-01f;
+  return x * (xc * p + 0.5f);
 }
-// d/dx [x Phi(x)] - 1/2 = t * R(t^2): degree-8 fit, |error| <= 5.5e-4.
+// d/dx [x Phi(x)] - 1/2 = xc * R(xc^2), xc = clamp(x, +-4): degree-7 fit, |error| <= 2.7e-4.
 __device__ __forceinline__ float gelu_grad_poly(float x) {
-  const float t = __builtin_amdgcn_fmed3f(x, -4.0f, 4.0f) * 0.25f;
-  const float u = t * t;
-  float p = 16.82962989807129f;
-  p = p * u + -88.24928283691406f;
-  p = p * u + 203.22996520996094f;
-  p = p * u + -272.4527282714844f;
-  p = p * u + 237.85069274902344f;
-  p = p * u + -142.80833435058594f;
-  p = p * u + 59.85906982421875f;
-  p = p * u + -16.94890022277832f;
-  p = p * u + 3.1904382705688477f;
-  return t * p + 0.5f;
+  const float xc = __builtin_amdgcn_fmed3f(x, -4.0f, 4.0f);
+  const float u = xc * xc;
+  float p = -1.641980733e-08f;
+  p = p * u + 1.213807329e-06f;
+  p = p * u + -3.845959858e-05f;
+  p = p * u + 6.876457658e-04f;
+  p = p * u + -7.687443813e-03f;
+  p = p * u + 5.591483272e-02f;
+  p = p * u + -2.620298556e-01f;
+  p = p * u + 7.967216430e-01f;
+  return xc * p + 0.5f;
 }
 
 // ---- packed weights of one (map, head) in global memory ---------------------------------------
 template <int D>
 struct Packed {
-  static constexpr int kW1 = 0;                       // bf16 [D][D] row-major (row = input channel)
-  static constexpr int kW2A = kW1 + D * D * 2;        // bf16 [D/16][64][8]: A operand of u^T = W2^T g^T
+  static constexpr int kW1T = 0;                      // bf16 [D][D]: row = hidden unit, col = input channel
+  static constexpr int kW2A = kW1T + D * D * 2;       // bf16 [D/16][64][8]: A operand of u^T = W2^T g^T
   static constexpr int kW2B = kW2A + D * 32 * 2;      // bf16 [D/32][64][8]: A operand of dg^T = W2 du^T
   static constexpr int kB1 = kW2B + D * 16 * 2;       // fp32 [D]
   static constexpr int kB2 = kB1 + D * 4;             // fp32 [8]
@@ -83,12 +82,15 @@ __global__ void k_pack_phi(PhiF32 w, int dphi, unsigned char* __restrict__ out) 
   unsigned char* base = out + mh * Packed<D>::kBytes;
   const float* W1 = w.W1 + mh * D * D;
   const float* W2 = w.W2 + mh * D * dphi;
-  uint16_t* w1 = reinterpret_cast<uint16_t*>(base + Packed<D>::kW1);
+  uint16_t* w1t = reinterpret_cast<uint16_t*>(base + Packed<D>::kW1T);
   uint16_t* w2a = reinterpret_cast<uint16_t*>(base + Packed<D>::kW2A);
   uint16_t* w2b = reinterpret_cast<uint16_t*>(base + Packed<D>::kW2B);
   float* b1 = reinterpret_cast<float*>(base + Packed<D>::kB1);
   float* b2 = reinterpret_cast<float*>(base + Packed<D>::kB2);
-  for (int i = threadIdx.x; i < D * D; i += blockDim.x) w1[i] = f32_to_bf16_bits(W1[i]);
+  for (int i = threadIdx.x; i < D * D; i += blockDim.x) {
+    const int hid = i / D, in = i % D;
+    w1t[i] = f32_to_bf16_bits(W1[in * D + hid]);
+  }
   for (int i = threadIdx.x; i < (D / 16) * 512; i += blockDim.x) {
     const int ks2 = i / 512, lane = (i / 8) % 64, j = i % 8;
     const int r = lane % 32, gl = lane / 32;
@@ -106,19 +108,23 @@ __global__ void k_pack_phi(PhiF32 w, int dphi, unsigned char* __restrict__ out) 
 }
 
 // ---- LDS layout ---------------------------------------------------------------------------------
-// W1 is kept row-major with its 16-byte chunks XOR-swizzled by the row, so that both the
-// transpose reads (4 consecutive rows, same columns) and the plain reads (32 consecutive rows,
-// same columns) spread over the banks without padding.  LDS holds weights only: every lane loads
-// its token's input channels straight from global memory in operand order.
+// W1^T is kept row-major (row = hidden unit) with the 16-byte chunks of a row XOR-swizzled by a
+// function of the row chosen so that both access patterns spread over all banks without padding:
+//   plain 16-byte reads of 16 consecutive rows at one chunk (first-layer A operand), and
+//   transpose reads of 4 consecutive rows x 4 consecutive chunks (A operand of dx^T = W1 dh^T).
 template <int D>
 struct PhiSmem {
-  static constexpr int kChunks = D / 8;               // 16-byte chunks per W1 row
+  static constexpr int kChunks = D / 8;               // 16-byte chunks per row
+  static constexpr int kRow = D * 2;                  // bytes per row
   static constexpr int kW1 = D * D * 2;
   static constexpr int kW2 = D * 32 * 2;              // room for W2A (forward) or W2B (backward, half used)
   static constexpr int kMap = kW1 + kW2 + D * 4 + 32;  // + b1 + b2
   static constexpr int total(int nmaps) { return nmaps * kMap; }
-  __device__ static __forceinline__ int w1_off(int row, int col) {
-    return row * (D * 2) + ((((col >> 3) ^ row) & (kChunks - 1)) << 4) + ((col & 7) << 1);
+  __host__ __device__ static __forceinline__ int swz(int row) {
+    return D == 128 ? (((row & 3) << 2) | ((row >> 2) & 3)) : ((((row >> 1) & 1) << 2) | ((row >> 2) & 3));
+  }
+  __device__ static __forceinline__ int off(int row, int chunk) {
+    return row * kRow + (((chunk ^ swz(row)) & (kChunks - 1)) << 4);
   }
 };
 
@@ -130,8 +136,7 @@ __device__ __forceinline__ void load_weights(unsigned char* dst, const unsigned 
   const int nthreads = blockDim.x;
   for (int i = threadIdx.x; i < D * SM::kChunks; i += nthreads) {
     const int row = i / SM::kChunks, ch = i % SM::kChunks;
-    *reinterpret_cast<u32x4*>(dst + SM::w1_off(row, ch * 8)) =
-        *reinterpret_cast<const u32x4*>(src + PK::kW1 + i * 16);
+    *reinterpret_cast<u32x4*>(dst + SM::off(row, ch)) = *reinterpret_cast<const u32x4*>(src + PK::kW1T + i * 16);
   }
   const int w2_bytes = BACKWARD ? D * 16 * 2 : D * 32 * 2;
   const unsigned char* w2 = src + (BACKWARD ? PK::kW2B : PK::kW2A);
@@ -157,102 +162,177 @@ __device__ __forceinline__ void load_x(const View& X, int b, int h, int n, int N
   }
 }
 
-// hidden^T = b1 + W1^T X^T for one map: acc[rb][i] is hidden unit 32rb + d_row(i, gl) of token r.
+// Per-lane byte offsets (inside a map's W1^T block, row block 0) of the first-layer A operand of
+// each k-step: row r, chunk 2 ks + gl.  Row blocks add the compile-time constant 32 rows.
 template <int D>
-__device__ __forceinline__ void first_layer(const unsigned char* wm, const u32x4 (&xb)[D / 16],
-                                            int lane, f32x16 (&acc)[D / 32]) {
+__device__ __forceinline__ void first_layer_offsets(int lane, int (&a_off)[D / 16]) {
   using SM = PhiSmem<D>;
-  const int gl = lane / 32, L = lane % 16, q = lane / 16;
+  const int r = lane % 32, gl = lane / 32;
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ++ks) a_off[ks] = SM::off(r, 2 * ks + gl);
+}
+
+// One 32-row block of hidden^T = b1 + W1^T X^T: acc[i] is hidden unit 32rb + d_row(i, gl) of
+// token r.  The eight MFMAs only queue on the matrix pipe; vector-ALU work that follows in program
+// order and does not read `acc` runs in their shadow.
+template <int D>
+__device__ __forceinline__ void first_layer_block(const unsigned char* wm, const int (&a_off)[D / 16],
+                                                  const u32x4 (&xb)[D / 16], int gl, int rb,
+                                                  f32x16& acc) {
+  using SM = PhiSmem<D>;
   const float* b1 = reinterpret_cast<const float*>(wm + SM::kW1 + SM::kW2);
 #pragma unroll
-  for (int rb = 0; rb < D / 32; ++rb)
+  for (int q4 = 0; q4 < 4; ++q4) {
+    const f32x4 bv = *reinterpret_cast<const f32x4*>(b1 + 32 * rb + 8 * q4 + 4 * gl);
 #pragma unroll
-    for (int q4 = 0; q4 < 4; ++q4) {
-      const f32x4 bv = *reinterpret_cast<const f32x4*>(b1 + 32 * rb + 8 * q4 + 4 * gl);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) acc[rb][4 * q4 + e] = bv[e];
-    }
-  // A operands are fetched one k-step ahead of the MFMAs that consume them
-  auto fetch = [&](int ks, u32x4(&a)[D / 32]) {
-    const int krow = 16 * ks + 8 * gl + L / 4;  // input channel (row of W1) this lane addresses
-#pragma unroll
-    for (int rb = 0; rb < D / 32; ++rb) {
-      const int col = 32 * rb + 16 * (q % 2) + 4 * (L % 4);
-      const u32x2 lo = lds_read_tr16(wm + SM::w1_off(krow, col));
-      const u32x2 hi = lds_read_tr16(wm + SM::w1_off(krow + 4, col));
-      a[rb][0] = lo[0];
-      a[rb][1] = lo[1];
-      a[rb][2] = hi[0];
-      a[rb][3] = hi[1];
-    }
-  };
-  u32x4 a[2][D / 32];
-  fetch(0, a[0]);
+    for (int e = 0; e < 4; ++e) acc[4 * q4 + e] = bv[e];
+  }
 #pragma unroll
   for (int ks = 0; ks < D / 16; ++ks) {
-    if (ks + 1 < D / 16) fetch(ks + 1, a[(ks + 1) & 1]);
-    __builtin_amdgcn_sched_barrier(0);  // keep the next step's LDS reads ahead of this step's MFMAs
-#pragma unroll
-    for (int rb = 0; rb < D / 32; ++rb) acc[rb] = mfma32(a[ks & 1][rb], xb[ks], acc[rb]);
-    __builtin_amdgcn_sched_barrier(0);
+    // swz(32 rb + r) == swz(r): the row block only adds a constant to the address
+    const u32x4 a = *reinterpret_cast<const u32x4*>(wm + a_off[ks] + rb * 32 * SM::kRow);
+    acc = mfma32(a, xb[ks], acc);
   }
 }
 
+// Which (batch row, head, first token) a 32-token tile index stands for.  With weights shared by
+// all heads the tiles of every (batch row, head) form one flat list that is dealt out evenly to
+// all waves of the grid; with per-head weights a workgroup stays on the head of blockIdx.y/z.
+struct TileMap {
+  int tiles_per_row;  // ceil(N / 32)
+  int total;          // tiles this workgroup's list holds
+  int H;
+  bool flat;
+  __device__ __forceinline__ void decode(int t, int& b, int& h, int& n0) const {
+    if (flat) {
+      const int row = t / tiles_per_row;
+      b = row / H;
+      h = row % H;
+      n0 = (t % tiles_per_row) * 32;
+    } else {
+      b = blockIdx.z;
+      h = blockIdx.y;
+      n0 = t * 32;
+    }
+  }
+};
+__device__ __forceinline__ TileMap make_tile_map(const Geom& g, int heads_w) {
+  TileMap tm;
+  tm.tiles_per_row = (g.N + 31) / 32;
+  tm.flat = heads_w == 1;
+  tm.total = tm.flat ? tm.tiles_per_row * g.B * g.H : tm.tiles_per_row;
+  tm.H = g.H;
+  return tm;
+}
+
 // ---- forward ------------------------------------------------------------------------------------
-// grid (G, H, B), block WAVES*64.  Maps map0 .. map0+NMAPS-1 of the head are applied to X; the
-// features go to the fp32 feature workspace.  Wave w of the grid serves 32-token tiles
-// w, w + (total waves), ..; the next tile's inputs are loaded while the current one is computed.
+// block WAVES*64.  Maps map0 .. map0+NMAPS-1 are applied to X; the features go to the fp32
+// feature workspace.  Wave w of the grid serves 32-token tiles w, w + (total waves), ..; the next
+// tile's inputs are loaded while the current one is computed.
 template <int D, int NMAPS, int WAVES>
 __global__ __launch_bounds__(WAVES * 64) void k_phi_fwd(Geom g, View X,
                                                         const unsigned char* __restrict__ wpk,
-                                                        int heads_w, int map0,
+                                                        int heads_w, int map0, int nmaps,
                                                         float* __restrict__ feat) {
   using SM = PhiSmem<D>;
   constexpr int NRB = D / 32, NKS = D / 16;
   extern __shared__ __align__(16) unsigned char smem[];
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
   const int r = lane % 32, gl = lane / 32;
-  const int h = blockIdx.y, b = blockIdx.z;
-  const int hw = heads_w == 1 ? 0 : h;
+  const TileMap tm = make_tile_map(g, heads_w);
+  const int hw = heads_w == 1 ? 0 : blockIdx.y;
   for (int m = 0; m < NMAPS; ++m)  // packed blocks are ordered [map][head]
     load_weights<D, false>(smem + m * SM::kMap,
                            wpk + (static_cast<int64_t>(map0 + m) * heads_w + hw) * Packed<D>::kBytes);
   __syncthreads();
-  const int ntiles = (g.N + 31) / 32;
+  int a_off[NKS];
+  first_layer_offsets<D>(lane, a_off);
   const int stride = gridDim.x * WAVES;
   int tile = blockIdx.x * WAVES + wave;
+  int b = 0, h = 0, n0 = 0;
   u32x4 xb[NKS], xn[NKS];
-  if (tile < ntiles) load_x<D>(X, b, h, tile * 32 + r, g.N, gl, xb);
-  for (; tile < ntiles; tile += stride) {
-    const int n = tile * 32 + r;
+  if (tile < tm.total) {
+    tm.decode(tile, b, h, n0);
+    load_x<D>(X, b, h, n0 + r, g.N, gl, xb);
+  }
+  for (; tile < tm.total; tile += stride) {
+    const int n = n0 + r;
     const bool live = n < g.N;
-    if (tile + stride < ntiles) load_x<D>(X, b, h, (tile + stride) * 32 + r, g.N, gl, xn);
-#pragma unroll
-    for (int m = 0; m < NMAPS; ++m) {
+    const int64_t th = g.th(b, h, n);
+    if (tile + stride < tm.total) {
+      tm.decode(tile + stride, b, h, n0);
+      load_x<D>(X, b, h, n0 + r, g.N, gl, xn);
+    }
+    // Software pipeline over 32-row blocks of the hidden layer: while the vector ALU evaluates
+    // GELU on block (m, rb), the matrix pipe already works on the next block.
+    f32x16 cur;
+    first_layer_block<D>(smem, a_off, xb, gl, 0, cur);
+#pragma unroll 1
+    for (int m = 0; m < nmaps; ++m) {  // nmaps == NMAPS, passed at run time so this stays a loop
       const unsigned char* wm = smem + m * SM::kMap;
-      f32x16 acc[NRB];
-      first_layer<D>(wm, xb, lane, acc);
       f32x16 u;
 #pragma unroll
       for (int i = 0; i < 16; ++i) u[i] = 0.0f;
 #pragma unroll
-      for (int rb = 0; rb < NRB; ++rb)
+      for (int rb = 0; rb < NRB; ++rb) {
+        // Stage (m, rb): the eight MFMAs of the next block are issued one at a time between
+        // eighths of this block's GELU arithmetic.  An MFMA holds the wave's issue while the
+        // matrix pipe is busy, so they must be spread through the vector-ALU stream to overlap.
+        const bool more = rb + 1 < NRB || m + 1 < nmaps;
+        const unsigned char* wn = rb + 1 < NRB ? wm : wm + SM::kMap;
+        const int rbn = rb + 1 < NRB ? rb + 1 : 0;
+        f32x16 nxt;
+        u32x4 an[NKS];
+        if (more) {
+          const float* b1 = reinterpret_cast<const float*>(wn + SM::kW1 + SM::kW2);
 #pragma unroll
-        for (int half = 0; half < 2; ++half) {
-          u32x4 gb;
+          for (int q4 = 0; q4 < 4; ++q4) {
+            const f32x4 bv = *reinterpret_cast<const f32x4*>(b1 + 32 * rbn + 8 * q4 + 4 * gl);
 #pragma unroll
-          for (int p = 0; p < 4; ++p)
-            gb[p] = pack_bf16(gelu_poly(acc[rb][8 * half + 2 * p]), gelu_poly(acc[rb][8 * half + 2 * p + 1]));
-          const u32x4 a2 = *reinterpret_cast<const u32x4*>(wm + SM::kW1 + ((2 * rb + half) * 64 + lane) * 16);
-          u = mfma32(a2, gb, u);
+            for (int e = 0; e < 4; ++e) nxt[4 * q4 + e] = bv[e];
+          }
+#pragma unroll
+          for (int ks = 0; ks < NKS; ++ks)
+            an[ks] = *reinterpret_cast<const u32x4*>(wn + a_off[ks] + rbn * 32 * SM::kRow);
+        } else {
+#pragma unroll
+          for (int i = 0; i < 16; ++i) nxt[i] = 0.0f;
+#pragma unroll
+          for (int ks = 0; ks < NKS; ++ks) an[ks] = xb[ks];
         }
+        const u32x4 a20 = *reinterpret_cast<const u32x4*>(wm + SM::kW1 + ((2 * rb) * 64 + lane) * 16);
+        const u32x4 a21 = *reinterpret_cast<const u32x4*>(wm + SM::kW1 + ((2 * rb + 1) * 64 + lane) * 16);
+        u32x4 gb[2];
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          constexpr int kPer = NKS / 8 > 0 ? NKS / 8 : 1;  // MFMAs of the next block per slice
+          if (more) {
+#pragma unroll
+            for (int t = 0; t < kPer; ++t)
+              if (j * kPer + t < NKS) nxt = mfma32(an[j * kPer + t], xb[j * kPer + t], nxt);
+          }
+          if (j == 5) u = mfma32(a20, gb[0], u);
+          __builtin_amdgcn_sched_barrier(0);
+          gb[j / 4][j % 4] = pack_bf16(gelu_poly(cur[2 * j]), gelu_poly(cur[2 * j + 1]));
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        u = mfma32(a21, gb[1], u);
+        cur = nxt;
+      }
       // rows d_row(i, gl) < d_phi: lane gl=0 holds features 0..3, lane gl=1 features 4, 5
       if (live) {
-        const float* b2 = reinterpret_cast<const float*>(wm + SM::kW1 + SM::kW2 + D * 4);
-        float* f = feat + g.th(b, h, n) * g.nfeat + (map0 + m) * kDP + 4 * gl;
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-          if (4 * gl + i < kDP) f[i] = fmaxf(u[i] + b2[4 * gl + i], 0.0f);
+        const float* b2 = reinterpret_cast<const float*>(wm + SM::kW1 + SM::kW2 + D * 4) + 4 * gl;
+        float* f = feat + th * g.nfeat + (map0 + m) * kDP + 4 * gl;
+        float2 lo, hi;
+        lo.x = fmaxf(u[0] + b2[0], 0.0f);
+        lo.y = fmaxf(u[1] + b2[1], 0.0f);
+        *reinterpret_cast<float2*>(f) = lo;
+        if (gl == 0) {
+          hi.x = fmaxf(u[2] + b2[2], 0.0f);
+          hi.y = fmaxf(u[3] + b2[3], 0.0f);
+          *reinterpret_cast<float2*>(f + 2) = hi;
+        }
       }
     }
 #pragma unroll
@@ -261,12 +341,12 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_fwd(Geom g, View X,
 }
 
 // ---- backward -----------------------------------------------------------------------------------
-// grid (G, H, B), block WAVES*64.  dX = sum over the NMAPS maps of W1 (GELU'(h) * (W2 du)), with
-// du = d(feature) where the ReLU was open.  Hidden activations are recomputed.
+// block WAVES*64.  dX = sum over the NMAPS maps of W1 (GELU'(h) * (W2 du)), with du = d(feature)
+// where the ReLU was open.  Hidden activations are recomputed.
 template <int D, int NMAPS, int WAVES>
 __global__ __launch_bounds__(WAVES * 64) void k_phi_bwd(Geom g, View X,
                                                         const unsigned char* __restrict__ wpk,
-                                                        int heads_w, int map0,
+                                                        int heads_w, int map0, int nmaps,
                                                         const float* __restrict__ feat,
                                                         const float* __restrict__ dfeat, View dX) {
   using SM = PhiSmem<D>;
@@ -274,46 +354,72 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_bwd(Geom g, View X,
   extern __shared__ __align__(16) unsigned char smem[];
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
   const int r = lane % 32, gl = lane / 32;
-  const int h = blockIdx.y, b = blockIdx.z;
-  const int hw = heads_w == 1 ? 0 : h;
+  const int L = lane % 16, q = lane / 16;
+  const TileMap tm = make_tile_map(g, heads_w);
+  const int hw = heads_w == 1 ? 0 : blockIdx.y;
   for (int m = 0; m < NMAPS; ++m)
     load_weights<D, true>(smem + m * SM::kMap,
                           wpk + (static_cast<int64_t>(map0 + m) * heads_w + hw) * Packed<D>::kBytes);
   __syncthreads();
-  const int ntiles = (g.N + 31) / 32;
+  int a_off[NKS];
+  first_layer_offsets<D>(lane, a_off);
+  // Transpose reads for dx^T[in x tok] += W1[in x hidden] dh^T: k-slots (ks2, gl, j) stand for
+  // hidden units 16 ks2 + 4 gl + {0..3} (j < 4) and + 8 (j >= 4); a lane of a 16-lane group
+  // addresses hidden row k0 + L/4 and the 4 input channels 32 rb + 16 (q%2) + 4 (L%4) ..+3.
+  // swz() ignores the row's bits 4 and up, so the k-step only adds a constant to the address.
+  int t_off[2][NRB];
+#pragma unroll
+  for (int hi = 0; hi < 2; ++hi)
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb) {
+      const int row = 4 * gl + 8 * hi + L / 4;
+      const int col = 32 * rb + 16 * (q % 2) + 4 * (L % 4);
+      t_off[hi][rb] = SM::off(row, col >> 3) + ((col & 7) << 1);
+    }
   const int stride = gridDim.x * WAVES;
   int tile = blockIdx.x * WAVES + wave;
+  int b = 0, h = 0, n0 = 0;
   u32x4 xb[NKS], xn[NKS];
-  if (tile < ntiles) load_x<D>(X, b, h, tile * 32 + r, g.N, gl, xb);
-  for (; tile < ntiles; tile += stride) {
-    const int n = tile * 32 + r;
+  if (tile < tm.total) {
+    tm.decode(tile, b, h, n0);
+    load_x<D>(X, b, h, n0 + r, g.N, gl, xb);
+  }
+  for (; tile < tm.total; tile += stride) {
+    const int n = n0 + r;
     const bool live = n < g.N;
-    if (tile + stride < ntiles) load_x<D>(X, b, h, (tile + stride) * 32 + r, g.N, gl, xn);
-    // du^T as B operand of one 16-slot step: slot (gl, j) is feature 8gl + j (only gl = 0 is used)
-    u32x4 dub[NMAPS];
-#pragma unroll
-    for (int m = 0; m < NMAPS; ++m) {
-      dub[m][0] = dub[m][1] = dub[m][2] = dub[m][3] = 0u;
-      if (live && gl == 0) {
-        const int64_t o = g.th(b, h, n) * g.nfeat + (map0 + m) * kDP;
-        float du[8];
-#pragma unroll
-        for (int a = 0; a < 8; ++a)
-          du[a] = (a < kDP && feat[o + (a < kDP ? a : 0)] > 0.0f) ? dfeat[o + (a < kDP ? a : 0)] : 0.0f;
-#pragma unroll
-        for (int p = 0; p < 4; ++p) dub[m][p] = pack_bf16(du[2 * p], du[2 * p + 1]);
-      }
+    const int64_t th = g.th(b, h, live ? n : 0);
+    bf16_t* orow = dX.row<bf16_t>(b, h, live ? n : 0);
+    if (tile + stride < tm.total) {
+      tm.decode(tile + stride, b, h, n0);
+      load_x<D>(X, b, h, n0 + r, g.N, gl, xn);
     }
     f32x16 dx[NRB];
 #pragma unroll
     for (int rb = 0; rb < NRB; ++rb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) dx[rb][i] = 0.0f;
-#pragma unroll
-    for (int m = 0; m < NMAPS; ++m) {
+#pragma unroll 1
+    for (int m = 0; m < nmaps; ++m) {  // nmaps == NMAPS, passed at run time so this stays a loop
       const unsigned char* wm = smem + m * SM::kMap;
+      // du^T as B operand of one 16-slot step: slot (gl, j) is feature 8gl + j (only gl = 0 is used)
+      u32x4 dub;
+      dub[0] = dub[1] = dub[2] = dub[3] = 0u;
+      if (live && gl == 0) {
+        const int64_t o = th * g.nfeat + (map0 + m) * kDP;
+        float du[kDP];
+#pragma unroll
+        for (int a = 0; a < kDP; a += 2) {
+          const float2 f = *reinterpret_cast<const float2*>(feat + o + a);
+          const float2 d = *reinterpret_cast<const float2*>(dfeat + o + a);
+          du[a] = f.x > 0.0f ? d.x : 0.0f;
+          du[a + 1] = f.y > 0.0f ? d.y : 0.0f;
+        }
+#pragma unroll
+        for (int p = 0; p < kDP / 2; ++p) dub[p] = pack_bf16(du[2 * p], du[2 * p + 1]);
+      }
       f32x16 acc[NRB];
-      first_layer<D>(wm, xb, lane, acc);
+#pragma unroll
+      for (int rb = 0; rb < NRB; ++rb) first_layer_block<D>(wm, a_off, xb, gl, rb, acc[rb]);
       u32x4 dhb[NKS];
 #pragma unroll
       for (int rb = 0; rb < NRB; ++rb) {
@@ -321,7 +427,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_bwd(Geom g, View X,
 #pragma unroll
         for (int i = 0; i < 16; ++i) dg[i] = 0.0f;
         const u32x4 a2 = *reinterpret_cast<const u32x4*>(wm + SM::kW1 + (rb * 64 + lane) * 16);
-        dg = mfma32(a2, dub[m], dg);
+        dg = mfma32(a2, dub, dg);
 #pragma unroll
         for (int half = 0; half < 2; ++half)
 #pragma unroll
@@ -331,33 +437,22 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_bwd(Geom g, View X,
                                               dg[i + 1] * gelu_grad_poly(acc[rb][i + 1]));
           }
       }
-      // dx^T[in x tok] += W1[in x hidden] dh^T: A rows = input channels, plain reads of the W1 copy
-      auto fetch = [&](int ks2, u32x4(&a)[NRB]) {
-        const int ncol = 32 * (ks2 / 2) + 16 * (ks2 % 2) + 4 * gl;  // hidden units ncol..+3 and ncol+8..+11
+#pragma unroll
+      for (int ks2 = 0; ks2 < NKS; ++ks2)
 #pragma unroll
         for (int rb = 0; rb < NRB; ++rb) {
-          const int row = 32 * rb + r;
-          const u32x2 lo = *reinterpret_cast<const u32x2*>(wm + SM::w1_off(row, ncol));
-          const u32x2 hi = *reinterpret_cast<const u32x2*>(wm + SM::w1_off(row, ncol + 8));
-          a[rb][0] = lo[0];
-          a[rb][1] = lo[1];
-          a[rb][2] = hi[0];
-          a[rb][3] = hi[1];
+          const unsigned char* p = wm + ks2 * 16 * SM::kRow;
+          const u32x2 lo = lds_read_tr16(p + t_off[0][rb]);
+          const u32x2 hi = lds_read_tr16(p + t_off[1][rb]);
+          u32x4 a;
+          a[0] = lo[0];
+          a[1] = lo[1];
+          a[2] = hi[0];
+          a[3] = hi[1];
+          dx[rb] = mfma32(a, dhb[ks2], dx[rb]);
         }
-      };
-      u32x4 aw[2][NRB];
-      fetch(0, aw[0]);
-#pragma unroll
-      for (int ks2 = 0; ks2 < NKS; ++ks2) {
-        if (ks2 + 1 < NKS) fetch(ks2 + 1, aw[(ks2 + 1) & 1]);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int rb = 0; rb < NRB; ++rb) dx[rb] = mfma32(aw[ks2 & 1][rb], dhb[ks2], dx[rb]);
-        __builtin_amdgcn_sched_barrier(0);
-      }
     }
     if (live) {
-      bf16_t* orow = dX.row<bf16_t>(b, h, n);
 #pragma unroll
       for (int rb = 0; rb < NRB; ++rb)
 #pragma unroll
@@ -381,16 +476,24 @@ hla_status allow_lds(K kernel, int bytes) {
              : HLA_ERR_HIP;
 }
 
-int grid_x(const Geom& g, int waves) {
-  // about one workgroup per compute unit in total, at least one per (batch row, head)
+// One workgroup per compute unit in total.  Shared weights: a flat grid over all tiles; per-head
+// weights: (x, H, B) with x workgroups per (batch row, head).
+dim3 phi_grid(const hla_handle* hd, int waves) {
+  const Geom& g = hd->g;
+  const int tiles = (g.N + 31) / 32;
+  if (hd->phi.heads_w == 1) {
+    const int64_t total = static_cast<int64_t>(tiles) * g.B * g.H;
+    const int64_t want = (total + waves - 1) / waves;
+    return dim3(static_cast<unsigned>(want < 256 ? (want < 1 ? 1 : want) : 256), 1, 1);
+  }
   const int units = g.B * g.H;
-  const int tiles = (g.N + 32 * waves - 1) / (32 * waves);
   int gx = 256 / units;  // rounding down keeps the whole grid resident in one round
-  if (gx > tiles) gx = tiles;
-  return gx < 1 ? 1 : gx;
+  const int need = (tiles + waves - 1) / waves;
+  if (gx > need) gx = need;
+  return dim3(gx < 1 ? 1 : gx, g.H, g.B);
 }
 
-constexpr int kWavesQ = HLA_PHI_WAVES_Q, kWavesK = HLA_PHI_WAVES_K;
+constexpr int kWavesF = HLA_PHI_WAVES_F, kWavesB = HLA_PHI_WAVES_B;
 
 template <int D>
 hla_status forward_t(hla_handle* hd, const hla_call_args& a) {
@@ -399,14 +502,15 @@ hla_status forward_t(hla_handle* hd, const hla_call_args& a) {
   const unsigned char* wpk = static_cast<const unsigned char*>(hd->path_ws) + hd->w_packed_off;
   static bool attr = false;
   if (!attr) {
-    HLA_TRY(allow_lds(&k_phi_fwd<D, 1, kWavesQ>, SM::total(1)));
-    HLA_TRY(allow_lds(&k_phi_fwd<D, 3, kWavesK>, SM::total(3)));
+    HLA_TRY(allow_lds(&k_phi_fwd<D, 1, kWavesF>, SM::total(1)));
+    HLA_TRY(allow_lds(&k_phi_fwd<D, 3, kWavesF>, SM::total(3)));
     attr = true;
   }
-  HLA_TRY(launch(hd, "mfma_phi_forward_q", k_phi_fwd<D, 1, kWavesQ>, dim3(grid_x(g, kWavesQ), g.H, g.B),
-                 dim3(kWavesQ * 64), SM::total(1), a.stream, g, a.Q, wpk, hd->phi.heads_w, 0, hd->feat));
-  HLA_TRY(launch(hd, "mfma_phi_forward_k", k_phi_fwd<D, 3, kWavesK>, dim3(grid_x(g, kWavesK), g.H, g.B),
-                 dim3(kWavesK * 64), SM::total(3), a.stream, g, a.K, wpk, hd->phi.heads_w, 1, hd->feat));
+  const dim3 grid = phi_grid(hd, kWavesF);
+  HLA_TRY(launch(hd, "mfma_phi_forward_q", k_phi_fwd<D, 1, kWavesF>, grid, dim3(kWavesF * 64),
+                 SM::total(1), a.stream, g, a.Q, wpk, hd->phi.heads_w, 0, 1, hd->feat));
+  HLA_TRY(launch(hd, "mfma_phi_forward_k", k_phi_fwd<D, 3, kWavesF>, grid, dim3(kWavesF * 64),
+                 SM::total(3), a.stream, g, a.K, wpk, hd->phi.heads_w, 1, 3, hd->feat));
   return HLA_OK;
 }
 
@@ -417,16 +521,15 @@ hla_status backward_t(hla_handle* hd, const hla_call_args& a) {
   const unsigned char* wpk = static_cast<const unsigned char*>(hd->path_ws) + hd->w_packed_off;
   static bool attr = false;
   if (!attr) {
-    HLA_TRY(allow_lds(&k_phi_bwd<D, 1, kWavesQ>, SM::total(1)));
-    HLA_TRY(allow_lds(&k_phi_bwd<D, 3, kWavesK>, SM::total(3)));
+    HLA_TRY(allow_lds(&k_phi_bwd<D, 1, kWavesB>, SM::total(1)));
+    HLA_TRY(allow_lds(&k_phi_bwd<D, 3, kWavesB>, SM::total(3)));
     attr = true;
   }
-  HLA_TRY(launch(hd, "mfma_phi_backward_q", k_phi_bwd<D, 1, kWavesQ>, dim3(grid_x(g, kWavesQ), g.H, g.B),
-                 dim3(kWavesQ * 64), SM::total(1), a.stream, g, a.Q, wpk, hd->phi.heads_w, 0, hd->feat,
-                 hd->dfeat, a.dQ));
-  HLA_TRY(launch(hd, "mfma_phi_backward_k", k_phi_bwd<D, 3, kWavesK>, dim3(grid_x(g, kWavesK), g.H, g.B),
-                 dim3(kWavesK * 64), SM::total(3), a.stream, g, a.K, wpk, hd->phi.heads_w, 1, hd->feat,
-                 hd->dfeat, a.dK));
+  const dim3 grid = phi_grid(hd, kWavesB);
+  HLA_TRY(launch(hd, "mfma_phi_backward_q", k_phi_bwd<D, 1, kWavesB>, grid, dim3(kWavesB * 64),
+                 SM::total(1), a.stream, g, a.Q, wpk, hd->phi.heads_w, 0, 1, hd->feat, hd->dfeat, a.dQ));
+  HLA_TRY(launch(hd, "mfma_phi_backward_k", k_phi_bwd<D, 3, kWavesB>, grid, dim3(kWavesB * 64),
+                 SM::total(3), a.stream, g, a.K, wpk, hd->phi.heads_w, 1, 3, hd->feat, hd->dfeat, a.dK));
   return HLA_OK;
 }
 
