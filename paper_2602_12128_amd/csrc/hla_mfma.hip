@@ -273,7 +273,9 @@ __global__ __launch_bounds__(kThreads) void k_query(Geom g, const BlockEnt* __re
   using SL = StateLayout<DP, D>;
   constexpr int SP = SY::SP, MP = SY::MP;
   constexpr int NRB = D / 32, NKS = MP / 16;
+  __shared__ __align__(16) unsigned char smem[kWaves * RowTile<D>::kBytes];
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  unsigned char* tile = smem + wave * RowTile<D>::kBytes;
   const int r = lane % 32, gl = lane / 32;
   const BlockEnt e = blocks[blockIdx.x];
   const int h = blockIdx.y;
@@ -326,18 +328,9 @@ __global__ __launch_bounds__(kThreads) void k_query(Geom g, const BlockEnt* __re
 #pragma unroll
       for (int ks = 0; ks < NKS; ++ks) acc[rb] = mfma32(a[rb][ks], b[ks], acc[rb]);
     }
-    if (live) {
-      bf16_t* orow = O.row<bf16_t>(e.b, h, n);
-#pragma unroll
-      for (int rb = 0; rb < NRB; ++rb)
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-          u32x2 w;
-          w[0] = pack_bf16(acc[rb][4 * q4] * inv, acc[rb][4 * q4 + 1] * inv);
-          w[1] = pack_bf16(acc[rb][4 * q4 + 2] * inv, acc[rb][4 * q4 + 3] * inv);
-          *reinterpret_cast<u32x2*>(orow + 32 * rb + 8 * q4 + 4 * gl) = w;
-        }
-    }
+    store_rows_bf16<D>(acc, inv, lane, tile, [&](int t) -> bf16_t* {
+      return n0 + t < e.t1 ? O.row<bf16_t>(e.b, h, n0 + t) : nullptr;
+    });
   }
 }
 
@@ -559,15 +552,12 @@ __global__ __launch_bounds__(kThreads) void k_bwd_query(
 }
 
 // ---- k_bwd_key --------------------------------------------------------------------------------
-template <int D>
-struct BwdKSmem {
-  static constexpr int kRow = D * 2 + 32;
-  static constexpr int kWaveBytes = 32 * kRow;
-  static constexpr int kTotal = kWaves * kWaveBytes;
-};
-
-// grid (blocks of kQueryBlock tokens, H), block 256.  Per 32-token tile and lane (token r, gl):
+// grid (chunks, H), block 256.  Per 32-token tile and lane (token r, gl):
 //   dS^T = dCsym V^T (+ dzsym) -> chain rule to d(phi_k1..3);  dV^T = dCsym^T S^T.
+// LDS only serves the transpose of the dV tile for whole-row stores.
+// Both contractions run over channels or monomials, never over tokens, so a lane loads its own
+// token's V row straight into B-operand order; the next tile's row and features are fetched while
+// the current tile is computed.
 template <int DP, int D>
 __global__ __launch_bounds__(kThreads) void k_bwd_key(Geom g, const BlockEnt* __restrict__ blocks,
                                                       const float* __restrict__ feat,
@@ -575,12 +565,11 @@ __global__ __launch_bounds__(kThreads) void k_bwd_key(Geom g, const BlockEnt* __
                                                       float* __restrict__ dfeat, View dV) {
   using SY = Sym3<DP>;
   using SL = StateLayout<DP, D>;
-  using SM = BwdKSmem<D>;
   constexpr int SP = SY::SP, MP = SY::MP;
   constexpr int NRB = D / 32, NKS = MP / 16, NKD = D / 16;
-  extern __shared__ __align__(16) unsigned char smem[];
+  __shared__ __align__(16) unsigned char smem[kWaves * RowTile<D>::kBytes];
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
-  unsigned char* vs = smem + wave * SM::kWaveBytes;
+  unsigned char* tile = smem + wave * RowTile<D>::kBytes;
   const int r = lane % 32, gl = lane / 32;
   const BlockEnt e = blocks[blockIdx.x];
   const int h = blockIdx.y;
@@ -599,38 +588,80 @@ __global__ __launch_bounds__(kThreads) void k_bwd_key(Geom g, const BlockEnt* __
     for (int ks = 0; ks < NKD; ++ks) a_mo[rb][ks] = opB[(rb * NKD + ks) * 64 + lane];
   float dz[SP];
 #pragma unroll
-  for (int s = 0; s < SP; ++s) dz[s] = dzslot[s];
+  for (int s4 = 0; s4 < SP / 4; ++s4) {
+    const f32x4 v = *reinterpret_cast<const f32x4*>(dzslot + 4 * s4);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) dz[4 * s4 + i] = v[i];
+  }
 
-  for (int n0 = e.t0 + wave * 32; n0 < e.t1; n0 += kWaves * 32) {
-    stage_tile32<D>(V, e.b, h, n0, e.t1, lane, vs, SM::kRow);
-    wave_lds_sync();
+  // one tile's inputs: the V row pieces (B operand, k-slot (ks, gl, j) = channel 16ks + 8gl + j;
+  // the 32-byte runs of a row that one load instruction touches are merged by the vector cache)
+  // and the 18 key features of the token
+  u32x4 vb[NKD], vn[NKD];
+  float2 kb[3 * DP / 2], kn[3 * DP / 2];
+  auto fetch = [&](int n0, u32x4(&v)[NKD], float2(&k)[3 * DP / 2]) {
+    const int n = n0 + r;
+    if (n < e.t1) {
+      const bf16_t* row = V.row<const bf16_t>(e.b, h, n);
+#pragma unroll
+      for (int ks = 0; ks < NKD; ++ks) v[ks] = *reinterpret_cast<const u32x4*>(row + 16 * ks + 8 * gl);
+      const float2* f = reinterpret_cast<const float2*>(feat + g.th(e.b, h, n) * g.nfeat + DP);
+#pragma unroll
+      for (int a = 0; a < 3 * DP / 2; ++a) k[a] = f[a];
+    } else {
+#pragma unroll
+      for (int ks = 0; ks < NKD; ++ks) v[ks][0] = v[ks][1] = v[ks][2] = v[ks][3] = 0u;
+#pragma unroll
+      for (int a = 0; a < 3 * DP / 2; ++a) k[a].x = k[a].y = 0.0f;
+    }
+  };
+  int n0 = e.t0 + wave * 32;
+  if (n0 < e.t1) fetch(n0, vb, kb);
+  for (; n0 < e.t1; n0 += kWaves * 32) {
     const int n = n0 + r;
     const bool live = n < e.t1;
     const int64_t th = g.th(e.b, h, live ? n : e.t0);
+    if (n0 + kWaves * 32 < e.t1) fetch(n0 + kWaves * 32, vn, kn);
     f32x16 dS[2];
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) dS[rb][i] = 0.0f;
 #pragma unroll
-    for (int ks = 0; ks < NKD; ++ks) {
-      const u32x4 bv = *reinterpret_cast<const u32x4*>(vs + r * SM::kRow + (16 * ks + 8 * gl) * 2);
+    for (int ks = 0; ks < NKD; ++ks)
 #pragma unroll
-      for (int rb = 0; rb < 2; ++rb) dS[rb] = mfma32(a_mo[rb][ks], bv, dS[rb]);
-    }
+      for (int rb = 0; rb < 2; ++rb) dS[rb] = mfma32(a_mo[rb][ks], vb[ks], dS[rb]);
+    // features of this lane's half: gl = 1 works on the reversed vectors
     float k1[DP], k2[DP], k3[DP];
-    if (live) {
-      const float* f = feat + th * g.nfeat + DP;
+    {
+      float kf[3 * DP];
+#pragma unroll
+      for (int a = 0; a < 3 * DP / 2; ++a) {
+        kf[2 * a] = kb[a].x;
+        kf[2 * a + 1] = kb[a].y;
+      }
 #pragma unroll
       for (int c = 0; c < DP; ++c) {
-        const int cc = gl ? DP - 1 - c : c;
-        k1[c] = f[cc];
-        k2[c] = f[DP + cc];
-        k3[c] = f[2 * DP + cc];
+        k1[c] = gl ? kf[DP - 1 - c] : kf[c];
+        k2[c] = gl ? kf[2 * DP - 1 - c] : kf[DP + c];
+        k3[c] = gl ? kf[3 * DP - 1 - c] : kf[2 * DP + c];
       }
-    } else {
+    }
+    // dV^T = dCsym^T S^T first: its MFMAs run while the chain rule below occupies the vector ALU
+    float sm[SP];
+    key_monomials_slots<DP>(k1, k2, k3, sm);
+    f32x16 acc[NRB];
 #pragma unroll
-      for (int c = 0; c < DP; ++c) k1[c] = k2[c] = k3[c] = 0.0f;
+    for (int rb = 0; rb < NRB; ++rb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[rb][i] = 0.0f;
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) {
+      u32x4 b;
+#pragma unroll
+      for (int p = 0; p < 4; ++p) b[p] = pack_bf16(sm[8 * ks + 2 * p], sm[8 * ks + 2 * p + 1]);
+#pragma unroll
+      for (int rb = 0; rb < NRB; ++rb) acc[rb] = mfma32(a_ch[rb][ks], b, acc[rb]);
     }
     {
       float ds[SP];
@@ -650,43 +681,22 @@ __global__ __launch_bounds__(kThreads) void k_bwd_key(Geom g, const BlockEnt* __
         o3[c] = partner32(dk3[c]);
       }
       if (live && gl == 0) {
-        float* df = dfeat + th * g.nfeat + DP;
+        float2* df = reinterpret_cast<float2*>(dfeat + th * g.nfeat + DP);
 #pragma unroll
-        for (int c = 0; c < DP; ++c) {
-          df[c] = dk1[c] + o1[DP - 1 - c];
-          df[DP + c] = dk2[c] + o2[DP - 1 - c];
-          df[2 * DP + c] = dk3[c] + o3[DP - 1 - c];
+        for (int c = 0; c < DP; c += 2) {
+          df[c / 2] = make_float2(dk1[c] + o1[DP - 1 - c], dk1[c + 1] + o1[DP - 2 - c]);
+          df[(DP + c) / 2] = make_float2(dk2[c] + o2[DP - 1 - c], dk2[c + 1] + o2[DP - 2 - c]);
+          df[(2 * DP + c) / 2] = make_float2(dk3[c] + o3[DP - 1 - c], dk3[c + 1] + o3[DP - 2 - c]);
         }
       }
     }
-    float sm[SP];
-    key_monomials_slots<DP>(k1, k2, k3, sm);
-    f32x16 acc[NRB];
+    store_rows_bf16<D>(acc, 1.0f, lane, tile, [&](int t) -> bf16_t* {
+      return n0 + t < e.t1 ? dV.row<bf16_t>(e.b, h, n0 + t) : nullptr;
+    });
 #pragma unroll
-    for (int rb = 0; rb < NRB; ++rb)
+    for (int ks = 0; ks < NKD; ++ks) vb[ks] = vn[ks];
 #pragma unroll
-      for (int i = 0; i < 16; ++i) acc[rb][i] = 0.0f;
-#pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) {
-      u32x4 b;
-#pragma unroll
-      for (int p = 0; p < 4; ++p) b[p] = pack_bf16(sm[8 * ks + 2 * p], sm[8 * ks + 2 * p + 1]);
-#pragma unroll
-      for (int rb = 0; rb < NRB; ++rb) acc[rb] = mfma32(a_ch[rb][ks], b, acc[rb]);
-    }
-    if (live) {
-      bf16_t* orow = dV.row<bf16_t>(e.b, h, n);
-#pragma unroll
-      for (int rb = 0; rb < NRB; ++rb)
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-          u32x2 w;
-          w[0] = pack_bf16(acc[rb][4 * q4], acc[rb][4 * q4 + 1]);
-          w[1] = pack_bf16(acc[rb][4 * q4 + 2], acc[rb][4 * q4 + 3]);
-          *reinterpret_cast<u32x2*>(orow + 32 * rb + 8 * q4 + 4 * gl) = w;
-        }
-    }
-    wave_lds_sync();
+    for (int a = 0; a < 3 * DP / 2; ++a) kb[a] = kn[a];
   }
 }
 
@@ -721,7 +731,6 @@ hla_status backward_core(hla_handle* hd, const hla_call_args& a) {
   static bool attr_set = false;
   if (!attr_set) {
     HLA_TRY(allow_big_lds(&k_bwd_query<DP, D>, BwdQSmem<D>::kTotal));
-    HLA_TRY(allow_big_lds(&k_bwd_key<DP, D>, BwdKSmem<D>::kTotal));
     attr_set = true;
   }
   unsigned char* ops = static_cast<unsigned char*>(hd->path_ws);
@@ -733,7 +742,7 @@ hla_status backward_core(hla_handle* hd, const hla_call_args& a) {
                  dim3(256), 0, s, g, chunks->seq_off_dev, hd->partial, SL::kF32, hd->dstate, dops,
                  make_slot_map<DP>()));
   HLA_TRY(launch(hd, "mfma_bwd_key", k_bwd_key<DP, D>, dim3(chunks->count, g.H), dim3(kThreads),
-                 BwdKSmem<D>::kTotal, s, g, chunks->dev, hd->feat, dops, a.V, hd->dfeat, a.dV));
+                 0, s, g, chunks->dev, hd->feat, dops, a.V, hd->dfeat, a.dV));
   return HLA_OK;
 }
 

@@ -121,6 +121,65 @@ __device__ __forceinline__ void put_tile(const TileRegs<D, ROWS>& t, int lane, u
     *reinterpret_cast<u32x4*>(dst + (i * T::RPL + prow) * stride + pcol * 16) = t.v[i];
 }
 
+// ---- coalesced row stores of a token-per-lane accumulator tile ---------------------------------
+// acc[rb][i] holds channel 32rb + d_row(i, gl) of token r (lane (r, gl)).  The tile is rounded to
+// bf16, exchanged between the two lanes of a token (v_permlane32_swap) so that each lane owns two
+// runs of 8 consecutive channels per row block, written to a wave-private LDS tile and read back
+// with 16 consecutive lanes covering one token row, so that every global store instruction
+// writes whole 2D-byte rows.  `row_ptr(t)` returns the destination of tile row t or nullptr.
+template <int D, int ROWS = 32>
+struct RowTile {
+  static constexpr int kStride = D * 2 + 16;   // bytes; 16-byte reads and writes stay conflict-free
+  static constexpr int kBytes = ROWS * kStride;
+};
+// ROWS (32 or 16) = token rows the LDS tile holds; with 16 the tile goes out in two passes.
+template <int D, int ROWS = 32, class RowPtr>
+__device__ __forceinline__ void store_rows_bf16(const f32x16 (&acc)[D / 32], float scale, int lane,
+                                                unsigned char* lds, RowPtr&& row_ptr) {
+  using RT = RowTile<D, ROWS>;
+  const int r = lane % 32, gl = lane / 32;
+  u32x4 w[D / 32][2];
+#pragma unroll
+  for (int rb = 0; rb < D / 32; ++rb)
+#pragma unroll
+    for (int pr = 0; pr < 2; ++pr) {
+      const int x = 8 * pr, y = 8 * pr + 4;  // accumulator registers of the two 4-channel groups
+      const uint32_t x0 = pack_bf16(acc[rb][x] * scale, acc[rb][x + 1] * scale);
+      const uint32_t x1 = pack_bf16(acc[rb][x + 2] * scale, acc[rb][x + 3] * scale);
+      const uint32_t y0 = pack_bf16(acc[rb][y] * scale, acc[rb][y + 1] * scale);
+      const uint32_t y1 = pack_bf16(acc[rb][y + 2] * scale, acc[rb][y + 3] * scale);
+      // upper lanes of x swap with lower lanes of y: lane gl = 0 ends with channels +0..7 of the
+      // 16-channel group, lane gl = 1 with channels +8..15
+      const auto s0 = __builtin_amdgcn_permlane32_swap(x0, y0, false, false);
+      const auto s1 = __builtin_amdgcn_permlane32_swap(x1, y1, false, false);
+      w[rb][pr][0] = s0[0];
+      w[rb][pr][1] = s1[0];
+      w[rb][pr][2] = s0[1];
+      w[rb][pr][3] = s1[1];
+    }
+  constexpr int PIECES = D / 8;        // 16-byte pieces per row
+  constexpr int RPI = 64 / PIECES;     // rows per store instruction
+#pragma unroll
+  for (int pass = 0; pass < 32 / ROWS; ++pass) {
+    if (ROWS == 32 || r / ROWS == pass) {
+#pragma unroll
+      for (int rb = 0; rb < D / 32; ++rb)
+#pragma unroll
+        for (int pr = 0; pr < 2; ++pr)
+          *reinterpret_cast<u32x4*>(lds + (r % ROWS) * RT::kStride + (32 * rb + 16 * pr + 8 * gl) * 2) = w[rb][pr];
+    }
+    wave_lds_sync();
+#pragma unroll
+    for (int i = 0; i < ROWS / RPI; ++i) {
+      const int row = i * RPI + lane / PIECES, piece = lane % PIECES;
+      const u32x4 v = *reinterpret_cast<const u32x4*>(lds + row * RT::kStride + piece * 16);
+      bf16_t* dst = row_ptr(pass * ROWS + row);
+      if (dst != nullptr) *reinterpret_cast<u32x4*>(dst + piece * 8) = v;
+    }
+    wave_lds_sync();
+  }
+}
+
 template <int I, int N, class Fn>
 __device__ __forceinline__ void static_for(Fn&& f) {
   if constexpr (I < N) {

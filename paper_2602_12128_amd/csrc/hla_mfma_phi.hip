@@ -112,14 +112,17 @@ __global__ void k_pack_phi(PhiF32 w, int dphi, unsigned char* __restrict__ out) 
 // function of the row chosen so that both access patterns spread over all banks without padding:
 //   plain 16-byte reads of 16 consecutive rows at one chunk (first-layer A operand), and
 //   transpose reads of 4 consecutive rows x 4 consecutive chunks (A operand of dx^T = W1 dh^T).
-template <int D>
+template <int D, bool BACKWARD = false>
 struct PhiSmem {
   static constexpr int kChunks = D / 8;               // 16-byte chunks per row
   static constexpr int kRow = D * 2;                  // bytes per row
   static constexpr int kW1 = D * D * 2;
-  static constexpr int kW2 = D * 32 * 2;              // room for W2A (forward) or W2B (backward, half used)
+  static constexpr int kW2 = BACKWARD ? D * 16 * 2 : D * 32 * 2;  // W2B (backward) or W2A (forward)
   static constexpr int kMap = kW1 + kW2 + D * 4 + 32;  // + b1 + b2
-  static constexpr int total(int nmaps) { return nmaps * kMap; }
+  // backward adds a 16-row transpose tile per wave for whole-row stores of dX
+  static constexpr int total(int nmaps, int waves) {
+    return nmaps * kMap + (BACKWARD ? waves * RowTile<D, 16>::kBytes : 0);
+  }
   __host__ __device__ static __forceinline__ int swz(int row) {
     return D == 128 ? (((row & 3) << 2) | ((row >> 2) & 3)) : ((((row >> 1) & 1) << 2) | ((row >> 2) & 3));
   }
@@ -131,7 +134,7 @@ struct PhiSmem {
 // Copy one (map, head) block of packed weights into LDS (all threads of the workgroup).
 template <int D, bool BACKWARD>
 __device__ __forceinline__ void load_weights(unsigned char* dst, const unsigned char* src) {
-  using SM = PhiSmem<D>;
+  using SM = PhiSmem<D, BACKWARD>;
   using PK = Packed<D>;
   const int nthreads = blockDim.x;
   for (int i = threadIdx.x; i < D * SM::kChunks; i += nthreads) {
@@ -175,11 +178,11 @@ __device__ __forceinline__ void first_layer_offsets(int lane, int (&a_off)[D / 1
 // One 32-row block of hidden^T = b1 + W1^T X^T: acc[i] is hidden unit 32rb + d_row(i, gl) of
 // token r.  The eight MFMAs only queue on the matrix pipe; vector-ALU work that follows in program
 // order and does not read `acc` runs in their shadow.
-template <int D>
+template <int D, bool BACKWARD>
 __device__ __forceinline__ void first_layer_block(const unsigned char* wm, const int (&a_off)[D / 16],
                                                   const u32x4 (&xb)[D / 16], int gl, int rb,
                                                   f32x16& acc) {
-  using SM = PhiSmem<D>;
+  using SM = PhiSmem<D, BACKWARD>;
   const float* b1 = reinterpret_cast<const float*>(wm + SM::kW1 + SM::kW2);
 #pragma unroll
   for (int q4 = 0; q4 < 4; ++q4) {
@@ -266,7 +269,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_fwd(Geom g, View X,
     // Software pipeline over 32-row blocks of the hidden layer: while the vector ALU evaluates
     // GELU on block (m, rb), the matrix pipe already works on the next block.
     f32x16 cur;
-    first_layer_block<D>(smem, a_off, xb, gl, 0, cur);
+    first_layer_block<D, false>(smem, a_off, xb, gl, 0, cur);
 #pragma unroll 1
     for (int m = 0; m < nmaps; ++m) {  // nmaps == NMAPS, passed at run time so this stays a loop
       const unsigned char* wm = smem + m * SM::kMap;
@@ -349,7 +352,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_bwd(Geom g, View X,
                                                         int heads_w, int map0, int nmaps,
                                                         const float* __restrict__ feat,
                                                         const float* __restrict__ dfeat, View dX) {
-  using SM = PhiSmem<D>;
+  using SM = PhiSmem<D, true>;
   constexpr int NRB = D / 32, NKS = D / 16;
   extern __shared__ __align__(16) unsigned char smem[];
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
@@ -361,6 +364,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_bwd(Geom g, View X,
     load_weights<D, true>(smem + m * SM::kMap,
                           wpk + (static_cast<int64_t>(map0 + m) * heads_w + hw) * Packed<D>::kBytes);
   __syncthreads();
+  unsigned char* ttile = smem + nmaps * SM::kMap + wave * RowTile<D, 16>::kBytes;  // dX transpose tile
   int a_off[NKS];
   first_layer_offsets<D>(lane, a_off);
   // Transpose reads for dx^T[in x tok] += W1[in x hidden] dh^T: k-slots (ks2, gl, j) stand for
@@ -388,7 +392,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_bwd(Geom g, View X,
     const int n = n0 + r;
     const bool live = n < g.N;
     const int64_t th = g.th(b, h, live ? n : 0);
-    bf16_t* orow = dX.row<bf16_t>(b, h, live ? n : 0);
+    const int ob = b, oh = h, on0 = n0;  // this tile's coordinates (b, h, n0 move on to the next tile below)
     if (tile + stride < tm.total) {
       tm.decode(tile + stride, b, h, n0);
       load_x<D>(X, b, h, n0 + r, g.N, gl, xn);
@@ -419,7 +423,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_bwd(Geom g, View X,
       }
       f32x16 acc[NRB];
 #pragma unroll
-      for (int rb = 0; rb < NRB; ++rb) first_layer_block<D>(wm, a_off, xb, gl, rb, acc[rb]);
+      for (int rb = 0; rb < NRB; ++rb) first_layer_block<D, true>(wm, a_off, xb, gl, rb, acc[rb]);
       u32x4 dhb[NKS];
 #pragma unroll
       for (int rb = 0; rb < NRB; ++rb) {
@@ -452,17 +456,9 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_bwd(Geom g, View X,
           dx[rb] = mfma32(a, dhb[ks2], dx[rb]);
         }
     }
-    if (live) {
-#pragma unroll
-      for (int rb = 0; rb < NRB; ++rb)
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-          u32x2 w;
-          w[0] = pack_bf16(dx[rb][4 * q4], dx[rb][4 * q4 + 1]);
-          w[1] = pack_bf16(dx[rb][4 * q4 + 2], dx[rb][4 * q4 + 3]);
-          *reinterpret_cast<u32x2*>(orow + 32 * rb + 8 * q4 + 4 * gl) = w;
-        }
-    }
+    store_rows_bf16<D, 16>(dx, 1.0f, lane, ttile, [&](int t) -> bf16_t* {
+      return on0 + t < g.N ? dX.row<bf16_t>(ob, oh, on0 + t) : nullptr;
+    });
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) xb[ks] = xn[ks];
   }
@@ -502,34 +498,34 @@ hla_status forward_t(hla_handle* hd, const hla_call_args& a) {
   const unsigned char* wpk = static_cast<const unsigned char*>(hd->path_ws) + hd->w_packed_off;
   static bool attr = false;
   if (!attr) {
-    HLA_TRY(allow_lds(&k_phi_fwd<D, 1, kWavesF>, SM::total(1)));
-    HLA_TRY(allow_lds(&k_phi_fwd<D, 3, kWavesF>, SM::total(3)));
+    HLA_TRY(allow_lds(&k_phi_fwd<D, 1, kWavesF>, SM::total(1, kWavesF)));
+    HLA_TRY(allow_lds(&k_phi_fwd<D, 3, kWavesF>, SM::total(3, kWavesF)));
     attr = true;
   }
   const dim3 grid = phi_grid(hd, kWavesF);
   HLA_TRY(launch(hd, "mfma_phi_forward_q", k_phi_fwd<D, 1, kWavesF>, grid, dim3(kWavesF * 64),
-                 SM::total(1), a.stream, g, a.Q, wpk, hd->phi.heads_w, 0, 1, hd->feat));
+                 SM::total(1, kWavesF), a.stream, g, a.Q, wpk, hd->phi.heads_w, 0, 1, hd->feat));
   HLA_TRY(launch(hd, "mfma_phi_forward_k", k_phi_fwd<D, 3, kWavesF>, grid, dim3(kWavesF * 64),
-                 SM::total(3), a.stream, g, a.K, wpk, hd->phi.heads_w, 1, 3, hd->feat));
+                 SM::total(3, kWavesF), a.stream, g, a.K, wpk, hd->phi.heads_w, 1, 3, hd->feat));
   return HLA_OK;
 }
 
 template <int D>
 hla_status backward_t(hla_handle* hd, const hla_call_args& a) {
-  using SM = PhiSmem<D>;
+  using SM = PhiSmem<D, true>;
   Geom g = hd->g;
   const unsigned char* wpk = static_cast<const unsigned char*>(hd->path_ws) + hd->w_packed_off;
   static bool attr = false;
   if (!attr) {
-    HLA_TRY(allow_lds(&k_phi_bwd<D, 1, kWavesB>, SM::total(1)));
-    HLA_TRY(allow_lds(&k_phi_bwd<D, 3, kWavesB>, SM::total(3)));
+    HLA_TRY(allow_lds(&k_phi_bwd<D, 1, kWavesB>, SM::total(1, kWavesB)));
+    HLA_TRY(allow_lds(&k_phi_bwd<D, 3, kWavesB>, SM::total(3, kWavesB)));
     attr = true;
   }
   const dim3 grid = phi_grid(hd, kWavesB);
   HLA_TRY(launch(hd, "mfma_phi_backward_q", k_phi_bwd<D, 1, kWavesB>, grid, dim3(kWavesB * 64),
-                 SM::total(1), a.stream, g, a.Q, wpk, hd->phi.heads_w, 0, 1, hd->feat, hd->dfeat, a.dQ));
+                 SM::total(1, kWavesB), a.stream, g, a.Q, wpk, hd->phi.heads_w, 0, 1, hd->feat, hd->dfeat, a.dQ));
   HLA_TRY(launch(hd, "mfma_phi_backward_k", k_phi_bwd<D, 3, kWavesB>, grid, dim3(kWavesB * 64),
-                 SM::total(3), a.stream, g, a.K, wpk, hd->phi.heads_w, 1, 3, hd->feat, hd->dfeat, a.dK));
+                 SM::total(3, kWavesB), a.stream, g, a.K, wpk, hd->phi.heads_w, 1, 3, hd->feat, hd->dfeat, a.dK));
   return HLA_OK;
 }
 
