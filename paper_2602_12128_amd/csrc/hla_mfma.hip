@@ -19,7 +19,7 @@ constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
 constexpr int kQueryBlock = 1024;  // tokens per workgroup in token-parallel kernels
 constexpr int kChunkTarget = 240;   // workgroups aimed at by the chunked (token-contraction) kernels
-constexpr int kReduceSlices = 32;  // row slices of the state per (sequence, head) in k_reduce
+constexpr int kReduceSlices = 8;   // slices of the state per (sequence, head) in k_reduce
 
 // Where canonical monomial m sits among the (g, slot) pairs.
 struct SlotMap {
@@ -209,54 +209,79 @@ __global__ __launch_bounds__(kThreads) void k_state(Geom g, const BlockEnt* __re
 
 // ---- k_reduce ---------------------------------------------------------------------------------
 // grid (num_seqs, H, kReduceSlices), block 256.  Sums the chunk partials of one (sequence, head)
-// in chunk order, writes the fp32 state and scatters its bf16 copy into the two operand layouts:
+// in chunk order and scatters the bf16 copy of the state into the two operand layouts:
 //   opA[rb][ks][lane=(r,gl)][j] = Csym[mono(gl, 8ks+j)][32rb + r]           (rows = channels)
 //   opB[rb][ks][lane=(r,gl)][j] = Csym[mono of row 32rb + r][16ks + 8gl + j]  (rows = monomials)
 // where state row rho = 32rb + r belongs to (g, s) with rho%32 = 8*(i/4) + 4g + i%4, s = 16rb + i.
-template <int DP, int D>
-__global__ void k_reduce(Geom g, const int32_t* __restrict__ seq_chunk_off,
-                         const float* __restrict__ partial, int64_t partial_stride,
-                         float* __restrict__ state, unsigned char* __restrict__ ops, SlotMap sm) {
+// SLOT_ROWS = false: partial rows are canonical monomials (k_state); true: partial row 32g + s is
+// slot (g, s) already (k_bwd_query).  A thread owns four consecutive channels of one row; the
+// loads of eight chunks are in flight together, the additions stay in chunk order.
+template <int DP, int D, bool SLOT_ROWS>
+__global__ __launch_bounds__(256) void k_reduce(Geom g, const int32_t* __restrict__ seq_chunk_off,
+                                                const float* __restrict__ partial,
+                                                int64_t partial_stride,
+                                                unsigned char* __restrict__ ops, SlotMap sm) {
   using SL = StateLayout<DP, D>;
   constexpr int MP = SL::MP, SP = SL::SP;
-  constexpr int RW = MP / kReduceSlices;  // state rows per slice: RW * D consecutive floats
+  constexpr int VPR = D / 4;                         // float4 per state row
+  constexpr int PER = MP * VPR / kReduceSlices;      // float4 per slice
   const int s = blockIdx.x, h = blockIdx.y, sl = blockIdx.z;
   const int c0 = seq_chunk_off[s], c1 = seq_chunk_off[s + 1];
   const int64_t u = static_cast<int64_t>(s) * g.H + h;
-  float* st = state + u * SL::kF32;
   uint16_t* opA = reinterpret_cast<uint16_t*>(ops + u * SL::kOpBytes);
   uint16_t* opB = opA + SL::kOpElems;
   float* zslot = reinterpret_cast<float*>(opB + SL::kOpElems);
-  for (int idx = threadIdx.x; idx < RW * D; idx += blockDim.x) {
-    const int m = sl * RW + idx / D, c = idx % D;
-    float a = 0.0f;
-    for (int ch = c0; ch < c1; ++ch)
-      a += partial[(static_cast<int64_t>(ch) * g.H + h) * partial_stride + m * D + c];
-    st[m * D + c] = a;
-    const int mg = m < 64 ? sm.g[m] : -1;
+  const float* base = partial + static_cast<int64_t>(h) * partial_stride;
+  const int64_t cstride = static_cast<int64_t>(g.H) * partial_stride;
+  auto sum_chunks = [&](const float* p0, auto& acc, auto load) {
+    int ch = c0;
+    for (; ch + 8 <= c1; ch += 8) {
+      decltype(load(p0)) v[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) v[k] = load(p0 + (ch + k) * cstride);
+#pragma unroll
+      for (int k = 0; k < 8; ++k) acc += v[k];
+    }
+    for (; ch < c1; ++ch) acc += load(p0 + ch * cstride);
+  };
+  for (int idx = threadIdx.x; idx < PER; idx += blockDim.x) {
+    const int v = sl * PER + idx;
+    const int m = v / VPR, c = (v % VPR) * 4;
+    f32x4 a;
+    a[0] = a[1] = a[2] = a[3] = 0.0f;
+    sum_chunks(base + m * D + c, a, [](const float* p) { return *reinterpret_cast<const f32x4*>(p); });
+    const int mg = SLOT_ROWS ? m / 32 : sm.g[m];
+    const int ms = SLOT_ROWS ? m % 32 : sm.s[m];
     if (mg >= 0) {
-      const int ms = sm.s[m];
-      const uint16_t bits = f32_to_bf16_bits(a);
-      {  // opA: channel c is the row, slot (mg, ms) the contraction index
-        const int rb = c / 32, r = c % 32, ks = ms / 8, j = ms % 8;
-        opA[((rb * (MP / 16) + ks) * 64 + 32 * mg + r) * 8 + j] = bits;
+      uint16_t bits[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) bits[e] = f32_to_bf16_bits(a[e]);
+      {  // opA: channel c+e is the row, slot (mg, ms) the contraction index
+        const int ks = ms / 8, j = ms % 8;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int rb = (c + e) / 32, r = (c + e) % 32;
+          opA[((rb * (MP / 16) + ks) * 64 + 32 * mg + r) * 8 + j] = bits[e];
+        }
       }
-      {  // opB: monomial row from (mg, ms), channel c the contraction index
+      {  // opB: monomial row from (mg, ms), channels c..c+3 the contraction index (4 consecutive j)
         const int rb = ms / 16, i = ms % 16;
         const int r = 8 * (i / 4) + 4 * mg + i % 4;
         const int ks = c / 16, gl = (c % 16) / 8, j = c % 8;
-        opB[((rb * (D / 16) + ks) * 64 + 32 * gl + r) * 8 + j] = bits;
+        u32x2 w;
+        w[0] = bits[0] | (static_cast<uint32_t>(bits[1]) << 16);
+        w[1] = bits[2] | (static_cast<uint32_t>(bits[3]) << 16);
+        *reinterpret_cast<u32x2*>(opB + ((rb * (D / 16) + ks) * 64 + 32 * gl + r) * 8 + j) = w;
       }
     }
   }
   if (sl == 0) {
     for (int m = threadIdx.x; m < MP; m += blockDim.x) {
       float a = 0.0f;
-      for (int ch = c0; ch < c1; ++ch)
-        a += partial[(static_cast<int64_t>(ch) * g.H + h) * partial_stride + MP * D + m];
-      st[MP * D + m] = a;
-      const int mg = m < 64 ? sm.g[m] : -1;
-      if (mg >= 0) zslot[mg * SP + sm.s[m]] = a;
+      sum_chunks(base + MP * D + m, a, [](const float* p) { return *p; });
+      const int mg = SLOT_ROWS ? m / 32 : sm.g[m];
+      const int ms = SLOT_ROWS ? m % 32 : sm.s[m];
+      if (mg >= 0) zslot[mg * SP + ms] = a;
     }
   }
 }
@@ -334,50 +359,41 @@ __global__ __launch_bounds__(kThreads) void k_query(Geom g, const BlockEnt* __re
   }
 }
 
-// Canonical monomial served by (g, slot); -1 for padding slots.
-struct CanonMap {
-  int8_t canon[2][32];
-};
-template <int DP>
-CanonMap make_canon_map() {
-  CanonMap cm{};
-  for (int g = 0; g < 2; ++g)
-    for (int s = 0; s < 32; ++s) cm.canon[g][s] = static_cast<int8_t>(sym3_slot_canon(DP, g, s));
-  return cm;
-}
-
 // ---- k_bwd_query ------------------------------------------------------------------------------
 template <int D>
 struct BwdQSmem {
-  static constexpr int kRow = D * 2 + 32;       // bytes per token row of the dO (-> g) and O tiles
-  static constexpr int kTile = 32 * kRow;
-  static constexpr int kQStride = 64 * 2 + 32;  // bytes per token row of the Qm tile (64 slot columns)
-  static constexpr int kQBytes = 32 * kQStride;
-  static constexpr int kWaveBytes = 2 * kTile + kQBytes;
+  static constexpr int kDoBytes = 32 * D * 2;   // dO tile [32 tokens][D] bf16, swizzled, unpadded
+  static constexpr int kQBytes = 32 * 128;      // scaled-monomial tile [32 tokens][64 slot columns] bf16
+  static constexpr int kWaveBytes = kDoBytes + kQBytes;
   static constexpr int kRedBytes = (64 * D + 64) * 4;
   static constexpr int kTotal = kWaves * kWaveBytes > kRedBytes ? kWaves * kWaveBytes : kRedBytes;
 };
 
-// grid (chunks, H), block 256.  Per 32-token tile and lane (token r, slot half gl):
-//   g = dO/den, s = -<dO,o>/den;  dM^T = Csym g^T (+ s z)  -> chain rule to d(phi_q) ;
-//   dCsym += Qm^T g (contraction over the tile's tokens), dzsym += s Qm.
-// The chunk's dCsym/dzsym are summed over the four waves in wave order and written as a partial
-// with canonical monomial rows.
+// grid (chunks, H), block 256.  Per 32-token tile and lane (token r, slot half gl), with
+// inv = 1/den and the raw upstream gradient rows dO as the operand of both contractions:
+//   X^T = Csym dO^T               (contraction over channels; dO loaded in B-operand order)
+//   s   = -inv^2 <Qm, X>          (= -<dO, o>/den, because o = Csym^T Qm / den: O is not re-read)
+//   dM  = inv X + s zsym   -> chain rule to d(phi_q)
+//   dCsym += (inv Qm)^T dO        (contraction over the tile's tokens: both operands through LDS
+//                                  with transpose reads),   dzsym += s Qm.
+// Taking s from the same X that feeds dM makes the component of dM along Qm cancel exactly, which
+// is where the query gradient loses its precision otherwise.  The chunk's dCsym/dzsym are summed
+// over the four waves in wave order and written as one partial whose row 32g + s is slot (g, s).
 template <int DP, int D>
 __global__ __launch_bounds__(kThreads) void k_bwd_query(
     Geom g, const BlockEnt* __restrict__ chunks, const float* __restrict__ feat,
-    const float* __restrict__ den, const unsigned char* __restrict__ ops, View dO, View O,
-    float* __restrict__ dfeat, float* __restrict__ partial, int64_t partial_stride, CanonMap cm) {
+    const float* __restrict__ den, const unsigned char* __restrict__ ops, View dO,
+    float* __restrict__ dfeat, float* __restrict__ partial, int64_t partial_stride) {
   using SY = Sym3<DP>;
   using SL = StateLayout<DP, D>;
   using SM = BwdQSmem<D>;
   constexpr int SP = SY::SP;
   constexpr int NCB = D / 32, NKD = D / 16;
+  constexpr int DROW = D * 2;  // bytes per dO tile row
   extern __shared__ __align__(16) unsigned char smem[];
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
-  unsigned char* gs = smem + wave * SM::kWaveBytes;
-  unsigned char* os = gs + SM::kTile;
-  unsigned char* qs = os + SM::kTile;
+  unsigned char* ds = smem + wave * SM::kWaveBytes;
+  unsigned char* qs = ds + SM::kDoBytes;
   const BlockEnt e = chunks[blockIdx.x];
   const int h = blockIdx.y;
   const int r = lane % 32, gl = lane / 32;
@@ -392,7 +408,30 @@ __global__ __launch_bounds__(kThreads) void k_bwd_query(
     for (int ks = 0; ks < NKD; ++ks) a_mo[rb][ks] = opB[(rb * NKD + ks) * 64 + lane];
   float z[SP];
 #pragma unroll
-  for (int s = 0; s < SP; ++s) z[s] = zslot[s];
+  for (int s4 = 0; s4 < SP / 4; ++s4) {
+    const f32x4 v = *reinterpret_cast<const f32x4*>(zslot + 4 * s4);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) z[4 * s4 + i] = v[i];
+  }
+  // per-lane LDS offsets: own-row writes, and transpose reads of token rows 8gl + L/4 (+4) at the
+  // 4 columns 32x + 16(q%2) + 4(L%4) ..+3 (x = row block of Qm^T or column block of dO)
+  int dw_off[NKD];
+#pragma unroll
+  for (int ks = 0; ks < NKD; ++ks) dw_off[ks] = tile_off<DROW>(r, 2 * ks + gl);
+  int qw_off[SP / 8];
+#pragma unroll
+  for (int p4 = 0; p4 < SP / 8; ++p4) qw_off[p4] = tile_off<128>(r, 4 * gl + p4);
+  int qa_off[2][2], db_off[2][NCB];
+#pragma unroll
+  for (int hi = 0; hi < 2; ++hi) {
+    const int row = 8 * gl + 4 * hi + L / 4;
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+      qa_off[hi][rb] = tile_off<128>(row, 4 * rb + 2 * (q % 2) + (L % 4) / 2) + (L % 2) * 8;
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb)
+      db_off[hi][cb] = tile_off<DROW>(row, 4 * cb + 2 * (q % 2) + (L % 4) / 2) + (L % 2) * 8;
+  }
 
   f32x16 dC[2][NCB];
 #pragma unroll
@@ -405,49 +444,56 @@ __global__ __launch_bounds__(kThreads) void k_bwd_query(
 #pragma unroll
   for (int s = 0; s < SP; ++s) dzacc[s] = 0.0f;
 
-  for (int n0 = e.t0 + wave * 32; n0 < e.t1; n0 += kWaves * 32) {
-    stage_tile32<D>(dO, e.b, h, n0, e.t1, lane, gs, SM::kRow);
-    stage_tile32<D>(O, e.b, h, n0, e.t1, lane, os, SM::kRow);
-    wave_lds_sync();
+  // one tile's inputs: the dO row pieces (B operand, k-slot (ks, gl, j) = channel 16ks + 8gl + j),
+  // the query features of this lane's half (gl = 1: reversed) and the denominator
+  u32x4 xb[NKD], xn[NKD];
+  float2 fb[DP / 2], fn[DP / 2];
+  float denb = 1.0f, denn = 1.0f;
+  auto fetch = [&](int n0, u32x4(&x)[NKD], float2(&f)[DP / 2], float& dn) {
+    const int n = n0 + r;
+    if (n < e.t1) {
+      const bf16_t* row = dO.row<const bf16_t>(e.b, h, n);
+#pragma unroll
+      for (int ks = 0; ks < NKD; ++ks) x[ks] = *reinterpret_cast<const u32x4*>(row + 16 * ks + 8 * gl);
+      const int64_t th = g.th(e.b, h, n);
+      const float2* fp = reinterpret_cast<const float2*>(feat + th * g.nfeat);
+#pragma unroll
+      for (int a = 0; a < DP / 2; ++a) f[a] = fp[a];
+      dn = den[th];
+    } else {
+#pragma unroll
+      for (int ks = 0; ks < NKD; ++ks) x[ks][0] = x[ks][1] = x[ks][2] = x[ks][3] = 0u;
+#pragma unroll
+      for (int a = 0; a < DP / 2; ++a) f[a].x = f[a].y = 0.0f;
+      dn = 1.0f;
+    }
+  };
+  int n0 = e.t0 + wave * 32;
+  if (n0 < e.t1) fetch(n0, xb, fb, denb);
+  for (; n0 < e.t1; n0 += kWaves * 32) {
     const int n = n0 + r;
     const bool live = n < e.t1;
     const int64_t th = g.th(e.b, h, live ? n : e.t0);
-    const float inv = live ? 1.0f / den[th] : 0.0f;
-    u32x4 dov[NKD];
-    float dot = 0.0f;
+    if (n0 + kWaves * 32 < e.t1) fetch(n0 + kWaves * 32, xn, fn, denn);
+    // dO tile for the token contraction, X^T = Csym dO^T on the matrix pipe
 #pragma unroll
-    for (int ks = 0; ks < NKD; ++ks) {
-      dov[ks] = *reinterpret_cast<const u32x4*>(gs + r * SM::kRow + (16 * ks + 8 * gl) * 2);
-      const u32x4 ov = *reinterpret_cast<const u32x4*>(os + r * SM::kRow + (16 * ks + 8 * gl) * 2);
-#pragma unroll
-      for (int p = 0; p < 4; ++p)
-        dot += bf16_lo(dov[ks][p]) * bf16_lo(ov[p]) + bf16_hi(dov[ks][p]) * bf16_hi(ov[p]);
-    }
-    dot += partner32(dot);
-    const float si = -dot * inv;
-    f32x16 dM[2];
+    for (int ks = 0; ks < NKD; ++ks) *reinterpret_cast<u32x4*>(ds + dw_off[ks]) = xb[ks];
+    f32x16 X[2];
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) dM[rb][i] = 0.0f;
+      for (int i = 0; i < 16; ++i) X[rb][i] = 0.0f;
 #pragma unroll
-    for (int ks = 0; ks < NKD; ++ks) {
-      u32x4 gv;
+    for (int ks = 0; ks < NKD; ++ks)
 #pragma unroll
-      for (int p = 0; p < 4; ++p)
-        gv[p] = pack_bf16(bf16_lo(dov[ks][p]) * inv, bf16_hi(dov[ks][p]) * inv);
-      *reinterpret_cast<u32x4*>(gs + r * SM::kRow + (16 * ks + 8 * gl) * 2) = gv;  // dO tile becomes g tile
-#pragma unroll
-      for (int rb = 0; rb < 2; ++rb) dM[rb] = mfma32(a_mo[rb][ks], gv, dM[rb]);
-    }
+      for (int rb = 0; rb < 2; ++rb) X[rb] = mfma32(a_mo[rb][ks], xb[ks], X[rb]);
+    // monomials of this lane's slots and their scaled bf16 copy (a row of the A^T tile)
+    const float inv = live ? 1.0f / denb : 0.0f;
     float qf[DP];
-    if (live) {
-      const float* f = feat + th * g.nfeat;
 #pragma unroll
-      for (int c = 0; c < DP; ++c) qf[c] = f[gl ? DP - 1 - c : c];
-    } else {
-#pragma unroll
-      for (int c = 0; c < DP; ++c) qf[c] = 0.0f;
+    for (int c = 0; c < DP; ++c) {
+      const int cc = gl ? DP - 1 - c : c;
+      qf[c] = cc % 2 ? fb[cc / 2].y : fb[cc / 2].x;
     }
     float qm[SP];
     query_monomials<DP>(qf, qm);
@@ -455,19 +501,24 @@ __global__ __launch_bounds__(kThreads) void k_bwd_query(
     for (int p4 = 0; p4 < SP / 8; ++p4) {
       u32x4 w;
 #pragma unroll
-      for (int p = 0; p < 4; ++p) {
-        const int s = 8 * p4 + 2 * p;
-        w[p] = pack_bf16(qm[s], qm[s + 1]);
-        dzacc[s] += si * bf16_lo(w[p]);
-        dzacc[s + 1] += si * bf16_hi(w[p]);
-      }
-      *reinterpret_cast<u32x4*>(qs + r * SM::kQStride + (32 * gl + 8 * p4) * 2) = w;
+      for (int p = 0; p < 4; ++p) w[p] = pack_bf16(qm[8 * p4 + 2 * p] * inv, qm[8 * p4 + 2 * p + 1] * inv);
+      *reinterpret_cast<u32x4*>(qs + qw_off[p4]) = w;
     }
+    float dot = 0.0f;
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) dot += qm[16 * rb + i] * X[rb][i];
+    dot += partner32(dot);
+    const float si = -(inv * inv) * dot;
     float dm[SP];
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) dm[16 * rb + i] = dM[rb][i] + si * z[16 * rb + i];
+      for (int i = 0; i < 16; ++i) {
+        dm[16 * rb + i] = inv * X[rb][i] + si * z[16 * rb + i];
+        dzacc[16 * rb + i] += si * qm[16 * rb + i];
+      }
     float dq[DP];
 #pragma unroll
     for (int c = 0; c < DP; ++c) dq[c] = 0.0f;
@@ -476,20 +527,20 @@ __global__ __launch_bounds__(kThreads) void k_bwd_query(
 #pragma unroll
     for (int c = 0; c < DP; ++c) other[c] = partner32(dq[c]);
     if (live && gl == 0) {
+      float2* df = reinterpret_cast<float2*>(dfeat + th * g.nfeat);
 #pragma unroll
-      for (int c = 0; c < DP; ++c) dfeat[th * g.nfeat + c] = dq[c] + other[DP - 1 - c];
+      for (int c = 0; c < DP; c += 2)
+        df[c / 2] = make_float2(dq[c] + other[DP - 1 - c], dq[c + 1] + other[DP - 2 - c]);
     }
     wave_lds_sync();
-    // dCsym[(g,s) rows x D] += Qm^T[64 x 32 tokens] g[32 tokens x D]
+    // dCsym[(g,s) rows x D] += (inv Qm)^T[64 x 32 tokens] dO[32 tokens x D]
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) {
-      const int krow = 16 * ks + 8 * gl + L / 4;
       u32x4 a[2];
 #pragma unroll
       for (int rb = 0; rb < 2; ++rb) {
-        const unsigned char* p = qs + krow * SM::kQStride + (32 * rb + 16 * (q % 2) + 4 * (L % 4)) * 2;
-        const u32x2 lo = lds_read_tr16(p);
-        const u32x2 hi = lds_read_tr16(p + 4 * SM::kQStride);
+        const u32x2 lo = lds_read_tr16(qs + ks * 16 * 128 + qa_off[0][rb]);
+        const u32x2 hi = lds_read_tr16(qs + ks * 16 * 128 + qa_off[1][rb]);
         a[rb][0] = lo[0];
         a[rb][1] = lo[1];
         a[rb][2] = hi[0];
@@ -497,9 +548,8 @@ __global__ __launch_bounds__(kThreads) void k_bwd_query(
       }
 #pragma unroll
       for (int cb = 0; cb < NCB; ++cb) {
-        const unsigned char* p = gs + krow * SM::kRow + (32 * cb + 16 * (q % 2) + 4 * (L % 4)) * 2;
-        const u32x2 lo = lds_read_tr16(p);
-        const u32x2 hi = lds_read_tr16(p + 4 * SM::kRow);
+        const u32x2 lo = lds_read_tr16(ds + ks * 16 * DROW + db_off[0][cb]);
+        const u32x2 hi = lds_read_tr16(ds + ks * 16 * DROW + db_off[1][cb]);
         u32x4 b;
         b[0] = lo[0];
         b[1] = lo[1];
@@ -510,6 +560,11 @@ __global__ __launch_bounds__(kThreads) void k_bwd_query(
       }
     }
     wave_lds_sync();
+#pragma unroll
+    for (int ks = 0; ks < NKD; ++ks) xb[ks] = xn[ks];
+#pragma unroll
+    for (int a = 0; a < DP / 2; ++a) fb[a] = fn[a];
+    denb = denn;
   }
   // dz: sum over the 32 token lanes of each half
 #pragma unroll
@@ -519,36 +574,35 @@ __global__ __launch_bounds__(kThreads) void k_bwd_query(
     for (int m = 1; m < 32; m <<= 1) v += __shfl_xor(v, m, 64);
     dzacc[s] = v;
   }
+  // sum the four waves in wave order: row 32rb + d_row(i, gl) of the accumulators is column
+  // 32g' + s' of the monomial tile, i.e. slot (g', s')
   float* red = reinterpret_cast<float*>(smem);
-  __syncthreads();
-  for (int i = threadIdx.x; i < 64 * D + 64; i += kThreads) red[i] = 0.0f;
   for (int w = 0; w < kWaves; ++w) {
     __syncthreads();
     if (wave == w) {
 #pragma unroll
-      for (int rb = 0; rb < 2; ++rb) {
+      for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-          const int row = 32 * rb + d_row(i, gl);  // = 32 g' + s' : column of the Qm tile
-          const int m = cm.canon[row / 32][row % 32];
-          if (m >= 0) {
+          const int row = 32 * rb + d_row(i, gl);
 #pragma unroll
-            for (int cb = 0; cb < NCB; ++cb) red[m * D + 32 * cb + r] += dC[rb][cb][i];
+          for (int cb = 0; cb < NCB; ++cb) {
+            float* p = red + row * D + 32 * cb + r;
+            *p = (w == 0 ? 0.0f : *p) + dC[rb][cb][i];
           }
         }
-      }
       if (r == 0) {
 #pragma unroll
         for (int s = 0; s < SP; ++s) {
-          const int m = cm.canon[gl][s];
-          if (m >= 0) red[64 * D + m] += dzacc[s];
+          float* p = red + 64 * D + 32 * gl + s;
+          *p = (w == 0 ? 0.0f : *p) + dzacc[s];
         }
       }
     }
   }
   __syncthreads();
-  float* out = partial + (static_cast<int64_t>(blockIdx.x) * g.H + h) * partial_stride;
-  for (int i = threadIdx.x; i < 64 * D + 64; i += kThreads) out[i] = red[i];
+  f32x4* out = reinterpret_cast<f32x4*>(partial + (static_cast<int64_t>(blockIdx.x) * g.H + h) * partial_stride);
+  for (int i = threadIdx.x; i < (64 * D + 64) / 4; i += kThreads) out[i] = reinterpret_cast<const f32x4*>(red)[i];
 }
 
 // ---- k_bwd_key --------------------------------------------------------------------------------
@@ -736,10 +790,10 @@ hla_status backward_core(hla_handle* hd, const hla_call_args& a) {
   unsigned char* ops = static_cast<unsigned char*>(hd->path_ws);
   unsigned char* dops = ops + SL::kOpBytes * hd->max_units;
   HLA_TRY(launch(hd, "mfma_bwd_query", k_bwd_query<DP, D>, dim3(chunks->count, g.H), dim3(kThreads),
-                 BwdQSmem<D>::kTotal, s, g, chunks->dev, hd->feat, hd->den, ops, a.dO, a.O, hd->dfeat,
-                 hd->partial, SL::kF32, make_canon_map<DP>()));
-  HLA_TRY(launch(hd, "mfma_dstate_reduce", k_reduce<DP, D>, dim3(a.num_seqs, g.H, kReduceSlices),
-                 dim3(256), 0, s, g, chunks->seq_off_dev, hd->partial, SL::kF32, hd->dstate, dops,
+                 BwdQSmem<D>::kTotal, s, g, chunks->dev, hd->feat, hd->den, ops, a.dO, hd->dfeat,
+                 hd->partial, SL::kF32));
+  HLA_TRY(launch(hd, "mfma_dstate_reduce", k_reduce<DP, D, true>, dim3(a.num_seqs, g.H, kReduceSlices),
+                 dim3(256), 0, s, g, chunks->seq_off_dev, hd->partial, SL::kF32, dops,
                  make_slot_map<DP>()));
   HLA_TRY(launch(hd, "mfma_bwd_key", k_bwd_key<DP, D>, dim3(chunks->count, g.H), dim3(kThreads),
                  0, s, g, chunks->dev, hd->feat, dops, a.V, hd->dfeat, a.dV));
@@ -768,8 +822,8 @@ hla_status forward_core(hla_handle* hd, const hla_call_args& a) {
                  SM::kTotal, s, g, chunks->dev, hd->feat, a.V, hd->partial, SL::kF32));
   const SlotMap sm = make_slot_map<DP>();
   unsigned char* ops = static_cast<unsigned char*>(hd->path_ws);
-  HLA_TRY(launch(hd, "mfma_state_reduce", k_reduce<DP, D>, dim3(a.num_seqs, g.H, kReduceSlices),
-                 dim3(256), 0, s, g, chunks->seq_off_dev, hd->partial, SL::kF32, hd->state, ops, sm));
+  HLA_TRY(launch(hd, "mfma_state_reduce", k_reduce<DP, D, false>, dim3(a.num_seqs, g.H, kReduceSlices),
+                 dim3(256), 0, s, g, chunks->seq_off_dev, hd->partial, SL::kF32, ops, sm));
   HLA_TRY(launch(hd, "mfma_query", k_query<DP, D>, dim3(qblocks->count, g.H), dim3(kThreads), 0, s,
                  g, qblocks->dev, hd->feat, ops, a.O, hd->den));
   return HLA_OK;

@@ -66,6 +66,20 @@ __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// ---- swizzled LDS tiles --------------------------------------------------------------------------
+// A [rows][ROWB bytes] tile (ROWB = 256 or 128) whose 16-byte chunks are XOR-swizzled by a function
+// of the row, so that both access patterns the kernels use are bank-conflict free without padding:
+// 16-byte accesses of 16 consecutive rows at one chunk, and transpose reads of 4 consecutive rows
+// (starting at a multiple of 4) x 4 consecutive chunks (starting at a multiple of 4).
+template <int ROWB>
+__host__ __device__ __forceinline__ int tile_swz(int row) {
+  return ROWB == 256 ? (((row & 3) << 2) | ((row >> 2) & 3)) : ((((row >> 1) & 1) << 2) | ((row >> 2) & 3));
+}
+template <int ROWB>
+__host__ __device__ __forceinline__ int tile_off(int row, int chunk) {
+  return row * ROWB + (((chunk ^ tile_swz<ROWB>(row)) & (ROWB / 16 - 1)) << 4);
+}
+
 // value held by the lane 32 away (the other half of a (token, g) lane pair)
 __device__ __forceinline__ float partner32(float v) { return __shfl_xor(v, 32, 64); }
 
