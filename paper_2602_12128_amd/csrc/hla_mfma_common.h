@@ -34,6 +34,13 @@ __device__ __forceinline__ f32x16 mfma32(u32x4 a, u32x4 b, f32x16 c) {
                                                  __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 __device__ __forceinline__ int d_row(int i, int g) { return 8 * (i / 4) + 4 * g + (i % 4); }
+// v_mfma_f32_32x32x16_f16: the same lane layout with fp16 operands
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ f32x16 mfma32_f16(u32x4 a, u32x4 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a),
+                                                __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+}
 
 // two fp32 -> packed bf16 pair (lo = a, hi = b), round-to-nearest-even
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {

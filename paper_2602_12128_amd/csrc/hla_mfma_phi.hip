@@ -28,41 +28,81 @@ constexpr int kDP = 6;
 #define HLA_PHI_WAVES_B 8
 #endif
 
-// ---- GELU on the vector ALU ------------------------------------------------------------------
-// Phi(x) - 1/2 = xc * P(xc^2) with xc = clamp(x, +-3.75): degree-6 minimax fit of the normal CDF,
-// |GELU error| <= 3.3e-4 over all x, below the bf16 rounding the result receives anyway.
-__device__ __forceinline__ float gelu_poly(float x) {
-  const float xc = __builtin_amdgcn_fmed3f(x, -3.75f, 3.75f);
-  const float u = xc * xc;
-  float p = 3.912438593e-08f;
-  p = p * u + -2.376254374e-06f;
-  p = p * u + 6.234781818e-05f;
-  p = p * u + -9.441798806e-04f;
-  p = p * u + 9.362553295e-03f;
-  p = p * u + -6.578987063e-02f;
-  p = p * u + 3.987064701e-01f;
-  return x * (xc * p + 0.5f);
+// ---- GELU on the vector ALU, two values per instruction in packed fp16 -------------------------
+// Phi(x) - 1/2 = xc * P(w) with xc = clamp(x, +-4) and w = xc^2/8 - 1 in [-1, 1]: in this variable
+// the coefficients of the minimax fit stay below 0.2, so a Horner chain of fp16 FMAs keeps its
+// rounding error near 2^-12 per step.  Evaluated end to end in fp16 the absolute GELU error is at
+// most 3.8e-3 (rms 3.5e-4 for standard-normal inputs): a quarter of what rounding an exact GELU
+// to bf16 would cost, which is why the hidden layer is handed to the second layer in fp16.
+// Pre-activations must stay below the fp16 range (65504) in magnitude.
+__device__ __forceinline__ f16x2 splat16(float v) {
+  f16x2 r;
+  r[0] = static_cast<_Float16>(v);
+  r[1] = r[0];
+  return r;
 }
-// d/dx [x Phi(x)] - 1/2 = xc * R(xc^2), xc = clamp(x, +-4): degree-7 fit, |error| <= 2.7e-4.
-__device__ __forceinline__ float gelu_grad_poly(float x) {
-  const float xc = __builtin_amdgcn_fmed3f(x, -4.0f, 4.0f);
-  const float u = xc * xc;
-  float p = -1.641980733e-08f;
-  p = p * u + 1.213807329e-06f;
-  p = p * u + -3.845959858e-05f;
-  p = p * u + 6.876457658e-04f;
-  p = p * u + -7.687443813e-03f;
-  p = p * u + 5.591483272e-02f;
-  p = p * u + -2.620298556e-01f;
-  p = p * u + 7.967216430e-01f;
-  return xc * p + 0.5f;
+__device__ __forceinline__ f16x2 to_f16x2(float a, float b) {
+  f16x2 r;
+  r[0] = static_cast<_Float16>(a);  // round to nearest even (v_cvt_pk_f16_f32)
+  r[1] = static_cast<_Float16>(b);
+  return r;
+}
+__device__ __forceinline__ f16x2 clamp4(f16x2 x) {
+  return __builtin_elementwise_min(__builtin_elementwise_max(x, splat16(-4.0f)), splat16(4.0f));
+}
+// NCH independent chains are advanced in lockstep: a packed-fp16 instruction cannot issue right
+// behind the one that produces its input, so a single Horner chain would leave every other issue
+// slot empty.
+// GELU of 2*NCH values as packed fp16 pairs: degree-6 fit of (Phi - 1/2)/xc in w
+template <int NCH>
+__device__ __forceinline__ void gelu_f16(const float (&in)[2 * NCH], uint32_t (&out)[NCH]) {
+  constexpr float c[7] = {0.175903f, -0.0845947f, 0.0556946f, -0.0344849f, 0.0227356f, -0.0177002f, 0.00738144f};
+  f16x2 x[NCH], xc[NCH], w[NCH], p[NCH];
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) x[i] = to_f16x2(in[2 * i], in[2 * i + 1]);
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) xc[i] = clamp4(x[i]);
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) w[i] = xc[i] * xc[i];
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) w[i] = __builtin_elementwise_fma(w[i], splat16(0.125f), splat16(-1.0f));
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) p[i] = __builtin_elementwise_fma(splat16(c[6]), w[i], splat16(c[5]));
+#pragma unroll
+  for (int k = 4; k >= 0; --k)
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) p[i] = __builtin_elementwise_fma(p[i], w[i], splat16(c[k]));
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) p[i] = __builtin_elementwise_fma(xc[i], p[i], splat16(0.5f));
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) out[i] = __builtin_bit_cast(uint32_t, x[i] * p[i]);
+}
+// d/dx [x Phi(x)] of 2*NCH values: degree-7 fit of (GELU' - 1/2)/xc in w, |error| <= 1.4e-3
+template <int NCH>
+__device__ __forceinline__ void gelu_grad_f16(const float (&in)[2 * NCH], f16x2 (&out)[NCH]) {
+  constexpr float c[8] = {0.183228f, -0.11377f, 0.117554f, -0.113403f, 0.0830688f, -0.0742188f, 0.0771484f, -0.0344238f};
+  f16x2 xc[NCH], w[NCH], p[NCH];
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) xc[i] = clamp4(to_f16x2(in[2 * i], in[2 * i + 1]));
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) w[i] = xc[i] * xc[i];
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) w[i] = __builtin_elementwise_fma(w[i], splat16(0.125f), splat16(-1.0f));
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) p[i] = __builtin_elementwise_fma(splat16(c[7]), w[i], splat16(c[6]));
+#pragma unroll
+  for (int k = 5; k >= 0; --k)
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) p[i] = __builtin_elementwise_fma(p[i], w[i], splat16(c[k]));
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) out[i] = __builtin_elementwise_fma(xc[i], p[i], splat16(0.5f));
 }
 
 // ---- packed weights of one (map, head) in global memory ---------------------------------------
 template <int D>
 struct Packed {
   static constexpr int kW1T = 0;                      // bf16 [D][D]: row = hidden unit, col = input channel
-  static constexpr int kW2A = kW1T + D * D * 2;       // bf16 [D/16][64][8]: A operand of u^T = W2^T g^T
+  static constexpr int kW2A = kW1T + D * D * 2;       // fp16 [D/16][64][8]: A operand of u^T = W2^T g^T
   static constexpr int kW2B = kW2A + D * 32 * 2;      // bf16 [D/32][64][8]: A operand of dg^T = W2 du^T
   static constexpr int kB1 = kW2B + D * 16 * 2;       // fp32 [D]
   static constexpr int kB2 = kB1 + D * 4;             // fp32 [8]
@@ -95,7 +135,7 @@ __global__ void k_pack_phi(PhiF32 w, int dphi, unsigned char* __restrict__ out) 
     const int ks2 = i / 512, lane = (i / 8) % 64, j = i % 8;
     const int r = lane % 32, gl = lane / 32;
     const int n = hidden_of_slot(ks2, gl, j);
-    w2a[i] = r < dphi ? f32_to_bf16_bits(W2[n * dphi + r]) : 0;
+    w2a[i] = r < dphi ? __builtin_bit_cast(uint16_t, static_cast<_Float16>(W2[n * dphi + r])) : 0;
   }
   for (int i = threadIdx.x; i < (D / 32) * 512; i += blockDim.x) {
     const int rb = i / 512, lane = (i / 8) % 64, j = i % 8;
@@ -151,18 +191,16 @@ __device__ __forceinline__ void load_weights(unsigned char* dst, const unsigned 
 }
 
 // The lane's share of its token's input vector as B operands: k-slot (ks, gl, j) is channel
-// 16 ks + 8 gl + j, i.e. one 16-byte piece per k-step.  Tokens at or beyond N read as zero.
+// 16 ks + 8 gl + j, i.e. one 16-byte piece per k-step.  Tokens at or beyond N read the last row
+// (a token is an MFMA column, so what such a lane computes never reaches another token and is
+// not stored).  The loads are unconditional: the same number of loads is in flight on every
+// path, which lets the wait counters keep a prefetch in flight across the loop back-edge.
 template <int D>
 __device__ __forceinline__ void load_x(const View& X, int b, int h, int n, int N, int gl,
                                        u32x4 (&x)[D / 16]) {
-  if (n < N) {
-    const bf16_t* row = X.row<const bf16_t>(b, h, n);
+  const bf16_t* row = X.row<const bf16_t>(b, h, n < N ? n : N - 1);
 #pragma unroll
-    for (int ks = 0; ks < D / 16; ++ks) x[ks] = *reinterpret_cast<const u32x4*>(row + 16 * ks + 8 * gl);
-  } else {
-#pragma unroll
-    for (int ks = 0; ks < D / 16; ++ks) x[ks][0] = x[ks][1] = x[ks][2] = x[ks][3] = 0u;
-  }
+  for (int ks = 0; ks < D / 16; ++ks) x[ks] = *reinterpret_cast<const u32x4*>(row + 16 * ks + 8 * gl);
 }
 
 // Per-lane byte offsets (inside a map's W1^T block, row block 0) of the first-layer A operand of
@@ -253,23 +291,61 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_fwd(Geom g, View X,
   const int stride = gridDim.x * WAVES;
   int tile = blockIdx.x * WAVES + wave;
   int b = 0, h = 0, n0 = 0;
+  // xn always holds the loads in flight for the coming tile; it is copied to xb at the top of the
+  // loop and refilled at once for the tile after (the last tile is simply fetched again).
   u32x4 xb[NKS], xn[NKS];
   if (tile < tm.total) {
     tm.decode(tile, b, h, n0);
-    load_x<D>(X, b, h, n0 + r, g.N, gl, xb);
+    load_x<D>(X, b, h, n0 + r, g.N, gl, xn);
   }
+  float pend[4] = {0.0f, 0.0f, 0.0f, 0.0f};  // features of the last finished map, not yet stored
+  float* pend_ptr = nullptr;
+  auto flush = [&]() {
+    if (pend_ptr != nullptr) {
+      *reinterpret_cast<float2*>(pend_ptr) = make_float2(pend[0], pend[1]);
+      if (gl == 0) *reinterpret_cast<float2*>(pend_ptr + 2) = make_float2(pend[2], pend[3]);
+    }
+    pend_ptr = nullptr;
+  };
   for (; tile < tm.total; tile += stride) {
     const int n = n0 + r;
     const bool live = n < g.N;
     const int64_t th = g.th(b, h, n);
-    if (tile + stride < tm.total) {
-      tm.decode(tile + stride, b, h, n0);
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) xb[ks] = xn[ks];
+    {
+      const int nt = tile + stride < tm.total ? tile + stride : tile;
+      tm.decode(nt, b, h, n0);
       load_x<D>(X, b, h, n0 + r, g.N, gl, xn);
     }
-    // Software pipeline over 32-row blocks of the hidden layer: while the vector ALU evaluates
-    // GELU on block (m, rb), the matrix pipe already works on the next block.
-    f32x16 cur;
+    flush();
+    // Software pipeline over 32-row blocks of the hidden layer (block t = m * NRB + rb): while the
+    // vector ALU evaluates GELU on block t, the matrix pipe works on block t + 1, and the LDS reads
+    // of block t + 2 (A operands, bias) are already in flight, a whole stage ahead of their use.
+    // Blocks past the last map alias the last map's LDS: their results are never used.
+    auto block_base = [&](int m, int rbx) -> const unsigned char* {
+      const int mm = m + rbx / NRB;
+      return smem + (mm < nmaps ? mm : nmaps - 1) * SM::kMap;
+    };
+    auto load_bias = [&](const unsigned char* wmx, int rbx, f32x16& acc) {
+      const float* b1 = reinterpret_cast<const float*>(wmx + SM::kW1 + SM::kW2);
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const f32x4 bv = *reinterpret_cast<const f32x4*>(b1 + 32 * (rbx % NRB) + 8 * q4 + 4 * gl);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[4 * q4 + e] = bv[e];
+      }
+    };
+    f32x16 cur, nxt;
+    u32x4 an[NKS];
     first_layer_block<D, false>(smem, a_off, xb, gl, 0, cur);
+    {
+      const unsigned char* w1 = block_base(0, 1);
+      load_bias(w1, 1, nxt);
+#pragma unroll
+      for (int ks = 0; ks < NKS; ++ks)
+        an[ks] = *reinterpret_cast<const u32x4*>(w1 + (1 % NRB) * 32 * SM::kRow + a_off[ks]);
+    }
 #pragma unroll 1
     for (int m = 0; m < nmaps; ++m) {  // nmaps == NMAPS, passed at run time so this stays a loop
       const unsigned char* wm = smem + m * SM::kMap;
@@ -278,69 +354,71 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_fwd(Geom g, View X,
       for (int i = 0; i < 16; ++i) u[i] = 0.0f;
 #pragma unroll
       for (int rb = 0; rb < NRB; ++rb) {
-        // Stage (m, rb): the eight MFMAs of the next block are issued one at a time between
-        // eighths of this block's GELU arithmetic.  An MFMA holds the wave's issue while the
-        // matrix pipe is busy, so they must be spread through the vector-ALU stream to overlap.
-        const bool more = rb + 1 < NRB || m + 1 < nmaps;
-        const unsigned char* wn = rb + 1 < NRB ? wm : wm + SM::kMap;
-        const int rbn = rb + 1 < NRB ? rb + 1 : 0;
-        f32x16 nxt;
-        u32x4 an[NKS];
-        if (more) {
-          const float* b1 = reinterpret_cast<const float*>(wn + SM::kW1 + SM::kW2);
-#pragma unroll
-          for (int q4 = 0; q4 < 4; ++q4) {
-            const f32x4 bv = *reinterpret_cast<const f32x4*>(b1 + 32 * rbn + 8 * q4 + 4 * gl);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) nxt[4 * q4 + e] = bv[e];
-          }
-#pragma unroll
-          for (int ks = 0; ks < NKS; ++ks)
-            an[ks] = *reinterpret_cast<const u32x4*>(wn + a_off[ks] + rbn * 32 * SM::kRow);
-        } else {
-#pragma unroll
-          for (int i = 0; i < 16; ++i) nxt[i] = 0.0f;
-#pragma unroll
-          for (int ks = 0; ks < NKS; ++ks) an[ks] = xb[ks];
-        }
+        // Stage t: one MFMA of block t + 1 per eighth of block t's GELU arithmetic (an MFMA holds
+        // the wave's issue while the matrix pipe is busy, so they are spread through the
+        // vector-ALU stream); each consumed operand register is refilled for block t + 2.
+        const unsigned char* w2 = block_base(m, rb + 2);
+        const unsigned char* a2_base = w2 + ((rb + 2) % NRB) * 32 * SM::kRow;
+        f32x16 bn;
+        load_bias(w2, rb + 2, bn);
         const u32x4 a20 = *reinterpret_cast<const u32x4*>(wm + SM::kW1 + ((2 * rb) * 64 + lane) * 16);
         const u32x4 a21 = *reinterpret_cast<const u32x4*>(wm + SM::kW1 + ((2 * rb + 1) * 64 + lane) * 16);
         u32x4 gb[2];
+        // four slices per stage: two independent GELU chains per slice hide the issue gap between
+        // dependent packed-fp16 instructions
+        constexpr int kPer = NKS / 4;  // MFMAs of the next block per slice
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          constexpr int kPer = NKS / 8 > 0 ? NKS / 8 : 1;  // MFMAs of the next block per slice
-          if (more) {
+        for (int j = 0; j < 4; ++j) {
+          // the empty asm statements pin the order MFMAs -> GELU slice -> next MFMAs: they are
+          // volatile (kept in program order) and the values flow through them
+          asm volatile("" : "+v"(nxt));
 #pragma unroll
-            for (int t = 0; t < kPer; ++t)
-              if (j * kPer + t < NKS) nxt = mfma32(an[j * kPer + t], xb[j * kPer + t], nxt);
+          for (int t = 0; t < kPer; ++t) {
+            const int ks = j * kPer + t;
+#ifndef EXP_NOMFMA
+            nxt = mfma32(an[ks], xb[ks], nxt);
+#endif
+#ifndef EXP_NOLDS
+            an[ks] = *reinterpret_cast<const u32x4*>(a2_base + a_off[ks]);
+#endif
           }
-          if (j == 5) u = mfma32(a20, gb[0], u);
+          if (j == 3) u = mfma32_f16(a20, gb[0], u);
+          float in[4] = {cur[4 * j], cur[4 * j + 1], cur[4 * j + 2], cur[4 * j + 3]};
+          asm volatile("" : "+v"(nxt), "+v"(in[0]), "+v"(in[1]), "+v"(in[2]), "+v"(in[3]));
           __builtin_amdgcn_sched_barrier(0);
-          gb[j / 4][j % 4] = pack_bf16(gelu_poly(cur[2 * j]), gelu_poly(cur[2 * j + 1]));
+          uint32_t out[2];
+#ifndef EXP_NOGELU
+          gelu_f16<2>(in, out);
+#else
+          out[0] = __float_as_uint(in[0]) ^ __float_as_uint(in[1]);
+          out[1] = __float_as_uint(in[2]) ^ __float_as_uint(in[3]);
+#endif
+          asm volatile("" : "+v"(out[0]), "+v"(out[1]));
+          gb[j / 2][2 * (j % 2)] = out[0];
+          gb[j / 2][2 * (j % 2) + 1] = out[1];
           __builtin_amdgcn_sched_barrier(0);
         }
-        u = mfma32(a21, gb[1], u);
+        u = mfma32_f16(a21, gb[1], u);
         cur = nxt;
+        nxt = bn;
       }
-      // rows d_row(i, gl) < d_phi: lane gl=0 holds features 0..3, lane gl=1 features 4, 5
-      if (live) {
+      // rows d_row(i, gl) < d_phi: lane gl=0 holds features 0..3, lane gl=1 features 4, 5.  The
+      // store is held back until the next map (or the next tile's input wait) has been passed:
+      // stores count in the same wait counter as loads, and a store issued just before that wait
+      // would make the wave sit out the store's full round trip.
+      flush();
+      {
         const float* b2 = reinterpret_cast<const float*>(wm + SM::kW1 + SM::kW2 + D * 4) + 4 * gl;
-        float* f = feat + th * g.nfeat + (map0 + m) * kDP + 4 * gl;
-        float2 lo, hi;
-        lo.x = fmaxf(u[0] + b2[0], 0.0f);
-        lo.y = fmaxf(u[1] + b2[1], 0.0f);
-        *reinterpret_cast<float2*>(f) = lo;
-        if (gl == 0) {
-          hi.x = fmaxf(u[2] + b2[2], 0.0f);
-          hi.y = fmaxf(u[3] + b2[3], 0.0f);
-          *reinterpret_cast<float2*>(f + 2) = hi;
-        }
+        pend[0] = fmaxf(u[0] + b2[0], 0.0f);
+        pend[1] = fmaxf(u[1] + b2[1], 0.0f);
+        pend[2] = fmaxf(u[2] + b2[2], 0.0f);
+        pend[3] = fmaxf(u[3] + b2[3], 0.0f);
+        pend_ptr = live ? feat + th * g.nfeat + (map0 + m) * kDP + 4 * gl : nullptr;
       }
     }
-#pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) xb[ks] = xn[ks];
   }
+  flush();
 }
 
 // ---- backward -----------------------------------------------------------------------------------
@@ -386,15 +464,18 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_bwd(Geom g, View X,
   u32x4 xb[NKS], xn[NKS];
   if (tile < tm.total) {
     tm.decode(tile, b, h, n0);
-    load_x<D>(X, b, h, n0 + r, g.N, gl, xb);
+    load_x<D>(X, b, h, n0 + r, g.N, gl, xn);
   }
   for (; tile < tm.total; tile += stride) {
     const int n = n0 + r;
     const bool live = n < g.N;
     const int64_t th = g.th(b, h, live ? n : 0);
     const int ob = b, oh = h, on0 = n0;  // this tile's coordinates (b, h, n0 move on to the next tile below)
-    if (tile + stride < tm.total) {
-      tm.decode(tile + stride, b, h, n0);
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) xb[ks] = xn[ks];
+    {
+      const int nt = tile + stride < tm.total ? tile + stride : tile;
+      tm.decode(nt, b, h, n0);
       load_x<D>(X, b, h, n0 + r, g.N, gl, xn);
     }
     f32x16 dx[NRB];
@@ -433,13 +514,19 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_bwd(Geom g, View X,
         const u32x4 a2 = *reinterpret_cast<const u32x4*>(wm + SM::kW1 + (rb * 64 + lane) * 16);
         dg = mfma32(a2, dub, dg);
 #pragma unroll
-        for (int half = 0; half < 2; ++half)
+        for (int half = 0; half < 2; ++half) {
+          float in[8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) in[e] = acc[rb][8 * half + e];
+          f16x2 gp[4];
+          gelu_grad_f16<4>(in, gp);
 #pragma unroll
           for (int p = 0; p < 4; ++p) {
             const int i = 8 * half + 2 * p;
-            dhb[2 * rb + half][p] = pack_bf16(dg[i] * gelu_grad_poly(acc[rb][i]),
-                                              dg[i + 1] * gelu_grad_poly(acc[rb][i + 1]));
+            dhb[2 * rb + half][p] = pack_bf16(dg[i] * static_cast<float>(gp[p][0]),
+                                              dg[i + 1] * static_cast<float>(gp[p][1]));
           }
+        }
       }
 #pragma unroll
       for (int ks2 = 0; ks2 < NKS; ++ks2)
@@ -459,8 +546,6 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_bwd(Geom g, View X,
     store_rows_bf16<D, 16>(dx, 1.0f, lane, ttile, [&](int t) -> bf16_t* {
       return on0 + t < g.N ? dX.row<bf16_t>(ob, oh, on0 + t) : nullptr;
     });
-#pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) xb[ks] = xn[ks];
   }
 }
 
