@@ -225,11 +225,13 @@ hla_status hla_create(const hla_config* c, hla_handle** out) {
     return HLA_ERR_UNSUPPORTED;
   }
   hd->path = (c->kernel_path == HLA_PATH_GENERIC || !mfma_ok) ? HLA_PATH_GENERIC : HLA_PATH_MFMA;
+  hd->g.feat_tiled = hd->path == HLA_PATH_MFMA ? 1 : 0;
 
   hla_status st = hd->path == HLA_PATH_MFMA ? mfma_workspace_plan(hd) : generic_workspace_plan(hd);
   // allocate what the plan asked for
-  if (st == HLA_OK) st = dev_alloc(&hd->feat, hd->max_th * hd->g.nfeat);
-  if (st == HLA_OK) st = dev_alloc(&hd->dfeat, hd->max_th * hd->g.nfeat);
+  const int64_t feat_rows = (hd->max_th + 31) / 32 * 32;  // whole 32-token groups for the tiled layout
+  if (st == HLA_OK) st = dev_alloc(&hd->feat, feat_rows * hd->g.nfeat);
+  if (st == HLA_OK) st = dev_alloc(&hd->dfeat, feat_rows * hd->g.nfeat);
   if (st == HLA_OK) st = dev_alloc(&hd->den, hd->max_th);
   if (st == HLA_OK) st = dev_alloc(&hd->yhat, hd->yhat_floats);
   if (st == HLA_OK) st = dev_alloc(&hd->state, hd->max_units * hd->state_stride);
@@ -386,7 +388,17 @@ hla_status hla_read_workspace(hla_handle* hd, int32_t kind, float* host_dst, int
   if (count > avail) return HLA_ERR_INVALID_ARG;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   HLA_HIP_TRY(hipStreamSynchronize(s));
-  if (count > 0) HLA_HIP_TRY(hipMemcpy(host_dst, src, count * sizeof(float), hipMemcpyDeviceToHost));
+  if (count == 0) return HLA_OK;
+  if (kind != HLA_WS_DENOMINATORS && hd->g.feat_tiled) {
+    // the workspace is tiled on the device; hand out the documented [token-head][feature] order
+    const int64_t rows = (th + 31) / 32 * 32;
+    std::vector<float> raw(static_cast<size_t>(rows * hd->g.nfeat));
+    HLA_HIP_TRY(hipMemcpy(raw.data(), src, raw.size() * sizeof(float), hipMemcpyDeviceToHost));
+    for (int64_t i = 0; i < count; ++i)
+      host_dst[i] = raw[static_cast<size_t>(hd->g.fidx(i / hd->g.nfeat, static_cast<int>(i % hd->g.nfeat)))];
+    return HLA_OK;
+  }
+  HLA_HIP_TRY(hipMemcpy(host_dst, src, count * sizeof(float), hipMemcpyDeviceToHost));
   return HLA_OK;
 }
 

@@ -65,10 +65,17 @@ struct BlockEnt {
 struct Geom {
   int32_t B, H, N;       // as passed by the caller (N = tokens per batch row)
   int32_t d, dphi, F, D;  // head dim, feature dim, degree, dphi^F
-  int32_t nfeat;          // (1+F)*dphi, width of a row of the feature workspace
+  int32_t nfeat;          // (1+F)*dphi, features per token-head in the feature workspace
+  int32_t feat_tiled;     // layout of the feature workspaces, see fidx()
   float eps;
   __host__ __device__ __forceinline__ int64_t th(int b, int h, int n) const {
     return (static_cast<int64_t>(b) * H + h) * N + n;
+  }
+  // Index of feature a of token-head th in the feature / feature-gradient workspace.  Plain:
+  // [th][nfeat].  Tiled (matrix-core path): [th / 32][nfeat][32], so that the 32 lanes that hold
+  // one feature of 32 consecutive token-heads read and write one contiguous 128-byte run.
+  __host__ __device__ __forceinline__ int64_t fidx(int64_t th, int a) const {
+    return feat_tiled ? (th >> 5) * (static_cast<int64_t>(nfeat) * 32) + a * 32 + (th & 31) : th * nfeat + a;
   }
 };
 

@@ -70,8 +70,8 @@ __global__ void k_feat_import(Geom g, View Q, View K, float* __restrict__ feat) 
   const int n = static_cast<int>(th % g.N);
   const int h = static_cast<int>((th / g.N) % g.H);
   const int b = static_cast<int>(th / (static_cast<int64_t>(g.N) * g.H));
-  feat[idx] = j < g.dphi ? to_float(Q.row<const T>(b, h, n)[j])
-                         : to_float(K.row<const T>(b, h, n)[j - g.dphi]);
+  feat[g.fidx(th, j)] = j < g.dphi ? to_float(Q.row<const T>(b, h, n)[j])
+                                   : to_float(K.row<const T>(b, h, n)[j - g.dphi]);
 }
 
 // PHI_NONE: feature gradients are the answer; store them in the I/O dtype.
@@ -86,9 +86,9 @@ __global__ void k_dfeat_export(Geom g, const float* __restrict__ dfeat, View dQ,
   const int h = static_cast<int>((th / g.N) % g.H);
   const int b = static_cast<int>(th / (static_cast<int64_t>(g.N) * g.H));
   if (j < g.dphi)
-    dQ.row<T>(b, h, n)[j] = from_float<T>(dfeat[idx]);
+    dQ.row<T>(b, h, n)[j] = from_float<T>(dfeat[g.fidx(th, j)]);
   else
-    dK.row<T>(b, h, n)[j - g.dphi] = from_float<T>(dfeat[idx]);
+    dK.row<T>(b, h, n)[j - g.dphi] = from_float<T>(dfeat[g.fidx(th, j)]);
 }
 
 // ---- feature maps (App. A.1) ------------------------------------------------------------------

@@ -15,6 +15,10 @@ namespace {
 
 using namespace mf;
 
+
+#ifndef HLA_STAGGER_CORE
+#define HLA_STAGGER_CORE 5
+#endif
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
 constexpr int kQueryBlock = 1024;  // tokens per workgroup in token-parallel kernels
@@ -51,6 +55,58 @@ struct StateLayout {
   static constexpr int64_t kOpBytes = 2 * kOpElems * 2 + 2 * SP * 4;
 };
 
+// ---- sum of per-wave accumulator tiles over the four waves of a workgroup ------------------------
+// Every wave holds a [64 rows x D] fp32 tile in MFMA accumulator layout (acc[rb][cb][i]: row
+// 32rb + d_row(i, gl), column 32cb + r) and a 64-vector zl (element 32 gl + k, replicated over r).
+// Fixed order (w0 + w1) + (w2 + w3), two LDS regions of (64 D + 64) floats, four barriers; the sum
+// ends in region 0 with tile row `row` at floats [row * D, row * D + D) and the vector at 64 D.
+template <int D>
+struct WaveSum {
+  static constexpr int kRegion = 64 * D + 64;          // floats
+  static constexpr int kBytes = 2 * kRegion * 4;
+};
+template <int D>
+__device__ __forceinline__ void sum_over_waves(f32x16 (&acc)[2][D / 32], float (&zl)[32], float* lds,
+                                               int wave, int lane) {
+  constexpr int NCB = D / 32;
+  const int r = lane % 32, gl = lane / 32;
+  auto put = [&](float* reg) {
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i)
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb) reg[(32 * rb + d_row(i, gl)) * D + 32 * cb + r] = acc[rb][cb][i];
+    if (r == 0) {
+#pragma unroll
+      for (int k = 0; k < 32; ++k) reg[64 * D + 32 * gl + k] = zl[k];
+    }
+  };
+  auto add = [&](const float* reg) {
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i)
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb) acc[rb][cb][i] += reg[(32 * rb + d_row(i, gl)) * D + 32 * cb + r];
+#pragma unroll
+    for (int k = 0; k < 32; ++k) zl[k] += reg[64 * D + 32 * gl + k];
+  };
+  float* reg = lds + (wave / 2) * WaveSum<D>::kRegion;
+  __syncthreads();
+  if (wave % 2 == 1) put(reg);
+  __syncthreads();
+  if (wave % 2 == 0) add(reg);
+  __syncthreads();
+  if (wave == 2) put(lds);
+  __syncthreads();
+  if (wave == 0) {
+    add(lds);
+    put(lds);
+  }
+  __syncthreads();
+}
+
 // ---- k_state ----------------------------------------------------------------------------------
 template <int D>
 struct StateSmem {
@@ -59,7 +115,7 @@ struct StateSmem {
   static constexpr int kVBytes = 64 * kVStride;
   static constexpr int kSBytes = 64 * kSStride;
   static constexpr int kWaveBytes = kVBytes + kSBytes;
-  static constexpr int kRedBytes = (64 * D + 64) * 4;
+  static constexpr int kRedBytes = 2 * (64 * D + 64) * 4;
   static constexpr int kTotal = kWaves * kWaveBytes > kRedBytes ? kWaves * kWaveBytes : kRedBytes;
 };
 
@@ -105,9 +161,9 @@ __global__ __launch_bounds__(kThreads) void k_state(Geom g, const BlockEnt* __re
     fetch_tile<D, 64>(V, e.b, h, n0, e.t1, lane, vt);
     const int n = n0 + lane;
     if (n < e.t1) {
-      const float* f = feat + g.th(e.b, h, n) * g.nfeat + DP;
+      const float* f = feat + g.fidx(g.th(e.b, h, n), DP);
 #pragma unroll
-      for (int a = 0; a < 3 * DP; ++a) kf[a] = f[a];
+      for (int a = 0; a < 3 * DP; ++a) kf[a] = f[32 * a];
     } else {
 #pragma unroll
       for (int a = 0; a < 3 * DP; ++a) kf[a] = 0.0f;
@@ -179,32 +235,22 @@ __global__ __launch_bounds__(kThreads) void k_state(Geom g, const BlockEnt* __re
     }
     wave_lds_sync();
   }
-  // ---- sum the four waves in wave order through LDS, then write the partial state
+  // ---- sum the four waves through LDS, then write the partial state (rows = canonical monomials)
+  float zl[32];
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) zl[16 * rb + i] = zacc[rb][i];
   float* red = reinterpret_cast<float*>(smem);
-  for (int w = 0; w < kWaves; ++w) {
-    __syncthreads();
-    if (wave == w) {
-#pragma unroll
-      for (int rb = 0; rb < 2; ++rb) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int row = 32 * rb + d_row(i, gq);
-#pragma unroll
-          for (int cb = 0; cb < NCB; ++cb) {
-            float* p = red + row * D + 32 * cb + r;
-            *p = (w == 0 ? 0.0f : *p) + acc[rb][cb][i];
-          }
-          if (r == 0) {
-            float* p = red + 64 * D + row;
-            *p = (w == 0 ? 0.0f : *p) + zacc[rb][i];
-          }
-        }
-      }
-    }
-  }
-  __syncthreads();
+  sum_over_waves<D>(acc, zl, red, wave, lane);
   float* out = partial + (static_cast<int64_t>(blockIdx.x) * g.H + h) * partial_stride;
-  for (int i = threadIdx.x; i < 64 * D + 64; i += kThreads) out[i] = red[i];
+  for (int i = threadIdx.x; i < 64 * D / 4; i += kThreads)
+    reinterpret_cast<f32x4*>(out)[i] = reinterpret_cast<const f32x4*>(red)[i];
+  // vector element 32 gl + 16 rb + i is state row 32 rb + d_row(i, gl)
+  if (threadIdx.x < 64) {
+    const int gg = threadIdx.x / 32, k = threadIdx.x % 32;
+    out[64 * D + 32 * (k / 16) + d_row(k % 16, gg)] = red[64 * D + threadIdx.x];
+  }
 }
 
 // ---- k_reduce ---------------------------------------------------------------------------------
@@ -321,9 +367,9 @@ __global__ __launch_bounds__(kThreads) void k_query(Geom g, const BlockEnt* __re
     const bool live = n < e.t1;
     float qf[DP];
     if (live) {
-      const float* f = feat + g.th(e.b, h, n) * g.nfeat;
+      const float* f = feat + g.fidx(g.th(e.b, h, n), 0);
 #pragma unroll
-      for (int c = 0; c < DP; ++c) qf[c] = f[gl ? DP - 1 - c : c];
+      for (int c = 0; c < DP; ++c) qf[c] = f[32 * (gl ? DP - 1 - c : c)];
     } else {
 #pragma unroll
       for (int c = 0; c < DP; ++c) qf[c] = 0.0f;
@@ -365,7 +411,7 @@ struct BwdQSmem {
   static constexpr int kDoBytes = 32 * D * 2;   // dO tile [32 tokens][D] bf16, swizzled, unpadded
   static constexpr int kQBytes = 32 * 128;      // scaled-monomial tile [32 tokens][64 slot columns] bf16
   static constexpr int kWaveBytes = kDoBytes + kQBytes;
-  static constexpr int kRedBytes = (64 * D + 64) * 4;
+  static constexpr int kRedBytes = 2 * (64 * D + 64) * 4;
   static constexpr int kTotal = kWaves * kWaveBytes > kRedBytes ? kWaves * kWaveBytes : kRedBytes;
 };
 
@@ -447,27 +493,28 @@ __global__ __launch_bounds__(kThreads) void k_bwd_query(
   // one tile's inputs: the dO row pieces (B operand, k-slot (ks, gl, j) = channel 16ks + 8gl + j),
   // the query features of this lane's half (gl = 1: reversed) and the denominator
   u32x4 xb[NKD], xn[NKD];
-  float2 fb[DP / 2], fn[DP / 2];
+  float fb[DP], fn[DP];
   float denb = 1.0f, denn = 1.0f;
-  auto fetch = [&](int n0, u32x4(&x)[NKD], float2(&f)[DP / 2], float& dn) {
+  auto fetch = [&](int n0, u32x4(&x)[NKD], float(&f)[DP], float& dn) {
     const int n = n0 + r;
     if (n < e.t1) {
       const bf16_t* row = dO.row<const bf16_t>(e.b, h, n);
 #pragma unroll
       for (int ks = 0; ks < NKD; ++ks) x[ks] = *reinterpret_cast<const u32x4*>(row + 16 * ks + 8 * gl);
       const int64_t th = g.th(e.b, h, n);
-      const float2* fp = reinterpret_cast<const float2*>(feat + th * g.nfeat);
+      const float* fp = feat + g.fidx(th, 0);
 #pragma unroll
-      for (int a = 0; a < DP / 2; ++a) f[a] = fp[a];
+      for (int a = 0; a < DP; ++a) f[a] = fp[32 * a];
       dn = den[th];
     } else {
 #pragma unroll
       for (int ks = 0; ks < NKD; ++ks) x[ks][0] = x[ks][1] = x[ks][2] = x[ks][3] = 0u;
 #pragma unroll
-      for (int a = 0; a < DP / 2; ++a) f[a].x = f[a].y = 0.0f;
+      for (int a = 0; a < DP; ++a) f[a] = 0.0f;
       dn = 1.0f;
     }
   };
+  stagger_start(wave, blockIdx.x, HLA_STAGGER_CORE);
   int n0 = e.t0 + wave * 32;
   if (n0 < e.t1) fetch(n0, xb, fb, denb);
   for (; n0 < e.t1; n0 += kWaves * 32) {
@@ -491,10 +538,7 @@ __global__ __launch_bounds__(kThreads) void k_bwd_query(
     const float inv = live ? 1.0f / denb : 0.0f;
     float qf[DP];
 #pragma unroll
-    for (int c = 0; c < DP; ++c) {
-      const int cc = gl ? DP - 1 - c : c;
-      qf[c] = cc % 2 ? fb[cc / 2].y : fb[cc / 2].x;
-    }
+    for (int c = 0; c < DP; ++c) qf[c] = gl ? fb[DP - 1 - c] : fb[c];
     float qm[SP];
     query_monomials<DP>(qf, qm);
 #pragma unroll
@@ -527,10 +571,9 @@ __global__ __launch_bounds__(kThreads) void k_bwd_query(
 #pragma unroll
     for (int c = 0; c < DP; ++c) other[c] = partner32(dq[c]);
     if (live && gl == 0) {
-      float2* df = reinterpret_cast<float2*>(dfeat + th * g.nfeat);
+      float* df = dfeat + g.fidx(th, 0);
 #pragma unroll
-      for (int c = 0; c < DP; c += 2)
-        df[c / 2] = make_float2(dq[c] + other[DP - 1 - c], dq[c + 1] + other[DP - 2 - c]);
+      for (int c = 0; c < DP; ++c) df[32 * c] = dq[c] + other[DP - 1 - c];
     }
     wave_lds_sync();
     // dCsym[(g,s) rows x D] += (inv Qm)^T[64 x 32 tokens] dO[32 tokens x D]
@@ -563,7 +606,7 @@ __global__ __launch_bounds__(kThreads) void k_bwd_query(
 #pragma unroll
     for (int ks = 0; ks < NKD; ++ks) xb[ks] = xn[ks];
 #pragma unroll
-    for (int a = 0; a < DP / 2; ++a) fb[a] = fn[a];
+    for (int a = 0; a < DP; ++a) fb[a] = fn[a];
     denb = denn;
   }
   // dz: sum over the 32 token lanes of each half
@@ -574,33 +617,10 @@ __global__ __launch_bounds__(kThreads) void k_bwd_query(
     for (int m = 1; m < 32; m <<= 1) v += __shfl_xor(v, m, 64);
     dzacc[s] = v;
   }
-  // sum the four waves in wave order: row 32rb + d_row(i, gl) of the accumulators is column
-  // 32g' + s' of the monomial tile, i.e. slot (g', s')
+  // sum the four waves: row 32rb + d_row(i, gl) of the accumulators is column 32g' + s' of the
+  // monomial tile, i.e. slot (g', s'); the vector element 32 gl + s is slot (gl, s) as well
   float* red = reinterpret_cast<float*>(smem);
-  for (int w = 0; w < kWaves; ++w) {
-    __syncthreads();
-    if (wave == w) {
-#pragma unroll
-      for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int row = 32 * rb + d_row(i, gl);
-#pragma unroll
-          for (int cb = 0; cb < NCB; ++cb) {
-            float* p = red + row * D + 32 * cb + r;
-            *p = (w == 0 ? 0.0f : *p) + dC[rb][cb][i];
-          }
-        }
-      if (r == 0) {
-#pragma unroll
-        for (int s = 0; s < SP; ++s) {
-          float* p = red + 64 * D + 32 * gl + s;
-          *p = (w == 0 ? 0.0f : *p) + dzacc[s];
-        }
-      }
-    }
-  }
-  __syncthreads();
+  sum_over_waves<D>(dC, dzacc, red, wave, lane);
   f32x4* out = reinterpret_cast<f32x4*>(partial + (static_cast<int64_t>(blockIdx.x) * g.H + h) * partial_stride);
   for (int i = threadIdx.x; i < (64 * D + 64) / 4; i += kThreads) out[i] = reinterpret_cast<const f32x4*>(red)[i];
 }
@@ -621,25 +641,30 @@ __global__ __launch_bounds__(kThreads) void k_bwd_key(Geom g, const BlockEnt* __
   using SL = StateLayout<DP, D>;
   constexpr int SP = SY::SP, MP = SY::MP;
   constexpr int NRB = D / 32, NKS = MP / 16, NKD = D / 16;
-  __shared__ __align__(16) unsigned char smem[kWaves * RowTile<D>::kBytes];
+  // LDS: the two operand images of the state gradient (shared by the four waves, read per use:
+  // holding them in registers would leave no room for the software pipeline below), then one
+  // transpose tile per wave for whole-row stores of dV
+  constexpr int kOpImg = static_cast<int>(SL::kOpElems) * 2;  // bytes of one operand image
+  __shared__ __align__(16) unsigned char smem[2 * kOpImg + kWaves * RowTile<D>::kBytes];
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
-  unsigned char* tile = smem + wave * RowTile<D>::kBytes;
+  unsigned char* tile = smem + 2 * kOpImg + wave * RowTile<D>::kBytes;
   const int r = lane % 32, gl = lane / 32;
   const BlockEnt e = blocks[blockIdx.x];
   const int h = blockIdx.y;
   const int64_t u = static_cast<int64_t>(e.seq) * g.H + h;
-  const u32x4* opA = reinterpret_cast<const u32x4*>(dops + u * SL::kOpBytes);
-  const u32x4* opB = reinterpret_cast<const u32x4*>(dops + u * SL::kOpBytes + SL::kOpElems * 2);
+  {
+    const u32x4* src = reinterpret_cast<const u32x4*>(dops + u * SL::kOpBytes);
+    constexpr int N16 = 2 * kOpImg / 16, PER = N16 / kThreads;
+    static_assert(N16 % kThreads == 0, "operand images are copied in whole rounds");
+    u32x4 v[PER];
+#pragma unroll
+    for (int k = 0; k < PER; ++k) v[k] = src[threadIdx.x + k * kThreads];
+#pragma unroll
+    for (int k = 0; k < PER; ++k) reinterpret_cast<u32x4*>(smem)[threadIdx.x + k * kThreads] = v[k];
+  }
+  const u32x4* opA = reinterpret_cast<const u32x4*>(smem) + lane;            // [rb * NKS + ks] * 64
+  const u32x4* opB = reinterpret_cast<const u32x4*>(smem + kOpImg) + lane;   // [rb * NKD + ks] * 64
   const float* dzslot = reinterpret_cast<const float*>(dops + u * SL::kOpBytes + 2 * SL::kOpElems * 2) + gl * SP;
-  u32x4 a_ch[NRB][NKS], a_mo[2][NKD];
-#pragma unroll
-  for (int rb = 0; rb < NRB; ++rb)
-#pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) a_ch[rb][ks] = opA[(rb * NKS + ks) * 64 + lane];
-#pragma unroll
-  for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-    for (int ks = 0; ks < NKD; ++ks) a_mo[rb][ks] = opB[(rb * NKD + ks) * 64 + lane];
   float dz[SP];
 #pragma unroll
   for (int s4 = 0; s4 < SP / 4; ++s4) {
@@ -647,53 +672,83 @@ __global__ __launch_bounds__(kThreads) void k_bwd_key(Geom g, const BlockEnt* __
 #pragma unroll
     for (int i = 0; i < 4; ++i) dz[4 * s4 + i] = v[i];
   }
+  __syncthreads();
 
-  // one tile's inputs: the V row pieces (B operand, k-slot (ks, gl, j) = channel 16ks + 8gl + j;
+  // One tile's inputs: the V row pieces (B operand, k-slot (ks, gl, j) = channel 16ks + 8gl + j;
   // the 32-byte runs of a row that one load instruction touches are merged by the vector cache)
-  // and the 18 key features of the token
+  // and the 18 key features of the token.  vn/kn always hold the loads in flight for the coming
+  // tile (rows past the chunk read its last row and are masked below) and are copied at the top
+  // of the loop.  Memory instructions are spread through the iteration instead of issued in
+  // bursts: the next tile's loads go out one at a time between the MFMAs of the first half, the
+  // previous tile's outputs (dV rows staged in LDS, feature gradients held in registers) leave
+  // between quarters of the chain rule.  All waves of the grid run the same schedule, and
+  // back-to-back bursts from all of them at once stall on the memory pipeline's queues.
+  constexpr int PIECES = D / 8, RPI = 64 / PIECES, NST = 32 / RPI;  // dV row stores per tile
   u32x4 vb[NKD], vn[NKD];
-  float2 kb[3 * DP / 2], kn[3 * DP / 2];
-  auto fetch = [&](int n0, u32x4(&v)[NKD], float2(&k)[3 * DP / 2]) {
-    const int n = n0 + r;
-    if (n < e.t1) {
-      const bf16_t* row = V.row<const bf16_t>(e.b, h, n);
+  float kb[3 * DP], kn[3 * DP];
+  stagger_start(wave, blockIdx.x, HLA_STAGGER_CORE);
+  int n0 = e.t0 + wave * 32;
+  const bf16_t* nrow = nullptr;   // the coming tile's V row and feature address of this lane
+  const float* nfeat = nullptr;
+  auto next_addr = [&](int t0) {
+    const int n = t0 + r < e.t1 ? t0 + r : e.t1 - 1;
+    nrow = V.row<const bf16_t>(e.b, h, n);
+    nfeat = feat + g.fidx(g.th(e.b, h, n), DP);
+  };
+  if (n0 < e.t1) {
+    next_addr(n0);
 #pragma unroll
-      for (int ks = 0; ks < NKD; ++ks) v[ks] = *reinterpret_cast<const u32x4*>(row + 16 * ks + 8 * gl);
-      const float2* f = reinterpret_cast<const float2*>(feat + g.th(e.b, h, n) * g.nfeat + DP);
+    for (int ks = 0; ks < NKD; ++ks) vn[ks] = *reinterpret_cast<const u32x4*>(nrow + 16 * ks + 8 * gl);
 #pragma unroll
-      for (int a = 0; a < 3 * DP / 2; ++a) k[a] = f[a];
-    } else {
+    for (int a = 0; a < 3 * DP; ++a) kn[a] = nfeat[32 * a];
+  }
+  int pend_n0 = -1;            // first token of the tile staged in LDS, -1: none
+  float pend_df[3 * DP];       // its feature gradients (this lane's token)
 #pragma unroll
-      for (int ks = 0; ks < NKD; ++ks) v[ks][0] = v[ks][1] = v[ks][2] = v[ks][3] = 0u;
+  for (int a = 0; a < 3 * DP; ++a) pend_df[a] = 0.0f;
+  // one dV row store of the staged tile
+  auto flush_piece = [&](int i) {
+    const int row = i * RPI + lane / PIECES, piece = lane % PIECES;
+    const u32x4 v = *reinterpret_cast<const u32x4*>(tile + row * RowTile<D, 32>::kStride + piece * 16);
+    if (pend_n0 >= 0 && pend_n0 + row < e.t1)
+      *reinterpret_cast<u32x4*>(dV.row<bf16_t>(e.b, h, pend_n0 + row) + piece * 8) = v;
+  };
+  // feature gradients a0 .. a1-1 of the staged tile
+  auto flush_df = [&](int a0, int a1) {
+    if (pend_n0 >= 0 && pend_n0 + r < e.t1 && gl == 0) {
+      float* df = dfeat + g.fidx(g.th(e.b, h, pend_n0 + r), DP);
 #pragma unroll
-      for (int a = 0; a < 3 * DP / 2; ++a) k[a].x = k[a].y = 0.0f;
+      for (int a = 0; a < 3 * DP; ++a)
+        if (a >= a0 && a < a1) df[32 * a] = pend_df[a];
     }
   };
-  int n0 = e.t0 + wave * 32;
-  if (n0 < e.t1) fetch(n0, vb, kb);
   for (; n0 < e.t1; n0 += kWaves * 32) {
-    const int n = n0 + r;
-    const bool live = n < e.t1;
-    const int64_t th = g.th(e.b, h, live ? n : e.t0);
-    if (n0 + kWaves * 32 < e.t1) fetch(n0 + kWaves * 32, vn, kn);
+    const bool live = n0 + r < e.t1;
+#pragma unroll
+    for (int ks = 0; ks < NKD; ++ks) vb[ks] = vn[ks];
+#pragma unroll
+    for (int a = 0; a < 3 * DP; ++a) kb[a] = kn[a];
+    next_addr(n0 + kWaves * 32 < e.t1 ? n0 + kWaves * 32 : n0);
     f32x16 dS[2];
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) dS[rb][i] = 0.0f;
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int ks = 0; ks < NKD; ++ks)
+    for (int ks = 0; ks < NKD; ++ks) {
 #pragma unroll
-      for (int rb = 0; rb < 2; ++rb) dS[rb] = mfma32(a_mo[rb][ks], vb[ks], dS[rb]);
-    // features of this lane's half: gl = 1 works on the reversed vectors
+      for (int rb = 0; rb < 2; ++rb) dS[rb] = mfma32(opB[(rb * NKD + ks) * 64], vb[ks], dS[rb]);
+      vn[ks] = *reinterpret_cast<const u32x4*>(nrow + 16 * ks + 8 * gl);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    // features of this lane's half: gl = 1 works on the reversed vectors; lanes past the chunk
+    // work on zeros
     float k1[DP], k2[DP], k3[DP];
     {
       float kf[3 * DP];
 #pragma unroll
-      for (int a = 0; a < 3 * DP / 2; ++a) {
-        kf[2 * a] = kb[a].x;
-        kf[2 * a + 1] = kb[a].y;
-      }
+      for (int a = 0; a < 3 * DP; ++a) kf[a] = live ? kb[a] : 0.0f;
 #pragma unroll
       for (int c = 0; c < DP; ++c) {
         k1[c] = gl ? kf[DP - 1 - c] : kf[c];
@@ -701,7 +756,7 @@ __global__ __launch_bounds__(kThreads) void k_bwd_key(Geom g, const BlockEnt* __
         k3[c] = gl ? kf[3 * DP - 1 - c] : kf[2 * DP + c];
       }
     }
-    // dV^T = dCsym^T S^T first: its MFMAs run while the chain rule below occupies the vector ALU
+    // dV^T = dCsym^T S^T
     float sm[SP];
     key_monomials_slots<DP>(k1, k2, k3, sm);
     f32x16 acc[NRB];
@@ -709,24 +764,47 @@ __global__ __launch_bounds__(kThreads) void k_bwd_key(Geom g, const BlockEnt* __
     for (int rb = 0; rb < NRB; ++rb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[rb][i] = 0.0f;
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) {
       u32x4 b;
 #pragma unroll
       for (int p = 0; p < 4; ++p) b[p] = pack_bf16(sm[8 * ks + 2 * p], sm[8 * ks + 2 * p + 1]);
 #pragma unroll
-      for (int rb = 0; rb < NRB; ++rb) acc[rb] = mfma32(a_ch[rb][ks], b, acc[rb]);
+      for (int rb = 0; rb < NRB; ++rb) {
+        acc[rb] = mfma32(opA[(rb * NKS + ks) * 64], b, acc[rb]);
+        // the coming tile's features, a few per MFMA
+        constexpr int kPerM = (3 * DP + NKS * NRB - 1) / (NKS * NRB);
+#pragma unroll
+        for (int t = 0; t < kPerM; ++t) {
+          const int a = (ks * NRB + rb) * kPerM + t;
+          if (a < 3 * DP) kn[a] = nfeat[32 * a];
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
     }
+    float dk1[DP], dk2[DP], dk3[DP];
     {
       float ds[SP];
 #pragma unroll
       for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
         for (int i = 0; i < 16; ++i) ds[16 * rb + i] = dS[rb][i] + dz[16 * rb + i];
-      float dk1[DP], dk2[DP], dk3[DP];
 #pragma unroll
       for (int c = 0; c < DP; ++c) dk1[c] = dk2[c] = dk3[c] = 0.0f;
-      key_monomials_grad<DP>(k1, k2, k3, ds, dk1, dk2, dk3);
+      // chain rule in four quarters, the previous tile's outputs leaving in between
+      static_for<0, 4>([&](auto Q) {
+        constexpr int qd = decltype(Q)::value;
+        constexpr int NS = SY::NS, S0 = qd * ((NS + 3) / 4), S1 = (qd + 1) * ((NS + 3) / 4);
+        key_monomials_grad_range<DP, S0, S1>(k1, k2, k3, ds, dk1, dk2, dk3);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = qd * NST / 4; i < (qd + 1) * NST / 4; ++i) flush_piece(i);
+        flush_df(qd * (3 * DP + 3) / 4, (qd + 1) * (3 * DP + 3) / 4 < 3 * DP ? (qd + 1) * (3 * DP + 3) / 4 : 3 * DP);
+        __builtin_amdgcn_sched_barrier(0);
+      });
+    }
+    {
       float o1[DP], o2[DP], o3[DP];
 #pragma unroll
       for (int c = 0; c < DP; ++c) {
@@ -734,24 +812,25 @@ __global__ __launch_bounds__(kThreads) void k_bwd_key(Geom g, const BlockEnt* __
         o2[c] = partner32(dk2[c]);
         o3[c] = partner32(dk3[c]);
       }
-      if (live && gl == 0) {
-        float2* df = reinterpret_cast<float2*>(dfeat + th * g.nfeat + DP);
 #pragma unroll
-        for (int c = 0; c < DP; c += 2) {
-          df[c / 2] = make_float2(dk1[c] + o1[DP - 1 - c], dk1[c + 1] + o1[DP - 2 - c]);
-          df[(DP + c) / 2] = make_float2(dk2[c] + o2[DP - 1 - c], dk2[c + 1] + o2[DP - 2 - c]);
-          df[(2 * DP + c) / 2] = make_float2(dk3[c] + o3[DP - 1 - c], dk3[c + 1] + o3[DP - 2 - c]);
-        }
+      for (int c = 0; c < DP; ++c) {
+        pend_df[c] = dk1[c] + o1[DP - 1 - c];
+        pend_df[DP + c] = dk2[c] + o2[DP - 1 - c];
+        pend_df[2 * DP + c] = dk3[c] + o3[DP - 1 - c];
       }
     }
-    store_rows_bf16<D>(acc, 1.0f, lane, tile, [&](int t) -> bf16_t* {
-      return n0 + t < e.t1 ? dV.row<bf16_t>(e.b, h, n0 + t) : nullptr;
-    });
-#pragma unroll
-    for (int ks = 0; ks < NKD; ++ks) vb[ks] = vn[ks];
-#pragma unroll
-    for (int a = 0; a < 3 * DP / 2; ++a) kb[a] = kn[a];
+    {
+      wave_lds_sync();  // the flush above has read the whole staged tile
+      u32x4 w[NRB][2];
+      pack_rows<D>(acc, 1.0f, w);
+      put_rows<D, 32>(w, 0, lane, tile);
+      pend_n0 = n0;
+    }
   }
+  // the last tile's outputs
+#pragma unroll
+  for (int i = 0; i < NST; ++i) flush_piece(i);
+  flush_df(0, 3 * DP);
 }
 
 inline int pick_chunk(const Geom& g, int num_seqs) {

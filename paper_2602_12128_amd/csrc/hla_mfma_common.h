@@ -87,6 +87,17 @@ __host__ __device__ __forceinline__ int tile_off(int row, int chunk) {
   return row * ROWB + (((chunk ^ tile_swz<ROWB>(row)) & (ROWB / 16 - 1)) << 4);
 }
 
+// All waves of a streaming kernel run the same schedule; started together they reach their LDS,
+// vector-memory and matrix phases at the same moment and queue on the units a compute unit
+// shares.  A start-up delay that differs per wave (and per workgroup) spreads the phases out.
+// `unit` is in steps of 64 * 8 cycles.
+__device__ __forceinline__ void stagger_start(int wave, int block, int unit) {
+#ifndef HLA_NO_STAGGER
+  const int n = wave * unit + (block & 3);
+  for (int i = 0; i < n; ++i) __builtin_amdgcn_s_sleep(8);
+#endif
+}
+
 // value held by the lane 32 away (the other half of a (token, g) lane pair)
 __device__ __forceinline__ float partner32(float v) { return __shfl_xor(v, 32, 64); }
 
@@ -154,12 +165,14 @@ struct RowTile {
   static constexpr int kBytes = ROWS * kStride;
 };
 // ROWS (32 or 16) = token rows the LDS tile holds; with 16 the tile goes out in two passes.
-template <int D, int ROWS = 32, class RowPtr>
-__device__ __forceinline__ void store_rows_bf16(const f32x16 (&acc)[D / 32], float scale, int lane,
-                                                unsigned char* lds, RowPtr&& row_ptr) {
-  using RT = RowTile<D, ROWS>;
-  const int r = lane % 32, gl = lane / 32;
-  u32x4 w[D / 32][2];
+// pack_rows rounds and exchanges, put_rows writes one pass into the LDS tile, flush_rows stores
+// that pass to global memory.  Kernels that stream tiles split the two: a tile is staged at the
+// end of its iteration and flushed at the top of the next one, right after the wait for that
+// iteration's inputs.  Stores count in the same wait counter as loads, so a store issued just
+// before such a wait would cost its whole round trip.
+template <int D>
+__device__ __forceinline__ void pack_rows(const f32x16 (&acc)[D / 32], float scale,
+                                          u32x4 (&w)[D / 32][2]) {
 #pragma unroll
   for (int rb = 0; rb < D / 32; ++rb)
 #pragma unroll
@@ -178,26 +191,45 @@ __device__ __forceinline__ void store_rows_bf16(const f32x16 (&acc)[D / 32], flo
       w[rb][pr][2] = s0[1];
       w[rb][pr][3] = s1[1];
     }
+}
+template <int D, int ROWS>
+__device__ __forceinline__ void put_rows(const u32x4 (&w)[D / 32][2], int pass, int lane,
+                                         unsigned char* lds) {
+  using RT = RowTile<D, ROWS>;
+  const int r = lane % 32, gl = lane / 32;
+  if (ROWS == 32 || r / ROWS == pass) {
+#pragma unroll
+    for (int rb = 0; rb < D / 32; ++rb)
+#pragma unroll
+      for (int pr = 0; pr < 2; ++pr)
+        *reinterpret_cast<u32x4*>(lds + (r % ROWS) * RT::kStride + (32 * rb + 16 * pr + 8 * gl) * 2) = w[rb][pr];
+  }
+  wave_lds_sync();
+}
+// row_ptr(t) returns the destination of tile row t (0..31) or nullptr
+template <int D, int ROWS, class RowPtr>
+__device__ __forceinline__ void flush_rows(int pass, int lane, const unsigned char* lds, RowPtr&& row_ptr) {
+  using RT = RowTile<D, ROWS>;
   constexpr int PIECES = D / 8;        // 16-byte pieces per row
   constexpr int RPI = 64 / PIECES;     // rows per store instruction
 #pragma unroll
+  for (int i = 0; i < ROWS / RPI; ++i) {
+    const int row = i * RPI + lane / PIECES, piece = lane % PIECES;
+    const u32x4 v = *reinterpret_cast<const u32x4*>(lds + row * RT::kStride + piece * 16);
+    bf16_t* dst = row_ptr(pass * ROWS + row);
+    if (dst != nullptr) *reinterpret_cast<u32x4*>(dst + piece * 8) = v;
+  }
+  wave_lds_sync();
+}
+template <int D, int ROWS = 32, class RowPtr>
+__device__ __forceinline__ void store_rows_bf16(const f32x16 (&acc)[D / 32], float scale, int lane,
+                                                unsigned char* lds, RowPtr&& row_ptr) {
+  u32x4 w[D / 32][2];
+  pack_rows<D>(acc, scale, w);
+#pragma unroll
   for (int pass = 0; pass < 32 / ROWS; ++pass) {
-    if (ROWS == 32 || r / ROWS == pass) {
-#pragma unroll
-      for (int rb = 0; rb < D / 32; ++rb)
-#pragma unroll
-        for (int pr = 0; pr < 2; ++pr)
-          *reinterpret_cast<u32x4*>(lds + (r % ROWS) * RT::kStride + (32 * rb + 16 * pr + 8 * gl) * 2) = w[rb][pr];
-    }
-    wave_lds_sync();
-#pragma unroll
-    for (int i = 0; i < ROWS / RPI; ++i) {
-      const int row = i * RPI + lane / PIECES, piece = lane % PIECES;
-      const u32x4 v = *reinterpret_cast<const u32x4*>(lds + row * RT::kStride + piece * 16);
-      bf16_t* dst = row_ptr(pass * ROWS + row);
-      if (dst != nullptr) *reinterpret_cast<u32x4*>(dst + piece * 8) = v;
-    }
-    wave_lds_sync();
+    put_rows<D, ROWS>(w, pass, lane, lds);
+    flush_rows<D, ROWS>(pass, lane, lds, row_ptr);
   }
 }
 
@@ -370,13 +402,14 @@ __device__ __forceinline__ void key_monomials_slots(const float (&k1)[DP], const
 
 // Chain rule of key_monomials_slots: every distinct ordering (a,b,c) of slot s feeds
 // dk1[a] += ds * k2_b k3_c, dk2[b] += ds * k1_a k3_c, dk3[c] += ds * k1_a k2_b.
-template <int DP>
-__device__ __forceinline__ void key_monomials_grad(const float (&k1)[DP], const float (&k2)[DP],
-                                                   const float (&k3)[DP],
-                                                   const float (&ds)[Sym3<DP>::SP],
-                                                   float (&dk1)[DP], float (&dk2)[DP],
-                                                   float (&dk3)[DP]) {
-  static_for<0, Sym3<DP>::NS>([&](auto S) {
+// Slots S0 .. S1-1 only, so that callers can interleave other work between ranges.
+template <int DP, int S0, int S1>
+__device__ __forceinline__ void key_monomials_grad_range(const float (&k1)[DP], const float (&k2)[DP],
+                                                         const float (&k3)[DP],
+                                                         const float (&ds)[Sym3<DP>::SP],
+                                                         float (&dk1)[DP], float (&dk2)[DP],
+                                                         float (&dk3)[DP]) {
+  static_for<S0, (S1 < Sym3<DP>::NS ? S1 : Sym3<DP>::NS)>([&](auto S) {
     constexpr int s = decltype(S)::value;
     constexpr Tri t = sym3_slot(DP, s);
     constexpr Perm3 p = sym3_perms(t);
@@ -387,6 +420,14 @@ __device__ __forceinline__ void key_monomials_grad(const float (&k1)[DP], const 
       dk3[p.c[e]] += ds[s] * (k1[p.a[e]] * k2[p.b[e]]);
     });
   });
+}
+template <int DP>
+__device__ __forceinline__ void key_monomials_grad(const float (&k1)[DP], const float (&k2)[DP],
+                                                   const float (&k3)[DP],
+                                                   const float (&ds)[Sym3<DP>::SP],
+                                                   float (&dk1)[DP], float (&dk2)[DP],
+                                                   float (&dk3)[DP]) {
+  key_monomials_grad_range<DP, 0, Sym3<DP>::NS>(k1, k2, k3, ds, dk1, dk2, dk3);
 }
 
 }  // namespace mf

@@ -171,23 +171,39 @@ struct PhiSmem {
   }
 };
 
-// Copy one (map, head) block of packed weights into LDS (all threads of the workgroup).
-template <int D, bool BACKWARD>
+// Copy the packed weights of NMAPS (map, head) blocks into LDS (all THREADS threads of the
+// workgroup).  All global loads of a map are issued before the first LDS store so that they are
+// in flight together: the copy costs one memory round trip per map instead of one per 16 bytes.
+template <int D, bool BACKWARD, int THREADS>
 __device__ __forceinline__ void load_weights(unsigned char* dst, const unsigned char* src) {
   using SM = PhiSmem<D, BACKWARD>;
   using PK = Packed<D>;
-  const int nthreads = blockDim.x;
-  for (int i = threadIdx.x; i < D * SM::kChunks; i += nthreads) {
-    const int row = i / SM::kChunks, ch = i % SM::kChunks;
-    *reinterpret_cast<u32x4*>(dst + SM::off(row, ch)) = *reinterpret_cast<const u32x4*>(src + PK::kW1T + i * 16);
-  }
-  const int w2_bytes = BACKWARD ? D * 16 * 2 : D * 32 * 2;
+  constexpr int N1 = D * SM::kChunks;                              // 16-byte chunks of W1^T
+  constexpr int N2 = (BACKWARD ? D * 16 * 2 : D * 32 * 2) / 16;    // 16-byte chunks of the W2 image
+  constexpr int NB = D + 8;                                        // floats of b1 and b2
+  constexpr int I1 = (N1 + THREADS - 1) / THREADS, I2 = (N2 + THREADS - 1) / THREADS;
   const unsigned char* w2 = src + (BACKWARD ? PK::kW2B : PK::kW2A);
-  for (int i = threadIdx.x; i < w2_bytes / 16; i += nthreads)
-    *reinterpret_cast<u32x4*>(dst + SM::kW1 + i * 16) = *reinterpret_cast<const u32x4*>(w2 + i * 16);
-  for (int i = threadIdx.x; i < D + 8; i += nthreads)
-    *reinterpret_cast<float*>(dst + SM::kW1 + SM::kW2 + i * 4) =
-        *reinterpret_cast<const float*>(src + PK::kB1 + i * 4);
+  const int t = threadIdx.x;
+  u32x4 v1[I1], v2[I2];
+  float vb = 0.0f;
+#pragma unroll
+  for (int k = 0; k < I1; ++k)
+    if (N1 % THREADS == 0 || t + k * THREADS < N1) v1[k] = *reinterpret_cast<const u32x4*>(src + PK::kW1T + (t + k * THREADS) * 16);
+#pragma unroll
+  for (int k = 0; k < I2; ++k)
+    if (N2 % THREADS == 0 || t + k * THREADS < N2) v2[k] = *reinterpret_cast<const u32x4*>(w2 + (t + k * THREADS) * 16);
+  if (t < NB) vb = *reinterpret_cast<const float*>(src + PK::kB1 + t * 4);
+#pragma unroll
+  for (int k = 0; k < I1; ++k) {
+    const int i = t + k * THREADS;
+    if (N1 % THREADS == 0 || i < N1) *reinterpret_cast<u32x4*>(dst + SM::off(i / SM::kChunks, i % SM::kChunks)) = v1[k];
+  }
+#pragma unroll
+  for (int k = 0; k < I2; ++k) {
+    const int i = t + k * THREADS;
+    if (N2 % THREADS == 0 || i < N2) *reinterpret_cast<u32x4*>(dst + SM::kW1 + i * 16) = v2[k];
+  }
+  if (t < NB) *reinterpret_cast<float*>(dst + SM::kW1 + SM::kW2 + t * 4) = vb;
 }
 
 // The lane's share of its token's input vector as B operands: k-slot (ks, gl, j) is channel
@@ -283,7 +299,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_fwd(Geom g, View X,
   const TileMap tm = make_tile_map(g, heads_w);
   const int hw = heads_w == 1 ? 0 : blockIdx.y;
   for (int m = 0; m < NMAPS; ++m)  // packed blocks are ordered [map][head]
-    load_weights<D, false>(smem + m * SM::kMap,
+    load_weights<D, false, WAVES * 64>(smem + m * SM::kMap,
                            wpk + (static_cast<int64_t>(map0 + m) * heads_w + hw) * Packed<D>::kBytes);
   __syncthreads();
   int a_off[NKS];
@@ -300,10 +316,14 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_fwd(Geom g, View X,
   }
   float pend[4] = {0.0f, 0.0f, 0.0f, 0.0f};  // features of the last finished map, not yet stored
   float* pend_ptr = nullptr;
-  auto flush = [&]() {
+  auto flush = [&]() {  // feature a of 32 consecutive tokens is one contiguous 128-byte run
     if (pend_ptr != nullptr) {
-      *reinterpret_cast<float2*>(pend_ptr) = make_float2(pend[0], pend[1]);
-      if (gl == 0) *reinterpret_cast<float2*>(pend_ptr + 2) = make_float2(pend[2], pend[3]);
+      pend_ptr[0] = pend[0];
+      pend_ptr[32] = pend[1];
+      if (gl == 0) {
+        pend_ptr[64] = pend[2];
+        pend_ptr[96] = pend[3];
+      }
     }
     pend_ptr = nullptr;
   };
@@ -376,24 +396,15 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_fwd(Geom g, View X,
 #pragma unroll
           for (int t = 0; t < kPer; ++t) {
             const int ks = j * kPer + t;
-#ifndef EXP_NOMFMA
             nxt = mfma32(an[ks], xb[ks], nxt);
-#endif
-#ifndef EXP_NOLDS
             an[ks] = *reinterpret_cast<const u32x4*>(a2_base + a_off[ks]);
-#endif
           }
           if (j == 3) u = mfma32_f16(a20, gb[0], u);
           float in[4] = {cur[4 * j], cur[4 * j + 1], cur[4 * j + 2], cur[4 * j + 3]};
           asm volatile("" : "+v"(nxt), "+v"(in[0]), "+v"(in[1]), "+v"(in[2]), "+v"(in[3]));
           __builtin_amdgcn_sched_barrier(0);
           uint32_t out[2];
-#ifndef EXP_NOGELU
           gelu_f16<2>(in, out);
-#else
-          out[0] = __float_as_uint(in[0]) ^ __float_as_uint(in[1]);
-          out[1] = __float_as_uint(in[2]) ^ __float_as_uint(in[3]);
-#endif
           asm volatile("" : "+v"(out[0]), "+v"(out[1]));
           gb[j / 2][2 * (j % 2)] = out[0];
           gb[j / 2][2 * (j % 2) + 1] = out[1];
@@ -414,7 +425,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_fwd(Geom g, View X,
         pend[1] = fmaxf(u[1] + b2[1], 0.0f);
         pend[2] = fmaxf(u[2] + b2[2], 0.0f);
         pend[3] = fmaxf(u[3] + b2[3], 0.0f);
-        pend_ptr = live ? feat + th * g.nfeat + (map0 + m) * kDP + 4 * gl : nullptr;
+        pend_ptr = live ? feat + g.fidx(th, (map0 + m) * kDP + 4 * gl) : nullptr;
       }
     }
   }
@@ -439,7 +450,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_bwd(Geom g, View X,
   const TileMap tm = make_tile_map(g, heads_w);
   const int hw = heads_w == 1 ? 0 : blockIdx.y;
   for (int m = 0; m < NMAPS; ++m)
-    load_weights<D, true>(smem + m * SM::kMap,
+    load_weights<D, true, WAVES * 64>(smem + m * SM::kMap,
                           wpk + (static_cast<int64_t>(map0 + m) * heads_w + hw) * Packed<D>::kBytes);
   __syncthreads();
   unsigned char* ttile = smem + nmaps * SM::kMap + wave * RowTile<D, 16>::kBytes;  // dX transpose tile
@@ -490,15 +501,15 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_bwd(Geom g, View X,
       u32x4 dub;
       dub[0] = dub[1] = dub[2] = dub[3] = 0u;
       if (live && gl == 0) {
-        const int64_t o = th * g.nfeat + (map0 + m) * kDP;
-        float du[kDP];
+        const int64_t o = g.fidx(th, (map0 + m) * kDP);
+        float fv[kDP], dv[kDP], du[kDP];  // both loaded unconditionally: one round trip, not six
 #pragma unroll
-        for (int a = 0; a < kDP; a += 2) {
-          const float2 f = *reinterpret_cast<const float2*>(feat + o + a);
-          const float2 d = *reinterpret_cast<const float2*>(dfeat + o + a);
-          du[a] = f.x > 0.0f ? d.x : 0.0f;
-          du[a + 1] = f.y > 0.0f ? d.y : 0.0f;
+        for (int a = 0; a < kDP; ++a) {
+          fv[a] = feat[o + 32 * a];
+          dv[a] = dfeat[o + 32 * a];
         }
+#pragma unroll
+        for (int a = 0; a < kDP; ++a) du[a] = fv[a] > 0.0f ? dv[a] : 0.0f;
 #pragma unroll
         for (int p = 0; p < kDP / 2; ++p) dub[p] = pack_bf16(du[2 * p], du[2 * p + 1]);
       }
