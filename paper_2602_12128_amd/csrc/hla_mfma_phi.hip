@@ -401,7 +401,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_fwd(Geom g, View X,
           }
           if (j == 3) u = mfma32_f16(a20, gb[0], u);
           float in[4] = {cur[4 * j], cur[4 * j + 1], cur[4 * j + 2], cur[4 * j + 3]};
-          asm volatile("" : "+v"(nxt), "+v"(in[0]), "+v"(in[1]), "+v"(in[2]), "+v"(in[3]));
+          asm volatile("" : "+v"(in[0]), "+v"(in[1]), "+v"(in[2]), "+v"(in[3]));  // not nxt: that would wait for the MFMAs
           __builtin_amdgcn_sched_barrier(0);
           uint32_t out[2];
           gelu_f16<2>(in, out);
