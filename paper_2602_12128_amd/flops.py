@@ -77,7 +77,7 @@ def kernel_model(name: str, d: int, d_phi: int, F: int, e: int = 2):
         "mfma_phi_forward_k": (d * e + kf, F * lin, "mfma"),
         "mfma_state": (d * e + kf, 2 * D * d + D, "hbm"),
         "mfma_query": (qf + d * e + 4, 2 * D * d + 2 * D, "hbm"),
-        "mfma_bwd_query": (2 * d * e + qf + 4 + qf, 4 * D * d, "hbm"),
+        "mfma_bwd_query": (d * e + qf + 4 + qf, 4 * D * d, "hbm"),   # dO, features, den in; feature grads out
         "mfma_bwd_key": (d * e + kf + d * e + kf, 4 * D * d, "hbm"),
         "mfma_phi_backward_q": (2 * d * e + 2 * qf, lin_b, "mfma"),
         "mfma_phi_backward_k": (2 * d * e + 2 * kf, F * lin_b, "mfma"),
