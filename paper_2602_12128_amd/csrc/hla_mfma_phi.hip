@@ -98,6 +98,27 @@ __device__ __forceinline__ void gelu_grad_f16(const float (&in)[2 * NCH], f16x2 
   for (int i = 0; i < NCH; ++i) out[i] = __builtin_elementwise_fma(xc[i], p[i], splat16(0.5f));
 }
 
+// The same derivative fit on inputs that are already packed fp16 (pre-activation + bias).
+template <int NCH>
+__device__ __forceinline__ void gelu_grad_h(const f16x2 (&x)[NCH], f16x2 (&out)[NCH]) {
+  constexpr float c[8] = {0.183228f, -0.11377f, 0.117554f, -0.113403f, 0.0830688f, -0.0742188f, 0.0771484f, -0.0344238f};
+  f16x2 xc[NCH], w[NCH], p[NCH];
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) xc[i] = clamp4(x[i]);
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) w[i] = xc[i] * xc[i];
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) w[i] = __builtin_elementwise_fma(w[i], splat16(0.125f), splat16(-1.0f));
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) p[i] = __builtin_elementwise_fma(splat16(c[7]), w[i], splat16(c[6]));
+#pragma unroll
+  for (int k = 5; k >= 0; --k)
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) p[i] = __builtin_elementwise_fma(p[i], w[i], splat16(c[k]));
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) out[i] = __builtin_elementwise_fma(xc[i], p[i], splat16(0.5f));
+}
+
 // ---- packed weights of one (map, head) in global memory ---------------------------------------
 template <int D>
 struct Packed {
@@ -106,7 +127,9 @@ struct Packed {
   static constexpr int kW2B = kW2A + D * 32 * 2;      // bf16 [D/32][64][8]: A operand of dg^T = W2 du^T
   static constexpr int kB1 = kW2B + D * 16 * 2;       // fp32 [D]
   static constexpr int kB2 = kB1 + D * 4;             // fp32 [8]
-  static constexpr int kBytes = kB2 + 32;
+  static constexpr int kB1A = kB2 + 32;               // fp32 [D/32][2][16]: b1 in accumulator order, i.e.
+                                                      // entry (rb, gl, i) is b1[32 rb + 8 (i/4) + 4 gl + i%4]
+  static constexpr int kBytes = kB1A + D * 4;
 };
 
 // hidden unit that k-slot (ks2, gl, j) of the second-layer contraction stands for: the slots
@@ -145,6 +168,11 @@ __global__ void k_pack_phi(PhiF32 w, int dphi, unsigned char* __restrict__ out) 
   }
   for (int i = threadIdx.x; i < D; i += blockDim.x) b1[i] = w.b1[mh * D + i];
   for (int i = threadIdx.x; i < 8; i += blockDim.x) b2[i] = i < dphi ? w.b2[mh * dphi + i] : 0.0f;
+  float* b1a = reinterpret_cast<float*>(base + Packed<D>::kB1A);
+  for (int i = threadIdx.x; i < D; i += blockDim.x) {
+    const int rb = i / 32, gl = (i / 16) % 2, k = i % 16;
+    b1a[i] = w.b1[mh * D + 32 * rb + 8 * (k / 4) + 4 * gl + k % 4];
+  }
 }
 
 // ---- LDS layout ---------------------------------------------------------------------------------
@@ -158,7 +186,8 @@ struct PhiSmem {
   static constexpr int kRow = D * 2;                  // bytes per row
   static constexpr int kW1 = D * D * 2;
   static constexpr int kW2 = BACKWARD ? D * 16 * 2 : D * 32 * 2;  // W2B (backward) or W2A (forward)
-  static constexpr int kMap = kW1 + kW2 + D * 4 + 32;  // + b1 + b2
+  static constexpr int kB1A = kW1 + kW2 + D * 4 + 32;  // bias in accumulator order, after b1 + b2
+  static constexpr int kMap = kB1A + D * 4;
   // backward adds a 16-row transpose tile per wave for whole-row stores of dX
   static constexpr int total(int nmaps, int waves) {
     return nmaps * kMap + (BACKWARD ? waves * RowTile<D, 16>::kBytes : 0);
@@ -180,7 +209,7 @@ __device__ __forceinline__ void load_weights(unsigned char* dst, const unsigned 
   using PK = Packed<D>;
   constexpr int N1 = D * SM::kChunks;                              // 16-byte chunks of W1^T
   constexpr int N2 = (BACKWARD ? D * 16 * 2 : D * 32 * 2) / 16;    // 16-byte chunks of the W2 image
-  constexpr int NB = D + 8;                                        // floats of b1 and b2
+  constexpr int NB = D + 8 + D;                                    // floats of b1, b2 and the bias image
   constexpr int I1 = (N1 + THREADS - 1) / THREADS, I2 = (N2 + THREADS - 1) / THREADS;
   const unsigned char* w2 = src + (BACKWARD ? PK::kW2B : PK::kW2A);
   const int t = threadIdx.x;
@@ -472,86 +501,178 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_bwd(Geom g, View X,
   const int stride = gridDim.x * WAVES;
   int tile = blockIdx.x * WAVES + wave;
   int b = 0, h = 0, n0 = 0;
-  u32x4 xb[NKS], xn[NKS];
+  // The tile's inputs live in xb only: the next tile's loads are issued into xb as soon as the
+  // last first-layer MFMA of the current tile has read it (one and a half stages before the end).
+  u32x4 xb[NKS];
   if (tile < tm.total) {
     tm.decode(tile, b, h, n0);
-    load_x<D>(X, b, h, n0 + r, g.N, gl, xn);
+    load_x<D>(X, b, h, n0 + r, g.N, gl, xb);
   }
+  // du^T of one map as B operand of a single 16-slot step: slot (gl, j) is feature 8gl + j (only
+  // gl = 0 is used); zero where the ReLU was closed
+  auto load_du = [&](int64_t th, bool live, int m) -> u32x4 {
+    u32x4 d;
+    d[0] = d[1] = d[2] = d[3] = 0u;
+    if (live && gl == 0) {
+      const int64_t o = g.fidx(th, (map0 + m) * kDP);
+      float fv[kDP], dv[kDP];  // both loaded unconditionally: one round trip, not six
+#pragma unroll
+      for (int a = 0; a < kDP; ++a) {
+        fv[a] = feat[o + 32 * a];
+        dv[a] = dfeat[o + 32 * a];
+      }
+#pragma unroll
+      for (int p = 0; p < kDP / 2; ++p)
+        d[p] = pack_bf16(fv[2 * p] > 0.0f ? dv[2 * p] : 0.0f, fv[2 * p + 1] > 0.0f ? dv[2 * p + 1] : 0.0f);
+    }
+    return d;
+  };
+  auto zero_acc = []() {  // a constant: becomes the inline 0 of the MFMA's C operand
+    f32x16 z;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) z[i] = 0.0f;
+    return z;
+  };
+  // the first layer accumulates on top of its bias: the lane's 16 entries of a 32-row block
+  auto bias_acc = [&](const unsigned char* wmap, int rb) {
+    f32x16 z;
+    const unsigned char* p = wmap + SM::kB1A + (rb * 2 + gl) * 64;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const f32x4 v = *reinterpret_cast<const f32x4*>(p + 16 * i);
+      z[4 * i] = v[0];
+      z[4 * i + 1] = v[1];
+      z[4 * i + 2] = v[2];
+      z[4 * i + 3] = v[3];
+    }
+    return z;
+  };
   for (; tile < tm.total; tile += stride) {
     const int n = n0 + r;
     const bool live = n < g.N;
     const int64_t th = g.th(b, h, live ? n : 0);
-    const int ob = b, oh = h, on0 = n0;  // this tile's coordinates (b, h, n0 move on to the next tile below)
-#pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) xb[ks] = xn[ks];
-    {
-      const int nt = tile + stride < tm.total ? tile + stride : tile;
-      tm.decode(nt, b, h, n0);
-      load_x<D>(X, b, h, n0 + r, g.N, gl, xn);
-    }
+    const int ob = b, oh = h, on0 = n0;  // this tile's coordinates
+    const bool more_tiles = tile + stride < tm.total;
+    if (more_tiles) tm.decode(tile + stride, b, h, n0);  // b, h, n0 now name the next tile
     f32x16 dx[NRB];
 #pragma unroll
-    for (int rb = 0; rb < NRB; ++rb)
+    for (int rb = 0; rb < NRB; ++rb) dx[rb] = zero_acc();
+    // Software pipeline over 32-row blocks of the hidden layer, block t = m * NRB + rb.  Stage t:
+    //   vector ALU : dh(t) = dg(t) * GELU'(hidden(t) + b1), packed as the B operand of dx
+    //   matrix pipe: hidden(t+1) = W1^T X^T block (A: 16-byte LDS reads), dg(t) = W2 du^T block,
+    //                dx += W1 dh(t-1)^T (A: transpose reads of the same LDS copy),
+    // the MFMAs two or three at a time between quarters of the vector-ALU work, their LDS
+    // operands read one step ahead.  Blocks before the first / after the last alias valid LDS
+    // and meet zero operands or are dropped.
+    f32x16 cur, nxt;
+    constexpr int kPer = NKS / 4;  // first-layer MFMAs per slice
+    u32x4 an[kPer];                // their A operands, read one slice ahead
+    {
+      u32x4 a0[NKS];
 #pragma unroll
-      for (int i = 0; i < 16; ++i) dx[rb][i] = 0.0f;
+      for (int ks = 0; ks < NKS; ++ks) a0[ks] = *reinterpret_cast<const u32x4*>(smem + a_off[ks]);
+      cur = bias_acc(smem, 0);
+#pragma unroll
+      for (int ks = 0; ks < NKS; ++ks) cur = mfma32(a0[ks], xb[ks], cur);
+#pragma unroll
+      for (int t = 0; t < kPer; ++t)
+        an[t] = *reinterpret_cast<const u32x4*>(smem + (1 % NRB) * 32 * SM::kRow + a_off[t]);
+    }
+    u32x4 dub = load_du(th, live, 0);
+    u32x4 dhp[2];  // dh of the previous block (two 16-slot steps)
+    dhp[0][0] = dhp[0][1] = dhp[0][2] = dhp[0][3] = 0u;
+    dhp[1] = dhp[0];
 #pragma unroll 1
     for (int m = 0; m < nmaps; ++m) {  // nmaps == NMAPS, passed at run time so this stays a loop
       const unsigned char* wm = smem + m * SM::kMap;
-      // du^T as B operand of one 16-slot step: slot (gl, j) is feature 8gl + j (only gl = 0 is used)
-      u32x4 dub;
-      dub[0] = dub[1] = dub[2] = dub[3] = 0u;
-      if (live && gl == 0) {
-        const int64_t o = g.fidx(th, (map0 + m) * kDP);
-        float fv[kDP], dv[kDP], du[kDP];  // both loaded unconditionally: one round trip, not six
-#pragma unroll
-        for (int a = 0; a < kDP; ++a) {
-          fv[a] = feat[o + 32 * a];
-          dv[a] = dfeat[o + 32 * a];
-        }
-#pragma unroll
-        for (int a = 0; a < kDP; ++a) du[a] = fv[a] > 0.0f ? dv[a] : 0.0f;
-#pragma unroll
-        for (int p = 0; p < kDP / 2; ++p) dub[p] = pack_bf16(du[2 * p], du[2 * p + 1]);
-      }
-      f32x16 acc[NRB];
-#pragma unroll
-      for (int rb = 0; rb < NRB; ++rb) first_layer_block<D, true>(wm, a_off, xb, gl, rb, acc[rb]);
-      u32x4 dhb[NKS];
+      const bool last_map = m + 1 == nmaps;
+      const u32x4 dubn = load_du(th, live, last_map ? m : m + 1);
 #pragma unroll
       for (int rb = 0; rb < NRB; ++rb) {
-        f32x16 dg;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) dg[i] = 0.0f;
+        // block t+1 (first layer, this stage) and block t+2 (whose first operands the last slice reads)
+        const unsigned char* a1_base = (rb + 1 < NRB ? wm : (last_map ? wm : wm + SM::kMap)) + ((rb + 1) % NRB) * 32 * SM::kRow;
+        const unsigned char* a2_base = (rb + 2 < NRB ? wm : (last_map ? wm : wm + SM::kMap)) + ((rb + 2) % NRB) * 32 * SM::kRow;
+        const unsigned char* wp = rb > 0 ? wm : (m > 0 ? wm - SM::kMap : wm);
+        const int ks2p = 2 * ((rb + NRB - 1) % NRB);  // first of the two 16-slot steps of block t-1
         const u32x4 a2 = *reinterpret_cast<const u32x4*>(wm + SM::kW1 + (rb * 64 + lane) * 16);
-        dg = mfma32(a2, dub, dg);
+        const f32x16 dg = mfma32(a2, dub, zero_acc());
+        nxt = bias_acc(rb + 1 < NRB ? wm : (last_map ? wm : wm + SM::kMap), (rb + 1) % NRB);
+        u32x4 dhc[2];
+        // transpose-read operands of the first dx step of this stage
+        u32x2 tlo[NRB / 2], thi[NRB / 2];
 #pragma unroll
-        for (int half = 0; half < 2; ++half) {
-          float in[8];
-#pragma unroll
-          for (int e = 0; e < 8; ++e) in[e] = acc[rb][8 * half + e];
-          f16x2 gp[4];
-          gelu_grad_f16<4>(in, gp);
-#pragma unroll
-          for (int p = 0; p < 4; ++p) {
-            const int i = 8 * half + 2 * p;
-            dhb[2 * rb + half][p] = pack_bf16(dg[i] * static_cast<float>(gp[p][0]),
-                                              dg[i + 1] * static_cast<float>(gp[p][1]));
-          }
+        for (int x = 0; x < NRB / 2; ++x) {
+          tlo[x] = lds_read_tr16(wp + ks2p * 16 * SM::kRow + t_off[0][x]);
+          thi[x] = lds_read_tr16(wp + ks2p * 16 * SM::kRow + t_off[1][x]);
         }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          asm volatile("" : "+v"(nxt));
+          // first layer of block t+1 (there is none after the last block, and xb already belongs
+          // to the next tile's loads by then)
+          if (rb + 1 < NRB || !last_map) {
+#pragma unroll
+            for (int t = 0; t < kPer; ++t) {
+              nxt = mfma32(an[t], xb[j * kPer + t], nxt);
+              an[t] = j < 3 ? *reinterpret_cast<const u32x4*>(a1_base + a_off[(j + 1) * kPer + t])
+                            : *reinterpret_cast<const u32x4*>(a2_base + a_off[t]);
+            }
+          }
+          // dx += W1[row blocks of this slice, hidden of block t-1] dh(t-1)^T
+#pragma unroll
+          for (int x = 0; x < NRB / 2; ++x) {
+            const int rbx = (j % 2) * (NRB / 2) + x;
+            u32x4 a;
+            a[0] = tlo[x][0];
+            a[1] = tlo[x][1];
+            a[2] = thi[x][0];
+            a[3] = thi[x][1];
+            dx[rbx] = mfma32(a, dhp[j / 2], dx[rbx]);
+            // operands of the next slice's dx step (the last slice reads ahead into valid LDS)
+            const int jn = j + 1 < 4 ? j + 1 : 3;
+            const int rbn = (jn % 2) * (NRB / 2) + x;
+            tlo[x] = lds_read_tr16(wp + (ks2p + jn / 2) * 16 * SM::kRow + t_off[0][rbn]);
+            thi[x] = lds_read_tr16(wp + (ks2p + jn / 2) * 16 * SM::kRow + t_off[1][rbn]);
+          }
+          // the next tile's inputs: xb is free once the last first-layer MFMA has been issued
+          if (last_map && rb == NRB - 2 && j == 3 && more_tiles) load_x<D>(X, b, h, n0 + r, g.N, gl, xb);
+          f16x2 xin[2];
+          xin[0] = to_f16x2(cur[4 * j], cur[4 * j + 1]);
+          xin[1] = to_f16x2(cur[4 * j + 2], cur[4 * j + 3]);
+          asm volatile("" : "+v"(xin[0]), "+v"(xin[1]));
+          __builtin_amdgcn_sched_barrier(0);
+          f16x2 gp[2];
+          gelu_grad_h<2>(xin, gp);
+          uint32_t o0 = pack_bf16(dg[4 * j] * static_cast<float>(gp[0][0]), dg[4 * j + 1] * static_cast<float>(gp[0][1]));
+          uint32_t o1 = pack_bf16(dg[4 * j + 2] * static_cast<float>(gp[1][0]), dg[4 * j + 3] * static_cast<float>(gp[1][1]));
+          asm volatile("" : "+v"(o0), "+v"(o1));
+          dhc[j / 2][2 * (j % 2)] = o0;
+          dhc[j / 2][2 * (j % 2) + 1] = o1;
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        dhp[0] = dhc[0];
+        dhp[1] = dhc[1];
+        cur = nxt;
       }
+      dub = dubn;
+    }
+    // dx of the last block
+    {
+      const unsigned char* wp = smem + (nmaps - 1) * SM::kMap;
+      constexpr int ks2p = 2 * (NRB - 1);
 #pragma unroll
-      for (int ks2 = 0; ks2 < NKS; ++ks2)
+      for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
-        for (int rb = 0; rb < NRB; ++rb) {
-          const unsigned char* p = wm + ks2 * 16 * SM::kRow;
-          const u32x2 lo = lds_read_tr16(p + t_off[0][rb]);
-          const u32x2 hi = lds_read_tr16(p + t_off[1][rb]);
+        for (int rbx = 0; rbx < NRB; ++rbx) {
+          const u32x2 lo = lds_read_tr16(wp + (ks2p + hf) * 16 * SM::kRow + t_off[0][rbx]);
+          const u32x2 hi = lds_read_tr16(wp + (ks2p + hf) * 16 * SM::kRow + t_off[1][rbx]);
           u32x4 a;
           a[0] = lo[0];
           a[1] = lo[1];
           a[2] = hi[0];
           a[3] = hi[1];
-          dx[rb] = mfma32(a, dhb[ks2], dx[rb]);
+          dx[rbx] = mfma32(a, dhp[hf], dx[rbx]);
         }
     }
     store_rows_bf16<D, 16>(dx, 1.0f, lane, ttile, [&](int t) -> bf16_t* {
