@@ -127,9 +127,7 @@ struct Packed {
   static constexpr int kW2B = kW2A + D * 32 * 2;      // bf16 [D/32][64][8]: A operand of dg^T = W2 du^T
   static constexpr int kB1 = kW2B + D * 16 * 2;       // fp32 [D]
   static constexpr int kB2 = kB1 + D * 4;             // fp32 [8]
-  static constexpr int kB1A = kB2 + 32;               // fp32 [D/32][2][16]: b1 in accumulator order, i.e.
-                                                      // entry (rb, gl, i) is b1[32 rb + 8 (i/4) + 4 gl + i%4]
-  static constexpr int kBytes = kB1A + D * 4;
+  static constexpr int kBytes = kB2 + 32;
 };
 
 // hidden unit that k-slot (ks2, gl, j) of the second-layer contraction stands for: the slots
@@ -168,11 +166,6 @@ __global__ void k_pack_phi(PhiF32 w, int dphi, unsigned char* __restrict__ out) 
   }
   for (int i = threadIdx.x; i < D; i += blockDim.x) b1[i] = w.b1[mh * D + i];
   for (int i = threadIdx.x; i < 8; i += blockDim.x) b2[i] = i < dphi ? w.b2[mh * dphi + i] : 0.0f;
-  float* b1a = reinterpret_cast<float*>(base + Packed<D>::kB1A);
-  for (int i = threadIdx.x; i < D; i += blockDim.x) {
-    const int rb = i / 32, gl = (i / 16) % 2, k = i % 16;
-    b1a[i] = w.b1[mh * D + 32 * rb + 8 * (k / 4) + 4 * gl + k % 4];
-  }
 }
 
 // ---- LDS layout ---------------------------------------------------------------------------------
@@ -186,8 +179,7 @@ struct PhiSmem {
   static constexpr int kRow = D * 2;                  // bytes per row
   static constexpr int kW1 = D * D * 2;
   static constexpr int kW2 = BACKWARD ? D * 16 * 2 : D * 32 * 2;  // W2B (backward) or W2A (forward)
-  static constexpr int kB1A = kW1 + kW2 + D * 4 + 32;  // bias in accumulator order, after b1 + b2
-  static constexpr int kMap = kB1A + D * 4;
+  static constexpr int kMap = kW1 + kW2 + D * 4 + 32;  // then b1 [D] and b2 [8] in fp32
   // backward adds a 16-row transpose tile per wave for whole-row stores of dX
   static constexpr int total(int nmaps, int waves) {
     return nmaps * kMap + (BACKWARD ? waves * RowTile<D, 16>::kBytes : 0);
@@ -209,7 +201,7 @@ __device__ __forceinline__ void load_weights(unsigned char* dst, const unsigned 
   using PK = Packed<D>;
   constexpr int N1 = D * SM::kChunks;                              // 16-byte chunks of W1^T
   constexpr int N2 = (BACKWARD ? D * 16 * 2 : D * 32 * 2) / 16;    // 16-byte chunks of the W2 image
-  constexpr int NB = D + 8 + D;                                    // floats of b1, b2 and the bias image
+  constexpr int NB = D + 8;                                        // floats of b1 and b2
   constexpr int I1 = (N1 + THREADS - 1) / THREADS, I2 = (N2 + THREADS - 1) / THREADS;
   const unsigned char* w2 = src + (BACKWARD ? PK::kW2B : PK::kW2A);
   const int t = threadIdx.x;
@@ -536,10 +528,10 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_bwd(Geom g, View X,
   // the first layer accumulates on top of its bias: the lane's 16 entries of a 32-row block
   auto bias_acc = [&](const unsigned char* wmap, int rb) {
     f32x16 z;
-    const unsigned char* p = wmap + SM::kB1A + (rb * 2 + gl) * 64;
+    const float* b1 = reinterpret_cast<const float*>(wmap + SM::kW1 + SM::kW2) + 32 * rb + 4 * gl;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const f32x4 v = *reinterpret_cast<const f32x4*>(p + 16 * i);
+    for (int i = 0; i < 4; ++i) {  // registers 4i..4i+3 are hidden units 32 rb + 8 i + 4 gl + 0..3
+      const f32x4 v = *reinterpret_cast<const f32x4*>(b1 + 8 * i);
       z[4 * i] = v[0];
       z[4 * i + 1] = v[1];
       z[4 * i + 2] = v[2];
