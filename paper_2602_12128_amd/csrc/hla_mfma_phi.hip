@@ -29,12 +29,16 @@ constexpr int kDP = 6;
 #endif
 
 // ---- GELU on the vector ALU, two values per instruction in packed fp16 -------------------------
-// Phi(x) - 1/2 = xc * P(w) with xc = clamp(x, +-4) and w = xc^2/8 - 1 in [-1, 1]: in this variable
-// the coefficients of the minimax fit stay below 0.2, so a Horner chain of fp16 FMAs keeps its
-// rounding error near 2^-12 per step.  Evaluated end to end in fp16 the absolute GELU error is at
-// most 3.8e-3 (rms 3.5e-4 for standard-normal inputs): a quarter of what rounding an exact GELU
-// to bf16 would cost, which is why the hidden layer is handed to the second layer in fp16.
-// Pre-activations must stay below the fp16 range (65504) in magnitude.
+// The first layer is computed at a quarter of its scale (W1 and b1 are packed times 1/4, an exact
+// scaling), so the vector ALU sees y = x/4.  With yc = clamp(y, +-1) and v = yc^2 - 1/2 in
+// [-1/2, 1/2]:   Phi(x) - 1/2 = yc * P(v),   GELU(x)/4 = y * (1/2 + yc * P(v)),
+// GELU'(x) = 1/2 + yc * Q(v); the factor 4 is folded into the packed second-layer weights.  In this
+// variable v costs one FMA, and a Horner chain of fp16 FMAs keeps its rounding error near 2^-12
+// per step.  Evaluated end to end in fp16 the absolute GELU error is at most 3.7e-3 (rms 3.5e-4
+// for standard-normal inputs): a quarter of what rounding an exact GELU to bf16 would cost, which
+// is why the hidden layer is handed to the second layer in fp16.
+// Pre-activations must stay below four times the fp16 range (65504) in magnitude.
+constexpr float kHiddenScale = 0.25f;
 __device__ __forceinline__ f16x2 splat16(float v) {
   f16x2 r;
   r[0] = static_cast<_Float16>(v);
@@ -47,85 +51,61 @@ __device__ __forceinline__ f16x2 to_f16x2(float a, float b) {
   r[1] = static_cast<_Float16>(b);
   return r;
 }
-__device__ __forceinline__ f16x2 clamp4(f16x2 x) {
-  return __builtin_elementwise_min(__builtin_elementwise_max(x, splat16(-4.0f)), splat16(4.0f));
+__device__ __forceinline__ f16x2 clamp1(f16x2 x) {
+  return __builtin_elementwise_min(__builtin_elementwise_max(x, splat16(-1.0f)), splat16(1.0f));
 }
 // NCH independent chains are advanced in lockstep: a packed-fp16 instruction cannot issue right
 // behind the one that produces its input, so a single Horner chain would leave every other issue
 // slot empty.
-// GELU of 2*NCH values as packed fp16 pairs: degree-6 fit of (Phi - 1/2)/xc in w
+// GELU(x)/4 of 2*NCH values y = x/4 as packed fp16 pairs: degree-6 fit of (Phi - 1/2)/yc in v
 template <int NCH>
 __device__ __forceinline__ void gelu_f16(const float (&in)[2 * NCH], uint32_t (&out)[NCH]) {
-  constexpr float c[7] = {0.175903f, -0.0845947f, 0.0556946f, -0.0344849f, 0.0227356f, -0.0177002f, 0.00738144f};
-  f16x2 x[NCH], xc[NCH], w[NCH], p[NCH];
+  constexpr float c[7] = {0.703613f, -0.676758f, 0.891113f, -1.10352f, 1.45508f, -2.26562f, 1.88965f};
+  f16x2 y[NCH], yc[NCH], v[NCH], p[NCH];
 #pragma unroll
-  for (int i = 0; i < NCH; ++i) x[i] = to_f16x2(in[2 * i], in[2 * i + 1]);
+  for (int i = 0; i < NCH; ++i) y[i] = to_f16x2(in[2 * i], in[2 * i + 1]);
 #pragma unroll
-  for (int i = 0; i < NCH; ++i) xc[i] = clamp4(x[i]);
+  for (int i = 0; i < NCH; ++i) yc[i] = clamp1(y[i]);
 #pragma unroll
-  for (int i = 0; i < NCH; ++i) w[i] = xc[i] * xc[i];
+  for (int i = 0; i < NCH; ++i) v[i] = __builtin_elementwise_fma(yc[i], yc[i], splat16(-0.5f));
 #pragma unroll
-  for (int i = 0; i < NCH; ++i) w[i] = __builtin_elementwise_fma(w[i], splat16(0.125f), splat16(-1.0f));
-#pragma unroll
-  for (int i = 0; i < NCH; ++i) p[i] = __builtin_elementwise_fma(splat16(c[6]), w[i], splat16(c[5]));
+  for (int i = 0; i < NCH; ++i) p[i] = __builtin_elementwise_fma(splat16(c[6]), v[i], splat16(c[5]));
 #pragma unroll
   for (int k = 4; k >= 0; --k)
 #pragma unroll
-    for (int i = 0; i < NCH; ++i) p[i] = __builtin_elementwise_fma(p[i], w[i], splat16(c[k]));
+    for (int i = 0; i < NCH; ++i) p[i] = __builtin_elementwise_fma(p[i], v[i], splat16(c[k]));
 #pragma unroll
-  for (int i = 0; i < NCH; ++i) p[i] = __builtin_elementwise_fma(xc[i], p[i], splat16(0.5f));
+  for (int i = 0; i < NCH; ++i) p[i] = __builtin_elementwise_fma(yc[i], p[i], splat16(0.5f));
 #pragma unroll
-  for (int i = 0; i < NCH; ++i) out[i] = __builtin_bit_cast(uint32_t, x[i] * p[i]);
+  for (int i = 0; i < NCH; ++i) out[i] = __builtin_bit_cast(uint32_t, y[i] * p[i]);
 }
-// d/dx [x Phi(x)] of 2*NCH values: degree-7 fit of (GELU' - 1/2)/xc in w, |error| <= 1.4e-3
+// d/dx [x Phi(x)] at x = 4y for 2*NCH values y: degree-7 fit of (GELU' - 1/2)/yc in v,
+// |error| <= 1.4e-3
 template <int NCH>
 __device__ __forceinline__ void gelu_grad_f16(const float (&in)[2 * NCH], f16x2 (&out)[NCH]) {
-  constexpr float c[8] = {0.183228f, -0.11377f, 0.117554f, -0.113403f, 0.0830688f, -0.0742188f, 0.0771484f, -0.0344238f};
-  f16x2 xc[NCH], w[NCH], p[NCH];
+  constexpr float c[8] = {0.73291f, -0.910156f, 1.88086f, -3.62891f, 5.31641f, -9.5f, 19.75f, -17.625f};
+  f16x2 yc[NCH], v[NCH], p[NCH];
 #pragma unroll
-  for (int i = 0; i < NCH; ++i) xc[i] = clamp4(to_f16x2(in[2 * i], in[2 * i + 1]));
+  for (int i = 0; i < NCH; ++i) yc[i] = clamp1(to_f16x2(in[2 * i], in[2 * i + 1]));
 #pragma unroll
-  for (int i = 0; i < NCH; ++i) w[i] = xc[i] * xc[i];
+  for (int i = 0; i < NCH; ++i) v[i] = __builtin_elementwise_fma(yc[i], yc[i], splat16(-0.5f));
 #pragma unroll
-  for (int i = 0; i < NCH; ++i) w[i] = __builtin_elementwise_fma(w[i], splat16(0.125f), splat16(-1.0f));
-#pragma unroll
-  for (int i = 0; i < NCH; ++i) p[i] = __builtin_elementwise_fma(splat16(c[7]), w[i], splat16(c[6]));
+  for (int i = 0; i < NCH; ++i) p[i] = __builtin_elementwise_fma(splat16(c[7]), v[i], splat16(c[6]));
 #pragma unroll
   for (int k = 5; k >= 0; --k)
 #pragma unroll
-    for (int i = 0; i < NCH; ++i) p[i] = __builtin_elementwise_fma(p[i], w[i], splat16(c[k]));
+    for (int i = 0; i < NCH; ++i) p[i] = __builtin_elementwise_fma(p[i], v[i], splat16(c[k]));
 #pragma unroll
-  for (int i = 0; i < NCH; ++i) out[i] = __builtin_elementwise_fma(xc[i], p[i], splat16(0.5f));
-}
-
-// The same derivative fit on inputs that are already packed fp16 (pre-activation + bias).
-template <int NCH>
-__device__ __forceinline__ void gelu_grad_h(const f16x2 (&x)[NCH], f16x2 (&out)[NCH]) {
-  constexpr float c[8] = {0.183228f, -0.11377f, 0.117554f, -0.113403f, 0.0830688f, -0.0742188f, 0.0771484f, -0.0344238f};
-  f16x2 xc[NCH], w[NCH], p[NCH];
-#pragma unroll
-  for (int i = 0; i < NCH; ++i) xc[i] = clamp4(x[i]);
-#pragma unroll
-  for (int i = 0; i < NCH; ++i) w[i] = xc[i] * xc[i];
-#pragma unroll
-  for (int i = 0; i < NCH; ++i) w[i] = __builtin_elementwise_fma(w[i], splat16(0.125f), splat16(-1.0f));
-#pragma unroll
-  for (int i = 0; i < NCH; ++i) p[i] = __builtin_elementwise_fma(splat16(c[7]), w[i], splat16(c[6]));
-#pragma unroll
-  for (int k = 5; k >= 0; --k)
-#pragma unroll
-    for (int i = 0; i < NCH; ++i) p[i] = __builtin_elementwise_fma(p[i], w[i], splat16(c[k]));
-#pragma unroll
-  for (int i = 0; i < NCH; ++i) out[i] = __builtin_elementwise_fma(xc[i], p[i], splat16(0.5f));
+  for (int i = 0; i < NCH; ++i) out[i] = __builtin_elementwise_fma(yc[i], p[i], splat16(0.5f));
 }
 
 // ---- packed weights of one (map, head) in global memory ---------------------------------------
 template <int D>
 struct Packed {
-  static constexpr int kW1T = 0;                      // bf16 [D][D]: row = hidden unit, col = input channel
-  static constexpr int kW2A = kW1T + D * D * 2;       // fp16 [D/16][64][8]: A operand of u^T = W2^T g^T
-  static constexpr int kW2B = kW2A + D * 32 * 2;      // bf16 [D/32][64][8]: A operand of dg^T = W2 du^T
-  static constexpr int kB1 = kW2B + D * 16 * 2;       // fp32 [D]
+  static constexpr int kW1T = 0;                      // bf16 [D][D]: row = hidden unit, col = input channel; times 1/4
+  static constexpr int kW2A = kW1T + D * D * 2;       // fp16 [D/16][64][8]: A operand of u^T = W2^T g^T; times 4
+  static constexpr int kW2B = kW2A + D * 32 * 2;      // bf16 [D/32][64][8]: A operand of dg^T = W2 du^T; times 4
+  static constexpr int kB1 = kW2B + D * 16 * 2;       // fp32 [D]; times 1/4
   static constexpr int kB2 = kB1 + D * 4;             // fp32 [8]
   static constexpr int kBytes = kB2 + 32;
 };
@@ -150,21 +130,21 @@ __global__ void k_pack_phi(PhiF32 w, int dphi, unsigned char* __restrict__ out) 
   float* b2 = reinterpret_cast<float*>(base + Packed<D>::kB2);
   for (int i = threadIdx.x; i < D * D; i += blockDim.x) {
     const int hid = i / D, in = i % D;
-    w1t[i] = f32_to_bf16_bits(W1[in * D + hid]);
+    w1t[i] = f32_to_bf16_bits(kHiddenScale * W1[in * D + hid]);
   }
   for (int i = threadIdx.x; i < (D / 16) * 512; i += blockDim.x) {
     const int ks2 = i / 512, lane = (i / 8) % 64, j = i % 8;
     const int r = lane % 32, gl = lane / 32;
     const int n = hidden_of_slot(ks2, gl, j);
-    w2a[i] = r < dphi ? __builtin_bit_cast(uint16_t, static_cast<_Float16>(W2[n * dphi + r])) : 0;
+    w2a[i] = r < dphi ? __builtin_bit_cast(uint16_t, static_cast<_Float16>(W2[n * dphi + r] / kHiddenScale)) : 0;
   }
   for (int i = threadIdx.x; i < (D / 32) * 512; i += blockDim.x) {
     const int rb = i / 512, lane = (i / 8) % 64, j = i % 8;
     const int r = lane % 32, gl = lane / 32;
     const int a = 8 * gl + j;
-    w2b[i] = a < dphi ? f32_to_bf16_bits(W2[(32 * rb + r) * dphi + a]) : 0;
+    w2b[i] = a < dphi ? f32_to_bf16_bits(W2[(32 * rb + r) * dphi + a] / kHiddenScale) : 0;
   }
-  for (int i = threadIdx.x; i < D; i += blockDim.x) b1[i] = w.b1[mh * D + i];
+  for (int i = threadIdx.x; i < D; i += blockDim.x) b1[i] = kHiddenScale * w.b1[mh * D + i];
   for (int i = threadIdx.x; i < 8; i += blockDim.x) b2[i] = i < dphi ? w.b2[mh * dphi + i] : 0.0f;
 }
 
@@ -629,15 +609,16 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_bwd(Geom g, View X,
           }
           // the next tile's inputs: xb is free once the last first-layer MFMA has been issued
           if (last_map && rb == NRB - 2 && j == 3 && more_tiles) load_x<D>(X, b, h, n0 + r, g.N, gl, xb);
-          f16x2 xin[2];
-          xin[0] = to_f16x2(cur[4 * j], cur[4 * j + 1]);
-          xin[1] = to_f16x2(cur[4 * j + 2], cur[4 * j + 3]);
-          asm volatile("" : "+v"(xin[0]), "+v"(xin[1]));
+          float in[4] = {cur[4 * j], cur[4 * j + 1], cur[4 * j + 2], cur[4 * j + 3]};
+          asm volatile("" : "+v"(in[0]), "+v"(in[1]), "+v"(in[2]), "+v"(in[3]));
           __builtin_amdgcn_sched_barrier(0);
           f16x2 gp[2];
-          gelu_grad_h<2>(xin, gp);
-          uint32_t o0 = pack_bf16(dg[4 * j] * static_cast<float>(gp[0][0]), dg[4 * j + 1] * static_cast<float>(gp[0][1]));
-          uint32_t o1 = pack_bf16(dg[4 * j + 2] * static_cast<float>(gp[1][0]), dg[4 * j + 3] * static_cast<float>(gp[1][1]));
+          gelu_grad_f16<2>(in, gp);
+          // dg * GELU' in fp32 with the fp16 factor read in place (mixed-precision FMA)
+          uint32_t o0 = pack_bf16(__builtin_fmaf(static_cast<float>(gp[0][0]), dg[4 * j], 0.0f),
+                                  __builtin_fmaf(static_cast<float>(gp[0][1]), dg[4 * j + 1], 0.0f));
+          uint32_t o1 = pack_bf16(__builtin_fmaf(static_cast<float>(gp[1][0]), dg[4 * j + 2], 0.0f),
+                                  __builtin_fmaf(static_cast<float>(gp[1][1]), dg[4 * j + 3], 0.0f));
           asm volatile("" : "+v"(o0), "+v"(o1));
           dhc[j / 2][2 * (j % 2)] = o0;
           dhc[j / 2][2 * (j % 2) + 1] = o1;
