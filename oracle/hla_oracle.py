@@ -14,8 +14,8 @@ v is [N, d].
 Pins (tests/test_oracle_*.py): brute force == factorized; F=1 == textbook linear attention;
 d_phi=1, identical-key, one-hot and N=1 closed forms; row normalisation; convexity; permutation
 invariance; homogeneity (rational-function form); the sequential state update; Lemma 4.1; GELU
-against tabulated normal-CDF values; both backward routes against central finite differences.
-No function here is "parity unpinned".
+against tabulated normal-CDF values; both backward routes, and the feature-map weight gradients,
+against central finite differences.  No function here is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -66,6 +66,22 @@ def phi_backward(dfeat, x, W1, b1, W2, b2):
     dg = du @ np.asarray(W2, F64).T
     dh = dg * gelu_erf_grad(h)
     return dh @ np.asarray(W1, F64).T
+
+
+def phi_weight_grads(dfeat, x, W1, b1, W2, b2):
+    """Gradient of a scalar loss w.r.t. the weights of one feature map given its gradient w.r.t.
+    phi(x) for the N rows of x (same chain rule as phi_backward, App. A.1 layers; the paper trains
+    these layers, Sec. 5 stage 1, and leaves the formulas to autograd):
+      du = dfeat * [u > 0];  dW2 = g^T du;  db2 = sum_n du;  dg = du W2^T;
+      dh = dg * GELU'(h);    dW1 = x^T dh;  db1 = sum_n dh.
+    Returns (dW1 [d,d], db1 [d], dW2 [d,d_phi], db2 [d_phi])."""
+    x = np.asarray(x, F64)
+    _, h, u = phi_forward(x, W1, b1, W2, b2)
+    g = gelu_erf(h)
+    du = np.asarray(dfeat, F64) * (u > 0.0)
+    dg = du @ np.asarray(W2, F64).T
+    dh = dg * gelu_erf_grad(h)
+    return x.T @ dh, dh.sum(axis=0), g.T @ du, du.sum(axis=0)
 
 
 # --------------------------------------------------------------------------------------------
@@ -277,13 +293,20 @@ def hla_operator_forward(Q, K, V, F: int, d_phi: int, eps: float,
 def hla_operator_backward(Q, K, V, dO, F: int, d_phi: int, eps: float,
                           phi: Optional[Sequence[PhiWeights]] = None,
                           cu_seqlens: Optional[Sequence[int]] = None,
-                          route: str = "factorized"):
+                          route: str = "factorized", weight_grads: bool = False):
     """(dQ, dK, dV) with the shapes of Q, K, V for L = sum(O * dO).  With feature maps, dK sums
-    the contributions of the F key maps (they all read the same K)."""
+    the contributions of the F key maps (they all read the same K).  With weight_grads (needs
+    `phi`) a fourth result lists (dW1, db1, dW2, db2) for phi_q, phi_k1..phi_kF, each summed over
+    every sequence, head and token that shares the map."""
     B, H, N = V.shape[:3]
     dQ = np.zeros(Q.shape, F64)
     dK = np.zeros(K.shape, F64)
     dV = np.zeros(V.shape, F64)
+    wg = None
+    if weight_grads:
+        if phi is None:
+            raise ValueError("weight gradients need the feature maps")
+        wg = [[np.zeros_like(a) for a in m.astuple()] for m in phi]
     bwd = hla_backward_factorized if route == "factorized" else hla_backward_bruteforce
     for (b, lo, hi) in _units(B, N, cu_seqlens):
         if hi == lo:
@@ -302,6 +325,15 @@ def hla_operator_backward(Q, K, V, dO, F: int, d_phi: int, eps: float,
                 for f in range(F):
                     acc += phi_backward(dkfs[f], K[b, h, lo:hi], *phi[1 + f].astuple())
                 dK[b, h, lo:hi] = acc
+                if wg is not None:
+                    parts = [phi_weight_grads(dqf, Q[b, h, lo:hi], *phi[0].astuple())]
+                    parts += [phi_weight_grads(dkfs[f], K[b, h, lo:hi], *phi[1 + f].astuple())
+                              for f in range(F)]
+                    for m, part in enumerate(parts):
+                        for a, da in zip(wg[m], part):
+                            a += da
+    if wg is not None:
+        return dQ, dK, dV, [tuple(m) for m in wg]
     return dQ, dK, dV
 
 

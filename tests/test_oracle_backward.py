@@ -128,3 +128,63 @@ def test_operator_backward_feature_level_layout():
     dQ, dK, dV = orc.hla_operator_backward(Q, K, V, dO, F, dp, 1e-5)
     np.testing.assert_allclose(dK, _fd(f, K), rtol=1e-6, atol=1e-8)
     np.testing.assert_allclose(dQ, _fd(f, Q), rtol=1e-6, atol=1e-8)
+
+
+def test_phi_weight_grads_against_finite_differences():
+    # one feature map alone: L = sum(phi(x) * w), every weight entry perturbed in turn
+    rng = np.random.default_rng(54)
+    n, d, dp = 6, 5, 3
+    x = rng.standard_normal((n, d))
+    W1, b1 = rng.standard_normal((d, d)), rng.standard_normal(d)
+    W2, b2 = rng.standard_normal((d, dp)), rng.standard_normal(dp) + 0.5
+    w = rng.standard_normal((n, dp))
+    f = lambda: float((orc.phi_forward(x, W1, b1, W2, b2)[0] * w).sum())
+    dW1, db1, dW2, db2 = orc.phi_weight_grads(w, x, W1, b1, W2, b2)
+    np.testing.assert_allclose(dW1, _fd(f, W1), rtol=1e-6, atol=1e-8)
+    np.testing.assert_allclose(db1, _fd(f, b1), rtol=1e-6, atol=1e-8)
+    np.testing.assert_allclose(dW2, _fd(f, W2), rtol=1e-6, atol=1e-8)
+    np.testing.assert_allclose(db2, _fd(f, b2), rtol=1e-6, atol=1e-8)
+    # a transposed operand or a dropped GELU' would survive none of the above; the shapes pin
+    # the orientation (W1 acts from the right: rows = input channels)
+    assert dW1.shape == (d, d) and dW2.shape == (d, dp)
+    # rows are independent: the gradient of the whole batch is the sum of per-row gradients
+    parts = [orc.phi_weight_grads(w[i:i + 1], x[i:i + 1], W1, b1, W2, b2) for i in range(n)]
+    for k, whole in enumerate((dW1, db1, dW2, db2)):
+        np.testing.assert_allclose(sum(p[k] for p in parts), whole, rtol=1e-12, atol=1e-14)
+
+
+@pytest.mark.parametrize("packed", [False, True])
+def test_operator_weight_grads_against_finite_differences(packed):
+    # the whole operator: L = sum(O * dO) differentiated w.r.t. every weight of every map, with
+    # the maps shared by all heads, batch rows and packed sequences
+    rng = np.random.default_rng(55)
+    B, H, N, d, F, dp = (1, 2, 7, 3, 3, 2) if packed else (2, 2, 4, 3, 3, 2)
+    cu = [0, 3, 7] if packed else None
+    Q, K, V, dO = (rng.standard_normal((B, H, N, d)) for _ in range(4))
+    phi = [orc.PhiWeights(rng.standard_normal((d, d)), 0.3 * rng.standard_normal(d),
+                          rng.standard_normal((d, dp)), rng.standard_normal(dp) + 1.5)
+           for _ in range(1 + F)]
+    eps = 1e-4
+    f = lambda: float((orc.hla_operator_forward(Q, K, V, F, dp, eps, phi=phi, cu_seqlens=cu,
+                                                route="bruteforce") * dO).sum())
+    for route in ("factorized", "bruteforce"):
+        res = orc.hla_operator_backward(Q, K, V, dO, F, dp, eps, phi=phi, cu_seqlens=cu,
+                                        route=route, weight_grads=True)
+        assert len(res) == 4 and len(res[3]) == 1 + F
+        for m, grads in enumerate(res[3]):
+            for arr, g in zip(phi[m].astuple(), grads):
+                np.testing.assert_allclose(g, _fd(f, arr), rtol=5e-6, atol=5e-8)
+        # input gradients are unchanged by asking for the weight gradients
+        plain = orc.hla_operator_backward(Q, K, V, dO, F, dp, eps, phi=phi, cu_seqlens=cu,
+                                          route=route)
+        for a, b in zip(plain, res[:3]):
+            np.testing.assert_array_equal(a, b)
+
+
+def test_weight_grads_need_feature_maps():
+    rng = np.random.default_rng(56)
+    Q = np.abs(rng.standard_normal((1, 1, 3, 2)))
+    K = np.abs(rng.standard_normal((1, 1, 3, 4)))
+    V = rng.standard_normal((1, 1, 3, 2))
+    with pytest.raises(ValueError):
+        orc.hla_operator_backward(Q, K, V, V, 2, 2, 1e-6, weight_grads=True)
