@@ -127,6 +127,32 @@ hla_status hla_backward(hla_handle* h, int32_t B, int32_t H, int32_t N, const in
                         hla_tensor dO, hla_tensor dQ, hla_tensor dK, hla_tensor dV,
                         void* hip_stream);
 
+/* Optional outputs of hla_backward, PHI_MLP only: gradients of L = sum(O * dO) w.r.t. the weights
+ * of the 1+F feature maps (App. A.1 layers; the paper trains them, Sec. 5, and leaves the
+ * formulas to autograd): with du = d(feature) where the ReLU was open, dg = du W2^T,
+ * dh = dg * GELU'(h):  dW2 = GELU(h)^T du, db2 = sum du, dW1 = x^T dh, db1 = sum dh, summed over
+ * every batch row, sequence and token that uses the map (and over heads when the weights are
+ * shared).  DEVICE pointers to fp32 arrays owned by the caller, shaped and ordered like the
+ * weights (dW1 [d, d], db1 [d], dW2 [d, d_phi], db2 [d_phi], row-major); accumulation and the
+ * results are fp32 whatever io_dtype is.  If the weights were registered per head (any non-zero
+ * head stride) each array holds max_heads consecutive copies, head h at ptr + h * (elements of one
+ * copy), and a call with H < max_heads leaves the copies of heads >= H untouched. */
+typedef struct {
+  float* dW1;
+  float* db1;
+  float* dW2;
+  float* db2;
+} hla_phi_weight_grads;
+
+/* Register (maps != NULL, num_maps = 1+F, order phi_q, phi_k1, .., phi_kF) or clear (maps = NULL)
+ * the weight-gradient outputs.  While registered, every hla_backward OVERWRITES them on its
+ * stream after the input gradients; they must stay valid until that work has completed.  Needs a
+ * prior hla_set_phi_weights (HLA_ERR_STATE otherwise; registering new weights keeps the outputs).
+ * The first registration allocates the partial-sum workspace (synchronous; HLA_ERR_ALLOC on
+ * failure). */
+hla_status hla_set_phi_weight_grads(hla_handle* h, const hla_phi_weight_grads* maps,
+                                    int32_t num_maps);
+
 /* Release the workspace.  Synchronises the device first.  NULL is accepted. */
 hla_status hla_destroy(hla_handle* h);
 

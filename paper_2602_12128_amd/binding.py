@@ -22,7 +22,7 @@ HLA_PATH_AUTO, HLA_PATH_GENERIC, HLA_PATH_MFMA = 0, 1, 2
 EXPORTS = (
     "hla_create", "hla_set_phi_weights", "hla_forward", "hla_backward", "hla_destroy",
     "hla_status_string", "hla_active_path", "hla_profile_enable", "hla_profile_read",
-    "hla_read_workspace",
+    "hla_read_workspace", "hla_set_phi_weight_grads",
 )
 HLA_WS_FEATURES, HLA_WS_FEATURE_GRADS, HLA_WS_DENOMINATORS = 0, 1, 2
 
@@ -42,6 +42,10 @@ class hla_phi_weights(C.Structure):
         ("head_stride_W1", C.c_int64), ("head_stride_b1", C.c_int64),
         ("head_stride_W2", C.c_int64), ("head_stride_b2", C.c_int64),
     ]
+
+
+class hla_phi_weight_grads(C.Structure):
+    _fields_ = [("dW1", C.c_void_p), ("db1", C.c_void_p), ("dW2", C.c_void_p), ("db2", C.c_void_p)]
 
 
 class hla_tensor(C.Structure):
@@ -72,6 +76,8 @@ def load_library() -> C.CDLL:
     lib.hla_create.restype = C.c_int
     lib.hla_set_phi_weights.argtypes = [H, C.POINTER(hla_phi_weights), C.c_int32, C.c_void_p]
     lib.hla_set_phi_weights.restype = C.c_int
+    lib.hla_set_phi_weight_grads.argtypes = [H, C.POINTER(hla_phi_weight_grads), C.c_int32]
+    lib.hla_set_phi_weight_grads.restype = C.c_int
     lib.hla_forward.argtypes = [H, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32),
                                 C.c_int32, hla_tensor, hla_tensor, hla_tensor, hla_tensor,
                                 C.c_void_p]
@@ -133,6 +139,7 @@ class HLA:
         self._h = C.c_void_p()
         _check(self._lib.hla_create(C.byref(self.config), C.byref(self._h)), "hla_create")
         self._keepalive = None
+        self._keepalive_grads = None
 
     # -- hla_destroy
     def destroy(self):
@@ -166,6 +173,27 @@ class HLA:
         self._keepalive = list(maps)
         _check(self._lib.hla_set_phi_weights(self._h, arr, len(maps), _stream_ptr(stream)),
                "hla_set_phi_weights")
+
+    # -- hla_set_phi_weight_grads
+    def set_phi_weight_grads(self, maps: Optional[Sequence[dict]]):
+        """maps: [phi_q, phi_k1, .., phi_kF], each {'dW1','db1','dW2','db2'} contiguous fp32 device
+        tensors shaped like the weights (with the leading head dimension if the weights have
+        one), overwritten by every following backward; None switches the outputs off."""
+        import torch
+        if maps is None:
+            _check(self._lib.hla_set_phi_weight_grads(self._h, None, 0), "hla_set_phi_weight_grads")
+            self._keepalive_grads = None
+            return
+        arr = (hla_phi_weight_grads * len(maps))()
+        for i, m in enumerate(maps):
+            for k in ("dW1", "db1", "dW2", "db2"):
+                if m[k].dtype != torch.float32 or not m[k].is_contiguous():
+                    raise ValueError("weight gradients must be contiguous fp32 tensors")
+            arr[i] = hla_phi_weight_grads(m["dW1"].data_ptr(), m["db1"].data_ptr(),
+                                          m["dW2"].data_ptr(), m["db2"].data_ptr())
+        self._keepalive_grads = list(maps)
+        _check(self._lib.hla_set_phi_weight_grads(self._h, arr, len(maps)),
+               "hla_set_phi_weight_grads")
 
     @staticmethod
     def _cu(cu_seqlens: Optional[Sequence[int]]):

@@ -120,6 +120,7 @@ void free_all(hla_handle* hd) {
   (void)hipFree(hd->partial);
   (void)hipFree(hd->path_ws);
   (void)hipFree(hd->w_f32);
+  (void)hipFree(hd->wg_partial);
   for (auto& kv : hd->tables) {
     (void)hipFree(kv.second.dev);
     (void)hipFree(kv.second.seq_off_dev);
@@ -296,6 +297,31 @@ hla_status hla_set_phi_weights(hla_handle* hd, const hla_phi_weights* maps, int3
   return HLA_OK;
 }
 
+hla_status hla_set_phi_weight_grads(hla_handle* hd, const hla_phi_weight_grads* maps,
+                                    int32_t num_maps) {
+  if (hd == nullptr) return HLA_ERR_INVALID_ARG;
+  if (hd->cfg.phi_mode != HLA_PHI_MLP) return HLA_ERR_STATE;
+  if (maps == nullptr) {
+    hd->wg_on = false;
+    return HLA_OK;
+  }
+  if (!hd->have_weights) return HLA_ERR_STATE;
+  if (num_maps != 1 + hd->cfg.degree) return HLA_ERR_INVALID_ARG;
+  for (int m = 0; m < num_maps; ++m)
+    if (!maps[m].dW1 || !maps[m].db1 || !maps[m].dW2 || !maps[m].db2) return HLA_ERR_INVALID_ARG;
+  if (hd->wg_partial == nullptr) {
+    const Geom& g = hd->g;
+    hd->wg_part_floats = static_cast<int64_t>(g.d) * g.d + g.d + static_cast<int64_t>(g.d) * g.dphi + g.dphi;
+    // at most about 512 partial sums are ever in flight (a few per workgroup of one full grid),
+    // and never fewer than one per (map, head)
+    hd->wg_parts_cap = 512 + 2 * static_cast<int64_t>(num_maps) * hd->cfg.max_heads;
+    HLA_TRY(dev_alloc(&hd->wg_partial, hd->wg_parts_cap * hd->wg_part_floats));
+  }
+  for (int m = 0; m < num_maps; ++m) hd->wg_out[m] = maps[m];
+  hd->wg_on = true;
+  return HLA_OK;
+}
+
 hla_status hla_forward(hla_handle* hd, int32_t B, int32_t H, int32_t N, const int32_t* cu_seqlens,
                        int32_t num_seqs, hla_tensor Q, hla_tensor K, hla_tensor V, hla_tensor O,
                        void* hip_stream) {
@@ -369,7 +395,9 @@ hla_status hla_backward(hla_handle* hd, int32_t B, int32_t H, int32_t N, const i
   a.dK = make_view(dK);
   a.dV = make_view(dV);
   a.stream = static_cast<hipStream_t>(hip_stream);
-  return hd->path == HLA_PATH_MFMA ? mfma_backward(hd, a) : generic_backward(hd, a);
+  HLA_TRY(hd->path == HLA_PATH_MFMA ? mfma_backward(hd, a) : generic_backward(hd, a));
+  if (hd->wg_on) HLA_TRY(phi_weight_grads(hd, a));
+  return HLA_OK;
 }
 
 hla_status hla_read_workspace(hla_handle* hd, int32_t kind, float* host_dst, int64_t count,

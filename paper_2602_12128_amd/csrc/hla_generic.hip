@@ -22,6 +22,7 @@ constexpr int kMaxRows = 128;     // accumulator rows per thread in accumulate: 
 constexpr int kTokPerThread = 4;  // contract: tokens per thread
 constexpr int kDtTile = 8;        // dtensor: tokens per block
 constexpr int kPhiTile = 16;      // feature maps: tokens per block
+constexpr int kWgTile = 8;        // weight gradients: tokens staged per step
 constexpr int kMaxF = 4;
 
 __device__ __forceinline__ float gelu_erf(float h) {
@@ -200,6 +201,179 @@ __global__ void k_phi_backward(Geom g, PhiF32 w, View Q, View K, const float* __
       for (int t = 0; t < nt; ++t) dX.row<T>(b, h, n0 + t)[j] = from_float<T>(dx[t]);
     }
   }
+}
+
+// ---- weight gradients of the feature maps -----------------------------------------------------
+// dW1 = x^T dh, db1 = sum dh, dW2 = GELU(h)^T du, db2 = sum du over the tokens of a chunk; hidden
+// activations are recomputed.  grid (chunks, 1+F, heads_w), block DD = d threads.  Thread j owns
+// hidden unit j: column j of dW1, row j of dW2 and entry j of db1 stay in its registers for the
+// whole chunk, so nothing is reduced across threads.  The chunk's sums go to
+// partial[((map * gridDim.z + hw) * chunks + chunk)][d*d | d | d*dphi | dphi].
+// Token tiles: with shared weights (heads_w == 1) the tiles of all (batch row, head) pairs form
+// one list; with per-head weights the list of head blockIdx.z holds that head's tiles only.
+template <typename T, int DD>
+__global__ __launch_bounds__(DD) void k_phi_wgrad(Geom g, PhiF32 w, View Q, View K,
+                                                  const float* __restrict__ feat,
+                                                  const float* __restrict__ dfeat,
+                                                  float* __restrict__ partial) {
+  __shared__ float xs[kWgTile][DD];
+  __shared__ float dhs[kWgTile][DD];
+  __shared__ float dus[kWgTile][16];
+  const int dphi = g.dphi;
+  const int j = threadIdx.x;
+  const int chunk = blockIdx.x, nchunk = gridDim.x, m = blockIdx.y, hw = blockIdx.z;
+  const bool shared = w.heads_w == 1;
+  const int tpr = (g.N + kWgTile - 1) / kWgTile;
+  const int rows = shared ? g.B * g.H : g.B;
+  const int total = rows * tpr;
+  const int per = (total + nchunk - 1) / nchunk;
+  const int t_begin = chunk * per, t_end = min(total, t_begin + per);
+  const int64_t mh = static_cast<int64_t>(m) * w.heads_w + hw;
+  const float* W1 = w.W1 + mh * DD * DD;
+  const float* W2 = w.W2 + mh * DD * dphi;
+  const float bias = w.b1[mh * DD + j];
+  float w2row[16];
+#pragma unroll
+  for (int c = 0; c < 16; ++c) w2row[c] = c < dphi ? W2[j * dphi + c] : 0.0f;
+  const View& X = m == 0 ? Q : K;
+  float dW1c[DD];     // column j of dW1
+  float dW2r[16];     // row j of dW2
+  float db1 = 0.0f, db2 = 0.0f;
+#pragma unroll
+  for (int i = 0; i < DD; ++i) dW1c[i] = 0.0f;
+#pragma unroll
+  for (int c = 0; c < 16; ++c) dW2r[c] = 0.0f;
+  for (int tile = t_begin; tile < t_end; ++tile) {
+    const int row = tile / tpr, n0 = (tile % tpr) * kWgTile;
+    const int b = shared ? row / g.H : row, h = shared ? row % g.H : hw;
+    const int nt = min(kWgTile, g.N - n0);
+    __syncthreads();
+    for (int t = 0; t < kWgTile; ++t) xs[t][j] = t < nt ? to_float(X.row<const T>(b, h, n0 + t)[j]) : 0.0f;
+    for (int idx = j; idx < kWgTile * 16; idx += DD) {
+      const int t = idx / 16, c = idx % 16;
+      float du = 0.0f;
+      if (t < nt && c < dphi) {
+        const int64_t o = g.fidx(g.th(b, h, n0 + t), m * dphi + c);
+        du = feat[o] > 0.0f ? dfeat[o] : 0.0f;  // ReLU passes gradient only where it was open
+      }
+      dus[t][c] = du;
+    }
+    __syncthreads();
+    float acc[kWgTile];
+#pragma unroll
+    for (int t = 0; t < kWgTile; ++t) acc[t] = bias;
+    for (int i = 0; i < DD; ++i) {
+      const float wv = W1[i * DD + j];
+#pragma unroll
+      for (int t = 0; t < kWgTile; ++t) acc[t] += xs[t][i] * wv;
+    }
+#pragma unroll
+    for (int t = 0; t < kWgTile; ++t) {
+      float dg = 0.0f;
+#pragma unroll
+      for (int c = 0; c < 16; ++c) dg += dus[t][c] * w2row[c];
+      const float gv = gelu_erf(acc[t]);
+      const float dh = dg * gelu_erf_grad(acc[t]);
+      db1 += dh;
+#pragma unroll
+      for (int c = 0; c < 16; ++c) dW2r[c] += gv * dus[t][c];
+      if (j < dphi) db2 += dus[t][j];
+      dhs[t][j] = dh;  // read back by this thread only
+    }
+    // one token at a time, so that only one row of x is in flight beside the DD accumulators
+#pragma unroll 1
+    for (int t = 0; t < kWgTile; ++t) {
+      const float dh = dhs[t][j];
+#pragma unroll
+      for (int i = 0; i < DD; ++i) dW1c[i] += xs[t][i] * dh;
+    }
+  }
+  float* out = partial + ((static_cast<int64_t>(m) * gridDim.z + hw) * nchunk + chunk) *
+                             (static_cast<int64_t>(DD) * DD + DD + DD * dphi + dphi);
+#pragma unroll
+  for (int i = 0; i < DD; ++i) out[i * DD + j] = dW1c[i];
+  out[DD * DD + j] = db1;
+#pragma unroll
+  for (int c = 0; c < 16; ++c)
+    if (c < dphi) out[DD * DD + DD + j * dphi + c] = dW2r[c];
+  if (j < dphi) out[DD * DD + DD + DD * dphi + j] = db2;
+}
+
+// Sum of the partial weight gradients of one (map, head) in partial order, times the scale of
+// its section, into the caller's arrays.  grid (ceil(floats / 256), 1+F, heads), block 256.
+struct WgradOut {
+  float* dW1[kMaxF + 1];
+  float* db1[kMaxF + 1];
+  float* dW2[kMaxF + 1];
+  float* db2[kMaxF + 1];
+};
+__global__ void k_wgrad_reduce(int d, int dphi, int nparts,
+                               const float* __restrict__ partial, WgradOut out, float sW1, float sb1,
+                               float sW2, float sb2) {
+  const int nW1 = d * d, nb1 = d, nW2 = d * dphi, nb2 = dphi;
+  const int floats = nW1 + nb1 + nW2 + nb2;
+  const int e = blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= floats) return;
+  const int m = blockIdx.y, hw = blockIdx.z;
+  const float* p = partial + (static_cast<int64_t>(m) * gridDim.z + hw) * nparts * floats + e;
+  float sum = 0.0f;
+  for (int k = 0; k < nparts; ++k) sum += p[static_cast<int64_t>(k) * floats];
+  if (e < nW1) {
+    out.dW1[m][static_cast<int64_t>(hw) * nW1 + e] = sW1 * sum;
+  } else if (e < nW1 + nb1) {
+    out.db1[m][static_cast<int64_t>(hw) * nb1 + (e - nW1)] = sb1 * sum;
+  } else if (e < nW1 + nb1 + nW2) {
+    out.dW2[m][static_cast<int64_t>(hw) * nW2 + (e - nW1 - nb1)] = sW2 * sum;
+  } else {
+    out.db2[m][static_cast<int64_t>(hw) * nb2 + (e - nW1 - nb1 - nW2)] = sb2 * sum;
+  }
+}
+
+template <typename T>
+hla_status weight_grads_t(hla_handle* hd, const hla_call_args& a) {
+  Geom g = hd->g;
+  g.B = a.B;
+  g.H = a.H;
+  g.N = a.N;
+  if (g.dphi > 16) return HLA_ERR_UNSUPPORTED;
+  const int nm = 1 + g.F;
+  const int heads = hd->phi.heads_w == 1 ? 1 : a.H;
+  // about one full grid of workgroups in total, never more partial sums than the workspace holds
+  int64_t nchunk = 512 / (static_cast<int64_t>(nm) * heads);
+  const int64_t tiles = (hd->phi.heads_w == 1 ? static_cast<int64_t>(a.B) * a.H : a.B) *
+                        ((a.N + kWgTile - 1) / kWgTile);
+  if (nchunk > tiles) nchunk = tiles;
+  if (nchunk < 1) nchunk = 1;
+  if (nm * static_cast<int64_t>(heads) * nchunk > hd->wg_parts_cap) return HLA_ERR_STATE;
+  const dim3 grid(static_cast<unsigned>(nchunk), nm, heads);
+  hipStream_t s = a.stream;
+  switch (g.d) {
+    case 32:
+      HLA_TRY(launch(hd, "phi_weight_grads", k_phi_wgrad<T, 32>, grid, dim3(32), 0, s, g, hd->phi, a.Q, a.K,
+                     static_cast<const float*>(hd->feat), static_cast<const float*>(hd->dfeat), hd->wg_partial));
+      break;
+    case 64:
+      HLA_TRY(launch(hd, "phi_weight_grads", k_phi_wgrad<T, 64>, grid, dim3(64), 0, s, g, hd->phi, a.Q, a.K,
+                     static_cast<const float*>(hd->feat), static_cast<const float*>(hd->dfeat), hd->wg_partial));
+      break;
+    case 128:
+      HLA_TRY(launch(hd, "phi_weight_grads", k_phi_wgrad<T, 128>, grid, dim3(128), 0, s, g, hd->phi, a.Q, a.K,
+                     static_cast<const float*>(hd->feat), static_cast<const float*>(hd->dfeat), hd->wg_partial));
+      break;
+    default:
+      return HLA_ERR_UNSUPPORTED;
+  }
+  WgradOut out{};
+  for (int m = 0; m < nm; ++m) {
+    out.dW1[m] = hd->wg_out[m].dW1;
+    out.db1[m] = hd->wg_out[m].db1;
+    out.dW2[m] = hd->wg_out[m].dW2;
+    out.db2[m] = hd->wg_out[m].db2;
+  }
+  const int floats = static_cast<int>(hd->wg_part_floats);
+  return launch(hd, "phi_weight_grads_reduce", k_wgrad_reduce, dim3((floats + 255) / 256, nm, heads),
+                dim3(256), 0, s, g.d, g.dphi, static_cast<int>(nchunk),
+                static_cast<const float*>(hd->wg_partial), out, 1.0f, 1.0f, 1.0f, 1.0f);
 }
 
 // ---- accumulate: partial Chat = sum over a chunk of tokens of T (x) yhat -----------------------
@@ -613,6 +787,10 @@ hla_status convert_weights_to_f32(hla_handle* hd, const hla_phi_weights* maps, h
 }
 
 hla_status generic_set_weights(hla_handle*, hipStream_t) { return HLA_OK; }
+
+hla_status phi_weight_grads(hla_handle* hd, const hla_call_args& a) {
+  return hd->cfg.io_dtype == HLA_F32 ? weight_grads_t<float>(hd, a) : weight_grads_t<bf16_t>(hd, a);
+}
 
 // Features in (feature maps, or import of caller-provided features) and feature gradients out
 // (through the maps, or exported as they are); shared with the MFMA path.

@@ -52,6 +52,13 @@ struct hla_handle {
   hla::PhiF32 phi{};
   bool have_weights = false;
 
+  // weight-gradient outputs (optional): caller's fp32 arrays and the per-workgroup partial sums
+  bool wg_on = false;
+  hla_phi_weight_grads wg_out[5] = {};
+  float* wg_partial = nullptr;     // [wg_parts_cap][wg_part_floats]
+  int64_t wg_parts_cap = 0;
+  int64_t wg_part_floats = 0;      // d*d + d + d*dphi + dphi
+
   // token tables keyed by block size
   std::map<int32_t, hla_token_table> tables;
   std::vector<int32_t> cu_host;    // shape signature of the tables (effective cu, B rows if dense)
@@ -105,6 +112,8 @@ hla_status mfma_phi_backward(hla_handle* hd, const hla_call_args& a);
 
 // Shared helper kernels' host wrappers (hla_generic.hip).
 hla_status convert_weights_to_f32(hla_handle* hd, const hla_phi_weights* maps, hipStream_t s);
+// Weight gradients of the feature maps from the saved features and feature gradients (any path).
+hla_status phi_weight_grads(hla_handle* hd, const hla_call_args& a);
 
 }  // namespace hla
 

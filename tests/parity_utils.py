@@ -46,15 +46,26 @@ def make_handle(tensors, F, d_phi, eps, phi, cu_seqlens, path=hla.HLA_PATH_AUTO,
     return h
 
 
+WG_KEYS = ("dW1", "db1", "dW2", "db2")
+
+
 def run_gpu(tensors: Dict[str, torch.Tensor], F: int, d_phi: int, eps: float,
-            phi=None, cu_seqlens=None, backward=True, path=hla.HLA_PATH_AUTO, handle=None):
-    """Returns dict of CPU tensors O (and dQ, dK, dV) computed by the HIP library."""
+            phi=None, cu_seqlens=None, backward=True, path=hla.HLA_PATH_AUTO, handle=None,
+            weight_grads=False, per_head=False):
+    """Returns dict of CPU tensors O (and dQ, dK, dV) computed by the HIP library; with
+    weight_grads also 'wg': per map a dict of the fp32 weight gradients.  per_head: the weights
+    carry a leading head dimension."""
     dev = torch.device("cuda:0")
     t = {k: v.to(dev) for k, v in tensors.items()}
     h = handle or make_handle(tensors, F, d_phi, eps, phi, cu_seqlens, path)
+    wg = None
     if phi is not None:
         phi_dev = [{k: v.to(dev) for k, v in m.items()} for m in phi]
-        h.set_phi_weights(phi_dev)
+        h.set_phi_weights(phi_dev, per_head=per_head)
+        if weight_grads:
+            wg = [{"d" + k: torch.full(v.shape, float("nan"), dtype=torch.float32, device=dev)
+                   for k, v in m.items()} for m in phi_dev]
+            h.set_phi_weight_grads(wg)
     out = {"O": torch.full_like(t["V"], float("nan"))}
     h.forward(t["Q"], t["K"], t["V"], out["O"], cu_seqlens=cu_seqlens)
     if backward:
@@ -64,6 +75,8 @@ def run_gpu(tensors: Dict[str, torch.Tensor], F: int, d_phi: int, eps: float,
                    cu_seqlens=cu_seqlens)
     torch.cuda.synchronize()
     res = {k: v.cpu() for k, v in out.items()}
+    if wg is not None:
+        res["wg"] = [{k: v.cpu() for k, v in m.items()} for m in wg]
     res["_path"] = h.active_path
     if handle is None:
         h.destroy()
@@ -71,16 +84,53 @@ def run_gpu(tensors: Dict[str, torch.Tensor], F: int, d_phi: int, eps: float,
 
 
 def run_oracle(tensors, F, d_phi, eps, phi=None, cu_seqlens=None, backward=True,
-               route="factorized"):
+               route="factorized", weight_grads=False):
     Q, K, V = (to_np(tensors[k]) for k in ("Q", "K", "V"))
     ophi = oracle_phi(phi)
     out = {"O": orc.hla_operator_forward(Q, K, V, F, d_phi, eps, phi=ophi, cu_seqlens=cu_seqlens,
                                          route=route)}
     if backward:
-        dQ, dK, dV = orc.hla_operator_backward(Q, K, V, to_np(tensors["dO"]), F, d_phi, eps,
-                                               phi=ophi, cu_seqlens=cu_seqlens, route=route)
-        out.update(dQ=dQ, dK=dK, dV=dV)
+        res = orc.hla_operator_backward(Q, K, V, to_np(tensors["dO"]), F, d_phi, eps,
+                                        phi=ophi, cu_seqlens=cu_seqlens, route=route,
+                                        weight_grads=weight_grads)
+        out.update(dQ=res[0], dK=res[1], dV=res[2])
+        if weight_grads:
+            out["wg"] = [dict(zip(WG_KEYS, m)) for m in res[3]]
     return out
+
+
+def run_oracle_per_head(tensors, F, d_phi, eps, phi, cu_seqlens=None, weight_grads=True):
+    """Oracle for weights that carry a leading head dimension: the oracle's maps are shared by
+    the heads it is given, so every head is run on its own with its own weights."""
+    H = tensors["V"].shape[1]
+    outs = []
+    for h in range(H):
+        th = {k: v[:, h:h + 1] for k, v in tensors.items()}
+        ph = [{k: v[h] for k, v in m.items()} for m in phi]
+        outs.append(run_oracle(th, F, d_phi, eps, phi=ph, cu_seqlens=cu_seqlens,
+                               weight_grads=weight_grads))
+    out = {k: np.concatenate([o[k] for o in outs], axis=1) for k in ("O", "dQ", "dK", "dV")}
+    if weight_grads:
+        out["wg"] = [{k: np.stack([o["wg"][m][k] for o in outs]) for k in WG_KEYS}
+                     for m in range(len(phi))]
+    return out
+
+
+def assert_weight_grad_parity(gpu_wg, ref_wg, tol, what=""):
+    """Every weight-gradient array of every map against the oracle with the build's error
+    measure (max |diff| / max |ref| per array)."""
+    worst = {}
+    for m, (g, r) in enumerate(zip(gpu_wg, ref_wg)):
+        for k in WG_KEYS:
+            got = to_np(g[k])
+            assert np.isfinite(got).all(), f"{what}: map {m} {k} has non-finite entries"
+            assert got.shape == r[k].shape, f"{what}: map {m} {k} shape {got.shape} vs {r[k].shape}"
+            worst[f"{k}[{m}]"] = max_rel_err(got, r[k])
+    msg = ", ".join(f"{k}={e:.2e}" for k, e in worst.items())
+    print(f"[parity] {what}: {msg} (tol {tol:g})", flush=True)
+    bad = {k: e for k, e in worst.items() if not e <= tol}
+    assert not bad, f"{what}: weight gradients above {tol:g}: {bad}"
+    return worst
 
 
 def relu_kink_masks(tensors, phi, F, band):
@@ -99,6 +149,8 @@ def relu_kink_masks(tensors, phi, F, band):
 def assert_parity(gpu, ref, tol, what="", row_masks=None):
     errs = {}
     for k, r in ref.items():
+        if k == "wg":
+            continue
         g = to_np(gpu[k])
         assert np.isfinite(g).all(), f"{what}: {k} has non-finite entries"
         if row_masks is not None and k in row_masks:
