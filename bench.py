@@ -36,6 +36,9 @@ def parse():
                     help="before the warm-up, run one device-to-device copy of this many MiB: the "
                          "known-size kernel that scales rocprofv3's FETCH_SIZE / WRITE_SIZE")
     ap.add_argument("--path", choices=["auto", "generic", "mfma"], default="auto")
+    ap.add_argument("--weight-grads", action="store_true",
+                    help="also produce the feature-map weight gradients in every backward (a "
+                         "different workload from the headline one: named in config)")
     return ap.parse_args()
 
 
@@ -117,6 +120,14 @@ def main():
         h.set_phi_weights([{k: v.to(dev) for k, v in m.items()} for m in phi])
     O = torch.empty_like(t["V"])
     grads = [torch.empty_like(t[k]) for k in ("Q", "K", "V")] if backward else None
+    wgrads = None
+    if args.weight_grads:
+        if phi is None or not backward:
+            print("bench.py: --weight-grads needs feature maps and a backward pass", file=sys.stderr)
+            sys.exit(2)
+        wgrads = [{"d" + k: torch.empty(v.shape, dtype=torch.float32, device=dev) for k, v in m.items()}
+                  for m in phi]
+        h.set_phi_weight_grads(wgrads)
 
     def step():
         h.forward(t["Q"], t["K"], t["V"], O, cu_seqlens=w.cu_seqlens)
@@ -181,7 +192,8 @@ def main():
         "config": {"workload": w.name, "B": w.B, "H": w.H, "N": w.N, "d": w.d, "F": w.F,
                    "d_phi": w.d_phi, "phi": "mlp" if phi is not None else "none",
                    "packed_seqs": nseq if w.cu_seqlens else 0,
-                   "path": "mfma" if h.active_path == hla.HLA_PATH_MFMA else "generic"},
+                   "path": "mfma" if h.active_path == hla.HLA_PATH_MFMA else "generic",
+                   "weight_grads": wgrads is not None},
         "tflops_nominal": tflops,
         "mfma_peak_frac_nominal": tflops / 2500.0,
         "hbm_frac_whole_path": by / (elapsed / args.steps) / 8e12,

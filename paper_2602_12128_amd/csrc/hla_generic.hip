@@ -363,17 +363,7 @@ hla_status weight_grads_t(hla_handle* hd, const hla_call_args& a) {
     default:
       return HLA_ERR_UNSUPPORTED;
   }
-  WgradOut out{};
-  for (int m = 0; m < nm; ++m) {
-    out.dW1[m] = hd->wg_out[m].dW1;
-    out.db1[m] = hd->wg_out[m].db1;
-    out.dW2[m] = hd->wg_out[m].dW2;
-    out.db2[m] = hd->wg_out[m].db2;
-  }
-  const int floats = static_cast<int>(hd->wg_part_floats);
-  return launch(hd, "phi_weight_grads_reduce", k_wgrad_reduce, dim3((floats + 255) / 256, nm, heads),
-                dim3(256), 0, s, g.d, g.dphi, static_cast<int>(nchunk),
-                static_cast<const float*>(hd->wg_partial), out, 1.0f, 1.0f, 1.0f, 1.0f);
+  return weight_grads_reduce(hd, static_cast<int>(nchunk), heads, 1.0f, 1.0f, 1.0f, 1.0f, s);
 }
 
 // ---- accumulate: partial Chat = sum over a chunk of tokens of T (x) yhat -----------------------
@@ -788,7 +778,24 @@ hla_status convert_weights_to_f32(hla_handle* hd, const hla_phi_weights* maps, h
 
 hla_status generic_set_weights(hla_handle*, hipStream_t) { return HLA_OK; }
 
+hla_status weight_grads_reduce(hla_handle* hd, int nparts, int heads, float sW1, float sb1, float sW2,
+                               float sb2, hipStream_t s) {
+  const int nm = 1 + hd->g.F;
+  WgradOut out{};
+  for (int m = 0; m < nm; ++m) {
+    out.dW1[m] = hd->wg_out[m].dW1;
+    out.db1[m] = hd->wg_out[m].db1;
+    out.dW2[m] = hd->wg_out[m].dW2;
+    out.db2[m] = hd->wg_out[m].db2;
+  }
+  const int floats = static_cast<int>(hd->wg_part_floats);
+  return launch(hd, "phi_weight_grads_reduce", k_wgrad_reduce, dim3((floats + 255) / 256, nm, heads),
+                dim3(256), 0, s, hd->g.d, hd->g.dphi, nparts, static_cast<const float*>(hd->wg_partial), out,
+                sW1, sb1, sW2, sb2);
+}
+
 hla_status phi_weight_grads(hla_handle* hd, const hla_call_args& a) {
+  if (hd->path == HLA_PATH_MFMA && hd->cfg.io_dtype == HLA_BF16) return mfma_phi_weight_grads(hd, a);
   return hd->cfg.io_dtype == HLA_F32 ? weight_grads_t<float>(hd, a) : weight_grads_t<bf16_t>(hd, a);
 }
 

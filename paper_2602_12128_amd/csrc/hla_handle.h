@@ -112,8 +112,14 @@ hla_status mfma_phi_backward(hla_handle* hd, const hla_call_args& a);
 
 // Shared helper kernels' host wrappers (hla_generic.hip).
 hla_status convert_weights_to_f32(hla_handle* hd, const hla_phi_weights* maps, hipStream_t s);
-// Weight gradients of the feature maps from the saved features and feature gradients (any path).
+// Weight gradients of the feature maps from the saved features and feature gradients: partial
+// sums by the path's kernel (matrix cores where the MFMA path has one, else the fp32 kernel of
+// hla_generic.hip), then weight_grads_reduce adds `nparts` partials per (map, head) in order,
+// scales the four sections and writes the caller's arrays.
 hla_status phi_weight_grads(hla_handle* hd, const hla_call_args& a);
+hla_status mfma_phi_weight_grads(hla_handle* hd, const hla_call_args& a);
+hla_status weight_grads_reduce(hla_handle* hd, int nparts, int heads, float sW1, float sb1, float sW2,
+                               float sb2, hipStream_t s);
 
 }  // namespace hla
 

@@ -99,6 +99,41 @@ __device__ __forceinline__ void gelu_grad_f16(const float (&in)[2 * NCH], f16x2 
   for (int i = 0; i < NCH; ++i) out[i] = __builtin_elementwise_fma(yc[i], p[i], splat16(0.5f));
 }
 
+// GELU(x)/4 and GELU'(x) of the same 2*NCH values y = x/4 (the two fits share yc and v)
+template <int NCH>
+__device__ __forceinline__ void gelu_both_f16(const float (&in)[2 * NCH], f16x2 (&gout)[NCH],
+                                              f16x2 (&dout)[NCH]) {
+  constexpr float c[7] = {0.703613f, -0.676758f, 0.891113f, -1.10352f, 1.45508f, -2.26562f, 1.88965f};
+  constexpr float e[8] = {0.73291f, -0.910156f, 1.88086f, -3.62891f, 5.31641f, -9.5f, 19.75f, -17.625f};
+  f16x2 y[NCH], yc[NCH], v[NCH], p[NCH], q[NCH];
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) y[i] = to_f16x2(in[2 * i], in[2 * i + 1]);
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) yc[i] = clamp1(y[i]);
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) v[i] = __builtin_elementwise_fma(yc[i], yc[i], splat16(-0.5f));
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    p[i] = __builtin_elementwise_fma(splat16(c[6]), v[i], splat16(c[5]));
+    q[i] = __builtin_elementwise_fma(splat16(e[7]), v[i], splat16(e[6]));
+  }
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) q[i] = __builtin_elementwise_fma(q[i], v[i], splat16(e[5]));
+#pragma unroll
+  for (int k = 4; k >= 0; --k)
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      p[i] = __builtin_elementwise_fma(p[i], v[i], splat16(c[k]));
+      q[i] = __builtin_elementwise_fma(q[i], v[i], splat16(e[k]));
+    }
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    p[i] = __builtin_elementwise_fma(yc[i], p[i], splat16(0.5f));
+    dout[i] = __builtin_elementwise_fma(yc[i], q[i], splat16(0.5f));
+    gout[i] = y[i] * p[i];
+  }
+}
+
 // ---- packed weights of one (map, head) in global memory ---------------------------------------
 template <int D>
 struct Packed {
@@ -654,6 +689,206 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_bwd(Geom g, View X,
   }
 }
 
+// ---- weight gradients ---------------------------------------------------------------------------
+// dW1 = X^T dh, db1 = sum dh, dW2 = GELU(h)^T du, db2 = sum du over tokens, for one map per
+// workgroup (blockIdx.y) and, with per-head weights, one head (blockIdx.z).  Both products contract
+// over TOKENS, while the forward layout keeps a token in an MFMA column, so every 32-token tile
+// goes through two wave-private LDS tiles, [token][input channels | du] and [token][dh | GELU(h)],
+// that are read back with transpose reads as operands whose k index is the token.
+// Wave w of the workgroup owns hidden block hb = w % (D/32) -- its first-layer weights stay in
+// registers, it needs no LDS copy of W1 -- and serves the 32-token tiles th, th + T, .. of the
+// workgroup's share, th = w / (D/32), T = WAVES / (D/32).  Its sums end as the hidden-block
+// columns of partial number blockIdx.x * T + th of this (map, head):
+//   [dW1 D*D | db1 D | dW2 D*d_phi | db2 d_phi] floats, scaled by the packing factors
+// (dW1, db1 four times too large, dW2 four times too small); a second kernel adds the partials.
+template <int D>
+struct WgSmem {
+  static constexpr int kXStride = (D + 32) * 2 + 32;  // bytes per token row: channels, 32 du columns, pad
+  static constexpr int kGStride = 64 * 2 + 32;        // dh (32 columns), GELU(h) (32 columns), pad
+  static constexpr int kXBytes = 32 * kXStride;
+  static constexpr int kWaveBytes = kXBytes + 32 * kGStride;
+};
+
+template <int D, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void k_phi_wgrad(Geom g, View Q, View K,
+                                                          const unsigned char* __restrict__ wpk,
+                                                          int heads_w,
+                                                          const float* __restrict__ feat,
+                                                          const float* __restrict__ dfeat,
+                                                          float* __restrict__ partial) {
+  using SM = WgSmem<D>;
+  using PK = Packed<D>;
+  constexpr int NRB = D / 32, NKS = D / 16, TH = WAVES / NRB;
+  static_assert(WAVES % NRB == 0, "whole groups of hidden blocks");
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const int r = lane % 32, gl = lane / 32;
+  const int L = lane % 16, q = lane / 16;
+  const int hb = wave % NRB, th = wave / NRB;
+  const int m = blockIdx.y, hw = blockIdx.z;
+  unsigned char* xt = smem + wave * SM::kWaveBytes;
+  unsigned char* gt = xt + SM::kXBytes;
+  const unsigned char* wm = wpk + (static_cast<int64_t>(m) * heads_w + hw) * PK::kBytes;
+  const View& X = m == 0 ? Q : K;
+  // this wave's first-layer operands: rows 32 hb + r of W1^T, k-slot (ks, gl, j) = channel 16ks + 8gl + j
+  u32x4 w1a[NKS];
+#pragma unroll
+  for (int ks = 0; ks < NKS; ++ks)
+    w1a[ks] = *reinterpret_cast<const u32x4*>(wm + PK::kW1T + ((32 * hb + r) * D + 16 * ks + 8 * gl) * 2);
+  const u32x4 w2b = *reinterpret_cast<const u32x4*>(wm + PK::kW2B + (hb * 64 + lane) * 16);
+  const float* b1 = reinterpret_cast<const float*>(wm + PK::kB1) + 32 * hb + 4 * gl;
+  // token tiles: one list over all (batch row, head) pairs when the weights are shared
+  const bool shared = heads_w == 1;
+  const int tpr = (g.N + 31) / 32;
+  const int total = (shared ? g.B * g.H : g.B) * tpr;
+  f32x16 acc[NRB];   // dW1 rows 32 ib + d_row(i, gl), column 32 hb + r
+  f32x16 acc2;       // dW2^T rows = features d_row(i, gl), column 32 hb + r
+  float db1[16];     // per-lane (token r) sums of dh for hidden 32 hb + d_row(i, gl)
+  float db2[kDP];    // per-lane sums of du (lanes gl == 0)
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+#pragma unroll
+    for (int ib = 0; ib < NRB; ++ib) acc[ib][i] = 0.0f;
+    acc2[i] = 0.0f;
+    db1[i] = 0.0f;
+  }
+#pragma unroll
+  for (int a = 0; a < kDP; ++a) db2[a] = 0.0f;
+  for (int tile = blockIdx.x * TH + th; tile < total; tile += gridDim.x * TH) {
+    const int row = tile / tpr, n0 = (tile % tpr) * 32;
+    const int b = shared ? row / g.H : row, h = shared ? row % g.H : hw;
+    const int n = n0 + r;
+    const bool live = n < g.N;
+    u32x4 xb[NKS];
+    load_x<D>(X, b, h, n, g.N, gl, xb);
+    // du of the token: zero where the ReLU was closed, and for tokens past the end (whose clamped
+    // input row then adds nothing to any sum)
+    float du[kDP];
+#pragma unroll
+    for (int a = 0; a < kDP; ++a) du[a] = 0.0f;
+    if (live && gl == 0) {
+      const int64_t o = g.fidx(g.th(b, h, n), m * kDP);
+      float fv[kDP], dv[kDP];
+#pragma unroll
+      for (int a = 0; a < kDP; ++a) {
+        fv[a] = feat[o + 32 * a];
+        dv[a] = dfeat[o + 32 * a];
+      }
+#pragma unroll
+      for (int a = 0; a < kDP; ++a) du[a] = fv[a] > 0.0f ? dv[a] : 0.0f;
+    }
+    u32x4 dub;
+    dub[0] = pack_bf16(du[0], du[1]);
+    dub[1] = pack_bf16(du[2], du[3]);
+    dub[2] = pack_bf16(du[4], du[5]);
+    dub[3] = 0u;
+#pragma unroll
+    for (int a = 0; a < kDP; ++a) db2[a] += du[a];
+    // hidden block of the first layer (a quarter of its scale) and dg = 4 W2 du
+    f32x16 cur;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const f32x4 bv = *reinterpret_cast<const f32x4*>(b1 + 8 * i);
+      cur[4 * i] = bv[0];
+      cur[4 * i + 1] = bv[1];
+      cur[4 * i + 2] = bv[2];
+      cur[4 * i + 3] = bv[3];
+    }
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) cur = mfma32(w1a[ks], xb[ks], cur);
+    f32x16 zero;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) zero[i] = 0.0f;
+    const f32x16 dg = mfma32(w2b, dub, zero);
+    // [token][channels | du] tile
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks)
+      *reinterpret_cast<u32x4*>(xt + r * SM::kXStride + (16 * ks + 8 * gl) * 2) = xb[ks];
+    {
+      u32x4 z4;
+      z4[0] = z4[1] = z4[2] = z4[3] = 0u;
+      *reinterpret_cast<u32x4*>(xt + r * SM::kXStride + (D + 16 * gl) * 2) = gl == 0 ? dub : z4;
+      *reinterpret_cast<u32x4*>(xt + r * SM::kXStride + (D + 16 * gl + 8) * 2) = z4;
+    }
+    // [token][dh | GELU(h)] tile: a slice covers hidden 8j + 4gl .. +3 of the block
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const float in[4] = {cur[4 * j], cur[4 * j + 1], cur[4 * j + 2], cur[4 * j + 3]};
+      f16x2 gv[2], gp[2];
+      gelu_both_f16<2>(in, gv, gp);
+      const float d0 = __builtin_fmaf(static_cast<float>(gp[0][0]), dg[4 * j], 0.0f);
+      const float d1 = __builtin_fmaf(static_cast<float>(gp[0][1]), dg[4 * j + 1], 0.0f);
+      const float d2 = __builtin_fmaf(static_cast<float>(gp[1][0]), dg[4 * j + 2], 0.0f);
+      const float d3 = __builtin_fmaf(static_cast<float>(gp[1][1]), dg[4 * j + 3], 0.0f);
+      db1[4 * j] += d0;
+      db1[4 * j + 1] += d1;
+      db1[4 * j + 2] += d2;
+      db1[4 * j + 3] += d3;
+      u32x2 dh2, g2;
+      dh2[0] = pack_bf16(d0, d1);
+      dh2[1] = pack_bf16(d2, d3);
+      g2[0] = pack_bf16(static_cast<float>(gv[0][0]), static_cast<float>(gv[0][1]));
+      g2[1] = pack_bf16(static_cast<float>(gv[1][0]), static_cast<float>(gv[1][1]));
+      *reinterpret_cast<u32x2*>(gt + r * SM::kGStride + (8 * j + 4 * gl) * 2) = dh2;
+      *reinterpret_cast<u32x2*>(gt + r * SM::kGStride + (32 + 8 * j + 4 * gl) * 2) = g2;
+    }
+    wave_lds_sync();
+    // contractions over the tile's 32 tokens (two 16-token steps)
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      const int krow = 16 * ks + 8 * gl + L / 4;  // token row this lane addresses for the transpose read
+      const int coff = (16 * (q % 2) + 4 * (L % 4)) * 2;
+      auto operand = [&](const unsigned char* tile, int stride, int col0) {
+        const unsigned char* p = tile + krow * stride + col0 * 2 + coff;
+        const u32x2 lo = lds_read_tr16(p);
+        const u32x2 hi = lds_read_tr16(p + 4 * stride);
+        u32x4 o;
+        o[0] = lo[0];
+        o[1] = lo[1];
+        o[2] = hi[0];
+        o[3] = hi[1];
+        return o;
+      };
+      const u32x4 bdh = operand(gt, SM::kGStride, 0);
+      const u32x4 bg = operand(gt, SM::kGStride, 32);
+#pragma unroll
+      for (int ib = 0; ib < NRB; ++ib) acc[ib] = mfma32(operand(xt, SM::kXStride, 32 * ib), bdh, acc[ib]);
+      acc2 = mfma32(operand(xt, SM::kXStride, D), bg, acc2);
+    }
+    wave_lds_sync();
+  }
+  // ---- this wave's share of the partial
+  const int nparts = gridDim.x * TH;
+  const int64_t floats = static_cast<int64_t>(D) * D + D + D * kDP + kDP;
+  float* out = partial + ((static_cast<int64_t>(m) * gridDim.z + hw) * nparts + blockIdx.x * TH + th) * floats;
+#pragma unroll
+  for (int ib = 0; ib < NRB; ++ib)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) out[(32 * ib + d_row(i, gl)) * D + 32 * hb + r] = acc[ib][i];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int a = 4 * gl + i;  // d_row(i, gl) for i < 4
+    if (a < kDP) out[D * D + D + (32 * hb + r) * kDP + a] = acc2[i];
+  }
+  // sums over the 32 tokens of a half-wave (xor offsets below 32 stay inside it)
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    float v = db1[i];
+#pragma unroll
+    for (int off = 16; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+    if (r == 0) out[D * D + 32 * hb + d_row(i, gl)] = v;
+  }
+  if (hb == 0) {
+#pragma unroll
+    for (int a = 0; a < kDP; ++a) {
+      float v = db2[a];
+#pragma unroll
+      for (int off = 16; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+      if (lane == 0) out[D * D + D + D * kDP + a] = v;
+    }
+  }
+}
+
 template <typename K>
 hla_status allow_lds(K kernel, int bytes) {
   return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
@@ -719,7 +954,45 @@ hla_status backward_t(hla_handle* hd, const hla_call_args& a) {
   return HLA_OK;
 }
 
+constexpr int kWavesW = 8;
+
+template <int D>
+hla_status weight_grads_t(hla_handle* hd, const hla_call_args& a) {
+  using SM = WgSmem<D>;
+  constexpr int TH = kWavesW / (D / 32);
+  constexpr int lds = kWavesW * SM::kWaveBytes;
+  Geom g = hd->g;
+  if (g.dphi != kDP || g.F != 3) return HLA_ERR_UNSUPPORTED;
+  const unsigned char* wpk = static_cast<const unsigned char*>(hd->path_ws) + hd->w_packed_off;
+  static bool attr = false;
+  if (!attr) {
+    HLA_TRY(allow_lds(&k_phi_wgrad<D, kWavesW>, lds));
+    attr = true;
+  }
+  const int nm = 1 + g.F;
+  const bool shared = hd->phi.heads_w == 1;
+  const int heads = shared ? 1 : g.H;
+  const int64_t tiles = static_cast<int64_t>(shared ? g.B * g.H : g.B) * ((g.N + 31) / 32);
+  // one workgroup per compute unit in total, each with at least one tile per wave group
+  int64_t nblk = 256 / (static_cast<int64_t>(nm) * heads);
+  if (nblk > (tiles + TH - 1) / TH) nblk = (tiles + TH - 1) / TH;
+  if (nblk < 1) nblk = 1;
+  const int64_t nparts = nblk * TH;
+  if (nm * heads * nparts > hd->wg_parts_cap) return HLA_ERR_STATE;
+  HLA_TRY(launch(hd, "mfma_phi_weight_grads", k_phi_wgrad<D, kWavesW>,
+                 dim3(static_cast<unsigned>(nblk), nm, heads), dim3(kWavesW * 64), lds, a.stream, g, a.Q, a.K,
+                 wpk, hd->phi.heads_w, static_cast<const float*>(hd->feat),
+                 static_cast<const float*>(hd->dfeat), hd->wg_partial));
+  // undo the packing factors: dh and dg carry 1/kHiddenScale, GELU(h) carries kHiddenScale
+  return weight_grads_reduce(hd, static_cast<int>(nparts), heads, kHiddenScale, kHiddenScale,
+                             1.0f / kHiddenScale, 1.0f, a.stream);
+}
+
 }  // namespace
+
+hla_status mfma_phi_weight_grads(hla_handle* hd, const hla_call_args& a) {
+  return hd->g.d == 128 ? weight_grads_t<128>(hd, a) : weight_grads_t<64>(hd, a);
+}
 
 size_t mfma_phi_packed_bytes(const hla_handle* hd) {
   const size_t per = hd->g.d == 128 ? Packed<128>::kBytes : Packed<64>::kBytes;
