@@ -317,7 +317,15 @@ __global__ void k_wgrad_reduce(int d, int dphi, int nparts,
   const int m = blockIdx.y, hw = blockIdx.z;
   const float* p = partial + (static_cast<int64_t>(m) * gridDim.z + hw) * nparts * floats + e;
   float sum = 0.0f;
-  for (int k = 0; k < nparts; ++k) sum += p[static_cast<int64_t>(k) * floats];
+  int k = 0;
+  for (; k + 8 <= nparts; k += 8) {  // eight loads in flight, added in partial order
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = p[static_cast<int64_t>(k + u) * floats];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) sum += v[u];
+  }
+  for (; k < nparts; ++k) sum += p[static_cast<int64_t>(k) * floats];
   if (e < nW1) {
     out.dW1[m][static_cast<int64_t>(hw) * nW1 + e] = sW1 * sum;
   } else if (e < nW1 + nb1) {
