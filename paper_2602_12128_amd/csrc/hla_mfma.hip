@@ -21,7 +21,10 @@ using namespace mf;
 #endif
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
-constexpr int kQueryBlock = 1024;  // tokens per workgroup in token-parallel kernels
+#ifndef HLA_QUERY_TARGET
+#define HLA_QUERY_TARGET 496
+#endif
+constexpr int kQueryTarget = HLA_QUERY_TARGET;  // workgroups aimed at by the query kernel
 constexpr int kChunkTarget = 240;   // workgroups aimed at by the chunked (token-contraction) kernels
 constexpr int kReduceSlices = 8;   // slices of the state per (sequence, head) in k_reduce
 
@@ -333,7 +336,7 @@ __global__ __launch_bounds__(256) void k_reduce(Geom g, const int32_t* __restric
 }
 
 // ---- k_query ----------------------------------------------------------------------------------
-// grid (blocks of kQueryBlock tokens, H), block 256.  Wave w serves 32-token tiles w, w+4, ..;
+// grid (blocks of pick_query_block tokens, H), block 256.  Wave w serves 32-token tiles w, w+4, ..;
 // lane (r, gl): token r of the tile, slot half gl (gl = 1 works on the reversed feature vector).
 template <int DP, int D>
 __global__ __launch_bounds__(kThreads) void k_query(Geom g, const BlockEnt* __restrict__ blocks,
@@ -844,6 +847,16 @@ inline int pick_chunk(const Geom& g, int num_seqs) {
   return static_cast<int>(chunk < 256 ? 256 : chunk);
 }
 
+inline int pick_query_block(const Geom& g, int num_seqs) {
+  // The query kernel keeps two workgroups per compute unit: aim at one resident round of them,
+  // in multiples of the 128 tokens a workgroup consumes per step.
+  const int units = num_seqs * g.H > 0 ? num_seqs * g.H : 1;
+  const int per_unit = kQueryTarget / units > 0 ? kQueryTarget / units : 1;
+  const int64_t mean_len = (static_cast<int64_t>(g.B) * g.N + num_seqs - 1) / (num_seqs > 0 ? num_seqs : 1);
+  const int64_t blk = ((mean_len + per_unit - 1) / per_unit + 127) / 128 * 128;
+  return static_cast<int>(blk < 128 ? 128 : blk);
+}
+
 template <typename K>
 hla_status allow_big_lds(K kernel, int bytes) {
   return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
@@ -858,9 +871,8 @@ hla_status backward_core(hla_handle* hd, const hla_call_args& a) {
   Geom g = hd->g;
   hipStream_t s = a.stream;
   const int chunk = pick_chunk(g, a.num_seqs);
-  hla_token_table *chunks = nullptr, *qblocks = nullptr;
+  hla_token_table* chunks = nullptr;
   HLA_TRY(get_table(hd, chunk, s, &chunks));
-  HLA_TRY(get_table(hd, kQueryBlock, s, &qblocks));
   static bool attr_set = false;
   if (!attr_set) {
     HLA_TRY(allow_big_lds(&k_bwd_query<DP, D>, BwdQSmem<D>::kTotal));
@@ -888,7 +900,7 @@ hla_status forward_core(hla_handle* hd, const hla_call_args& a) {
   const int chunk = pick_chunk(g, a.num_seqs);
   hla_token_table *chunks = nullptr, *qblocks = nullptr;
   HLA_TRY(get_table(hd, chunk, s, &chunks));
-  HLA_TRY(get_table(hd, kQueryBlock, s, &qblocks));
+  HLA_TRY(get_table(hd, pick_query_block(g, a.num_seqs), s, &qblocks));
   if (static_cast<int64_t>(chunks->count) * g.H > hd->max_chunks * hd->cfg.max_heads)
     return HLA_ERR_INVALID_ARG;
   static bool attr_set = false;
@@ -931,7 +943,6 @@ hla_status mfma_workspace_plan(hla_handle* hd) {
   hd->path_ws_bytes = static_cast<size_t>(2 * op_bytes * hd->max_units);
   hd->w_packed_off = hd->path_ws_bytes;
   if (hd->cfg.phi_mode == HLA_PHI_MLP) hd->path_ws_bytes += mfma_phi_packed_bytes(hd);
-  hd->tables[kQueryBlock];
   return HLA_OK;
 }
 
