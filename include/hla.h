@@ -147,7 +147,9 @@ typedef struct {
 /* Register (maps != NULL, num_maps = 1+F, order phi_q, phi_k1, .., phi_kF) or clear (maps = NULL)
  * the weight-gradient outputs.  While registered, every hla_backward OVERWRITES them on its
  * stream after the input gradients; they must stay valid until that work has completed.  Needs a
- * prior hla_set_phi_weights (HLA_ERR_STATE otherwise; registering new weights keeps the outputs).
+ * prior hla_set_phi_weights (HLA_ERR_STATE otherwise); registering new weights keeps the outputs
+ * unless it switches between shared and per-head weights, which clears them.  A backward over
+ * no tokens writes zeros.  d_phi above 16 is HLA_ERR_UNSUPPORTED.
  * The first registration allocates the partial-sum workspace (synchronous; HLA_ERR_ALLOC on
  * failure). */
 hla_status hla_set_phi_weight_grads(hla_handle* h, const hla_phi_weight_grads* maps,

@@ -290,7 +290,10 @@ hla_status hla_set_phi_weights(hla_handle* hd, const hla_phi_weights* maps, int3
   for (int m = 0; m < num_maps; ++m)
     if (!maps[m].W1 || !maps[m].b1 || !maps[m].W2 || !maps[m].b2) return HLA_ERR_INVALID_ARG;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const int32_t heads_w_before = hd->have_weights ? hd->phi.heads_w : 0;
   HLA_TRY(convert_weights_to_f32(hd, maps, s));
+  // gradient arrays registered for the other sharing mode no longer have the right shape
+  if (heads_w_before != 0 && heads_w_before != hd->phi.heads_w) hd->wg_on = false;
   HLA_TRY(hd->path == HLA_PATH_MFMA ? mfma_set_weights(hd, s) : generic_set_weights(hd, s));
   hd->have_weights = true;
   hd->have_forward = false;
@@ -309,6 +312,7 @@ hla_status hla_set_phi_weight_grads(hla_handle* hd, const hla_phi_weight_grads* 
   if (num_maps != 1 + hd->cfg.degree) return HLA_ERR_INVALID_ARG;
   for (int m = 0; m < num_maps; ++m)
     if (!maps[m].dW1 || !maps[m].db1 || !maps[m].dW2 || !maps[m].db2) return HLA_ERR_INVALID_ARG;
+  if (hd->cfg.feature_dim > 16) return HLA_ERR_UNSUPPORTED;  // the kernels keep a W2 row in 16 registers
   if (hd->wg_partial == nullptr) {
     const Geom& g = hd->g;
     hd->wg_part_floats = static_cast<int64_t>(g.d) * g.d + g.d + static_cast<int64_t>(g.d) * g.dphi + g.dphi;
@@ -376,7 +380,13 @@ hla_status hla_backward(hla_handle* hd, int32_t B, int32_t H, int32_t N, const i
     if (!same) return HLA_ERR_STATE;
   }
   HLA_TRY(prepare_call(hd, B, H, N, cu_seqlens, num_seqs, &empty, &nseq));
-  if (empty) return HLA_OK;
+  if (empty) {
+    // no token contributes: the registered weight gradients are still overwritten, with zeros
+    if (hd->wg_on && H > 0)
+      HLA_TRY(weight_grads_reduce(hd, 0, hd->phi.heads_w == 1 ? 1 : H, 0.0f, 0.0f, 0.0f, 0.0f,
+                                  static_cast<hipStream_t>(hip_stream)));
+    return HLA_OK;
+  }
   if (bad_view(Q) || bad_view(K) || bad_view(V) || bad_view(O) || bad_view(dO) || bad_view(dQ) ||
       bad_view(dK) || bad_view(dV))
     return HLA_ERR_INVALID_ARG;

@@ -109,3 +109,49 @@ def test_registration_rules_and_repeatability():
         h2.set_phi_weight_grads(wg)
     assert e.value.code == 5
     h2.destroy()
+
+
+def test_fewer_heads_than_the_handle_allows_and_empty_input():
+    dev = torch.device("cuda:0")
+    Hmax, H, N, d = 4, 2, 70, 64
+    t, _ = wl.make_raw_inputs(790, 1, H, N, d, 3, 6, torch.bfloat16)
+    phi = _per_head_phi(791, Hmax, d, 6, 4, torch.bfloat16)
+    h = hla.HLA(head_dim=d, io_dtype=hla.HLA_BF16, max_heads=Hmax, max_tokens=N, max_seqs=1)
+    phid = [{k: v.to(dev) for k, v in m.items()} for m in phi]
+    h.set_phi_weights(phid, per_head=True)
+    wg = [{"d" + k: torch.full(v.shape, 7.0, dtype=torch.float32, device=dev) for k, v in m.items()}
+          for m in phid]
+    h.set_phi_weight_grads(wg)
+    td = {k: v.to(dev) for k, v in t.items()}
+    O = torch.empty_like(td["V"])
+    g = [torch.empty_like(td[k]) for k in "QKV"]
+    h.forward(td["Q"], td["K"], td["V"], O)
+    h.backward(td["Q"], td["K"], td["V"], O, td["dO"], *g)
+    torch.cuda.synchronize()
+    # heads the call did not cover keep what the arrays held; the others match the oracle
+    ref = pu.run_oracle_per_head(t, 3, 6, 1e-6, [{k: v[:H] for k, v in m.items()} for m in phi])
+    for m in range(4):
+        for k in pu.WG_KEYS:
+            assert bool((wg[m][k][H:] == 7.0).all()), (m, k)
+    pu.assert_weight_grad_parity([{k: v[:H].cpu() for k, v in m.items()} for m in wg], ref["wg"], 2e-2,
+                                 "two of four heads")
+    # a backward over no tokens writes zeros for the heads it names
+    e = {k: v[:, :, :0] for k, v in td.items()}
+    Oe = torch.empty_like(e["V"])
+    ge = [torch.empty_like(e[k]) for k in "QKV"]
+    h.forward(e["Q"], e["K"], e["V"], Oe)
+    h.backward(e["Q"], e["K"], e["V"], Oe, e["dO"], *ge)
+    torch.cuda.synchronize()
+    for m in range(4):
+        for k in pu.WG_KEYS:
+            assert bool((wg[m][k][:H] == 0.0).all()) and bool((wg[m][k][H:] == 7.0).all()), (m, k)
+    # switching to shared weights drops the per-head registration: nothing is written any more
+    h.set_phi_weights([{k: v[0].contiguous() for k, v in m.items()} for m in phid])
+    for m in wg:
+        for v in m.values():
+            v.fill_(3.0)
+    h.forward(td["Q"], td["K"], td["V"], O)
+    h.backward(td["Q"], td["K"], td["V"], O, td["dO"], *g)
+    torch.cuda.synchronize()
+    assert all(bool((v == 3.0).all()) for m in wg for v in m.values())
+    h.destroy()
