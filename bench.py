@@ -68,8 +68,8 @@ def cpu_baseline(w, phi, backward, features):
         cores = os.cpu_count() or 1
     H = w.H
     n_seq = w.N if w.cu_seqlens is None else w.cu_seqlens[1] - w.cu_seqlens[0]
-    # about 2.5 s per 32760-token head on 8 cores: take enough heads for ~10 s
-    heads = max(1, min(H, int(round(4 * 32760 / max(n_seq, 1)))))
+    # about 1 s per 32760-token head (fwd+bwd) on 16 cores: take enough heads for 10 s or more
+    heads = max(1, min(H, int(round(12 * 32760 / max(n_seq, 1)))))
     sl = (slice(0, 1), slice(0, heads), slice(0, n_seq))
     t = {k: pu.to_np(v[sl]) for k, v in w.tensors.items()}
     ophi = None if features else pu.oracle_phi(phi)
