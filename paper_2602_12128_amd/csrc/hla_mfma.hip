@@ -836,15 +836,29 @@ __global__ __launch_bounds__(kThreads) void k_bwd_key(Geom g, const BlockEnt* __
   flush_df(0, 3 * DP);
 }
 
-inline int pick_chunk(const Geom& g, int num_seqs) {
-  // About one workgroup per compute unit over all (sequence, head) units (the kernels hold one
-  // workgroup per CU), in multiples of the 256 tokens a workgroup consumes per round.  With the
-  // mean sequence length L and c chunks wanted per unit: chunks * H <= kChunkTarget + units.
-  const int units = num_seqs * g.H > 0 ? num_seqs * g.H : 1;
-  const int per_unit = kChunkTarget / units > 0 ? kChunkTarget / units : 1;
-  const int64_t mean_len = (static_cast<int64_t>(g.B) * g.N + num_seqs - 1) / (num_seqs > 0 ? num_seqs : 1);
-  const int64_t chunk = ((mean_len + per_unit - 1) / per_unit + 255) / 256 * 256;
-  return static_cast<int>(chunk < 256 ? 256 : chunk);
+inline int pick_chunk(const hla_handle* hd, const Geom& g, int num_seqs) {
+  // The chunked kernels hold one workgroup per compute unit, so a grid of more than one round is
+  // mostly a second, nearly empty round: take the smallest chunk (a multiple of the 256 tokens a
+  // workgroup consumes per step) whose chunks, counted sequence by sequence and times H, stay
+  // within kChunkTarget -- or one chunk per sequence when even that is too many.
+  int64_t total = 0, longest = 0;
+  auto len = [&](int s) -> int64_t {
+    return hd->sig_packed ? hd->cu_host[s + 1] - hd->cu_host[s] : g.N;
+  };
+  for (int s = 0; s < num_seqs; ++s) {
+    total += len(s);
+    longest = len(s) > longest ? len(s) : longest;
+  }
+  auto count = [&](int64_t chunk) {
+    int64_t c = 0;
+    for (int s = 0; s < num_seqs; ++s) c += (len(s) + chunk - 1) / chunk;
+    return c * g.H;
+  };
+  const int64_t H = g.H > 0 ? g.H : 1;
+  int64_t chunk = ((total * H + kChunkTarget - 1) / kChunkTarget + 255) / 256 * 256;
+  if (chunk < 256) chunk = 256;
+  while (count(chunk) > kChunkTarget && chunk < longest) chunk += (chunk / 64 + 255) / 256 * 256;
+  return static_cast<int>(chunk);
 }
 
 inline int pick_query_block(const Geom& g, int num_seqs) {
@@ -870,7 +884,7 @@ hla_status backward_core(hla_handle* hd, const hla_call_args& a) {
   using SL = StateLayout<DP, D>;
   Geom g = hd->g;
   hipStream_t s = a.stream;
-  const int chunk = pick_chunk(g, a.num_seqs);
+  const int chunk = pick_chunk(hd, g, a.num_seqs);
   hla_token_table* chunks = nullptr;
   HLA_TRY(get_table(hd, chunk, s, &chunks));
   static bool attr_set = false;
@@ -897,7 +911,7 @@ hla_status forward_core(hla_handle* hd, const hla_call_args& a) {
   using SM = StateSmem<D>;
   Geom g = hd->g;
   hipStream_t s = a.stream;
-  const int chunk = pick_chunk(g, a.num_seqs);
+  const int chunk = pick_chunk(hd, g, a.num_seqs);
   hla_token_table *chunks = nullptr, *qblocks = nullptr;
   HLA_TRY(get_table(hd, chunk, s, &chunks));
   HLA_TRY(get_table(hd, pick_query_block(g, a.num_seqs), s, &qblocks));
@@ -935,7 +949,7 @@ hla_status mfma_workspace_plan(hla_handle* hd) {
   const Geom& g = hd->g;
   const int64_t MP = 64, SP = 32;
   hd->state_stride = MP * g.d + MP;
-  // pick_chunk keeps chunks * H <= kChunkTarget + num_seqs * H
+  // pick_chunk keeps chunks * H <= kChunkTarget + num_seqs * H (it only ever grows the chunk)
   hd->max_chunks = (kChunkTarget + hd->cfg.max_heads - 1) / hd->cfg.max_heads + hd->cfg.max_seqs + 1;
   hd->yhat_floats = 1;
   // per unit: opA + opB (bf16) + zslot, for the state and for its gradient

@@ -62,6 +62,13 @@ def _spec(idx: int) -> Workload:
         for n in lens:
             cu.append(cu[-1] + n)
         return Workload("c5_packed_fwdbwd_bf16", 1, 12, cu[-1], 128, seed=4, cu_seqlens=cu)
+    # variants of configuration 3 that the paper also evaluates (not headline configurations)
+    if idx == 6:  # the lower resolution of Sec. 5.1: 81x320x480 video -> 12600 tokens
+        return Workload("r2_dit320p_fwdbwd_bf16", 1, 12, 12600, 128, seed=5,
+                        value_recipe="unit_norm", grid=(21, 20, 30))
+    if idx == 7:  # two Hadamard factors with 12 features (App. A.1)
+        return Workload("c3_dit480p_2factor_fwdbwd_bf16", 1, 12, 32760, 128, F=2, d_phi=12, seed=6,
+                        value_recipe="unit_norm", grid=(21, 30, 52))
     raise ValueError(f"no such configuration: {idx}")
 
 
@@ -94,7 +101,7 @@ def draw_phi_weights(gen, d: int, d_phi: int, n_maps: int, dtype,
 
 
 def make_workload(idx: int, *, need_backward: Optional[bool] = None) -> Workload:
-    """Build configuration `idx` (1..5) with all tensors on the CPU in the I/O dtype."""
+    """Build configuration `idx` (1..5, or a variant 6..7) with all tensors on the CPU in the I/O dtype."""
     w = _spec(idx)
     if need_backward is not None:
         w.backward = w.backward and need_backward
