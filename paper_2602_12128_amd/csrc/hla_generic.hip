@@ -60,36 +60,49 @@ __global__ void k_convert_weights(const T* __restrict__ src, int64_t head_stride
   if (i < count && hw < heads_w) dst[static_cast<int64_t>(hw) * count + i] = to_float(src[hw * head_stride + i]);
 }
 
-// PHI_NONE: copy caller-provided features into the fp32 feature workspace.
+// PHI_NONE: copy caller-provided features into the fp32 feature workspace.  One thread per
+// token-head: its two feature rows are contiguous in the caller's tensors, and in the tiled
+// workspace of the MFMA path 32 consecutive threads write 32 consecutive floats per feature.
 template <typename T>
 __global__ void k_feat_import(Geom g, View Q, View K, float* __restrict__ feat) {
-  const int64_t idx = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
-  const int64_t total = static_cast<int64_t>(g.B) * g.H * g.N * g.nfeat;
-  if (idx >= total) return;
-  const int j = static_cast<int>(idx % g.nfeat);
-  const int64_t th = idx / g.nfeat;
+  const uint32_t th = blockIdx.x * blockDim.x + threadIdx.x;
+  if (th >= static_cast<uint32_t>(g.B) * g.H * g.N) return;  // < 2^31 by the create-time check
   const int n = static_cast<int>(th % g.N);
-  const int h = static_cast<int>((th / g.N) % g.H);
-  const int b = static_cast<int>(th / (static_cast<int64_t>(g.N) * g.H));
-  feat[g.fidx(th, j)] = j < g.dphi ? to_float(Q.row<const T>(b, h, n)[j])
-                                   : to_float(K.row<const T>(b, h, n)[j - g.dphi]);
+  const uint32_t bh = th / g.N;
+  const int h = static_cast<int>(bh % g.H), b = static_cast<int>(bh / g.H);
+  const T* q = Q.row<const T>(b, h, n);
+  const T* k = K.row<const T>(b, h, n);
+  for (int j = 0; j < g.dphi; ++j) feat[g.fidx(th, j)] = to_float(q[j]);
+  for (int j = g.dphi; j < g.nfeat; ++j) feat[g.fidx(th, j)] = to_float(k[j - g.dphi]);
 }
 
 // PHI_NONE: feature gradients are the answer; store them in the I/O dtype.
 template <typename T>
 __global__ void k_dfeat_export(Geom g, const float* __restrict__ dfeat, View dQ, View dK) {
-  const int64_t idx = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
-  const int64_t total = static_cast<int64_t>(g.B) * g.H * g.N * g.nfeat;
-  if (idx >= total) return;
-  const int j = static_cast<int>(idx % g.nfeat);
-  const int64_t th = idx / g.nfeat;
+  const uint32_t th = blockIdx.x * blockDim.x + threadIdx.x;
+  if (th >= static_cast<uint32_t>(g.B) * g.H * g.N) return;
   const int n = static_cast<int>(th % g.N);
-  const int h = static_cast<int>((th / g.N) % g.H);
-  const int b = static_cast<int>(th / (static_cast<int64_t>(g.N) * g.H));
-  if (j < g.dphi)
-    dQ.row<T>(b, h, n)[j] = from_float<T>(dfeat[g.fidx(th, j)]);
-  else
-    dK.row<T>(b, h, n)[j - g.dphi] = from_float<T>(dfeat[g.fidx(th, j)]);
+  const uint32_t bh = th / g.N;
+  const int h = static_cast<int>(bh % g.H), b = static_cast<int>(bh / g.H);
+  T* q = dQ.row<T>(b, h, n);
+  T* k = dK.row<T>(b, h, n);
+  if constexpr (sizeof(T) == 2) {
+    // two bf16 values per store where the rows allow it
+    const bool pairs = g.dphi % 2 == 0 && ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k)) & 3) == 0;
+    if (pairs) {
+      uint32_t* q2 = reinterpret_cast<uint32_t*>(q);
+      uint32_t* k2 = reinterpret_cast<uint32_t*>(k);
+      for (int j = 0; j < g.dphi; j += 2)
+        q2[j / 2] = static_cast<uint32_t>(f32_to_bf16_bits(dfeat[g.fidx(th, j)])) |
+                    (static_cast<uint32_t>(f32_to_bf16_bits(dfeat[g.fidx(th, j + 1)])) << 16);
+      for (int j = g.dphi; j < g.nfeat; j += 2)
+        k2[(j - g.dphi) / 2] = static_cast<uint32_t>(f32_to_bf16_bits(dfeat[g.fidx(th, j)])) |
+                               (static_cast<uint32_t>(f32_to_bf16_bits(dfeat[g.fidx(th, j + 1)])) << 16);
+      return;
+    }
+  }
+  for (int j = 0; j < g.dphi; ++j) q[j] = from_float<T>(dfeat[g.fidx(th, j)]);
+  for (int j = g.dphi; j < g.nfeat; ++j) k[j - g.dphi] = from_float<T>(dfeat[g.fidx(th, j)]);
 }
 
 // ---- feature maps (App. A.1) ------------------------------------------------------------------
@@ -640,7 +653,7 @@ hla_status features_in_t(hla_handle* hd, const hla_call_args& a) {
   hipStream_t s = a.stream;
   const int d = g.d;
   if (hd->cfg.phi_mode == HLA_PHI_NONE) {
-    const int64_t total = static_cast<int64_t>(g.B) * g.H * g.N * g.nfeat;
+    const int64_t total = static_cast<int64_t>(g.B) * g.H * g.N;
     return launch(hd, "generic_feat_import", k_feat_import<T>, dim3((total + 255) / 256), dim3(256),
                   0, s, g, a.Q, a.K, hd->feat);
   }
@@ -656,7 +669,7 @@ hla_status features_out_t(hla_handle* hd, const hla_call_args& a) {
   hipStream_t s = a.stream;
   const int d = g.d;
   if (hd->cfg.phi_mode == HLA_PHI_NONE) {
-    const int64_t total = static_cast<int64_t>(g.B) * g.H * g.N * g.nfeat;
+    const int64_t total = static_cast<int64_t>(g.B) * g.H * g.N;
     return launch(hd, "generic_dfeat_export", k_dfeat_export<T>, dim3((total + 255) / 256), dim3(256),
                   0, s, g, hd->dfeat, a.dQ, a.dK);
   }
