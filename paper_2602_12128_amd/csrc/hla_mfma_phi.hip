@@ -736,7 +736,18 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_wgrad(Geom g, View Q, View K
   for (int ks = 0; ks < NKS; ++ks)
     w1a[ks] = *reinterpret_cast<const u32x4*>(wm + PK::kW1T + ((32 * hb + r) * D + 16 * ks + 8 * gl) * 2);
   const u32x4 w2b = *reinterpret_cast<const u32x4*>(wm + PK::kW2B + (hb * 64 + lane) * 16);
-  const float* b1 = reinterpret_cast<const float*>(wm + PK::kB1) + 32 * hb + 4 * gl;
+  f32x16 bias;  // first-layer bias of the block in accumulator order
+  {
+    const float* b1 = reinterpret_cast<const float*>(wm + PK::kB1) + 32 * hb + 4 * gl;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const f32x4 bv = *reinterpret_cast<const f32x4*>(b1 + 8 * i);
+      bias[4 * i] = bv[0];
+      bias[4 * i + 1] = bv[1];
+      bias[4 * i + 2] = bv[2];
+      bias[4 * i + 3] = bv[3];
+    }
+  }
   // token tiles: one list over all (batch row, head) pairs when the weights are shared
   const bool shared = heads_w == 1;
   const int tpr = (g.N + 31) / 32;
@@ -754,29 +765,47 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_wgrad(Geom g, View Q, View K
   }
 #pragma unroll
   for (int a = 0; a < kDP; ++a) db2[a] = 0.0f;
-  for (int tile = blockIdx.x * TH + th; tile < total; tile += gridDim.x * TH) {
-    const int row = tile / tpr, n0 = (tile % tpr) * 32;
-    const int b = shared ? row / g.H : row, h = shared ? row % g.H : hw;
+  // The next tile's inputs are loaded as soon as the current tile's have been consumed (the
+  // input rows after the copy to LDS, the features once du is formed).  These loads are
+  // unconditional with clamped addresses, so that the same number is outstanding on every path;
+  // the last tile is simply fetched twice.
+  const int step = gridDim.x * TH;
+  int tile = blockIdx.x * TH + th;
+  u32x4 xb[NKS];
+  float fv[kDP], dv[kDP];
+  auto coords = [&](int t, int& b, int& h, int& n0) {
+    const int row = t / tpr;
+    n0 = (t % tpr) * 32;
+    b = shared ? row / g.H : row;
+    h = shared ? row % g.H : hw;
+  };
+  auto fetch_features = [&](int b, int h, int n0) {
     const int n = n0 + r;
-    const bool live = n < g.N;
-    u32x4 xb[NKS];
-    load_x<D>(X, b, h, n, g.N, gl, xb);
+    const int64_t o = g.fidx(g.th(b, h, n < g.N ? n : g.N - 1), m * kDP);
+#pragma unroll
+    for (int a = 0; a < kDP; ++a) {
+      fv[a] = feat[o + 32 * a];
+      dv[a] = dfeat[o + 32 * a];
+    }
+  };
+  if (tile < total) {
+    int b, h, n0;
+    coords(tile, b, h, n0);
+    load_x<D>(X, b, h, n0 + r, g.N, gl, xb);
+    fetch_features(b, h, n0);
+  }
+  for (; tile < total; tile += step) {
+    int b, h, n0;
+    coords(tile, b, h, n0);
+    const bool live = n0 + r < g.N;
+    int bn, hn, n0n;
+    coords(tile + step < total ? tile + step : tile, bn, hn, n0n);
     // du of the token: zero where the ReLU was closed, and for tokens past the end (whose clamped
     // input row then adds nothing to any sum)
     float du[kDP];
 #pragma unroll
-    for (int a = 0; a < kDP; ++a) du[a] = 0.0f;
-    if (live && gl == 0) {
-      const int64_t o = g.fidx(g.th(b, h, n), m * kDP);
-      float fv[kDP], dv[kDP];
-#pragma unroll
-      for (int a = 0; a < kDP; ++a) {
-        fv[a] = feat[o + 32 * a];
-        dv[a] = dfeat[o + 32 * a];
-      }
-#pragma unroll
-      for (int a = 0; a < kDP; ++a) du[a] = fv[a] > 0.0f ? dv[a] : 0.0f;
-    }
+    for (int a = 0; a < kDP; ++a) du[a] = live && gl == 0 && fv[a] > 0.0f ? dv[a] : 0.0f;
+    fetch_features(bn, hn, n0n);
     u32x4 dub;
     dub[0] = pack_bf16(du[0], du[1]);
     dub[1] = pack_bf16(du[2], du[3]);
@@ -785,15 +814,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_wgrad(Geom g, View Q, View K
 #pragma unroll
     for (int a = 0; a < kDP; ++a) db2[a] += du[a];
     // hidden block of the first layer (a quarter of its scale) and dg = 4 W2 du
-    f32x16 cur;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const f32x4 bv = *reinterpret_cast<const f32x4*>(b1 + 8 * i);
-      cur[4 * i] = bv[0];
-      cur[4 * i + 1] = bv[1];
-      cur[4 * i + 2] = bv[2];
-      cur[4 * i + 3] = bv[3];
-    }
+    f32x16 cur = bias;
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) cur = mfma32(w1a[ks], xb[ks], cur);
     f32x16 zero;
@@ -804,6 +825,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_wgrad(Geom g, View Q, View K
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks)
       *reinterpret_cast<u32x4*>(xt + r * SM::kXStride + (16 * ks + 8 * gl) * 2) = xb[ks];
+    load_x<D>(X, bn, hn, n0n + r, g.N, gl, xb);
     {
       u32x4 z4;
       z4[0] = z4[1] = z4[2] = z4[3] = 0u;
@@ -954,7 +976,10 @@ hla_status backward_t(hla_handle* hd, const hla_call_args& a) {
   return HLA_OK;
 }
 
-constexpr int kWavesW = 8;
+#ifndef HLA_WG_WAVES
+#define HLA_WG_WAVES 4
+#endif
+constexpr int kWavesW = HLA_WG_WAVES;  // one wave per SIMD: the live set needs more than 256 registers
 
 template <int D>
 hla_status weight_grads_t(hla_handle* hd, const hla_call_args& a) {
