@@ -701,6 +701,9 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_bwd(Geom g, View X,
 // columns of partial number blockIdx.x * T + th of this (map, head):
 //   [dW1 D*D | db1 D | dW2 D*d_phi | db2 d_phi] floats, scaled by the packing factors
 // (dW1, db1 four times too large, dW2 four times too small); a second kernel adds the partials.
+// A workgroup has four waves, one per SIMD: accumulators, resident operands and two tiles of
+// prefetched inputs need more than the 256 registers a wave gets when two share a SIMD, so the
+// overlap of vector and matrix work comes from a software pipeline inside the wave instead.
 template <int D>
 struct WgSmem {
   static constexpr int kXStride = (D + 32) * 2 + 32;  // bytes per token row: channels, 32 du columns, pad
@@ -721,12 +724,15 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_wgrad(Geom g, View Q, View K
   constexpr int NRB = D / 32, NKS = D / 16, TH = WAVES / NRB;
   static_assert(WAVES % NRB == 0, "whole groups of hidden blocks");
   extern __shared__ __align__(16) unsigned char smem[];
-  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const int lane = threadIdx.x % kWave;
+  // the wave index as a scalar: everything derived from it (tile numbers, batch row, head, first
+  // token) then lives on the scalar unit, integer divisions included
+  const int wave = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x) / kWave);
   const int r = lane % 32, gl = lane / 32;
   const int L = lane % 16, q = lane / 16;
   const int hb = wave % NRB, th = wave / NRB;
   const int m = blockIdx.y, hw = blockIdx.z;
-  unsigned char* xt = smem + wave * SM::kWaveBytes;
+  unsigned char* xt = smem + wave * 2 * SM::kWaveBytes;  // two sets of (X tile, G tile)
   unsigned char* gt = xt + SM::kXBytes;
   const unsigned char* wm = wpk + (static_cast<int64_t>(m) * heads_w + hw) * PK::kBytes;
   const View& X = m == 0 ? Q : K;
@@ -771,7 +777,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_wgrad(Geom g, View Q, View K
   // the last tile is simply fetched twice.
   const int step = gridDim.x * TH;
   int tile = blockIdx.x * TH + th;
-  u32x4 xb[NKS];
+  u32x4 xb[NKS], xn[NKS];  // input rows of the next tile and of the one after
   float fv[kDP], dv[kDP];
   auto coords = [&](int t, int& b, int& h, int& n0) {
     const int row = t / tpr;
@@ -788,53 +794,144 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_wgrad(Geom g, View Q, View K
       dv[a] = dfeat[o + 32 * a];
     }
   };
-  if (tile < total) {
-    int b, h, n0;
-    coords(tile, b, h, n0);
-    load_x<D>(X, b, h, n0 + r, g.N, gl, xb);
-    fetch_features(b, h, n0);
+  // Two sets of LDS tiles: while the vector ALU turns tile t's hidden block into dh and GELU(h)
+  // (set t % 2), the matrix pipe runs the first layer of tile t+1 and the contractions of tile
+  // t-1 (set (t-1) % 2), a few MFMAs between the quarters of the vector work.  The sets start as
+  // zeros, so the contraction "of the tile before the first" adds nothing.
+  // (set s of this wave: X tile at xt + s * kWaveBytes, G tile at gt + s * kWaveBytes)
+  {
+    u32x4 z4;
+    z4[0] = z4[1] = z4[2] = z4[3] = 0u;
+    for (int o = lane * 16; o < 2 * SM::kWaveBytes; o += 64 * 16) *reinterpret_cast<u32x4*>(xt + o) = z4;
   }
-  for (; tile < total; tile += step) {
-    int b, h, n0;
-    coords(tile, b, h, n0);
-    const bool live = n0 + r < g.N;
-    int bn, hn, n0n;
-    coords(tile + step < total ? tile + step : tile, bn, hn, n0n);
+  auto make_du = [&](bool live, u32x4& dub) {
     // du of the token: zero where the ReLU was closed, and for tokens past the end (whose clamped
     // input row then adds nothing to any sum)
     float du[kDP];
 #pragma unroll
     for (int a = 0; a < kDP; ++a) du[a] = live && gl == 0 && fv[a] > 0.0f ? dv[a] : 0.0f;
-    fetch_features(bn, hn, n0n);
-    u32x4 dub;
     dub[0] = pack_bf16(du[0], du[1]);
     dub[1] = pack_bf16(du[2], du[3]);
     dub[2] = pack_bf16(du[4], du[5]);
     dub[3] = 0u;
 #pragma unroll
     for (int a = 0; a < kDP; ++a) db2[a] += du[a];
-    // hidden block of the first layer (a quarter of its scale) and dg = 4 W2 du
-    f32x16 cur = bias;
-#pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) cur = mfma32(w1a[ks], xb[ks], cur);
-    f32x16 zero;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) zero[i] = 0.0f;
-    const f32x16 dg = mfma32(w2b, dub, zero);
-    // [token][channels | du] tile
+  };
+  auto put_x_tile = [&](unsigned char* xdst, const u32x4 (&xr)[NKS], const u32x4& dub) {  // [token][channels | du]
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks)
-      *reinterpret_cast<u32x4*>(xt + r * SM::kXStride + (16 * ks + 8 * gl) * 2) = xb[ks];
-    load_x<D>(X, bn, hn, n0n + r, g.N, gl, xb);
+      *reinterpret_cast<u32x4*>(xdst + r * SM::kXStride + (16 * ks + 8 * gl) * 2) = xr[ks];
+    u32x4 z4;
+    z4[0] = z4[1] = z4[2] = z4[3] = 0u;
+    *reinterpret_cast<u32x4*>(xdst + r * SM::kXStride + (D + 16 * gl) * 2) = gl == 0 ? dub : z4;
+    *reinterpret_cast<u32x4*>(xdst + r * SM::kXStride + (D + 16 * gl + 8) * 2) = z4;
+  };
+  // transpose-read operand: tokens 16 ks + 8 gl + {0..7} of 32 columns starting at col0
+  auto operand = [&](const unsigned char* tl, int stride, int ks, int col0) {
+    const int krow = 16 * ks + 8 * gl + L / 4;
+    const unsigned char* p = tl + krow * stride + (col0 + 16 * (q % 2) + 4 * (L % 4)) * 2;
+    const u32x2 lo = lds_read_tr16(p);
+    const u32x2 hi = lds_read_tr16(p + 4 * stride);
+    u32x4 o;
+    o[0] = lo[0];
+    o[1] = lo[1];
+    o[2] = hi[0];
+    o[3] = hi[1];
+    return o;
+  };
+  f32x16 zero;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) zero[i] = 0.0f;
+  f32x16 cur = bias, dg = zero;
+  int buf = 0;
+  if (tile < total) {
+    // first tile: inputs, first layer, dg, [token][channels | du] tile; then the second tile's loads
+    int b, h, n0;
+    coords(tile, b, h, n0);
+    load_x<D>(X, b, h, n0 + r, g.N, gl, xb);
+    fetch_features(b, h, n0);
+    u32x4 dub;
+    make_du(n0 + r < g.N, dub);
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) cur = mfma32(w1a[ks], xb[ks], cur);
+    dg = mfma32(w2b, dub, zero);
+    wave_lds_sync();  // the zero fill is complete
+    put_x_tile(xt, xb, dub);
+    coords(tile + step < total ? tile + step : tile, b, h, n0);
+    load_x<D>(X, b, h, n0 + r, g.N, gl, xb);
+    fetch_features(b, h, n0);
+  }
+  // One stage per tile t: its vector work, the first layer of tile t+1 (input rows in xb) and the
+  // contractions of tile t-1; tile t+2's input rows are loaded into xn and move to xb at the end.
+  for (; tile < total; tile += step) {
+    // xb, fv, dv hold tile t+1 (the last tile again when there is none); cur, dg belong to tile t
+    const int tn = tile + step < total ? tile + step : tile;
+    int b, h, n0;
+    coords(tn, b, h, n0);
+    // tile t+2's input rows: issued first, a whole stage ahead of their use
     {
-      u32x4 z4;
-      z4[0] = z4[1] = z4[2] = z4[3] = 0u;
-      *reinterpret_cast<u32x4*>(xt + r * SM::kXStride + (D + 16 * gl) * 2) = gl == 0 ? dub : z4;
-      *reinterpret_cast<u32x4*>(xt + r * SM::kXStride + (D + 16 * gl + 8) * 2) = z4;
+      int b2, h2, n02;
+      coords(tile + 2 * step < total ? tile + 2 * step : tn, b2, h2, n02);
+      load_x<D>(X, b2, h2, n02 + r, g.N, gl, xn);
     }
-    // [token][dh | GELU(h)] tile: a slice covers hidden 8j + 4gl .. +3 of the block
+    u32x4 dubn;
+    {
+      // the next tile's du without touching db2 twice for a repeated last tile
+      float du[kDP];
+      const bool live = n0 + r < g.N && tile + step < total;
+#pragma unroll
+      for (int a = 0; a < kDP; ++a) du[a] = live && gl == 0 && fv[a] > 0.0f ? dv[a] : 0.0f;
+      dubn[0] = pack_bf16(du[0], du[1]);
+      dubn[1] = pack_bf16(du[2], du[3]);
+      dubn[2] = pack_bf16(du[4], du[5]);
+      dubn[3] = 0u;
+#pragma unroll
+      for (int a = 0; a < kDP; ++a) db2[a] += du[a];
+    }
+    {
+      int b2, h2, n02;
+      coords(tile + 2 * step < total ? tile + 2 * step : tn, b2, h2, n02);
+      fetch_features(b2, h2, n02);
+    }
+    const unsigned char* xp = xt + (buf ^ 1) * SM::kWaveBytes;  // tiles of tile t-1
+    const unsigned char* gp_ = gt + (buf ^ 1) * SM::kWaveBytes;
+    unsigned char* gcur = gt + buf * SM::kWaveBytes;
+    f32x16 nxt = bias;
+    // Operands of the contractions are read one slice ahead, before that slice's LDS writes: a
+    // read cannot be moved above an earlier write to the same memory, so a read placed at its
+    // use would wait out its whole latency there.  Slice j = 2 ks + half uses the token step ks
+    // and the input-channel blocks of its half (the du block rides with the first half).
+    constexpr int NH = NRB / 2;
+    auto read_ops = [&](int j, u32x4 (&ops)[NH + 1], u32x4& bdh_, u32x4& bg_) {
+      const int ks = j / 2, half = j % 2;
+#pragma unroll
+      for (int x = 0; x < NH; ++x) ops[x] = operand(xp, SM::kXStride, ks, 32 * (half * NH + x));
+      if (half == 0) {
+        ops[NH] = operand(xp, SM::kXStride, ks, D);
+        bdh_ = operand(gp_, SM::kGStride, ks, 0);
+        bg_ = operand(gp_, SM::kGStride, ks, 32);
+      }
+    };
+    u32x4 ops[NH + 1], bdh, bg;
+    read_ops(0, ops, bdh, bg);
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
+      // matrix pipe: a quarter of tile t+1's first layer and of tile t-1's contractions
+      constexpr int kPer = NKS / 4;
+#pragma unroll
+      for (int t = 0; t < kPer; ++t) nxt = mfma32(w1a[j * kPer + t], xb[j * kPer + t], nxt);
+#pragma unroll
+      for (int x = 0; x < NH; ++x) acc[(j % 2) * NH + x] = mfma32(ops[x], bdh, acc[(j % 2) * NH + x]);
+      if (j % 2 == 0) acc2 = mfma32(ops[NH], bg, acc2);
+      if (j < 3) {
+        if (j % 2 == 0) {
+          u32x4 unused0, unused1;
+          read_ops(j + 1, ops, unused0, unused1);
+        } else {
+          read_ops(j + 1, ops, bdh, bg);
+        }
+      }
+      // vector ALU: slice j of tile t covers hidden 8j + 4gl .. +3 of the block
       const float in[4] = {cur[4 * j], cur[4 * j + 1], cur[4 * j + 2], cur[4 * j + 3]};
       f16x2 gv[2], gp[2];
       gelu_both_f16<2>(in, gv, gp);
@@ -851,33 +948,31 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_wgrad(Geom g, View Q, View K
       dh2[1] = pack_bf16(d2, d3);
       g2[0] = pack_bf16(static_cast<float>(gv[0][0]), static_cast<float>(gv[0][1]));
       g2[1] = pack_bf16(static_cast<float>(gv[1][0]), static_cast<float>(gv[1][1]));
-      *reinterpret_cast<u32x2*>(gt + r * SM::kGStride + (8 * j + 4 * gl) * 2) = dh2;
-      *reinterpret_cast<u32x2*>(gt + r * SM::kGStride + (32 + 8 * j + 4 * gl) * 2) = g2;
+      *reinterpret_cast<u32x2*>(gcur + r * SM::kGStride + (8 * j + 4 * gl) * 2) = dh2;
+      *reinterpret_cast<u32x2*>(gcur + r * SM::kGStride + (32 + 8 * j + 4 * gl) * 2) = g2;
     }
+    const f32x16 dgn = mfma32(w2b, dubn, zero);
+    // tile t+1's [token][channels | du] tile takes the set tile t-1 has just been read from
+    put_x_tile(xt + (buf ^ 1) * SM::kWaveBytes, xb, dubn);
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) xb[ks] = xn[ks];
     wave_lds_sync();
-    // contractions over the tile's 32 tokens (two 16-token steps)
+    cur = nxt;
+    dg = dgn;
+    buf ^= 1;
+  }
+  // contractions of the last tile (set buf ^ 1 after the final swap)
+  if (blockIdx.x * TH + th < total) {
+    const unsigned char* xp = xt + (buf ^ 1) * SM::kWaveBytes;
+    const unsigned char* gp_ = gt + (buf ^ 1) * SM::kWaveBytes;
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) {
-      const int krow = 16 * ks + 8 * gl + L / 4;  // token row this lane addresses for the transpose read
-      const int coff = (16 * (q % 2) + 4 * (L % 4)) * 2;
-      auto operand = [&](const unsigned char* tile, int stride, int col0) {
-        const unsigned char* p = tile + krow * stride + col0 * 2 + coff;
-        const u32x2 lo = lds_read_tr16(p);
-        const u32x2 hi = lds_read_tr16(p + 4 * stride);
-        u32x4 o;
-        o[0] = lo[0];
-        o[1] = lo[1];
-        o[2] = hi[0];
-        o[3] = hi[1];
-        return o;
-      };
-      const u32x4 bdh = operand(gt, SM::kGStride, 0);
-      const u32x4 bg = operand(gt, SM::kGStride, 32);
+      const u32x4 bdh = operand(gp_, SM::kGStride, ks, 0);
+      const u32x4 bg = operand(gp_, SM::kGStride, ks, 32);
 #pragma unroll
-      for (int ib = 0; ib < NRB; ++ib) acc[ib] = mfma32(operand(xt, SM::kXStride, 32 * ib), bdh, acc[ib]);
-      acc2 = mfma32(operand(xt, SM::kXStride, D), bg, acc2);
+      for (int ib = 0; ib < NRB; ++ib) acc[ib] = mfma32(operand(xp, SM::kXStride, ks, 32 * ib), bdh, acc[ib]);
+      acc2 = mfma32(operand(xp, SM::kXStride, ks, D), bg, acc2);
     }
-    wave_lds_sync();
   }
   // ---- this wave's share of the partial
   const int nparts = gridDim.x * TH;
@@ -985,7 +1080,7 @@ template <int D>
 hla_status weight_grads_t(hla_handle* hd, const hla_call_args& a) {
   using SM = WgSmem<D>;
   constexpr int TH = kWavesW / (D / 32);
-  constexpr int lds = kWavesW * SM::kWaveBytes;
+  constexpr int lds = 2 * kWavesW * SM::kWaveBytes;  // two sets of tiles per wave
   Geom g = hd->g;
   if (g.dphi != kDP || g.F != 3) return HLA_ERR_UNSUPPORTED;
   const unsigned char* wpk = static_cast<const unsigned char*>(hd->path_ws) + hd->w_packed_off;
@@ -1041,3 +1136,4 @@ hla_status mfma_phi_backward(hla_handle* hd, const hla_call_args& a) {
 }
 
 }  // namespace hla
+
