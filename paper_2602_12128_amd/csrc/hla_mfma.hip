@@ -135,7 +135,7 @@ __global__ __launch_bounds__(kThreads) void k_state(Geom g, const BlockEnt* __re
   static_assert(SY::MP == 64, "state kernel is laid out for a 64-row padded state");
   constexpr int NCB = D / 32;      // column blocks of the state
   extern __shared__ __align__(16) unsigned char smem[];
-  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const int lane = threadIdx.x % kWave, wave = wave_index();
   unsigned char* vs = smem + wave * SM::kWaveBytes;
   unsigned char* ss = vs + SM::kVBytes;
   const BlockEnt e = chunks[blockIdx.x];
@@ -348,7 +348,7 @@ __global__ __launch_bounds__(kThreads) void k_query(Geom g, const BlockEnt* __re
   constexpr int SP = SY::SP, MP = SY::MP;
   constexpr int NRB = D / 32, NKS = MP / 16;
   __shared__ __align__(16) unsigned char smem[kWaves * RowTile<D>::kBytes];
-  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const int lane = threadIdx.x % kWave, wave = wave_index();
   unsigned char* tile = smem + wave * RowTile<D>::kBytes;
   const int r = lane % 32, gl = lane / 32;
   const BlockEnt e = blocks[blockIdx.x];
@@ -440,7 +440,7 @@ __global__ __launch_bounds__(kThreads) void k_bwd_query(
   constexpr int NCB = D / 32, NKD = D / 16;
   constexpr int DROW = D * 2;  // bytes per dO tile row
   extern __shared__ __align__(16) unsigned char smem[];
-  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const int lane = threadIdx.x % kWave, wave = wave_index();
   unsigned char* ds = smem + wave * SM::kWaveBytes;
   unsigned char* qs = ds + SM::kDoBytes;
   const BlockEnt e = chunks[blockIdx.x];
@@ -649,7 +649,7 @@ __global__ __launch_bounds__(kThreads) void k_bwd_key(Geom g, const BlockEnt* __
   // transpose tile per wave for whole-row stores of dV
   constexpr int kOpImg = static_cast<int>(SL::kOpElems) * 2;  // bytes of one operand image
   __shared__ __align__(16) unsigned char smem[2 * kOpImg + kWaves * RowTile<D>::kBytes];
-  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const int lane = threadIdx.x % kWave, wave = wave_index();
   unsigned char* tile = smem + 2 * kOpImg + wave * RowTile<D>::kBytes;
   const int r = lane % 32, gl = lane / 32;
   const BlockEnt e = blocks[blockIdx.x];

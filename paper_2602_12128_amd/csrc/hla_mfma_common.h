@@ -65,6 +65,13 @@ __device__ __forceinline__ u32x2 lds_read_tr16(const void* lds_ptr) {
   return __builtin_bit_cast(u32x2, v);
 }
 
+// The wave's index in its workgroup as a scalar: what is derived from it (tile numbers, their
+// decoding into batch row / head / token with integer divisions, LDS region bases) then runs on
+// the scalar unit instead of costing vector-ALU slots in every lane.
+__device__ __forceinline__ int wave_index() {
+  return __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x) / kWave);
+}
+
 // Orders this wave's earlier LDS writes before its later LDS reads by other lanes of the same
 // wave (no s_barrier: waves of a workgroup run independent pipelines over private LDS regions).
 __device__ __forceinline__ void wave_lds_sync() {

@@ -330,7 +330,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_fwd(Geom g, View X,
   using SM = PhiSmem<D>;
   constexpr int NRB = D / 32, NKS = D / 16;
   extern __shared__ __align__(16) unsigned char smem[];
-  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const int lane = threadIdx.x % kWave, wave = wave_index();
   const int r = lane % 32, gl = lane / 32;
   const TileMap tm = make_tile_map(g, heads_w);
   const int hw = heads_w == 1 ? 0 : blockIdx.y;
@@ -480,7 +480,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_bwd(Geom g, View X,
   using SM = PhiSmem<D, true>;
   constexpr int NRB = D / 32, NKS = D / 16;
   extern __shared__ __align__(16) unsigned char smem[];
-  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const int lane = threadIdx.x % kWave, wave = wave_index();
   const int r = lane % 32, gl = lane / 32;
   const int L = lane % 16, q = lane / 16;
   const TileMap tm = make_tile_map(g, heads_w);
@@ -724,10 +724,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_wgrad(Geom g, View Q, View K
   constexpr int NRB = D / 32, NKS = D / 16, TH = WAVES / NRB;
   static_assert(WAVES % NRB == 0, "whole groups of hidden blocks");
   extern __shared__ __align__(16) unsigned char smem[];
-  const int lane = threadIdx.x % kWave;
-  // the wave index as a scalar: everything derived from it (tile numbers, batch row, head, first
-  // token) then lives on the scalar unit, integer divisions included
-  const int wave = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x) / kWave);
+  const int lane = threadIdx.x % kWave, wave = wave_index();
   const int r = lane % 32, gl = lane / 32;
   const int L = lane % 16, q = lane / 16;
   const int hb = wave % NRB, th = wave / NRB;
