@@ -20,6 +20,12 @@ namespace {
 using namespace mf;
 
 constexpr int kDP = 6;
+struct TrueTag {
+  static constexpr bool value = true;
+};
+struct FalseTag {
+  static constexpr bool value = false;
+};
 // waves per workgroup of the forward and backward kernels
 #ifndef HLA_PHI_WAVES_F
 #define HLA_PHI_WAVES_F 8
@@ -561,9 +567,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_bwd(Geom g, View X,
     const int ob = b, oh = h, on0 = n0;  // this tile's coordinates
     const bool more_tiles = tile + stride < tm.total;
     if (more_tiles) tm.decode(tile + stride, b, h, n0);  // b, h, n0 now name the next tile
-    f32x16 dx[NRB];
-#pragma unroll
-    for (int rb = 0; rb < NRB; ++rb) dx[rb] = zero_acc();
+    f32x16 dx[NRB];  // first written by the second stage of the first map (accumulating onto zero)
     // Software pipeline over 32-row blocks of the hidden layer, block t = m * NRB + rb.  Stage t:
     //   vector ALU : dh(t) = dg(t) * GELU'(hidden(t) + b1), packed as the B operand of dx
     //   matrix pipe: hidden(t+1) = W1^T X^T block (A: 16-byte LDS reads), dg(t) = W2 du^T block,
@@ -587,10 +591,11 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_bwd(Geom g, View X,
     }
     u32x4 dub = load_du(th, live, 0);
     u32x4 dhp[2];  // dh of the previous block (two 16-slot steps)
-    dhp[0][0] = dhp[0][1] = dhp[0][2] = dhp[0][3] = 0u;
-    dhp[1] = dhp[0];
-#pragma unroll 1
-    for (int m = 0; m < nmaps; ++m) {  // nmaps == NMAPS, passed at run time so this stays a loop
+    // The first map is peeled off the loop over maps: its first stage has no previous block (no dx
+    // step at all) and its second stage starts the dx accumulators from the constant zero, which
+    // spares clearing them and carrying them into the loop as copies.
+    auto run_map = [&](int m, auto first_tag) {
+      constexpr bool FIRST = decltype(first_tag)::value;
       const unsigned char* wm = smem + m * SM::kMap;
       const bool last_map = m + 1 == nmaps;
       const u32x4 dubn = load_du(th, live, last_map ? m : m + 1);
@@ -607,10 +612,13 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_bwd(Geom g, View X,
         u32x4 dhc[2];
         // transpose-read operands of the first dx step of this stage
         u32x2 tlo[NRB / 2], thi[NRB / 2];
+        const bool has_prev = !(FIRST && rb == 0);  // compile-time after unrolling
+        if (has_prev) {
 #pragma unroll
-        for (int x = 0; x < NRB / 2; ++x) {
-          tlo[x] = lds_read_tr16(wp + ks2p * 16 * SM::kRow + t_off[0][x]);
-          thi[x] = lds_read_tr16(wp + ks2p * 16 * SM::kRow + t_off[1][x]);
+          for (int x = 0; x < NRB / 2; ++x) {
+            tlo[x] = lds_read_tr16(wp + ks2p * 16 * SM::kRow + t_off[0][x]);
+            thi[x] = lds_read_tr16(wp + ks2p * 16 * SM::kRow + t_off[1][x]);
+          }
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -629,13 +637,16 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_bwd(Geom g, View X,
           // dx += W1[row blocks of this slice, hidden of block t-1] dh(t-1)^T
 #pragma unroll
           for (int x = 0; x < NRB / 2; ++x) {
+            if (!has_prev) break;
             const int rbx = (j % 2) * (NRB / 2) + x;
             u32x4 a;
             a[0] = tlo[x][0];
             a[1] = tlo[x][1];
             a[2] = thi[x][0];
             a[3] = thi[x][1];
-            dx[rbx] = mfma32(a, dhp[j / 2], dx[rbx]);
+            // each accumulator is touched twice per stage; its very first touch starts from zero
+            dx[rbx] = FIRST && rb == 1 && j < 2 ? mfma32(a, dhp[j / 2], zero_acc())
+                                                : mfma32(a, dhp[j / 2], dx[rbx]);
             // operands of the next slice's dx step (the last slice reads ahead into valid LDS)
             const int jn = j + 1 < 4 ? j + 1 : 3;
             const int rbn = (jn % 2) * (NRB / 2) + x;
@@ -664,7 +675,10 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_bwd(Geom g, View X,
         cur = nxt;
       }
       dub = dubn;
-    }
+    };
+    run_map(0, TrueTag{});
+#pragma unroll 1
+    for (int m = 1; m < nmaps; ++m) run_map(m, FalseTag{});  // nmaps == NMAPS, passed at run time so this stays a loop
     // dx of the last block
     {
       const unsigned char* wp = smem + (nmaps - 1) * SM::kMap;
