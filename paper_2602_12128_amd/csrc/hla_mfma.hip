@@ -25,7 +25,8 @@ constexpr int kWaves = kThreads / kWave;
 #define HLA_QUERY_TARGET 496
 #endif
 constexpr int kQueryTarget = HLA_QUERY_TARGET;  // workgroups aimed at by the query kernel
-constexpr int kChunkTarget = 240;   // workgroups aimed at by the chunked (token-contraction) kernels
+constexpr int kChunkTarget = 256;  // workgroups aimed at by the chunked (token-contraction) kernels: one per CU
+constexpr int kChunkGrain = 64;    // chunk sizes are multiples of this many tokens (one wave step of k_state)
 constexpr int kReduceSlices = 8;   // slices of the state per (sequence, head) in k_reduce
 
 // Where canonical monomial m sits among the (g, slot) pairs.
@@ -838,9 +839,9 @@ __global__ __launch_bounds__(kThreads) void k_bwd_key(Geom g, const BlockEnt* __
 
 inline int pick_chunk(const hla_handle* hd, const Geom& g, int num_seqs) {
   // The chunked kernels hold one workgroup per compute unit, so a grid of more than one round is
-  // mostly a second, nearly empty round: take the smallest chunk (a multiple of the 256 tokens a
-  // workgroup consumes per step) whose chunks, counted sequence by sequence and times H, stay
-  // within kChunkTarget -- or one chunk per sequence when even that is too many.
+  // mostly a second, nearly empty round, and the longest chunk sets the kernel's time: take the
+  // smallest chunk (a multiple of kChunkGrain tokens) whose chunks, counted sequence by sequence
+  // and times H, stay within kChunkTarget -- or one chunk per sequence when even that is too many.
   int64_t total = 0, longest = 0;
   auto len = [&](int s) -> int64_t {
     return hd->sig_packed ? hd->cu_host[s + 1] - hd->cu_host[s] : g.N;
@@ -855,9 +856,10 @@ inline int pick_chunk(const hla_handle* hd, const Geom& g, int num_seqs) {
     return c * g.H;
   };
   const int64_t H = g.H > 0 ? g.H : 1;
-  int64_t chunk = ((total * H + kChunkTarget - 1) / kChunkTarget + 255) / 256 * 256;
+  int64_t chunk = ((total * H + kChunkTarget - 1) / kChunkTarget + kChunkGrain - 1) / kChunkGrain * kChunkGrain;
   if (chunk < 256) chunk = 256;
-  while (count(chunk) > kChunkTarget && chunk < longest) chunk += (chunk / 64 + 255) / 256 * 256;
+  while (count(chunk) > kChunkTarget && chunk < longest)
+    chunk += (chunk / 64 + kChunkGrain - 1) / kChunkGrain * kChunkGrain;
   return static_cast<int>(chunk);
 }
 
