@@ -27,7 +27,7 @@ LAUNCH_NAMES = {
     "k_phi_bwd<64, 1": "mfma_phi_backward_q", "k_phi_bwd<64, 3": "mfma_phi_backward_k",
     "k_state<": "mfma_state", "k_query<": "mfma_query", "k_bwd_query<": "mfma_bwd_query",
     "k_bwd_key<": "mfma_bwd_key", "k_reduce<": "mfma_reduce",
-    "k_phi_wgrad<128, 8": "mfma_phi_weight_grads", "k_phi_wgrad<64, 8": "mfma_phi_weight_grads",
+    "k_phi_wgrad<128,": "mfma_phi_weight_grads", "k_phi_wgrad<64,": "mfma_phi_weight_grads",
     "k_wgrad_reduce": "phi_weight_grads_reduce",
 }
 
