@@ -141,7 +141,7 @@ __global__ __launch_bounds__(kThreads) void k_state(Geom g, const BlockEnt* __re
   unsigned char* ss = vs + SM::kVBytes;
   const BlockEnt e = chunks[blockIdx.x];
   const int h = blockIdx.y;
-  const int r = lane % 32, gq = lane / 32;   // MFMA operand coordinates
+  const int gq = lane / 32;                   // MFMA operand coordinates
   const int L = lane % 16, q = lane / 16;
 
   f32x16 acc[2][NCB];

@@ -973,7 +973,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_wgrad(Geom g, View Q, View K
     buf ^= 1;
   }
   // contractions of the last tile (set buf ^ 1 after the final swap)
-  if (blockIdx.x * TH + th < total) {
+  if (static_cast<int>(blockIdx.x) * TH + th < total) {
     const unsigned char* xp = xt + (buf ^ 1) * SM::kWaveBytes;
     const unsigned char* gp_ = gt + (buf ^ 1) * SM::kWaveBytes;
 #pragma unroll
