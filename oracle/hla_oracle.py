@@ -58,27 +58,32 @@ def phi_forward(x, W1, b1, W2, b2):
     return np.maximum(u, 0.0), h, u
 
 
-def phi_backward(dfeat, x, W1, b1, W2, b2):
+def phi_backward(dfeat, x, W1, b1, W2, b2, relu_open=None):
     """Gradient of a scalar loss w.r.t. x given its gradient w.r.t. phi(x) (chain rule through
-    ReLU, the second linear layer, GELU and the first linear layer of App. A.1)."""
+    ReLU, the second linear layer, GELU and the first linear layer of App. A.1).
+
+    The ReLU makes this gradient discontinuous where a pre-activation u crosses zero.  relu_open
+    (bool [N, d_phi]) replaces the oracle's own decision u > 0 by one taken elsewhere -- a parity
+    test passes the decisions of the implementation under test, taken in its precision, so that
+    both sides differentiate the same branch."""
     _, h, u = phi_forward(x, W1, b1, W2, b2)
-    du = np.asarray(dfeat, F64) * (u > 0.0)
+    du = np.asarray(dfeat, F64) * ((u > 0.0) if relu_open is None else np.asarray(relu_open, bool))
     dg = du @ np.asarray(W2, F64).T
     dh = dg * gelu_erf_grad(h)
     return dh @ np.asarray(W1, F64).T
 
 
-def phi_weight_grads(dfeat, x, W1, b1, W2, b2):
+def phi_weight_grads(dfeat, x, W1, b1, W2, b2, relu_open=None):
     """Gradient of a scalar loss w.r.t. the weights of one feature map given its gradient w.r.t.
     phi(x) for the N rows of x (same chain rule as phi_backward, App. A.1 layers; the paper trains
     these layers, Sec. 5 stage 1, and leaves the formulas to autograd):
       du = dfeat * [u > 0];  dW2 = g^T du;  db2 = sum_n du;  dg = du W2^T;
       dh = dg * GELU'(h);    dW1 = x^T dh;  db1 = sum_n dh.
-    Returns (dW1 [d,d], db1 [d], dW2 [d,d_phi], db2 [d_phi])."""
+    relu_open: as in phi_backward.  Returns (dW1 [d,d], db1 [d], dW2 [d,d_phi], db2 [d_phi])."""
     x = np.asarray(x, F64)
     _, h, u = phi_forward(x, W1, b1, W2, b2)
     g = gelu_erf(h)
-    du = np.asarray(dfeat, F64) * (u > 0.0)
+    du = np.asarray(dfeat, F64) * ((u > 0.0) if relu_open is None else np.asarray(relu_open, bool))
     dg = du @ np.asarray(W2, F64).T
     dh = dg * gelu_erf_grad(h)
     return x.T @ dh, dh.sum(axis=0), g.T @ du, du.sum(axis=0)
@@ -293,11 +298,14 @@ def hla_operator_forward(Q, K, V, F: int, d_phi: int, eps: float,
 def hla_operator_backward(Q, K, V, dO, F: int, d_phi: int, eps: float,
                           phi: Optional[Sequence[PhiWeights]] = None,
                           cu_seqlens: Optional[Sequence[int]] = None,
-                          route: str = "factorized", weight_grads: bool = False):
+                          route: str = "factorized", weight_grads: bool = False,
+                          relu_open=None):
     """(dQ, dK, dV) with the shapes of Q, K, V for L = sum(O * dO).  With feature maps, dK sums
     the contributions of the F key maps (they all read the same K).  With weight_grads (needs
     `phi`) a fourth result lists (dW1, db1, dW2, db2) for phi_q, phi_k1..phi_kF, each summed over
-    every sequence, head and token that shares the map."""
+    every sequence, head and token that shares the map.  relu_open (bool [B,H,N,(1+F)*d_phi], map
+    by map along the last dim) hands every feature map the ReLU decisions to differentiate
+    through (see phi_backward); None = the oracle's own."""
     B, H, N = V.shape[:3]
     dQ = np.zeros(Q.shape, F64)
     dK = np.zeros(K.shape, F64)
@@ -320,15 +328,20 @@ def hla_operator_backward(Q, K, V, dO, F: int, d_phi: int, eps: float,
                 dQ[b, h, lo:hi] = dqf
                 dK[b, h, lo:hi] = np.concatenate(dkfs, axis=1)
             else:
-                dQ[b, h, lo:hi] = phi_backward(dqf, Q[b, h, lo:hi], *phi[0].astuple())
+                def ro(m):  # ReLU decisions handed in for map m of this unit, or None
+                    if relu_open is None:
+                        return None
+                    return np.asarray(relu_open)[b, h, lo:hi, m * d_phi:(m + 1) * d_phi]
+                dQ[b, h, lo:hi] = phi_backward(dqf, Q[b, h, lo:hi], *phi[0].astuple(), relu_open=ro(0))
                 acc = np.zeros((hi - lo, K.shape[-1]), F64)
                 for f in range(F):
-                    acc += phi_backward(dkfs[f], K[b, h, lo:hi], *phi[1 + f].astuple())
+                    acc += phi_backward(dkfs[f], K[b, h, lo:hi], *phi[1 + f].astuple(),
+                                        relu_open=ro(1 + f))
                 dK[b, h, lo:hi] = acc
                 if wg is not None:
-                    parts = [phi_weight_grads(dqf, Q[b, h, lo:hi], *phi[0].astuple())]
-                    parts += [phi_weight_grads(dkfs[f], K[b, h, lo:hi], *phi[1 + f].astuple())
-                              for f in range(F)]
+                    parts = [phi_weight_grads(dqf, Q[b, h, lo:hi], *phi[0].astuple(), relu_open=ro(0))]
+                    parts += [phi_weight_grads(dkfs[f], K[b, h, lo:hi], *phi[1 + f].astuple(),
+                                               relu_open=ro(1 + f)) for f in range(F)]
                     for m, part in enumerate(parts):
                         for a, da in zip(wg[m], part):
                             a += da

@@ -77,6 +77,12 @@ def run_gpu(tensors: Dict[str, torch.Tensor], F: int, d_phi: int, eps: float,
     res = {k: v.cpu() for k, v in out.items()}
     if wg is not None:
         res["wg"] = [{k: v.cpu() for k, v in m.items()} for m in wg]
+        # the library's own ReLU decisions (feature > 0), for an oracle that differentiates the
+        # same branches: [B, H, N, (1+F)*d_phi]
+        B, H, N = t["V"].shape[:3]
+        nfeat = (1 + F) * d_phi
+        feats = h.read_workspace(hla.binding.HLA_WS_FEATURES, B * H * N * nfeat)
+        res["relu_open"] = feats.reshape(B, H, N, nfeat) > 0
     res["_path"] = h.active_path
     if handle is None:
         h.destroy()
@@ -84,7 +90,7 @@ def run_gpu(tensors: Dict[str, torch.Tensor], F: int, d_phi: int, eps: float,
 
 
 def run_oracle(tensors, F, d_phi, eps, phi=None, cu_seqlens=None, backward=True,
-               route="factorized", weight_grads=False):
+               route="factorized", weight_grads=False, relu_open=None):
     Q, K, V = (to_np(tensors[k]) for k in ("Q", "K", "V"))
     ophi = oracle_phi(phi)
     out = {"O": orc.hla_operator_forward(Q, K, V, F, d_phi, eps, phi=ophi, cu_seqlens=cu_seqlens,
@@ -92,14 +98,15 @@ def run_oracle(tensors, F, d_phi, eps, phi=None, cu_seqlens=None, backward=True,
     if backward:
         res = orc.hla_operator_backward(Q, K, V, to_np(tensors["dO"]), F, d_phi, eps,
                                         phi=ophi, cu_seqlens=cu_seqlens, route=route,
-                                        weight_grads=weight_grads)
+                                        weight_grads=weight_grads, relu_open=relu_open)
         out.update(dQ=res[0], dK=res[1], dV=res[2])
         if weight_grads:
             out["wg"] = [dict(zip(WG_KEYS, m)) for m in res[3]]
     return out
 
 
-def run_oracle_per_head(tensors, F, d_phi, eps, phi, cu_seqlens=None, weight_grads=True):
+def run_oracle_per_head(tensors, F, d_phi, eps, phi, cu_seqlens=None, weight_grads=True,
+                        relu_open=None):
     """Oracle for weights that carry a leading head dimension: the oracle's maps are shared by
     the heads it is given, so every head is run on its own with its own weights."""
     H = tensors["V"].shape[1]
@@ -108,7 +115,8 @@ def run_oracle_per_head(tensors, F, d_phi, eps, phi, cu_seqlens=None, weight_gra
         th = {k: v[:, h:h + 1] for k, v in tensors.items()}
         ph = [{k: v[h] for k, v in m.items()} for m in phi]
         outs.append(run_oracle(th, F, d_phi, eps, phi=ph, cu_seqlens=cu_seqlens,
-                               weight_grads=weight_grads))
+                               weight_grads=weight_grads,
+                               relu_open=None if relu_open is None else relu_open[:, h:h + 1]))
     out = {k: np.concatenate([o[k] for o in outs], axis=1) for k in ("O", "dQ", "dK", "dV")}
     if weight_grads:
         out["wg"] = [{k: np.stack([o["wg"][m][k] for o in outs]) for k in WG_KEYS}

@@ -34,7 +34,10 @@ def test_weight_grads_bf16_mfma_path(d, B, H, N):
     t, phi = wl.make_raw_inputs(720 + N, B, H, N, d, 3, 6, torch.bfloat16)
     gpu = pu.run_gpu(t, 3, 6, 1e-6, phi=phi, path=hla.HLA_PATH_MFMA, weight_grads=True)
     assert gpu["_path"] == hla.HLA_PATH_MFMA
-    ref = pu.run_oracle(t, 3, 6, 1e-6, phi=phi, weight_grads=True)
+    # a weight gradient sums over all tokens, so a token whose pre-ReLU value lies within the bf16
+    # noise of zero cannot be left out of the comparison: the oracle differentiates through the
+    # library's own ReLU decisions instead (the decision is taken in the kernel's precision)
+    ref = pu.run_oracle(t, 3, 6, 1e-6, phi=phi, weight_grads=True, relu_open=gpu["relu_open"])
     pu.assert_weight_grad_parity(gpu["wg"], ref["wg"], 2e-2, f"mfma bf16 d={d} N={N}")
 
 
@@ -45,14 +48,9 @@ def test_per_head_weights_and_their_gradients(path, dtype, tol):
     t, _ = wl.make_raw_inputs(740, B, H, N, d, 3, 6, dtype)
     phi = _per_head_phi(741, H, d, 6, 4, dtype)
     gpu = pu.run_gpu(t, 3, 6, 1e-6, phi=phi, path=path, weight_grads=True, per_head=True)
-    ref = pu.run_oracle_per_head(t, 3, 6, 1e-6, phi)
-    masks = None
-    if dtype == torch.bfloat16:
-        ok = [pu.relu_kink_masks({k: v[:, h:h + 1] for k, v in t.items()},
-                                 [{k: v[h] for k, v in m.items()} for m in phi], 3, 1e-2)
-              for h in range(H)]
-        masks = {k: np.concatenate([o[k] for o in ok], axis=1) for k in ("dQ", "dK")}
-    pu.assert_parity(gpu, ref, tol, "per-head weights", row_masks=masks)
+    ref = pu.run_oracle_per_head(t, 3, 6, 1e-6, phi,
+                                 relu_open=gpu["relu_open"] if dtype == torch.bfloat16 else None)
+    pu.assert_parity(gpu, ref, tol, "per-head weights")
     pu.assert_weight_grad_parity(gpu["wg"], ref["wg"], tol, "per-head weights")
 
 
@@ -60,7 +58,8 @@ def test_weight_grads_packed_sequences_bf16():
     cu = [0, 100, 100, 457, 600]
     t, phi = wl.make_raw_inputs(760, 1, 2, 600, 128, 3, 6, torch.bfloat16)
     gpu = pu.run_gpu(t, 3, 6, 1e-6, phi=phi, cu_seqlens=cu, weight_grads=True)
-    ref = pu.run_oracle(t, 3, 6, 1e-6, phi=phi, cu_seqlens=cu, weight_grads=True)
+    ref = pu.run_oracle(t, 3, 6, 1e-6, phi=phi, cu_seqlens=cu, weight_grads=True,
+                        relu_open=gpu["relu_open"])
     pu.assert_weight_grad_parity(gpu["wg"], ref["wg"], 2e-2, "packed bf16")
 
 
@@ -129,7 +128,10 @@ def test_fewer_heads_than_the_handle_allows_and_empty_input():
     h.backward(td["Q"], td["K"], td["V"], O, td["dO"], *g)
     torch.cuda.synchronize()
     # heads the call did not cover keep what the arrays held; the others match the oracle
-    ref = pu.run_oracle_per_head(t, 3, 6, 1e-6, [{k: v[:H] for k, v in m.items()} for m in phi])
+    torch.cuda.synchronize()
+    feats = h.read_workspace(hla.binding.HLA_WS_FEATURES, 1 * H * N * 24).reshape(1, H, N, 24)
+    ref = pu.run_oracle_per_head(t, 3, 6, 1e-6, [{k: v[:H] for k, v in m.items()} for m in phi],
+                                 relu_open=feats > 0)
     for m in range(4):
         for k in pu.WG_KEYS:
             assert bool((wg[m][k][H:] == 7.0).all()), (m, k)

@@ -188,3 +188,29 @@ def test_weight_grads_need_feature_maps():
     V = rng.standard_normal((1, 1, 3, 2))
     with pytest.raises(ValueError):
         orc.hla_operator_backward(Q, K, V, V, 2, 2, 1e-6, weight_grads=True)
+
+
+def test_relu_decisions_handed_in():
+    # With decisions handed in, the feature map is differentiated as mask * u(x): the gradients
+    # must equal the finite differences of exactly that (smooth) function, and with the oracle's
+    # own decisions nothing changes.
+    rng = np.random.default_rng(57)
+    n, d, dp = 6, 5, 4
+    x = rng.standard_normal((n, d))
+    W1, b1 = rng.standard_normal((d, d)), rng.standard_normal(d)
+    W2, b2 = rng.standard_normal((d, dp)), rng.standard_normal(dp)
+    w = rng.standard_normal((n, dp))
+    own = orc.phi_forward(x, W1, b1, W2, b2)[2] > 0
+    assert own.any() and not own.all()
+    np.testing.assert_array_equal(orc.phi_backward(w, x, W1, b1, W2, b2, relu_open=own),
+                                  orc.phi_backward(w, x, W1, b1, W2, b2))
+    mask = rng.random((n, dp)) < 0.5  # decisions that differ from the oracle's own
+    assert (mask != own).any()
+    f = lambda: float((orc.phi_forward(x, W1, b1, W2, b2)[2] * mask * w).sum())
+    np.testing.assert_allclose(orc.phi_backward(w, x, W1, b1, W2, b2, relu_open=mask), _fd(f, x),
+                               rtol=1e-6, atol=1e-8)
+    dW1, db1, dW2, db2 = orc.phi_weight_grads(w, x, W1, b1, W2, b2, relu_open=mask)
+    np.testing.assert_allclose(dW1, _fd(f, W1), rtol=1e-6, atol=1e-8)
+    np.testing.assert_allclose(db1, _fd(f, b1), rtol=1e-6, atol=1e-8)
+    np.testing.assert_allclose(dW2, _fd(f, W2), rtol=1e-6, atol=1e-8)
+    np.testing.assert_allclose(db2, _fd(f, b2), rtol=1e-6, atol=1e-8)
