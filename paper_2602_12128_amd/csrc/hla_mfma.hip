@@ -366,18 +366,24 @@ __global__ __launch_bounds__(kThreads) void k_query(Geom g, const BlockEnt* __re
 #pragma unroll
   for (int s = 0; s < SP; ++s) z[s] = zslot[s];
 
+  // The features of the next tile are loaded while the current one is computed; the loads are
+  // unconditional (token clamped into the block) so that they stay in flight across the loop
+  // back-edge, and a lane past the block's end zeroes its copy instead.
+  float qn[DP];
+  auto fetch = [&](int n0) {
+    const int n = n0 + r < e.t1 ? n0 + r : e.t1 - 1;
+    const float* f = feat + g.fidx(g.th(e.b, h, n), 0);
+#pragma unroll
+    for (int c = 0; c < DP; ++c) qn[c] = f[32 * (gl ? DP - 1 - c : c)];
+  };
+  if (e.t0 + wave * 32 < e.t1) fetch(e.t0 + wave * 32);
   for (int n0 = e.t0 + wave * 32; n0 < e.t1; n0 += kWaves * 32) {
     const int n = n0 + r;
     const bool live = n < e.t1;
     float qf[DP];
-    if (live) {
-      const float* f = feat + g.fidx(g.th(e.b, h, n), 0);
 #pragma unroll
-      for (int c = 0; c < DP; ++c) qf[c] = f[32 * (gl ? DP - 1 - c : c)];
-    } else {
-#pragma unroll
-      for (int c = 0; c < DP; ++c) qf[c] = 0.0f;
-    }
+    for (int c = 0; c < DP; ++c) qf[c] = live ? qn[c] : 0.0f;
+    fetch(n0 + kWaves * 32);
     float qm[SP];
     query_monomials<DP>(qf, qm);
     u32x4 b[NKS];
