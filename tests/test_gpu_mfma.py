@@ -91,3 +91,43 @@ def test_unsupported_shapes_fall_back_or_report():
                 phi_mode=hla.HLA_PHI_NONE, kernel_path=hla.HLA_PATH_MFMA, max_heads=1,
                 max_tokens=8, max_seqs=1)
     assert e.value.code == 2
+
+
+def test_forward_backward_can_be_captured_in_a_graph():
+    # After a first eager step (tables uploaded, kernel attributes set) the two calls allocate
+    # nothing, copy nothing and never synchronise, so a stream capture of them replays to the
+    # eager result; replays are interleaved with eager steps and checked every time.
+    dev = torch.device("cuda:0")
+    t, phi = wl.make_raw_inputs(900, 1, 2, 777, 128, 3, 6, torch.bfloat16)
+    td = {k: v.to(dev) for k, v in t.items()}
+    h = pu.make_handle(t, 3, 6, 1e-6, phi, None, path=hla.HLA_PATH_MFMA)
+    h.set_phi_weights([{k: v.to(dev) for k, v in m.items()} for m in phi])
+    outs = [torch.empty_like(td[k]) for k in ("V", "Q", "K", "V")]
+
+    def step():
+        h.forward(td["Q"], td["K"], td["V"], outs[0])
+        h.backward(td["Q"], td["K"], td["V"], outs[0], td["dO"], outs[1], outs[2], outs[3])
+
+    step()
+    torch.cuda.synchronize()
+    ref = [x.clone() for x in outs]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(3):
+        for x in outs:
+            x.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(ref, outs):
+            assert torch.equal(a, b), f"replay {rep}"
+        step()  # eager work between the replays
+        torch.cuda.synchronize()
+        for a, b in zip(ref, outs):
+            assert torch.equal(a, b), f"eager after replay {rep}"
+    h.destroy()
