@@ -9,8 +9,8 @@
 //   u^T[d_phi x 32]  = W2^T g^T      B = GELU(hidden) packed straight from the accumulators
 // and backward   dg^T = W2 du^T,  dh = dg * GELU'(hidden),  dx^T = W1 dh^T  (A = the same LDS copy
 // of W1^T, transpose reads).  The weights of a head stay resident in LDS for the workgroup's
-// lifetime; each wave streams its own 32-token tiles, and two waves share a SIMD so that one
-// wave's GELU arithmetic overlaps the other's matrix and LDS work.
+// lifetime; each wave streams its own 32-token tiles, and two (backward) or three (forward) waves
+// share a SIMD so that one wave's GELU arithmetic overlaps the others' matrix and LDS work.
 #include "hla_handle.h"
 #include "hla_mfma_common.h"
 
@@ -28,7 +28,7 @@ struct FalseTag {
 };
 // waves per workgroup of the forward and backward kernels
 #ifndef HLA_PHI_WAVES_F
-#define HLA_PHI_WAVES_F 8
+#define HLA_PHI_WAVES_F 12  // three per SIMD: the forward kernel stays within 168 registers
 #endif
 #ifndef HLA_PHI_WAVES_B
 #define HLA_PHI_WAVES_B 8
@@ -272,29 +272,6 @@ __device__ __forceinline__ void first_layer_offsets(int lane, int (&a_off)[D / 1
   for (int ks = 0; ks < D / 16; ++ks) a_off[ks] = SM::off(r, 2 * ks + gl);
 }
 
-// One 32-row block of hidden^T = b1 + W1^T X^T: acc[i] is hidden unit 32rb + d_row(i, gl) of
-// token r.  The eight MFMAs only queue on the matrix pipe; vector-ALU work that follows in program
-// order and does not read `acc` runs in their shadow.
-template <int D, bool BACKWARD>
-__device__ __forceinline__ void first_layer_block(const unsigned char* wm, const int (&a_off)[D / 16],
-                                                  const u32x4 (&xb)[D / 16], int gl, int rb,
-                                                  f32x16& acc) {
-  using SM = PhiSmem<D, BACKWARD>;
-  const float* b1 = reinterpret_cast<const float*>(wm + SM::kW1 + SM::kW2);
-#pragma unroll
-  for (int q4 = 0; q4 < 4; ++q4) {
-    const f32x4 bv = *reinterpret_cast<const f32x4*>(b1 + 32 * rb + 8 * q4 + 4 * gl);
-#pragma unroll
-    for (int e = 0; e < 4; ++e) acc[4 * q4 + e] = bv[e];
-  }
-#pragma unroll
-  for (int ks = 0; ks < D / 16; ++ks) {
-    // swz(32 rb + r) == swz(r): the row block only adds a constant to the address
-    const u32x4 a = *reinterpret_cast<const u32x4*>(wm + a_off[ks] + rb * 32 * SM::kRow);
-    acc = mfma32(a, xb[ks], acc);
-  }
-}
-
 // Which (batch row, head, first token) a 32-token tile index stands for.  With weights shared by
 // all heads the tiles of every (batch row, head) form one flat list that is dealt out evenly to
 // all waves of the grid; with per-head weights a workgroup stays on the head of blockIdx.y/z.
@@ -350,12 +327,13 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_fwd(Geom g, View X,
   const int stride = gridDim.x * WAVES;
   int tile = blockIdx.x * WAVES + wave;
   int b = 0, h = 0, n0 = 0;
-  // xn always holds the loads in flight for the coming tile; it is copied to xb at the top of the
-  // loop and refilled at once for the tile after (the last tile is simply fetched again).
-  u32x4 xb[NKS], xn[NKS];
+  // The tile's inputs live in xb only: the next tile's loads are issued into xb as soon as the
+  // last first-layer MFMA of the current tile has read it (one and a half stages before the end).
+  // The kernel is kept lean in registers (168) so that three waves share a SIMD.
+  u32x4 xb[NKS];
   if (tile < tm.total) {
     tm.decode(tile, b, h, n0);
-    load_x<D>(X, b, h, n0 + r, g.N, gl, xn);
+    load_x<D>(X, b, h, n0 + r, g.N, gl, xb);
   }
   float pend[4] = {0.0f, 0.0f, 0.0f, 0.0f};  // features of the last finished map, not yet stored
   float* pend_ptr = nullptr;
@@ -370,79 +348,82 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_fwd(Geom g, View X,
     }
     pend_ptr = nullptr;
   };
+  // the first layer accumulates on top of its bias: the lane's 16 entries of a 32-row block
+  auto bias_acc = [&](const unsigned char* wmap, int rb) {
+    f32x16 z;
+    const float* b1 = reinterpret_cast<const float*>(wmap + SM::kW1 + SM::kW2) + 32 * rb + 4 * gl;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {  // registers 4i..4i+3 are hidden units 32 rb + 8 i + 4 gl + 0..3
+      const f32x4 v = *reinterpret_cast<const f32x4*>(b1 + 8 * i);
+      z[4 * i] = v[0];
+      z[4 * i + 1] = v[1];
+      z[4 * i + 2] = v[2];
+      z[4 * i + 3] = v[3];
+    }
+    return z;
+  };
   for (; tile < tm.total; tile += stride) {
     const int n = n0 + r;
     const bool live = n < g.N;
-    const int64_t th = g.th(b, h, n);
-#pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) xb[ks] = xn[ks];
+    const int64_t th = g.th(b, h, live ? n : 0);
+    const bool more_tiles = tile + stride < tm.total;
+    if (more_tiles) tm.decode(tile + stride, b, h, n0);  // b, h, n0 now name the next tile
+    // Software pipeline over 32-row blocks of the hidden layer (block t = m * NRB + rb): while the
+    // vector ALU evaluates GELU on block t, the matrix pipe works on block t + 1, two MFMAs
+    // between quarters of the vector work, their LDS operands read one quarter ahead.  Blocks
+    // past the last map alias the last map's LDS: their results are never used.
+    f32x16 cur, nxt;
+    constexpr int kPer = NKS / 4;  // first-layer MFMAs per slice
+    u32x4 an[kPer];                // their A operands, read one slice ahead
     {
-      const int nt = tile + stride < tm.total ? tile + stride : tile;
-      tm.decode(nt, b, h, n0);
-      load_x<D>(X, b, h, n0 + r, g.N, gl, xn);
+      u32x4 a0[NKS];
+#pragma unroll
+      for (int ks = 0; ks < NKS; ++ks) a0[ks] = *reinterpret_cast<const u32x4*>(smem + a_off[ks]);
+      cur = bias_acc(smem, 0);
+#pragma unroll
+      for (int ks = 0; ks < NKS; ++ks) cur = mfma32(a0[ks], xb[ks], cur);
+#pragma unroll
+      for (int t = 0; t < kPer; ++t)
+        an[t] = *reinterpret_cast<const u32x4*>(smem + (1 % NRB) * 32 * SM::kRow + a_off[t]);
     }
     flush();
-    // Software pipeline over 32-row blocks of the hidden layer (block t = m * NRB + rb): while the
-    // vector ALU evaluates GELU on block t, the matrix pipe works on block t + 1, and the LDS reads
-    // of block t + 2 (A operands, bias) are already in flight, a whole stage ahead of their use.
-    // Blocks past the last map alias the last map's LDS: their results are never used.
-    auto block_base = [&](int m, int rbx) -> const unsigned char* {
-      const int mm = m + rbx / NRB;
-      return smem + (mm < nmaps ? mm : nmaps - 1) * SM::kMap;
-    };
-    auto load_bias = [&](const unsigned char* wmx, int rbx, f32x16& acc) {
-      const float* b1 = reinterpret_cast<const float*>(wmx + SM::kW1 + SM::kW2);
-#pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        const f32x4 bv = *reinterpret_cast<const f32x4*>(b1 + 32 * (rbx % NRB) + 8 * q4 + 4 * gl);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) acc[4 * q4 + e] = bv[e];
-      }
-    };
-    f32x16 cur, nxt;
-    u32x4 an[NKS];
-    first_layer_block<D, false>(smem, a_off, xb, gl, 0, cur);
-    {
-      const unsigned char* w1 = block_base(0, 1);
-      load_bias(w1, 1, nxt);
-#pragma unroll
-      for (int ks = 0; ks < NKS; ++ks)
-        an[ks] = *reinterpret_cast<const u32x4*>(w1 + (1 % NRB) * 32 * SM::kRow + a_off[ks]);
-    }
 #pragma unroll 1
     for (int m = 0; m < nmaps; ++m) {  // nmaps == NMAPS, passed at run time so this stays a loop
       const unsigned char* wm = smem + m * SM::kMap;
+      const bool last_map = m + 1 == nmaps;
       f32x16 u;
 #pragma unroll
       for (int i = 0; i < 16; ++i) u[i] = 0.0f;
 #pragma unroll
       for (int rb = 0; rb < NRB; ++rb) {
-        // Stage t: one MFMA of block t + 1 per eighth of block t's GELU arithmetic (an MFMA holds
-        // the wave's issue while the matrix pipe is busy, so they are spread through the
-        // vector-ALU stream); each consumed operand register is refilled for block t + 2.
-        const unsigned char* w2 = block_base(m, rb + 2);
+        // block t+1 (first layer, this stage) and block t+2 (whose first operands the last slice reads)
+        const unsigned char* w1 = rb + 1 < NRB ? wm : (last_map ? wm : wm + SM::kMap);
+        const unsigned char* w2 = rb + 2 < NRB ? wm : (last_map ? wm : wm + SM::kMap);
+        const unsigned char* a1_base = w1 + ((rb + 1) % NRB) * 32 * SM::kRow;
         const unsigned char* a2_base = w2 + ((rb + 2) % NRB) * 32 * SM::kRow;
-        f32x16 bn;
-        load_bias(w2, rb + 2, bn);
+        nxt = bias_acc(w1, (rb + 1) % NRB);
         const u32x4 a20 = *reinterpret_cast<const u32x4*>(wm + SM::kW1 + ((2 * rb) * 64 + lane) * 16);
         const u32x4 a21 = *reinterpret_cast<const u32x4*>(wm + SM::kW1 + ((2 * rb + 1) * 64 + lane) * 16);
         u32x4 gb[2];
-        // four slices per stage: two independent GELU chains per slice hide the issue gap between
-        // dependent packed-fp16 instructions
-        constexpr int kPer = NKS / 4;  // MFMAs of the next block per slice
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           // the empty asm statements pin the order MFMAs -> GELU slice -> next MFMAs: they are
           // volatile (kept in program order) and the values flow through them
           asm volatile("" : "+v"(nxt));
+          // first layer of block t+1 (there is none after the last block, and xb already belongs
+          // to the next tile's loads by then)
+          if (rb + 1 < NRB || !last_map) {
 #pragma unroll
-          for (int t = 0; t < kPer; ++t) {
-            const int ks = j * kPer + t;
-            nxt = mfma32(an[ks], xb[ks], nxt);
-            an[ks] = *reinterpret_cast<const u32x4*>(a2_base + a_off[ks]);
+            for (int t = 0; t < kPer; ++t) {
+              nxt = mfma32(an[t], xb[j * kPer + t], nxt);
+              an[t] = j < 3 ? *reinterpret_cast<const u32x4*>(a1_base + a_off[(j + 1) * kPer + t])
+                            : *reinterpret_cast<const u32x4*>(a2_base + a_off[t]);
+            }
           }
           if (j == 3) u = mfma32_f16(a20, gb[0], u);
+          // the next tile's inputs: xb is free once the last first-layer MFMA has been issued
+          if (last_map && rb == NRB - 2 && j == 3 && more_tiles) load_x<D>(X, b, h, n0 + r, g.N, gl, xb);
           float in[4] = {cur[4 * j], cur[4 * j + 1], cur[4 * j + 2], cur[4 * j + 3]};
           asm volatile("" : "+v"(in[0]), "+v"(in[1]), "+v"(in[2]), "+v"(in[3]));  // not nxt: that would wait for the MFMAs
           __builtin_amdgcn_sched_barrier(0);
@@ -455,7 +436,6 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_fwd(Geom g, View X,
         }
         u = mfma32_f16(a21, gb[1], u);
         cur = nxt;
-        nxt = bn;
       }
       // rows d_row(i, gl) < d_phi: lane gl=0 holds features 0..3, lane gl=1 features 4, 5.  The
       // store is held back until the next map (or the next tile's input wait) has been passed:
