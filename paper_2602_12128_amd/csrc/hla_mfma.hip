@@ -265,7 +265,7 @@ __global__ __launch_bounds__(kThreads) void k_state(Geom g, const BlockEnt* __re
 // where state row rho = 32rb + r belongs to (g, s) with rho%32 = 8*(i/4) + 4g + i%4, s = 16rb + i.
 // SLOT_ROWS = false: partial rows are canonical monomials (k_state); true: partial row 32g + s is
 // slot (g, s) already (k_bwd_query).  A thread owns four consecutive channels of one row; the
-// loads of eight chunks are in flight together, the additions stay in chunk order.
+// loads of sixteen chunks are in flight together, the additions stay in chunk order.
 template <int DP, int D, bool SLOT_ROWS>
 __global__ __launch_bounds__(256) void k_reduce(Geom g, const int32_t* __restrict__ seq_chunk_off,
                                                 const float* __restrict__ partial,
@@ -283,16 +283,19 @@ __global__ __launch_bounds__(256) void k_reduce(Geom g, const int32_t* __restric
   float* zslot = reinterpret_cast<float*>(opB + SL::kOpElems);
   const float* base = partial + static_cast<int64_t>(h) * partial_stride;
   const int64_t cstride = static_cast<int64_t>(g.H) * partial_stride;
+  // sixteen chunk loads in flight at a time, the ragged last batch included (its surplus loads
+  // repeat the last chunk and are not added): a batch costs one memory round trip, a chunk
+  // loaded on its own would cost one each
   auto sum_chunks = [&](const float* p0, auto& acc, auto load) {
-    int ch = c0;
-    for (; ch + 8 <= c1; ch += 8) {
-      decltype(load(p0)) v[8];
+    constexpr int NB = 16;
+    for (int ch = c0; ch < c1; ch += NB) {
+      decltype(load(p0)) v[NB];
 #pragma unroll
-      for (int k = 0; k < 8; ++k) v[k] = load(p0 + (ch + k) * cstride);
+      for (int k = 0; k < NB; ++k) v[k] = load(p0 + (ch + k < c1 ? ch + k : c1 - 1) * cstride);
 #pragma unroll
-      for (int k = 0; k < 8; ++k) acc += v[k];
+      for (int k = 0; k < NB; ++k)
+        if (ch + k < c1) acc += v[k];
     }
-    for (; ch < c1; ++ch) acc += load(p0 + ch * cstride);
   };
   for (int idx = threadIdx.x; idx < PER; idx += blockDim.x) {
     const int v = sl * PER + idx;
