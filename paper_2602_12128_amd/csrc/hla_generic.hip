@@ -144,7 +144,7 @@ __global__ void k_phi_forward(Geom g, PhiF32 w, View Q, View K, float* __restric
       const int t = idx / dphi, c = idx % dphi;
       float u = w.b2[mh * dphi + c];
       for (int jj = 0; jj < d; ++jj) u += gs[t * d + jj] * W2[jj * dphi + c];
-      feat[g.th(b, h, n0 + t) * g.nfeat + m * dphi + c] = fmaxf(u, 0.0f);
+      feat[g.fidx(g.th(b, h, n0 + t), m * dphi + c)] = fmaxf(u, 0.0f);
     }
     __syncthreads();
   }
@@ -179,7 +179,7 @@ __global__ void k_phi_backward(Geom g, PhiF32 w, View Q, View K, const float* __
       const int t = idx / dphi, c = idx % dphi;
       float du = 0.0f;
       if (t < nt) {
-        const int64_t o = g.th(b, h, n0 + t) * g.nfeat + m * dphi + c;
+        const int64_t o = g.fidx(g.th(b, h, n0 + t), m * dphi + c);
         du = feat[o] > 0.0f ? dfeat[o] : 0.0f;  // ReLU passes gradient only where it was open
       }
       dus[idx] = du;
@@ -816,7 +816,8 @@ hla_status weight_grads_reduce(hla_handle* hd, int nparts, int heads, float sW1,
 }
 
 hla_status phi_weight_grads(hla_handle* hd, const hla_call_args& a) {
-  if (hd->path == HLA_PATH_MFMA && hd->cfg.io_dtype == HLA_BF16) return mfma_phi_weight_grads(hd, a);
+  if (hd->path == HLA_PATH_MFMA && hd->cfg.io_dtype == HLA_BF16 && hd->g.dphi == 6 && hd->g.F == 3)
+    return mfma_phi_weight_grads(hd, a);
   return hd->cfg.io_dtype == HLA_F32 ? weight_grads_t<float>(hd, a) : weight_grads_t<bf16_t>(hd, a);
 }
 

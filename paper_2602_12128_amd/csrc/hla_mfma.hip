@@ -1,5 +1,6 @@
 // MFMA path: bf16 matrix-core kernels for gfx950 over the symmetric (monomial) form of the
-// degree-3 feature tensor (see hla_mfma_common.h).  Forward core:
+// degree-3 (d_phi = 6) or degree-2 (d_phi = 12) feature tensor (see hla_mfma_common.h; SY below is
+// the Sym<F, d_phi> that describes it, MP = SY::MP its padded row count: 64 or 96).  Forward core:
 //   k_state   : per chunk of tokens,  Csym += S^T V,  zsym += S^T 1     (contraction over tokens)
 //   k_reduce  : sums the chunk partials in fixed order and emits the state as MFMA operands
 //   k_query   : O^T = Csym^T Qm^T, eta = Qm . zsym, O = num / (eta + eps)
@@ -31,17 +32,18 @@ constexpr int kReduceSlices = 8;   // slices of the state per (sequence, head) i
 
 // Where canonical monomial m sits among the (g, slot) pairs.
 struct SlotMap {
-  int8_t g[64];
-  int8_t s[64];
+  int8_t g[128];
+  int8_t s[128];
 };
 
-template <int DP>
+template <class SY>
 SlotMap make_slot_map() {
   SlotMap sm{};
-  for (int m = 0; m < 64; ++m) sm.g[m] = sm.s[m] = -1;
+  for (int m = 0; m < 128; ++m) sm.g[m] = sm.s[m] = -1;
   for (int g = 0; g < 2; ++g)
-    for (int s = 0; s < Sym3<DP>::NS; ++s) {
-      const int m = sym3_slot_canon(DP, g, s);
+    for (int s = 0; s < SY::NS; ++s) {
+      const int m = SY::slot_canon(g, s);
+      if (m < 0) continue;  // padding (the second copy of a self-mirrored monomial)
       sm.g[m] = static_cast<int8_t>(g);
       sm.s[m] = static_cast<int8_t>(s);
     }
@@ -49,10 +51,10 @@ SlotMap make_slot_map() {
 }
 
 // Per-unit device state of the MFMA path (all inside hd->path_ws).
-template <int DP, int D>
+template <class SY, int D>
 struct StateLayout {
-  static constexpr int MP = Sym3<DP>::MP;
-  static constexpr int SP = Sym3<DP>::SP;
+  static constexpr int MP = SY::MP;
+  static constexpr int SP = SY::SP;
   static constexpr int64_t kF32 = static_cast<int64_t>(MP) * D + MP;  // canonical C rows, then z
   static constexpr int64_t kOpElems = static_cast<int64_t>(MP) * D;   // bf16 elements per operand array
   // bytes per unit: opA, opB (bf16), zslot (fp32 [2][SP])
@@ -60,43 +62,44 @@ struct StateLayout {
 };
 
 // ---- sum of per-wave accumulator tiles over the four waves of a workgroup ------------------------
-// Every wave holds a [64 rows x D] fp32 tile in MFMA accumulator layout (acc[rb][cb][i]: row
-// 32rb + d_row(i, gl), column 32cb + r) and a 64-vector zl (element 32 gl + k, replicated over r).
-// Fixed order (w0 + w1) + (w2 + w3), two LDS regions of (64 D + 64) floats, four barriers; the sum
-// ends in region 0 with tile row `row` at floats [row * D, row * D + D) and the vector at 64 D.
-template <int D>
+// Every wave holds a [MP rows x D] fp32 tile in MFMA accumulator layout (acc[rb][cb][i]: row
+// 32rb + d_row(i, gl), column 32cb + r) and an MP-vector zl (element (MP/2) gl + k, replicated
+// over r).  Fixed order (w0 + w1) + (w2 + w3), two LDS regions of (MP D + MP) floats, four barriers;
+// the sum ends in region 0 with tile row `row` at floats [row * D, row * D + D) and the vector at
+// MP D.
+template <int D, int MP>
 struct WaveSum {
-  static constexpr int kRegion = 64 * D + 64;          // floats
+  static constexpr int kRegion = MP * D + MP;          // floats
   static constexpr int kBytes = 2 * kRegion * 4;
 };
-template <int D>
-__device__ __forceinline__ void sum_over_waves(f32x16 (&acc)[2][D / 32], float (&zl)[32], float* lds,
-                                               int wave, int lane) {
-  constexpr int NCB = D / 32;
+template <int D, int MP>
+__device__ __forceinline__ void sum_over_waves(f32x16 (&acc)[MP / 32][D / 32], float (&zl)[MP / 2],
+                                               float* lds, int wave, int lane) {
+  constexpr int NCB = D / 32, NRM = MP / 32, HALF = MP / 2;
   const int r = lane % 32, gl = lane / 32;
   auto put = [&](float* reg) {
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
+    for (int rb = 0; rb < NRM; ++rb)
 #pragma unroll
       for (int i = 0; i < 16; ++i)
 #pragma unroll
         for (int cb = 0; cb < NCB; ++cb) reg[(32 * rb + d_row(i, gl)) * D + 32 * cb + r] = acc[rb][cb][i];
     if (r == 0) {
 #pragma unroll
-      for (int k = 0; k < 32; ++k) reg[64 * D + 32 * gl + k] = zl[k];
+      for (int k = 0; k < HALF; ++k) reg[MP * D + HALF * gl + k] = zl[k];
     }
   };
   auto add = [&](const float* reg) {
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
+    for (int rb = 0; rb < NRM; ++rb)
 #pragma unroll
       for (int i = 0; i < 16; ++i)
 #pragma unroll
         for (int cb = 0; cb < NCB; ++cb) acc[rb][cb][i] += reg[(32 * rb + d_row(i, gl)) * D + 32 * cb + r];
 #pragma unroll
-    for (int k = 0; k < 32; ++k) zl[k] += reg[64 * D + 32 * gl + k];
+    for (int k = 0; k < HALF; ++k) zl[k] += reg[MP * D + HALF * gl + k];
   };
-  float* reg = lds + (wave / 2) * WaveSum<D>::kRegion;
+  float* reg = lds + (wave / 2) * WaveSum<D, MP>::kRegion;
   __syncthreads();
   if (wave % 2 == 1) put(reg);
   __syncthreads();
@@ -112,29 +115,29 @@ __device__ __forceinline__ void sum_over_waves(f32x16 (&acc)[2][D / 32], float (
 }
 
 // ---- k_state ----------------------------------------------------------------------------------
-template <int D>
+template <int D, int MP>
 struct StateSmem {
   static constexpr int kVStride = D * 2 + 32;   // bytes per token row of the V tile
-  static constexpr int kSStride = 64 * 2 + 32;  // bytes per token row of the S tile (64 monomial cols)
+  static constexpr int kSStride = MP * 2 + 32;  // bytes per token row of the S tile (MP monomial cols)
   static constexpr int kVBytes = 64 * kVStride;
   static constexpr int kSBytes = 64 * kSStride;
   static constexpr int kWaveBytes = kVBytes + kSBytes;
-  static constexpr int kRedBytes = 2 * (64 * D + 64) * 4;
+  static constexpr int kRedBytes = WaveSum<D, MP>::kBytes;
   static constexpr int kTotal = kWaves * kWaveBytes > kRedBytes ? kWaves * kWaveBytes : kRedBytes;
 };
 
 // grid (chunks, H), block 256.  Each wave streams 64-token sub-tiles w, w+4, .. of the chunk
 // through its private LDS region; the four waves' accumulators are summed in wave order at the
 // end and written as one partial state.
-template <int DP, int D>
+template <class SY, int D>
 __global__ __launch_bounds__(kThreads) void k_state(Geom g, const BlockEnt* __restrict__ chunks,
                                                     const float* __restrict__ feat, View V,
                                                     float* __restrict__ partial,
                                                     int64_t partial_stride) {
-  using SY = Sym3<DP>;
-  using SM = StateSmem<D>;
-  static_assert(SY::MP == 64, "state kernel is laid out for a 64-row padded state");
+  constexpr int DP = SY::DPHI, F = SY::F, MP = SY::MP;
+  using SM = StateSmem<D, MP>;
   constexpr int NCB = D / 32;      // column blocks of the state
+  constexpr int NRM = MP / 32;     // row blocks of the state
   extern __shared__ __align__(16) unsigned char smem[];
   const int lane = threadIdx.x % kWave, wave = wave_index();
   unsigned char* vs = smem + wave * SM::kWaveBytes;
@@ -144,10 +147,10 @@ __global__ __launch_bounds__(kThreads) void k_state(Geom g, const BlockEnt* __re
   const int gq = lane / 32;                   // MFMA operand coordinates
   const int L = lane % 16, q = lane / 16;
 
-  f32x16 acc[2][NCB];
-  f32x16 zacc[2];
+  f32x16 acc[NRM][NCB];
+  f32x16 zacc[NRM];
 #pragma unroll
-  for (int rb = 0; rb < 2; ++rb) {
+  for (int rb = 0; rb < NRM; ++rb) {
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb)
 #pragma unroll
@@ -160,17 +163,17 @@ __global__ __launch_bounds__(kThreads) void k_state(Geom g, const BlockEnt* __re
 
   // the next sub-tile's V rows and key features are fetched while the current one is consumed
   TileRegs<D, 64> vt;
-  float kf[3 * DP];
+  float kf[F * DP];
   auto fetch = [&](int n0) {
     fetch_tile<D, 64>(V, e.b, h, n0, e.t1, lane, vt);
     const int n = n0 + lane;
     if (n < e.t1) {
       const float* f = feat + g.fidx(g.th(e.b, h, n), DP);
 #pragma unroll
-      for (int a = 0; a < 3 * DP; ++a) kf[a] = f[32 * a];
+      for (int a = 0; a < F * DP; ++a) kf[a] = f[32 * a];
     } else {
 #pragma unroll
-      for (int a = 0; a < 3 * DP; ++a) kf[a] = 0.0f;
+      for (int a = 0; a < F * DP; ++a) kf[a] = 0.0f;
     }
   };
   if (e.t0 + wave * 64 < e.t1) fetch(e.t0 + wave * 64);
@@ -178,25 +181,23 @@ __global__ __launch_bounds__(kThreads) void k_state(Geom g, const BlockEnt* __re
     put_tile<D, 64>(vt, lane, vs, SM::kVStride);
     // ---- key monomials of token n0 + lane (all NM, canonical order), as bf16 row of the S tile
     {
-      float k1[DP], k2[DP], k3[DP];
+      float kk[F][DP];
 #pragma unroll
-      for (int a = 0; a < DP; ++a) {
-        k1[a] = kf[a];
-        k2[a] = kf[DP + a];
-        k3[a] = kf[2 * DP + a];
-      }
+      for (int f = 0; f < F; ++f)
+#pragma unroll
+        for (int a = 0; a < DP; ++a) kk[f][a] = kf[f * DP + a];
       if (n0 + kWaves * 64 < e.t1) fetch(n0 + kWaves * 64);
       float sm[SY::NM];
-      key_monomials_all<DP>(k1, k2, k3, sm);
-      uint32_t packed[32];
+      sym_key_monomials_all<SY>(kk, sm);
+      uint32_t packed[MP / 2];
 #pragma unroll
-      for (int p = 0; p < 32; ++p) {
+      for (int p = 0; p < MP / 2; ++p) {
         const float lo = 2 * p < SY::NM ? sm[2 * p < SY::NM ? 2 * p : 0] : 0.0f;
         const float hi = 2 * p + 1 < SY::NM ? sm[2 * p + 1 < SY::NM ? 2 * p + 1 : 0] : 0.0f;
         packed[p] = pack_bf16(lo, hi);
       }
 #pragma unroll
-      for (int p = 0; p < 8; ++p) {
+      for (int p = 0; p < MP / 8; ++p) {
         u32x4 w;
         w[0] = packed[4 * p];
         w[1] = packed[4 * p + 1];
@@ -206,13 +207,13 @@ __global__ __launch_bounds__(kThreads) void k_state(Geom g, const BlockEnt* __re
       }
     }
     wave_lds_sync();
-    // ---- Csym[64 x D] += S^T[64 x 64 tokens] V[64 tokens x D]; zsym += S^T 1
+    // ---- Csym[MP x D] += S^T[MP x 64 tokens] V[64 tokens x D]; zsym += S^T 1
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
       const int krow = 16 * ks + 8 * gq + L / 4;  // token row this lane addresses for the transpose read
-      u32x4 a[2];
+      u32x4 a[NRM];
 #pragma unroll
-      for (int rb = 0; rb < 2; ++rb) {
+      for (int rb = 0; rb < NRM; ++rb) {
         const unsigned char* p = ss + krow * SM::kSStride + (32 * rb + 16 * (q % 2) + 4 * (L % 4)) * 2;
         const u32x2 lo = lds_read_tr16(p);
         const u32x2 hi = lds_read_tr16(p + 4 * SM::kSStride);
@@ -232,28 +233,28 @@ __global__ __launch_bounds__(kThreads) void k_state(Geom g, const BlockEnt* __re
         b[2] = hi[0];
         b[3] = hi[1];
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb) acc[rb][cb] = mfma32(a[rb], b, acc[rb][cb]);
+        for (int rb = 0; rb < NRM; ++rb) acc[rb][cb] = mfma32(a[rb], b, acc[rb][cb]);
       }
 #pragma unroll
-      for (int rb = 0; rb < 2; ++rb) zacc[rb] = mfma32(a[rb], ones, zacc[rb]);
+      for (int rb = 0; rb < NRM; ++rb) zacc[rb] = mfma32(a[rb], ones, zacc[rb]);
     }
     wave_lds_sync();
   }
   // ---- sum the four waves through LDS, then write the partial state (rows = canonical monomials)
-  float zl[32];
+  float zl[MP / 2];
 #pragma unroll
-  for (int rb = 0; rb < 2; ++rb)
+  for (int rb = 0; rb < NRM; ++rb)
 #pragma unroll
     for (int i = 0; i < 16; ++i) zl[16 * rb + i] = zacc[rb][i];
   float* red = reinterpret_cast<float*>(smem);
-  sum_over_waves<D>(acc, zl, red, wave, lane);
+  sum_over_waves<D, MP>(acc, zl, red, wave, lane);
   float* out = partial + (static_cast<int64_t>(blockIdx.x) * g.H + h) * partial_stride;
-  for (int i = threadIdx.x; i < 64 * D / 4; i += kThreads)
+  for (int i = threadIdx.x; i < MP * D / 4; i += kThreads)
     reinterpret_cast<f32x4*>(out)[i] = reinterpret_cast<const f32x4*>(red)[i];
-  // vector element 32 gl + 16 rb + i is state row 32 rb + d_row(i, gl)
-  if (threadIdx.x < 64) {
-    const int gg = threadIdx.x / 32, k = threadIdx.x % 32;
-    out[64 * D + 32 * (k / 16) + d_row(k % 16, gg)] = red[64 * D + threadIdx.x];
+  // vector element (MP/2) gl + 16 rb + i is state row 32 rb + d_row(i, gl)
+  if (threadIdx.x < MP) {
+    const int gg = threadIdx.x / (MP / 2), k = threadIdx.x % (MP / 2);
+    out[MP * D + 32 * (k / 16) + d_row(k % 16, gg)] = red[MP * D + threadIdx.x];
   }
 }
 
@@ -263,17 +264,18 @@ __global__ __launch_bounds__(kThreads) void k_state(Geom g, const BlockEnt* __re
 //   opA[rb][ks][lane=(r,gl)][j] = Csym[mono(gl, 8ks+j)][32rb + r]           (rows = channels)
 //   opB[rb][ks][lane=(r,gl)][j] = Csym[mono of row 32rb + r][16ks + 8gl + j]  (rows = monomials)
 // where state row rho = 32rb + r belongs to (g, s) with rho%32 = 8*(i/4) + 4g + i%4, s = 16rb + i.
-// SLOT_ROWS = false: partial rows are canonical monomials (k_state); true: partial row 32g + s is
+// SLOT_ROWS = false: partial rows are canonical monomials (k_state); true: partial row SP g + s is
 // slot (g, s) already (k_bwd_query).  A thread owns four consecutive channels of one row; the
 // loads of sixteen chunks are in flight together, the additions stay in chunk order.
-template <int DP, int D, bool SLOT_ROWS>
+template <class SY, int D, bool SLOT_ROWS>
 __global__ __launch_bounds__(256) void k_reduce(Geom g, const int32_t* __restrict__ seq_chunk_off,
                                                 const float* __restrict__ partial,
                                                 int64_t partial_stride,
                                                 unsigned char* __restrict__ ops, SlotMap sm) {
-  using SL = StateLayout<DP, D>;
+  using SL = StateLayout<SY, D>;
   constexpr int MP = SL::MP, SP = SL::SP;
   constexpr int VPR = D / 4;                         // float4 per state row
+  static_assert(MP * VPR % kReduceSlices == 0, "slices cover the state evenly");
   constexpr int PER = MP * VPR / kReduceSlices;      // float4 per slice
   const int s = blockIdx.x, h = blockIdx.y, sl = blockIdx.z;
   const int c0 = seq_chunk_off[s], c1 = seq_chunk_off[s + 1];
@@ -303,8 +305,8 @@ __global__ __launch_bounds__(256) void k_reduce(Geom g, const int32_t* __restric
     f32x4 a;
     a[0] = a[1] = a[2] = a[3] = 0.0f;
     sum_chunks(base + m * D + c, a, [](const float* p) { return *reinterpret_cast<const f32x4*>(p); });
-    const int mg = SLOT_ROWS ? m / 32 : sm.g[m];
-    const int ms = SLOT_ROWS ? m % 32 : sm.s[m];
+    const int mg = SLOT_ROWS ? m / SP : sm.g[m];
+    const int ms = SLOT_ROWS ? m % SP : sm.s[m];
     if (mg >= 0) {
       uint16_t bits[4];
 #pragma unroll
@@ -332,8 +334,8 @@ __global__ __launch_bounds__(256) void k_reduce(Geom g, const int32_t* __restric
     for (int m = threadIdx.x; m < MP; m += blockDim.x) {
       float a = 0.0f;
       sum_chunks(base + MP * D + m, a, [](const float* p) { return *p; });
-      const int mg = SLOT_ROWS ? m / 32 : sm.g[m];
-      const int ms = SLOT_ROWS ? m % 32 : sm.s[m];
+      const int mg = SLOT_ROWS ? m / SP : sm.g[m];
+      const int ms = SLOT_ROWS ? m % SP : sm.s[m];
       if (mg >= 0) zslot[mg * SP + ms] = a;
     }
   }
@@ -342,14 +344,13 @@ __global__ __launch_bounds__(256) void k_reduce(Geom g, const int32_t* __restric
 // ---- k_query ----------------------------------------------------------------------------------
 // grid (blocks of pick_query_block tokens, H), block 256.  Wave w serves 32-token tiles w, w+4, ..;
 // lane (r, gl): token r of the tile, slot half gl (gl = 1 works on the reversed feature vector).
-template <int DP, int D>
+template <class SY, int D>
 __global__ __launch_bounds__(kThreads) void k_query(Geom g, const BlockEnt* __restrict__ blocks,
                                                     const float* __restrict__ feat,
                                                     const unsigned char* __restrict__ ops, View O,
                                                     float* __restrict__ den) {
-  using SY = Sym3<DP>;
-  using SL = StateLayout<DP, D>;
-  constexpr int SP = SY::SP, MP = SY::MP;
+  using SL = StateLayout<SY, D>;
+  constexpr int SP = SY::SP, MP = SY::MP, DP = SY::DPHI;
   constexpr int NRB = D / 32, NKS = MP / 16;
   __shared__ __align__(16) unsigned char smem[kWaves * RowTile<D>::kBytes];
   const int lane = threadIdx.x % kWave, wave = wave_index();
@@ -388,7 +389,7 @@ __global__ __launch_bounds__(kThreads) void k_query(Geom g, const BlockEnt* __re
     for (int c = 0; c < DP; ++c) qf[c] = live ? qn[c] : 0.0f;
     fetch(n0 + kWaves * 32);
     float qm[SP];
-    query_monomials<DP>(qf, qm);
+    sym_query_monomials<SY>(qf, qm, gl);
     u32x4 b[NKS];
     float eta = 0.0f;
 #pragma unroll
@@ -419,13 +420,20 @@ __global__ __launch_bounds__(kThreads) void k_query(Geom g, const BlockEnt* __re
 }
 
 // ---- k_bwd_query ------------------------------------------------------------------------------
-template <int D>
+template <int D, int MP>
 struct BwdQSmem {
   static constexpr int kDoBytes = 32 * D * 2;   // dO tile [32 tokens][D] bf16, swizzled, unpadded
-  static constexpr int kQBytes = 32 * 128;      // scaled-monomial tile [32 tokens][64 slot columns] bf16
+  // scaled-monomial tile [32 tokens][MP slot columns] bf16, swizzled; rows of 128 or 256 bytes
+  static constexpr int kQRow = MP <= 64 ? 128 : 256;
+  static constexpr int kQBytes = 32 * kQRow;
   static constexpr int kWaveBytes = kDoBytes + kQBytes;
-  static constexpr int kRedBytes = 2 * (64 * D + 64) * 4;
-  static constexpr int kTotal = kWaves * kWaveBytes > kRedBytes ? kWaves * kWaveBytes : kRedBytes;
+  // With more than 64 state rows the monomial-row operand image of the state does not fit the
+  // register file next to the accumulators: the workgroup keeps one copy in LDS instead.
+  static constexpr bool kOpsInLds = MP > 64;
+  static constexpr int kOpBytes = kOpsInLds ? MP * D * 2 : 0;
+  static constexpr int kStream = kOpBytes + kWaves * kWaveBytes;
+  static constexpr int kRedBytes = WaveSum<D, MP>::kBytes;
+  static constexpr int kTotal = kStream > kRedBytes ? kStream : kRedBytes;
 };
 
 // grid (chunks, H), block 256.  Per 32-token tile and lane (token r, slot half gl), with
@@ -437,21 +445,21 @@ struct BwdQSmem {
 //                                  with transpose reads),   dzsym += s Qm.
 // Taking s from the same X that feeds dM makes the component of dM along Qm cancel exactly, which
 // is where the query gradient loses its precision otherwise.  The chunk's dCsym/dzsym are summed
-// over the four waves in wave order and written as one partial whose row 32g + s is slot (g, s).
-template <int DP, int D>
+// over the four waves in wave order and written as one partial whose row SP g + s is slot (g, s).
+template <class SY, int D>
 __global__ __launch_bounds__(kThreads) void k_bwd_query(
     Geom g, const BlockEnt* __restrict__ chunks, const float* __restrict__ feat,
     const float* __restrict__ den, const unsigned char* __restrict__ ops, View dO,
     float* __restrict__ dfeat, float* __restrict__ partial, int64_t partial_stride) {
-  using SY = Sym3<DP>;
-  using SL = StateLayout<DP, D>;
-  using SM = BwdQSmem<D>;
-  constexpr int SP = SY::SP;
-  constexpr int NCB = D / 32, NKD = D / 16;
+  using SL = StateLayout<SY, D>;
+  using SM = BwdQSmem<D, SY::MP>;
+  constexpr int SP = SY::SP, MP = SY::MP, DP = SY::DPHI;
+  constexpr int NCB = D / 32, NKD = D / 16, NRM = MP / 32;
   constexpr int DROW = D * 2;  // bytes per dO tile row
+  constexpr int QROW = SM::kQRow;
   extern __shared__ __align__(16) unsigned char smem[];
   const int lane = threadIdx.x % kWave, wave = wave_index();
-  unsigned char* ds = smem + wave * SM::kWaveBytes;
+  unsigned char* ds = smem + SM::kOpBytes + wave * SM::kWaveBytes;
   unsigned char* qs = ds + SM::kDoBytes;
   const BlockEnt e = chunks[blockIdx.x];
   const int h = blockIdx.y;
@@ -460,11 +468,26 @@ __global__ __launch_bounds__(kThreads) void k_bwd_query(
   const int64_t u = static_cast<int64_t>(e.seq) * g.H + h;
   const u32x4* opB = reinterpret_cast<const u32x4*>(ops + u * SL::kOpBytes + SL::kOpElems * 2);
   const float* zslot = reinterpret_cast<const float*>(ops + u * SL::kOpBytes + 2 * SL::kOpElems * 2) + gl * SP;
-  u32x4 a_mo[2][NKD];
+  u32x4 a_mo[SM::kOpsInLds ? 1 : NRM][SM::kOpsInLds ? 1 : NKD];
+  if constexpr (SM::kOpsInLds) {
+    constexpr int N16 = SM::kOpBytes / 16;
+    static_assert(N16 % kThreads == 0, "the operand image is copied in whole rounds");
 #pragma unroll
-  for (int rb = 0; rb < 2; ++rb)
+    for (int k = 0; k < N16 / kThreads; ++k)
+      reinterpret_cast<u32x4*>(smem)[threadIdx.x + k * kThreads] = opB[threadIdx.x + k * kThreads];
+    __syncthreads();
+  } else {
 #pragma unroll
-    for (int ks = 0; ks < NKD; ++ks) a_mo[rb][ks] = opB[(rb * NKD + ks) * 64 + lane];
+    for (int rb = 0; rb < NRM; ++rb)
+#pragma unroll
+      for (int ks = 0; ks < NKD; ++ks) a_mo[rb][ks] = opB[(rb * NKD + ks) * 64 + lane];
+  }
+  auto state_op = [&](int rb, int ks) -> u32x4 {
+    if constexpr (SM::kOpsInLds)
+      return reinterpret_cast<const u32x4*>(smem)[(rb * NKD + ks) * 64 + lane];
+    else
+      return a_mo[rb][ks];
+  };
   float z[SP];
 #pragma unroll
   for (int s4 = 0; s4 < SP / 4; ++s4) {
@@ -479,22 +502,22 @@ __global__ __launch_bounds__(kThreads) void k_bwd_query(
   for (int ks = 0; ks < NKD; ++ks) dw_off[ks] = tile_off<DROW>(r, 2 * ks + gl);
   int qw_off[SP / 8];
 #pragma unroll
-  for (int p4 = 0; p4 < SP / 8; ++p4) qw_off[p4] = tile_off<128>(r, 4 * gl + p4);
-  int qa_off[2][2], db_off[2][NCB];
+  for (int p4 = 0; p4 < SP / 8; ++p4) qw_off[p4] = tile_off<QROW>(r, (SP / 8) * gl + p4);
+  int qa_off[2][NRM], db_off[2][NCB];
 #pragma unroll
   for (int hi = 0; hi < 2; ++hi) {
     const int row = 8 * gl + 4 * hi + L / 4;
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
-      qa_off[hi][rb] = tile_off<128>(row, 4 * rb + 2 * (q % 2) + (L % 4) / 2) + (L % 2) * 8;
+    for (int rb = 0; rb < NRM; ++rb)
+      qa_off[hi][rb] = tile_off<QROW>(row, 4 * rb + 2 * (q % 2) + (L % 4) / 2) + (L % 2) * 8;
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb)
       db_off[hi][cb] = tile_off<DROW>(row, 4 * cb + 2 * (q % 2) + (L % 4) / 2) + (L % 2) * 8;
   }
 
-  f32x16 dC[2][NCB];
+  f32x16 dC[NRM][NCB];
 #pragma unroll
-  for (int rb = 0; rb < 2; ++rb)
+  for (int rb = 0; rb < NRM; ++rb)
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb)
 #pragma unroll
@@ -538,22 +561,22 @@ __global__ __launch_bounds__(kThreads) void k_bwd_query(
     // dO tile for the token contraction, X^T = Csym dO^T on the matrix pipe
 #pragma unroll
     for (int ks = 0; ks < NKD; ++ks) *reinterpret_cast<u32x4*>(ds + dw_off[ks]) = xb[ks];
-    f32x16 X[2];
+    f32x16 X[NRM];
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
+    for (int rb = 0; rb < NRM; ++rb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) X[rb][i] = 0.0f;
 #pragma unroll
     for (int ks = 0; ks < NKD; ++ks)
 #pragma unroll
-      for (int rb = 0; rb < 2; ++rb) X[rb] = mfma32(a_mo[rb][ks], xb[ks], X[rb]);
+      for (int rb = 0; rb < NRM; ++rb) X[rb] = mfma32(state_op(rb, ks), xb[ks], X[rb]);
     // monomials of this lane's slots and their scaled bf16 copy (a row of the A^T tile)
     const float inv = live ? 1.0f / denb : 0.0f;
     float qf[DP];
 #pragma unroll
     for (int c = 0; c < DP; ++c) qf[c] = gl ? fb[DP - 1 - c] : fb[c];
     float qm[SP];
-    query_monomials<DP>(qf, qm);
+    sym_query_monomials<SY>(qf, qm, gl);
 #pragma unroll
     for (int p4 = 0; p4 < SP / 8; ++p4) {
       u32x4 w;
@@ -563,14 +586,14 @@ __global__ __launch_bounds__(kThreads) void k_bwd_query(
     }
     float dot = 0.0f;
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
+    for (int rb = 0; rb < NRM; ++rb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) dot += qm[16 * rb + i] * X[rb][i];
     dot += partner32(dot);
     const float si = -(inv * inv) * dot;
     float dm[SP];
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
+    for (int rb = 0; rb < NRM; ++rb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
         dm[16 * rb + i] = inv * X[rb][i] + si * z[16 * rb + i];
@@ -579,7 +602,7 @@ __global__ __launch_bounds__(kThreads) void k_bwd_query(
     float dq[DP];
 #pragma unroll
     for (int c = 0; c < DP; ++c) dq[c] = 0.0f;
-    query_monomials_grad<DP>(qf, dm, dq);
+    sym_query_monomials_grad<SY>(qf, dm, dq, gl);
     float other[DP];
 #pragma unroll
     for (int c = 0; c < DP; ++c) other[c] = partner32(dq[c]);
@@ -589,14 +612,14 @@ __global__ __launch_bounds__(kThreads) void k_bwd_query(
       for (int c = 0; c < DP; ++c) df[32 * c] = dq[c] + other[DP - 1 - c];
     }
     wave_lds_sync();
-    // dCsym[(g,s) rows x D] += (inv Qm)^T[64 x 32 tokens] dO[32 tokens x D]
+    // dCsym[(g,s) rows x D] += (inv Qm)^T[MP x 32 tokens] dO[32 tokens x D]
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) {
-      u32x4 a[2];
+      u32x4 a[NRM];
 #pragma unroll
-      for (int rb = 0; rb < 2; ++rb) {
-        const u32x2 lo = lds_read_tr16(qs + ks * 16 * 128 + qa_off[0][rb]);
-        const u32x2 hi = lds_read_tr16(qs + ks * 16 * 128 + qa_off[1][rb]);
+      for (int rb = 0; rb < NRM; ++rb) {
+        const u32x2 lo = lds_read_tr16(qs + ks * 16 * QROW + qa_off[0][rb]);
+        const u32x2 hi = lds_read_tr16(qs + ks * 16 * QROW + qa_off[1][rb]);
         a[rb][0] = lo[0];
         a[rb][1] = lo[1];
         a[rb][2] = hi[0];
@@ -612,7 +635,7 @@ __global__ __launch_bounds__(kThreads) void k_bwd_query(
         b[2] = hi[0];
         b[3] = hi[1];
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb) dC[rb][cb] = mfma32(a[rb], b, dC[rb][cb]);
+        for (int rb = 0; rb < NRM; ++rb) dC[rb][cb] = mfma32(a[rb], b, dC[rb][cb]);
       }
     }
     wave_lds_sync();
@@ -630,30 +653,30 @@ __global__ __launch_bounds__(kThreads) void k_bwd_query(
     for (int m = 1; m < 32; m <<= 1) v += __shfl_xor(v, m, 64);
     dzacc[s] = v;
   }
-  // sum the four waves: row 32rb + d_row(i, gl) of the accumulators is column 32g' + s' of the
-  // monomial tile, i.e. slot (g', s'); the vector element 32 gl + s is slot (gl, s) as well
+  // sum the four waves: row 32rb + d_row(i, gl) of the accumulators is column SP g' + s' of the
+  // monomial tile, i.e. slot (g', s'); the vector element SP gl + s is slot (gl, s) as well
   float* red = reinterpret_cast<float*>(smem);
-  sum_over_waves<D>(dC, dzacc, red, wave, lane);
+  sum_over_waves<D, MP>(dC, dzacc, red, wave, lane);
   f32x4* out = reinterpret_cast<f32x4*>(partial + (static_cast<int64_t>(blockIdx.x) * g.H + h) * partial_stride);
-  for (int i = threadIdx.x; i < (64 * D + 64) / 4; i += kThreads) out[i] = reinterpret_cast<const f32x4*>(red)[i];
+  for (int i = threadIdx.x; i < (MP * D + MP) / 4; i += kThreads) out[i] = reinterpret_cast<const f32x4*>(red)[i];
 }
 
 // ---- k_bwd_key --------------------------------------------------------------------------------
 // grid (chunks, H), block 256.  Per 32-token tile and lane (token r, gl):
-//   dS^T = dCsym V^T (+ dzsym) -> chain rule to d(phi_k1..3);  dV^T = dCsym^T S^T.
+//   dS^T = dCsym V^T (+ dzsym) -> chain rule to d(phi_k1..F);  dV^T = dCsym^T S^T.
 // LDS only serves the transpose of the dV tile for whole-row stores.
 // Both contractions run over channels or monomials, never over tokens, so a lane loads its own
 // token's V row straight into B-operand order; the next tile's row and features are fetched while
 // the current tile is computed.
-template <int DP, int D>
+template <class SY, int D>
 __global__ __launch_bounds__(kThreads) void k_bwd_key(Geom g, const BlockEnt* __restrict__ blocks,
                                                       const float* __restrict__ feat,
                                                       const unsigned char* __restrict__ dops, View V,
                                                       float* __restrict__ dfeat, View dV) {
-  using SY = Sym3<DP>;
-  using SL = StateLayout<DP, D>;
-  constexpr int SP = SY::SP, MP = SY::MP;
-  constexpr int NRB = D / 32, NKS = MP / 16, NKD = D / 16;
+  using SL = StateLayout<SY, D>;
+  constexpr int SP = SY::SP, MP = SY::MP, DP = SY::DPHI, F = SY::F;
+  constexpr int NRB = D / 32, NKS = MP / 16, NKD = D / 16, NRM = MP / 32;
+  constexpr int NF = F * DP;  // key features per token
   // LDS: the two operand images of the state gradient (shared by the four waves, read per use:
   // holding them in registers would leave no room for the software pipeline below), then one
   // transpose tile per wave for whole-row stores of dV
@@ -689,7 +712,7 @@ __global__ __launch_bounds__(kThreads) void k_bwd_key(Geom g, const BlockEnt* __
 
   // One tile's inputs: the V row pieces (B operand, k-slot (ks, gl, j) = channel 16ks + 8gl + j;
   // the 32-byte runs of a row that one load instruction touches are merged by the vector cache)
-  // and the 18 key features of the token.  vn/kn always hold the loads in flight for the coming
+  // and the F d_phi key features of the token.  vn/kn always hold the loads in flight for the coming
   // tile (rows past the chunk read its last row and are masked below) and are copied at the top
   // of the loop.  Memory instructions are spread through the iteration instead of issued in
   // bursts: the next tile's loads go out one at a time between the MFMAs of the first half, the
@@ -698,7 +721,7 @@ __global__ __launch_bounds__(kThreads) void k_bwd_key(Geom g, const BlockEnt* __
   // back-to-back bursts from all of them at once stall on the memory pipeline's queues.
   constexpr int PIECES = D / 8, RPI = 64 / PIECES, NST = 32 / RPI;  // dV row stores per tile
   u32x4 vb[NKD], vn[NKD];
-  float kb[3 * DP], kn[3 * DP];
+  float kb[NF], kn[NF];
   stagger_start(wave, blockIdx.x, HLA_STAGGER_CORE);
   int n0 = e.t0 + wave * 32;
   const bf16_t* nrow = nullptr;   // the coming tile's V row and feature address of this lane
@@ -713,12 +736,12 @@ __global__ __launch_bounds__(kThreads) void k_bwd_key(Geom g, const BlockEnt* __
 #pragma unroll
     for (int ks = 0; ks < NKD; ++ks) vn[ks] = *reinterpret_cast<const u32x4*>(nrow + 16 * ks + 8 * gl);
 #pragma unroll
-    for (int a = 0; a < 3 * DP; ++a) kn[a] = nfeat[32 * a];
+    for (int a = 0; a < NF; ++a) kn[a] = nfeat[32 * a];
   }
   int pend_n0 = -1;            // first token of the tile staged in LDS, -1: none
-  float pend_df[3 * DP];       // its feature gradients (this lane's token)
+  float pend_df[NF];           // its feature gradients (this lane's token)
 #pragma unroll
-  for (int a = 0; a < 3 * DP; ++a) pend_df[a] = 0.0f;
+  for (int a = 0; a < NF; ++a) pend_df[a] = 0.0f;
   // one dV row store of the staged tile
   auto flush_piece = [&](int i) {
     const int row = i * RPI + lane / PIECES, piece = lane % PIECES;
@@ -731,7 +754,7 @@ __global__ __launch_bounds__(kThreads) void k_bwd_key(Geom g, const BlockEnt* __
     if (pend_n0 >= 0 && pend_n0 + r < e.t1 && gl == 0) {
       float* df = dfeat + g.fidx(g.th(e.b, h, pend_n0 + r), DP);
 #pragma unroll
-      for (int a = 0; a < 3 * DP; ++a)
+      for (int a = 0; a < NF; ++a)
         if (a >= a0 && a < a1) df[32 * a] = pend_df[a];
     }
   };
@@ -740,38 +763,36 @@ __global__ __launch_bounds__(kThreads) void k_bwd_key(Geom g, const BlockEnt* __
 #pragma unroll
     for (int ks = 0; ks < NKD; ++ks) vb[ks] = vn[ks];
 #pragma unroll
-    for (int a = 0; a < 3 * DP; ++a) kb[a] = kn[a];
+    for (int a = 0; a < NF; ++a) kb[a] = kn[a];
     next_addr(n0 + kWaves * 32 < e.t1 ? n0 + kWaves * 32 : n0);
-    f32x16 dS[2];
+    f32x16 dS[NRM];
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
+    for (int rb = 0; rb < NRM; ++rb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) dS[rb][i] = 0.0f;
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int ks = 0; ks < NKD; ++ks) {
 #pragma unroll
-      for (int rb = 0; rb < 2; ++rb) dS[rb] = mfma32(opB[(rb * NKD + ks) * 64], vb[ks], dS[rb]);
+      for (int rb = 0; rb < NRM; ++rb) dS[rb] = mfma32(opB[(rb * NKD + ks) * 64], vb[ks], dS[rb]);
       vn[ks] = *reinterpret_cast<const u32x4*>(nrow + 16 * ks + 8 * gl);
       __builtin_amdgcn_sched_barrier(0);
     }
     // features of this lane's half: gl = 1 works on the reversed vectors; lanes past the chunk
     // work on zeros
-    float k1[DP], k2[DP], k3[DP];
+    float kk[F][DP];
     {
-      float kf[3 * DP];
+      float kf[NF];
 #pragma unroll
-      for (int a = 0; a < 3 * DP; ++a) kf[a] = live ? kb[a] : 0.0f;
+      for (int a = 0; a < NF; ++a) kf[a] = live ? kb[a] : 0.0f;
 #pragma unroll
-      for (int c = 0; c < DP; ++c) {
-        k1[c] = gl ? kf[DP - 1 - c] : kf[c];
-        k2[c] = gl ? kf[2 * DP - 1 - c] : kf[DP + c];
-        k3[c] = gl ? kf[3 * DP - 1 - c] : kf[2 * DP + c];
-      }
+      for (int f = 0; f < F; ++f)
+#pragma unroll
+        for (int c = 0; c < DP; ++c) kk[f][c] = gl ? kf[(f + 1) * DP - 1 - c] : kf[f * DP + c];
     }
     // dV^T = dCsym^T S^T
     float sm[SP];
-    key_monomials_slots<DP>(k1, k2, k3, sm);
+    sym_key_monomials_slots<SY>(kk, sm, gl);
     f32x16 acc[NRB];
 #pragma unroll
     for (int rb = 0; rb < NRB; ++rb)
@@ -787,50 +808,48 @@ __global__ __launch_bounds__(kThreads) void k_bwd_key(Geom g, const BlockEnt* __
       for (int rb = 0; rb < NRB; ++rb) {
         acc[rb] = mfma32(opA[(rb * NKS + ks) * 64], b, acc[rb]);
         // the coming tile's features, a few per MFMA
-        constexpr int kPerM = (3 * DP + NKS * NRB - 1) / (NKS * NRB);
+        constexpr int kPerM = (NF + NKS * NRB - 1) / (NKS * NRB);
 #pragma unroll
         for (int t = 0; t < kPerM; ++t) {
           const int a = (ks * NRB + rb) * kPerM + t;
-          if (a < 3 * DP) kn[a] = nfeat[32 * a];
+          if (a < NF) kn[a] = nfeat[32 * a];
         }
       }
       __builtin_amdgcn_sched_barrier(0);
     }
-    float dk1[DP], dk2[DP], dk3[DP];
+    float dk[F][DP];
     {
       float ds[SP];
 #pragma unroll
-      for (int rb = 0; rb < 2; ++rb)
+      for (int rb = 0; rb < NRM; ++rb)
 #pragma unroll
         for (int i = 0; i < 16; ++i) ds[16 * rb + i] = dS[rb][i] + dz[16 * rb + i];
 #pragma unroll
-      for (int c = 0; c < DP; ++c) dk1[c] = dk2[c] = dk3[c] = 0.0f;
+      for (int f = 0; f < F; ++f)
+#pragma unroll
+        for (int c = 0; c < DP; ++c) dk[f][c] = 0.0f;
       // chain rule in four quarters, the previous tile's outputs leaving in between
       static_for<0, 4>([&](auto Q) {
         constexpr int qd = decltype(Q)::value;
         constexpr int NS = SY::NS, S0 = qd * ((NS + 3) / 4), S1 = (qd + 1) * ((NS + 3) / 4);
-        key_monomials_grad_range<DP, S0, S1>(k1, k2, k3, ds, dk1, dk2, dk3);
+        sym_key_monomials_grad_range<SY, S0, S1>(kk, ds, dk, gl);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = qd * NST / 4; i < (qd + 1) * NST / 4; ++i) flush_piece(i);
-        flush_df(qd * (3 * DP + 3) / 4, (qd + 1) * (3 * DP + 3) / 4 < 3 * DP ? (qd + 1) * (3 * DP + 3) / 4 : 3 * DP);
+        flush_df(qd * (NF + 3) / 4, (qd + 1) * (NF + 3) / 4 < NF ? (qd + 1) * (NF + 3) / 4 : NF);
         __builtin_amdgcn_sched_barrier(0);
       });
     }
     {
-      float o1[DP], o2[DP], o3[DP];
+      float other[F][DP];
 #pragma unroll
-      for (int c = 0; c < DP; ++c) {
-        o1[c] = partner32(dk1[c]);
-        o2[c] = partner32(dk2[c]);
-        o3[c] = partner32(dk3[c]);
-      }
+      for (int f = 0; f < F; ++f)
 #pragma unroll
-      for (int c = 0; c < DP; ++c) {
-        pend_df[c] = dk1[c] + o1[DP - 1 - c];
-        pend_df[DP + c] = dk2[c] + o2[DP - 1 - c];
-        pend_df[2 * DP + c] = dk3[c] + o3[DP - 1 - c];
-      }
+        for (int c = 0; c < DP; ++c) other[f][c] = partner32(dk[f][c]);
+#pragma unroll
+      for (int f = 0; f < F; ++f)
+#pragma unroll
+        for (int c = 0; c < DP; ++c) pend_df[f * DP + c] = dk[f][c] + other[f][DP - 1 - c];
     }
     {
       wave_lds_sync();  // the flush above has read the whole staged tile
@@ -843,7 +862,7 @@ __global__ __launch_bounds__(kThreads) void k_bwd_key(Geom g, const BlockEnt* __
   // the last tile's outputs
 #pragma unroll
   for (int i = 0; i < NST; ++i) flush_piece(i);
-  flush_df(0, 3 * DP);
+  flush_df(0, NF);
 }
 
 inline int pick_chunk(const hla_handle* hd, const Geom& g, int num_seqs) {
@@ -890,9 +909,10 @@ hla_status allow_big_lds(K kernel, int bytes) {
              : HLA_ERR_HIP;
 }
 
-template <int DP, int D>
+template <class SY, int D>
 hla_status backward_core(hla_handle* hd, const hla_call_args& a) {
-  using SL = StateLayout<DP, D>;
+  using SL = StateLayout<SY, D>;
+  using SQ = BwdQSmem<D, SY::MP>;
   Geom g = hd->g;
   hipStream_t s = a.stream;
   const int chunk = pick_chunk(hd, g, a.num_seqs);
@@ -900,26 +920,26 @@ hla_status backward_core(hla_handle* hd, const hla_call_args& a) {
   HLA_TRY(get_table(hd, chunk, s, &chunks));
   static bool attr_set = false;
   if (!attr_set) {
-    HLA_TRY(allow_big_lds(&k_bwd_query<DP, D>, BwdQSmem<D>::kTotal));
+    HLA_TRY(allow_big_lds(&k_bwd_query<SY, D>, SQ::kTotal));
     attr_set = true;
   }
   unsigned char* ops = static_cast<unsigned char*>(hd->path_ws);
   unsigned char* dops = ops + SL::kOpBytes * hd->max_units;
-  HLA_TRY(launch(hd, "mfma_bwd_query", k_bwd_query<DP, D>, dim3(chunks->count, g.H), dim3(kThreads),
-                 BwdQSmem<D>::kTotal, s, g, chunks->dev, hd->feat, hd->den, ops, a.dO, hd->dfeat,
+  HLA_TRY(launch(hd, "mfma_bwd_query", k_bwd_query<SY, D>, dim3(chunks->count, g.H), dim3(kThreads),
+                 SQ::kTotal, s, g, chunks->dev, hd->feat, hd->den, ops, a.dO, hd->dfeat,
                  hd->partial, SL::kF32));
-  HLA_TRY(launch(hd, "mfma_dstate_reduce", k_reduce<DP, D, true>, dim3(a.num_seqs, g.H, kReduceSlices),
+  HLA_TRY(launch(hd, "mfma_dstate_reduce", k_reduce<SY, D, true>, dim3(a.num_seqs, g.H, kReduceSlices),
                  dim3(256), 0, s, g, chunks->seq_off_dev, hd->partial, SL::kF32, dops,
-                 make_slot_map<DP>()));
-  HLA_TRY(launch(hd, "mfma_bwd_key", k_bwd_key<DP, D>, dim3(chunks->count, g.H), dim3(kThreads),
+                 make_slot_map<SY>()));
+  HLA_TRY(launch(hd, "mfma_bwd_key", k_bwd_key<SY, D>, dim3(chunks->count, g.H), dim3(kThreads),
                  0, s, g, chunks->dev, hd->feat, dops, a.V, hd->dfeat, a.dV));
   return HLA_OK;
 }
 
-template <int DP, int D>
+template <class SY, int D>
 hla_status forward_core(hla_handle* hd, const hla_call_args& a) {
-  using SL = StateLayout<DP, D>;
-  using SM = StateSmem<D>;
+  using SL = StateLayout<SY, D>;
+  using SM = StateSmem<D, SY::MP>;
   Geom g = hd->g;
   hipStream_t s = a.stream;
   const int chunk = pick_chunk(hd, g, a.num_seqs);
@@ -930,17 +950,17 @@ hla_status forward_core(hla_handle* hd, const hla_call_args& a) {
     return HLA_ERR_INVALID_ARG;
   static bool attr_set = false;
   if (!attr_set) {
-    HLA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_state<DP, D>),
+    HLA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_state<SY, D>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, SM::kTotal));
     attr_set = true;
   }
-  HLA_TRY(launch(hd, "mfma_state", k_state<DP, D>, dim3(chunks->count, g.H), dim3(kThreads),
+  HLA_TRY(launch(hd, "mfma_state", k_state<SY, D>, dim3(chunks->count, g.H), dim3(kThreads),
                  SM::kTotal, s, g, chunks->dev, hd->feat, a.V, hd->partial, SL::kF32));
-  const SlotMap sm = make_slot_map<DP>();
+  const SlotMap sm = make_slot_map<SY>();
   unsigned char* ops = static_cast<unsigned char*>(hd->path_ws);
-  HLA_TRY(launch(hd, "mfma_state_reduce", k_reduce<DP, D, false>, dim3(a.num_seqs, g.H, kReduceSlices),
+  HLA_TRY(launch(hd, "mfma_state_reduce", k_reduce<SY, D, false>, dim3(a.num_seqs, g.H, kReduceSlices),
                  dim3(256), 0, s, g, chunks->seq_off_dev, hd->partial, SL::kF32, ops, sm));
-  HLA_TRY(launch(hd, "mfma_query", k_query<DP, D>, dim3(qblocks->count, g.H), dim3(kThreads), 0, s,
+  HLA_TRY(launch(hd, "mfma_query", k_query<SY, D>, dim3(qblocks->count, g.H), dim3(kThreads), 0, s,
                  g, qblocks->dev, hd->feat, ops, a.O, hd->den));
   return HLA_OK;
 }
@@ -951,14 +971,20 @@ bool aligned16(const View& v) {
 
 }  // namespace
 
+using Sym36 = Sym<3, 6>;    // three factors of six features: 56 monomials in 64 rows
+using Sym212 = Sym<2, 12>;  // two factors of twelve features: 78 monomials in 96 rows
+
 bool mfma_supported(const hla_config& c) {
-  return c.io_dtype == HLA_BF16 && c.degree == 3 && c.feature_dim == 6 &&
-         (c.head_dim == 64 || c.head_dim == 128);
+  const bool form = (c.degree == 3 && c.feature_dim == 6) || (c.degree == 2 && c.feature_dim == 12);
+  return c.io_dtype == HLA_BF16 && form && (c.head_dim == 64 || c.head_dim == 128);
 }
+
+// feature maps on the matrix cores: built for d_phi = 6; other forms take the fp32 kernels
+static bool mfma_phi(const hla_handle* hd) { return hd->g.dphi == 6 && hd->g.F == 3; }
 
 hla_status mfma_workspace_plan(hla_handle* hd) {
   const Geom& g = hd->g;
-  const int64_t MP = 64, SP = 32;
+  const int64_t MP = g.F == 3 ? Sym36::MP : Sym212::MP, SP = MP / 2;
   hd->state_stride = MP * g.d + MP;
   // pick_chunk keeps chunks * H <= kChunkTarget + num_seqs * H (it only ever grows the chunk)
   hd->max_chunks = (kChunkTarget + hd->cfg.max_heads - 1) / hd->cfg.max_heads + hd->cfg.max_seqs + 1;
@@ -967,32 +993,39 @@ hla_status mfma_workspace_plan(hla_handle* hd) {
   const int64_t op_bytes = 2 * MP * g.d * 2 + 2 * SP * 4;
   hd->path_ws_bytes = static_cast<size_t>(2 * op_bytes * hd->max_units);
   hd->w_packed_off = hd->path_ws_bytes;
-  if (hd->cfg.phi_mode == HLA_PHI_MLP) hd->path_ws_bytes += mfma_phi_packed_bytes(hd);
+  if (hd->cfg.phi_mode == HLA_PHI_MLP && mfma_phi(hd)) hd->path_ws_bytes += mfma_phi_packed_bytes(hd);
   return HLA_OK;
 }
 
-hla_status mfma_set_weights(hla_handle* hd, hipStream_t s) { return mfma_phi_set_weights(hd, s); }
+hla_status mfma_set_weights(hla_handle* hd, hipStream_t s) {
+  return mfma_phi(hd) ? mfma_phi_set_weights(hd, s) : HLA_OK;
+}
+
+template <class SY>
+static hla_status forward_sym(hla_handle* hd, const hla_call_args& a) {
+  return hd->g.d == 128 ? forward_core<SY, 128>(hd, a) : forward_core<SY, 64>(hd, a);
+}
+template <class SY>
+static hla_status backward_sym(hla_handle* hd, const hla_call_args& a) {
+  return hd->g.d == 128 ? backward_core<SY, 128>(hd, a) : backward_core<SY, 64>(hd, a);
+}
 
 hla_status mfma_forward(hla_handle* hd, const hla_call_args& a) {
   if (!aligned16(a.V) || !aligned16(a.O)) return HLA_ERR_UNSUPPORTED;
-  if (hd->cfg.phi_mode == HLA_PHI_MLP) {
+  if (hd->cfg.phi_mode == HLA_PHI_MLP && mfma_phi(hd)) {
     if (!aligned16(a.Q) || !aligned16(a.K)) return HLA_ERR_UNSUPPORTED;
     HLA_TRY(mfma_phi_forward(hd, a));
   } else {
     HLA_TRY(generic_features_in(hd, a));
   }
-  if (hd->g.d == 128) return forward_core<6, 128>(hd, a);
-  return forward_core<6, 64>(hd, a);
+  return hd->g.F == 3 ? forward_sym<Sym36>(hd, a) : forward_sym<Sym212>(hd, a);
 }
 
 hla_status mfma_backward(hla_handle* hd, const hla_call_args& a) {
   if (!aligned16(a.V) || !aligned16(a.O) || !aligned16(a.dO) || !aligned16(a.dV))
     return HLA_ERR_UNSUPPORTED;
-  if (hd->g.d == 128)
-    HLA_TRY((backward_core<6, 128>(hd, a)));
-  else
-    HLA_TRY((backward_core<6, 64>(hd, a)));
-  if (hd->cfg.phi_mode == HLA_PHI_MLP) {
+  HLA_TRY(hd->g.F == 3 ? backward_sym<Sym36>(hd, a) : backward_sym<Sym212>(hd, a));
+  if (hd->cfg.phi_mode == HLA_PHI_MLP && mfma_phi(hd)) {
     if (!aligned16(a.Q) || !aligned16(a.K) || !aligned16(a.dQ) || !aligned16(a.dK))
       return HLA_ERR_UNSUPPORTED;
     return mfma_phi_backward(hd, a);

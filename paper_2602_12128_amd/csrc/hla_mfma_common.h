@@ -437,6 +437,187 @@ __device__ __forceinline__ void key_monomials_grad(const float (&k1)[DP], const 
   key_monomials_grad_range<DP, 0, Sym3<DP>::NS>(k1, k2, k3, ds, dk1, dk2, dk3);
 }
 
+
+// ---- symmetric form of the degree-2 feature tensor -------------------------------------------
+// The same construction for T_q = q (x) q: monomials {x <= y}, query feature q_x q_y, key feature
+// k1_x k2_y + k1_y k2_x (one term when x == y).  Index reversal maps (x, y) to
+// (dphi-1-y, dphi-1-x) and fixes the dphi/2 monomials with x + y = dphi - 1, so the slots are the
+// NPAIR mirror pairs followed by the NFIX self-mirrored monomials.  Lane g = 0 serves a
+// self-mirrored monomial; on lane g = 1 the same instructions would produce it a second time, so
+// that lane multiplies those slots (values and gradients) by zero: (1, s) is padding there.
+struct Duo {
+  int x, y;
+};
+constexpr int sym2_num_mono(int dp) { return dp * (dp + 1) / 2; }
+constexpr Duo sym2_mono(int dp, int m) {
+  int c = 0;
+  for (int x = 0; x < dp; ++x)
+    for (int y = x; y < dp; ++y) {
+      if (c == m) return Duo{x, y};
+      ++c;
+    }
+  return Duo{-1, -1};
+}
+constexpr int sym2_canon(int dp, Duo t) {
+  int c = 0;
+  for (int x = 0; x < dp; ++x)
+    for (int y = x; y < dp; ++y) {
+      if (x == t.x && y == t.y) return c;
+      ++c;
+    }
+  return -1;
+}
+constexpr Duo sym2_mirror(int dp, Duo t) { return Duo{dp - 1 - t.y, dp - 1 - t.x}; }
+constexpr int sym2_num_pairs(int dp) { return (sym2_num_mono(dp) - dp / 2) / 2; }
+// slot s: first the monomials that precede their mirror image, then the self-mirrored ones
+constexpr Duo sym2_slot(int dp, int s) {
+  int c = 0;
+  for (int pass = 0; pass < 2; ++pass)
+    for (int m = 0; m < sym2_num_mono(dp); ++m) {
+      const Duo t = sym2_mono(dp, m);
+      const int mm = sym2_canon(dp, sym2_mirror(dp, t));
+      if (pass == 0 ? m < mm : m == mm) {
+        if (c == s) return t;
+        ++c;
+      }
+    }
+  return Duo{-1, -1};
+}
+constexpr int sym2_slot_canon(int dp, int g, int s) {
+  const int np = sym2_num_pairs(dp);
+  if (s >= np + dp / 2) return -1;
+  const Duo t = sym2_slot(dp, s);
+  if (s >= np) return g == 0 ? sym2_canon(dp, t) : -1;
+  return g == 0 ? sym2_canon(dp, t) : sym2_canon(dp, sym2_mirror(dp, t));
+}
+
+// Degree-generic view of the symmetric form: F = 3 is Sym3 above.
+template <int F_, int DP>
+struct Sym;
+template <int DP>
+struct Sym<3, DP> : Sym3<DP> {
+  static constexpr int F = 3;
+  static constexpr int DPHI = DP;
+  static constexpr int slot_canon(int g, int s) { return sym3_slot_canon(DP, g, s); }
+};
+template <int DP>
+struct Sym<2, DP> {
+  static_assert(DP % 2 == 0, "mirror pairing needs an even feature dim");
+  static constexpr int F = 2;
+  static constexpr int DPHI = DP;
+  static constexpr int NM = sym2_num_mono(DP);
+  static constexpr int NPAIR = sym2_num_pairs(DP);
+  static constexpr int NFIX = DP / 2;
+  static constexpr int NS = NPAIR + NFIX;
+  static constexpr int SP = (NS + 15) / 16 * 16;
+  static constexpr int MP = 2 * SP;
+  static constexpr int slot_canon(int g, int s) { return sym2_slot_canon(DP, g, s); }
+};
+
+// The monomial helpers below take the features of a token as f[map][DP] (already reversed on the
+// lanes of half gl = 1) and dispatch on the degree.
+template <class SY>
+__device__ __forceinline__ void sym_query_monomials(const float (&q)[SY::DPHI], float (&qm)[SY::SP],
+                                                    int gl) {
+  constexpr int DP = SY::DPHI;
+  if constexpr (SY::F == 3) {
+    query_monomials<DP>(q, qm);
+  } else {
+    const float fx = gl ? 0.0f : 1.0f;
+    static_for<0, SY::SP>([&](auto S) {
+      constexpr int s = decltype(S)::value;
+      if constexpr (s < SY::NS) {
+        constexpr Duo t = sym2_slot(DP, s);
+        qm[s] = s < SY::NPAIR ? q[t.x] * q[t.y] : (q[t.x] * q[t.y]) * fx;
+      } else {
+        qm[s] = 0.0f;
+      }
+    });
+  }
+}
+template <class SY>
+__device__ __forceinline__ void sym_query_monomials_grad(const float (&q)[SY::DPHI],
+                                                         const float (&dm)[SY::SP],
+                                                         float (&dq)[SY::DPHI], int gl) {
+  constexpr int DP = SY::DPHI;
+  if constexpr (SY::F == 3) {
+    query_monomials_grad<DP>(q, dm, dq);
+  } else {
+    const float fx = gl ? 0.0f : 1.0f;
+    static_for<0, SY::NS>([&](auto S) {
+      constexpr int s = decltype(S)::value;
+      constexpr Duo t = sym2_slot(DP, s);
+      const float w = s < SY::NPAIR ? dm[s] : dm[s] * fx;
+      dq[t.x] += w * q[t.y];
+      dq[t.y] += w * q[t.x];
+    });
+  }
+}
+// all NM key monomials in canonical order (one lane serves one token, features not reversed)
+template <class SY>
+__device__ __forceinline__ void sym_key_monomials_all(const float (&k)[SY::F][SY::DPHI],
+                                                      float (&sm)[SY::NM]) {
+  constexpr int DP = SY::DPHI;
+  if constexpr (SY::F == 3) {
+    key_monomials_all<DP>(k[0], k[1], k[2], sm);
+  } else {
+    static_for<0, SY::NM>([&](auto M) {
+      constexpr int m = decltype(M)::value;
+      constexpr Duo t = sym2_mono(DP, m);
+      if constexpr (t.x == t.y)
+        sm[m] = k[0][t.x] * k[1][t.x];
+      else
+        sm[m] = k[0][t.x] * k[1][t.y] + k[0][t.y] * k[1][t.x];
+    });
+  }
+}
+template <class SY>
+__device__ __forceinline__ void sym_key_monomials_slots(const float (&k)[SY::F][SY::DPHI],
+                                                        float (&sm)[SY::SP], int gl) {
+  constexpr int DP = SY::DPHI;
+  if constexpr (SY::F == 3) {
+    key_monomials_slots<DP>(k[0], k[1], k[2], sm);
+  } else {
+    const float fx = gl ? 0.0f : 1.0f;
+    static_for<0, SY::SP>([&](auto S) {
+      constexpr int s = decltype(S)::value;
+      if constexpr (s < SY::NS) {
+        constexpr Duo t = sym2_slot(DP, s);
+        if constexpr (t.x == t.y)
+          sm[s] = k[0][t.x] * k[1][t.x];
+        else
+          sm[s] = k[0][t.x] * k[1][t.y] + k[0][t.y] * k[1][t.x];
+        if constexpr (s >= SY::NPAIR) sm[s] *= fx;
+      } else {
+        sm[s] = 0.0f;
+      }
+    });
+  }
+}
+// chain rule of sym_key_monomials_slots over slots S0 .. S1-1
+template <class SY, int S0, int S1>
+__device__ __forceinline__ void sym_key_monomials_grad_range(const float (&k)[SY::F][SY::DPHI],
+                                                             const float (&ds)[SY::SP],
+                                                             float (&dk)[SY::F][SY::DPHI], int gl) {
+  constexpr int DP = SY::DPHI;
+  if constexpr (SY::F == 3) {
+    key_monomials_grad_range<DP, S0, S1>(k[0], k[1], k[2], ds, dk[0], dk[1], dk[2]);
+  } else {
+    const float fx = gl ? 0.0f : 1.0f;
+    static_for<S0, (S1 < SY::NS ? S1 : SY::NS)>([&](auto S) {
+      constexpr int s = decltype(S)::value;
+      constexpr Duo t = sym2_slot(DP, s);
+      const float w = s < SY::NPAIR ? ds[s] : ds[s] * fx;
+      dk[0][t.x] += w * k[1][t.y];
+      dk[1][t.y] += w * k[0][t.x];
+      if constexpr (t.x != t.y) {
+        dk[0][t.y] += w * k[1][t.x];
+        dk[1][t.x] += w * k[0][t.y];
+      }
+    });
+  }
+}
+
 }  // namespace mf
 }  // namespace hla
 

@@ -87,7 +87,7 @@ def test_unsupported_shapes_fall_back_or_report():
     assert h.active_path == hla.HLA_PATH_GENERIC
     h.destroy()
     with pytest.raises(hla.HLAError) as e:
-        hla.HLA(head_dim=128, feature_dim=12, degree=2, io_dtype=hla.HLA_BF16,
+        hla.HLA(head_dim=128, feature_dim=8, degree=2, io_dtype=hla.HLA_BF16,
                 phi_mode=hla.HLA_PHI_NONE, kernel_path=hla.HLA_PATH_MFMA, max_heads=1,
                 max_tokens=8, max_seqs=1)
     assert e.value.code == 2
