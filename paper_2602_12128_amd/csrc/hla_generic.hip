@@ -816,8 +816,7 @@ hla_status weight_grads_reduce(hla_handle* hd, int nparts, int heads, float sW1,
 }
 
 hla_status phi_weight_grads(hla_handle* hd, const hla_call_args& a) {
-  if (hd->path == HLA_PATH_MFMA && hd->cfg.io_dtype == HLA_BF16 && hd->g.dphi == 6 && hd->g.F == 3)
-    return mfma_phi_weight_grads(hd, a);
+  if (hd->path == HLA_PATH_MFMA && hd->cfg.io_dtype == HLA_BF16) return mfma_phi_weight_grads(hd, a);
   return hd->cfg.io_dtype == HLA_F32 ? weight_grads_t<float>(hd, a) : weight_grads_t<bf16_t>(hd, a);
 }
 

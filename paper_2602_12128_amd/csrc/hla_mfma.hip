@@ -974,13 +974,27 @@ bool aligned16(const View& v) {
 using Sym36 = Sym<3, 6>;    // three factors of six features: 56 monomials in 64 rows
 using Sym212 = Sym<2, 12>;  // two factors of twelve features: 78 monomials in 96 rows
 
+// every canonical monomial is served by exactly one (lane half, slot) pair
+template <class SY>
+constexpr bool slots_cover_monomials() {
+  int seen[SY::NM] = {};
+  for (int g = 0; g < 2; ++g)
+    for (int s = 0; s < SY::SP; ++s) {
+      const int m = SY::slot_canon(g, s);
+      if (m >= SY::NM) return false;
+      if (m >= 0) ++seen[m];
+    }
+  for (int m = 0; m < SY::NM; ++m)
+    if (seen[m] != 1) return false;
+  return true;
+}
+static_assert(Sym36::NM == 56 && Sym36::MP == 64 && slots_cover_monomials<Sym36>(), "degree-3 slot table");
+static_assert(Sym212::NM == 78 && Sym212::MP == 96 && slots_cover_monomials<Sym212>(), "degree-2 slot table");
+
 bool mfma_supported(const hla_config& c) {
   const bool form = (c.degree == 3 && c.feature_dim == 6) || (c.degree == 2 && c.feature_dim == 12);
   return c.io_dtype == HLA_BF16 && form && (c.head_dim == 64 || c.head_dim == 128);
 }
-
-// feature maps on the matrix cores: built for d_phi = 6; other forms take the fp32 kernels
-static bool mfma_phi(const hla_handle* hd) { return hd->g.dphi == 6 && hd->g.F == 3; }
 
 hla_status mfma_workspace_plan(hla_handle* hd) {
   const Geom& g = hd->g;
@@ -993,13 +1007,11 @@ hla_status mfma_workspace_plan(hla_handle* hd) {
   const int64_t op_bytes = 2 * MP * g.d * 2 + 2 * SP * 4;
   hd->path_ws_bytes = static_cast<size_t>(2 * op_bytes * hd->max_units);
   hd->w_packed_off = hd->path_ws_bytes;
-  if (hd->cfg.phi_mode == HLA_PHI_MLP && mfma_phi(hd)) hd->path_ws_bytes += mfma_phi_packed_bytes(hd);
+  if (hd->cfg.phi_mode == HLA_PHI_MLP) hd->path_ws_bytes += mfma_phi_packed_bytes(hd);
   return HLA_OK;
 }
 
-hla_status mfma_set_weights(hla_handle* hd, hipStream_t s) {
-  return mfma_phi(hd) ? mfma_phi_set_weights(hd, s) : HLA_OK;
-}
+hla_status mfma_set_weights(hla_handle* hd, hipStream_t s) { return mfma_phi_set_weights(hd, s); }
 
 template <class SY>
 static hla_status forward_sym(hla_handle* hd, const hla_call_args& a) {
@@ -1012,7 +1024,7 @@ static hla_status backward_sym(hla_handle* hd, const hla_call_args& a) {
 
 hla_status mfma_forward(hla_handle* hd, const hla_call_args& a) {
   if (!aligned16(a.V) || !aligned16(a.O)) return HLA_ERR_UNSUPPORTED;
-  if (hd->cfg.phi_mode == HLA_PHI_MLP && mfma_phi(hd)) {
+  if (hd->cfg.phi_mode == HLA_PHI_MLP) {
     if (!aligned16(a.Q) || !aligned16(a.K)) return HLA_ERR_UNSUPPORTED;
     HLA_TRY(mfma_phi_forward(hd, a));
   } else {
@@ -1025,7 +1037,7 @@ hla_status mfma_backward(hla_handle* hd, const hla_call_args& a) {
   if (!aligned16(a.V) || !aligned16(a.O) || !aligned16(a.dO) || !aligned16(a.dV))
     return HLA_ERR_UNSUPPORTED;
   HLA_TRY(hd->g.F == 3 ? backward_sym<Sym36>(hd, a) : backward_sym<Sym212>(hd, a));
-  if (hd->cfg.phi_mode == HLA_PHI_MLP && mfma_phi(hd)) {
+  if (hd->cfg.phi_mode == HLA_PHI_MLP) {
     if (!aligned16(a.Q) || !aligned16(a.K) || !aligned16(a.dQ) || !aligned16(a.dK))
       return HLA_ERR_UNSUPPORTED;
     return mfma_phi_backward(hd, a);

@@ -19,7 +19,6 @@ namespace {
 
 using namespace mf;
 
-constexpr int kDP = 6;
 struct TrueTag {
   static constexpr bool value = true;
 };
@@ -148,8 +147,8 @@ struct Packed {
   static constexpr int kW2A = kW1T + D * D * 2;       // fp16 [D/16][64][8]: A operand of u^T = W2^T g^T; times 4
   static constexpr int kW2B = kW2A + D * 32 * 2;      // bf16 [D/32][64][8]: A operand of dg^T = W2 du^T; times 4
   static constexpr int kB1 = kW2B + D * 16 * 2;       // fp32 [D]; times 1/4
-  static constexpr int kB2 = kB1 + D * 4;             // fp32 [8]
-  static constexpr int kBytes = kB2 + 32;
+  static constexpr int kB2 = kB1 + D * 4;             // fp32 [16]
+  static constexpr int kBytes = kB2 + 64;
 };
 
 // hidden unit that k-slot (ks2, gl, j) of the second-layer contraction stands for: the slots
@@ -187,7 +186,7 @@ __global__ void k_pack_phi(PhiF32 w, int dphi, unsigned char* __restrict__ out) 
     w2b[i] = a < dphi ? f32_to_bf16_bits(W2[(32 * rb + r) * dphi + a] / kHiddenScale) : 0;
   }
   for (int i = threadIdx.x; i < D; i += blockDim.x) b1[i] = kHiddenScale * w.b1[mh * D + i];
-  for (int i = threadIdx.x; i < 8; i += blockDim.x) b2[i] = i < dphi ? w.b2[mh * dphi + i] : 0.0f;
+  for (int i = threadIdx.x; i < 16; i += blockDim.x) b2[i] = i < dphi ? w.b2[mh * dphi + i] : 0.0f;
 }
 
 // ---- LDS layout ---------------------------------------------------------------------------------
@@ -201,7 +200,7 @@ struct PhiSmem {
   static constexpr int kRow = D * 2;                  // bytes per row
   static constexpr int kW1 = D * D * 2;
   static constexpr int kW2 = BACKWARD ? D * 16 * 2 : D * 32 * 2;  // W2B (backward) or W2A (forward)
-  static constexpr int kMap = kW1 + kW2 + D * 4 + 32;  // then b1 [D] and b2 [8] in fp32
+  static constexpr int kMap = kW1 + kW2 + D * 4 + 64;  // then b1 [D] and b2 [16] in fp32
   // backward adds a 16-row transpose tile per wave for whole-row stores of dX
   static constexpr int total(int nmaps, int waves) {
     return nmaps * kMap + (BACKWARD ? waves * RowTile<D, 16>::kBytes : 0);
@@ -223,7 +222,7 @@ __device__ __forceinline__ void load_weights(unsigned char* dst, const unsigned 
   using PK = Packed<D>;
   constexpr int N1 = D * SM::kChunks;                              // 16-byte chunks of W1^T
   constexpr int N2 = (BACKWARD ? D * 16 * 2 : D * 32 * 2) / 16;    // 16-byte chunks of the W2 image
-  constexpr int NB = D + 8;                                        // floats of b1 and b2
+  constexpr int NB = D + 16;                                       // floats of b1 and b2
   constexpr int I1 = (N1 + THREADS - 1) / THREADS, I2 = (N2 + THREADS - 1) / THREADS;
   const unsigned char* w2 = src + (BACKWARD ? PK::kW2B : PK::kW2A);
   const int t = threadIdx.x;
@@ -306,7 +305,7 @@ __device__ __forceinline__ TileMap make_tile_map(const Geom& g, int heads_w) {
 // block WAVES*64.  Maps map0 .. map0+NMAPS-1 are applied to X; the features go to the fp32
 // feature workspace.  Wave w of the grid serves 32-token tiles w, w + (total waves), ..; the next
 // tile's inputs are loaded while the current one is computed.
-template <int D, int NMAPS, int WAVES>
+template <int D, int NMAPS, int WAVES, int DPH>
 __global__ __launch_bounds__(WAVES * 64) void k_phi_fwd(Geom g, View X,
                                                         const unsigned char* __restrict__ wpk,
                                                         int heads_w, int map0, int nmaps,
@@ -335,15 +334,25 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_fwd(Geom g, View X,
     tm.decode(tile, b, h, n0);
     load_x<D>(X, b, h, n0 + r, g.N, gl, xb);
   }
-  float pend[4] = {0.0f, 0.0f, 0.0f, 0.0f};  // features of the last finished map, not yet stored
-  float* pend_ptr = nullptr;
+  // features of the last finished map, not yet stored: accumulator register i of the second layer
+  // is feature d_row(i, gl) = 8 (i/4) + 4 gl + i%4; the registers with a feature below d_phi on
+  // either lane half are kept
+  constexpr int NU = DPH > 8 ? 8 : 4;
+  static_assert(DPH <= 16, "one 16-row group of second-layer outputs");
+  float pend[NU];
+#pragma unroll
+  for (int i = 0; i < NU; ++i) pend[i] = 0.0f;
+  float* pend_ptr = nullptr;  // feature 4 gl of the token
   auto flush = [&]() {  // feature a of 32 consecutive tokens is one contiguous 128-byte run
     if (pend_ptr != nullptr) {
-      pend_ptr[0] = pend[0];
-      pend_ptr[32] = pend[1];
-      if (gl == 0) {
-        pend_ptr[64] = pend[2];
-        pend_ptr[96] = pend[3];
+#pragma unroll
+      for (int i = 0; i < NU; ++i) {
+        const int a0 = 8 * (i / 4) + i % 4;  // feature held by lane half 0; half 1 holds a0 + 4
+        if (a0 + 4 < DPH) {
+          pend_ptr[32 * a0] = pend[i];
+        } else if (a0 < DPH) {
+          if (gl == 0) pend_ptr[32 * a0] = pend[i];
+        }
       }
     }
     pend_ptr = nullptr;
@@ -437,18 +446,15 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_fwd(Geom g, View X,
         u = mfma32_f16(a21, gb[1], u);
         cur = nxt;
       }
-      // rows d_row(i, gl) < d_phi: lane gl=0 holds features 0..3, lane gl=1 features 4, 5.  The
-      // store is held back until the next map (or the next tile's input wait) has been passed:
+      // The store is held back until the next map (or the next tile's input wait) has been passed:
       // stores count in the same wait counter as loads, and a store issued just before that wait
       // would make the wave sit out the store's full round trip.
       flush();
       {
         const float* b2 = reinterpret_cast<const float*>(wm + SM::kW1 + SM::kW2 + D * 4) + 4 * gl;
-        pend[0] = fmaxf(u[0] + b2[0], 0.0f);
-        pend[1] = fmaxf(u[1] + b2[1], 0.0f);
-        pend[2] = fmaxf(u[2] + b2[2], 0.0f);
-        pend[3] = fmaxf(u[3] + b2[3], 0.0f);
-        pend_ptr = live ? feat + g.fidx(th, (map0 + m) * kDP + 4 * gl) : nullptr;
+#pragma unroll
+        for (int i = 0; i < NU; ++i) pend[i] = fmaxf(u[i] + b2[8 * (i / 4) + i % 4], 0.0f);
+        pend_ptr = live ? feat + g.fidx(th, (map0 + m) * DPH + 4 * gl) : nullptr;
       }
     }
   }
@@ -458,7 +464,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_fwd(Geom g, View X,
 // ---- backward -----------------------------------------------------------------------------------
 // block WAVES*64.  dX = sum over the NMAPS maps of W1 (GELU'(h) * (W2 du)), with du = d(feature)
 // where the ReLU was open.  Hidden activations are recomputed.
-template <int D, int NMAPS, int WAVES>
+template <int D, int NMAPS, int WAVES, int DPH>
 __global__ __launch_bounds__(WAVES * 64) void k_phi_bwd(Geom g, View X,
                                                         const unsigned char* __restrict__ wpk,
                                                         int heads_w, int map0, int nmaps,
@@ -502,22 +508,42 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_bwd(Geom g, View X,
     tm.decode(tile, b, h, n0);
     load_x<D>(X, b, h, n0 + r, g.N, gl, xb);
   }
-  // du^T of one map as B operand of a single 16-slot step: slot (gl, j) is feature 8gl + j (only
-  // gl = 0 is used); zero where the ReLU was closed
+  // du^T of one map as B operand of a single 16-slot step: slot (gl, j) is feature 8gl + j (with
+  // d_phi <= 8 only gl = 0 is used); zero where the ReLU was closed
   auto load_du = [&](int64_t th, bool live, int m) -> u32x4 {
     u32x4 d;
     d[0] = d[1] = d[2] = d[3] = 0u;
-    if (live && gl == 0) {
-      const int64_t o = g.fidx(th, (map0 + m) * kDP);
-      float fv[kDP], dv[kDP];  // both loaded unconditionally: one round trip, not six
+    static_assert(DPH % 2 == 0 && DPH <= 16, "features are packed in pairs into one k-step");
+    if constexpr (DPH <= 8) {
+      if (live && gl == 0) {
+        const int64_t o = g.fidx(th, (map0 + m) * DPH);
+        float fv[DPH], dv[DPH];  // both loaded unconditionally: one round trip, not one per feature
 #pragma unroll
-      for (int a = 0; a < kDP; ++a) {
-        fv[a] = feat[o + 32 * a];
-        dv[a] = dfeat[o + 32 * a];
+        for (int a = 0; a < DPH; ++a) {
+          fv[a] = feat[o + 32 * a];
+          dv[a] = dfeat[o + 32 * a];
+        }
+#pragma unroll
+        for (int p = 0; p < DPH / 2; ++p)
+          d[p] = pack_bf16(fv[2 * p] > 0.0f ? dv[2 * p] : 0.0f, fv[2 * p + 1] > 0.0f ? dv[2 * p + 1] : 0.0f);
       }
+    } else {
+      if (live) {
+        // lane half 1 holds the DPH - 8 features from the ninth on; its surplus slots re-read the
+        // half's first feature and stay zero
+        const int64_t o = g.fidx(th, (map0 + m) * DPH + 8 * gl);
+        const int have = gl ? DPH - 8 : 8;
+        float fv[8], dv[8];
 #pragma unroll
-      for (int p = 0; p < kDP / 2; ++p)
-        d[p] = pack_bf16(fv[2 * p] > 0.0f ? dv[2 * p] : 0.0f, fv[2 * p + 1] > 0.0f ? dv[2 * p + 1] : 0.0f);
+        for (int a = 0; a < 8; ++a) {
+          fv[a] = feat[o + 32 * (a < have ? a : 0)];
+          dv[a] = dfeat[o + 32 * (a < have ? a : 0)];
+        }
+#pragma unroll
+        for (int p = 0; p < 4; ++p)
+          d[p] = pack_bf16(2 * p < have && fv[2 * p] > 0.0f ? dv[2 * p] : 0.0f,
+                           2 * p + 1 < have && fv[2 * p + 1] > 0.0f ? dv[2 * p + 1] : 0.0f);
+      }
     }
     return d;
   };
@@ -707,7 +733,7 @@ struct WgSmem {
   static constexpr int kWaveBytes = kXBytes + 32 * kGStride;
 };
 
-template <int D, int WAVES>
+template <int D, int WAVES, int DPH>
 __global__ __launch_bounds__(WAVES * 64) void k_phi_wgrad(Geom g, View Q, View K,
                                                           const unsigned char* __restrict__ wpk,
                                                           int heads_w,
@@ -753,7 +779,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_wgrad(Geom g, View Q, View K
   f32x16 acc[NRB];   // dW1 rows 32 ib + d_row(i, gl), column 32 hb + r
   f32x16 acc2;       // dW2^T rows = features d_row(i, gl), column 32 hb + r
   float db1[16];     // per-lane (token r) sums of dh for hidden 32 hb + d_row(i, gl)
-  float db2[kDP];    // per-lane sums of du (lanes gl == 0)
+  float db2[DPH];    // per-lane sums of du (read from the lanes gl == 0)
 #pragma unroll
   for (int i = 0; i < 16; ++i) {
 #pragma unroll
@@ -762,7 +788,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_wgrad(Geom g, View Q, View K
     db1[i] = 0.0f;
   }
 #pragma unroll
-  for (int a = 0; a < kDP; ++a) db2[a] = 0.0f;
+  for (int a = 0; a < DPH; ++a) db2[a] = 0.0f;
   // The next tile's inputs are loaded as soon as the current tile's have been consumed (the
   // input rows after the copy to LDS, the features once du is formed).  These loads are
   // unconditional with clamped addresses, so that the same number is outstanding on every path;
@@ -770,7 +796,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_wgrad(Geom g, View Q, View K
   const int step = gridDim.x * TH;
   int tile = blockIdx.x * TH + th;
   u32x4 xb[NKS], xn[NKS];  // input rows of the next tile and of the one after
-  float fv[kDP], dv[kDP];
+  float fv[DPH], dv[DPH];
   auto coords = [&](int t, int& b, int& h, int& n0) {
     const int row = t / tpr;
     n0 = (t % tpr) * 32;
@@ -779,9 +805,9 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_wgrad(Geom g, View Q, View K
   };
   auto fetch_features = [&](int b, int h, int n0) {
     const int n = n0 + r;
-    const int64_t o = g.fidx(g.th(b, h, n < g.N ? n : g.N - 1), m * kDP);
+    const int64_t o = g.fidx(g.th(b, h, n < g.N ? n : g.N - 1), m * DPH);
 #pragma unroll
-    for (int a = 0; a < kDP; ++a) {
+    for (int a = 0; a < DPH; ++a) {
       fv[a] = feat[o + 32 * a];
       dv[a] = dfeat[o + 32 * a];
     }
@@ -796,18 +822,24 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_wgrad(Geom g, View Q, View K
     z4[0] = z4[1] = z4[2] = z4[3] = 0u;
     for (int o = lane * 16; o < 2 * SM::kWaveBytes; o += 64 * 16) *reinterpret_cast<u32x4*>(xt + o) = z4;
   }
+  // du of the token: zero where the ReLU was closed, and for tokens past the end (whose clamped
+  // input row then adds nothing to any sum).  As the B operand of dg = W2 du^T, slot (gl, j) is
+  // feature 8 gl + j: with d_phi <= 8 the lanes gl = 1 hold zeros throughout (db2 included), with
+  // more features they hold the ninth feature on.
   auto make_du = [&](bool live, u32x4& dub) {
-    // du of the token: zero where the ReLU was closed, and for tokens past the end (whose clamped
-    // input row then adds nothing to any sum)
-    float du[kDP];
+    float du[DPH];
 #pragma unroll
-    for (int a = 0; a < kDP; ++a) du[a] = live && gl == 0 && fv[a] > 0.0f ? dv[a] : 0.0f;
-    dub[0] = pack_bf16(du[0], du[1]);
-    dub[1] = pack_bf16(du[2], du[3]);
-    dub[2] = pack_bf16(du[4], du[5]);
-    dub[3] = 0u;
+    for (int a = 0; a < DPH; ++a) du[a] = live && (DPH > 8 || gl == 0) && fv[a] > 0.0f ? dv[a] : 0.0f;
 #pragma unroll
-    for (int a = 0; a < kDP; ++a) db2[a] += du[a];
+    for (int p = 0; p < 4; ++p) {
+      const float lo0 = 2 * p < DPH ? du[2 * p < DPH ? 2 * p : 0] : 0.0f;
+      const float hi0 = 2 * p + 1 < DPH ? du[2 * p + 1 < DPH ? 2 * p + 1 : 0] : 0.0f;
+      const float lo1 = 8 + 2 * p < DPH ? du[8 + 2 * p < DPH ? 8 + 2 * p : 0] : 0.0f;
+      const float hi1 = 9 + 2 * p < DPH ? du[9 + 2 * p < DPH ? 9 + 2 * p : 0] : 0.0f;
+      dub[p] = DPH > 8 ? pack_bf16(gl ? lo1 : lo0, gl ? hi1 : hi0) : pack_bf16(lo0, hi0);
+    }
+#pragma unroll
+    for (int a = 0; a < DPH; ++a) db2[a] += du[a];
   };
   auto put_x_tile = [&](unsigned char* xdst, const u32x4 (&xr)[NKS], const u32x4& dub) {  // [token][channels | du]
 #pragma unroll
@@ -815,8 +847,9 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_wgrad(Geom g, View Q, View K
       *reinterpret_cast<u32x4*>(xdst + r * SM::kXStride + (16 * ks + 8 * gl) * 2) = xr[ks];
     u32x4 z4;
     z4[0] = z4[1] = z4[2] = z4[3] = 0u;
-    *reinterpret_cast<u32x4*>(xdst + r * SM::kXStride + (D + 16 * gl) * 2) = gl == 0 ? dub : z4;
-    *reinterpret_cast<u32x4*>(xdst + r * SM::kXStride + (D + 16 * gl + 8) * 2) = z4;
+    // du columns D + 8 gl .. + 7 are this lane's operand slots; columns D + 16 .. D + 31 are zero
+    *reinterpret_cast<u32x4*>(xdst + r * SM::kXStride + (D + 8 * gl) * 2) = dub;
+    *reinterpret_cast<u32x4*>(xdst + r * SM::kXStride + (D + 16 + 8 * gl) * 2) = z4;
   };
   // transpose-read operand: tokens 16 ks + 8 gl + {0..7} of 32 columns starting at col0
   auto operand = [&](const unsigned char* tl, int stride, int ks, int col0) {
@@ -868,17 +901,9 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_wgrad(Geom g, View Q, View K
     }
     u32x4 dubn;
     {
-      // the next tile's du without touching db2 twice for a repeated last tile
-      float du[kDP];
-      const bool live = n0 + r < g.N && tile + step < total;
-#pragma unroll
-      for (int a = 0; a < kDP; ++a) du[a] = live && gl == 0 && fv[a] > 0.0f ? dv[a] : 0.0f;
-      dubn[0] = pack_bf16(du[0], du[1]);
-      dubn[1] = pack_bf16(du[2], du[3]);
-      dubn[2] = pack_bf16(du[4], du[5]);
-      dubn[3] = 0u;
-#pragma unroll
-      for (int a = 0; a < kDP; ++a) db2[a] += du[a];
+      // the next tile's du; a repeated last tile counts as past the end, so that db2 is not
+      // touched twice
+      make_du(n0 + r < g.N && tile + step < total, dubn);
     }
     {
       int b2, h2, n02;
@@ -968,16 +993,16 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_wgrad(Geom g, View Q, View K
   }
   // ---- this wave's share of the partial
   const int nparts = gridDim.x * TH;
-  const int64_t floats = static_cast<int64_t>(D) * D + D + D * kDP + kDP;
+  const int64_t floats = static_cast<int64_t>(D) * D + D + D * DPH + DPH;
   float* out = partial + ((static_cast<int64_t>(m) * gridDim.z + hw) * nparts + blockIdx.x * TH + th) * floats;
 #pragma unroll
   for (int ib = 0; ib < NRB; ++ib)
 #pragma unroll
     for (int i = 0; i < 16; ++i) out[(32 * ib + d_row(i, gl)) * D + 32 * hb + r] = acc[ib][i];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int a = 4 * gl + i;  // d_row(i, gl) for i < 4
-    if (a < kDP) out[D * D + D + (32 * hb + r) * kDP + a] = acc2[i];
+  for (int i = 0; i < (DPH > 8 ? 8 : 4); ++i) {
+    const int a = d_row(i, gl);
+    if (a < DPH) out[D * D + D + (32 * hb + r) * DPH + a] = acc2[i];
   }
   // sums over the 32 tokens of a half-wave (xor offsets below 32 stay inside it)
 #pragma unroll
@@ -989,11 +1014,11 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_wgrad(Geom g, View Q, View K
   }
   if (hb == 0) {
 #pragma unroll
-    for (int a = 0; a < kDP; ++a) {
+    for (int a = 0; a < DPH; ++a) {
       float v = db2[a];
 #pragma unroll
       for (int off = 16; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
-      if (lane == 0) out[D * D + D + D * kDP + a] = v;
+      if (lane == 0) out[D * D + D + D * DPH + a] = v;
     }
   }
 }
@@ -1025,41 +1050,42 @@ dim3 phi_grid(const hla_handle* hd, int waves) {
 
 constexpr int kWavesF = HLA_PHI_WAVES_F, kWavesB = HLA_PHI_WAVES_B;
 
-template <int D>
+// F key maps of DPH features each, after the query map
+template <int D, int F, int DPH>
 hla_status forward_t(hla_handle* hd, const hla_call_args& a) {
   using SM = PhiSmem<D>;
   Geom g = hd->g;
   const unsigned char* wpk = static_cast<const unsigned char*>(hd->path_ws) + hd->w_packed_off;
   static bool attr = false;
   if (!attr) {
-    HLA_TRY(allow_lds(&k_phi_fwd<D, 1, kWavesF>, SM::total(1, kWavesF)));
-    HLA_TRY(allow_lds(&k_phi_fwd<D, 3, kWavesF>, SM::total(3, kWavesF)));
+    HLA_TRY(allow_lds(&k_phi_fwd<D, 1, kWavesF, DPH>, SM::total(1, kWavesF)));
+    HLA_TRY(allow_lds(&k_phi_fwd<D, F, kWavesF, DPH>, SM::total(F, kWavesF)));
     attr = true;
   }
   const dim3 grid = phi_grid(hd, kWavesF);
-  HLA_TRY(launch(hd, "mfma_phi_forward_q", k_phi_fwd<D, 1, kWavesF>, grid, dim3(kWavesF * 64),
+  HLA_TRY(launch(hd, "mfma_phi_forward_q", k_phi_fwd<D, 1, kWavesF, DPH>, grid, dim3(kWavesF * 64),
                  SM::total(1, kWavesF), a.stream, g, a.Q, wpk, hd->phi.heads_w, 0, 1, hd->feat));
-  HLA_TRY(launch(hd, "mfma_phi_forward_k", k_phi_fwd<D, 3, kWavesF>, grid, dim3(kWavesF * 64),
-                 SM::total(3, kWavesF), a.stream, g, a.K, wpk, hd->phi.heads_w, 1, 3, hd->feat));
+  HLA_TRY(launch(hd, "mfma_phi_forward_k", k_phi_fwd<D, F, kWavesF, DPH>, grid, dim3(kWavesF * 64),
+                 SM::total(F, kWavesF), a.stream, g, a.K, wpk, hd->phi.heads_w, 1, F, hd->feat));
   return HLA_OK;
 }
 
-template <int D>
+template <int D, int F, int DPH>
 hla_status backward_t(hla_handle* hd, const hla_call_args& a) {
   using SM = PhiSmem<D, true>;
   Geom g = hd->g;
   const unsigned char* wpk = static_cast<const unsigned char*>(hd->path_ws) + hd->w_packed_off;
   static bool attr = false;
   if (!attr) {
-    HLA_TRY(allow_lds(&k_phi_bwd<D, 1, kWavesB>, SM::total(1, kWavesB)));
-    HLA_TRY(allow_lds(&k_phi_bwd<D, 3, kWavesB>, SM::total(3, kWavesB)));
+    HLA_TRY(allow_lds(&k_phi_bwd<D, 1, kWavesB, DPH>, SM::total(1, kWavesB)));
+    HLA_TRY(allow_lds(&k_phi_bwd<D, F, kWavesB, DPH>, SM::total(F, kWavesB)));
     attr = true;
   }
   const dim3 grid = phi_grid(hd, kWavesB);
-  HLA_TRY(launch(hd, "mfma_phi_backward_q", k_phi_bwd<D, 1, kWavesB>, grid, dim3(kWavesB * 64),
+  HLA_TRY(launch(hd, "mfma_phi_backward_q", k_phi_bwd<D, 1, kWavesB, DPH>, grid, dim3(kWavesB * 64),
                  SM::total(1, kWavesB), a.stream, g, a.Q, wpk, hd->phi.heads_w, 0, 1, hd->feat, hd->dfeat, a.dQ));
-  HLA_TRY(launch(hd, "mfma_phi_backward_k", k_phi_bwd<D, 3, kWavesB>, grid, dim3(kWavesB * 64),
-                 SM::total(3, kWavesB), a.stream, g, a.K, wpk, hd->phi.heads_w, 1, 3, hd->feat, hd->dfeat, a.dK));
+  HLA_TRY(launch(hd, "mfma_phi_backward_k", k_phi_bwd<D, F, kWavesB, DPH>, grid, dim3(kWavesB * 64),
+                 SM::total(F, kWavesB), a.stream, g, a.K, wpk, hd->phi.heads_w, 1, F, hd->feat, hd->dfeat, a.dK));
   return HLA_OK;
 }
 
@@ -1068,17 +1094,16 @@ hla_status backward_t(hla_handle* hd, const hla_call_args& a) {
 #endif
 constexpr int kWavesW = HLA_WG_WAVES;  // one wave per SIMD: the live set needs more than 256 registers
 
-template <int D>
+template <int D, int DPH>
 hla_status weight_grads_t(hla_handle* hd, const hla_call_args& a) {
   using SM = WgSmem<D>;
   constexpr int TH = kWavesW / (D / 32);
   constexpr int lds = 2 * kWavesW * SM::kWaveBytes;  // two sets of tiles per wave
   Geom g = hd->g;
-  if (g.dphi != kDP || g.F != 3) return HLA_ERR_UNSUPPORTED;
   const unsigned char* wpk = static_cast<const unsigned char*>(hd->path_ws) + hd->w_packed_off;
   static bool attr = false;
   if (!attr) {
-    HLA_TRY(allow_lds(&k_phi_wgrad<D, kWavesW>, lds));
+    HLA_TRY(allow_lds(&k_phi_wgrad<D, kWavesW, DPH>, lds));
     attr = true;
   }
   const int nm = 1 + g.F;
@@ -1091,7 +1116,7 @@ hla_status weight_grads_t(hla_handle* hd, const hla_call_args& a) {
   if (nblk < 1) nblk = 1;
   const int64_t nparts = nblk * TH;
   if (nm * heads * nparts > hd->wg_parts_cap) return HLA_ERR_STATE;
-  HLA_TRY(launch(hd, "mfma_phi_weight_grads", k_phi_wgrad<D, kWavesW>,
+  HLA_TRY(launch(hd, "mfma_phi_weight_grads", k_phi_wgrad<D, kWavesW, DPH>,
                  dim3(static_cast<unsigned>(nblk), nm, heads), dim3(kWavesW * 64), lds, a.stream, g, a.Q, a.K,
                  wpk, hd->phi.heads_w, static_cast<const float*>(hd->feat),
                  static_cast<const float*>(hd->dfeat), hd->wg_partial));
@@ -1102,8 +1127,15 @@ hla_status weight_grads_t(hla_handle* hd, const hla_call_args& a) {
 
 }  // namespace
 
+// the two forms the matrix-core path serves: (F, d_phi) = (3, 6) and (2, 12)
+bool mfma_phi_supported(const hla_handle* hd) {
+  return (hd->g.F == 3 && hd->g.dphi == 6) || (hd->g.F == 2 && hd->g.dphi == 12);
+}
+
 hla_status mfma_phi_weight_grads(hla_handle* hd, const hla_call_args& a) {
-  return hd->g.d == 128 ? weight_grads_t<128>(hd, a) : weight_grads_t<64>(hd, a);
+  if (!mfma_phi_supported(hd)) return HLA_ERR_UNSUPPORTED;
+  if (hd->g.F == 3) return hd->g.d == 128 ? weight_grads_t<128, 6>(hd, a) : weight_grads_t<64, 6>(hd, a);
+  return hd->g.d == 128 ? weight_grads_t<128, 12>(hd, a) : weight_grads_t<64, 12>(hd, a);
 }
 
 size_t mfma_phi_packed_bytes(const hla_handle* hd) {
@@ -1120,11 +1152,15 @@ hla_status mfma_phi_set_weights(hla_handle* hd, hipStream_t s) {
 }
 
 hla_status mfma_phi_forward(hla_handle* hd, const hla_call_args& a) {
-  return hd->g.d == 128 ? forward_t<128>(hd, a) : forward_t<64>(hd, a);
+  if (!mfma_phi_supported(hd)) return HLA_ERR_UNSUPPORTED;
+  if (hd->g.F == 3) return hd->g.d == 128 ? forward_t<128, 3, 6>(hd, a) : forward_t<64, 3, 6>(hd, a);
+  return hd->g.d == 128 ? forward_t<128, 2, 12>(hd, a) : forward_t<64, 2, 12>(hd, a);
 }
 
 hla_status mfma_phi_backward(hla_handle* hd, const hla_call_args& a) {
-  return hd->g.d == 128 ? backward_t<128>(hd, a) : backward_t<64>(hd, a);
+  if (!mfma_phi_supported(hd)) return HLA_ERR_UNSUPPORTED;
+  if (hd->g.F == 3) return hd->g.d == 128 ? backward_t<128, 3, 6>(hd, a) : backward_t<64, 3, 6>(hd, a);
+  return hd->g.d == 128 ? backward_t<128, 2, 12>(hd, a) : backward_t<64, 2, 12>(hd, a);
 }
 
 }  // namespace hla
