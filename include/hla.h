@@ -50,7 +50,9 @@ typedef enum { HLA_F32 = 0, HLA_BF16 = 1 } hla_dtype;
  *               and 3 factors take them.  Features are expected >= 0 (Sec. 4.2); not checked. */
 typedef enum { HLA_PHI_MLP = 0, HLA_PHI_NONE = 1 } hla_phi_mode;
 
-/* Which kernels serve the handle.  AUTO picks the MFMA path when the configuration has one. */
+/* Which kernels serve the handle.  AUTO picks the MFMA path when the configuration has one: bf16
+ * tensors, head_dim 64 or 128, and one of the paper's two forms (App. A.1), F = 3 with d_phi = 6
+ * or F = 2 with d_phi = 12. */
 typedef enum {
   HLA_PATH_AUTO = 0,
   HLA_PATH_GENERIC = 1, /* fp32 vector-ALU kernels over the literal d_phi^F state; any supported shape */

@@ -17,14 +17,16 @@ import json
 import re
 import sys
 
-_KERNEL = re.compile(r"(k_[a-z_0-9]+<[^>]*>|k_[a-z_0-9]+|__amd_rocclr_\w+)")
+_KERNEL = re.compile(r"(k_[a-z_0-9]+|__amd_rocclr_\w+)")
 
 # kernel symbol -> name used by the library's launch records / bench.py
 LAUNCH_NAMES = {
     "k_phi_fwd<128, 1": "mfma_phi_forward_q", "k_phi_fwd<128, 3": "mfma_phi_forward_k",
     "k_phi_fwd<64, 1": "mfma_phi_forward_q", "k_phi_fwd<64, 3": "mfma_phi_forward_k",
+    "k_phi_fwd<128, 2": "mfma_phi_forward_k", "k_phi_fwd<64, 2": "mfma_phi_forward_k",
     "k_phi_bwd<128, 1": "mfma_phi_backward_q", "k_phi_bwd<128, 3": "mfma_phi_backward_k",
     "k_phi_bwd<64, 1": "mfma_phi_backward_q", "k_phi_bwd<64, 3": "mfma_phi_backward_k",
+    "k_phi_bwd<128, 2": "mfma_phi_backward_k", "k_phi_bwd<64, 2": "mfma_phi_backward_k",
     "k_state<": "mfma_state", "k_query<": "mfma_query", "k_bwd_query<": "mfma_bwd_query",
     "k_bwd_key<": "mfma_bwd_key", "k_reduce<": "mfma_reduce",
     "k_phi_wgrad<128,": "mfma_phi_weight_grads", "k_phi_wgrad<64,": "mfma_phi_weight_grads",
@@ -33,8 +35,20 @@ LAUNCH_NAMES = {
 
 
 def _short(name: str) -> str:
+    """`k_name<template arguments>` out of a demangled symbol (nested brackets kept whole,
+    namespaces dropped)."""
     m = _KERNEL.search(name)
-    return m.group(1) if m else name[:40]
+    if not m:
+        return name[:40]
+    end = m.end()
+    if name[end:end + 1] == "<":
+        depth = 0
+        for i in range(end, len(name)):
+            depth += {"<": 1, ">": -1}.get(name[i], 0)
+            if depth == 0:
+                end = i + 1
+                break
+    return name[m.start():end].replace("hla::mf::", "").replace("hla::", "")
 
 
 def stats(d: str) -> None:
