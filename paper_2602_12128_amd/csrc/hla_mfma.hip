@@ -366,9 +366,24 @@ __global__ __launch_bounds__(kThreads) void k_query(Geom g, const BlockEnt* __re
   for (int rb = 0; rb < NRB; ++rb)
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) a[rb][ks] = opA[(rb * NKS + ks) * 64 + lane];
-  float z[SP];
+  // The normaliser vector of this lane's half: in registers, or -- when the state has more than 64
+  // rows and the registers would no longer allow two waves per SIMD -- in LDS, read per tile.
+  constexpr bool kZInLds = SP > 32;
+  __shared__ __align__(16) float zs[kZInLds ? 2 * SP : 4];
+  float z[kZInLds ? 1 : SP];
+  if constexpr (kZInLds) {
+    if (threadIdx.x < 2 * SP) zs[threadIdx.x] = (zslot - gl * SP)[threadIdx.x];
+    __syncthreads();
+  } else {
 #pragma unroll
-  for (int s = 0; s < SP; ++s) z[s] = zslot[s];
+    for (int s = 0; s < SP; ++s) z[s] = zslot[s];
+  }
+  auto zval = [&](int s) -> float {
+    if constexpr (kZInLds)
+      return zs[gl * SP + s];
+    else
+      return z[s];
+  };
 
   // The features of the next tile are loaded while the current one is computed; the loads are
   // unconditional (token clamped into the block) so that they stay in flight across the loop
@@ -399,7 +414,7 @@ __global__ __launch_bounds__(kThreads) void k_query(Geom g, const BlockEnt* __re
         const int s = 8 * ks + 2 * p;
         const uint32_t pk = pack_bf16(qm[s], qm[s + 1]);
         b[ks][p] = pk;
-        eta += bf16_lo(pk) * z[s] + bf16_hi(pk) * z[s + 1];  // the same rounded values the MFMA sees
+        eta += bf16_lo(pk) * zval(s) + bf16_hi(pk) * zval(s + 1);  // the same rounded values the MFMA sees
       }
     eta += partner32(eta);
     const float dn = eta + g.eps;
@@ -430,7 +445,7 @@ struct BwdQSmem {
   // With more than 64 state rows the monomial-row operand image of the state does not fit the
   // register file next to the accumulators: the workgroup keeps one copy in LDS instead.
   static constexpr bool kOpsInLds = MP > 64;
-  static constexpr int kOpBytes = kOpsInLds ? MP * D * 2 : 0;
+  static constexpr int kOpBytes = kOpsInLds ? MP * D * 2 + MP * 4 : 0;  // image, then the normaliser vector
   static constexpr int kStream = kOpBytes + kWaves * kWaveBytes;
   static constexpr int kRedBytes = WaveSum<D, MP>::kBytes;
   static constexpr int kTotal = kStream > kRedBytes ? kStream : kRedBytes;
@@ -470,11 +485,12 @@ __global__ __launch_bounds__(kThreads) void k_bwd_query(
   const float* zslot = reinterpret_cast<const float*>(ops + u * SL::kOpBytes + 2 * SL::kOpElems * 2) + gl * SP;
   u32x4 a_mo[SM::kOpsInLds ? 1 : NRM][SM::kOpsInLds ? 1 : NKD];
   if constexpr (SM::kOpsInLds) {
-    constexpr int N16 = SM::kOpBytes / 16;
+    constexpr int N16 = MP * D * 2 / 16;
     static_assert(N16 % kThreads == 0, "the operand image is copied in whole rounds");
 #pragma unroll
     for (int k = 0; k < N16 / kThreads; ++k)
       reinterpret_cast<u32x4*>(smem)[threadIdx.x + k * kThreads] = opB[threadIdx.x + k * kThreads];
+    if (threadIdx.x < MP) reinterpret_cast<float*>(smem + MP * D * 2)[threadIdx.x] = (zslot - gl * SP)[threadIdx.x];
     __syncthreads();
   } else {
 #pragma unroll
@@ -488,13 +504,21 @@ __global__ __launch_bounds__(kThreads) void k_bwd_query(
     else
       return a_mo[rb][ks];
   };
-  float z[SP];
+  float z[SM::kOpsInLds ? 1 : SP];  // this half's normaliser entries (in LDS next to the image otherwise)
+  if constexpr (!SM::kOpsInLds) {
 #pragma unroll
-  for (int s4 = 0; s4 < SP / 4; ++s4) {
-    const f32x4 v = *reinterpret_cast<const f32x4*>(zslot + 4 * s4);
+    for (int s4 = 0; s4 < SP / 4; ++s4) {
+      const f32x4 v = *reinterpret_cast<const f32x4*>(zslot + 4 * s4);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) z[4 * s4 + i] = v[i];
+      for (int i = 0; i < 4; ++i) z[4 * s4 + i] = v[i];
+    }
   }
+  auto zval = [&](int s) -> float {
+    if constexpr (SM::kOpsInLds)
+      return reinterpret_cast<const float*>(smem + MP * D * 2)[gl * SP + s];
+    else
+      return z[s];
+  };
   // per-lane LDS offsets: own-row writes, and transpose reads of token rows 8gl + L/4 (+4) at the
   // 4 columns 32x + 16(q%2) + 4(L%4) ..+3 (x = row block of Qm^T or column block of dO)
   int dw_off[NKD];
@@ -573,8 +597,13 @@ __global__ __launch_bounds__(kThreads) void k_bwd_query(
     // monomials of this lane's slots and their scaled bf16 copy (a row of the A^T tile)
     const float inv = live ? 1.0f / denb : 0.0f;
     float qf[DP];
+    {
+      float fr[DP];  // reversed copy first: see the note on selects in k_bwd_key
 #pragma unroll
-    for (int c = 0; c < DP; ++c) qf[c] = gl ? fb[DP - 1 - c] : fb[c];
+      for (int c = 0; c < DP; ++c) fr[c] = fb[DP - 1 - c];
+#pragma unroll
+      for (int c = 0; c < DP; ++c) qf[c] = gl ? fr[c] : fb[c];
+    }
     float qm[SP];
     sym_query_monomials<SY>(qf, qm, gl);
 #pragma unroll
@@ -596,7 +625,7 @@ __global__ __launch_bounds__(kThreads) void k_bwd_query(
     for (int rb = 0; rb < NRM; ++rb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        dm[16 * rb + i] = inv * X[rb][i] + si * z[16 * rb + i];
+        dm[16 * rb + i] = inv * X[rb][i] + si * zval(16 * rb + i);
         dzacc[16 * rb + i] += si * qm[16 * rb + i];
       }
     float dq[DP];
@@ -782,13 +811,20 @@ __global__ __launch_bounds__(kThreads) void k_bwd_key(Geom g, const BlockEnt* __
     // work on zeros
     float kk[F][DP];
     {
-      float kf[NF];
+      // the reversed copy is a renaming of registers; selecting between the two arrays element by
+      // element costs one v_cndmask each (a select between two elements of ONE array may be turned
+      // into a run-time index, which is lowered to a compare-and-select chain over the whole array)
+      float kf[NF], kr[NF];
 #pragma unroll
       for (int a = 0; a < NF; ++a) kf[a] = live ? kb[a] : 0.0f;
 #pragma unroll
       for (int f = 0; f < F; ++f)
 #pragma unroll
-        for (int c = 0; c < DP; ++c) kk[f][c] = gl ? kf[(f + 1) * DP - 1 - c] : kf[f * DP + c];
+        for (int c = 0; c < DP; ++c) kr[f * DP + c] = kf[(f + 1) * DP - 1 - c];
+#pragma unroll
+      for (int f = 0; f < F; ++f)
+#pragma unroll
+        for (int c = 0; c < DP; ++c) kk[f][c] = gl ? kr[f * DP + c] : kf[f * DP + c];
     }
     // dV^T = dCsym^T S^T
     float sm[SP];
