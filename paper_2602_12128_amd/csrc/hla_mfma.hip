@@ -574,18 +574,13 @@ __global__ __launch_bounds__(kThreads) void k_bwd_query(
       dn = 1.0f;
     }
   };
-  stagger_start(wave, blockIdx.x, HLA_STAGGER_CORE);
-  int n0 = e.t0 + wave * 32;
-  if (n0 < e.t1) fetch(n0, xb, fb, denb);
-  for (; n0 < e.t1; n0 += kWaves * 32) {
-    const int n = n0 + r;
-    const bool live = n < e.t1;
-    const int64_t th = g.th(e.b, h, live ? n : e.t0);
-    if (n0 + kWaves * 32 < e.t1) fetch(n0 + kWaves * 32, xn, fn, denn);
-    // dO tile for the token contraction, X^T = Csym dO^T on the matrix pipe
-#pragma unroll
-    for (int ks = 0; ks < NKD; ++ks) *reinterpret_cast<u32x4*>(ds + dw_off[ks]) = xb[ks];
-    f32x16 X[NRM];
+  // X^T = Csym dO^T of one tile: NKD dependent MFMAs per row block that everything else in the
+  // tile waits for.  With the operand image in registers there is room to run them one tile ahead,
+  // at the end of the previous iteration (the rows are prefetched by then), so that they complete
+  // in the shadow of the next tile's monomial arithmetic.
+  constexpr bool kXAhead = !SM::kOpsInLds;
+  f32x16 X[NRM];
+  auto x_product = [&](const u32x4(&x)[NKD]) {
 #pragma unroll
     for (int rb = 0; rb < NRM; ++rb)
 #pragma unroll
@@ -593,7 +588,23 @@ __global__ __launch_bounds__(kThreads) void k_bwd_query(
 #pragma unroll
     for (int ks = 0; ks < NKD; ++ks)
 #pragma unroll
-      for (int rb = 0; rb < NRM; ++rb) X[rb] = mfma32(state_op(rb, ks), xb[ks], X[rb]);
+      for (int rb = 0; rb < NRM; ++rb) X[rb] = mfma32(state_op(rb, ks), x[ks], X[rb]);
+  };
+  stagger_start(wave, blockIdx.x, HLA_STAGGER_CORE);
+  int n0 = e.t0 + wave * 32;
+  if (n0 < e.t1) {
+    fetch(n0, xb, fb, denb);
+    if constexpr (kXAhead) x_product(xb);
+  }
+  for (; n0 < e.t1; n0 += kWaves * 32) {
+    const int n = n0 + r;
+    const bool live = n < e.t1;
+    const int64_t th = g.th(e.b, h, live ? n : e.t0);
+    if (n0 + kWaves * 32 < e.t1) fetch(n0 + kWaves * 32, xn, fn, denn);
+    // dO tile for the token contraction
+#pragma unroll
+    for (int ks = 0; ks < NKD; ++ks) *reinterpret_cast<u32x4*>(ds + dw_off[ks]) = xb[ks];
+    if constexpr (!kXAhead) x_product(xb);
     // monomials of this lane's slots and their scaled bf16 copy (a row of the A^T tile)
     const float inv = live ? 1.0f / denb : 0.0f;
     float qf[DP];
@@ -668,6 +679,7 @@ __global__ __launch_bounds__(kThreads) void k_bwd_query(
       }
     }
     wave_lds_sync();
+    if constexpr (kXAhead) x_product(xn);  // the next tile's (after the last tile: unused)
 #pragma unroll
     for (int ks = 0; ks < NKD; ++ks) xb[ks] = xn[ks];
 #pragma unroll
