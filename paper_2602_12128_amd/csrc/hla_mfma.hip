@@ -575,10 +575,9 @@ __global__ __launch_bounds__(kThreads) void k_bwd_query(
     }
   };
   // X^T = Csym dO^T of one tile: NKD dependent MFMAs per row block that everything else in the
-  // tile waits for.  With the operand image in registers there is room to run them one tile ahead,
-  // at the end of the previous iteration (the rows are prefetched by then), so that they complete
-  // in the shadow of the next tile's monomial arithmetic.
-  constexpr bool kXAhead = !SM::kOpsInLds;
+  // tile waits for.  They run one tile ahead, at the end of the previous iteration (the rows are
+  // prefetched by then), so that they complete in the shadow of the next tile's monomial
+  // arithmetic.
   f32x16 X[NRM];
   auto x_product = [&](const u32x4(&x)[NKD]) {
 #pragma unroll
@@ -594,7 +593,7 @@ __global__ __launch_bounds__(kThreads) void k_bwd_query(
   int n0 = e.t0 + wave * 32;
   if (n0 < e.t1) {
     fetch(n0, xb, fb, denb);
-    if constexpr (kXAhead) x_product(xb);
+    x_product(xb);
   }
   for (; n0 < e.t1; n0 += kWaves * 32) {
     const int n = n0 + r;
@@ -604,7 +603,6 @@ __global__ __launch_bounds__(kThreads) void k_bwd_query(
     // dO tile for the token contraction
 #pragma unroll
     for (int ks = 0; ks < NKD; ++ks) *reinterpret_cast<u32x4*>(ds + dw_off[ks]) = xb[ks];
-    if constexpr (!kXAhead) x_product(xb);
     // monomials of this lane's slots and their scaled bf16 copy (a row of the A^T tile)
     const float inv = live ? 1.0f / denb : 0.0f;
     float qf[DP];
@@ -679,7 +677,7 @@ __global__ __launch_bounds__(kThreads) void k_bwd_query(
       }
     }
     wave_lds_sync();
-    if constexpr (kXAhead) x_product(xn);  // the next tile's (after the last tile: unused)
+    x_product(xn);  // the next tile's (after the last tile: unused)
 #pragma unroll
     for (int ks = 0; ks < NKD; ++ks) xb[ks] = xn[ks];
 #pragma unroll
