@@ -306,10 +306,9 @@ __device__ __forceinline__ TileMap make_tile_map(const Geom& g, int heads_w) {
 // feature workspace.  Wave w of the grid serves 32-token tiles w, w + (total waves), ..; the next
 // tile's inputs are loaded while the current one is computed.
 template <int D, int NMAPS, int WAVES, int DPH>
-__global__ __launch_bounds__(WAVES * 64) void k_phi_fwd(Geom g, View X,
-                                                        const unsigned char* __restrict__ wpk,
-                                                        int heads_w, int map0, int nmaps,
-                                                        float* __restrict__ feat) {
+__device__ __forceinline__ void phi_fwd_body(const Geom& g, const View& X,
+                                             const unsigned char* __restrict__ wpk, int heads_w,
+                                             int map0, int nmaps, float* __restrict__ feat) {
   using SM = PhiSmem<D>;
   constexpr int NRB = D / 32, NKS = D / 16;
   extern __shared__ __align__(16) unsigned char smem[];
@@ -461,15 +460,26 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_fwd(Geom g, View X,
   flush();
 }
 
+// The query map, then the F key maps, in one launch: a workgroup that has finished its share of
+// the query tiles swaps the weights in LDS and goes on with the key tiles, so the launch has no
+// boundary in between (no drain of the grid, no second cold start).  `nk` is F at run time.
+template <int D, int F, int WAVES, int DPH>
+__global__ __launch_bounds__(WAVES * 64) void k_phi_fwd(Geom g, View Q, View K,
+                                                        const unsigned char* __restrict__ wpk,
+                                                        int heads_w, int nk, float* __restrict__ feat) {
+  phi_fwd_body<D, 1, WAVES, DPH>(g, Q, wpk, heads_w, 0, 1, feat);
+  __syncthreads();  // every wave is done with the query map's weights
+  phi_fwd_body<D, F, WAVES, DPH>(g, K, wpk, heads_w, 1, nk, feat);
+}
+
 // ---- backward -----------------------------------------------------------------------------------
 // block WAVES*64.  dX = sum over the NMAPS maps of W1 (GELU'(h) * (W2 du)), with du = d(feature)
 // where the ReLU was open.  Hidden activations are recomputed.
 template <int D, int NMAPS, int WAVES, int DPH>
-__global__ __launch_bounds__(WAVES * 64) void k_phi_bwd(Geom g, View X,
-                                                        const unsigned char* __restrict__ wpk,
-                                                        int heads_w, int map0, int nmaps,
-                                                        const float* __restrict__ feat,
-                                                        const float* __restrict__ dfeat, View dX) {
+__device__ __forceinline__ void phi_bwd_body(const Geom& g, const View& X,
+                                             const unsigned char* __restrict__ wpk, int heads_w,
+                                             int map0, int nmaps, const float* __restrict__ feat,
+                                             const float* __restrict__ dfeat, const View& dX) {
   using SM = PhiSmem<D, true>;
   constexpr int NRB = D / 32, NKS = D / 16;
   extern __shared__ __align__(16) unsigned char smem[];
@@ -708,6 +718,19 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_bwd(Geom g, View X,
       return on0 + t < g.N ? dX.row<bf16_t>(ob, oh, on0 + t) : nullptr;
     });
   }
+}
+
+// dQ through the query map, then dK through the F key maps, in one launch (see k_phi_fwd)
+template <int D, int F, int WAVES, int DPH>
+__global__ __launch_bounds__(WAVES * 64) void k_phi_bwd(Geom g, View Q, View K,
+                                                        const unsigned char* __restrict__ wpk,
+                                                        int heads_w, int nk,
+                                                        const float* __restrict__ feat,
+                                                        const float* __restrict__ dfeat, View dQ,
+                                                        View dK) {
+  phi_bwd_body<D, 1, WAVES, DPH>(g, Q, wpk, heads_w, 0, 1, feat, dfeat, dQ);
+  __syncthreads();  // every wave is done with the query map's weights and its transpose tile
+  phi_bwd_body<D, F, WAVES, DPH>(g, K, wpk, heads_w, 1, nk, feat, dfeat, dK);
 }
 
 // ---- weight gradients ---------------------------------------------------------------------------
@@ -1058,15 +1081,12 @@ hla_status forward_t(hla_handle* hd, const hla_call_args& a) {
   const unsigned char* wpk = static_cast<const unsigned char*>(hd->path_ws) + hd->w_packed_off;
   static bool attr = false;
   if (!attr) {
-    HLA_TRY(allow_lds(&k_phi_fwd<D, 1, kWavesF, DPH>, SM::total(1, kWavesF)));
     HLA_TRY(allow_lds(&k_phi_fwd<D, F, kWavesF, DPH>, SM::total(F, kWavesF)));
     attr = true;
   }
   const dim3 grid = phi_grid(hd, kWavesF);
-  HLA_TRY(launch(hd, "mfma_phi_forward_q", k_phi_fwd<D, 1, kWavesF, DPH>, grid, dim3(kWavesF * 64),
-                 SM::total(1, kWavesF), a.stream, g, a.Q, wpk, hd->phi.heads_w, 0, 1, hd->feat));
-  HLA_TRY(launch(hd, "mfma_phi_forward_k", k_phi_fwd<D, F, kWavesF, DPH>, grid, dim3(kWavesF * 64),
-                 SM::total(F, kWavesF), a.stream, g, a.K, wpk, hd->phi.heads_w, 1, F, hd->feat));
+  HLA_TRY(launch(hd, "mfma_phi_forward", k_phi_fwd<D, F, kWavesF, DPH>, grid, dim3(kWavesF * 64),
+                 SM::total(F, kWavesF), a.stream, g, a.Q, a.K, wpk, hd->phi.heads_w, F, hd->feat));
   return HLA_OK;
 }
 
@@ -1077,15 +1097,13 @@ hla_status backward_t(hla_handle* hd, const hla_call_args& a) {
   const unsigned char* wpk = static_cast<const unsigned char*>(hd->path_ws) + hd->w_packed_off;
   static bool attr = false;
   if (!attr) {
-    HLA_TRY(allow_lds(&k_phi_bwd<D, 1, kWavesB, DPH>, SM::total(1, kWavesB)));
     HLA_TRY(allow_lds(&k_phi_bwd<D, F, kWavesB, DPH>, SM::total(F, kWavesB)));
     attr = true;
   }
   const dim3 grid = phi_grid(hd, kWavesB);
-  HLA_TRY(launch(hd, "mfma_phi_backward_q", k_phi_bwd<D, 1, kWavesB, DPH>, grid, dim3(kWavesB * 64),
-                 SM::total(1, kWavesB), a.stream, g, a.Q, wpk, hd->phi.heads_w, 0, 1, hd->feat, hd->dfeat, a.dQ));
-  HLA_TRY(launch(hd, "mfma_phi_backward_k", k_phi_bwd<D, F, kWavesB, DPH>, grid, dim3(kWavesB * 64),
-                 SM::total(F, kWavesB), a.stream, g, a.K, wpk, hd->phi.heads_w, 1, F, hd->feat, hd->dfeat, a.dK));
+  HLA_TRY(launch(hd, "mfma_phi_backward", k_phi_bwd<D, F, kWavesB, DPH>, grid, dim3(kWavesB * 64),
+                 SM::total(F, kWavesB), a.stream, g, a.Q, a.K, wpk, hd->phi.heads_w, F, hd->feat,
+                 hd->dfeat, a.dQ, a.dK));
   return HLA_OK;
 }
 

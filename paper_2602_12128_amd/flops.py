@@ -73,14 +73,12 @@ def kernel_model(name: str, d: int, d_phi: int, F: int, e: int = 2):
     lin = 2 * d * d + 2 * d * d_phi            # one feature map forward
     lin_b = 4 * d * d + 2 * d * d_phi          # one feature map backward (recompute + input grad)
     m = {
-        "mfma_phi_forward_q": (d * e + qf, lin, "mfma"),
-        "mfma_phi_forward_k": (d * e + kf, F * lin, "mfma"),
+        "mfma_phi_forward": (2 * d * e + qf + kf, (1 + F) * lin, "mfma"),     # query map and key maps, one launch
         "mfma_state": (d * e + kf, 2 * D * d + D, "hbm"),
         "mfma_query": (qf + d * e + 4, 2 * D * d + 2 * D, "hbm"),
         "mfma_bwd_query": (d * e + qf + 4 + qf, 4 * D * d, "hbm"),   # dO, features, den in; feature grads out
         "mfma_bwd_key": (d * e + kf + d * e + kf, 4 * D * d, "hbm"),
-        "mfma_phi_backward_q": (2 * d * e + 2 * qf, lin_b, "mfma"),
-        "mfma_phi_backward_k": (2 * d * e + 2 * kf, F * lin_b, "mfma"),
+        "mfma_phi_backward": (4 * d * e + 2 * (qf + kf), (1 + F) * lin_b, "mfma"),
         "generic_phi_forward": (2 * d * e + qf + kf, phi_forward_flops(d, d_phi, F), "alu"),
         "generic_phi_backward": (2 * d * e + 2 * (qf + kf) + 2 * d * e, phi_backward_flops(d, d_phi, F), "alu"),
     }

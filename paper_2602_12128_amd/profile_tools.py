@@ -21,12 +21,7 @@ _KERNEL = re.compile(r"(k_[a-z_0-9]+|__amd_rocclr_\w+)")
 
 # kernel symbol -> name used by the library's launch records / bench.py
 LAUNCH_NAMES = {
-    "k_phi_fwd<128, 1": "mfma_phi_forward_q", "k_phi_fwd<128, 3": "mfma_phi_forward_k",
-    "k_phi_fwd<64, 1": "mfma_phi_forward_q", "k_phi_fwd<64, 3": "mfma_phi_forward_k",
-    "k_phi_fwd<128, 2": "mfma_phi_forward_k", "k_phi_fwd<64, 2": "mfma_phi_forward_k",
-    "k_phi_bwd<128, 1": "mfma_phi_backward_q", "k_phi_bwd<128, 3": "mfma_phi_backward_k",
-    "k_phi_bwd<64, 1": "mfma_phi_backward_q", "k_phi_bwd<64, 3": "mfma_phi_backward_k",
-    "k_phi_bwd<128, 2": "mfma_phi_backward_k", "k_phi_bwd<64, 2": "mfma_phi_backward_k",
+    "k_phi_fwd<": "mfma_phi_forward", "k_phi_bwd<": "mfma_phi_backward",
     "k_state<": "mfma_state", "k_query<": "mfma_query", "k_bwd_query<": "mfma_bwd_query",
     "k_bwd_key<": "mfma_bwd_key", "k_reduce<": "mfma_reduce",
     "k_phi_wgrad<128,": "mfma_phi_weight_grads", "k_phi_wgrad<64,": "mfma_phi_weight_grads",
