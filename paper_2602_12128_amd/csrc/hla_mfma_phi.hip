@@ -8,8 +8,9 @@
 //                                    memory in operand order
 //   u^T[d_phi x 32]  = W2^T g^T      B = GELU(hidden) packed straight from the accumulators
 // and backward   dg^T = W2 du^T,  dh = dg * GELU'(hidden),  dx^T = W1 dh^T  (A = the same LDS copy
-// of W1^T, transpose reads).  The weights of a head stay resident in LDS for the workgroup's
-// lifetime; each wave streams its own 32-token tiles, and two (backward) or three (forward) waves
+// of W1^T, transpose reads).  The weights of a head stay resident in LDS while the workgroup
+// works through its tiles (first the query map's, then the key maps'); each wave streams its own
+// 32-token tiles, and two (backward) or three (forward) waves
 // share a SIMD so that one wave's GELU arithmetic overlaps the others' matrix and LDS work.
 #include "hla_handle.h"
 #include "hla_mfma_common.h"
