@@ -131,3 +131,23 @@ def test_forward_backward_can_be_captured_in_a_graph():
         for a, b in zip(ref, outs):
             assert torch.equal(a, b), f"eager after replay {rep}"
     h.destroy()
+
+
+@pytest.mark.parametrize("F,dphi", [(3, 6), (2, 12)])
+def test_handle_reuse_sees_fresh_partial_states(F, dphi):
+    # A handle keeps its workspace (chunk partials, reduced states, features) between calls; a call
+    # must read only what it wrote itself, never what an earlier call left at the same addresses.
+    # Two different inputs through one handle, several times over: every result must equal, bit
+    # for bit, what a fresh handle computes for that input.
+    B, H, N, d = 2, 6, 9000, 128   # 12 units of several chunks each, workgroups on every XCD
+    ta = wl.make_feature_inputs(901, B, H, N, d, F, dphi, torch.bfloat16)
+    tb = wl.make_feature_inputs(902, B, H, N, d, F, dphi, torch.bfloat16, kind="lognormal")
+    fresh = {id(t): pu.run_gpu(t, F, dphi, 1e-6, path=hla.HLA_PATH_MFMA) for t in (ta, tb)}
+    h = pu.make_handle(ta, F, dphi, 1e-6, None, None, hla.HLA_PATH_MFMA)
+    for t in (ta, tb, tb, ta, tb, ta):
+        got = pu.run_gpu(t, F, dphi, 1e-6, handle=h)
+        for k in ("O", "dQ", "dK", "dV"):
+            assert torch.equal(got[k], fresh[id(t)][k]), k
+    h.destroy()
+    ref = pu.run_oracle({k: v[:, :2] for k, v in tb.items()}, F, dphi, 1e-6)
+    pu.assert_parity({k: fresh[id(tb)][k][:, :2] for k in ref}, ref, 2e-2, f"reuse F={F}")
