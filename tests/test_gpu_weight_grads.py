@@ -110,12 +110,16 @@ def test_registration_rules_and_repeatability():
     h2.destroy()
 
 
-def test_fewer_heads_than_the_handle_allows_and_empty_input():
+@pytest.mark.parametrize("F,dphi", [(3, 6), (2, 12)])
+def test_fewer_heads_than_the_handle_allows_and_empty_input(F, dphi):
     dev = torch.device("cuda:0")
     Hmax, H, N, d = 4, 2, 70, 64
-    t, _ = wl.make_raw_inputs(790, 1, H, N, d, 3, 6, torch.bfloat16)
-    phi = _per_head_phi(791, Hmax, d, 6, 4, torch.bfloat16)
-    h = hla.HLA(head_dim=d, io_dtype=hla.HLA_BF16, max_heads=Hmax, max_tokens=N, max_seqs=1)
+    nmaps, nfeat = 1 + F, (1 + F) * dphi
+    t, _ = wl.make_raw_inputs(790, 1, H, N, d, F, dphi, torch.bfloat16)
+    phi = _per_head_phi(791, Hmax, d, dphi, nmaps, torch.bfloat16)
+    h = hla.HLA(head_dim=d, feature_dim=dphi, degree=F, io_dtype=hla.HLA_BF16, max_heads=Hmax,
+                max_tokens=N, max_seqs=1)
+    assert h.active_path == hla.HLA_PATH_MFMA
     phid = [{k: v.to(dev) for k, v in m.items()} for m in phi]
     h.set_phi_weights(phid, per_head=True)
     wg = [{"d" + k: torch.full(v.shape, 7.0, dtype=torch.float32, device=dev) for k, v in m.items()}
@@ -129,10 +133,10 @@ def test_fewer_heads_than_the_handle_allows_and_empty_input():
     torch.cuda.synchronize()
     # heads the call did not cover keep what the arrays held; the others match the oracle
     torch.cuda.synchronize()
-    feats = h.read_workspace(hla.binding.HLA_WS_FEATURES, 1 * H * N * 24).reshape(1, H, N, 24)
-    ref = pu.run_oracle_per_head(t, 3, 6, 1e-6, [{k: v[:H] for k, v in m.items()} for m in phi],
+    feats = h.read_workspace(hla.binding.HLA_WS_FEATURES, 1 * H * N * nfeat).reshape(1, H, N, nfeat)
+    ref = pu.run_oracle_per_head(t, F, dphi, 1e-6, [{k: v[:H] for k, v in m.items()} for m in phi],
                                  relu_open=feats > 0)
-    for m in range(4):
+    for m in range(nmaps):
         for k in pu.WG_KEYS:
             assert bool((wg[m][k][H:] == 7.0).all()), (m, k)
     pu.assert_weight_grad_parity([{k: v[:H].cpu() for k, v in m.items()} for m in wg], ref["wg"], 2e-2,
@@ -144,7 +148,7 @@ def test_fewer_heads_than_the_handle_allows_and_empty_input():
     h.forward(e["Q"], e["K"], e["V"], Oe)
     h.backward(e["Q"], e["K"], e["V"], Oe, e["dO"], *ge)
     torch.cuda.synchronize()
-    for m in range(4):
+    for m in range(nmaps):
         for k in pu.WG_KEYS:
             assert bool((wg[m][k][:H] == 0.0).all()) and bool((wg[m][k][H:] == 7.0).all()), (m, k)
     # switching to shared weights drops the per-head registration: nothing is written any more
