@@ -32,18 +32,19 @@ CASES = [
 ]
 
 
+@pytest.mark.parametrize("F,dphi", [(3, 6), (2, 12)])
 @pytest.mark.parametrize("d,B,H,N,lens", CASES)
-def test_shape_sweep_bf16(d, B, H, N, lens):
+def test_shape_sweep_bf16(d, B, H, N, lens, F, dphi):
     cu = None if lens is None else _cu(lens)
     n_tok = N if lens is None else cu[-1]
-    seed = 1000 + 7 * d + 13 * B + 17 * H + n_tok
-    t, phi = wl.make_raw_inputs(seed, B, H, n_tok, d, 3, 6, torch.bfloat16)
-    gpu = pu.run_gpu(t, 3, 6, 1e-6, phi=phi, cu_seqlens=cu, path=hla.HLA_PATH_MFMA, weight_grads=True)
+    seed = 1000 + 7 * d + 13 * B + 17 * H + n_tok + F
+    t, phi = wl.make_raw_inputs(seed, B, H, n_tok, d, F, dphi, torch.bfloat16)
+    gpu = pu.run_gpu(t, F, dphi, 1e-6, phi=phi, cu_seqlens=cu, path=hla.HLA_PATH_MFMA, weight_grads=True)
     assert gpu["_path"] == hla.HLA_PATH_MFMA
     # both sides differentiate the ReLU branches the library took (decided in its precision)
-    ref = pu.run_oracle(t, 3, 6, 1e-6, phi=phi, cu_seqlens=cu, weight_grads=True,
+    ref = pu.run_oracle(t, F, dphi, 1e-6, phi=phi, cu_seqlens=cu, weight_grads=True,
                         relu_open=gpu["relu_open"])
-    what = f"sweep d={d} B={B} H={H} " + (f"N={N}" if lens is None else f"lens={lens}")
+    what = f"sweep F={F} d={d} B={B} H={H} " + (f"N={N}" if lens is None else f"lens={lens}")
     # sequences of one or two tokens have outputs that barely depend on Q and K: their dQ, dK are
     # rounding noise around (nearly) zero references, so those two are compared on an absolute
     # scale set by the other gradients' magnitude instead
