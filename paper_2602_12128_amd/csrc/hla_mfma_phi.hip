@@ -578,6 +578,13 @@ __device__ __forceinline__ void phi_bwd_body(const Geom& g, const View& X,
     }
     return z;
   };
+  // du of the coming tile's first map: loaded during the last map of the tile before, like the
+  // later maps' du is loaded a map ahead (with more than eight features the extra live values make
+  // the kernel spill: there it is loaded at the tile's start)
+  constexpr bool kDuAhead = DPH <= 8;
+  u32x4 dub_first;
+  if (kDuAhead && tile < tm.total)
+    dub_first = load_du(g.th(b, h, n0 + r < g.N ? n0 + r : 0), n0 + r < g.N, 0);
   for (; tile < tm.total; tile += stride) {
     const int n = n0 + r;
     const bool live = n < g.N;
@@ -585,6 +592,8 @@ __device__ __forceinline__ void phi_bwd_body(const Geom& g, const View& X,
     const int ob = b, oh = h, on0 = n0;  // this tile's coordinates
     const bool more_tiles = tile + stride < tm.total;
     if (more_tiles) tm.decode(tile + stride, b, h, n0);  // b, h, n0 now name the next tile
+    const bool live_next = more_tiles && n0 + r < g.N;
+    const int64_t th_next = g.th(b, h, live_next ? n0 + r : 0);
     f32x16 dx[NRB];  // first written by the second stage of the first map (accumulating onto zero)
     // Software pipeline over 32-row blocks of the hidden layer, block t = m * NRB + rb.  Stage t:
     //   vector ALU : dh(t) = dg(t) * GELU'(hidden(t) + b1), packed as the B operand of dx
@@ -607,7 +616,7 @@ __device__ __forceinline__ void phi_bwd_body(const Geom& g, const View& X,
       for (int t = 0; t < kPer; ++t)
         an[t] = *reinterpret_cast<const u32x4*>(smem + (1 % NRB) * 32 * SM::kRow + a_off[t]);
     }
-    u32x4 dub = load_du(th, live, 0);
+    u32x4 dub = kDuAhead ? dub_first : load_du(th, live, 0);
     u32x4 dhp[2];  // dh of the previous block (two 16-slot steps)
     // The first map is peeled off the loop over maps: its first stage has no previous block (no dx
     // step at all) and its second stage starts the dx accumulators from the constant zero, which
@@ -616,7 +625,8 @@ __device__ __forceinline__ void phi_bwd_body(const Geom& g, const View& X,
       constexpr bool FIRST = decltype(first_tag)::value;
       const unsigned char* wm = smem + m * SM::kMap;
       const bool last_map = m + 1 == nmaps;
-      const u32x4 dubn = load_du(th, live, last_map ? m : m + 1);
+      const u32x4 dubn = last_map ? (kDuAhead ? load_du(th_next, live_next, 0) : dub)
+                                  : load_du(th, live, m + 1);
 #pragma unroll
       for (int rb = 0; rb < NRB; ++rb) {
         // block t+1 (first layer, this stage) and block t+2 (whose first operands the last slice reads)
@@ -692,11 +702,12 @@ __device__ __forceinline__ void phi_bwd_body(const Geom& g, const View& X,
         dhp[1] = dhc[1];
         cur = nxt;
       }
-      dub = dubn;
+      dub = dubn;  // after the last map: the coming tile's
     };
     run_map(0, TrueTag{});
 #pragma unroll 1
     for (int m = 1; m < nmaps; ++m) run_map(m, FalseTag{});  // nmaps == NMAPS, passed at run time so this stays a loop
+    dub_first = dub;
     // dx of the last block
     {
       const unsigned char* wp = smem + (nmaps - 1) * SM::kMap;
