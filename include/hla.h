@@ -169,7 +169,9 @@ int32_t hla_active_path(const hla_handle* h);
 /* Intermediate results of the last forward / backward, for tests of the individual steps:
  *   HLA_WS_FEATURES      [B*H*N][(1+F)*d_phi] fp32: phi_q, then phi_k1..phi_kF of every token-head
  *                        (Alg. 1 Step 4), row index (b*H + h)*N + n
- *   HLA_WS_FEATURE_GRADS same layout: gradient w.r.t. those features (after hla_backward)
+ *   HLA_WS_FEATURE_GRADS same layout: gradient w.r.t. those features (after hla_backward).  With
+ *                        HLA_PHI_MLP on the MFMA path it is the gradient at the input of the
+ *                        maps' final ReLU: entries whose feature is zero hold zero
  *   HLA_WS_DENOMINATORS  [B*H*N] fp32: eta + eps (Sec. 4.2 normaliser)
  * Copies `count` floats to the HOST buffer `host_dst` after synchronising `hip_stream`.  count
  * above what the last call produced is HLA_ERR_INVALID_ARG. */

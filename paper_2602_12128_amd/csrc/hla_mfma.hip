@@ -465,7 +465,7 @@ template <class SY, int D>
 __global__ __launch_bounds__(kThreads) void k_bwd_query(
     Geom g, const BlockEnt* __restrict__ chunks, const float* __restrict__ feat,
     const float* __restrict__ den, const unsigned char* __restrict__ ops, View dO,
-    float* __restrict__ dfeat, float* __restrict__ partial, int64_t partial_stride) {
+    float* __restrict__ dfeat, float* __restrict__ partial, int64_t partial_stride, int relu_mask) {
   using SL = StateLayout<SY, D>;
   using SM = BwdQSmem<D, SY::MP>;
   constexpr int SP = SY::SP, MP = SY::MP, DP = SY::DPHI;
@@ -647,7 +647,12 @@ __global__ __launch_bounds__(kThreads) void k_bwd_query(
     if (live && gl == 0) {
       float* df = dfeat + g.fidx(th, 0);
 #pragma unroll
-      for (int c = 0; c < DP; ++c) df[32 * c] = dq[c] + other[DP - 1 - c];
+      for (int c = 0; c < DP; ++c) {
+        // relu_mask: the features came out of a ReLU, and what the feature-map backward needs is
+        // the gradient of its input: zero where the feature is zero
+        const float v = dq[c] + other[DP - 1 - c];
+        df[32 * c] = (!relu_mask || fb[c] > 0.0f) ? v : 0.0f;
+      }
     }
     wave_lds_sync();
     // dCsym[(g,s) rows x D] += (inv Qm)^T[MP x 32 tokens] dO[32 tokens x D]
@@ -711,7 +716,8 @@ template <class SY, int D>
 __global__ __launch_bounds__(kThreads) void k_bwd_key(Geom g, const BlockEnt* __restrict__ blocks,
                                                       const float* __restrict__ feat,
                                                       const unsigned char* __restrict__ dops, View V,
-                                                      float* __restrict__ dfeat, View dV) {
+                                                      float* __restrict__ dfeat, View dV,
+                                                      int relu_mask) {
   using SL = StateLayout<SY, D>;
   constexpr int SP = SY::SP, MP = SY::MP, DP = SY::DPHI, F = SY::F;
   constexpr int NRB = D / 32, NKS = MP / 16, NKD = D / 16, NRM = MP / 32;
@@ -895,7 +901,10 @@ __global__ __launch_bounds__(kThreads) void k_bwd_key(Geom g, const BlockEnt* __
 #pragma unroll
       for (int f = 0; f < F; ++f)
 #pragma unroll
-        for (int c = 0; c < DP; ++c) pend_df[f * DP + c] = dk[f][c] + other[f][DP - 1 - c];
+        for (int c = 0; c < DP; ++c) {
+          const float v = dk[f][c] + other[f][DP - 1 - c];
+          pend_df[f * DP + c] = (!relu_mask || kb[f * DP + c] > 0.0f) ? v : 0.0f;  // see k_bwd_query
+        }
     }
     {
       wave_lds_sync();  // the flush above has read the whole staged tile
@@ -971,14 +980,15 @@ hla_status backward_core(hla_handle* hd, const hla_call_args& a) {
   }
   unsigned char* ops = static_cast<unsigned char*>(hd->path_ws);
   unsigned char* dops = ops + SL::kOpBytes * hd->max_units;
+  const int relu_mask = hd->cfg.phi_mode == HLA_PHI_MLP ? 1 : 0;
   HLA_TRY(launch(hd, "mfma_bwd_query", k_bwd_query<SY, D>, dim3(chunks->count, g.H), dim3(kThreads),
                  SQ::kTotal, s, g, chunks->dev, hd->feat, hd->den, ops, a.dO, hd->dfeat,
-                 hd->partial, SL::kF32));
+                 hd->partial, SL::kF32, relu_mask));
   HLA_TRY(launch(hd, "mfma_dstate_reduce", k_reduce<SY, D, true>, dim3(a.num_seqs, g.H, kReduceSlices),
                  dim3(256), 0, s, g, chunks->seq_off_dev, hd->partial, SL::kF32, dops,
                  make_slot_map<SY>()));
   HLA_TRY(launch(hd, "mfma_bwd_key", k_bwd_key<SY, D>, dim3(chunks->count, g.H), dim3(kThreads),
-                 0, s, g, chunks->dev, hd->feat, dops, a.V, hd->dfeat, a.dV));
+                 0, s, g, chunks->dev, hd->feat, dops, a.V, hd->dfeat, a.dV, relu_mask));
   return HLA_OK;
 }
 

@@ -475,11 +475,12 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_fwd(Geom g, View Q, View K,
 
 // ---- backward -----------------------------------------------------------------------------------
 // block WAVES*64.  dX = sum over the NMAPS maps of W1 (GELU'(h) * (W2 du)), with du = d(feature)
-// where the ReLU was open.  Hidden activations are recomputed.
+// where the ReLU was open (the form in which the feature-gradient workspace arrives).  Hidden
+// activations are recomputed.
 template <int D, int NMAPS, int WAVES, int DPH>
 __device__ __forceinline__ void phi_bwd_body(const Geom& g, const View& X,
                                              const unsigned char* __restrict__ wpk, int heads_w,
-                                             int map0, int nmaps, const float* __restrict__ feat,
+                                             int map0, int nmaps,
                                              const float* __restrict__ dfeat, const View& dX) {
   using SM = PhiSmem<D, true>;
   constexpr int NRB = D / 32, NKS = D / 16;
@@ -520,42 +521,29 @@ __device__ __forceinline__ void phi_bwd_body(const Geom& g, const View& X,
     load_x<D>(X, b, h, n0 + r, g.N, gl, xb);
   }
   // du^T of one map as B operand of a single 16-slot step: slot (gl, j) is feature 8gl + j (with
-  // d_phi <= 8 only gl = 0 is used); zero where the ReLU was closed
-  auto load_du = [&](int64_t th, bool live, int m) -> u32x4 {
+  // d_phi <= 8 only gl = 0 is used).  The feature gradients arrive already zeroed where the ReLU
+  // was closed (the core backward kernels, which hold the features anyway, write them that way), so
+  // this is a plain load.  In two halves: issue_du puts the loads in flight (unconditional, from
+  // addresses valid for every lane), finish_du packs them a whole map later.  Anything that looks
+  // at the loaded values next to the loads makes the wave sit out the memory round trip there.
+  static_assert(DPH % 2 == 0 && DPH <= 16, "features are packed in pairs into one k-step");
+  constexpr int NJ = DPH <= 8 ? DPH : 8;  // features per lane half
+  auto issue_du = [&](int64_t th, int m, float (&dv)[NJ]) {
+    // lane half 1 holds the features from the ninth on (none when d_phi <= 8: it re-reads half 0's);
+    // surplus slots re-read the half's first feature
+    const int first = DPH <= 8 ? 0 : 8 * gl;
+    const int have = DPH <= 8 ? DPH : (gl ? DPH - 8 : 8);
+    const int64_t o = g.fidx(th, (map0 + m) * DPH + first);
+#pragma unroll
+    for (int a = 0; a < NJ; ++a) dv[a] = dfeat[o + 32 * (a < have ? a : 0)];
+  };
+  auto finish_du = [&](const float (&dv)[NJ], bool live) -> u32x4 {
+    const int have = DPH <= 8 ? (gl ? 0 : DPH) : (gl ? DPH - 8 : 8);
     u32x4 d;
     d[0] = d[1] = d[2] = d[3] = 0u;
-    static_assert(DPH % 2 == 0 && DPH <= 16, "features are packed in pairs into one k-step");
-    if constexpr (DPH <= 8) {
-      if (live && gl == 0) {
-        const int64_t o = g.fidx(th, (map0 + m) * DPH);
-        float fv[DPH], dv[DPH];  // both loaded unconditionally: one round trip, not one per feature
 #pragma unroll
-        for (int a = 0; a < DPH; ++a) {
-          fv[a] = feat[o + 32 * a];
-          dv[a] = dfeat[o + 32 * a];
-        }
-#pragma unroll
-        for (int p = 0; p < DPH / 2; ++p)
-          d[p] = pack_bf16(fv[2 * p] > 0.0f ? dv[2 * p] : 0.0f, fv[2 * p + 1] > 0.0f ? dv[2 * p + 1] : 0.0f);
-      }
-    } else {
-      if (live) {
-        // lane half 1 holds the DPH - 8 features from the ninth on; its surplus slots re-read the
-        // half's first feature and stay zero
-        const int64_t o = g.fidx(th, (map0 + m) * DPH + 8 * gl);
-        const int have = gl ? DPH - 8 : 8;
-        float fv[8], dv[8];
-#pragma unroll
-        for (int a = 0; a < 8; ++a) {
-          fv[a] = feat[o + 32 * (a < have ? a : 0)];
-          dv[a] = dfeat[o + 32 * (a < have ? a : 0)];
-        }
-#pragma unroll
-        for (int p = 0; p < 4; ++p)
-          d[p] = pack_bf16(2 * p < have && fv[2 * p] > 0.0f ? dv[2 * p] : 0.0f,
-                           2 * p + 1 < have && fv[2 * p + 1] > 0.0f ? dv[2 * p + 1] : 0.0f);
-      }
-    }
+    for (int p = 0; p < NJ / 2; ++p)
+      d[p] = pack_bf16(live && 2 * p < have ? dv[2 * p] : 0.0f, live && 2 * p + 1 < have ? dv[2 * p + 1] : 0.0f);
     return d;
   };
   auto zero_acc = []() {  // a constant: becomes the inline 0 of the MFMA's C operand
@@ -579,12 +567,13 @@ __device__ __forceinline__ void phi_bwd_body(const Geom& g, const View& X,
     return z;
   };
   // du of the coming tile's first map: loaded during the last map of the tile before, like the
-  // later maps' du is loaded a map ahead (with more than eight features the extra live values make
-  // the kernel spill: there it is loaded at the tile's start)
-  constexpr bool kDuAhead = DPH <= 8;
+  // later maps' du is loaded a map ahead
   u32x4 dub_first;
-  if (kDuAhead && tile < tm.total)
-    dub_first = load_du(g.th(b, h, n0 + r < g.N ? n0 + r : 0), n0 + r < g.N, 0);
+  if (tile < tm.total) {
+    float dv0[NJ];
+    issue_du(g.th(b, h, n0 + r < g.N ? n0 + r : 0), 0, dv0);
+    dub_first = finish_du(dv0, n0 + r < g.N);
+  }
   for (; tile < tm.total; tile += stride) {
     const int n = n0 + r;
     const bool live = n < g.N;
@@ -616,17 +605,17 @@ __device__ __forceinline__ void phi_bwd_body(const Geom& g, const View& X,
       for (int t = 0; t < kPer; ++t)
         an[t] = *reinterpret_cast<const u32x4*>(smem + (1 % NRB) * 32 * SM::kRow + a_off[t]);
     }
-    u32x4 dub = kDuAhead ? dub_first : load_du(th, live, 0);
+    u32x4 dub = dub_first;
     u32x4 dhp[2];  // dh of the previous block (two 16-slot steps)
     // The first map is peeled off the loop over maps: its first stage has no previous block (no dx
     // step at all) and its second stage starts the dx accumulators from the constant zero, which
     // spares clearing them and carrying them into the loop as copies.
-    auto run_map = [&](int m, auto first_tag) {
+    auto run_map = [&](int m, auto first_tag, int64_t th_nx, bool live_nx) {
       constexpr bool FIRST = decltype(first_tag)::value;
       const unsigned char* wm = smem + m * SM::kMap;
       const bool last_map = m + 1 == nmaps;
-      const u32x4 dubn = last_map ? (kDuAhead ? load_du(th_next, live_next, 0) : dub)
-                                  : load_du(th, live, m + 1);
+      float dvn[NJ];  // the next map's du, or the coming tile's first
+      issue_du(last_map ? th_nx : th, last_map ? 0 : m + 1, dvn);
 #pragma unroll
       for (int rb = 0; rb < NRB; ++rb) {
         // block t+1 (first layer, this stage) and block t+2 (whose first operands the last slice reads)
@@ -702,11 +691,11 @@ __device__ __forceinline__ void phi_bwd_body(const Geom& g, const View& X,
         dhp[1] = dhc[1];
         cur = nxt;
       }
-      dub = dubn;  // after the last map: the coming tile's
+      dub = finish_du(dvn, last_map ? live_nx : live);  // after the last map: the coming tile's
     };
-    run_map(0, TrueTag{});
+    run_map(0, TrueTag{}, th_next, live_next);
 #pragma unroll 1
-    for (int m = 1; m < nmaps; ++m) run_map(m, FalseTag{});  // nmaps == NMAPS, passed at run time so this stays a loop
+    for (int m = 1; m < nmaps; ++m) run_map(m, FalseTag{}, th_next, live_next);  // nmaps == NMAPS, passed at run time so this stays a loop
     dub_first = dub;
     // dx of the last block
     {
@@ -737,12 +726,11 @@ template <int D, int F, int WAVES, int DPH>
 __global__ __launch_bounds__(WAVES * 64) void k_phi_bwd(Geom g, View Q, View K,
                                                         const unsigned char* __restrict__ wpk,
                                                         int heads_w, int nk,
-                                                        const float* __restrict__ feat,
                                                         const float* __restrict__ dfeat, View dQ,
                                                         View dK) {
-  phi_bwd_body<D, 1, WAVES, DPH>(g, Q, wpk, heads_w, 0, 1, feat, dfeat, dQ);
+  phi_bwd_body<D, 1, WAVES, DPH>(g, Q, wpk, heads_w, 0, 1, dfeat, dQ);
   __syncthreads();  // every wave is done with the query map's weights and its transpose tile
-  phi_bwd_body<D, F, WAVES, DPH>(g, K, wpk, heads_w, 1, nk, feat, dfeat, dK);
+  phi_bwd_body<D, F, WAVES, DPH>(g, K, wpk, heads_w, 1, nk, dfeat, dK);
 }
 
 // ---- weight gradients ---------------------------------------------------------------------------
@@ -1114,8 +1102,8 @@ hla_status backward_t(hla_handle* hd, const hla_call_args& a) {
   }
   const dim3 grid = phi_grid(hd, kWavesB);
   HLA_TRY(launch(hd, "mfma_phi_backward", k_phi_bwd<D, F, kWavesB, DPH>, grid, dim3(kWavesB * 64),
-                 SM::total(F, kWavesB), a.stream, g, a.Q, a.K, wpk, hd->phi.heads_w, F, hd->feat,
-                 hd->dfeat, a.dQ, a.dK));
+                 SM::total(F, kWavesB), a.stream, g, a.Q, a.K, wpk, hd->phi.heads_w, F, hd->dfeat,
+                 a.dQ, a.dK));
   return HLA_OK;
 }
 
