@@ -792,7 +792,7 @@ __global__ __launch_bounds__(kThreads) void k_bwd_key(Geom g, const BlockEnt* __
     const int row = i * RPI + lane / PIECES, piece = lane % PIECES;
     const u32x4 v = *reinterpret_cast<const u32x4*>(tile + row * RowTile<D, 32>::kStride + piece * 16);
     if (pend_n0 >= 0 && pend_n0 + row < e.t1)
-      *reinterpret_cast<u32x4*>(dV.row<bf16_t>(e.b, h, pend_n0 + row) + piece * 8) = v;
+      __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(dV.row<bf16_t>(e.b, h, pend_n0 + row) + piece * 8));
   };
   // feature gradients a0 .. a1-1 of the staged tile
   auto flush_df = [&](int a0, int a1) {

@@ -224,7 +224,9 @@ __device__ __forceinline__ void flush_rows(int pass, int lane, const unsigned ch
     const int row = i * RPI + lane / PIECES, piece = lane % PIECES;
     const u32x4 v = *reinterpret_cast<const u32x4*>(lds + row * RT::kStride + piece * 16);
     bf16_t* dst = row_ptr(pass * ROWS + row);
-    if (dst != nullptr) *reinterpret_cast<u32x4*>(dst + piece * 8) = v;
+    // nontemporal: the outputs are not read again by the library; stored plainly they push the
+    // inputs of the following kernels out of the caches
+    if (dst != nullptr) __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(dst + piece * 8));
   }
   wave_lds_sync();
 }
