@@ -26,8 +26,8 @@ if ROOT not in sys.path:
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=3, help="workload configuration 2..5 (default 3: the headline one); 6 = 12600-token resolution, 7 = two-factor variant")
     ap.add_argument("--features", action="store_true",
                     help="feature-level interface (Q,K already phi-mapped): times the core alone")
