@@ -89,10 +89,33 @@ def run_gpu(tensors: Dict[str, torch.Tensor], F: int, d_phi: int, eps: float,
     return res
 
 
+RELU_BAND = 1e-2  # |pre-activation| below this: the library may decide the ReLU either way
+
+
+def assert_relu_decisions_valid(tensors, phi, F, relu_open, band=RELU_BAND):
+    """The ReLU decisions read back from the library (feature > 0) are only handed to the oracle
+    after the oracle has confirmed them: wherever its own fp64 pre-activation is further than
+    `band` from zero (the rounding error of the library's bf16/fp16 feature maps) the decision
+    must be the oracle's own; inside the band either branch is a valid one."""
+    ophi = oracle_phi(phi)
+    Q, K = to_np(tensors["Q"]), to_np(tensors["K"])
+    u = [orc.phi_forward(Q, *ophi[0].astuple())[2]]
+    u += [orc.phi_forward(K, *ophi[1 + f].astuple())[2] for f in range(F)]
+    u = np.concatenate(u, axis=-1)
+    relu_open = np.asarray(relu_open)
+    assert relu_open.shape == u.shape, (relu_open.shape, u.shape)
+    clear = np.abs(u) > band
+    wrong = clear & (relu_open != (u > 0))
+    assert not wrong.any(), f"{int(wrong.sum())} ReLU decisions differ from the oracle's outside the band"
+    assert clear.mean() > 0.9, "the band covers too many pre-activations to mean anything"
+
+
 def run_oracle(tensors, F, d_phi, eps, phi=None, cu_seqlens=None, backward=True,
                route="factorized", weight_grads=False, relu_open=None):
     Q, K, V = (to_np(tensors[k]) for k in ("Q", "K", "V"))
     ophi = oracle_phi(phi)
+    if relu_open is not None and phi is not None:
+        assert_relu_decisions_valid(tensors, phi, F, relu_open)
     out = {"O": orc.hla_operator_forward(Q, K, V, F, d_phi, eps, phi=ophi, cu_seqlens=cu_seqlens,
                                          route=route)}
     if backward:
