@@ -72,10 +72,12 @@ struct Geom {
     return (static_cast<int64_t>(b) * H + h) * N + n;
   }
   // Index of feature a of token-head th in the feature / feature-gradient workspace.  Plain:
-  // [th][nfeat].  Tiled (matrix-core path): [th / 32][nfeat][32], so that the 32 lanes that hold
-  // one feature of 32 consecutive token-heads read and write one contiguous 128-byte run.
+  // [th][nfeat].  Tiled (matrix-core path, nfeat even): [th / 32][nfeat / 2][32][2], so that the 32
+  // lanes that hold one PAIR of features (2p, 2p + 1) of 32 consecutive token-heads read and write
+  // one contiguous 256-byte run with one 8-byte access each.
   __host__ __device__ __forceinline__ int64_t fidx(int64_t th, int a) const {
-    return feat_tiled ? (th >> 5) * (static_cast<int64_t>(nfeat) * 32) + a * 32 + (th & 31) : th * nfeat + a;
+    return feat_tiled ? (th >> 5) * (static_cast<int64_t>(nfeat) * 32) + (a >> 1) * 64 + ((th & 31) << 1) + (a & 1)
+                      : th * nfeat + a;
   }
 };
 

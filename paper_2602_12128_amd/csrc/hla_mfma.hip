@@ -168,9 +168,14 @@ __global__ __launch_bounds__(kThreads) void k_state(Geom g, const BlockEnt* __re
     fetch_tile<D, 64>(V, e.b, h, n0, e.t1, lane, vt);
     const int n = n0 + lane;
     if (n < e.t1) {
-      const float* f = feat + g.fidx(g.th(e.b, h, n), DP);
+      // pair p of the tile's 32 tokens is one 256-byte run: an 8-byte load per lane and pair
+      const f32x2* f = reinterpret_cast<const f32x2*>(feat + g.fidx(g.th(e.b, h, n), DP));
 #pragma unroll
-      for (int a = 0; a < F * DP; ++a) kf[a] = f[32 * a];
+      for (int p = 0; p < F * DP / 2; ++p) {
+        const f32x2 v = f[32 * p];
+        kf[2 * p] = v[0];
+        kf[2 * p + 1] = v[1];
+      }
     } else {
 #pragma unroll
       for (int a = 0; a < F * DP; ++a) kf[a] = 0.0f;
@@ -391,9 +396,13 @@ __global__ __launch_bounds__(kThreads) void k_query(Geom g, const BlockEnt* __re
   float qn[DP];
   auto fetch = [&](int n0) {
     const int n = n0 + r < e.t1 ? n0 + r : e.t1 - 1;
-    const float* f = feat + g.fidx(g.th(e.b, h, n), 0);
+    const f32x2* f = reinterpret_cast<const f32x2*>(feat + g.fidx(g.th(e.b, h, n), 0));
 #pragma unroll
-    for (int c = 0; c < DP; ++c) qn[c] = f[32 * (gl ? DP - 1 - c : c)];
+    for (int p = 0; p < DP / 2; ++p) {  // lane half 1 takes the pairs, and each pair, in reverse
+      const f32x2 v = f[32 * (gl ? DP / 2 - 1 - p : p)];
+      qn[2 * p] = gl ? v[1] : v[0];
+      qn[2 * p + 1] = gl ? v[0] : v[1];
+    }
   };
   if (e.t0 + wave * 32 < e.t1) fetch(e.t0 + wave * 32);
   for (int n0 = e.t0 + wave * 32; n0 < e.t1; n0 += kWaves * 32) {
@@ -562,9 +571,13 @@ __global__ __launch_bounds__(kThreads) void k_bwd_query(
 #pragma unroll
       for (int ks = 0; ks < NKD; ++ks) x[ks] = *reinterpret_cast<const u32x4*>(row + 16 * ks + 8 * gl);
       const int64_t th = g.th(e.b, h, n);
-      const float* fp = feat + g.fidx(th, 0);
+      const f32x2* fp = reinterpret_cast<const f32x2*>(feat + g.fidx(th, 0));
 #pragma unroll
-      for (int a = 0; a < DP; ++a) f[a] = fp[32 * a];
+      for (int p = 0; p < DP / 2; ++p) {
+        const f32x2 v = fp[32 * p];
+        f[2 * p] = v[0];
+        f[2 * p + 1] = v[1];
+      }
       dn = den[th];
     } else {
 #pragma unroll
@@ -645,13 +658,15 @@ __global__ __launch_bounds__(kThreads) void k_bwd_query(
 #pragma unroll
     for (int c = 0; c < DP; ++c) other[c] = partner32(dq[c]);
     if (live && gl == 0) {
-      float* df = dfeat + g.fidx(th, 0);
+      // relu_mask: the features came out of a ReLU, and what the feature-map backward needs is
+      // the gradient of its input: zero where the feature is zero
+      f32x2* df = reinterpret_cast<f32x2*>(dfeat + g.fidx(th, 0));
 #pragma unroll
-      for (int c = 0; c < DP; ++c) {
-        // relu_mask: the features came out of a ReLU, and what the feature-map backward needs is
-        // the gradient of its input: zero where the feature is zero
-        const float v = dq[c] + other[DP - 1 - c];
-        df[32 * c] = (!relu_mask || fb[c] > 0.0f) ? v : 0.0f;
+      for (int c = 0; c < DP; c += 2) {
+        f32x2 v;
+        v[0] = (!relu_mask || fb[c] > 0.0f) ? dq[c] + other[DP - 1 - c] : 0.0f;
+        v[1] = (!relu_mask || fb[c + 1] > 0.0f) ? dq[c + 1] + other[DP - 2 - c] : 0.0f;
+        df[32 * (c / 2)] = v;
       }
     }
     wave_lds_sync();
@@ -770,18 +785,22 @@ __global__ __launch_bounds__(kThreads) void k_bwd_key(Geom g, const BlockEnt* __
   stagger_start(wave, blockIdx.x, HLA_STAGGER_CORE);
   int n0 = e.t0 + wave * 32;
   const bf16_t* nrow = nullptr;   // the coming tile's V row and feature address of this lane
-  const float* nfeat = nullptr;
+  const f32x2* nfeat = nullptr;  // feature pairs
   auto next_addr = [&](int t0) {
     const int n = t0 + r < e.t1 ? t0 + r : e.t1 - 1;
     nrow = V.row<const bf16_t>(e.b, h, n);
-    nfeat = feat + g.fidx(g.th(e.b, h, n), DP);
+    nfeat = reinterpret_cast<const f32x2*>(feat + g.fidx(g.th(e.b, h, n), DP));
   };
   if (n0 < e.t1) {
     next_addr(n0);
 #pragma unroll
     for (int ks = 0; ks < NKD; ++ks) vn[ks] = *reinterpret_cast<const u32x4*>(nrow + 16 * ks + 8 * gl);
 #pragma unroll
-    for (int a = 0; a < NF; ++a) kn[a] = nfeat[32 * a];
+    for (int p = 0; p < NF / 2; ++p) {
+      const f32x2 v = nfeat[32 * p];
+      kn[2 * p] = v[0];
+      kn[2 * p + 1] = v[1];
+    }
   }
   int pend_n0 = -1;            // first token of the tile staged in LDS, -1: none
   float pend_df[NF];           // its feature gradients (this lane's token)
@@ -794,13 +813,18 @@ __global__ __launch_bounds__(kThreads) void k_bwd_key(Geom g, const BlockEnt* __
     if (pend_n0 >= 0 && pend_n0 + row < e.t1)
       __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(dV.row<bf16_t>(e.b, h, pend_n0 + row) + piece * 8));
   };
-  // feature gradients a0 .. a1-1 of the staged tile
+  // feature-gradient pairs a0 .. a1-1 of the staged tile
   auto flush_df = [&](int a0, int a1) {
     if (pend_n0 >= 0 && pend_n0 + r < e.t1 && gl == 0) {
-      float* df = dfeat + g.fidx(g.th(e.b, h, pend_n0 + r), DP);
+      f32x2* df = reinterpret_cast<f32x2*>(dfeat + g.fidx(g.th(e.b, h, pend_n0 + r), DP));
 #pragma unroll
-      for (int a = 0; a < NF; ++a)
-        if (a >= a0 && a < a1) df[32 * a] = pend_df[a];
+      for (int p = 0; p < NF / 2; ++p)
+        if (p >= a0 && p < a1) {
+          f32x2 v;
+          v[0] = pend_df[2 * p];
+          v[1] = pend_df[2 * p + 1];
+          df[32 * p] = v;
+        }
     }
   };
   for (; n0 < e.t1; n0 += kWaves * 32) {
@@ -859,12 +883,16 @@ __global__ __launch_bounds__(kThreads) void k_bwd_key(Geom g, const BlockEnt* __
 #pragma unroll
       for (int rb = 0; rb < NRB; ++rb) {
         acc[rb] = mfma32(opA[(rb * NKS + ks) * 64], b, acc[rb]);
-        // the coming tile's features, a few per MFMA
-        constexpr int kPerM = (NF + NKS * NRB - 1) / (NKS * NRB);
+        // the coming tile's feature pairs, a few per MFMA
+        constexpr int kPerM = (NF / 2 + NKS * NRB - 1) / (NKS * NRB);
 #pragma unroll
         for (int t = 0; t < kPerM; ++t) {
-          const int a = (ks * NRB + rb) * kPerM + t;
-          if (a < NF) kn[a] = nfeat[32 * a];
+          const int p = (ks * NRB + rb) * kPerM + t;
+          if (p < NF / 2) {
+            const f32x2 v = nfeat[32 * p];
+            kn[2 * p] = v[0];
+            kn[2 * p + 1] = v[1];
+          }
         }
       }
       __builtin_amdgcn_sched_barrier(0);
@@ -888,7 +916,8 @@ __global__ __launch_bounds__(kThreads) void k_bwd_key(Geom g, const BlockEnt* __
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = qd * NST / 4; i < (qd + 1) * NST / 4; ++i) flush_piece(i);
-        flush_df(qd * (NF + 3) / 4, (qd + 1) * (NF + 3) / 4 < NF ? (qd + 1) * (NF + 3) / 4 : NF);
+        constexpr int NP = NF / 2;
+        flush_df(qd * ((NP + 3) / 4), (qd + 1) * ((NP + 3) / 4) < NP ? (qd + 1) * ((NP + 3) / 4) : NP);
         __builtin_amdgcn_sched_barrier(0);
       });
     }
@@ -917,7 +946,7 @@ __global__ __launch_bounds__(kThreads) void k_bwd_key(Geom g, const BlockEnt* __
   // the last tile's outputs
 #pragma unroll
   for (int i = 0; i < NST; ++i) flush_piece(i);
-  flush_df(0, NF);
+  flush_df(0, NF / 2);
 }
 
 inline int pick_chunk(const hla_handle* hd, const Geom& g, int num_seqs) {

@@ -343,15 +343,19 @@ __device__ __forceinline__ void phi_fwd_body(const Geom& g, const View& X,
 #pragma unroll
   for (int i = 0; i < NU; ++i) pend[i] = 0.0f;
   float* pend_ptr = nullptr;  // feature 4 gl of the token
-  auto flush = [&]() {  // feature a of 32 consecutive tokens is one contiguous 128-byte run
+  auto flush = [&]() {  // a pair of features of 32 consecutive tokens is one contiguous 256-byte run
     if (pend_ptr != nullptr) {
+      f32x2* pp = reinterpret_cast<f32x2*>(pend_ptr);
 #pragma unroll
-      for (int i = 0; i < NU; ++i) {
-        const int a0 = 8 * (i / 4) + i % 4;  // feature held by lane half 0; half 1 holds a0 + 4
+      for (int i = 0; i < NU; i += 2) {
+        const int a0 = 8 * (i / 4) + i % 4;  // even feature held by lane half 0; half 1 holds a0 + 4
+        f32x2 v;
+        v[0] = pend[i];
+        v[1] = pend[i + 1];
         if (a0 + 4 < DPH) {
-          pend_ptr[32 * a0] = pend[i];
+          pp[32 * (a0 / 2)] = v;
         } else if (a0 < DPH) {
-          if (gl == 0) pend_ptr[32 * a0] = pend[i];
+          if (gl == 0) pp[32 * (a0 / 2)] = v;
         }
       }
     }
@@ -533,9 +537,13 @@ __device__ __forceinline__ void phi_bwd_body(const Geom& g, const View& X,
     // surplus slots re-read the half's first feature
     const int first = DPH <= 8 ? 0 : 8 * gl;
     const int have = DPH <= 8 ? DPH : (gl ? DPH - 8 : 8);
-    const int64_t o = g.fidx(th, (map0 + m) * DPH + first);
+    const f32x2* dp = reinterpret_cast<const f32x2*>(dfeat + g.fidx(th, (map0 + m) * DPH + first));
 #pragma unroll
-    for (int a = 0; a < NJ; ++a) dv[a] = dfeat[o + 32 * (a < have ? a : 0)];
+    for (int p = 0; p < NJ / 2; ++p) {
+      const f32x2 v = dp[32 * (2 * p < have ? p : 0)];
+      dv[2 * p] = v[0];
+      dv[2 * p + 1] = v[1];
+    }
   };
   auto finish_du = [&](const float (&dv)[NJ], bool live) -> u32x4 {
     const int have = DPH <= 8 ? (gl ? 0 : DPH) : (gl ? DPH - 8 : 8);
@@ -829,10 +837,15 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_wgrad(Geom g, View Q, View K
   auto fetch_features = [&](int b, int h, int n0) {
     const int n = n0 + r;
     const int64_t o = g.fidx(g.th(b, h, n < g.N ? n : g.N - 1), m * DPH);
+    const f32x2* fp = reinterpret_cast<const f32x2*>(feat + o);
+    const f32x2* dp = reinterpret_cast<const f32x2*>(dfeat + o);
 #pragma unroll
-    for (int a = 0; a < DPH; ++a) {
-      fv[a] = feat[o + 32 * a];
-      dv[a] = dfeat[o + 32 * a];
+    for (int p = 0; p < DPH / 2; ++p) {
+      const f32x2 f2 = fp[32 * p], d2 = dp[32 * p];
+      fv[2 * p] = f2[0];
+      fv[2 * p + 1] = f2[1];
+      dv[2 * p] = d2[0];
+      dv[2 * p + 1] = d2[1];
     }
   };
   // Two sets of LDS tiles: while the vector ALU turns tile t's hidden block into dh and GELU(h)
