@@ -15,7 +15,8 @@ Pins (tests/test_oracle_*.py): brute force == factorized; F=1 == textbook linear
 d_phi=1, identical-key, one-hot and N=1 closed forms; row normalisation; convexity; permutation
 invariance; homogeneity (rational-function form); the sequential state update; Lemma 4.1; GELU
 against tabulated normal-CDF values; both backward routes, and the feature-map weight gradients,
-against central finite differences.  No function here is "parity unpinned".
+against central finite differences; the enumeration of ReLU branch choices against the masked
+(smooth) map.  No function here is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -63,9 +64,11 @@ def phi_backward(dfeat, x, W1, b1, W2, b2, relu_open=None):
     ReLU, the second linear layer, GELU and the first linear layer of App. A.1).
 
     The ReLU makes this gradient discontinuous where a pre-activation u crosses zero.  relu_open
-    (bool [N, d_phi]) replaces the oracle's own decision u > 0 by one taken elsewhere -- a parity
-    test passes the decisions of the implementation under test, taken in its precision, so that
-    both sides differentiate the same branch."""
+    (bool [N, d_phi]) replaces the decision u > 0 by a given branch choice: the map is then
+    differentiated as relu_open * u(x).  It exists for phi_backward_branches below, which
+    enumerates the choices an implementation in lower precision may legitimately take for
+    pre-activations that are zero to within its rounding error; the choices always come from this
+    oracle's own pre-activations, never from an implementation under test."""
     _, h, u = phi_forward(x, W1, b1, W2, b2)
     du = np.asarray(dfeat, F64) * ((u > 0.0) if relu_open is None else np.asarray(relu_open, bool))
     dg = du @ np.asarray(W2, F64).T
@@ -87,6 +90,61 @@ def phi_weight_grads(dfeat, x, W1, b1, W2, b2, relu_open=None):
     dg = du @ np.asarray(W2, F64).T
     dh = dg * gelu_erf_grad(h)
     return x.T @ dh, dh.sum(axis=0), g.T @ du, du.sum(axis=0)
+
+
+def phi_backward_branches(dfeats, x, maps, band: float, max_inband: int = 12):
+    """Every input-gradient row a correct implementation may produce for the rows of x whose ReLU
+    decisions are not settled at resolution `band` (App. A.1: the ReLU ends each map).
+
+    x [N, d] feeds len(maps) feature maps (maps[m] = (W1, b1, W2, b2)); dfeats[m] [N, d_phi] is
+    the loss gradient w.r.t. map m's features; the gradient w.r.t. x sums the maps (as dK sums
+    the key maps).  A feature (m, a) of row n is "in band" when |u_m[n, a]| < band.  For every
+    row with k >= 1 in-band features the result holds the 2^k gradient rows obtained by opening
+    or closing each of them, all other features following u > 0.  Candidate 0 closes all of them.
+    Returns {row: array [2^k, d]}.  More than max_inband in-band features in one row raise."""
+    x = np.asarray(x, F64)
+    us = [phi_forward(x, *m)[2] for m in maps]
+    inband = [np.abs(u) < band for u in us]
+    rows = np.nonzero(np.any(np.concatenate(inband, axis=1), axis=1))[0]
+    out = {}
+    for n in rows:
+        slots = [(m, a) for m in range(len(maps)) for a in np.nonzero(inband[m][n])[0]]
+        if len(slots) > max_inband:
+            raise ValueError(f"row {n}: {len(slots)} pre-activations within {band} of zero")
+        cands = np.zeros((1 << len(slots), x.shape[1]), F64)
+        for bits in range(1 << len(slots)):
+            opens = [(u[n] > 0.0) & ~ib[n] for u, ib in zip(us, inband)]
+            for i, (m, a) in enumerate(slots):
+                opens[m][a] = bool((bits >> i) & 1)
+            for m in range(len(maps)):
+                cands[bits] += phi_backward(np.asarray(dfeats[m], F64)[n:n + 1], x[n:n + 1], *maps[m],
+                                            relu_open=opens[m][None, :])[0]
+        out[int(n)] = cands
+    return out
+
+
+def phi_weight_grad_branches(dfeat, x, W1, b1, W2, b2, band: float):
+    """The weight gradients of one feature map as a function of the ReLU branch choices that are
+    not settled at resolution `band` (companion of phi_backward_branches; the gradients are sums
+    over all rows, so the choices of all rows enter every entry, linearly):
+        grads(choice) = base + sum over in-band pairs p of choice[p] * contrib[p],   choice[p] in {0, 1}
+    with base = phi_weight_grads taking every in-band feature as closed and the others by u > 0, and
+    contrib[p] = phi_weight_grads of the single pair p = (row n, feature a) taken as open.
+    Returns (base, pairs, contribs, own): base and each contribs[i] are (dW1, db1, dW2, db2);
+    pairs[i] = (n, a); own[i] = the oracle's own decision u[n, a] > 0."""
+    x = np.asarray(x, F64)
+    dfeat = np.asarray(dfeat, F64)
+    u = phi_forward(x, W1, b1, W2, b2)[2]
+    inband = np.abs(u) < band
+    base = phi_weight_grads(dfeat, x, W1, b1, W2, b2, relu_open=(u > 0.0) & ~inband)
+    pairs = [(int(n), int(a)) for n, a in zip(*np.nonzero(inband))]
+    contribs = []
+    for n, a in pairs:
+        one = np.zeros((1, u.shape[1]), bool)
+        one[0, a] = True
+        contribs.append(phi_weight_grads(dfeat[n:n + 1], x[n:n + 1], W1, b1, W2, b2, relu_open=one))
+    own = [bool(u[n, a] > 0.0) for n, a in pairs]
+    return base, pairs, contribs, own
 
 
 # --------------------------------------------------------------------------------------------
@@ -299,18 +357,20 @@ def hla_operator_backward(Q, K, V, dO, F: int, d_phi: int, eps: float,
                           phi: Optional[Sequence[PhiWeights]] = None,
                           cu_seqlens: Optional[Sequence[int]] = None,
                           route: str = "factorized", weight_grads: bool = False,
-                          relu_open=None):
+                          feature_grads: bool = False):
     """(dQ, dK, dV) with the shapes of Q, K, V for L = sum(O * dO).  With feature maps, dK sums
     the contributions of the F key maps (they all read the same K).  With weight_grads (needs
     `phi`) a fourth result lists (dW1, db1, dW2, db2) for phi_q, phi_k1..phi_kF, each summed over
-    every sequence, head and token that shares the map.  relu_open (bool [B,H,N,(1+F)*d_phi], map
-    by map along the last dim) hands every feature map the ReLU decisions to differentiate
-    through (see phi_backward); None = the oracle's own."""
+    every sequence, head and token that shares the map.  With feature_grads the last result is
+    the gradient w.r.t. the features themselves, (dqf [B,H,N,d_phi], dkf [B,H,N,F*d_phi]), the
+    intermediate that the feature maps' backward consumes."""
     B, H, N = V.shape[:3]
     dQ = np.zeros(Q.shape, F64)
     dK = np.zeros(K.shape, F64)
     dV = np.zeros(V.shape, F64)
     wg = None
+    dQf = np.zeros(Q.shape[:3] + (d_phi,), F64)
+    dKf = np.zeros(K.shape[:3] + (F * d_phi,), F64)
     if weight_grads:
         if phi is None:
             raise ValueError("weight gradients need the feature maps")
@@ -324,30 +384,30 @@ def hla_operator_backward(Q, K, V, dO, F: int, d_phi: int, eps: float,
             v = np.asarray(V[b, h, lo:hi], F64)
             dqf, dkfs, dv = bwd(qf, kfs, v, dO[b, h, lo:hi], eps)
             dV[b, h, lo:hi] = dv
+            dQf[b, h, lo:hi] = dqf
+            dKf[b, h, lo:hi] = np.concatenate(dkfs, axis=1)
             if phi is None:
                 dQ[b, h, lo:hi] = dqf
                 dK[b, h, lo:hi] = np.concatenate(dkfs, axis=1)
             else:
-                def ro(m):  # ReLU decisions handed in for map m of this unit, or None
-                    if relu_open is None:
-                        return None
-                    return np.asarray(relu_open)[b, h, lo:hi, m * d_phi:(m + 1) * d_phi]
-                dQ[b, h, lo:hi] = phi_backward(dqf, Q[b, h, lo:hi], *phi[0].astuple(), relu_open=ro(0))
+                dQ[b, h, lo:hi] = phi_backward(dqf, Q[b, h, lo:hi], *phi[0].astuple())
                 acc = np.zeros((hi - lo, K.shape[-1]), F64)
                 for f in range(F):
-                    acc += phi_backward(dkfs[f], K[b, h, lo:hi], *phi[1 + f].astuple(),
-                                        relu_open=ro(1 + f))
+                    acc += phi_backward(dkfs[f], K[b, h, lo:hi], *phi[1 + f].astuple())
                 dK[b, h, lo:hi] = acc
                 if wg is not None:
-                    parts = [phi_weight_grads(dqf, Q[b, h, lo:hi], *phi[0].astuple(), relu_open=ro(0))]
-                    parts += [phi_weight_grads(dkfs[f], K[b, h, lo:hi], *phi[1 + f].astuple(),
-                                               relu_open=ro(1 + f)) for f in range(F)]
+                    parts = [phi_weight_grads(dqf, Q[b, h, lo:hi], *phi[0].astuple())]
+                    parts += [phi_weight_grads(dkfs[f], K[b, h, lo:hi], *phi[1 + f].astuple())
+                              for f in range(F)]
                     for m, part in enumerate(parts):
                         for a, da in zip(wg[m], part):
                             a += da
+    res = (dQ, dK, dV)
     if wg is not None:
-        return dQ, dK, dV, [tuple(m) for m in wg]
-    return dQ, dK, dV
+        res += ([tuple(m) for m in wg],)
+    if feature_grads:
+        res += ((dQf, dKf),)
+    return res
 
 
 def hla_bruteforce_rows(qf_rows, kfs, v, eps: float) -> np.ndarray:

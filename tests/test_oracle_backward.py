@@ -190,8 +190,8 @@ def test_weight_grads_need_feature_maps():
         orc.hla_operator_backward(Q, K, V, V, 2, 2, 1e-6, weight_grads=True)
 
 
-def test_relu_decisions_handed_in():
-    # With decisions handed in, the feature map is differentiated as mask * u(x): the gradients
+def test_relu_branch_choices():
+    # With a branch choice given, the feature map is differentiated as mask * u(x): the gradients
     # must equal the finite differences of exactly that (smooth) function, and with the oracle's
     # own decisions nothing changes.
     rng = np.random.default_rng(57)
@@ -214,3 +214,95 @@ def test_relu_decisions_handed_in():
     np.testing.assert_allclose(db1, _fd(f, b1), rtol=1e-6, atol=1e-8)
     np.testing.assert_allclose(dW2, _fd(f, W2), rtol=1e-6, atol=1e-8)
     np.testing.assert_allclose(db2, _fd(f, b2), rtol=1e-6, atol=1e-8)
+
+
+def _branch_setup(seed, n=9, d=5, dp=3, nmaps=2):
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((n, d))
+    maps = [(rng.standard_normal((d, d)), rng.standard_normal(d), rng.standard_normal((d, dp)),
+             0.3 * rng.standard_normal(dp)) for _ in range(nmaps)]
+    dfeats = [rng.standard_normal((n, dp)) for _ in range(nmaps)]
+    return x, maps, dfeats
+
+
+def test_phi_backward_branches_enumerates_every_choice():
+    x, maps, dfeats = _branch_setup(58)
+    us = [orc.phi_forward(x, *m)[2] for m in maps]
+    allu = np.abs(np.concatenate(us, axis=1))
+    band = float(np.sort(allu.ravel())[7]) * 1.0001  # the seven smallest |u| are "in band"
+    br = orc.phi_backward_branches(dfeats, x, maps, band)
+    inband_rows = np.nonzero((allu < band).any(axis=1))[0]
+    assert sorted(br) == [int(r) for r in inband_rows] and len(br) >= 2
+    own = sum(orc.phi_backward(df, x, *m) for df, m in zip(dfeats, maps))
+    for n, cands in br.items():
+        slots = [(m, a) for m in range(len(maps)) for a in range(us[m].shape[1]) if abs(us[m][n, a]) < band]
+        assert cands.shape == (2 ** len(slots), x.shape[1])
+        # the oracle's own decisions are one of the choices, at the index their bits spell
+        bits = sum((1 << i) for i, (m, a) in enumerate(slots) if us[m][n, a] > 0)
+        np.testing.assert_allclose(cands[bits], own[n], rtol=1e-12, atol=1e-14)
+        # every choice is the finite difference of the correspondingly masked (smooth) maps
+        for b in range(cands.shape[0]):
+            masks = [(u[n] > 0) & (np.abs(u[n]) >= band) for u in us]
+            for i, (m, a) in enumerate(slots):
+                masks[m][a] = bool((b >> i) & 1)
+            xr = x[n:n + 1].copy()
+            f = lambda: float(sum((orc.phi_forward(xr, *maps[m])[2][0] * masks[m] * dfeats[m][n]).sum()
+                                  for m in range(len(maps))))
+            np.testing.assert_allclose(cands[b], _fd(f, xr)[0], rtol=1e-6, atol=1e-8)
+        # choices that differ in one open feature with a non-zero gradient are different rows
+        if cands.shape[0] > 1:
+            assert np.abs(cands[1] - cands[0]).max() > 0
+    # nothing is in band at resolution zero; too many in-band features in a row are refused
+    assert orc.phi_backward_branches(dfeats, x, maps, 0.0) == {}
+    with pytest.raises(ValueError):
+        orc.phi_backward_branches(dfeats, x, maps, 1e9, max_inband=3)
+
+
+def test_phi_weight_grad_branches_are_linear_in_the_choices():
+    x, maps, dfeats = _branch_setup(59, n=11)
+    m, df = maps[0], dfeats[0]
+    u = orc.phi_forward(x, *m)[2]
+    band = float(np.sort(np.abs(u).ravel())[5]) * 1.0001
+    base, pairs, contribs, own = orc.phi_weight_grad_branches(df, x, *m, band)
+    assert len(pairs) == 6 == len(contribs) == len(own)
+    assert all(abs(u[n, a]) < band for n, a in pairs)
+    # the oracle's own decisions reproduce phi_weight_grads
+    ref = orc.phi_weight_grads(df, x, *m)
+    for k in range(4):
+        tot = base[k] + sum(c[k] for c, o in zip(contribs, own) if o)
+        np.testing.assert_allclose(tot, ref[k], rtol=1e-12, atol=1e-13)
+    # an arbitrary choice equals phi_weight_grads under the corresponding mask
+    rng = np.random.default_rng(60)
+    choice = rng.random(len(pairs)) < 0.5
+    mask = (u > 0) & (np.abs(u) >= band)
+    for (n, a), c in zip(pairs, choice):
+        mask[n, a] = c
+    ref = orc.phi_weight_grads(df, x, *m, relu_open=mask)
+    for k in range(4):
+        tot = base[k] + sum(c[k] for c, ch in zip(contribs, choice) if ch)
+        np.testing.assert_allclose(tot, ref[k], rtol=1e-12, atol=1e-13)
+    assert orc.phi_weight_grad_branches(df, x, *m, 0.0)[1] == []
+
+
+def test_operator_backward_returns_the_feature_gradients():
+    # the intermediate handed out with feature_grads is what phi_backward consumes: pushing it
+    # through the maps reproduces dQ and dK, and at the feature level it is dQ, dK themselves
+    rng = np.random.default_rng(61)
+    B, H, N, d, F, dp = 1, 2, 6, 4, 2, 3
+    Q, K, V, dO = (rng.standard_normal((B, H, N, d)) for _ in range(4))
+    phi = [orc.PhiWeights(rng.standard_normal((d, d)), 0.3 * rng.standard_normal(d),
+                          rng.standard_normal((d, dp)), rng.standard_normal(dp) + 1.0)
+           for _ in range(1 + F)]
+    dQ, dK, dV, (dqf, dkf) = orc.hla_operator_backward(Q, K, V, dO, F, dp, 1e-4, phi=phi,
+                                                       feature_grads=True)
+    assert dqf.shape == (B, H, N, dp) and dkf.shape == (B, H, N, F * dp)
+    for h in range(H):
+        np.testing.assert_allclose(orc.phi_backward(dqf[0, h], Q[0, h], *phi[0].astuple()), dQ[0, h],
+                                   rtol=1e-12, atol=1e-14)
+        acc = sum(orc.phi_backward(dkf[0, h][:, f * dp:(f + 1) * dp], K[0, h], *phi[1 + f].astuple())
+                  for f in range(F))
+        np.testing.assert_allclose(acc, dK[0, h], rtol=1e-12, atol=1e-14)
+    Qf, Kf = np.abs(rng.standard_normal((B, H, N, dp))), np.abs(rng.standard_normal((B, H, N, F * dp)))
+    dQ2, dK2, _, (dqf2, dkf2) = orc.hla_operator_backward(Qf, Kf, V, dO, F, dp, 1e-4, feature_grads=True)
+    np.testing.assert_array_equal(dQ2, dqf2)
+    np.testing.assert_array_equal(dK2, dkf2)
