@@ -1,5 +1,10 @@
 """Helpers shared by the GPU parity tests: run the library through its C ABI (Python binding),
-run the CPU oracle on the same tensors, and compare with the build's error measure."""
+run the CPU oracle on the same tensors, and compare with the build's error measure.
+
+Every reference value comes from the oracle alone; nothing the library computes is ever handed to
+it.  Where the final ReLU of the feature maps (App. A.1) makes a gradient discontinuous, the
+oracle enumerates the branch choices that are open to an implementation in lower precision and
+the comparison asks the library's result to match one of them."""
 from __future__ import annotations
 
 from typing import Dict, List, Optional, Sequence
@@ -11,6 +16,12 @@ import paper_2602_12128_amd as hla
 from oracle import hla_oracle as orc
 
 TOL = {torch.float32: 1e-4, torch.bfloat16: 2e-2}
+
+# |pre-ReLU value| below which the library (bf16 first layer, fp16 GELU and second layer) may
+# take either branch of the ReLU.  test_gpu_mfma.py::test_features_match_oracle asserts that
+# the library's features stay within this distance of the oracle's, which is what makes the
+# band wide enough: outside it both sides decide alike.
+RELU_BAND = 1e-2
 
 
 def max_rel_err(got, ref) -> float:
@@ -51,10 +62,11 @@ WG_KEYS = ("dW1", "db1", "dW2", "db2")
 
 def run_gpu(tensors: Dict[str, torch.Tensor], F: int, d_phi: int, eps: float,
             phi=None, cu_seqlens=None, backward=True, path=hla.HLA_PATH_AUTO, handle=None,
-            weight_grads=False, per_head=False):
+            weight_grads=False, per_head=False, features=False):
     """Returns dict of CPU tensors O (and dQ, dK, dV) computed by the HIP library; with
     weight_grads also 'wg': per map a dict of the fp32 weight gradients.  per_head: the weights
-    carry a leading head dimension."""
+    carry a leading head dimension.  features: also '_features' [B,H,N,(1+F)*d_phi], the
+    library's own feature workspace (an output to be compared, like the others)."""
     dev = torch.device("cuda:0")
     t = {k: v.to(dev) for k, v in tensors.items()}
     h = handle or make_handle(tensors, F, d_phi, eps, phi, cu_seqlens, path)
@@ -77,59 +89,36 @@ def run_gpu(tensors: Dict[str, torch.Tensor], F: int, d_phi: int, eps: float,
     res = {k: v.cpu() for k, v in out.items()}
     if wg is not None:
         res["wg"] = [{k: v.cpu() for k, v in m.items()} for m in wg]
-        # the library's own ReLU decisions (feature > 0), for an oracle that differentiates the
-        # same branches: [B, H, N, (1+F)*d_phi]
+    if features:
         B, H, N = t["V"].shape[:3]
         nfeat = (1 + F) * d_phi
-        feats = h.read_workspace(hla.binding.HLA_WS_FEATURES, B * H * N * nfeat)
-        res["relu_open"] = feats.reshape(B, H, N, nfeat) > 0
+        res["_features"] = h.read_workspace(hla.binding.HLA_WS_FEATURES, B * H * N * nfeat).reshape(B, H, N, nfeat)
     res["_path"] = h.active_path
     if handle is None:
         h.destroy()
     return res
 
 
-RELU_BAND = 1e-2  # |pre-activation| below this: the library may decide the ReLU either way
-
-
-def assert_relu_decisions_valid(tensors, phi, F, relu_open, band=RELU_BAND):
-    """The ReLU decisions read back from the library (feature > 0) are only handed to the oracle
-    after the oracle has confirmed them: wherever its own fp64 pre-activation is further than
-    `band` from zero (the rounding error of the library's bf16/fp16 feature maps) the decision
-    must be the oracle's own; inside the band either branch is a valid one."""
-    ophi = oracle_phi(phi)
-    Q, K = to_np(tensors["Q"]), to_np(tensors["K"])
-    u = [orc.phi_forward(Q, *ophi[0].astuple())[2]]
-    u += [orc.phi_forward(K, *ophi[1 + f].astuple())[2] for f in range(F)]
-    u = np.concatenate(u, axis=-1)
-    relu_open = np.asarray(relu_open)
-    assert relu_open.shape == u.shape, (relu_open.shape, u.shape)
-    clear = np.abs(u) > band
-    wrong = clear & (relu_open != (u > 0))
-    assert not wrong.any(), f"{int(wrong.sum())} ReLU decisions differ from the oracle's outside the band"
-    assert clear.mean() > 0.9, "the band covers too many pre-activations to mean anything"
-
-
 def run_oracle(tensors, F, d_phi, eps, phi=None, cu_seqlens=None, backward=True,
-               route="factorized", weight_grads=False, relu_open=None):
+               route="factorized", weight_grads=False):
+    """O (and dQ, dK, dV, 'wg') from the oracle; with feature maps and a backward also the
+    feature gradients '_dqf', '_dkf' that the branch enumeration below starts from."""
     Q, K, V = (to_np(tensors[k]) for k in ("Q", "K", "V"))
     ophi = oracle_phi(phi)
-    if relu_open is not None and phi is not None:
-        assert_relu_decisions_valid(tensors, phi, F, relu_open)
     out = {"O": orc.hla_operator_forward(Q, K, V, F, d_phi, eps, phi=ophi, cu_seqlens=cu_seqlens,
                                          route=route)}
     if backward:
         res = orc.hla_operator_backward(Q, K, V, to_np(tensors["dO"]), F, d_phi, eps,
                                         phi=ophi, cu_seqlens=cu_seqlens, route=route,
-                                        weight_grads=weight_grads, relu_open=relu_open)
+                                        weight_grads=weight_grads, feature_grads=True)
         out.update(dQ=res[0], dK=res[1], dV=res[2])
         if weight_grads:
             out["wg"] = [dict(zip(WG_KEYS, m)) for m in res[3]]
+        out["_dqf"], out["_dkf"] = res[-1]
     return out
 
 
-def run_oracle_per_head(tensors, F, d_phi, eps, phi, cu_seqlens=None, weight_grads=True,
-                        relu_open=None):
+def run_oracle_per_head(tensors, F, d_phi, eps, phi, cu_seqlens=None, weight_grads=True):
     """Oracle for weights that carry a leading head dimension: the oracle's maps are shared by
     the heads it is given, so every head is run on its own with its own weights."""
     H = tensors["V"].shape[1]
@@ -138,25 +127,137 @@ def run_oracle_per_head(tensors, F, d_phi, eps, phi, cu_seqlens=None, weight_gra
         th = {k: v[:, h:h + 1] for k, v in tensors.items()}
         ph = [{k: v[h] for k, v in m.items()} for m in phi]
         outs.append(run_oracle(th, F, d_phi, eps, phi=ph, cu_seqlens=cu_seqlens,
-                               weight_grads=weight_grads,
-                               relu_open=None if relu_open is None else relu_open[:, h:h + 1]))
-    out = {k: np.concatenate([o[k] for o in outs], axis=1) for k in ("O", "dQ", "dK", "dV")}
+                               weight_grads=weight_grads))
+    out = {k: np.concatenate([o[k] for o in outs], axis=1) for k in ("O", "dQ", "dK", "dV", "_dqf", "_dkf")}
     if weight_grads:
         out["wg"] = [{k: np.stack([o["wg"][m][k] for o in outs]) for k in WG_KEYS}
                      for m in range(len(phi))]
     return out
 
 
-def assert_weight_grad_parity(gpu_wg, ref_wg, tol, what=""):
+# ---- ReLU kinks: the oracle's branch choices ------------------------------------------------------
+def _head_maps(phi, F, h, per_head):
+    """Oracle weight tuples (phi_q, phi_k1..kF) of head h."""
+    if per_head:
+        phi = [{k: v[h] for k, v in m.items()} for m in phi]
+    return [m.astuple() for m in oracle_phi(phi)]
+
+
+def oracle_kinks(tensors, phi, F, d_phi, ref, band=RELU_BAND, per_head=False):
+    """For dQ and dK: {(b, h, n): candidate rows [2^k, d]} for every token whose pre-ReLU values
+    include k >= 1 within `band` of zero: all gradient rows the oracle computes by opening or
+    closing those k features (orc.phi_backward_branches), from the oracle's own feature
+    gradients ref['_dqf'], ref['_dkf']."""
+    Q, K = to_np(tensors["Q"]), to_np(tensors["K"])
+    B, H = Q.shape[:2]
+    out = {"dQ": {}, "dK": {}}
+    for b in range(B):
+        for h in range(H):
+            maps = _head_maps(phi, F, h, per_head)
+            br = orc.phi_backward_branches([ref["_dqf"][b, h]], Q[b, h], maps[:1], band)
+            out["dQ"].update({(b, h, n): c for n, c in br.items()})
+            dk = [ref["_dkf"][b, h][:, f * d_phi:(f + 1) * d_phi] for f in range(F)]
+            br = orc.phi_backward_branches(dk, K[b, h], maps[1:], band)
+            out["dK"].update({(b, h, n): c for n, c in br.items()})
+    return out
+
+
+def _log_allclose(k, g, r, tol):
+    """Elementwise view next to the per-tensor measure: share of entries outside
+    |g - r| <= tol * |r| + tol * rms(r).  Logged, not asserted."""
+    rms = float(np.sqrt(np.mean(r * r))) if r.size else 0.0
+    bad = np.abs(g - r) > tol * np.abs(r) + tol * rms
+    return f"{k}:{bad.mean():.1e}"
+
+
+def assert_parity(gpu, ref, tol, what="", kinks=None, row_scale=None):
+    """Per tensor: max |gpu - ref| / max |ref| <= tol.  kinks (from oracle_kinks): rows of dQ / dK
+    listed there are compared with the closest of the oracle's branch choices instead of the
+    single reference row.  row_scale: {tensor: (mask [B,H,N], scale)}: rows under the mask are
+    measured against the absolute scale given instead of max |ref| (sequences too short for the
+    gradient to be more than the remainder of two cancelling terms)."""
+    errs, close, notes = {}, [], []
+    for k, r in ref.items():
+        if k == "wg" or k.startswith("_"):
+            continue
+        g = to_np(gpu[k])
+        assert np.isfinite(g).all(), f"{what}: {k} has non-finite entries"
+        diff = np.abs(g - r)
+        if kinks is not None and kinks.get(k):
+            n_other = 0
+            for (b, h, n), cands in kinks[k].items():
+                d_c = np.abs(cands - g[b, h, n][None, :]).max(axis=1)
+                best = int(d_c.argmin())
+                # the row is judged by its distance to the closest choice
+                diff[b, h, n] = np.abs(cands[best] - g[b, h, n])
+                n_other += int(np.abs(cands[best] - r[b, h, n]).max() > 0)
+            notes.append(f"{k}: {len(kinks[k])} kink rows ({len(kinks[k]) / max(1, r[..., 0].size):.2%}), "
+                         f"{n_other} on another branch than the oracle's own")
+        scale = np.abs(r).max() if r.size else 0.0
+        if row_scale is not None and k in row_scale:
+            mask, s_abs = row_scale[k]
+            short = diff[mask].max() / s_abs if mask.any() else 0.0
+            rest = diff[~mask].max() / scale if (~mask).any() and scale > 0 else 0.0
+            errs[k] = float(max(short, rest))
+            notes.append(f"{k}: {int(mask.sum())} short-sequence rows on the absolute scale {s_abs:.3g}: {short:.2e}")
+        elif scale == 0.0:
+            errs[k] = 0.0 if not diff.size or diff.max() == 0.0 else float("inf")
+        else:
+            errs[k] = float(diff.max() / scale)
+        close.append(_log_allclose(k, g, r, tol))
+    msg = ", ".join(f"{k}={e:.2e}" for k, e in errs.items())
+    print(f"[parity] {what}: {msg} (tol {tol:g}); outside elementwise allclose: {' '.join(close)}", flush=True)
+    for n in notes:
+        print(f"[parity]   {n}", flush=True)
+    bad = {k: e for k, e in errs.items() if not e <= tol}
+    assert not bad, f"{what}: max relative error above {tol:g}: {bad}"
+    return errs
+
+
+def assert_weight_grad_parity(gpu_wg, ref_wg, tol, what="", branches=None):
     """Every weight-gradient array of every map against the oracle with the build's error
-    measure (max |diff| / max |ref| per array)."""
+    measure (max |diff| / max |ref| per array).
+
+    branches (from oracle_weight_grad_branches; bf16 paths): per (map[, head]) the oracle's
+    (base, pairs, contribs, own).  The gradients are sums over all tokens, linear in the ReLU
+    branch choices of the in-band (token, feature) pairs, so the library must agree with
+    base + sum choice_p contrib_p for ONE assignment of choices in {0, 1}: the assignment is
+    fitted by least squares over all four arrays of the map, rounded to {0, 1}, and the
+    residual of that single assignment is what is measured."""
     worst = {}
     for m, (g, r) in enumerate(zip(gpu_wg, ref_wg)):
-        for k in WG_KEYS:
-            got = to_np(g[k])
-            assert np.isfinite(got).all(), f"{what}: map {m} {k} has non-finite entries"
-            assert got.shape == r[k].shape, f"{what}: map {m} {k} shape {got.shape} vs {r[k].shape}"
-            worst[f"{k}[{m}]"] = max_rel_err(got, r[k])
+        per_head = branches is not None and isinstance(branches[m], list)
+        heads = len(branches[m]) if per_head else 1
+        for hh in range(heads):
+            sel = (lambda a: a[hh]) if per_head else (lambda a: a)
+            got = {k: sel(to_np(g[k])) for k in WG_KEYS}
+            own = {k: sel(r[k]) for k in WG_KEYS}
+            for k in WG_KEYS:
+                assert np.isfinite(got[k]).all(), f"{what}: map {m} {k} has non-finite entries"
+                assert got[k].shape == own[k].shape, f"{what}: map {m} {k} shape {got[k].shape} vs {own[k].shape}"
+            tag = f"[{m}]" + (f"h{hh}" if per_head else "")
+            br = None if branches is None else (branches[m][hh] if per_head else branches[m])
+            if br is None or not br[1]:
+                for k in WG_KEYS:
+                    worst[k + tag] = max_rel_err(got[k], own[k])
+                continue
+            base, pairs, contribs, own_choice = br
+            scale = [max(np.abs(own[k]).max(), 1e-300) for k in WG_KEYS]
+            resid = np.concatenate([((got[k] - base[i]) / scale[i]).ravel() for i, k in enumerate(WG_KEYS)])
+            A = np.stack([np.concatenate([(c[i] / scale[i]).ravel() for i in range(4)]) for c in contribs], axis=1)
+            coef = np.linalg.lstsq(A, resid, rcond=None)[0]
+            choice = coef > 0.5
+            fit = resid - A @ choice.astype(np.float64)
+            off = 0
+            for i, k in enumerate(WG_KEYS):
+                n = got[k].size
+                worst[k + tag] = float(np.abs(fit[off:off + n]).max())
+                off += n
+            slack = [float(sum(np.abs(c[i]) for c in contribs).max() / scale[i]) for i in range(4)]
+            flips = int((choice != np.asarray(own_choice)).sum())
+            print(f"[parity]   {what} map {m}{' head %d' % hh if per_head else ''}: {len(pairs)} in-band pairs, "
+                  f"{flips} taken on the other branch than the oracle's own; a bound that ignored the choices "
+                  f"would add {', '.join(f'{k} {s:.1e}' for k, s in zip(WG_KEYS, slack))} of max|ref|", flush=True)
     msg = ", ".join(f"{k}={e:.2e}" for k, e in worst.items())
     print(f"[parity] {what}: {msg} (tol {tol:g})", flush=True)
     bad = {k: e for k, e in worst.items() if not e <= tol}
@@ -164,35 +265,48 @@ def assert_weight_grad_parity(gpu_wg, ref_wg, tol, what=""):
     return worst
 
 
-def relu_kink_masks(tensors, phi, F, band):
-    """Token masks (True = compare) for dQ and dK.  The ReLU of the feature maps makes the
-    gradient discontinuous where a pre-activation u crosses zero; a token whose |u| is within
-    the arithmetic's error `band` of zero may take the other branch on the GPU (which decides in
-    its own precision), so its gradient row is compared only through the finiteness check."""
-    ophi = oracle_phi(phi)
+def oracle_weight_grad_branches(tensors, phi, F, d_phi, ref, cu_seqlens=None, band=RELU_BAND,
+                                per_head=False):
+    """orc.phi_weight_grad_branches for every map over all rows that share its weights (every
+    batch row, head and sequence; one head at a time when the weights are per head): a list over
+    maps of (base, pairs, contribs, own), or of per-head lists of them."""
     Q, K = to_np(tensors["Q"]), to_np(tensors["K"])
-    uq = np.abs(orc.phi_forward(Q, *ophi[0].astuple())[2]).min(-1)
-    uk = np.minimum.reduce([np.abs(orc.phi_forward(K, *ophi[1 + f].astuple())[2]).min(-1)
-                            for f in range(F)])
-    return {"dQ": uq > band, "dK": uk > band}
+    B, H, N, d = Q.shape
+    if cu_seqlens is not None:  # tokens outside every sequence do not exist for the operator
+        assert cu_seqlens[0] == 0 and cu_seqlens[-1] == N
+    out = []
+    for m in range(1 + F):
+        X = Q if m == 0 else K
+        dfe = ref["_dqf"] if m == 0 else ref["_dkf"][..., (m - 1) * d_phi:m * d_phi]
+        if per_head:
+            res = []
+            for h in range(H):
+                w = _head_maps(phi, F, h, True)[m]
+                res.append(orc.phi_weight_grad_branches(dfe[:, h].reshape(-1, d_phi), X[:, h].reshape(-1, d), *w, band))
+            out.append(res)
+        else:
+            w = _head_maps(phi, F, 0, False)[m]
+            out.append(orc.phi_weight_grad_branches(dfe.reshape(-1, d_phi), X.reshape(-1, d), *w, band))
+    return out
 
 
-def assert_parity(gpu, ref, tol, what="", row_masks=None):
-    errs = {}
-    for k, r in ref.items():
-        if k == "wg":
-            continue
-        g = to_np(gpu[k])
-        assert np.isfinite(g).all(), f"{what}: {k} has non-finite entries"
-        if row_masks is not None and k in row_masks:
-            m = row_masks[k]
-            assert m.mean() > 0.8, f"{what}: kink band excludes too many rows of {k}"
-            scale = np.abs(r).max()
-            errs[k] = float(np.abs(g - r)[m].max() / scale) if m.any() else 0.0
-            continue
-        errs[k] = max_rel_err(g, r)
-    msg = ", ".join(f"{k}={e:.2e}" for k, e in errs.items())
-    print(f"[parity] {what}: {msg} (tol {tol:g})", flush=True)
-    bad = {k: e for k, e in errs.items() if not e <= tol}
-    assert not bad, f"{what}: max relative error above {tol:g}: {bad}"
-    return errs
+def short_sequence_rows(tensors, ref, cu_seqlens, max_len=2):
+    """row_scale argument of assert_parity for dQ and dK: rows of packed sequences of at most
+    max_len tokens.  Their outputs barely depend on Q and K (one token: not at all, up to eps),
+    so the gradient is what is left of two cancelling terms of size |dO| |v| (times the gain of
+    the feature map's backward, taken as max |dX| / max |d feature| over the other rows of the
+    oracle's result) and is measured on that scale."""
+    B, H, N = tensors["V"].shape[:3]
+    mask = np.zeros((B, H, N), bool)
+    for lo, hi in zip(cu_seqlens[:-1], cu_seqlens[1:]):
+        if 0 < hi - lo <= max_len:
+            mask[:, :, lo:hi] = True
+    base = float(tensors["dO"].float().abs().max() * tensors["V"].float().abs().max())
+    out = {}
+    for k, fk in (("dQ", "_dqf"), ("dK", "_dkf")):
+        if fk in ref and (~mask).any():
+            gain = np.abs(ref[k][~mask]).max() / max(np.abs(ref[fk][~mask]).max(), 1e-300)
+        else:
+            gain = 1.0
+        out[k] = (mask, base * max(gain, 1.0))
+    return out

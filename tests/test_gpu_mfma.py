@@ -5,6 +5,7 @@ import pytest
 import torch
 
 import paper_2602_12128_amd as hla
+from oracle import hla_oracle as orc
 from paper_2602_12128_amd import workloads as wl
 from tests import parity_utils as pu
 
@@ -30,21 +31,104 @@ def test_feature_level_bf16(d, N, kind):
     pu.assert_parity(gpu, ref, 2e-2, f"mfma features d={d} N={N} {kind}")
 
 
+# Error of the library's pre-ReLU values (bf16 first layer, fp16 polynomial GELU, fp16 second
+# layer) against the oracle's: FEATURE_NOISE bounds its rms, pu.RELU_BAND its maximum.
+FEATURE_NOISE = 1.5e-3
+
+
+def _feature_errors(t, phi, F, d_phi, gpu_feat):
+    ophi = pu.oracle_phi(phi)
+    Q, K = pu.to_np(t["Q"]), pu.to_np(t["K"])
+    ref = np.concatenate([orc.phi_forward(Q, *ophi[0].astuple())[0]] +
+                         [orc.phi_forward(K, *ophi[1 + f].astuple())[0] for f in range(F)], axis=-1)
+    return np.abs(np.asarray(gpu_feat, np.float64) - ref), ref
+
+
+@pytest.mark.parametrize("F,dphi,d,N,b2", [(3, 6, 128, 2000, 2.0), (3, 6, 64, 1300, 0.5), (2, 12, 128, 900, 2.0)])
+def test_features_match_oracle(F, dphi, d, N, b2):
+    # Alg. 1 Step 4 on its own: the feature workspace the forward leaves behind against the
+    # oracle's feature maps.  The maximum error is what the ReLU band of the gradient comparisons
+    # rests on: a feature the oracle sees further than the band from zero is decided alike.
+    t, phi = wl.make_raw_inputs(430 + N, 1, 3, N, d, F, dphi, torch.bfloat16, b2_mean=b2)
+    gpu = pu.run_gpu(t, F, dphi, 1e-6, phi=phi, path=hla.HLA_PATH_MFMA, backward=False, features=True)
+    err, ref = _feature_errors(t, phi, F, dphi, gpu["_features"])
+    rms = float(np.sqrt((err ** 2).mean()))
+    print(f"[parity] features F={F} d={d} N={N} b2={b2}: max {err.max():.2e}, 99.99% "
+          f"{np.quantile(err, 0.9999):.2e}, rms {rms:.2e} (max|ref| {ref.max():.2f})", flush=True)
+    assert err.max() <= pu.RELU_BAND
+    assert rms <= FEATURE_NOISE
+    # clipped features are exactly zero on both sides wherever the oracle is clear of the band
+    uq = [orc.phi_forward(pu.to_np(t["Q" if m == 0 else "K"]), *pu.oracle_phi(phi)[m].astuple())[2]
+          for m in range(1 + F)]
+    u = np.concatenate(uq, axis=-1)
+    assert np.all(np.asarray(gpu["_features"])[u < -pu.RELU_BAND] == 0.0)
+    assert np.all(np.asarray(gpu["_features"])[u > pu.RELU_BAND] > 0.0)
+
+
+def _oracle_dq_sensitivity(t, phi, F, d_phi, eps, ref, noise, seed=0):
+    """max |dQ' - dQ| / max |dQ| of the ORACLE when the pre-ReLU values of all maps move by a
+    seeded uniform perturbation of amplitude `noise` (ReLU decisions held): how much of the
+    feature maps' arithmetic error the input itself turns into query-gradient error."""
+    ophi = pu.oracle_phi(phi)
+    Q, K, V, dO = (pu.to_np(t[k]) for k in ("Q", "K", "V", "dO"))
+    rng = np.random.default_rng(seed)
+    worst = 0.0
+    for b in range(Q.shape[0]):
+        for h in range(Q.shape[1]):
+            uq = orc.phi_forward(Q[b, h], *ophi[0].astuple())[2]
+            uk = [orc.phi_forward(K[b, h], *ophi[1 + f].astuple())[2] for f in range(F)]
+            qf = np.maximum(uq + noise * rng.uniform(-1, 1, uq.shape), 0.0) * (uq > 0)
+            kf = [np.maximum(u + noise * rng.uniform(-1, 1, u.shape), 0.0) * (u > 0) for u in uk]
+            dqf = orc.hla_backward_factorized(qf, kf, V[b, h], dO[b, h], eps)[0]
+            dq = orc.phi_backward(dqf, Q[b, h], *ophi[0].astuple())
+            worst = max(worst, float(np.abs(dq - ref["dQ"][b, h]).max()))
+    return worst / float(np.abs(ref["dQ"]).max())
+
+
 @pytest.mark.parametrize("d,N,b2", [(128, 700, 2.0), (64, 1300, 0.5), (128, 95, 1.0)])
 def test_feature_maps_bf16(d, N, b2):
     t, phi = wl.make_raw_inputs(400 + N, 1, 2, N, d, 3, 6, torch.bfloat16, b2_mean=b2)
     gpu = pu.run_gpu(t, 3, 6, 1e-6, phi=phi, path=hla.HLA_PATH_MFMA, backward=BWD)
     ref = pu.run_oracle(t, 3, 6, 1e-6, phi=phi, backward=BWD)
-    # bf16 hidden activations put about 2e-3 of noise on the pre-ReLU values: rows within 1e-2 of
-    # the kink may legitimately take the other branch and are left out of the gradient comparison
-    masks = pu.relu_kink_masks(t, phi, 3, 1e-2)
-    if b2 < 1.0:
-        # many queries have all features near zero here: their tiny denominators amplify the
-        # feature maps' bf16 rounding in dQ (an input-conditioning effect, not a kernel one), so
-        # dQ gets a wider bound in this stress case; the benchmark recipe (b2 = 2) does not.
-        dq = {"dQ": gpu["dQ"]}
-        pu.assert_parity(dq, {"dQ": ref.pop("dQ")}, 8e-2, f"mfma phi d={d} N={N} b2={b2} (dQ)", row_masks=masks)
-    pu.assert_parity(gpu, ref, 2e-2, f"mfma phi d={d} N={N} b2={b2}", row_masks=masks)
+    kinks = pu.oracle_kinks(t, phi, 3, 6, ref)
+    # The query gradient's tolerance grows with what the INPUT makes of the feature maps' own
+    # arithmetic error: with small b2 many queries have all features near zero, their tiny
+    # denominators amplify a feature error of FEATURE_NOISE far more than the benchmark recipe
+    # (b2 = 2) does.  The amplification is measured on the oracle alone and added to the bound.
+    kappa = _oracle_dq_sensitivity(t, phi, 3, 6, 1e-6, ref, FEATURE_NOISE)
+    print(f"[parity] mfma phi d={d} N={N} b2={b2}: oracle dQ sensitivity to a feature error of "
+          f"{FEATURE_NOISE:g}: {kappa:.2e}", flush=True)
+    dq_tol = 2e-2 + 2.0 * kappa if b2 < 1.0 else 2e-2
+    pu.assert_parity({"dQ": gpu["dQ"]}, {"dQ": ref["dQ"]}, dq_tol, f"mfma phi d={d} N={N} b2={b2} (dQ)",
+                     kinks=kinks)
+    rest = {k: v for k, v in ref.items() if k != "dQ"}
+    pu.assert_parity(gpu, rest, 2e-2, f"mfma phi d={d} N={N} b2={b2}", kinks=kinks)
+
+
+@pytest.mark.parametrize("F,dphi", [(3, 6), (2, 12)])
+def test_strided_views_bf16(F, dphi):
+    # every tensor stored [B, N, H, w] and passed as the [B, H, N, w] view the interface takes
+    # (the layout a projection followed by a head split leaves behind)
+    B, H, N, d = 2, 3, 700, 128
+    t, phi = wl.make_raw_inputs(440 + F, B, H, N, d, F, dphi, torch.bfloat16)
+    dev = torch.device("cuda:0")
+    view = lambda x: x.to(dev).permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    td = {k: view(v) for k, v in t.items()}
+    assert not td["V"].is_contiguous()
+    h = pu.make_handle(t, F, dphi, 1e-6, phi, None, hla.HLA_PATH_MFMA)
+    h.set_phi_weights([{k: v.to(dev) for k, v in m.items()} for m in phi])
+    out = {k: torch.full((B, N, H, d), float("nan"), dtype=torch.bfloat16, device=dev).permute(0, 2, 1, 3)
+           for k in ("O", "dQ", "dK", "dV")}
+    h.forward(td["Q"], td["K"], td["V"], out["O"])
+    h.backward(td["Q"], td["K"], td["V"], out["O"], td["dO"], out["dQ"], out["dK"], out["dV"])
+    torch.cuda.synchronize()
+    h.destroy()
+    dense = pu.run_gpu(t, F, dphi, 1e-6, phi=phi, path=hla.HLA_PATH_MFMA)
+    for k in out:  # the storage order changes no arithmetic
+        assert torch.equal(out[k].cpu(), dense[k]), k
+    ref = pu.run_oracle(t, F, dphi, 1e-6, phi=phi)
+    pu.assert_parity({k: v.cpu() for k, v in out.items()}, ref, 2e-2, f"mfma strided F={F}",
+                     kinks=pu.oracle_kinks(t, phi, F, dphi, ref))
 
 
 def test_packed_sequences_no_leak_bf16():

@@ -41,18 +41,13 @@ def test_shape_sweep_bf16(d, B, H, N, lens, F, dphi):
     t, phi = wl.make_raw_inputs(seed, B, H, n_tok, d, F, dphi, torch.bfloat16)
     gpu = pu.run_gpu(t, F, dphi, 1e-6, phi=phi, cu_seqlens=cu, path=hla.HLA_PATH_MFMA, weight_grads=True)
     assert gpu["_path"] == hla.HLA_PATH_MFMA
-    # both sides differentiate the ReLU branches the library took (decided in its precision)
-    ref = pu.run_oracle(t, F, dphi, 1e-6, phi=phi, cu_seqlens=cu, weight_grads=True,
-                        relu_open=gpu["relu_open"])
+    ref = pu.run_oracle(t, F, dphi, 1e-6, phi=phi, cu_seqlens=cu, weight_grads=True)
     what = f"sweep F={F} d={d} B={B} H={H} " + (f"N={N}" if lens is None else f"lens={lens}")
+    kinks = pu.oracle_kinks(t, phi, F, dphi, ref)
     # sequences of one or two tokens have outputs that barely depend on Q and K: their dQ, dK are
-    # rounding noise around (nearly) zero references, so those two are compared on an absolute
-    # scale set by the other gradients' magnitude instead
+    # what two cancelling terms leave behind, and are measured on those terms' scale
     short = lens is not None and min(x for x in lens if x > 0) <= 2
-    if short:
-        for k in ("dQ", "dK"):
-            assert np.isfinite(pu.to_np(gpu[k])).all()
-        pu.assert_parity({k: gpu[k] for k in ("O", "dV")}, {k: ref[k] for k in ("O", "dV")}, 2e-2, what)
-    else:
-        pu.assert_parity(gpu, ref, 2e-2, what)
-    pu.assert_weight_grad_parity(gpu["wg"], ref["wg"], 2e-2, what)
+    pu.assert_parity(gpu, ref, 2e-2, what, kinks=kinks,
+                     row_scale=pu.short_sequence_rows(t, ref, cu) if short else None)
+    br = pu.oracle_weight_grad_branches(t, phi, F, dphi, ref, cu_seqlens=cu)
+    pu.assert_weight_grad_parity(gpu["wg"], ref["wg"], 2e-2, what, branches=br)

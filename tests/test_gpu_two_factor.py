@@ -13,7 +13,6 @@ from tests import parity_utils as pu
 pytestmark = pytest.mark.gpu
 
 F, DPHI, EPS, TOL = 2, 12, 1e-6, 2e-2
-KINK_BAND = 1e-2  # see parity_utils.relu_kink_masks
 
 
 def _mfma(t, **kw):
@@ -71,8 +70,8 @@ def test_feature_maps_forward_backward(B, H, N, d):
     t, phi = wl.make_raw_inputs(820 + N, B, H, N, d, F, DPHI, torch.bfloat16)
     gpu = _mfma(t, phi=phi)
     ref = pu.run_oracle(t, F, DPHI, EPS, phi=phi)
-    masks = pu.relu_kink_masks(t, phi, F, KINK_BAND)
-    pu.assert_parity(gpu, ref, TOL, f"two-factor maps B{B} H{H} N{N} d{d}", row_masks=masks)
+    pu.assert_parity(gpu, ref, TOL, f"two-factor maps B{B} H{H} N{N} d{d}",
+                     kinks=pu.oracle_kinks(t, phi, F, DPHI, ref))
 
 
 @pytest.mark.parametrize("B,H,N,d,per_head", [(1, 2, 700, 128, False), (2, 3, 333, 64, False),
@@ -85,13 +84,14 @@ def test_weight_gradients(B, H, N, d, per_head):
         phi = [{k: torch.stack([heads[h][m][k] for h in range(H)]).contiguous() for k in heads[0][m]}
                for m in range(1 + F)]
     gpu = _mfma(t, phi=phi, weight_grads=True, per_head=per_head)
-    relu_open = np.asarray(gpu["relu_open"])
     if per_head:
-        ref = pu.run_oracle_per_head(t, F, DPHI, EPS, phi, relu_open=relu_open)
+        ref = pu.run_oracle_per_head(t, F, DPHI, EPS, phi)
     else:
-        ref = pu.run_oracle(t, F, DPHI, EPS, phi=phi, weight_grads=True, relu_open=relu_open)
-    pu.assert_parity(gpu, ref, TOL, f"two-factor outputs with shared ReLU decisions N{N} d{d}")
-    pu.assert_weight_grad_parity(gpu["wg"], ref["wg"], TOL, f"two-factor weight grads N{N} d{d}")
+        ref = pu.run_oracle(t, F, DPHI, EPS, phi=phi, weight_grads=True)
+    pu.assert_parity(gpu, ref, TOL, f"two-factor outputs N{N} d{d}",
+                     kinks=pu.oracle_kinks(t, phi, F, DPHI, ref, per_head=per_head))
+    br = pu.oracle_weight_grad_branches(t, phi, F, DPHI, ref, per_head=per_head)
+    pu.assert_weight_grad_parity(gpu["wg"], ref["wg"], TOL, f"two-factor weight grads N{N} d{d}", branches=br)
 
 
 def test_video_size_forward_backward():
@@ -105,9 +105,8 @@ def test_video_size_forward_backward():
     heads = [0, 7]
     sub = {k: v[:, heads].contiguous() for k, v in w.tensors.items()}
     ref = pu.run_oracle(sub, w.F, w.d_phi, w.eps, phi=w.phi)
-    masks = pu.relu_kink_masks(sub, w.phi, w.F, KINK_BAND)
-    pu.assert_parity({k: gpu[k][:, heads] for k in ref}, ref, TOL, "two-factor 480p heads 0,7",
-                     row_masks=masks)
+    pu.assert_parity({k: gpu[k][:, heads] for k in ref if not k.startswith("_")}, ref, TOL,
+                     "two-factor 480p heads 0,7", kinks=pu.oracle_kinks(sub, w.phi, w.F, w.d_phi, ref))
     ophi = pu.oracle_phi(w.phi)
     rows = np.random.default_rng(w.seed + 99).choice(w.N, size=64, replace=False)
     for hh in (3, 11):
