@@ -43,14 +43,17 @@ def parse():
 
 
 def measured_traffic(workload: str, kernel: str):
-    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary of this
-    workload (profiles/hbm_traffic_<workload>.json, written by profile_tools.py), or None."""
-    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.json")
+    """(HBM bytes per launch of `kernel`, where the figure comes from): the committed rocprofv3
+    counter summary of this workload (profiles/hbm_traffic_<workload>.json, written by
+    profile_tools.py from two --pmc runs of this script), not a measurement of the present run."""
+    rel = os.path.join("profiles", f"hbm_traffic_{workload}.json")
     try:
-        t = json.load(open(path)).get(kernel)
-        return None if t is None else t["read_bytes"] + t["write_bytes"]
+        t = json.load(open(os.path.join(ROOT, rel))).get(kernel)
+        if t is None:
+            return None, None
+        return t["read_bytes"] + t["write_bytes"], f"{rel} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, an earlier run of this command)"
     except (OSError, ValueError, KeyError):
-        return None
+        return None, None
 
 
 def cpu_baseline(w, phi, backward, features):
@@ -80,7 +83,7 @@ def cpu_baseline(w, phi, backward, features):
     dt = time.perf_counter() - t0
     # whole-job rate: a token counts once all H heads are done
     value = n_seq / (dt * H / heads)
-    return {"value": value, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+    return {"value": value, "unit": "tokens/s", "cores": int(cores), "kind": "oracle", "blas": True,
             "sample": f"{heads} of {H} heads of one {n_seq}-token sequence, "
                       f"{'fwd+bwd' if backward else 'fwd'}, fp64 numpy, {dt:.1f} s"}
 
@@ -168,20 +171,35 @@ def main():
     by = flops.path_bytes(w.d, w.d_phi, w.F, backward, phi is not None) * th
     tflops = fl / (elapsed / args.steps) / 1e12
 
+    mfma_path = h.active_path == hla.HLA_PATH_MFMA
+    fl_exec = flops.executed_path_flops(w.d, w.d_phi, w.F, backward, phi is not None) * th if mfma_path else None
     roofline = None
     if kernels:
         dom = max(kernels, key=lambda k: kernels[k]["avg_us"] * kernels[k]["launches_per_step"])
         model = flops.kernel_model(dom, w.d, w.d_phi, w.F)
         if model is not None:
             kb, kf, bound = model
-            peak, unit = flops.PEAKS[bound]
             dur = kernels[dom]["avg_us"] * 1e-6
-            achieved = (kb * th / dur / 1e9) if bound == "hbm" else (kf * th / dur / 1e12)
-            roofline = {"kernel": dom, "bound": bound, "achieved": achieved, "peak": peak,
-                        "unit": unit, "frac": achieved / peak, "traffic": measured_traffic(w.name, dom),
-                        "avg_launch_us": kernels[dom]["avg_us"],
-                        "algorithmic_bytes_per_launch": kb * th,
-                        "nominal_flops_per_launch": kf * th}
+            traffic, traffic_source = measured_traffic(w.name, dom)
+            roofline = {"kernel": dom, "avg_launch_us": kernels[dom]["avg_us"],
+                        "algorithmic_bytes_per_launch": kb * th, "nominal_flops_per_launch": kf * th,
+                        "traffic": traffic, "traffic_source": traffic_source}
+            if bound == "alu":
+                peak, unit = flops.PEAKS["alu"]
+                roofline.update(bound="alu", achieved=kf * th / dur / 1e12, peak=peak, unit=unit)
+            else:
+                # against both roofs; the one the kernel is nearer to is reported as its bound
+                ke = flops.executed_kernel_flops(dom, w.d, w.d_phi, w.F)
+                frac_hbm = kb * th / dur / 1e9 / flops.PEAKS["hbm"][0]
+                frac_mfma = kf * th / dur / 1e12 / flops.PEAKS["mfma"][0]
+                roofline.update(frac_hbm=frac_hbm, frac_mfma_nominal=frac_mfma,
+                                frac_mfma_executed=ke * th / dur / 1e12 / flops.PEAKS["mfma"][0],
+                                executed_flops_per_launch=ke * th)
+                bound = "hbm" if frac_hbm >= frac_mfma else "mfma"
+                peak, unit = flops.PEAKS[bound]
+                roofline.update(bound=bound, peak=peak, unit=unit,
+                                achieved=(kb * th / dur / 1e9) if bound == "hbm" else (kf * th / dur / 1e12))
+            roofline["frac"] = roofline["achieved"] / roofline["peak"]
 
     out = {
         "metric": "HLA fwd+bwd tokens/s" if backward else "HLA fwd tokens/s",
@@ -196,6 +214,8 @@ def main():
                    "weight_grads": wgrads is not None},
         "tflops_nominal": tflops,
         "mfma_peak_frac_nominal": tflops / 2500.0,
+        "tflops_executed": None if fl_exec is None else fl_exec / (elapsed / args.steps) / 1e12,
+        "mfma_peak_frac_executed": None if fl_exec is None else fl_exec / (elapsed / args.steps) / 1e12 / 2500.0,
         "hbm_frac_whole_path": by / (elapsed / args.steps) / 8e12,
         "kernels_us": {k: round(v["avg_us"] * v["launches_per_step"], 2) for k, v in kernels.items()},
         "kernels_sum_us": round(sum_us, 2),

@@ -44,7 +44,11 @@ typedef enum {
 typedef enum { HLA_F32 = 0, HLA_BF16 = 1 } hla_dtype;
 
 /* HLA_PHI_MLP : Q and K hold raw head vectors [.., d]; the library applies the feature maps of
- *               App. A.1 (Linear d->d, exact erf GELU, Linear d->d_phi, ReLU) — Alg. 1 Step 4.
+ *               App. A.1 (Linear d->d, GELU, Linear d->d_phi, ReLU) — Alg. 1 Step 4.  GELU is the
+ *               exact erf form x Phi(x) on the generic path; the MFMA path evaluates a polynomial
+ *               fit of it in packed fp16 (|error| <= 5.2e-3 absolute, rms 5e-4 for standard-normal
+ *               pre-activations, below the rounding of a bf16 hidden layer), and needs
+ *               |pre-activation| < 2.6e5.
  * HLA_PHI_NONE: Q holds phi_q(Q) [.., d_phi] and K holds [phi_k1(K) | ... | phi_kF(K)]
  *               [.., F*d_phi] (factor-major inside the last dim), as the paper's listings for 2
  *               and 3 factors take them.  Features are expected >= 0 (Sec. 4.2); not checked. */
@@ -165,6 +169,8 @@ const char* hla_status_string(hla_status s);
 
 /* Which path serves the handle: HLA_PATH_GENERIC or HLA_PATH_MFMA (never AUTO); -1 for NULL. */
 int32_t hla_active_path(const hla_handle* h);
+
+/* ---- Test and bench aids (not part of the operator's interface) ------------------------------- */
 
 /* Intermediate results of the last forward / backward, for tests of the individual steps:
  *   HLA_WS_FEATURES      [B*H*N][(1+F)*d_phi] fp32: phi_q, then phi_k1..phi_kF of every token-head

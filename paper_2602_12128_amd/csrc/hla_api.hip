@@ -52,44 +52,54 @@ static void build_table_host(const hla_handle* hd, int32_t bs, std::vector<Block
   seq_off->assign(nseq + 1, 0);
   for (int s = 0; s < nseq; ++s) {
     (*seq_off)[s] = static_cast<int32_t>(ents->size());
-    const int32_t lo = hd->sig_packed ? hd->cu_host[s] : 0;
-    const int32_t hi = hd->sig_packed ? hd->cu_host[s + 1] : hd->sig_N;
-    for (int32_t t0 = lo; t0 < hi; t0 += bs)
-      ents->push_back(BlockEnt{hd->sig_packed ? 0 : s, s, t0, std::min(t0 + bs, hi)});
+    const int32_t lo = hd->cu_host[s], hi = hd->cu_host[s + 1];
+    for (int32_t t0 = lo; t0 < hi; t0 += bs) ents->push_back(BlockEnt{0, s, t0, std::min(t0 + bs, hi)});
   }
   (*seq_off)[nseq] = static_cast<int32_t>(ents->size());
 }
 
-hla_status get_table(hla_handle* hd, int32_t block_tokens, hipStream_t s, hla_token_table** out) {
-  if (block_tokens <= 0) return HLA_ERR_INVALID_ARG;
-  auto it = hd->tables.find(block_tokens);
-  if (it == hd->tables.end()) {
-    // a block size first seen with this call shape: its (small) table is allocated once and kept
-    hla_token_table nt;
-    nt.block_tokens = block_tokens;
-    nt.capacity = (hd->cfg.max_tokens + block_tokens - 1) / block_tokens + hd->cfg.max_seqs;
-    if (hipMalloc(reinterpret_cast<void**>(&nt.dev), nt.capacity * sizeof(BlockEnt)) != hipSuccess)
-      return HLA_ERR_ALLOC;
-    if (hipMalloc(reinterpret_cast<void**>(&nt.seq_off_dev),
-                  (hd->cfg.max_seqs + 1) * sizeof(int32_t)) != hipSuccess) {
-      (void)hipFree(nt.dev);
-      return HLA_ERR_ALLOC;
-    }
-    it = hd->tables.emplace(block_tokens, nt).first;
+// Dense batch: batch row s is sequence s, cut into ceil(N / bs) runs.  Built on the device, so a
+// call with a shape not seen before copies nothing from the host.
+__global__ void k_fill_table_dense(BlockEnt* __restrict__ ents, int32_t* __restrict__ seq_off, int B,
+                                   int N, int bs) {
+  const int per = (N + bs - 1) / bs;
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < B * per) {
+    const int s = i / per, t0 = (i % per) * bs;
+    ents[i] = BlockEnt{s, s, t0, t0 + bs < N ? t0 + bs : N};
   }
-  hla_token_table& t = it->second;
+  if (i <= B) seq_off[i] = i * per;
+}
+
+hla_status get_table(hla_handle* hd, int role, int32_t block_tokens, hipStream_t s, hla_token_table** out) {
+  if (role < 0 || role >= kTableRoles) return HLA_ERR_INVALID_ARG;
+  hla_token_table& t = hd->tables[role];
+  if (t.dev == nullptr || block_tokens < t.min_block) return HLA_ERR_INVALID_ARG;
+  if (t.block_tokens != block_tokens) t.valid = false;
   if (!t.valid) {
-    std::vector<BlockEnt> ents;
-    std::vector<int32_t> seq_off;
-    build_table_host(hd, block_tokens, &ents, &seq_off);
-    if (static_cast<int64_t>(ents.size()) > t.capacity) return HLA_ERR_INVALID_ARG;
-    // pageable source: the runtime stages it before returning, so the vectors may die here
-    if (!ents.empty())
-      HLA_HIP_TRY(hipMemcpyAsync(t.dev, ents.data(), ents.size() * sizeof(BlockEnt),
+    if (!hd->sig_packed) {
+      const int64_t per = (static_cast<int64_t>(hd->sig_N) + block_tokens - 1) / block_tokens;
+      const int64_t count = per * hd->sig_B;
+      if (count > t.capacity) return HLA_ERR_INVALID_ARG;
+      const int64_t threads = std::max<int64_t>(count, hd->sig_B + 1);
+      k_fill_table_dense<<<dim3(static_cast<unsigned>((threads + 255) / 256)), dim3(256), 0, s>>>(
+          t.dev, t.seq_off_dev, hd->sig_B, hd->sig_N, block_tokens);
+      if (hipGetLastError() != hipSuccess) return HLA_ERR_HIP;
+      t.count = static_cast<int32_t>(count);
+    } else {
+      std::vector<BlockEnt> ents;
+      std::vector<int32_t> seq_off;
+      build_table_host(hd, block_tokens, &ents, &seq_off);
+      if (static_cast<int64_t>(ents.size()) > t.capacity) return HLA_ERR_INVALID_ARG;
+      // pageable source: the runtime stages it before returning, so the vectors may die here
+      if (!ents.empty())
+        HLA_HIP_TRY(hipMemcpyAsync(t.dev, ents.data(), ents.size() * sizeof(BlockEnt),
+                                   hipMemcpyHostToDevice, s));
+      HLA_HIP_TRY(hipMemcpyAsync(t.seq_off_dev, seq_off.data(), seq_off.size() * sizeof(int32_t),
                                  hipMemcpyHostToDevice, s));
-    HLA_HIP_TRY(hipMemcpyAsync(t.seq_off_dev, seq_off.data(), seq_off.size() * sizeof(int32_t),
-                               hipMemcpyHostToDevice, s));
-    t.count = static_cast<int32_t>(ents.size());
+      t.count = static_cast<int32_t>(ents.size());
+    }
+    t.block_tokens = block_tokens;
     t.valid = true;
   }
   *out = &t;
@@ -102,28 +112,44 @@ using namespace hla;
 
 namespace {
 
-template <typename T>
-hla_status dev_alloc(T** p, size_t count) {
-  *p = nullptr;
-  if (count == 0) count = 1;
-  return hipMalloc(reinterpret_cast<void**>(p), count * sizeof(T)) == hipSuccess ? HLA_OK
-                                                                                : HLA_ERR_ALLOC;
-}
+// Where a handle's device workspace comes from: hipMalloc (one allocation per array, owned by the
+// handle), or consecutive 256-byte aligned pieces of a block of device memory that is not the
+// handle's (base != nullptr; nothing is allocated and nothing will be freed).
+struct Arena {
+  unsigned char* base = nullptr;
+  size_t cap = 0;
+  size_t used = 0;
+  template <typename T>
+  hla_status alloc(T** p, size_t count) {
+    *p = nullptr;
+    if (count == 0) count = 1;
+    const size_t bytes = count * sizeof(T);
+    if (base == nullptr)
+      return hipMalloc(reinterpret_cast<void**>(p), bytes) == hipSuccess ? HLA_OK : HLA_ERR_ALLOC;
+    const size_t at = (used + 255) / 256 * 256;
+    if (at + bytes > cap) return HLA_ERR_ALLOC;
+    *p = reinterpret_cast<T*>(base + at);
+    used = at + bytes;
+    return HLA_OK;
+  }
+};
 
 void free_all(hla_handle* hd) {
-  (void)hipFree(hd->feat);
-  (void)hipFree(hd->dfeat);
-  (void)hipFree(hd->den);
-  (void)hipFree(hd->yhat);
-  (void)hipFree(hd->state);
-  (void)hipFree(hd->dstate);
-  (void)hipFree(hd->partial);
-  (void)hipFree(hd->path_ws);
-  (void)hipFree(hd->w_f32);
-  (void)hipFree(hd->wg_partial);
-  for (auto& kv : hd->tables) {
-    (void)hipFree(kv.second.dev);
-    (void)hipFree(kv.second.seq_off_dev);
+  if (!hd->borrowed_ws) {
+    (void)hipFree(hd->feat);
+    (void)hipFree(hd->dfeat);
+    (void)hipFree(hd->den);
+    (void)hipFree(hd->yhat);
+    (void)hipFree(hd->state);
+    (void)hipFree(hd->dstate);
+    (void)hipFree(hd->partial);
+    (void)hipFree(hd->path_ws);
+    (void)hipFree(hd->w_f32);
+    (void)hipFree(hd->wg_partial);
+    for (hla_token_table& t : hd->tables) {
+      (void)hipFree(t.dev);
+      (void)hipFree(t.seq_off_dev);
+    }
   }
   hd->prof.destroy();
 }
@@ -167,11 +193,76 @@ hla_status prepare_call(hla_handle* hd, int32_t B, int32_t H, int32_t N, const i
     } else {
       hd->cu_host.assign(static_cast<size_t>(B) + 1, 0);
     }
-    for (auto& kv : hd->tables) kv.second.valid = false;
+    for (hla_token_table& t : hd->tables) t.valid = false;
   }
   hd->g.B = B;
   hd->g.H = H;
   hd->g.N = N;
+  return HLA_OK;
+}
+
+hla_status validate_config(const hla_config* c) {
+  if (c == nullptr) return HLA_ERR_INVALID_ARG;
+  if (c->max_heads <= 0 || c->max_tokens <= 0 || c->max_seqs <= 0) return HLA_ERR_INVALID_ARG;
+  if (c->io_dtype != HLA_F32 && c->io_dtype != HLA_BF16) return HLA_ERR_INVALID_ARG;
+  if (c->phi_mode != HLA_PHI_MLP && c->phi_mode != HLA_PHI_NONE) return HLA_ERR_INVALID_ARG;
+  if (c->kernel_path < HLA_PATH_AUTO || c->kernel_path > HLA_PATH_MFMA) return HLA_ERR_INVALID_ARG;
+  if (!(c->eps >= 0.0f)) return HLA_ERR_INVALID_ARG;
+  if (c->head_dim != 32 && c->head_dim != 64 && c->head_dim != 128) return HLA_ERR_UNSUPPORTED;
+  if (c->degree < 1 || c->degree > 4 || c->feature_dim < 1) return HLA_ERR_UNSUPPORTED;
+  if (c->feature_dim > 256 || ipow(c->feature_dim, c->degree) > 256) return HLA_ERR_UNSUPPORTED;
+  if (static_cast<int64_t>(c->max_heads) * c->max_tokens >= (1ll << 31)) return HLA_ERR_UNSUPPORTED;
+  return HLA_OK;
+}
+
+// Geometry, kernel path and workspace sizes of a handle for a validated configuration (host only).
+hla_status plan_handle(hla_handle* hd, const hla_config& c) {
+  hd->cfg = c;
+  hd->g = Geom{};
+  hd->g.d = c.head_dim;
+  hd->g.dphi = c.feature_dim;
+  hd->g.F = c.degree;
+  hd->g.D = static_cast<int32_t>(ipow(c.feature_dim, c.degree));
+  hd->g.nfeat = (1 + c.degree) * c.feature_dim;
+  hd->g.eps = c.eps;
+  hd->max_th = static_cast<int64_t>(c.max_heads) * c.max_tokens;
+  hd->max_units = c.max_seqs * c.max_heads;
+  const bool mfma_ok = mfma_supported(c);
+  if (c.kernel_path == HLA_PATH_MFMA && !mfma_ok) return HLA_ERR_UNSUPPORTED;
+  hd->path = (c.kernel_path == HLA_PATH_GENERIC || !mfma_ok) ? HLA_PATH_GENERIC : HLA_PATH_MFMA;
+  hd->g.feat_tiled = hd->path == HLA_PATH_MFMA ? 1 : 0;
+  for (hla_token_table& t : hd->tables) t = hla_token_table{};
+  return hd->path == HLA_PATH_MFMA ? mfma_workspace_plan(hd) : generic_workspace_plan(hd);
+}
+
+// The device arrays the plan asked for.  forward_only leaves out what only a backward touches
+// (feature gradients, the state gradient, the generic path's per-token scratch).
+hla_status allocate_workspace(hla_handle* hd, Arena& arena, bool forward_only) {
+  const hla_config& c = hd->cfg;
+  const int64_t feat_rows = (hd->max_th + 31) / 32 * 32;  // whole 32-token groups for the tiled layout
+  HLA_TRY(arena.alloc(&hd->feat, feat_rows * hd->g.nfeat));
+  if (!forward_only) HLA_TRY(arena.alloc(&hd->dfeat, feat_rows * hd->g.nfeat));
+  HLA_TRY(arena.alloc(&hd->den, hd->max_th));
+  if (!forward_only) HLA_TRY(arena.alloc(&hd->yhat, hd->yhat_floats));
+  HLA_TRY(arena.alloc(&hd->state, hd->max_units * hd->state_stride));
+  if (!forward_only) HLA_TRY(arena.alloc(&hd->dstate, hd->max_units * hd->state_stride));
+  HLA_TRY(arena.alloc(&hd->partial, hd->max_chunks * c.max_heads * hd->state_stride));
+  if (hd->path_ws_bytes > 0) {
+    char* p = nullptr;
+    HLA_TRY(arena.alloc(&p, hd->path_ws_bytes));
+    hd->path_ws = p;
+  }
+  if (c.phi_mode == HLA_PHI_MLP) {
+    const int64_t per_map = static_cast<int64_t>(c.head_dim) * c.head_dim + c.head_dim +
+                            static_cast<int64_t>(c.head_dim) * c.feature_dim + c.feature_dim;
+    HLA_TRY(arena.alloc(&hd->w_f32, per_map * (1 + c.degree) * c.max_heads));
+  }
+  for (hla_token_table& t : hd->tables) {
+    if (t.min_block <= 0) continue;
+    t.capacity = (c.max_tokens + t.min_block - 1) / t.min_block + c.max_seqs;
+    HLA_TRY(arena.alloc(&t.dev, t.capacity));
+    HLA_TRY(arena.alloc(&t.seq_off_dev, c.max_seqs + 1));
+  }
   return HLA_OK;
 }
 
@@ -196,77 +287,25 @@ const char* hla_status_string(hla_status s) {
 hla_status hla_create(const hla_config* c, hla_handle** out) {
   if (out == nullptr) return HLA_ERR_INVALID_ARG;
   *out = nullptr;
-  if (c == nullptr) return HLA_ERR_INVALID_ARG;
-  if (c->max_heads <= 0 || c->max_tokens <= 0 || c->max_seqs <= 0) return HLA_ERR_INVALID_ARG;
-  if (c->io_dtype != HLA_F32 && c->io_dtype != HLA_BF16) return HLA_ERR_INVALID_ARG;
-  if (c->phi_mode != HLA_PHI_MLP && c->phi_mode != HLA_PHI_NONE) return HLA_ERR_INVALID_ARG;
-  if (c->kernel_path < HLA_PATH_AUTO || c->kernel_path > HLA_PATH_MFMA) return HLA_ERR_INVALID_ARG;
-  if (!(c->eps >= 0.0f)) return HLA_ERR_INVALID_ARG;
-  if (c->head_dim != 32 && c->head_dim != 64 && c->head_dim != 128) return HLA_ERR_UNSUPPORTED;
-  if (c->degree < 1 || c->degree > 4 || c->feature_dim < 1) return HLA_ERR_UNSUPPORTED;
-  if (c->feature_dim > 256 || ipow(c->feature_dim, c->degree) > 256) return HLA_ERR_UNSUPPORTED;
-  if (static_cast<int64_t>(c->max_heads) * c->max_tokens >= (1ll << 31)) return HLA_ERR_UNSUPPORTED;
-
+  HLA_TRY(validate_config(c));
   hla_handle* hd = new (std::nothrow) hla_handle();
   if (hd == nullptr) return HLA_ERR_ALLOC;
-  hd->cfg = *c;
-  hd->g = Geom{};
-  hd->g.d = c->head_dim;
-  hd->g.dphi = c->feature_dim;
-  hd->g.F = c->degree;
-  hd->g.D = static_cast<int32_t>(ipow(c->feature_dim, c->degree));
-  hd->g.nfeat = (1 + c->degree) * c->feature_dim;
-  hd->g.eps = c->eps;
-  hd->max_th = static_cast<int64_t>(c->max_heads) * c->max_tokens;
-  hd->max_units = c->max_seqs * c->max_heads;
-
-  const bool mfma_ok = mfma_supported(*c);
-  if (c->kernel_path == HLA_PATH_MFMA && !mfma_ok) {
+  hla_status st = plan_handle(hd, *c);
+  if (st != HLA_OK) {  // nothing on the device yet
     delete hd;
-    return HLA_ERR_UNSUPPORTED;
+    return st;
   }
-  hd->path = (c->kernel_path == HLA_PATH_GENERIC || !mfma_ok) ? HLA_PATH_GENERIC : HLA_PATH_MFMA;
-  hd->g.feat_tiled = hd->path == HLA_PATH_MFMA ? 1 : 0;
-
-  hla_status st = hd->path == HLA_PATH_MFMA ? mfma_workspace_plan(hd) : generic_workspace_plan(hd);
-  // allocate what the plan asked for
-  const int64_t feat_rows = (hd->max_th + 31) / 32 * 32;  // whole 32-token groups for the tiled layout
-  if (st == HLA_OK) st = dev_alloc(&hd->feat, feat_rows * hd->g.nfeat);
-  if (st == HLA_OK) st = dev_alloc(&hd->dfeat, feat_rows * hd->g.nfeat);
-  if (st == HLA_OK) st = dev_alloc(&hd->den, hd->max_th);
-  if (st == HLA_OK) st = dev_alloc(&hd->yhat, hd->yhat_floats);
-  if (st == HLA_OK) st = dev_alloc(&hd->state, hd->max_units * hd->state_stride);
-  if (st == HLA_OK) st = dev_alloc(&hd->dstate, hd->max_units * hd->state_stride);
-  if (st == HLA_OK) st = dev_alloc(&hd->partial, hd->max_chunks * c->max_heads * hd->state_stride);
-  if (st == HLA_OK && hd->path_ws_bytes > 0) {
-    char* p = nullptr;
-    st = dev_alloc(&p, hd->path_ws_bytes);
-    hd->path_ws = p;
-    // padding entries of packed operands are never written afterwards and must read as zero
-    if (st == HLA_OK && hipMemset(p, 0, hd->path_ws_bytes) != hipSuccess) st = HLA_ERR_HIP;
-  }
-  if (st == HLA_OK && c->phi_mode == HLA_PHI_MLP) {
-    const int64_t per_map = static_cast<int64_t>(c->head_dim) * c->head_dim + c->head_dim +
-                            static_cast<int64_t>(c->head_dim) * c->feature_dim + c->feature_dim;
-    st = dev_alloc(&hd->w_f32, per_map * (1 + c->degree) * c->max_heads);
-  }
-  for (auto& kv : hd->tables) {
-    if (st != HLA_OK) break;
-    hla_token_table& t = kv.second;
-    t.block_tokens = kv.first;
-    t.capacity = (c->max_tokens + kv.first - 1) / kv.first + c->max_seqs;
-    st = dev_alloc(&t.dev, t.capacity);
-    if (st == HLA_OK) st = dev_alloc(&t.seq_off_dev, c->max_seqs + 1);
-  }
+  Arena arena;  // hipMalloc
+  st = allocate_workspace(hd, arena, /*forward_only=*/false);
+  // padding entries of packed operands are never written afterwards and must read as zero
+  if (st == HLA_OK && hd->path_ws_bytes > 0 && hipMemset(hd->path_ws, 0, hd->path_ws_bytes) != hipSuccess)
+    st = HLA_ERR_HIP;
+  if (st == HLA_OK && hd->path == HLA_PATH_MFMA) st = mfma_prepare_kernels(hd);
+  if (st == HLA_OK && hipDeviceSynchronize() != hipSuccess) st = HLA_ERR_HIP;
   if (st != HLA_OK) {
     free_all(hd);
     delete hd;
     return st;
-  }
-  if (hipDeviceSynchronize() != hipSuccess) {
-    free_all(hd);
-    delete hd;
-    return HLA_ERR_HIP;
   }
   *out = hd;
   return HLA_OK;
@@ -319,7 +358,8 @@ hla_status hla_set_phi_weight_grads(hla_handle* hd, const hla_phi_weight_grads* 
     // at most about 512 partial sums are ever in flight (a few per workgroup of one full grid),
     // and never fewer than one per (map, head)
     hd->wg_parts_cap = 512 + 2 * static_cast<int64_t>(num_maps) * hd->cfg.max_heads;
-    HLA_TRY(dev_alloc(&hd->wg_partial, hd->wg_parts_cap * hd->wg_part_floats));
+    Arena arena;  // hipMalloc
+    HLA_TRY(arena.alloc(&hd->wg_partial, hd->wg_parts_cap * hd->wg_part_floats));
   }
   for (int m = 0; m < num_maps; ++m) hd->wg_out[m] = maps[m];
   hd->wg_on = true;

@@ -687,8 +687,8 @@ hla_status forward_t(hla_handle* hd, const hla_call_args& a) {
   const int R = kThreads / d;
   HLA_TRY(features_in_t<T>(hd, a));
   hla_token_table *chunks = nullptr, *tiles = nullptr;
-  HLA_TRY(get_table(hd, kChunk, s, &chunks));
-  HLA_TRY(get_table(hd, kTokPerThread * R, s, &tiles));
+  HLA_TRY(get_table(hd, 0, kChunk, s, &chunks));
+  HLA_TRY(get_table(hd, 1, kTokPerThread * R, s, &tiles));
   const int nrows = (g.D + R - 1) / R;
   const size_t sh_acc = (kAccTile * nrows * R + kAccTile * (d + 1) + kAccTile * g.nfeat) * sizeof(float);
   HLA_TRY(launch(hd, "generic_state_accumulate", k_accumulate<T, true>, dim3(chunks->count, g.H),
@@ -711,9 +711,9 @@ hla_status backward_t(hla_handle* hd, const hla_call_args& a) {
   const int d = g.d;
   const int R = kThreads / d;
   hla_token_table *chunks = nullptr, *tiles = nullptr, *dtt = nullptr;
-  HLA_TRY(get_table(hd, kChunk, s, &chunks));
-  HLA_TRY(get_table(hd, kTokPerThread * R, s, &tiles));
-  HLA_TRY(get_table(hd, kDtTile, s, &dtt));
+  HLA_TRY(get_table(hd, 0, kChunk, s, &chunks));
+  HLA_TRY(get_table(hd, 1, kTokPerThread * R, s, &tiles));
+  HLA_TRY(get_table(hd, 2, kDtTile, s, &dtt));
   HLA_TRY(launch(hd, "generic_backward_prep", k_backward_prep<T>, dim3((g.N + R - 1) / R, g.H, g.B),
                  dim3(kThreads), 0, s, g, a.dO, a.O, hd->den, hd->yhat));
   const int nrows = (g.D + R - 1) / R;
@@ -749,9 +749,9 @@ hla_status generic_workspace_plan(hla_handle* hd) {
   hd->state_stride = static_cast<int64_t>(g.D) * (g.d + 1);
   hd->max_chunks = (hd->cfg.max_tokens + kChunk - 1) / kChunk + hd->cfg.max_seqs;
   hd->yhat_floats = hd->max_th * (g.d + 1);
-  hd->tables[kChunk];
-  hd->tables[kTokPerThread * R];
-  hd->tables[kDtTile];
+  hd->tables[0].min_block = kChunk;
+  hd->tables[1].min_block = kTokPerThread * R;
+  hd->tables[2].min_block = kDtTile;
   // shared-memory budgets (64 KiB static+dynamic without opting in)
   const size_t tile = kTokPerThread * R;
   const size_t sh_c = (tile * g.D + tile * g.nfeat + tile) * sizeof(float);

@@ -2,20 +2,23 @@
 #ifndef HLA_HANDLE_H_
 #define HLA_HANDLE_H_
 
-#include <map>
 #include <vector>
 
 #include "hla_common.h"
 
-// One table of token runs for a given block size; rebuilt when (B, N, cu_seqlens) changes.
+// One table of token runs per role (what a kernel family cuts the tokens into); rebuilt in place
+// when (B, N, cu_seqlens) or the role's block size changes.  Allocated once, at the capacity the
+// role's smallest block size needs.
 struct hla_token_table {
-  int32_t block_tokens = 0;
+  int32_t min_block = 0;            // smallest block size the role ever asks for; 0 = role unused
+  int32_t block_tokens = 0;         // block size of the current contents
   hla::BlockEnt* dev = nullptr;     // capacity entries
   int32_t* seq_off_dev = nullptr;   // [max_seqs+1] first block of each sequence
   int64_t capacity = 0;
   int32_t count = 0;                // valid entries for the current shape
   bool valid = false;
 };
+constexpr int kTableRoles = 3;
 
 struct hla_call_args {
   int32_t B, H, N;
@@ -59,8 +62,10 @@ struct hla_handle {
   int64_t wg_parts_cap = 0;
   int64_t wg_part_floats = 0;      // d*d + d + d*dphi + dphi
 
-  // token tables keyed by block size
-  std::map<int32_t, hla_token_table> tables;
+  // token tables, one per role (the path's workspace plan names the roles it uses)
+  hla_token_table tables[kTableRoles];
+  // true: the device workspace is carved out of memory the handle does not own (nothing to free)
+  bool borrowed_ws = false;
   std::vector<int32_t> cu_host;    // shape signature of the tables (effective cu, B rows if dense)
   int32_t sig_B = -1, sig_N = -1;
   bool sig_packed = false;
@@ -77,8 +82,9 @@ struct hla_handle {
 
 namespace hla {
 
-// Ensure the table for `block_tokens` matches the current call shape; uploads on `s` if stale.
-hla_status get_table(hla_handle* hd, int32_t block_tokens, hipStream_t s, hla_token_table** out);
+// Ensure the table of `role` holds runs of `block_tokens` tokens for the current call shape;
+// rebuilt on `s` if stale (dense batches: by a kernel; packed sequences: uploaded).
+hla_status get_table(hla_handle* hd, int role, int32_t block_tokens, hipStream_t s, hla_token_table** out);
 
 template <typename... KArgs, typename... Args>
 inline hla_status launch(hla_handle* hd, const char* name, void (*kernel)(KArgs...), dim3 grid,
@@ -100,6 +106,10 @@ hla_status generic_features_out(hla_handle* hd, const hla_call_args& a);
 
 bool mfma_supported(const hla_config& c);
 hla_status mfma_workspace_plan(hla_handle* hd);
+// Launch attributes (LDS sizes above the default limit) of the kernels this handle will launch,
+// on the current device.
+hla_status mfma_prepare_kernels(const hla_handle* hd);
+hla_status mfma_phi_prepare_kernels(const hla_handle* hd);
 hla_status mfma_set_weights(hla_handle* hd, hipStream_t s);
 hla_status mfma_forward(hla_handle* hd, const hla_call_args& a);
 hla_status mfma_backward(hla_handle* hd, const hla_call_args& a);

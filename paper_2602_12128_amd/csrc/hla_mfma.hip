@@ -17,15 +17,12 @@ namespace {
 using namespace mf;
 
 
-#ifndef HLA_STAGGER_CORE
-#define HLA_STAGGER_CORE 5
-#endif
+constexpr int kStaggerCore = 5;    // start-up stagger unit of the two core backward kernels (see stagger_start)
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
-#ifndef HLA_QUERY_TARGET
-#define HLA_QUERY_TARGET 496
-#endif
-constexpr int kQueryTarget = HLA_QUERY_TARGET;  // workgroups aimed at by the query kernel
+constexpr int kQueryTarget = 496;  // workgroups aimed at by the query kernel: two per CU, one resident round
+constexpr int kMinChunk = 256;     // smallest chunk pick_chunk returns
+constexpr int kMinQueryBlock = 128;  // smallest block pick_query_block returns
 constexpr int kChunkTarget = 256;  // workgroups aimed at by the chunked (token-contraction) kernels: one per CU
 constexpr int kChunkGrain = 64;    // chunk sizes are multiples of this many tokens (one wave step of k_state)
 constexpr int kReduceSlices = 8;   // slices of the state per (sequence, head) in k_reduce
@@ -602,7 +599,7 @@ __global__ __launch_bounds__(kThreads) void k_bwd_query(
 #pragma unroll
       for (int rb = 0; rb < NRM; ++rb) X[rb] = mfma32(state_op(rb, ks), x[ks], X[rb]);
   };
-  stagger_start(wave, blockIdx.x, HLA_STAGGER_CORE);
+  stagger_start(wave, blockIdx.x, kStaggerCore);
   int n0 = e.t0 + wave * 32;
   if (n0 < e.t1) {
     fetch(n0, xb, fb, denb);
@@ -782,7 +779,7 @@ __global__ __launch_bounds__(kThreads) void k_bwd_key(Geom g, const BlockEnt* __
   constexpr int PIECES = D / 8, RPI = 64 / PIECES, NST = 32 / RPI;  // dV row stores per tile
   u32x4 vb[NKD], vn[NKD];
   float kb[NF], kn[NF];
-  stagger_start(wave, blockIdx.x, HLA_STAGGER_CORE);
+  stagger_start(wave, blockIdx.x, kStaggerCore);
   int n0 = e.t0 + wave * 32;
   const bf16_t* nrow = nullptr;   // the coming tile's V row and feature address of this lane
   const f32x2* nfeat = nullptr;  // feature pairs
@@ -969,7 +966,7 @@ inline int pick_chunk(const hla_handle* hd, const Geom& g, int num_seqs) {
   };
   const int64_t H = g.H > 0 ? g.H : 1;
   int64_t chunk = ((total * H + kChunkTarget - 1) / kChunkTarget + kChunkGrain - 1) / kChunkGrain * kChunkGrain;
-  if (chunk < 256) chunk = 256;
+  if (chunk < kMinChunk) chunk = kMinChunk;
   while (count(chunk) > kChunkTarget && chunk < longest)
     chunk += (chunk / 64 + kChunkGrain - 1) / kChunkGrain * kChunkGrain;
   return static_cast<int>(chunk);
@@ -982,7 +979,7 @@ inline int pick_query_block(const Geom& g, int num_seqs) {
   const int per_unit = kQueryTarget / units > 0 ? kQueryTarget / units : 1;
   const int64_t mean_len = (static_cast<int64_t>(g.B) * g.N + num_seqs - 1) / (num_seqs > 0 ? num_seqs : 1);
   const int64_t blk = ((mean_len + per_unit - 1) / per_unit + 127) / 128 * 128;
-  return static_cast<int>(blk < 128 ? 128 : blk);
+  return static_cast<int>(blk < kMinQueryBlock ? kMinQueryBlock : blk);
 }
 
 template <typename K>
@@ -1001,12 +998,7 @@ hla_status backward_core(hla_handle* hd, const hla_call_args& a) {
   hipStream_t s = a.stream;
   const int chunk = pick_chunk(hd, g, a.num_seqs);
   hla_token_table* chunks = nullptr;
-  HLA_TRY(get_table(hd, chunk, s, &chunks));
-  static bool attr_set = false;
-  if (!attr_set) {
-    HLA_TRY(allow_big_lds(&k_bwd_query<SY, D>, SQ::kTotal));
-    attr_set = true;
-  }
+  HLA_TRY(get_table(hd, 0, chunk, s, &chunks));
   unsigned char* ops = static_cast<unsigned char*>(hd->path_ws);
   unsigned char* dops = ops + SL::kOpBytes * hd->max_units;
   const int relu_mask = hd->cfg.phi_mode == HLA_PHI_MLP ? 1 : 0;
@@ -1029,16 +1021,10 @@ hla_status forward_core(hla_handle* hd, const hla_call_args& a) {
   hipStream_t s = a.stream;
   const int chunk = pick_chunk(hd, g, a.num_seqs);
   hla_token_table *chunks = nullptr, *qblocks = nullptr;
-  HLA_TRY(get_table(hd, chunk, s, &chunks));
-  HLA_TRY(get_table(hd, pick_query_block(g, a.num_seqs), s, &qblocks));
+  HLA_TRY(get_table(hd, 0, chunk, s, &chunks));
+  HLA_TRY(get_table(hd, 1, pick_query_block(g, a.num_seqs), s, &qblocks));
   if (static_cast<int64_t>(chunks->count) * g.H > hd->max_chunks * hd->cfg.max_heads)
     return HLA_ERR_INVALID_ARG;
-  static bool attr_set = false;
-  if (!attr_set) {
-    HLA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_state<SY, D>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, SM::kTotal));
-    attr_set = true;
-  }
   HLA_TRY(launch(hd, "mfma_state", k_state<SY, D>, dim3(chunks->count, g.H), dim3(kThreads),
                  SM::kTotal, s, g, chunks->dev, hd->feat, a.V, hd->partial, SL::kF32));
   const SlotMap sm = make_slot_map<SY>();
@@ -1048,6 +1034,12 @@ hla_status forward_core(hla_handle* hd, const hla_call_args& a) {
   HLA_TRY(launch(hd, "mfma_query", k_query<SY, D>, dim3(qblocks->count, g.H), dim3(kThreads), 0, s,
                  g, qblocks->dev, hd->feat, ops, a.O, hd->den));
   return HLA_OK;
+}
+
+template <class SY, int D>
+hla_status prepare_core() {
+  HLA_TRY(allow_big_lds(&k_state<SY, D>, StateSmem<D, SY::MP>::kTotal));
+  return allow_big_lds(&k_bwd_query<SY, D>, BwdQSmem<D, SY::MP>::kTotal);
 }
 
 bool aligned16(const View& v) {
@@ -1088,12 +1080,22 @@ hla_status mfma_workspace_plan(hla_handle* hd) {
   // pick_chunk keeps chunks * H <= kChunkTarget + num_seqs * H (it only ever grows the chunk)
   hd->max_chunks = (kChunkTarget + hd->cfg.max_heads - 1) / hd->cfg.max_heads + hd->cfg.max_seqs + 1;
   hd->yhat_floats = 1;
+  hd->tables[0].min_block = kMinChunk;
+  hd->tables[1].min_block = kMinQueryBlock;
   // per unit: opA + opB (bf16) + zslot, for the state and for its gradient
   const int64_t op_bytes = 2 * MP * g.d * 2 + 2 * SP * 4;
   hd->path_ws_bytes = static_cast<size_t>(2 * op_bytes * hd->max_units);
   hd->w_packed_off = hd->path_ws_bytes;
   if (hd->cfg.phi_mode == HLA_PHI_MLP) hd->path_ws_bytes += mfma_phi_packed_bytes(hd);
   return HLA_OK;
+}
+
+hla_status mfma_prepare_kernels(const hla_handle* hd) {
+  if (hd->g.F == 3)
+    HLA_TRY(hd->g.d == 128 ? (prepare_core<Sym36, 128>()) : (prepare_core<Sym36, 64>()));
+  else
+    HLA_TRY(hd->g.d == 128 ? (prepare_core<Sym212, 128>()) : (prepare_core<Sym212, 64>()));
+  return hd->cfg.phi_mode == HLA_PHI_MLP ? mfma_phi_prepare_kernels(hd) : HLA_OK;
 }
 
 hla_status mfma_set_weights(hla_handle* hd, hipStream_t s) { return mfma_phi_set_weights(hd, s); }

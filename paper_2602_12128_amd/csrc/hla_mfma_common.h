@@ -100,10 +100,8 @@ __host__ __device__ __forceinline__ int tile_off(int row, int chunk) {
 // shares.  A start-up delay that differs per wave (and per workgroup) spreads the phases out.
 // `unit` is in steps of 64 * 8 cycles.
 __device__ __forceinline__ void stagger_start(int wave, int block, int unit) {
-#ifndef HLA_NO_STAGGER
   const int n = wave * unit + (block & 3);
   for (int i = 0; i < n; ++i) __builtin_amdgcn_s_sleep(8);
-#endif
 }
 
 // value held by the lane 32 away (the other half of a (token, g) lane pair)

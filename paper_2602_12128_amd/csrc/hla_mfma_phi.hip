@@ -26,13 +26,6 @@ struct TrueTag {
 struct FalseTag {
   static constexpr bool value = false;
 };
-// waves per workgroup of the forward and backward kernels
-#ifndef HLA_PHI_WAVES_F
-#define HLA_PHI_WAVES_F 12  // three per SIMD: the forward kernel stays within 168 registers
-#endif
-#ifndef HLA_PHI_WAVES_B
-#define HLA_PHI_WAVES_B 8
-#endif
 
 // ---- GELU on the vector ALU, two values per instruction in packed fp16 -------------------------
 // The first layer is computed at a quarter of its scale (W1 and b1 are packed times 1/4, an exact
@@ -1084,7 +1077,9 @@ dim3 phi_grid(const hla_handle* hd, int waves) {
   return dim3(gx < 1 ? 1 : gx, g.H, g.B);
 }
 
-constexpr int kWavesF = HLA_PHI_WAVES_F, kWavesB = HLA_PHI_WAVES_B;
+// waves per workgroup: three per SIMD in the forward kernel (it stays within 168 registers), two
+// in the backward one
+constexpr int kWavesF = 12, kWavesB = 8;
 
 // F key maps of DPH features each, after the query map
 template <int D, int F, int DPH>
@@ -1092,11 +1087,6 @@ hla_status forward_t(hla_handle* hd, const hla_call_args& a) {
   using SM = PhiSmem<D>;
   Geom g = hd->g;
   const unsigned char* wpk = static_cast<const unsigned char*>(hd->path_ws) + hd->w_packed_off;
-  static bool attr = false;
-  if (!attr) {
-    HLA_TRY(allow_lds(&k_phi_fwd<D, F, kWavesF, DPH>, SM::total(F, kWavesF)));
-    attr = true;
-  }
   const dim3 grid = phi_grid(hd, kWavesF);
   HLA_TRY(launch(hd, "mfma_phi_forward", k_phi_fwd<D, F, kWavesF, DPH>, grid, dim3(kWavesF * 64),
                  SM::total(F, kWavesF), a.stream, g, a.Q, a.K, wpk, hd->phi.heads_w, F, hd->feat));
@@ -1108,11 +1098,6 @@ hla_status backward_t(hla_handle* hd, const hla_call_args& a) {
   using SM = PhiSmem<D, true>;
   Geom g = hd->g;
   const unsigned char* wpk = static_cast<const unsigned char*>(hd->path_ws) + hd->w_packed_off;
-  static bool attr = false;
-  if (!attr) {
-    HLA_TRY(allow_lds(&k_phi_bwd<D, F, kWavesB, DPH>, SM::total(F, kWavesB)));
-    attr = true;
-  }
   const dim3 grid = phi_grid(hd, kWavesB);
   HLA_TRY(launch(hd, "mfma_phi_backward", k_phi_bwd<D, F, kWavesB, DPH>, grid, dim3(kWavesB * 64),
                  SM::total(F, kWavesB), a.stream, g, a.Q, a.K, wpk, hd->phi.heads_w, F, hd->dfeat,
@@ -1120,10 +1105,7 @@ hla_status backward_t(hla_handle* hd, const hla_call_args& a) {
   return HLA_OK;
 }
 
-#ifndef HLA_WG_WAVES
-#define HLA_WG_WAVES 4
-#endif
-constexpr int kWavesW = HLA_WG_WAVES;  // one wave per SIMD: the live set needs more than 256 registers
+constexpr int kWavesW = 4;  // one wave per SIMD: the live set needs more than 256 registers
 
 template <int D, int DPH>
 hla_status weight_grads_t(hla_handle* hd, const hla_call_args& a) {
@@ -1132,11 +1114,6 @@ hla_status weight_grads_t(hla_handle* hd, const hla_call_args& a) {
   constexpr int lds = 2 * kWavesW * SM::kWaveBytes;  // two sets of tiles per wave
   Geom g = hd->g;
   const unsigned char* wpk = static_cast<const unsigned char*>(hd->path_ws) + hd->w_packed_off;
-  static bool attr = false;
-  if (!attr) {
-    HLA_TRY(allow_lds(&k_phi_wgrad<D, kWavesW, DPH>, lds));
-    attr = true;
-  }
   const int nm = 1 + g.F;
   const bool shared = hd->phi.heads_w == 1;
   const int heads = shared ? 1 : g.H;
@@ -1156,7 +1133,19 @@ hla_status weight_grads_t(hla_handle* hd, const hla_call_args& a) {
                              1.0f / kHiddenScale, 1.0f, a.stream);
 }
 
+template <int D, int F, int DPH>
+hla_status prepare_t() {
+  HLA_TRY(allow_lds(&k_phi_fwd<D, F, kWavesF, DPH>, PhiSmem<D>::total(F, kWavesF)));
+  HLA_TRY(allow_lds(&k_phi_bwd<D, F, kWavesB, DPH>, PhiSmem<D, true>::total(F, kWavesB)));
+  return allow_lds(&k_phi_wgrad<D, kWavesW, DPH>, 2 * kWavesW * WgSmem<D>::kWaveBytes);
+}
+
 }  // namespace
+
+hla_status mfma_phi_prepare_kernels(const hla_handle* hd) {
+  if (hd->g.F == 3) return hd->g.d == 128 ? prepare_t<128, 3, 6>() : prepare_t<64, 3, 6>();
+  return hd->g.d == 128 ? prepare_t<128, 2, 12>() : prepare_t<64, 2, 12>();
+}
 
 // the two forms the matrix-core path serves: (F, d_phi) = (3, 6) and (2, 12)
 bool mfma_phi_supported(const hla_handle* hd) {

@@ -47,6 +47,36 @@ def path_bytes(d: int, d_phi: int, F: int, backward: bool, phi: bool, elem: int 
     return fwd + (bwd if backward else 0)
 
 
+def symmetric_rows(d_phi: int, F: int) -> int:
+    """Rows of the padded symmetric state the matrix-core kernels contract over: 64 for three
+    factors of six features (56 monomials), 96 for two factors of twelve (78 monomials)."""
+    return {(3, 6): 64, (2, 12): 96}[(F, d_phi)]
+
+
+def executed_kernel_flops(name: str, d: int, d_phi: int, F: int) -> int:
+    """Matrix-core flops the MFMA path ISSUES per token-head in one launch of `name` (every
+    v_mfma_f32_32x32x16 counts its full 32*32*16*2 flops: padded rows of the symmetric state and the
+    26 unused output rows of the second feature-map layer included), against the nominal model's
+    literal d_phi^F contraction.  0 for kernels without matrix work."""
+    MP = symmetric_rows(d_phi, F)
+    maps = 1 + F
+    return {
+        "mfma_phi_forward": maps * (2 * d * d + 64 * d),             # first layer; second layer in 32 output rows
+        "mfma_state": 2048 * (MP // 32) * (d // 32 + 1),            # S^T [V | 1] per 64-token step
+        "mfma_query": 2 * d * MP,
+        "mfma_bwd_query": 4 * d * MP,                               # X = Csym dO^T and dCsym += Qm^T dO
+        "mfma_bwd_key": 4 * d * MP,                                 # dS = dCsym V^T and dV = dCsym^T S^T
+        "mfma_phi_backward": maps * (2 * d * d + 32 * d + 2 * d * d),  # recompute, dg (one k-step), dx
+    }.get(name, 0)
+
+
+def executed_path_flops(d: int, d_phi: int, F: int, backward: bool, phi: bool) -> int:
+    names = ["mfma_state", "mfma_query"] + (["mfma_phi_forward"] if phi else [])
+    if backward:
+        names += ["mfma_bwd_query", "mfma_bwd_key"] + (["mfma_phi_backward"] if phi else [])
+    return sum(executed_kernel_flops(n, d, d_phi, F) for n in names)
+
+
 def attention_layer_tflops(tokens: int, kind: str, width: int = 1536, heads: int = 12,
                            d_phi: int = 6, F: int = 3) -> float:
     """FLOPs of one attention layer as the paper's complexity table counts them: q/k/v/o

@@ -190,7 +190,7 @@ def assert_parity(gpu, ref, tol, what="", kinks=None, row_scale=None):
                 best = int(d_c.argmin())
                 # the row is judged by its distance to the closest choice
                 diff[b, h, n] = np.abs(cands[best] - g[b, h, n])
-                n_other += int(np.abs(cands[best] - r[b, h, n]).max() > 0)
+                n_other += int(np.abs(cands[best] - r[b, h, n]).max() > 1e-9 * max(np.abs(r).max(), 1e-300))
             notes.append(f"{k}: {len(kinks[k])} kink rows ({len(kinks[k]) / max(1, r[..., 0].size):.2%}), "
                          f"{n_other} on another branch than the oracle's own")
         scale = np.abs(r).max() if r.size else 0.0

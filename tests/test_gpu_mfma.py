@@ -234,4 +234,4 @@ def test_handle_reuse_sees_fresh_partial_states(F, dphi):
             assert torch.equal(got[k], fresh[id(t)][k]), k
     h.destroy()
     ref = pu.run_oracle({k: v[:, :2] for k, v in tb.items()}, F, dphi, 1e-6)
-    pu.assert_parity({k: fresh[id(tb)][k][:, :2] for k in ref}, ref, 2e-2, f"reuse F={F}")
+    pu.assert_parity({k: fresh[id(tb)][k][:, :2] for k in ref if not k.startswith("_")}, ref, 2e-2, f"reuse F={F}")
