@@ -378,16 +378,19 @@ __device__ __forceinline__ void phi_fwd_body(const Geom& g, const View& X,
     // vector ALU evaluates GELU on block t, the matrix pipe works on block t + 1, two MFMAs
     // between quarters of the vector work, their LDS operands read one quarter ahead.  Blocks
     // past the last map alias the last map's LDS: their results are never used.
-    f32x16 cur, nxt;
+    // hidden blocks alternate between two accumulator sets (NRB is even, so block 0 of every map
+    // lands in set 0): no copy from "next" to "current" at the end of a stage
+    static_assert(NRB % 2 == 0, "two alternating accumulator sets");
+    f32x16 hb[2];
     constexpr int kPer = NKS / 4;  // first-layer MFMAs per slice
     u32x4 an[kPer];                // their A operands, read one slice ahead
     {
       u32x4 a0[NKS];
 #pragma unroll
       for (int ks = 0; ks < NKS; ++ks) a0[ks] = *reinterpret_cast<const u32x4*>(smem + a_off[ks]);
-      cur = bias_acc(smem, 0);
+      hb[0] = bias_acc(smem, 0);
 #pragma unroll
-      for (int ks = 0; ks < NKS; ++ks) cur = mfma32(a0[ks], xb[ks], cur);
+      for (int ks = 0; ks < NKS; ++ks) hb[0] = mfma32(a0[ks], xb[ks], hb[0]);
 #pragma unroll
       for (int t = 0; t < kPer; ++t)
         an[t] = *reinterpret_cast<const u32x4*>(smem + (1 % NRB) * 32 * SM::kRow + a_off[t]);
@@ -407,6 +410,8 @@ __device__ __forceinline__ void phi_fwd_body(const Geom& g, const View& X,
         const unsigned char* w2 = rb + 2 < NRB ? wm : (last_map ? wm : wm + SM::kMap);
         const unsigned char* a1_base = w1 + ((rb + 1) % NRB) * 32 * SM::kRow;
         const unsigned char* a2_base = w2 + ((rb + 2) % NRB) * 32 * SM::kRow;
+        f32x16& cur = hb[rb % 2];
+        f32x16& nxt = hb[(rb + 1) % 2];
         nxt = bias_acc(w1, (rb + 1) % NRB);
         const u32x4 a20 = *reinterpret_cast<const u32x4*>(wm + SM::kW1 + ((2 * rb) * 64 + lane) * 16);
         const u32x4 a21 = *reinterpret_cast<const u32x4*>(wm + SM::kW1 + ((2 * rb + 1) * 64 + lane) * 16);
@@ -430,8 +435,7 @@ __device__ __forceinline__ void phi_fwd_body(const Geom& g, const View& X,
           if (j == 3) u = mfma32_f16(a20, gb[0], u);
           // the next tile's inputs: xb is free once the last first-layer MFMA has been issued
           if (last_map && rb == NRB - 2 && j == 3 && more_tiles) load_x<D>(X, b, h, n0 + r, g.N, gl, xb);
-          float in[4] = {cur[4 * j], cur[4 * j + 1], cur[4 * j + 2], cur[4 * j + 3]};
-          asm volatile("" : "+v"(in[0]), "+v"(in[1]), "+v"(in[2]), "+v"(in[3]));  // not nxt: that would wait for the MFMAs
+          const float in[4] = {cur[4 * j], cur[4 * j + 1], cur[4 * j + 2], cur[4 * j + 3]};
           __builtin_amdgcn_sched_barrier(0);
           uint32_t out[2];
           gelu_f16<2>(in, out);
@@ -441,7 +445,6 @@ __device__ __forceinline__ void phi_fwd_body(const Geom& g, const View& X,
           __builtin_amdgcn_sched_barrier(0);
         }
         u = mfma32_f16(a21, gb[1], u);
-        cur = nxt;
       }
       // The store is held back until the next map (or the next tile's input wait) has been passed:
       // stores count in the same wait counter as loads, and a store issued just before that wait
@@ -592,16 +595,17 @@ __device__ __forceinline__ void phi_bwd_body(const Geom& g, const View& X,
     // the MFMAs two or three at a time between quarters of the vector-ALU work, their LDS
     // operands read one step ahead.  Blocks before the first / after the last alias valid LDS
     // and meet zero operands or are dropped.
-    f32x16 cur, nxt;
+    static_assert(NRB % 2 == 0, "two alternating accumulator sets");
+    f32x16 hb[2];  // hidden blocks alternate between two accumulator sets (as in the forward)
     constexpr int kPer = NKS / 4;  // first-layer MFMAs per slice
     u32x4 an[kPer];                // their A operands, read one slice ahead
     {
       u32x4 a0[NKS];
 #pragma unroll
       for (int ks = 0; ks < NKS; ++ks) a0[ks] = *reinterpret_cast<const u32x4*>(smem + a_off[ks]);
-      cur = bias_acc(smem, 0);
+      hb[0] = bias_acc(smem, 0);
 #pragma unroll
-      for (int ks = 0; ks < NKS; ++ks) cur = mfma32(a0[ks], xb[ks], cur);
+      for (int ks = 0; ks < NKS; ++ks) hb[0] = mfma32(a0[ks], xb[ks], hb[0]);
 #pragma unroll
       for (int t = 0; t < kPer; ++t)
         an[t] = *reinterpret_cast<const u32x4*>(smem + (1 % NRB) * 32 * SM::kRow + a_off[t]);
@@ -626,6 +630,8 @@ __device__ __forceinline__ void phi_bwd_body(const Geom& g, const View& X,
         const int ks2p = 2 * ((rb + NRB - 1) % NRB);  // first of the two 16-slot steps of block t-1
         const u32x4 a2 = *reinterpret_cast<const u32x4*>(wm + SM::kW1 + (rb * 64 + lane) * 16);
         const f32x16 dg = mfma32(a2, dub, zero_acc());
+        f32x16& cur = hb[rb % 2];
+        f32x16& nxt = hb[(rb + 1) % 2];
         nxt = bias_acc(rb + 1 < NRB ? wm : (last_map ? wm : wm + SM::kMap), (rb + 1) % NRB);
         u32x4 dhc[2];
         // transpose-read operands of the first dx step of this stage
@@ -673,8 +679,7 @@ __device__ __forceinline__ void phi_bwd_body(const Geom& g, const View& X,
           }
           // the next tile's inputs: xb is free once the last first-layer MFMA has been issued
           if (last_map && rb == NRB - 2 && j == 3 && more_tiles) load_x<D>(X, b, h, n0 + r, g.N, gl, xb);
-          float in[4] = {cur[4 * j], cur[4 * j + 1], cur[4 * j + 2], cur[4 * j + 3]};
-          asm volatile("" : "+v"(in[0]), "+v"(in[1]), "+v"(in[2]), "+v"(in[3]));
+          const float in[4] = {cur[4 * j], cur[4 * j + 1], cur[4 * j + 2], cur[4 * j + 3]};
           __builtin_amdgcn_sched_barrier(0);
           f16x2 gp[2];
           gelu_grad_f16<2>(in, gp);
@@ -690,7 +695,6 @@ __device__ __forceinline__ void phi_bwd_body(const Geom& g, const View& X,
         }
         dhp[0] = dhc[0];
         dhp[1] = dhc[1];
-        cur = nxt;
       }
       dub = finish_du(dvn, last_map ? live_nx : live);  // after the last map: the coming tile's
     };

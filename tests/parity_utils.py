@@ -223,7 +223,8 @@ def assert_weight_grad_parity(gpu_wg, ref_wg, tol, what="", branches=None):
     branch choices of the in-band (token, feature) pairs, so the library must agree with
     base + sum choice_p contrib_p for ONE assignment of choices in {0, 1}: the assignment is
     fitted by least squares over all four arrays of the map, rounded to {0, 1}, and the
-    residual of that single assignment is what is measured."""
+    rounded and refined by single flips, and the residual of that single assignment is what is
+    measured."""
     worst = {}
     for m, (g, r) in enumerate(zip(gpu_wg, ref_wg)):
         per_head = branches is not None and isinstance(branches[m], list)
@@ -247,12 +248,30 @@ def assert_weight_grad_parity(gpu_wg, ref_wg, tol, what="", branches=None):
             A = np.stack([np.concatenate([(c[i] / scale[i]).ravel() for i in range(4)]) for c in contribs], axis=1)
             coef = np.linalg.lstsq(A, resid, rcond=None)[0]
             choice = coef > 0.5
-            fit = resid - A @ choice.astype(np.float64)
-            off = 0
+            bounds = np.cumsum([0] + [got[k].size for k in WG_KEYS])
+
+            def per_array(c):
+                fit = resid - A @ c.astype(np.float64)
+                return [float(np.abs(fit[bounds[i]:bounds[i + 1]]).max()) for i in range(4)]
+
+            # The least-squares fit is dominated by the largest array; a pair whose contribution
+            # there is below the arithmetic's noise can come out on the wrong side of 1/2 and
+            # still matter for a six-entry bias gradient.  Refine the rounded assignment by
+            # single flips that lower the worst array error until none does.
+            errs = per_array(choice)
+            for _ in range(4):
+                improved = False
+                for pi in range(len(pairs)):
+                    choice[pi] = not choice[pi]
+                    e2 = per_array(choice)
+                    if max(e2) < max(errs):
+                        errs, improved = e2, True
+                    else:
+                        choice[pi] = not choice[pi]
+                if not improved:
+                    break
             for i, k in enumerate(WG_KEYS):
-                n = got[k].size
-                worst[k + tag] = float(np.abs(fit[off:off + n]).max())
-                off += n
+                worst[k + tag] = errs[i]
             slack = [float(sum(np.abs(c[i]) for c in contribs).max() / scale[i]) for i in range(4)]
             flips = int((choice != np.asarray(own_choice)).sum())
             print(f"[parity]   {what} map {m}{' head %d' % hh if per_head else ''}: {len(pairs)} in-band pairs, "
