@@ -36,7 +36,8 @@ typedef enum {
   HLA_ERR_UNSUPPORTED = 2, /* (F, d_phi, d, dtype, strides) combination no kernel covers */
   HLA_ERR_ALLOC = 3,       /* hipMalloc / host allocation failed */
   HLA_ERR_HIP = 4,         /* a HIP runtime call failed (launch, copy) */
-  HLA_ERR_STATE = 5        /* call order: backward without weights, weights in PHI_NONE mode, ... */
+  HLA_ERR_STATE = 5,       /* call order: backward without weights, weights in PHI_NONE mode, ... */
+  HLA_ERR_TOO_LARGE = 6    /* hla_forward_static: the call's workspace exceeds HLA_STATIC_SCRATCH_BYTES */
 } hla_status;
 
 /* I/O element type of Q, K, V, O, dO, dQ, dK, dV and of the feature-map weights.  Accumulation
@@ -160,6 +161,23 @@ typedef struct {
  * failure). */
 hla_status hla_set_phi_weight_grads(hla_handle* h, const hla_phi_weight_grads* maps,
                                     int32_t num_maps);
+
+/* hla_forward for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  No handle: the workspace (features, chunk
+ * partial states, the reduced state, token tables) lives in a static device array of
+ * HLA_STATIC_SCRATCH_BYTES inside the library, one copy per GPU, held until the process ends.  The
+ * call allocates nothing on the device, copies nothing from the host and never synchronises; it
+ * runs the same kernels as hla_forward and returns the same bits.
+ *   - HLA_PHI_NONE only (Q and K hold features, see hla_phi_mode); dense batches only (every
+ *     batch row one sequence).  config->max_heads / max_tokens / max_seqs are ignored: the
+ *     workspace is laid out for exactly (B, H, N).
+ *   - HLA_ERR_TOO_LARGE if that layout needs more than HLA_STATIC_SCRATCH_BYTES (about 2e5
+ *     token-heads B*H*N for the three-factor form at head_dim 128); outputs are then untouched.
+ *   - All calls on one GPU share the array and it keeps the last call's contents: calls that
+ *     overlap on one GPU (two streams, two threads) race.  Calls on one stream are ordered. */
+#define HLA_STATIC_SCRATCH_BYTES (32u << 20)
+hla_status hla_forward_static(const hla_config* config, int32_t B, int32_t H, int32_t N, hla_tensor Q,
+                              hla_tensor K, hla_tensor V, hla_tensor O, void* hip_stream);
 
 /* Release the workspace.  Synchronises the device first.  NULL is accepted. */
 hla_status hla_destroy(hla_handle* h);

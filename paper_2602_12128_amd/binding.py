@@ -22,7 +22,7 @@ HLA_PATH_AUTO, HLA_PATH_GENERIC, HLA_PATH_MFMA = 0, 1, 2
 EXPORTS = (
     "hla_create", "hla_set_phi_weights", "hla_forward", "hla_backward", "hla_destroy",
     "hla_status_string", "hla_active_path", "hla_profile_enable", "hla_profile_read",
-    "hla_read_workspace", "hla_set_phi_weight_grads",
+    "hla_read_workspace", "hla_set_phi_weight_grads", "hla_forward_static",
 )
 HLA_WS_FEATURES, HLA_WS_FEATURE_GRADS, HLA_WS_DENOMINATORS = 0, 1, 2
 
@@ -85,6 +85,9 @@ def load_library() -> C.CDLL:
     lib.hla_backward.argtypes = [H, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32),
                                  C.c_int32] + [hla_tensor] * 8 + [C.c_void_p]
     lib.hla_backward.restype = C.c_int
+    lib.hla_forward_static.argtypes = [C.POINTER(hla_config), C.c_int32, C.c_int32, C.c_int32,
+                                       hla_tensor, hla_tensor, hla_tensor, hla_tensor, C.c_void_p]
+    lib.hla_forward_static.restype = C.c_int
     lib.hla_destroy.argtypes = [H]
     lib.hla_destroy.restype = C.c_int
     lib.hla_status_string.argtypes = [C.c_int]
@@ -124,6 +127,20 @@ def _stream_ptr(stream) -> int:
     import torch
     s = stream if stream is not None else torch.cuda.current_stream()
     return s.cuda_stream
+
+
+HLA_STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def hla_forward_static(Q, K, V, O, feature_dim: int = 6, degree: int = 3, eps: float = 1e-6,
+                       io_dtype: int = HLA_BF16, kernel_path: int = HLA_PATH_AUTO, stream=None):
+    """hla_forward_static of the C ABI: the forward on features (HLA_PHI_NONE), dense batch, no
+    handle and no device allocation (the workspace is a static array inside the library)."""
+    lib = load_library()
+    B, H, N, d = V.shape
+    cfg = hla_config(d, feature_dim, degree, eps, io_dtype, HLA_PHI_NONE, kernel_path, 1, 1, 1)
+    _check(lib.hla_forward_static(C.byref(cfg), B, H, N, _view(Q), _view(K), _view(V), _view(O),
+                                  _stream_ptr(stream)), "hla_forward_static")
 
 
 class HLA:

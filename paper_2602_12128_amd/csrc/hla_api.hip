@@ -6,6 +6,11 @@
 
 #include "hla_handle.h"
 
+// Workspace of hla_forward_static: one copy per GPU, for as long as the process lives.  In host
+// code this name is only a handle for hipGetSymbolAddress; the address kernels and fills use is
+// the one that call returns, kept per device in g_static below.
+static __device__ __align__(256) unsigned char scratch[HLA_STATIC_SCRATCH_BYTES];
+
 namespace hla {
 
 // ---- profiler ---------------------------------------------------------------------------------
@@ -127,7 +132,7 @@ struct Arena {
     if (base == nullptr)
       return hipMalloc(reinterpret_cast<void**>(p), bytes) == hipSuccess ? HLA_OK : HLA_ERR_ALLOC;
     const size_t at = (used + 255) / 256 * 256;
-    if (at + bytes > cap) return HLA_ERR_ALLOC;
+    if (at + bytes > cap) return HLA_ERR_TOO_LARGE;
     *p = reinterpret_cast<T*>(base + at);
     used = at + bytes;
     return HLA_OK;
@@ -280,6 +285,7 @@ const char* hla_status_string(hla_status s) {
     case HLA_ERR_ALLOC: return "HLA_ERR_ALLOC";
     case HLA_ERR_HIP: return "HLA_ERR_HIP";
     case HLA_ERR_STATE: return "HLA_ERR_STATE";
+    case HLA_ERR_TOO_LARGE: return "HLA_ERR_TOO_LARGE";
   }
   return "HLA_ERR_UNKNOWN";
 }
@@ -448,6 +454,98 @@ hla_status hla_backward(hla_handle* hd, int32_t B, int32_t H, int32_t N, const i
   HLA_TRY(hd->path == HLA_PATH_MFMA ? mfma_backward(hd, a) : generic_backward(hd, a));
   if (hd->wg_on) HLA_TRY(phi_weight_grads(hd, a));
   return HLA_OK;
+}
+
+// ---- forward without a handle ---------------------------------------------------------------------
+namespace {
+
+__global__ void k_fill_zero(uint32_t* __restrict__ p, int64_t words) {
+  for (int64_t i = blockIdx.x * static_cast<int64_t>(blockDim.x) + threadIdx.x; i < words;
+       i += static_cast<int64_t>(gridDim.x) * blockDim.x)
+    p[i] = 0u;
+}
+
+constexpr int kMaxDevices = 64;
+struct StaticSlot {
+  unsigned char* ptr = nullptr;  // device address of this GPU's copy of `scratch`
+  hla_handle* hd = nullptr;      // host-side bookkeeping; its device pointers point into `scratch`
+  bool planned = false;          // hd is laid out for `cfg`
+  hla_config cfg{};
+};
+StaticSlot g_static[kMaxDevices];
+
+bool same_config(const hla_config& a, const hla_config& b) {
+  return a.head_dim == b.head_dim && a.feature_dim == b.feature_dim && a.degree == b.degree &&
+         a.eps == b.eps && a.io_dtype == b.io_dtype && a.phi_mode == b.phi_mode &&
+         a.kernel_path == b.kernel_path && a.max_heads == b.max_heads &&
+         a.max_tokens == b.max_tokens && a.max_seqs == b.max_seqs;
+}
+
+}  // namespace
+
+hla_status hla_forward_static(const hla_config* config, int32_t B, int32_t H, int32_t N, hla_tensor Q,
+                              hla_tensor K, hla_tensor V, hla_tensor O, void* hip_stream) {
+  if (config == nullptr || B < 0 || H < 0 || N < 0) return HLA_ERR_INVALID_ARG;
+  if (config->phi_mode != HLA_PHI_NONE) return HLA_ERR_UNSUPPORTED;
+  if (B == 0 || H == 0 || N == 0) return HLA_OK;
+  if (bad_view(Q) || bad_view(K) || bad_view(V) || bad_view(O)) return HLA_ERR_INVALID_ARG;
+  // the workspace is laid out for exactly this call's sizes
+  hla_config c = *config;
+  c.max_heads = H;
+  c.max_tokens = static_cast<int64_t>(B) * N;
+  c.max_seqs = B;
+  HLA_TRY(validate_config(&c));
+  int dev = -1;
+  HLA_HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return HLA_ERR_UNSUPPORTED;
+  StaticSlot& sl = g_static[dev];
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  if (sl.ptr == nullptr) {  // first call on this device
+    void* p = nullptr;
+    HLA_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (p == nullptr) return HLA_ERR_HIP;
+    hla_handle* hd = new (std::nothrow) hla_handle();
+    if (hd == nullptr) return HLA_ERR_ALLOC;
+    sl.hd = hd;
+    sl.ptr = static_cast<unsigned char*>(p);
+  }
+  hla_handle* hd = sl.hd;
+  if (!sl.planned || !same_config(sl.cfg, c)) {
+    sl.planned = false;
+    *hd = hla_handle();
+    hd->borrowed_ws = true;
+    HLA_TRY(plan_handle(hd, c));
+    Arena arena;
+    arena.base = sl.ptr;
+    arena.cap = HLA_STATIC_SCRATCH_BYTES;
+    HLA_TRY(allocate_workspace(hd, arena, /*forward_only=*/true));  // HLA_ERR_TOO_LARGE: does not fit
+    if (hd->path == HLA_PATH_MFMA) HLA_TRY(mfma_prepare_kernels(hd));
+    // the array keeps what the last call left: padding entries of the packed operands must read
+    // as zero (a fill kernel rather than a memset node, so that the call can be captured)
+    if (hd->path_ws_bytes > 0) {
+      const int64_t words = static_cast<int64_t>(hd->path_ws_bytes / 4);
+      k_fill_zero<<<dim3(static_cast<unsigned>(std::min<int64_t>((words + 255) / 256, 1024))), dim3(256), 0, s>>>(
+          static_cast<uint32_t*>(hd->path_ws), words);
+      if (hipGetLastError() != hipSuccess) return HLA_ERR_HIP;
+    }
+    sl.cfg = c;
+    sl.planned = true;
+  }
+  bool empty = false;
+  int32_t nseq = 0;
+  HLA_TRY(prepare_call(hd, B, H, N, nullptr, 0, &empty, &nseq));
+  hla_call_args a{};
+  a.B = B;
+  a.H = H;
+  a.N = N;
+  a.num_seqs = nseq;
+  a.packed = false;
+  a.Q = make_view(Q);
+  a.K = make_view(K);
+  a.V = make_view(V);
+  a.O = make_view(O);
+  a.stream = s;
+  return hd->path == HLA_PATH_MFMA ? mfma_forward(hd, a) : generic_forward(hd, a);
 }
 
 hla_status hla_read_workspace(hla_handle* hd, int32_t kind, float* host_dst, int64_t count,
