@@ -16,7 +16,9 @@ d_phi=1, identical-key, one-hot and N=1 closed forms; row normalisation; convexi
 invariance; homogeneity (rational-function form); the sequential state update; Lemma 4.1; GELU
 against tabulated normal-CDF values; both backward routes, and the feature-map weight gradients,
 against central finite differences; the enumeration of ReLU branch choices against the masked
-(smooth) map.  No function here is "parity unpinned".
+(smooth) map; the value modulation of Sec. 4.5 against scalar loops (LayerNorm, the map), the
+identity special case and finite differences (tests/test_oracle_value_modulation.py).  No
+function here is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -292,6 +294,75 @@ def hla_backward_bruteforce(qf, kfs, v, do, eps: float):
 
 
 # --------------------------------------------------------------------------------------------
+# Value modulation (Sec. 4.5): T <- T + phi_v1(T) * phi_v2(V), elementwise product
+# --------------------------------------------------------------------------------------------
+def layer_norm(u, gamma, beta, eps: float):
+    """LayerNorm over the last axis: (u - mean) / sqrt(var + eps) * gamma + beta, var the biased
+    (1/d) variance.  Returns (y, normalised u-hat, 1/sqrt(var + eps))."""
+    u = np.asarray(u, F64)
+    mu = u.mean(axis=-1, keepdims=True)
+    var = ((u - mu) ** 2).mean(axis=-1, keepdims=True)
+    rstd = 1.0 / np.sqrt(var + eps)
+    uhat = (u - mu) * rstd
+    return uhat * np.asarray(gamma, F64) + np.asarray(beta, F64), uhat, rstd
+
+
+class PhiVWeights:
+    """Weights of one value-modulation map phi_v (App. A.1): two linear layers d -> d -> d with
+    a GELU in between, no ReLU, and a LayerNorm (gamma, beta).  The paper's figure of the
+    network is missing from its text; the reading taken here puts the LayerNorm on the output
+    of the second layer."""
+
+    def __init__(self, W1, b1, W2, b2, gamma, beta):
+        self.W1, self.b1, self.W2, self.b2, self.gamma, self.beta = (
+            np.asarray(a, F64) for a in (W1, b1, W2, b2, gamma, beta))
+
+    def astuple(self):
+        return self.W1, self.b1, self.W2, self.b2, self.gamma, self.beta
+
+
+def phi_v_forward(x, W1, b1, W2, b2, gamma, beta, ln_eps: float):
+    """phi_v(x) = LayerNorm(GELU(x W1 + b1) W2 + b2) for rows x [N, d].
+    Returns (m [N, d], h, u-hat, rstd) -- the last three are what the backward needs."""
+    x = np.asarray(x, F64)
+    h = x @ np.asarray(W1, F64) + np.asarray(b1, F64)
+    u = gelu_erf(h) @ np.asarray(W2, F64) + np.asarray(b2, F64)
+    m, uhat, rstd = layer_norm(u, gamma, beta, ln_eps)
+    return m, h, uhat, rstd
+
+
+def phi_v_backward(dm, x, W1, b1, W2, b2, gamma, beta, ln_eps: float):
+    """Gradient w.r.t. x of a loss with gradient dm w.r.t. phi_v(x).  LayerNorm backward with
+    g = dm * gamma: du = rstd * (g - mean(g) - u-hat * mean(g * u-hat)); then the two layers as in
+    phi_backward (no ReLU)."""
+    _, h, uhat, rstd = phi_v_forward(x, W1, b1, W2, b2, gamma, beta, ln_eps)
+    g = np.asarray(dm, F64) * np.asarray(gamma, F64)
+    du = rstd * (g - g.mean(axis=-1, keepdims=True) - uhat * (g * uhat).mean(axis=-1, keepdims=True))
+    dh = (du @ np.asarray(W2, F64).T) * gelu_erf_grad(h)
+    return dh @ np.asarray(W1, F64).T
+
+
+def value_modulation_forward(t, v, pv1: PhiVWeights, pv2: PhiVWeights, ln_eps: float):
+    """Sec. 4.5: T + phi_v1(T) * phi_v2(V) (elementwise), T = A V the normalised attention output,
+    rows [N, d]."""
+    t = np.asarray(t, F64)
+    m1 = phi_v_forward(t, *pv1.astuple(), ln_eps)[0]
+    m2 = phi_v_forward(v, *pv2.astuple(), ln_eps)[0]
+    return t + m1 * m2
+
+
+def value_modulation_backward(dout, t, v, pv1: PhiVWeights, pv2: PhiVWeights, ln_eps: float):
+    """(dT, dV) of value_modulation_forward: dT = dOut + phi_v1'(T)^T (dOut * phi_v2(V)),
+    dV = phi_v2'(V)^T (dOut * phi_v1(T))."""
+    dout = np.asarray(dout, F64)
+    m1 = phi_v_forward(t, *pv1.astuple(), ln_eps)[0]
+    m2 = phi_v_forward(v, *pv2.astuple(), ln_eps)[0]
+    dt = dout + phi_v_backward(dout * m2, t, *pv1.astuple(), ln_eps)
+    dv = phi_v_backward(dout * m1, v, *pv2.astuple(), ln_eps)
+    return dt, dv
+
+
+# --------------------------------------------------------------------------------------------
 # Whole operator over batch / heads / packed sequences (Alg. 1 Steps 4-5)
 # --------------------------------------------------------------------------------------------
 class PhiWeights:
@@ -332,10 +403,11 @@ def _features(Q, K, lo, hi, b, h, F, d_phi, phi: Optional[Sequence[PhiWeights]])
 def hla_operator_forward(Q, K, V, F: int, d_phi: int, eps: float,
                          phi: Optional[Sequence[PhiWeights]] = None,
                          cu_seqlens: Optional[Sequence[int]] = None,
-                         route: str = "factorized") -> np.ndarray:
+                         route: str = "factorized", vmod=None) -> np.ndarray:
     """O [B,H,N,d] for Q,K,V [B,H,N,*].  `phi` = [phi_q, phi_k1..phi_kF] or None when Q and K
     already hold features.  Sequences (batch entries, or the packed ranges of cu_seqlens) never
-    share state."""
+    share state.  vmod = (phi_v1, phi_v2, ln_eps) applies the value modulation of Sec. 4.5 to the
+    attention output, token by token (maps shared by all heads)."""
     B, H, N = V.shape[:3]
     O = np.zeros(V.shape, F64)
     for (b, lo, hi) in _units(B, N, cu_seqlens):
@@ -350,6 +422,8 @@ def hla_operator_forward(Q, K, V, F: int, d_phi: int, eps: float,
                 O[b, h, lo:hi] = hla_bruteforce(qf, kfs, v, eps)[0]
             else:
                 raise ValueError(route)
+            if vmod is not None:
+                O[b, h, lo:hi] = value_modulation_forward(O[b, h, lo:hi], v, vmod[0], vmod[1], vmod[2])
     return O
 
 
@@ -357,13 +431,15 @@ def hla_operator_backward(Q, K, V, dO, F: int, d_phi: int, eps: float,
                           phi: Optional[Sequence[PhiWeights]] = None,
                           cu_seqlens: Optional[Sequence[int]] = None,
                           route: str = "factorized", weight_grads: bool = False,
-                          feature_grads: bool = False):
+                          feature_grads: bool = False, vmod=None):
     """(dQ, dK, dV) with the shapes of Q, K, V for L = sum(O * dO).  With feature maps, dK sums
     the contributions of the F key maps (they all read the same K).  With weight_grads (needs
     `phi`) a fourth result lists (dW1, db1, dW2, db2) for phi_q, phi_k1..phi_kF, each summed over
     every sequence, head and token that shares the map.  With feature_grads the last result is
     the gradient w.r.t. the features themselves, (dqf [B,H,N,d_phi], dkf [B,H,N,F*d_phi]), the
-    intermediate that the feature maps' backward consumes."""
+    intermediate that the feature maps' backward consumes.  vmod as in hla_operator_forward: dO
+    is then the gradient w.r.t. the modulated output; it is first taken back through the
+    modulation (to the attention output T and to V), T's share then goes through the operator."""
     B, H, N = V.shape[:3]
     dQ = np.zeros(Q.shape, F64)
     dK = np.zeros(K.shape, F64)
@@ -382,8 +458,13 @@ def hla_operator_backward(Q, K, V, dO, F: int, d_phi: int, eps: float,
         for h in range(H):
             qf, kfs = _features(Q, K, lo, hi, b, h, F, d_phi, phi)
             v = np.asarray(V[b, h, lo:hi], F64)
-            dqf, dkfs, dv = bwd(qf, kfs, v, dO[b, h, lo:hi], eps)
-            dV[b, h, lo:hi] = dv
+            do = np.asarray(dO[b, h, lo:hi], F64)
+            dv_mod = 0.0
+            if vmod is not None:
+                t = (hla_factorized if route == "factorized" else hla_bruteforce)(qf, kfs, v, eps)[0]
+                do, dv_mod = value_modulation_backward(do, t, v, vmod[0], vmod[1], vmod[2])
+            dqf, dkfs, dv = bwd(qf, kfs, v, do, eps)
+            dV[b, h, lo:hi] = dv + dv_mod
             dQf[b, h, lo:hi] = dqf
             dKf[b, h, lo:hi] = np.concatenate(dkfs, axis=1)
             if phi is None:
