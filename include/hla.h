@@ -162,6 +162,32 @@ typedef struct {
 hla_status hla_set_phi_weight_grads(hla_handle* h, const hla_phi_weight_grads* maps,
                                     int32_t num_maps);
 
+/* Value modulation (Sec. 4.5): with T the normalised attention output of the operator,
+ *     O = T + phi_v1(T) * phi_v2(V)          (elementwise product, per token and head)
+ * phi_v (App. A.1): h = x W1 + b1 (W1 [d, d]), u = GELU(h) W2 + b2 (W2 [d, d]),
+ * phi_v(x) = LayerNorm(u) * gamma + beta over the d channels (biased variance, ln_eps inside the
+ * square root).  The paper requires a LayerNorm in phi_v but its figure of the network is missing
+ * from the text: this library places it on the output of the second layer.  No ReLU.  The two
+ * maps are shared by all heads.  DEVICE pointers in io_dtype, row-major, applied from the right;
+ * the library converts them into its own workspace on `hip_stream`.
+ *
+ * maps = {phi_v1, phi_v2} switches the modulation on for the handle, maps = NULL off.  While on:
+ * hla_forward writes the modulated O and keeps T in the handle; hla_backward takes dO as the
+ * gradient w.r.t. the modulated O, carries it back through the modulation first (dV receives the
+ * share that reaches V through phi_v2 as well) and must follow a forward made in the same mode.
+ * The first registration allocates three [max_heads * max_tokens, d] arrays (synchronous;
+ * HLA_ERR_ALLOC on failure).  Gradients of the modulation's own weights are not produced. */
+typedef struct {
+  const void* W1;
+  const void* b1;
+  const void* W2;
+  const void* b2;
+  const void* gamma;
+  const void* beta;
+} hla_vmod_weights;
+hla_status hla_set_value_modulation(hla_handle* h, const hla_vmod_weights* maps, float ln_eps,
+                                    void* hip_stream);
+
 /* hla_forward for callers that cannot allocate device memory: code under HIP graph capture, tight
  * serving loops, harnesses that forbid hipMalloc.  No handle: the workspace (features, chunk
  * partial states, the reduced state, token tables) lives in a static device array of

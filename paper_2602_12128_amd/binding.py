@@ -23,6 +23,7 @@ EXPORTS = (
     "hla_create", "hla_set_phi_weights", "hla_forward", "hla_backward", "hla_destroy",
     "hla_status_string", "hla_active_path", "hla_profile_enable", "hla_profile_read",
     "hla_read_workspace", "hla_set_phi_weight_grads", "hla_forward_static",
+    "hla_set_value_modulation",
 )
 HLA_WS_FEATURES, HLA_WS_FEATURE_GRADS, HLA_WS_DENOMINATORS = 0, 1, 2
 
@@ -46,6 +47,11 @@ class hla_phi_weights(C.Structure):
 
 class hla_phi_weight_grads(C.Structure):
     _fields_ = [("dW1", C.c_void_p), ("db1", C.c_void_p), ("dW2", C.c_void_p), ("db2", C.c_void_p)]
+
+
+class hla_vmod_weights(C.Structure):
+    _fields_ = [("W1", C.c_void_p), ("b1", C.c_void_p), ("W2", C.c_void_p), ("b2", C.c_void_p),
+                ("gamma", C.c_void_p), ("beta", C.c_void_p)]
 
 
 class hla_tensor(C.Structure):
@@ -85,6 +91,8 @@ def load_library() -> C.CDLL:
     lib.hla_backward.argtypes = [H, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32),
                                  C.c_int32] + [hla_tensor] * 8 + [C.c_void_p]
     lib.hla_backward.restype = C.c_int
+    lib.hla_set_value_modulation.argtypes = [H, C.POINTER(hla_vmod_weights), C.c_float, C.c_void_p]
+    lib.hla_set_value_modulation.restype = C.c_int
     lib.hla_forward_static.argtypes = [C.POINTER(hla_config), C.c_int32, C.c_int32, C.c_int32,
                                        hla_tensor, hla_tensor, hla_tensor, hla_tensor, C.c_void_p]
     lib.hla_forward_static.restype = C.c_int
@@ -211,6 +219,25 @@ class HLA:
         self._keepalive_grads = list(maps)
         _check(self._lib.hla_set_phi_weight_grads(self._h, arr, len(maps)),
                "hla_set_phi_weight_grads")
+
+    # -- hla_set_value_modulation
+    def set_value_modulation(self, maps: Optional[Sequence[dict]], ln_eps: float = 1e-5, stream=None):
+        """maps: [phi_v1, phi_v2], each {'W1','b1','W2','b2','gamma','beta'} contiguous device
+        tensors in the I/O dtype (W1, W2 [d, d]; the rest [d]); None switches the modulation off."""
+        if maps is None:
+            _check(self._lib.hla_set_value_modulation(self._h, None, 0.0, _stream_ptr(stream)),
+                   "hla_set_value_modulation")
+            self._keepalive_vmod = None
+            return
+        arr = (hla_vmod_weights * 2)()
+        for i, m in enumerate(maps):
+            for k in ("W1", "b1", "W2", "b2", "gamma", "beta"):
+                if not m[k].is_contiguous():
+                    raise ValueError("weights must be contiguous")
+            arr[i] = hla_vmod_weights(*(m[k].data_ptr() for k in ("W1", "b1", "W2", "b2", "gamma", "beta")))
+        self._keepalive_vmod = list(maps)
+        _check(self._lib.hla_set_value_modulation(self._h, arr, ln_eps, _stream_ptr(stream)),
+               "hla_set_value_modulation")
 
     @staticmethod
     def _cu(cu_seqlens: Optional[Sequence[int]]):

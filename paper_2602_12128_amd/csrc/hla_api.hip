@@ -151,6 +151,10 @@ void free_all(hla_handle* hd) {
     (void)hipFree(hd->path_ws);
     (void)hipFree(hd->w_f32);
     (void)hipFree(hd->wg_partial);
+    (void)hipFree(hd->vmod_w);
+    (void)hipFree(hd->vmod_T);
+    (void)hipFree(hd->vmod_dT);
+    (void)hipFree(hd->vmod_dV);
     for (hla_token_table& t : hd->tables) {
       (void)hipFree(t.dev);
       (void)hipFree(t.seq_off_dev);
@@ -372,6 +376,46 @@ hla_status hla_set_phi_weight_grads(hla_handle* hd, const hla_phi_weight_grads* 
   return HLA_OK;
 }
 
+hla_status hla_set_value_modulation(hla_handle* hd, const hla_vmod_weights* maps, float ln_eps,
+                                    void* hip_stream) {
+  if (hd == nullptr) return HLA_ERR_INVALID_ARG;
+  hd->have_forward = false;
+  if (maps == nullptr) {
+    hd->vmod_on = false;
+    return HLA_OK;
+  }
+  if (!(ln_eps >= 0.0f)) return HLA_ERR_INVALID_ARG;
+  for (int m = 0; m < 2; ++m)
+    if (!maps[m].W1 || !maps[m].b1 || !maps[m].W2 || !maps[m].b2 || !maps[m].gamma || !maps[m].beta)
+      return HLA_ERR_INVALID_ARG;
+  if (hd->borrowed_ws) return HLA_ERR_STATE;
+  if (hd->vmod_w == nullptr) {
+    const int64_t d = hd->g.d;
+    const size_t elem = hd->cfg.io_dtype == HLA_F32 ? 4 : 2;
+    Arena arena;  // hipMalloc
+    char *t = nullptr, *dt = nullptr, *dv = nullptr;
+    hla_status st = arena.alloc(&hd->vmod_w, 2 * (4 * d * d + 4 * d));
+    if (st == HLA_OK) st = arena.alloc(&t, static_cast<size_t>(hd->max_th) * d * elem);
+    if (st == HLA_OK) st = arena.alloc(&dt, static_cast<size_t>(hd->max_th) * d * elem);
+    if (st == HLA_OK) st = arena.alloc(&dv, static_cast<size_t>(hd->max_th) * d * elem);
+    if (st != HLA_OK) {
+      (void)hipFree(hd->vmod_w);
+      (void)hipFree(t);
+      (void)hipFree(dt);
+      (void)hipFree(dv);
+      hd->vmod_w = nullptr;
+      return st;
+    }
+    hd->vmod_T = t;
+    hd->vmod_dT = dt;
+    hd->vmod_dV = dv;
+  }
+  HLA_TRY(vmod_set_weights(hd, maps, static_cast<hipStream_t>(hip_stream)));
+  hd->vmod_ln_eps = ln_eps;
+  hd->vmod_on = true;
+  return HLA_OK;
+}
+
 hla_status hla_forward(hla_handle* hd, int32_t B, int32_t H, int32_t N, const int32_t* cu_seqlens,
                        int32_t num_seqs, hla_tensor Q, hla_tensor K, hla_tensor V, hla_tensor O,
                        void* hip_stream) {
@@ -393,7 +437,17 @@ hla_status hla_forward(hla_handle* hd, int32_t B, int32_t H, int32_t N, const in
   a.V = make_view(V);
   a.O = make_view(O);
   a.stream = static_cast<hipStream_t>(hip_stream);
-  if (!empty) HLA_TRY(hd->path == HLA_PATH_MFMA ? mfma_forward(hd, a) : generic_forward(hd, a));
+  if (!empty) {
+    // with value modulation the operator's own output T goes to the handle and the caller's O
+    // receives T + phi_v1(T) * phi_v2(V)
+    if (hd->vmod_on) a.O = vmod_view(hd->vmod_T, hd->g);
+    HLA_TRY(hd->path == HLA_PATH_MFMA ? mfma_forward(hd, a) : generic_forward(hd, a));
+    if (hd->vmod_on) {
+      a.O = make_view(O);
+      HLA_TRY(vmod_forward(hd, a));
+    }
+  }
+  hd->fw_vmod = hd->vmod_on;
   hd->have_forward = true;
   hd->fw_B = B;
   hd->fw_H = H;
@@ -418,7 +472,7 @@ hla_status hla_backward(hla_handle* hd, int32_t B, int32_t H, int32_t N, const i
     const bool packed = cu_seqlens != nullptr;
     bool same = hd->have_forward && hd->fw_B == B && hd->fw_H == H && hd->fw_N == N &&
                 hd->fw_packed == packed && hd->fw_Q == Q.ptr && hd->fw_K == K.ptr &&
-                hd->fw_V == V.ptr;
+                hd->fw_V == V.ptr && hd->fw_vmod == hd->vmod_on;
     if (same && packed) {
       same = num_seqs >= 0 && static_cast<int32_t>(hd->fw_cu.size()) == num_seqs + 1 &&
              std::memcmp(hd->fw_cu.data(), cu_seqlens, sizeof(int32_t) * (num_seqs + 1)) == 0;
@@ -451,7 +505,15 @@ hla_status hla_backward(hla_handle* hd, int32_t B, int32_t H, int32_t N, const i
   a.dK = make_view(dK);
   a.dV = make_view(dV);
   a.stream = static_cast<hipStream_t>(hip_stream);
+  if (hd->vmod_on) {
+    // back through the modulation first: the operator then sees dT as its upstream gradient and
+    // T as its output; the modulation's share of dV is added once the operator has written dV
+    HLA_TRY(vmod_backward(hd, a));
+    a.dO = vmod_view(hd->vmod_dT, hd->g);
+    a.O = vmod_view(hd->vmod_T, hd->g);
+  }
   HLA_TRY(hd->path == HLA_PATH_MFMA ? mfma_backward(hd, a) : generic_backward(hd, a));
+  if (hd->vmod_on) HLA_TRY(vmod_add_value_grads(hd, a));
   if (hd->wg_on) HLA_TRY(phi_weight_grads(hd, a));
   return HLA_OK;
 }

@@ -62,6 +62,16 @@ struct hla_handle {
   int64_t wg_parts_cap = 0;
   int64_t wg_part_floats = 0;      // d*d + d + d*dphi + dphi
 
+  // value modulation (optional): fp32 weights of the two maps, the saved attention output T, the
+  // gradient w.r.t. T and the modulation's share of dV ([max_th][d] in the I/O dtype each)
+  bool vmod_on = false;
+  float vmod_ln_eps = 0.0f;
+  float* vmod_w = nullptr;
+  void* vmod_T = nullptr;
+  void* vmod_dT = nullptr;
+  void* vmod_dV = nullptr;
+  bool fw_vmod = false;            // mode of the last forward
+
   // token tables, one per role (the path's workspace plan names the roles it uses)
   hla_token_table tables[kTableRoles];
   // true: the device workspace is carved out of memory the handle does not own (nothing to free)
@@ -119,6 +129,14 @@ size_t mfma_phi_packed_bytes(const hla_handle* hd);
 hla_status mfma_phi_set_weights(hla_handle* hd, hipStream_t s);
 hla_status mfma_phi_forward(hla_handle* hd, const hla_call_args& a);
 hla_status mfma_phi_backward(hla_handle* hd, const hla_call_args& a);
+
+// Value modulation (hla_vmod.hip): weights into hd->vmod_w; O = T + phi_v1(T) * phi_v2(V) from
+// hd->vmod_T and a.V into a.O; (a.dO, T, V) -> hd->vmod_dT, hd->vmod_dV; a.dV += hd->vmod_dV.
+hla_status vmod_set_weights(hla_handle* hd, const hla_vmod_weights* maps, hipStream_t s);
+hla_status vmod_forward(hla_handle* hd, const hla_call_args& a);
+hla_status vmod_backward(hla_handle* hd, const hla_call_args& a);
+hla_status vmod_add_value_grads(hla_handle* hd, const hla_call_args& a);
+View vmod_view(void* p, const Geom& g);  // contiguous [B, H, N, d] view of a workspace array
 
 // Shared helper kernels' host wrappers (hla_generic.hip).
 hla_status convert_weights_to_f32(hla_handle* hd, const hla_phi_weights* maps, hipStream_t s);

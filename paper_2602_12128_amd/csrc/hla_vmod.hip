@@ -1,0 +1,324 @@
+// Value modulation (paper Sec. 4.5):  O = T + phi_v1(T) * phi_v2(V), elementwise, with T the
+// normalised attention output and phi_v (App. A.1) = Linear d->d, GELU, Linear d->d, LayerNorm.
+// Forward and the backward to (dT, dV), as fp32 vector-ALU kernels for any I/O dtype and head dim.
+// One workgroup of d threads serves a tile of tokens of one (batch row, head); thread j owns
+// hidden unit j of the first layer and channel j of everything after it.  The weights are read
+// through the caches ([in][out] order for the forward products, transposed copies for the
+// backward ones, so that every read is coalesced over the threads).
+#include <cmath>
+
+#include "hla_handle.h"
+
+namespace hla {
+namespace {
+
+constexpr int kFwdTile = 32;  // tokens per workgroup, forward
+constexpr int kBwdTile = 16;  // tokens per workgroup, backward
+
+__device__ __forceinline__ float gelu_erf(float h) {
+  return h * 0.5f * (1.0f + erff(h * 0.70710678118654752440f));
+}
+__device__ __forceinline__ float gelu_erf_grad(float h) {
+  const float cdf = 0.5f * (1.0f + erff(h * 0.70710678118654752440f));
+  const float pdf = 0.39894228040143267794f * expf(-0.5f * h * h);
+  return cdf + h * pdf;
+}
+
+// fp32 weights of the two maps, densely packed per map m in {0: phi_v1, 1: phi_v2}:
+//   W1 [d][d] (in, out), W1T [d][d], W2 [d][d], W2T [d][d], then b1, b2, gamma, beta [d] each
+struct VmodW {
+  const float* base;
+  int d;
+  __host__ __device__ int64_t per_map() const { return 4ll * d * d + 4ll * d; }
+  __device__ const float* W1(int m) const { return base + m * per_map(); }
+  __device__ const float* W1T(int m) const { return W1(m) + d * d; }
+  __device__ const float* W2(int m) const { return W1(m) + 2 * d * d; }
+  __device__ const float* W2T(int m) const { return W1(m) + 3 * d * d; }
+  __device__ const float* b1(int m) const { return W1(m) + 4 * d * d; }
+  __device__ const float* b2(int m) const { return b1(m) + d; }
+  __device__ const float* gamma(int m) const { return b1(m) + 2 * d; }
+  __device__ const float* beta(int m) const { return b1(m) + 3 * d; }
+};
+
+template <typename T>
+__global__ void k_vmod_pack(const T* W1, const T* b1, const T* W2, const T* b2, const T* gamma,
+                            const T* beta, int d, float* __restrict__ out) {
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < d * d; i += gridDim.x * blockDim.x) {
+    const int r = i / d, c = i % d;
+    out[i] = to_float(W1[i]);
+    out[d * d + c * d + r] = to_float(W1[i]);
+    out[2 * d * d + i] = to_float(W2[i]);
+    out[3 * d * d + c * d + r] = to_float(W2[i]);
+    if (i < d) {
+      out[4 * d * d + i] = to_float(b1[i]);
+      out[4 * d * d + d + i] = to_float(b2[i]);
+      out[4 * d * d + 2 * d + i] = to_float(gamma[i]);
+      out[4 * d * d + 3 * d + i] = to_float(beta[i]);
+    }
+  }
+}
+
+// One map applied to the TT rows staged in xs ([channel][token], so that a thread reads the TT
+// values of one input channel as consecutive floats): h = x W1 + b1 (kept in `hid`),
+// u = GELU(h) W2 + b2, then LayerNorm statistics per token through LDS.  On return thread j holds
+// u-hat[t][j] in `uhat`, and 1/std of token t sits in rstd_s[t] (LDS, left alone afterwards);
+// mean_s [TT] and gs are scratch.
+template <int TT>
+__device__ __forceinline__ void map_forward(const VmodW& w, int m, int d, int j, const float* xs,
+                                            float* gs, float* mean_s, float* rstd_s, float ln_eps,
+                                            float (&hid)[TT], float (&uhat)[TT]) {
+  const float* W1 = w.W1(m);
+  const float* W2 = w.W2(m);
+#pragma unroll
+  for (int t = 0; t < TT; ++t) hid[t] = 0.0f;
+  for (int i = 0; i < d; ++i) {
+    const float wv = W1[i * d + j];
+#pragma unroll
+    for (int t = 0; t < TT; ++t) hid[t] += xs[i * TT + t] * wv;
+  }
+  const float b1 = w.b1(m)[j];
+#pragma unroll
+  for (int t = 0; t < TT; ++t) {
+    hid[t] += b1;
+    gs[j * TT + t] = gelu_erf(hid[t]);
+  }
+  __syncthreads();
+  float u[TT];
+#pragma unroll
+  for (int t = 0; t < TT; ++t) u[t] = 0.0f;
+  for (int jj = 0; jj < d; ++jj) {
+    const float wv = W2[jj * d + j];
+#pragma unroll
+    for (int t = 0; t < TT; ++t) u[t] += gs[jj * TT + t] * wv;
+  }
+  const float b2 = w.b2(m)[j];
+  __syncthreads();  // everyone is done reading gs: it now carries u for the statistics
+#pragma unroll
+  for (int t = 0; t < TT; ++t) {
+    u[t] += b2;
+    gs[j * TT + t] = u[t];
+  }
+  __syncthreads();
+  if (j < TT) {  // thread t: mean and 1/std of token t over the d channels (two passes, fp32)
+    float s = 0.0f;
+    for (int c = 0; c < d; ++c) s += gs[c * TT + j];
+    const float mean = s / d;
+    float v = 0.0f;
+    for (int c = 0; c < d; ++c) {
+      const float e = gs[c * TT + j] - mean;
+      v += e * e;
+    }
+    mean_s[j] = mean;
+    rstd_s[j] = 1.0f / sqrtf(v / d + ln_eps);
+  }
+  __syncthreads();
+#pragma unroll
+  for (int t = 0; t < TT; ++t) uhat[t] = (u[t] - mean_s[t]) * rstd_s[t];
+  __syncthreads();  // mean_s and gs are free again
+}
+
+template <typename T, int TT>
+__device__ __forceinline__ void load_tile(const View& X, int b, int h, int n0, int nt, int d, int j,
+                                          float* xs) {
+  for (int t = 0; t < TT; ++t) xs[j * TT + t] = t < nt ? to_float(X.row<const T>(b, h, n0 + t)[j]) : 0.0f;
+}
+
+// grid (ceil(N / kFwdTile), H, B), block d.  Tin holds T; O receives T + phi_v1(T) * phi_v2(V).
+template <typename T>
+__global__ void k_vmod_forward(Geom g, VmodW w, float ln_eps, View Tin, View V, View O) {
+  constexpr int TT = kFwdTile;
+  extern __shared__ float smem[];
+  const int d = g.d, j = threadIdx.x;
+  float* xs = smem;             // [d][TT]
+  float* gs = xs + d * TT;      // [d][TT]
+  float* mean_s = gs + d * TT;  // [TT]
+  float* rstd_s = mean_s + TT;  // [TT]
+  const int n0 = blockIdx.x * TT, h = blockIdx.y, b = blockIdx.z;
+  const int nt = min(TT, g.N - n0);
+  float hid[TT], uhat[TT], m1[TT], tv[TT];
+  load_tile<T, TT>(Tin, b, h, n0, nt, d, j, xs);
+  __syncthreads();
+#pragma unroll
+  for (int t = 0; t < TT; ++t) tv[t] = xs[j * TT + t];
+  map_forward<TT>(w, 0, d, j, xs, gs, mean_s, rstd_s, ln_eps, hid, uhat);
+  {
+    const float ga = w.gamma(0)[j], be = w.beta(0)[j];
+#pragma unroll
+    for (int t = 0; t < TT; ++t) m1[t] = uhat[t] * ga + be;
+  }
+  load_tile<T, TT>(V, b, h, n0, nt, d, j, xs);
+  __syncthreads();
+  map_forward<TT>(w, 1, d, j, xs, gs, mean_s, rstd_s, ln_eps, hid, uhat);
+  const float ga = w.gamma(1)[j], be = w.beta(1)[j];
+  for (int t = 0; t < nt; ++t)
+    O.row<T>(b, h, n0 + t)[j] = from_float<T>(tv[t] + m1[t] * (uhat[t] * ga + be));
+}
+
+// Backward of one map for the tile: dm (gradient w.r.t. the map's output, thread j: channel j)
+// -> dx (thread j: input channel j).  LayerNorm backward with gg = dm * gamma:
+//   du = rstd (gg - mean(gg) - u-hat mean(gg u-hat)),  dg = du W2^T,  dh = dg GELU'(h),  dx = dh W1^T.
+// rstd_s [TT] is what map_forward left for this map; a_s, b_s ([d][TT]) and stats ([2][TT]) are scratch.
+template <int TT>
+__device__ __forceinline__ void map_backward(const VmodW& w, int m, int d, int j, const float (&dm)[TT],
+                                             const float (&hid)[TT], const float (&uhat)[TT],
+                                             const float* rstd_s, float* a_s, float* b_s, float* stats,
+                                             float (&dx)[TT]) {
+  const float ga = w.gamma(m)[j];
+  float gg[TT];
+#pragma unroll
+  for (int t = 0; t < TT; ++t) {
+    gg[t] = dm[t] * ga;
+    a_s[j * TT + t] = gg[t];
+    b_s[j * TT + t] = gg[t] * uhat[t];
+  }
+  __syncthreads();
+  if (j < TT) {
+    float s0 = 0.0f, s1 = 0.0f;
+    for (int c = 0; c < d; ++c) {
+      s0 += a_s[c * TT + j];
+      s1 += b_s[c * TT + j];
+    }
+    stats[j] = s0 / d;
+    stats[TT + j] = s1 / d;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int t = 0; t < TT; ++t)
+    a_s[j * TT + t] = rstd_s[t] * (gg[t] - stats[t] - uhat[t] * stats[TT + t]);  // du[t][j]
+  __syncthreads();
+  const float* W2T = w.W2T(m);  // [c][hidden]
+  float dg[TT];
+#pragma unroll
+  for (int t = 0; t < TT; ++t) dg[t] = 0.0f;
+  for (int c = 0; c < d; ++c) {
+    const float wv = W2T[c * d + j];
+#pragma unroll
+    for (int t = 0; t < TT; ++t) dg[t] += a_s[c * TT + t] * wv;
+  }
+#pragma unroll
+  for (int t = 0; t < TT; ++t) b_s[j * TT + t] = dg[t] * gelu_erf_grad(hid[t]);  // dh[t][j]
+  __syncthreads();
+  const float* W1T = w.W1T(m);  // [hidden][in]
+#pragma unroll
+  for (int t = 0; t < TT; ++t) dx[t] = 0.0f;
+  for (int jj = 0; jj < d; ++jj) {
+    const float wv = W1T[jj * d + j];
+#pragma unroll
+    for (int t = 0; t < TT; ++t) dx[t] += b_s[jj * TT + t] * wv;
+  }
+  __syncthreads();
+}
+
+// grid (ceil(N / kBwdTile), H, B), block d.  dT = dO + phi_v1'(T)^T (dO * phi_v2(V)),
+// dVm = phi_v2'(V)^T (dO * phi_v1(T)); both maps' forward values are recomputed.
+template <typename T>
+__global__ void k_vmod_backward(Geom g, VmodW w, float ln_eps, View Tin, View V, View dO, View dT,
+                                View dVm) {
+  constexpr int TT = kBwdTile;
+  extern __shared__ float smem[];
+  const int d = g.d, j = threadIdx.x;
+  float* xs = smem;               // [d][TT]  input rows, then scratch of the backward
+  float* gs = xs + d * TT;        // [d][TT]
+  float* stats = gs + d * TT;     // [2][TT]
+  float* rstd1 = stats + 2 * TT;  // [TT]
+  float* rstd2 = rstd1 + TT;      // [TT]
+  const int n0 = blockIdx.x * TT, h = blockIdx.y, b = blockIdx.z;
+  const int nt = min(TT, g.N - n0);
+  float hid1[TT], uhat1[TT], hid2[TT], uhat2[TT];
+  load_tile<T, TT>(Tin, b, h, n0, nt, d, j, xs);
+  __syncthreads();
+  map_forward<TT>(w, 0, d, j, xs, gs, stats, rstd1, ln_eps, hid1, uhat1);
+  load_tile<T, TT>(V, b, h, n0, nt, d, j, xs);
+  __syncthreads();
+  map_forward<TT>(w, 1, d, j, xs, gs, stats, rstd2, ln_eps, hid2, uhat2);
+  float dov[TT], dm[TT], dx[TT];
+#pragma unroll
+  for (int t = 0; t < TT; ++t) dov[t] = t < nt ? to_float(dO.row<const T>(b, h, n0 + t)[j]) : 0.0f;
+  const float ga1 = w.gamma(0)[j], be1 = w.beta(0)[j], ga2 = w.gamma(1)[j], be2 = w.beta(1)[j];
+#pragma unroll
+  for (int t = 0; t < TT; ++t) dm[t] = dov[t] * (uhat2[t] * ga2 + be2);  // d phi_v1(T) = dO * phi_v2(V)
+  map_backward<TT>(w, 0, d, j, dm, hid1, uhat1, rstd1, xs, gs, stats, dx);
+  for (int t = 0; t < nt; ++t) dT.row<T>(b, h, n0 + t)[j] = from_float<T>(dov[t] + dx[t]);
+#pragma unroll
+  for (int t = 0; t < TT; ++t) dm[t] = dov[t] * (uhat1[t] * ga1 + be1);  // d phi_v2(V) = dO * phi_v1(T)
+  map_backward<TT>(w, 1, d, j, dm, hid2, uhat2, rstd2, xs, gs, stats, dx);
+  for (int t = 0; t < nt; ++t) dVm.row<T>(b, h, n0 + t)[j] = from_float<T>(dx[t]);
+}
+
+// dst += src over [B, H, N, d] rows (the modulation's share of dV joins the operator's).
+template <typename T>
+__global__ void k_add_rows(Geom g, View dst, View src) {
+  const int64_t idx = blockIdx.x * static_cast<int64_t>(blockDim.x) + threadIdx.x;
+  const int64_t total = static_cast<int64_t>(g.B) * g.H * g.N * g.d;
+  if (idx >= total) return;
+  const int c = static_cast<int>(idx % g.d);
+  const int64_t th = idx / g.d;
+  const int n = static_cast<int>(th % g.N);
+  const int64_t bh = th / g.N;
+  const int h = static_cast<int>(bh % g.H), b = static_cast<int>(bh / g.H);
+  T* p = dst.row<T>(b, h, n) + c;
+  *p = from_float<T>(to_float(*p) + to_float(src.row<const T>(b, h, n)[c]));
+}
+
+template <typename T>
+hla_status set_weights_t(hla_handle* hd, const hla_vmod_weights* maps, hipStream_t s) {
+  const int d = hd->g.d;
+  const int64_t per = 4ll * d * d + 4ll * d;
+  for (int m = 0; m < 2; ++m)
+    HLA_TRY(launch(hd, "vmod_pack", k_vmod_pack<T>, dim3(64), dim3(256), 0, s,
+                   static_cast<const T*>(maps[m].W1), static_cast<const T*>(maps[m].b1),
+                   static_cast<const T*>(maps[m].W2), static_cast<const T*>(maps[m].b2),
+                   static_cast<const T*>(maps[m].gamma), static_cast<const T*>(maps[m].beta), d,
+                   hd->vmod_w + m * per));
+  return HLA_OK;
+}
+
+// contiguous [B, H, N, d] view of a workspace array for the current call shape
+View ws_view(void* p, const Geom& g) {
+  return View{p, static_cast<int64_t>(g.H) * g.N * g.d, static_cast<int64_t>(g.N) * g.d, g.d};
+}
+
+template <typename T>
+hla_status forward_t(hla_handle* hd, const hla_call_args& a) {
+  const Geom& g = hd->g;
+  const VmodW w{hd->vmod_w, g.d};
+  const size_t sh = (2 * static_cast<size_t>(g.d) * kFwdTile + 2 * kFwdTile) * sizeof(float);
+  return launch(hd, "vmod_forward", k_vmod_forward<T>, dim3((g.N + kFwdTile - 1) / kFwdTile, g.H, g.B),
+                dim3(g.d), sh, a.stream, g, w, hd->vmod_ln_eps, ws_view(hd->vmod_T, g), a.V, a.O);
+}
+
+template <typename T>
+hla_status backward_t(hla_handle* hd, const hla_call_args& a) {
+  const Geom& g = hd->g;
+  const VmodW w{hd->vmod_w, g.d};
+  const size_t sh = (2 * static_cast<size_t>(g.d) * kBwdTile + 4 * kBwdTile) * sizeof(float);
+  return launch(hd, "vmod_backward", k_vmod_backward<T>, dim3((g.N + kBwdTile - 1) / kBwdTile, g.H, g.B),
+                dim3(g.d), sh, a.stream, g, w, hd->vmod_ln_eps, ws_view(hd->vmod_T, g), a.V, a.dO,
+                ws_view(hd->vmod_dT, g), ws_view(hd->vmod_dV, g));
+}
+
+template <typename T>
+hla_status add_t(hla_handle* hd, const hla_call_args& a) {
+  const Geom& g = hd->g;
+  const int64_t total = static_cast<int64_t>(g.B) * g.H * g.N * g.d;
+  return launch(hd, "vmod_add_dv", k_add_rows<T>, dim3(static_cast<unsigned>((total + 255) / 256)), dim3(256),
+                0, a.stream, g, a.dV, ws_view(hd->vmod_dV, g));
+}
+
+}  // namespace
+
+hla_status vmod_set_weights(hla_handle* hd, const hla_vmod_weights* maps, hipStream_t s) {
+  return hd->cfg.io_dtype == HLA_F32 ? set_weights_t<float>(hd, maps, s) : set_weights_t<bf16_t>(hd, maps, s);
+}
+hla_status vmod_forward(hla_handle* hd, const hla_call_args& a) {
+  return hd->cfg.io_dtype == HLA_F32 ? forward_t<float>(hd, a) : forward_t<bf16_t>(hd, a);
+}
+hla_status vmod_backward(hla_handle* hd, const hla_call_args& a) {
+  return hd->cfg.io_dtype == HLA_F32 ? backward_t<float>(hd, a) : backward_t<bf16_t>(hd, a);
+}
+hla_status vmod_add_value_grads(hla_handle* hd, const hla_call_args& a) {
+  return hd->cfg.io_dtype == HLA_F32 ? add_t<float>(hd, a) : add_t<bf16_t>(hd, a);
+}
+View vmod_view(void* p, const Geom& g) { return ws_view(p, g); }
+
+}  // namespace hla

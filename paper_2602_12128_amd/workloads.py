@@ -100,6 +100,27 @@ def draw_phi_weights(gen, d: int, d_phi: int, n_maps: int, dtype,
     return maps
 
 
+def draw_vmod_weights(gen, d: int, dtype, in_scale=(32.0, 1.0), out_scale: float = 0.05):
+    """Stand-ins for the trained value-modulation maps phi_v1, phi_v2 (Sec. 4.5; App. A.1: two
+    d x d layers and a LayerNorm each).  phi_v1 reads the attention output, which for synthetic
+    inputs is an average of many nearly independent value vectors and therefore tiny: its first
+    layer is scaled up (in_scale[0]) so that its pre-activations are O(1) like phi_v2's.  gamma
+    and beta are scaled by out_scale so that the product of the two maps is comparable to the
+    attention output it is added to (otherwise the sum would hide that output below the bf16
+    resolution of the result)."""
+    maps = []
+    for k in range(2):
+        W1 = in_scale[k] * _draw(gen, (d, d))
+        b1 = 0.25 * _draw(gen, (d,))
+        W2 = _draw(gen, (d, d)) / math.sqrt(0.425 * d)
+        b2 = 0.25 * _draw(gen, (d,))
+        gamma = math.sqrt(out_scale) * (1.0 + 0.1 * _draw(gen, (d,)))
+        beta = math.sqrt(out_scale) * 0.1 * _draw(gen, (d,))
+        maps.append({n: t.to(dtype).contiguous() for n, t in
+                     (("W1", W1), ("b1", b1), ("W2", W2), ("b2", b2), ("gamma", gamma), ("beta", beta))})
+    return maps
+
+
 def make_workload(idx: int, *, need_backward: Optional[bool] = None) -> Workload:
     """Build configuration `idx` (1..5, or a variant 6..7) with all tensors on the CPU in the I/O dtype."""
     w = _spec(idx)

@@ -62,11 +62,12 @@ WG_KEYS = ("dW1", "db1", "dW2", "db2")
 
 def run_gpu(tensors: Dict[str, torch.Tensor], F: int, d_phi: int, eps: float,
             phi=None, cu_seqlens=None, backward=True, path=hla.HLA_PATH_AUTO, handle=None,
-            weight_grads=False, per_head=False, features=False):
+            weight_grads=False, per_head=False, features=False, vmod=None, ln_eps=1e-5):
     """Returns dict of CPU tensors O (and dQ, dK, dV) computed by the HIP library; with
     weight_grads also 'wg': per map a dict of the fp32 weight gradients.  per_head: the weights
     carry a leading head dimension.  features: also '_features' [B,H,N,(1+F)*d_phi], the
-    library's own feature workspace (an output to be compared, like the others)."""
+    library's own feature workspace (an output to be compared, like the others).  vmod: the two
+    value-modulation maps (Sec. 4.5), switched on for the call."""
     dev = torch.device("cuda:0")
     t = {k: v.to(dev) for k, v in tensors.items()}
     h = handle or make_handle(tensors, F, d_phi, eps, phi, cu_seqlens, path)
@@ -78,6 +79,8 @@ def run_gpu(tensors: Dict[str, torch.Tensor], F: int, d_phi: int, eps: float,
             wg = [{"d" + k: torch.full(v.shape, float("nan"), dtype=torch.float32, device=dev)
                    for k, v in m.items()} for m in phi_dev]
             h.set_phi_weight_grads(wg)
+    if vmod is not None:
+        h.set_value_modulation([{k: v.to(dev) for k, v in m.items()} for m in vmod], ln_eps)
     out = {"O": torch.full_like(t["V"], float("nan"))}
     h.forward(t["Q"], t["K"], t["V"], out["O"], cu_seqlens=cu_seqlens)
     if backward:
@@ -99,18 +102,26 @@ def run_gpu(tensors: Dict[str, torch.Tensor], F: int, d_phi: int, eps: float,
     return res
 
 
+def oracle_vmod(vmod, ln_eps):
+    if vmod is None:
+        return None
+    keys = ("W1", "b1", "W2", "b2", "gamma", "beta")
+    return tuple(orc.PhiVWeights(*(to_np(m[k]) for k in keys)) for m in vmod) + (ln_eps,)
+
+
 def run_oracle(tensors, F, d_phi, eps, phi=None, cu_seqlens=None, backward=True,
-               route="factorized", weight_grads=False):
+               route="factorized", weight_grads=False, vmod=None, ln_eps=1e-5):
     """O (and dQ, dK, dV, 'wg') from the oracle; with feature maps and a backward also the
     feature gradients '_dqf', '_dkf' that the branch enumeration below starts from."""
     Q, K, V = (to_np(tensors[k]) for k in ("Q", "K", "V"))
     ophi = oracle_phi(phi)
+    ovm = oracle_vmod(vmod, ln_eps)
     out = {"O": orc.hla_operator_forward(Q, K, V, F, d_phi, eps, phi=ophi, cu_seqlens=cu_seqlens,
-                                         route=route)}
+                                         route=route, vmod=ovm)}
     if backward:
         res = orc.hla_operator_backward(Q, K, V, to_np(tensors["dO"]), F, d_phi, eps,
                                         phi=ophi, cu_seqlens=cu_seqlens, route=route,
-                                        weight_grads=weight_grads, feature_grads=True)
+                                        weight_grads=weight_grads, feature_grads=True, vmod=ovm)
         out.update(dQ=res[0], dK=res[1], dV=res[2])
         if weight_grads:
             out["wg"] = [dict(zip(WG_KEYS, m)) for m in res[3]]

@@ -1,0 +1,75 @@
+"""GPU parity of the value modulation (Sec. 4.5: O = T + phi_v1(T) * phi_v2(V), phi_v of App. A.1
+with a LayerNorm on its output) through the C ABI: forward and backward on both kernel paths,
+feature-level and through the feature maps, packed sequences, strided views, switching it off."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2602_12128_amd as hla
+from paper_2602_12128_amd import workloads as wl
+from tests import parity_utils as pu
+
+pytestmark = pytest.mark.gpu
+
+
+def _vmod(seed, d, dtype):
+    return wl.draw_vmod_weights(torch.Generator("cpu").manual_seed(seed), d, dtype)
+
+
+@pytest.mark.parametrize("F,dphi,d,B,H,N", [(3, 6, 32, 2, 2, 83), (2, 12, 64, 1, 3, 150), (3, 6, 128, 1, 2, 70)])
+def test_value_modulation_fp32_generic_path(F, dphi, d, B, H, N):
+    t, phi = wl.make_raw_inputs(1100 + N, B, H, N, d, F, dphi, torch.float32)
+    vm = _vmod(1101 + N, d, torch.float32)
+    gpu = pu.run_gpu(t, F, dphi, 1e-6, phi=phi, path=hla.HLA_PATH_GENERIC, vmod=vm)
+    ref = pu.run_oracle(t, F, dphi, 1e-6, phi=phi, vmod=vm)
+    pu.assert_parity(gpu, ref, 1e-4, f"value modulation fp32 F={F} d={d} N={N}")
+    plain = pu.run_oracle(t, F, dphi, 1e-6, phi=phi, backward=False)
+    assert np.abs(ref["O"] - plain["O"]).max() > 0.1 * np.abs(plain["O"]).max()  # it does something
+
+
+@pytest.mark.parametrize("F,dphi,d,B,H,N", [(3, 6, 128, 1, 2, 700), (2, 12, 64, 2, 3, 333), (3, 6, 128, 2, 1, 2049)])
+def test_value_modulation_bf16_mfma_path(F, dphi, d, B, H, N):
+    t, phi = wl.make_raw_inputs(1120 + N, B, H, N, d, F, dphi, torch.bfloat16)
+    vm = _vmod(1121 + N, d, torch.bfloat16)
+    gpu = pu.run_gpu(t, F, dphi, 1e-6, phi=phi, path=hla.HLA_PATH_MFMA, vmod=vm)
+    assert gpu["_path"] == hla.HLA_PATH_MFMA
+    ref = pu.run_oracle(t, F, dphi, 1e-6, phi=phi, vmod=vm)
+    pu.assert_parity(gpu, ref, 2e-2, f"value modulation bf16 F={F} d={d} N={N}",
+                     kinks=pu.oracle_kinks(t, phi, F, dphi, ref))
+
+
+def test_value_modulation_feature_level_packed_bf16():
+    cu = [0, 100, 100, 1500, 1501, 2600]
+    t = wl.make_feature_inputs(1140, 1, 2, cu[-1], 128, 3, 6, torch.bfloat16)
+    vm = _vmod(1141, 128, torch.bfloat16)
+    gpu = pu.run_gpu(t, 3, 6, 1e-6, cu_seqlens=cu, vmod=vm)
+    ref = pu.run_oracle(t, 3, 6, 1e-6, cu_seqlens=cu, vmod=vm)
+    keep = np.ones(cu[-1], bool)
+    keep[1500] = False  # the single-token sequence: O(eps) feature gradients, compared apart elsewhere
+    pu.assert_parity({k: v[:, :, keep] for k, v in gpu.items() if k != "_path"},
+                     {k: v[:, :, keep] for k, v in ref.items()}, 2e-2, "value modulation packed")
+
+
+def test_switching_the_modulation_off_and_on():
+    dev = torch.device("cuda:0")
+    t = wl.make_feature_inputs(1150, 1, 2, 500, 64, 3, 6, torch.bfloat16)
+    vm = _vmod(1151, 64, torch.bfloat16)
+    td = {k: v.to(dev) for k, v in t.items()}
+    h = pu.make_handle(t, 3, 6, 1e-6, None, None)
+    O = [torch.empty_like(td["V"]) for _ in range(3)]
+    g = [torch.empty_like(td[k]) for k in "QKV"]
+    h.forward(td["Q"], td["K"], td["V"], O[0])
+    h.set_value_modulation([{k: v.to(dev) for k, v in m.items()} for m in vm])
+    with pytest.raises(hla.HLAError) as e:  # the saved forward was made without the modulation
+        h.backward(td["Q"], td["K"], td["V"], O[0], td["dO"], *g)
+    assert e.value.code == 5
+    h.forward(td["Q"], td["K"], td["V"], O[1])
+    h.backward(td["Q"], td["K"], td["V"], O[1], td["dO"], *g)
+    h.set_value_modulation(None)
+    h.forward(td["Q"], td["K"], td["V"], O[2])
+    torch.cuda.synchronize()
+    assert torch.equal(O[0], O[2]) and not torch.equal(O[0], O[1])
+    with pytest.raises(hla.HLAError) as e:
+        h.set_value_modulation([{k: v.to(dev) for k, v in m.items()} for m in vm], ln_eps=-1.0)
+    assert e.value.code == 1
+    h.destroy()
