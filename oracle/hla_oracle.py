@@ -17,8 +17,9 @@ invariance; homogeneity (rational-function form); the sequential state update; L
 against tabulated normal-CDF values; both backward routes, and the feature-map weight gradients,
 against central finite differences; the enumeration of ReLU branch choices against the masked
 (smooth) map; the value modulation of Sec. 4.5 against scalar loops (LayerNorm, the map), the
-identity special case and finite differences (tests/test_oracle_value_modulation.py).  No
-function here is "parity unpinned".
+identity special case and finite differences (tests/test_oracle_value_modulation.py); the
+causal variant of Sec. 4.4 through its two routes, its first and last rows and causality itself
+(tests/test_oracle_causal.py).  No function here is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -214,6 +215,45 @@ def hla_sequential_state(kfs, v):
 
 
 # --------------------------------------------------------------------------------------------
+# Causal variant (Sec. 4.4): token i attends to tokens j <= i only
+# --------------------------------------------------------------------------------------------
+def hla_causal_bruteforce(qf, kfs, v, eps: float, rows=None):
+    """Eq. 'hla' with the {0,1} causal mask of Sec. 4.4 on the N x N matrix: A_ij as before for
+    j <= i, zero for j > i; eta_i = sum_{j<=i} A_ij; o_i = sum_{j<=i} A_ij v_j / (eta_i + eps).
+    rows: optional indices of the query rows to evaluate (against all their keys)."""
+    qf = np.asarray(qf, F64)
+    v = np.asarray(v, F64)
+    idx = np.arange(qf.shape[0]) if rows is None else np.asarray(rows)
+    A = np.ones((len(idx), v.shape[0]), dtype=F64)
+    for kf in kfs:
+        A = A * (qf[idx] @ np.asarray(kf, F64).T)
+    A = A * (np.arange(v.shape[0])[None, :] <= idx[:, None])
+    eta = A.sum(axis=1)
+    return (A @ v) / (eta + eps)[:, None]
+
+
+def hla_causal_sequential(qf, kfs, v, eps: float):
+    """The sequential updates of Sec. 4.4: the context tensor is the state, C^i = C^{i-1} +
+    T_k,i (Kronecker) v_i (and z^i = z^{i-1} + T_k,i for the normaliser), and token i's output is
+    the contraction of T_q,i with C^i, divided by T_q,i . z^i + eps.  Python loop: small inputs."""
+    qf = np.asarray(qf, F64)
+    kfs = [np.asarray(k, F64) for k in kfs]
+    v = np.asarray(v, F64)
+    F = len(kfs)
+    D = kfs[0].shape[1] ** F
+    C = np.zeros((D, v.shape[1]), F64)
+    z = np.zeros(D, F64)
+    out = np.zeros_like(v)
+    for i in range(v.shape[0]):
+        tk = outer_features([k[i:i + 1] for k in kfs])[0]
+        C += np.outer(tk, v[i])
+        z += tk
+        tq = outer_features([qf[i:i + 1]] * F)[0]
+        out[i] = (tq @ C) / (tq @ z + eps)
+    return out
+
+
+# --------------------------------------------------------------------------------------------
 # Backward (the paper leaves this to autograd; derived from the factorized form)
 # --------------------------------------------------------------------------------------------
 def _slot_gradient(dT: np.ndarray, feats: Sequence[np.ndarray], slot: int) -> np.ndarray:
@@ -403,11 +443,13 @@ def _features(Q, K, lo, hi, b, h, F, d_phi, phi: Optional[Sequence[PhiWeights]])
 def hla_operator_forward(Q, K, V, F: int, d_phi: int, eps: float,
                          phi: Optional[Sequence[PhiWeights]] = None,
                          cu_seqlens: Optional[Sequence[int]] = None,
-                         route: str = "factorized", vmod=None) -> np.ndarray:
+                         route: str = "factorized", vmod=None, causal: bool = False) -> np.ndarray:
     """O [B,H,N,d] for Q,K,V [B,H,N,*].  `phi` = [phi_q, phi_k1..phi_kF] or None when Q and K
     already hold features.  Sequences (batch entries, or the packed ranges of cu_seqlens) never
     share state.  vmod = (phi_v1, phi_v2, ln_eps) applies the value modulation of Sec. 4.5 to the
-    attention output, token by token (maps shared by all heads)."""
+    attention output, token by token (maps shared by all heads).  causal: the masked variant of
+    Sec. 4.4 inside every sequence (route 'bruteforce' = masked N x N matrix, 'factorized' = the
+    sequential state updates)."""
     B, H, N = V.shape[:3]
     O = np.zeros(V.shape, F64)
     for (b, lo, hi) in _units(B, N, cu_seqlens):
@@ -416,7 +458,10 @@ def hla_operator_forward(Q, K, V, F: int, d_phi: int, eps: float,
         for h in range(H):
             qf, kfs = _features(Q, K, lo, hi, b, h, F, d_phi, phi)
             v = np.asarray(V[b, h, lo:hi], F64)
-            if route == "factorized":
+            if causal:
+                O[b, h, lo:hi] = (hla_causal_sequential if route == "factorized" else
+                                  hla_causal_bruteforce)(qf, kfs, v, eps)
+            elif route == "factorized":
                 O[b, h, lo:hi] = hla_factorized(qf, kfs, v, eps)[0]
             elif route == "bruteforce":
                 O[b, h, lo:hi] = hla_bruteforce(qf, kfs, v, eps)[0]

@@ -1,0 +1,86 @@
+"""Pins for the oracle's causal variant (Sec. 4.4): the masked N x N matrix against the
+sequential state updates the paper gives, against scalar loops, the rows whose value is known
+(first row, last row), causality itself, and F = 1 against causal linear attention by prefix sums."""
+import numpy as np
+import pytest
+
+from oracle import hla_oracle as orc
+
+
+def _inputs(seed, n, dp, d, F):
+    rng = np.random.default_rng(seed)
+    q = np.abs(rng.standard_normal((n, dp))) + 0.05
+    ks = [np.abs(rng.standard_normal((n, dp))) + 0.05 for _ in range(F)]
+    return q, ks, rng.standard_normal((n, d))
+
+
+@pytest.mark.parametrize("F,dp", [(1, 5), (2, 4), (3, 3), (3, 6), (2, 12)])
+def test_masked_matrix_equals_sequential_updates(F, dp):
+    q, ks, v = _inputs(80 + F, 23, dp, 5, F)
+    a = orc.hla_causal_bruteforce(q, ks, v, 1e-6)
+    b = orc.hla_causal_sequential(q, ks, v, 1e-6)
+    np.testing.assert_allclose(a, b, rtol=1e-11, atol=1e-13)
+
+
+def test_masked_matrix_against_scalar_loops():
+    q, ks, v = _inputs(85, 9, 3, 4, 3)
+    eps = 1e-3
+    got = orc.hla_causal_bruteforce(q, ks, v, eps)
+    for i in range(9):
+        num = np.zeros(4)
+        eta = 0.0
+        for j in range(i + 1):          # keys up to and including the query's own position
+            a = 1.0
+            for f in range(3):
+                a *= sum(q[i, c] * ks[f][j, c] for c in range(3))
+            eta += a
+            num += a * v[j]
+        np.testing.assert_allclose(got[i], num / (eta + eps), rtol=1e-12, atol=1e-14)
+
+
+def test_known_rows_and_causality():
+    q, ks, v = _inputs(86, 40, 6, 7, 3)
+    eps = 1e-6
+    c = orc.hla_causal_bruteforce(q, ks, v, eps)
+    full = orc.hla_bruteforce(q, ks, v, eps)[0]
+    # the last token sees every key: its row is the non-causal one; the first sees only itself
+    np.testing.assert_allclose(c[-1], full[-1], rtol=1e-12, atol=1e-14)
+    a00 = np.prod([q[0] @ k[0] for k in ks])
+    np.testing.assert_allclose(c[0], v[0] * a00 / (a00 + eps), rtol=1e-12, atol=1e-14)
+    assert np.abs(c[5] - full[5]).max() > 1e-3          # the mask matters elsewhere
+    # causality: changing tokens after position 17 (keys, values, queries) leaves rows 0..17 alone
+    q2, ks2, v2 = q.copy(), [k.copy() for k in ks], v.copy()
+    q2[18:] += 0.3
+    v2[18:] -= 1.0
+    for k in ks2:
+        k[18:] *= 1.7
+    c2 = orc.hla_causal_bruteforce(q2, ks2, v2, eps)
+    np.testing.assert_array_equal(c[:18], c2[:18])
+    assert np.abs(c[18:] - c2[18:]).max() > 1e-3
+    # a subset of rows is evaluated exactly as in the full call
+    np.testing.assert_array_equal(orc.hla_causal_bruteforce(q, ks, v, eps, rows=[3, 39, 11]), c[[3, 39, 11]])
+
+
+def test_one_factor_is_causal_linear_attention_by_prefix_sums():
+    q, ks, v = _inputs(87, 30, 5, 4, 1)
+    kv = np.cumsum(ks[0][:, :, None] * v[:, None, :], axis=0)   # running sum of phi(k_j) (x) v_j
+    kz = np.cumsum(ks[0], axis=0)
+    want = np.einsum("na,nad->nd", q, kv) / (np.einsum("na,na->n", q, kz) + 1e-6)[:, None]
+    np.testing.assert_allclose(orc.hla_causal_bruteforce(q, ks, v, 1e-6), want, rtol=1e-11, atol=1e-13)
+
+
+def test_operator_level_causal_is_per_sequence():
+    rng = np.random.default_rng(88)
+    B, H, N, d, F, dp = 1, 2, 12, 4, 2, 3
+    Q = np.abs(rng.standard_normal((B, H, N, dp)))
+    K = np.abs(rng.standard_normal((B, H, N, F * dp)))
+    V = rng.standard_normal((B, H, N, d))
+    cu = [0, 5, 12]
+    a = orc.hla_operator_forward(Q, K, V, F, dp, 1e-6, cu_seqlens=cu, causal=True, route="bruteforce")
+    b = orc.hla_operator_forward(Q, K, V, F, dp, 1e-6, cu_seqlens=cu, causal=True, route="factorized")
+    np.testing.assert_allclose(a, b, rtol=1e-11, atol=1e-13)
+    # the first token of the second sequence sees only itself, not the first sequence
+    for h in range(H):
+        kf = [K[0, h, 5, f * dp:(f + 1) * dp] for f in range(F)]
+        a55 = np.prod([Q[0, h, 5] @ k for k in kf])
+        np.testing.assert_allclose(a[0, h, 5], V[0, h, 5] * a55 / (a55 + 1e-6), rtol=1e-12)
