@@ -39,6 +39,10 @@ def parse():
     ap.add_argument("--weight-grads", action="store_true",
                     help="also produce the feature-map weight gradients in every backward (a "
                          "different workload from the headline one: named in config)")
+    ap.add_argument("--value-modulation", action="store_true",
+                    help="switch on the value modulation of Sec. 4.5 (a different workload: named in config)")
+    ap.add_argument("--causal", action="store_true",
+                    help="the causal variant of Sec. 4.4, forward only (a different workload: named in config)")
     return ap.parse_args()
 
 
@@ -106,7 +110,7 @@ def main():
     hla.load_library()
     dev = torch.device("cuda:0")
     w = wl.make_workload(args.config)
-    backward = w.backward
+    backward = w.backward and not args.causal
     phi = w.phi
     if args.features:
         ft = wl.make_feature_inputs(w.seed, w.B, w.H, w.N, w.d, w.F, w.d_phi, w.dtype)
@@ -118,9 +122,12 @@ def main():
     h = hla.HLA(head_dim=w.d, feature_dim=w.d_phi, degree=w.F, eps=w.eps,
                 io_dtype=hla.HLA_F32 if w.dtype == torch.float32 else hla.HLA_BF16,
                 phi_mode=hla.HLA_PHI_NONE if phi is None else hla.HLA_PHI_MLP, kernel_path=path,
-                max_heads=w.H, max_tokens=w.B * w.N, max_seqs=nseq)
+                max_heads=w.H, max_tokens=w.B * w.N, max_seqs=nseq, causal=args.causal)
     if phi is not None:
         h.set_phi_weights([{k: v.to(dev) for k, v in m.items()} for m in phi])
+    if args.value_modulation:
+        vm = wl.draw_vmod_weights(torch.Generator("cpu").manual_seed(w.seed + 100), w.d, w.dtype)
+        h.set_value_modulation([{k: v.to(dev) for k, v in m.items()} for m in vm])
     O = torch.empty_like(t["V"])
     grads = [torch.empty_like(t[k]) for k in ("Q", "K", "V")] if backward else None
     wgrads = None
@@ -218,7 +225,8 @@ def main():
                    "d_phi": w.d_phi, "phi": "mlp" if phi is not None else "none",
                    "packed_seqs": nseq if w.cu_seqlens else 0,
                    "path": "mfma" if h.active_path == hla.HLA_PATH_MFMA else "generic",
-                   "weight_grads": wgrads is not None},
+                   "weight_grads": wgrads is not None, "value_modulation": args.value_modulation,
+                   "causal": args.causal},
         "tflops_nominal": tflops,
         "mfma_peak_frac_nominal": tflops / 2500.0,
         "tflops_executed": None if fl_exec is None else fl_exec / (elapsed / args.steps) / 1e12,

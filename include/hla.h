@@ -75,6 +75,14 @@ typedef struct {
   int32_t max_heads;     /* largest H any call will pass */
   int64_t max_tokens;    /* largest B*N (tokens per head, all batch rows / packed sequences) */
   int32_t max_seqs;      /* largest number of independent sequences (B, or num_seqs when packed) */
+  int32_t causal;        /* 0: every token attends to every token of its sequence (the paper's video
+                            model); 1: the causal variant of Sec. 4.4, token i attends to tokens
+                            j <= i of its sequence (the {0,1} mask; eta_i sums the same entries), which
+                            is what the paper's sequential state update C^i = C^{i-1} + T_k,i (x) v_i
+                            computes.  Forward only, MFMA path only: hla_create returns
+                            HLA_ERR_UNSUPPORTED for a configuration without MFMA kernels,
+                            hla_backward and hla_forward_static return it for a causal handle.
+                            Decay factors are not implemented. */
 } hla_config;
 
 /* Weights of one feature map, device pointers in io_dtype, row-major, applied from the right:

@@ -33,7 +33,7 @@ class hla_config(C.Structure):
         ("head_dim", C.c_int32), ("feature_dim", C.c_int32), ("degree", C.c_int32),
         ("eps", C.c_float), ("io_dtype", C.c_int32), ("phi_mode", C.c_int32),
         ("kernel_path", C.c_int32), ("max_heads", C.c_int32), ("max_tokens", C.c_int64),
-        ("max_seqs", C.c_int32),
+        ("max_seqs", C.c_int32), ("causal", C.c_int32),
     ]
 
 
@@ -146,7 +146,7 @@ def hla_forward_static(Q, K, V, O, feature_dim: int = 6, degree: int = 3, eps: f
     handle and no device allocation (the workspace is a static array inside the library)."""
     lib = load_library()
     B, H, N, d = V.shape
-    cfg = hla_config(d, feature_dim, degree, eps, io_dtype, HLA_PHI_NONE, kernel_path, 1, 1, 1)
+    cfg = hla_config(d, feature_dim, degree, eps, io_dtype, HLA_PHI_NONE, kernel_path, 1, 1, 1, 0)
     _check(lib.hla_forward_static(C.byref(cfg), B, H, N, _view(Q), _view(K), _view(V), _view(O),
                                   _stream_ptr(stream)), "hla_forward_static")
 
@@ -157,10 +157,10 @@ class HLA:
     def __init__(self, head_dim: int, feature_dim: int = 6, degree: int = 3, eps: float = 1e-6,
                  io_dtype: int = HLA_BF16, phi_mode: int = HLA_PHI_MLP,
                  kernel_path: int = HLA_PATH_AUTO, max_heads: int = 1, max_tokens: int = 1,
-                 max_seqs: int = 1):
+                 max_seqs: int = 1, causal: bool = False):
         self._lib = load_library()
         self.config = hla_config(head_dim, feature_dim, degree, eps, io_dtype, phi_mode,
-                                 kernel_path, max_heads, max_tokens, max_seqs)
+                                 kernel_path, max_heads, max_tokens, max_seqs, int(causal))
         self._h = C.c_void_p()
         _check(self._lib.hla_create(C.byref(self.config), C.byref(self._h)), "hla_create")
         self._keepalive = None

@@ -217,6 +217,7 @@ hla_status validate_config(const hla_config* c) {
   if (c->phi_mode != HLA_PHI_MLP && c->phi_mode != HLA_PHI_NONE) return HLA_ERR_INVALID_ARG;
   if (c->kernel_path < HLA_PATH_AUTO || c->kernel_path > HLA_PATH_MFMA) return HLA_ERR_INVALID_ARG;
   if (!(c->eps >= 0.0f)) return HLA_ERR_INVALID_ARG;
+  if (c->causal != 0 && c->causal != 1) return HLA_ERR_INVALID_ARG;
   if (c->head_dim != 32 && c->head_dim != 64 && c->head_dim != 128) return HLA_ERR_UNSUPPORTED;
   if (c->degree < 1 || c->degree > 4 || c->feature_dim < 1) return HLA_ERR_UNSUPPORTED;
   if (c->feature_dim > 256 || ipow(c->feature_dim, c->degree) > 256) return HLA_ERR_UNSUPPORTED;
@@ -239,6 +240,7 @@ hla_status plan_handle(hla_handle* hd, const hla_config& c) {
   const bool mfma_ok = mfma_supported(c);
   if (c.kernel_path == HLA_PATH_MFMA && !mfma_ok) return HLA_ERR_UNSUPPORTED;
   hd->path = (c.kernel_path == HLA_PATH_GENERIC || !mfma_ok) ? HLA_PATH_GENERIC : HLA_PATH_MFMA;
+  if (c.causal && hd->path != HLA_PATH_MFMA) return HLA_ERR_UNSUPPORTED;  // only the MFMA path has the scan
   hd->g.feat_tiled = hd->path == HLA_PATH_MFMA ? 1 : 0;
   for (hla_token_table& t : hd->tables) t = hla_token_table{};
   return hd->path == HLA_PATH_MFMA ? mfma_workspace_plan(hd) : generic_workspace_plan(hd);
@@ -467,6 +469,7 @@ hla_status hla_backward(hla_handle* hd, int32_t B, int32_t H, int32_t N, const i
   bool empty = false;
   int32_t nseq = 0;
   if (hd == nullptr) return HLA_ERR_INVALID_ARG;
+  if (hd->cfg.causal) return HLA_ERR_UNSUPPORTED;  // the causal variant has a forward only
   // The tables and the saved features belong to the last forward: check before touching them.
   {
     const bool packed = cu_seqlens != nullptr;
@@ -539,7 +542,7 @@ StaticSlot g_static[kMaxDevices];
 bool same_config(const hla_config& a, const hla_config& b) {
   return a.head_dim == b.head_dim && a.feature_dim == b.feature_dim && a.degree == b.degree &&
          a.eps == b.eps && a.io_dtype == b.io_dtype && a.phi_mode == b.phi_mode &&
-         a.kernel_path == b.kernel_path && a.max_heads == b.max_heads &&
+         a.kernel_path == b.kernel_path && a.causal == b.causal && a.max_heads == b.max_heads &&
          a.max_tokens == b.max_tokens && a.max_seqs == b.max_seqs;
 }
 
@@ -548,7 +551,7 @@ bool same_config(const hla_config& a, const hla_config& b) {
 hla_status hla_forward_static(const hla_config* config, int32_t B, int32_t H, int32_t N, hla_tensor Q,
                               hla_tensor K, hla_tensor V, hla_tensor O, void* hip_stream) {
   if (config == nullptr || B < 0 || H < 0 || N < 0) return HLA_ERR_INVALID_ARG;
-  if (config->phi_mode != HLA_PHI_NONE) return HLA_ERR_UNSUPPORTED;
+  if (config->phi_mode != HLA_PHI_NONE || config->causal != 0) return HLA_ERR_UNSUPPORTED;
   if (B == 0 || H == 0 || N == 0) return HLA_OK;
   if (bad_view(Q) || bad_view(K) || bad_view(V) || bad_view(O)) return HLA_ERR_INVALID_ARG;
   // the workspace is laid out for exactly this call's sizes

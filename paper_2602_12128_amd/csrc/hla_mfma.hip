@@ -440,6 +440,252 @@ __global__ __launch_bounds__(kThreads) void k_query(Geom g, const BlockEnt* __re
   }
 }
 
+
+// ---- causal variant (Sec. 4.4): chunked scan -------------------------------------------------------
+// Token i attends to tokens j <= i of its sequence.  The sequence is cut into chunks of
+// kCausalChunk tokens: k_state gives every chunk's own state, k_prefix turns them into the state
+// BEFORE each chunk (exclusive running sum in chunk order, emitted as the query kernel's operand
+// image), and k_query_causal adds, for every query tile, the contribution of the earlier tiles of
+// its own chunk through the masked score tile  P^T = S Qm^T  (keys x queries) and  O^T += V^T P.
+constexpr int kCausalChunk = 256;
+
+template <class SY, int D>
+struct PrefixLayout {
+  static constexpr int64_t kOpElems = static_cast<int64_t>(SY::MP) * D;   // bf16: rows = channels image
+  static constexpr int64_t kBytes = kOpElems * 2 + 2 * SY::SP * 4;        // then the normaliser by slot
+};
+
+// grid (num_seqs, H, kReduceSlices), block 256.  Thread-owned entries as in k_reduce; the sum so far
+// is written for chunk c before chunk c's partial is added.
+template <class SY, int D>
+__global__ __launch_bounds__(256) void k_prefix(Geom g, const int32_t* __restrict__ seq_chunk_off,
+                                                const float* __restrict__ partial,
+                                                int64_t partial_stride, unsigned char* __restrict__ pfx,
+                                                SlotMap sm) {
+  using PL = PrefixLayout<SY, D>;
+  constexpr int MP = SY::MP, SP = SY::SP;
+  constexpr int VPR = D / 4;
+  constexpr int PER = MP * VPR / kReduceSlices;
+  const int s = blockIdx.x, h = blockIdx.y, sl = blockIdx.z;
+  const int c0 = seq_chunk_off[s], c1 = seq_chunk_off[s + 1];
+  const float* base = partial + static_cast<int64_t>(h) * partial_stride;
+  const int64_t cstride = static_cast<int64_t>(g.H) * partial_stride;
+  constexpr int NB = 8;  // chunk loads in flight
+  for (int idx = threadIdx.x; idx < PER; idx += blockDim.x) {
+    const int v = sl * PER + idx;
+    const int m = v / VPR, c = (v % VPR) * 4;
+    const int mg = sm.g[m], ms = sm.s[m];
+    f32x4 a;
+    a[0] = a[1] = a[2] = a[3] = 0.0f;
+    const float* p0 = base + m * D + c;
+    for (int ch = c0; ch < c1; ch += NB) {
+      f32x4 ld[NB];
+#pragma unroll
+      for (int k = 0; k < NB; ++k)
+        ld[k] = *reinterpret_cast<const f32x4*>(p0 + (ch + k < c1 ? ch + k : c1 - 1) * cstride);
+#pragma unroll
+      for (int k = 0; k < NB; ++k) {
+        if (ch + k >= c1) break;
+        if (mg >= 0) {
+          uint16_t* opA = reinterpret_cast<uint16_t*>(pfx + (static_cast<int64_t>(ch + k) * g.H + h) * PL::kBytes);
+          const int ks = ms / 8, j = ms % 8;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int rb = (c + e) / 32, r = (c + e) % 32;
+            opA[((rb * (MP / 16) + ks) * 64 + 32 * mg + r) * 8 + j] = f32_to_bf16_bits(a[e]);
+          }
+        }
+        a += ld[k];
+      }
+    }
+  }
+  if (sl == 0) {
+    for (int m = threadIdx.x; m < MP; m += blockDim.x) {
+      const int mg = sm.g[m], ms = sm.s[m];
+      float a = 0.0f;
+      for (int ch = c0; ch < c1; ++ch) {
+        if (mg >= 0) {
+          float* zslot = reinterpret_cast<float*>(pfx + (static_cast<int64_t>(ch) * g.H + h) * PL::kBytes + PL::kOpElems * 2);
+          zslot[mg * SP + ms] = a;
+        }
+        a += base[ch * cstride + MP * D + m];
+      }
+    }
+  }
+}
+
+template <class SY, int D>
+struct CausalSmem {
+  static constexpr int kTiles = kCausalChunk / 32;
+  static constexpr int NKS = SY::MP / 16;
+  static constexpr int kVStride = D * 2 + 32;                  // bytes per token row of the V tile
+  static constexpr int kVBytes = kCausalChunk * kVStride;
+  static constexpr int kSBytes = kTiles * NKS * 64 * 16;       // key-monomial operand images of the chunk
+  static constexpr int kTotal = kVBytes + kSBytes + kWaves * RowTile<D>::kBytes;
+};
+
+// grid (chunks of kCausalChunk tokens, H), block 256.  The workgroup stages the chunk's V rows and
+// the key monomials of its tokens (as MFMA A-operand images, one per 32-key tile) in LDS; wave w
+// then serves query tiles w and 7 - w (equal numbers of key tiles per wave).  Lane (r, gl): query
+// r of the tile, slot half gl, as in k_query.
+template <class SY, int D>
+__global__ __launch_bounds__(kThreads) void k_query_causal(Geom g, const BlockEnt* __restrict__ chunks,
+                                                           const float* __restrict__ feat, View V,
+                                                           const unsigned char* __restrict__ pfx, View O,
+                                                           float* __restrict__ den) {
+  using SM = CausalSmem<SY, D>;
+  using PL = PrefixLayout<SY, D>;
+  constexpr int SP = SY::SP, MP = SY::MP, DP = SY::DPHI, F = SY::F;
+  constexpr int NRB = D / 32, NKS = MP / 16, NF = F * DP;
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int lane = threadIdx.x % kWave, wave = wave_index();
+  unsigned char* vs = smem;
+  u32x4* simg = reinterpret_cast<u32x4*>(smem + SM::kVBytes);
+  unsigned char* tile = smem + SM::kVBytes + SM::kSBytes + wave * RowTile<D>::kBytes;
+  const int r = lane % 32, gl = lane / 32;
+  const int L = lane % 16, q = lane / 16;
+  const BlockEnt e = chunks[blockIdx.x];
+  const int h = blockIdx.y;
+  // ---- the chunk's V rows (64 per wave) and key-monomial images (two key tiles per wave)
+  {
+    TileRegs<D, 64> vt;
+    fetch_tile<D, 64>(V, e.b, h, e.t0 + 64 * wave, e.t1, lane, vt);
+    put_tile<D, 64>(vt, lane, vs + 64 * wave * SM::kVStride, SM::kVStride);
+  }
+#pragma unroll 1
+  for (int tt = 0; tt < 2; ++tt) {
+    const int t = 2 * wave + tt;
+    const int n = e.t0 + 32 * t + r;
+    float kf[NF], kr[NF];
+    if (n < e.t1) {
+      const f32x2* f = reinterpret_cast<const f32x2*>(feat + g.fidx(g.th(e.b, h, n), DP));
+#pragma unroll
+      for (int p = 0; p < NF / 2; ++p) {
+        const f32x2 v = f[32 * p];
+        kf[2 * p] = v[0];
+        kf[2 * p + 1] = v[1];
+      }
+    } else {
+#pragma unroll
+      for (int a = 0; a < NF; ++a) kf[a] = 0.0f;
+    }
+    float kk[F][DP];
+#pragma unroll
+    for (int f = 0; f < F; ++f)
+#pragma unroll
+      for (int c = 0; c < DP; ++c) kr[f * DP + c] = kf[(f + 1) * DP - 1 - c];
+#pragma unroll
+    for (int f = 0; f < F; ++f)
+#pragma unroll
+      for (int c = 0; c < DP; ++c) kk[f][c] = gl ? kr[f * DP + c] : kf[f * DP + c];
+    float sm[SP];
+    sym_key_monomials_slots<SY>(kk, sm, gl);
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) {
+      u32x4 w;
+#pragma unroll
+      for (int p = 0; p < 4; ++p) w[p] = pack_bf16(sm[8 * ks + 2 * p], sm[8 * ks + 2 * p + 1]);
+      simg[(t * NKS + ks) * 64 + lane] = w;
+    }
+  }
+  __syncthreads();
+  const unsigned char* pu = pfx + (static_cast<int64_t>(blockIdx.x) * g.H + h) * PL::kBytes;
+  const u32x4* opA = reinterpret_cast<const u32x4*>(pu);
+  const float* zslot = reinterpret_cast<const float*>(pu + PL::kOpElems * 2) + gl * SP;
+#pragma unroll 1
+  for (int qi = 0; qi < 2; ++qi) {
+    const int qt = qi == 0 ? wave : SM::kTiles - 1 - wave;
+    const int n0 = e.t0 + 32 * qt;
+    if (n0 >= e.t1) continue;
+    const int n = n0 + r;
+    const bool live = n < e.t1;
+    float qf[DP];
+    {
+      const f32x2* f = reinterpret_cast<const f32x2*>(feat + g.fidx(g.th(e.b, h, live ? n : e.t1 - 1), 0));
+#pragma unroll
+      for (int p = 0; p < DP / 2; ++p) {  // lane half 1 takes the pairs, and each pair, in reverse
+        const f32x2 v = f[32 * (gl ? DP / 2 - 1 - p : p)];
+        qf[2 * p] = live ? (gl ? v[1] : v[0]) : 0.0f;
+        qf[2 * p + 1] = live ? (gl ? v[0] : v[1]) : 0.0f;
+      }
+    }
+    float qm[SP];
+    sym_query_monomials<SY>(qf, qm, gl);
+    u32x4 b[NKS];
+    float eta = 0.0f;
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) {
+      const f32x4 z0 = *reinterpret_cast<const f32x4*>(zslot + 8 * ks);
+      const f32x4 z1 = *reinterpret_cast<const f32x4*>(zslot + 8 * ks + 4);
+#pragma unroll
+      for (int p = 0; p < 4; ++p) {
+        const int s = 8 * ks + 2 * p;
+        const uint32_t pk = pack_bf16(qm[s], qm[s + 1]);
+        b[ks][p] = pk;
+        const float za = p < 2 ? z0[2 * p] : z1[2 * p - 4], zb = p < 2 ? z0[2 * p + 1] : z1[2 * p - 3];
+        eta += bf16_lo(pk) * za + bf16_hi(pk) * zb;  // the same rounded values the MFMA sees
+      }
+    }
+    // everything before the chunk: the prefix state
+    f32x16 acc[NRB];
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[rb][i] = 0.0f;
+#pragma unroll
+      for (int ks = 0; ks < NKS; ++ks) acc[rb] = mfma32(opA[(rb * NKS + ks) * 64 + lane], b[ks], acc[rb]);
+    }
+    // the chunk's own tokens up to the query: key tiles 0 .. qt
+#pragma unroll 1
+    for (int kt = 0; kt <= qt; ++kt) {
+      f32x16 P;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) P[i] = 0.0f;
+#pragma unroll
+      for (int ks = 0; ks < NKS; ++ks) P = mfma32(simg[(kt * NKS + ks) * 64 + lane], b[ks], P);
+      if (kt == qt) {  // key d_row(i, gl) of the tile against query r: later keys are masked
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+          if (d_row(i, gl) > r) P[i] = 0.0f;
+      }
+      u32x4 pb[2];
+#pragma unroll
+      for (int ks2 = 0; ks2 < 2; ++ks2)
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+          const uint32_t pk = pack_bf16(P[8 * ks2 + 2 * p], P[8 * ks2 + 2 * p + 1]);
+          pb[ks2][p] = pk;
+          eta += bf16_lo(pk) + bf16_hi(pk);
+        }
+      // O^T += V^T P: k-slot (ks2, gl, j) is key 16 ks2 + 8 (j / 4) + 4 gl + j % 4 of the tile, the
+      // order in which the score accumulators hold the keys
+#pragma unroll
+      for (int ks2 = 0; ks2 < 2; ++ks2) {
+        const int krow = 32 * kt + 16 * ks2 + 4 * gl + L / 4;
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb) {
+          const unsigned char* p = vs + krow * SM::kVStride + (32 * rb + 16 * (q % 2) + 4 * (L % 4)) * 2;
+          const u32x2 lo = lds_read_tr16(p);
+          const u32x2 hi = lds_read_tr16(p + 8 * SM::kVStride);
+          u32x4 a;
+          a[0] = lo[0];
+          a[1] = lo[1];
+          a[2] = hi[0];
+          a[3] = hi[1];
+          acc[rb] = mfma32(a, pb[ks2], acc[rb]);
+        }
+      }
+    }
+    eta += partner32(eta);
+    const float dn = eta + g.eps;
+    const float inv = 1.0f / dn;
+    if (live && gl == 0) den[g.th(e.b, h, n)] = dn;
+    store_rows_bf16<D>(acc, inv, lane, tile, [&](int t) -> bf16_t* {
+      return n0 + t < e.t1 ? O.row<bf16_t>(e.b, h, n0 + t) : nullptr;
+    });
+  }
+}
+
 // ---- k_bwd_query ------------------------------------------------------------------------------
 template <int D, int MP>
 struct BwdQSmem {
@@ -1037,7 +1283,28 @@ hla_status forward_core(hla_handle* hd, const hla_call_args& a) {
 }
 
 template <class SY, int D>
+hla_status forward_causal(hla_handle* hd, const hla_call_args& a) {
+  using SL = StateLayout<SY, D>;
+  using SM = StateSmem<D, SY::MP>;
+  using SC = CausalSmem<SY, D>;
+  Geom g = hd->g;
+  hipStream_t s = a.stream;
+  hla_token_table* cch = nullptr;
+  HLA_TRY(get_table(hd, 2, kCausalChunk, s, &cch));
+  if (static_cast<int64_t>(cch->count) * g.H > hd->max_chunks * hd->cfg.max_heads) return HLA_ERR_INVALID_ARG;
+  unsigned char* pfx = static_cast<unsigned char*>(hd->path_ws) + hd->causal_off;
+  HLA_TRY(launch(hd, "mfma_state", k_state<SY, D>, dim3(cch->count, g.H), dim3(kThreads), SM::kTotal, s,
+                 g, cch->dev, hd->feat, a.V, hd->partial, SL::kF32));
+  HLA_TRY(launch(hd, "mfma_state_prefix", k_prefix<SY, D>, dim3(a.num_seqs, g.H, kReduceSlices), dim3(256),
+                 0, s, g, cch->seq_off_dev, hd->partial, SL::kF32, pfx, make_slot_map<SY>()));
+  HLA_TRY(launch(hd, "mfma_query_causal", k_query_causal<SY, D>, dim3(cch->count, g.H), dim3(kThreads),
+                 SC::kTotal, s, g, cch->dev, hd->feat, a.V, pfx, a.O, hd->den));
+  return HLA_OK;
+}
+
+template <class SY, int D>
 hla_status prepare_core() {
+  HLA_TRY(allow_big_lds(&k_query_causal<SY, D>, CausalSmem<SY, D>::kTotal));
   HLA_TRY(allow_big_lds(&k_state<SY, D>, StateSmem<D, SY::MP>::kTotal));
   return allow_big_lds(&k_bwd_query<SY, D>, BwdQSmem<D, SY::MP>::kTotal);
 }
@@ -1082,11 +1349,19 @@ hla_status mfma_workspace_plan(hla_handle* hd) {
   hd->yhat_floats = 1;
   hd->tables[0].min_block = kMinChunk;
   hd->tables[1].min_block = kMinQueryBlock;
+  if (hd->cfg.causal) {  // one partial state and one prefix image per chunk of kCausalChunk tokens
+    hd->tables[2].min_block = kCausalChunk;
+    const int64_t cc = (hd->cfg.max_tokens + kCausalChunk - 1) / kCausalChunk + hd->cfg.max_seqs;
+    if (cc > hd->max_chunks) hd->max_chunks = cc;
+  }
   // per unit: opA + opB (bf16) + zslot, for the state and for its gradient
   const int64_t op_bytes = 2 * MP * g.d * 2 + 2 * SP * 4;
   hd->path_ws_bytes = static_cast<size_t>(2 * op_bytes * hd->max_units);
   hd->w_packed_off = hd->path_ws_bytes;
   if (hd->cfg.phi_mode == HLA_PHI_MLP) hd->path_ws_bytes += mfma_phi_packed_bytes(hd);
+  hd->causal_off = hd->path_ws_bytes;
+  if (hd->cfg.causal)
+    hd->path_ws_bytes += static_cast<size_t>(hd->max_chunks * hd->cfg.max_heads * (MP * g.d * 2 + 2 * SP * 4));
   return HLA_OK;
 }
 
@@ -1102,6 +1377,7 @@ hla_status mfma_set_weights(hla_handle* hd, hipStream_t s) { return mfma_phi_set
 
 template <class SY>
 static hla_status forward_sym(hla_handle* hd, const hla_call_args& a) {
+  if (hd->cfg.causal) return hd->g.d == 128 ? forward_causal<SY, 128>(hd, a) : forward_causal<SY, 64>(hd, a);
   return hd->g.d == 128 ? forward_core<SY, 128>(hd, a) : forward_core<SY, 64>(hd, a);
 }
 template <class SY>

@@ -1,0 +1,108 @@
+"""GPU parity of the causal variant (Sec. 4.4: token i attends to tokens j <= i) through the C ABI,
+forward only: full comparison with the oracle's masked N x N matrix at sizes that span several
+chunks of the scan with ragged tails, sampled rows at the video-DiT size, packed sequences
+without leaks, both forms, through the feature maps, and the error codes."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2602_12128_amd as hla
+from oracle import hla_oracle as orc
+from paper_2602_12128_amd import workloads as wl
+from tests import parity_utils as pu
+
+pytestmark = pytest.mark.gpu
+
+
+def _causal_gpu(t, F, dphi, phi=None, cu=None):
+    dev = torch.device("cuda:0")
+    B, H, N, d = t["V"].shape
+    nseq = B if cu is None else len(cu) - 1
+    h = hla.HLA(head_dim=d, feature_dim=dphi, degree=F, eps=1e-6, io_dtype=hla.HLA_BF16,
+                phi_mode=hla.HLA_PHI_NONE if phi is None else hla.HLA_PHI_MLP, max_heads=H,
+                max_tokens=B * N, max_seqs=max(nseq, 1), causal=True)
+    assert h.active_path == hla.HLA_PATH_MFMA
+    if phi is not None:
+        h.set_phi_weights([{k: v.to(dev) for k, v in m.items()} for m in phi])
+    td = {k: v.to(dev) for k, v in t.items()}
+    O = torch.full_like(td["V"], float("nan"))
+    h.forward(td["Q"], td["K"], td["V"], O, cu_seqlens=cu)
+    torch.cuda.synchronize()
+    return h, O.cpu()
+
+
+def _causal_oracle(t, F, dphi, phi=None, cu=None):
+    Q, K, V = (pu.to_np(t[k]) for k in ("Q", "K", "V"))
+    return orc.hla_operator_forward(Q, K, V, F, dphi, 1e-6, phi=pu.oracle_phi(phi), cu_seqlens=cu,
+                                    route="bruteforce", causal=True)
+
+
+@pytest.mark.parametrize("F,dphi,d,B,H,N,kind", [
+    (3, 6, 128, 1, 2, 1000, "halfnormal"),   # four chunks, ragged last one
+    (3, 6, 64, 2, 3, 777, "lognormal"),
+    (2, 12, 128, 1, 2, 600, "halfnormal"),
+    (2, 12, 64, 1, 1, 256, "lognormal"),     # exactly one chunk
+    (3, 6, 128, 1, 1, 33, "halfnormal"),     # less than two tiles
+    (3, 6, 128, 2, 2, 1, "halfnormal"),      # one token: it sees itself only
+])
+def test_causal_feature_level_bf16(F, dphi, d, B, H, N, kind):
+    t = wl.make_feature_inputs(1200 + N, B, H, N, d, F, dphi, torch.bfloat16, kind=kind)
+    h, got = _causal_gpu(t, F, dphi)
+    h.destroy()
+    ref = _causal_oracle(t, F, dphi)
+    pu.assert_parity({"O": got}, {"O": ref}, 2e-2, f"causal features F={F} d={d} N={N}")
+    if N > 1:  # and it is not the non-causal result
+        plain = pu.run_oracle(t, F, dphi, 1e-6, backward=False)["O"]
+        assert np.abs(ref - plain).max() > 1e-2 * np.abs(plain).max()
+
+
+def test_causal_through_feature_maps_packed_no_leak():
+    cu = [0, 100, 100, 1500, 1501, 2600]
+    t, phi = wl.make_raw_inputs(1210, 1, 2, cu[-1], 128, 3, 6, torch.bfloat16)
+    h, got = _causal_gpu(t, 3, 6, phi=phi, cu=cu)
+    ref = _causal_oracle(t, 3, 6, phi=phi, cu=cu)
+    pu.assert_parity({"O": got}, {"O": ref}, 2e-2, "causal packed through the maps")
+    # later tokens never reach earlier ones, inside a sequence or across sequences: perturbing
+    # tokens from 2000 on leaves every output before 2000 bit-identical
+    t2 = {k: v.clone() for k, v in t.items()}
+    for k in ("Q", "K", "V"):
+        t2[k][:, :, 2000:] = (t2[k][:, :, 2000:].float() * 1.5 + 0.01).to(torch.bfloat16)
+    dev = torch.device("cuda:0")
+    td = {k: v.to(dev) for k, v in t2.items()}
+    O2 = torch.empty_like(td["V"])
+    h.forward(td["Q"], td["K"], td["V"], O2, cu_seqlens=cu)
+    torch.cuda.synchronize()
+    assert torch.equal(got[:, :, :2000], O2.cpu()[:, :, :2000])
+    assert not torch.equal(got[:, :, 2000:], O2.cpu()[:, :, 2000:])
+    # a causal handle has no backward
+    with pytest.raises(hla.HLAError) as e:
+        g = [torch.empty_like(td[k]) for k in "QKV"]
+        h.backward(td["Q"], td["K"], td["V"], O2, td["V"], *g, cu_seqlens=cu)
+    assert e.value.code == 2
+    h.destroy()
+    with pytest.raises(hla.HLAError) as e:  # no scan on the fp32 kernels
+        hla.HLA(head_dim=32, feature_dim=6, degree=3, io_dtype=hla.HLA_F32, phi_mode=hla.HLA_PHI_NONE,
+                max_heads=1, max_tokens=8, max_seqs=1, causal=True)
+    assert e.value.code == 2
+
+
+def test_causal_video_size_sampled_rows():
+    # the 480p video shape (Sec. 5.1) with the causal mask: every output is produced, sampled query
+    # rows of three heads are recomputed from the masked definition over all their keys
+    w = wl.make_workload(3, need_backward=False)
+    h, got = _causal_gpu(w.tensors, w.F, w.d_phi, phi=w.phi)
+    h.destroy()
+    assert torch.isfinite(got.float()).all()
+    ophi = pu.oracle_phi(w.phi)
+    rng = np.random.default_rng(7)
+    rows = np.sort(np.concatenate([[0, 1, 31, 32, 255, 256, 257, w.N - 1], rng.choice(w.N, 56, replace=False)]))
+    worst = 0.0
+    for hh in (0, 5, 11):
+        K = pu.to_np(w.tensors["K"][0, hh])
+        kfs = [orc.phi_forward(K, *ophi[1 + f].astuple())[0] for f in range(w.F)]
+        qf = orc.phi_forward(pu.to_np(w.tensors["Q"][0, hh]), *ophi[0].astuple())[0]
+        ref = orc.hla_causal_bruteforce(qf, kfs, pu.to_np(w.tensors["V"][0, hh]), w.eps, rows=rows)
+        g = pu.to_np(got[0, hh][rows])
+        worst = max(worst, float(np.abs(g - ref).max() / np.abs(ref).max()))
+    print(f"[parity] causal 480p sampled rows: worst rel err {worst:.2e} (tol 0.02)", flush=True)
+    assert worst <= 2e-2
