@@ -455,60 +455,95 @@ struct PrefixLayout {
   static constexpr int64_t kBytes = kOpElems * 2 + 2 * SY::SP * 4;        // then the normaliser by slot
 };
 
-// grid (num_seqs, H, kReduceSlices), block 256.  Thread-owned entries as in k_reduce; the sum so far
-// is written for chunk c before chunk c's partial is added.
+// canonical monomial of slot (g, s), -1 for padding slots: the inverse of SlotMap
+struct CanonMap {
+  int8_t m[2][64];
+};
+template <class SY>
+CanonMap make_canon_map() {
+  CanonMap cm{};
+  for (int g = 0; g < 2; ++g)
+    for (int s = 0; s < 64; ++s) cm.m[g][s] = static_cast<int8_t>(s < SY::SP ? SY::slot_canon(g, s) : -1);
+  return cm;
+}
+
+// grid (num_seqs, H, 2 * NKS * D / 256), block 256.  A thread owns the eight slots (g, 8 ks .. 8 ks + 7)
+// of one channel c: eight running sums, read from the eight partial rows of those monomials at
+// column c (consecutive threads: consecutive floats), written for chunk ch -- before chunk ch's own
+// partial is added -- as the 16 bytes these eight slots occupy in the operand image (consecutive
+// threads of a 32-channel block: consecutive 16-byte pieces).  Padding slots are written as zeros.
 template <class SY, int D>
 __global__ __launch_bounds__(256) void k_prefix(Geom g, const int32_t* __restrict__ seq_chunk_off,
                                                 const float* __restrict__ partial,
                                                 int64_t partial_stride, unsigned char* __restrict__ pfx,
-                                                SlotMap sm) {
+                                                CanonMap cm) {
   using PL = PrefixLayout<SY, D>;
-  constexpr int MP = SY::MP, SP = SY::SP;
-  constexpr int VPR = D / 4;
-  constexpr int PER = MP * VPR / kReduceSlices;
-  const int s = blockIdx.x, h = blockIdx.y, sl = blockIdx.z;
+  constexpr int MP = SY::MP, SP = SY::SP, NKS = MP / 16;
+  const int s = blockIdx.x, h = blockIdx.y;
   const int c0 = seq_chunk_off[s], c1 = seq_chunk_off[s + 1];
-  const float* base = partial + static_cast<int64_t>(h) * partial_stride;
+  const int item = blockIdx.z * 256 + threadIdx.x;  // (mg, ks, c)
+  const int c = item % D, ks = (item / D) % NKS, mg = item / (D * NKS);
+  const float* base = partial + static_cast<int64_t>(h) * partial_stride + c;
   const int64_t cstride = static_cast<int64_t>(g.H) * partial_stride;
-  constexpr int NB = 8;  // chunk loads in flight
-  for (int idx = threadIdx.x; idx < PER; idx += blockDim.x) {
-    const int v = sl * PER + idx;
-    const int m = v / VPR, c = (v % VPR) * 4;
-    const int mg = sm.g[m], ms = sm.s[m];
-    f32x4 a;
-    a[0] = a[1] = a[2] = a[3] = 0.0f;
-    const float* p0 = base + m * D + c;
-    for (int ch = c0; ch < c1; ch += NB) {
-      f32x4 ld[NB];
+  int row[8];
 #pragma unroll
-      for (int k = 0; k < NB; ++k)
-        ld[k] = *reinterpret_cast<const f32x4*>(p0 + (ch + k < c1 ? ch + k : c1 - 1) * cstride);
+  for (int j = 0; j < 8; ++j) row[j] = cm.m[mg][8 * ks + j];
+  float acc[8];
 #pragma unroll
-      for (int k = 0; k < NB; ++k) {
-        if (ch + k >= c1) break;
-        if (mg >= 0) {
-          uint16_t* opA = reinterpret_cast<uint16_t*>(pfx + (static_cast<int64_t>(ch + k) * g.H + h) * PL::kBytes);
-          const int ks = ms / 8, j = ms % 8;
+  for (int j = 0; j < 8; ++j) acc[j] = 0.0f;
+  const int rb = c / 32, r = c % 32;
+  constexpr int NB = 8;  // chunks in flight
+  for (int ch = c0; ch < c1; ch += NB) {
+    float ld[NB][8];
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int rb = (c + e) / 32, r = (c + e) % 32;
-            opA[((rb * (MP / 16) + ks) * 64 + 32 * mg + r) * 8 + j] = f32_to_bf16_bits(a[e]);
-          }
-        }
-        a += ld[k];
-      }
+    for (int k = 0; k < NB; ++k) {
+      const float* p = base + (ch + k < c1 ? ch + k : c1 - 1) * cstride;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) ld[k][j] = row[j] >= 0 ? p[row[j] * D] : 0.0f;
+    }
+#pragma unroll
+    for (int k = 0; k < NB; ++k) {
+      if (ch + k >= c1) break;
+      u32x4 w;
+#pragma unroll
+      for (int p = 0; p < 4; ++p) w[p] = pack_bf16(acc[2 * p], acc[2 * p + 1]);
+      u32x4* opA = reinterpret_cast<u32x4*>(pfx + (static_cast<int64_t>(ch + k) * g.H + h) * PL::kBytes);
+      opA[(rb * NKS + ks) * 64 + 32 * mg + r] = w;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc[j] += ld[k][j];
     }
   }
-  if (sl == 0) {
-    for (int m = threadIdx.x; m < MP; m += blockDim.x) {
-      const int mg = sm.g[m], ms = sm.s[m];
-      float a = 0.0f;
-      for (int ch = c0; ch < c1; ++ch) {
-        if (mg >= 0) {
-          float* zslot = reinterpret_cast<float*>(pfx + (static_cast<int64_t>(ch) * g.H + h) * PL::kBytes + PL::kOpElems * 2);
-          zslot[mg * SP + ms] = a;
+  // the normaliser vector by slot, carried by the threads of channel 0; loads batched like the
+  // rows above (a load per chunk issued next to the store that needs it would cost one memory
+  // round trip per chunk)
+  if (c == 0) {
+    float z[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) z[j] = 0.0f;
+    const float* zb = partial + static_cast<int64_t>(h) * partial_stride + MP * D;
+    constexpr int NZ = 16;
+    for (int ch = c0; ch < c1; ch += NZ) {
+      float ld[NZ][8];
+#pragma unroll
+      for (int k = 0; k < NZ; ++k) {
+        const float* p = zb + (ch + k < c1 ? ch + k : c1 - 1) * cstride;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) ld[k][j] = row[j] >= 0 ? p[row[j]] : 0.0f;
+      }
+#pragma unroll
+      for (int k = 0; k < NZ; ++k) {
+        if (ch + k >= c1) break;
+        float* zslot = reinterpret_cast<float*>(pfx + (static_cast<int64_t>(ch + k) * g.H + h) * PL::kBytes + PL::kOpElems * 2);
+        f32x4 lo, hi;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          lo[j] = z[j];
+          hi[j] = z[4 + j];
         }
-        a += base[ch * cstride + MP * D + m];
+        *reinterpret_cast<f32x4*>(zslot + mg * SP + 8 * ks) = lo;
+        *reinterpret_cast<f32x4*>(zslot + mg * SP + 8 * ks + 4) = hi;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) z[j] += ld[k][j];
       }
     }
   }
@@ -1295,8 +1330,9 @@ hla_status forward_causal(hla_handle* hd, const hla_call_args& a) {
   unsigned char* pfx = static_cast<unsigned char*>(hd->path_ws) + hd->causal_off;
   HLA_TRY(launch(hd, "mfma_state", k_state<SY, D>, dim3(cch->count, g.H), dim3(kThreads), SM::kTotal, s,
                  g, cch->dev, hd->feat, a.V, hd->partial, SL::kF32));
-  HLA_TRY(launch(hd, "mfma_state_prefix", k_prefix<SY, D>, dim3(a.num_seqs, g.H, kReduceSlices), dim3(256),
-                 0, s, g, cch->seq_off_dev, hd->partial, SL::kF32, pfx, make_slot_map<SY>()));
+  static_assert(2 * (SY::MP / 16) * D % 256 == 0, "whole workgroups of prefix items");
+  HLA_TRY(launch(hd, "mfma_state_prefix", k_prefix<SY, D>, dim3(a.num_seqs, g.H, 2 * (SY::MP / 16) * D / 256),
+                 dim3(256), 0, s, g, cch->seq_off_dev, hd->partial, SL::kF32, pfx, make_canon_map<SY>()));
   HLA_TRY(launch(hd, "mfma_query_causal", k_query_causal<SY, D>, dim3(cch->count, g.H), dim3(kThreads),
                  SC::kTotal, s, g, cch->dev, hd->feat, a.V, pfx, a.O, hd->den));
   return HLA_OK;
