@@ -152,6 +152,7 @@ void free_all(hla_handle* hd) {
     (void)hipFree(hd->w_f32);
     (void)hipFree(hd->wg_partial);
     (void)hipFree(hd->vmod_w);
+    (void)hipFree(hd->vmod_wpk);
     (void)hipFree(hd->vmod_T);
     (void)hipFree(hd->vmod_dT);
     (void)hipFree(hd->vmod_dV);
@@ -400,14 +401,21 @@ hla_status hla_set_value_modulation(hla_handle* hd, const hla_vmod_weights* maps
     if (st == HLA_OK) st = arena.alloc(&t, static_cast<size_t>(hd->max_th) * d * elem);
     if (st == HLA_OK) st = arena.alloc(&dt, static_cast<size_t>(hd->max_th) * d * elem);
     if (st == HLA_OK) st = arena.alloc(&dv, static_cast<size_t>(hd->max_th) * d * elem);
+    unsigned char* wpk = nullptr;
+    if (st == HLA_OK && vmod_mfma_supported(hd)) {
+      st = arena.alloc(&wpk, vmod_mfma_workspace_bytes(hd));
+      if (st == HLA_OK) st = vmod_mfma_prepare_kernels(hd);
+    }
     if (st != HLA_OK) {
       (void)hipFree(hd->vmod_w);
+      (void)hipFree(wpk);
       (void)hipFree(t);
       (void)hipFree(dt);
       (void)hipFree(dv);
       hd->vmod_w = nullptr;
       return st;
     }
+    hd->vmod_wpk = wpk;
     hd->vmod_T = t;
     hd->vmod_dT = dt;
     hd->vmod_dV = dv;

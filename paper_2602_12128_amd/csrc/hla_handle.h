@@ -68,6 +68,7 @@ struct hla_handle {
   bool vmod_on = false;
   float vmod_ln_eps = 0.0f;
   float* vmod_w = nullptr;
+  unsigned char* vmod_wpk = nullptr;  // matrix-core kernels' packed copy of the two maps and their scratch (if used)
   void* vmod_T = nullptr;
   void* vmod_dT = nullptr;
   void* vmod_dV = nullptr;
@@ -138,6 +139,15 @@ hla_status vmod_forward(hla_handle* hd, const hla_call_args& a);
 hla_status vmod_backward(hla_handle* hd, const hla_call_args& a);
 hla_status vmod_add_value_grads(hla_handle* hd, const hla_call_args& a);
 View vmod_view(void* p, const Geom& g);  // contiguous [B, H, N, d] view of a workspace array
+// The same on the matrix cores (hla_mfma_vmod.hip), used by the functions above where supported.
+bool vmod_mfma_supported(const hla_handle* hd);
+size_t vmod_mfma_packed_bytes(const hla_handle* hd);
+size_t vmod_mfma_workspace_bytes(const hla_handle* hd);  // packed weights + the backward's stash
+hla_status vmod_mfma_prepare_kernels(const hla_handle* hd);
+hla_status vmod_mfma_set_weights(hla_handle* hd, const hla_vmod_weights* maps, hipStream_t s);
+hla_status vmod_mfma_forward(hla_handle* hd, const hla_call_args& a);
+hla_status vmod_mfma_backward(hla_handle* hd, const hla_call_args& a);
+hla_status vmod_mfma_add_value_grads(hla_handle* hd, const hla_call_args& a);
 
 // Shared helper kernels' host wrappers (hla_generic.hip).
 hla_status convert_weights_to_f32(hla_handle* hd, const hla_phi_weights* maps, hipStream_t s);

@@ -1,0 +1,644 @@
+// Value modulation (paper Sec. 4.5) on the matrix cores, bf16 I/O, head dim 64 or 128:
+//   O = T + phi_v1(T) * phi_v2(V),   phi_v (App. A.1) = Linear d->d, GELU, Linear d->d, LayerNorm,
+// forward and the backward to (dT, dV).
+//
+// A token is an MFMA column (lane (r, gl): token r of a 32-token tile, half gl), as in the feature
+// maps.  Every product takes its A operand from the LDS copy of a weight matrix with lane r
+// addressing matrix row swap23(r) (bits 2 and 3 of the row exchanged) instead of row r.  With that
+// the accumulator register i of row block b on lane (r, gl) holds row
+//        32 b + 16 (i / 8) + 8 gl + i % 8
+// of the product: eight CONSECUTIVE rows per lane half, which is at once
+//   - the order in which a lane loads its token's input channels (one 16-byte piece per k-step),
+//   - the k-slot order of the B operand of the next product (packed straight from the registers,
+//     its A operand again a plain 16-byte LDS read at natural columns),
+//   - the order of a token row in memory (outputs leave as 16-byte pieces, no lane exchange).
+// Forward per map:   y^T = (W1^T/4) X^T + b1/4,  g = GELU(4y)/4 (packed fp16),  u^T = (4 W2^T) g^T + b2,
+// LayerNorm over the 128 channels of a token = over 64 registers of a lane and its partner lane.
+// Backward per map:  dg^T = W2 du^T,  dh = dg * GELU'(4y),  dx^T = W1 dh^T, with the A operands
+// read from the same LDS copies by transpose reads.  du is handed to the matrix cores in fp16
+// scaled per token to unit Euclidean norm (the scale goes back on dx, which is linear in du), so
+// its range does not depend on the size of the upstream gradient or of 1/std.
+// The weights of both maps stay resident in LDS; each wave streams its own 32-token tiles and two
+// waves share a SIMD.
+#include "hla_handle.h"
+#include "hla_mfma_common.h"
+#include "hla_mfma_gelu.h"
+
+namespace hla {
+namespace {
+
+using namespace mf;
+
+constexpr int kWavesV = 8;    // waves per workgroup (one workgroup per compute unit: LDS)
+constexpr int kRowsOut = 8;   // token rows of a wave's output tile in LDS (a tile leaves in 32/8 passes)
+
+// packed weights of one map in global memory
+template <int D>
+struct VPacked {
+  static constexpr int kW1T = 0;                  // bf16 [D][D]: row = hidden unit, col = input channel; times 1/4
+  static constexpr int kW2T = kW1T + D * D * 2;   // fp16 [D][D]: row = output channel, col = hidden unit; times 4
+  static constexpr int kB1 = kW2T + D * D * 2;    // fp32 [D]; times 1/4
+  static constexpr int kB2 = kB1 + D * 4;         // fp32 [D]
+  static constexpr int kGamma = kB2 + D * 4;      // fp32 [D]
+  static constexpr int kBeta = kGamma + D * 4;    // fp32 [D]
+  static constexpr int kBytes = kBeta + D * 4;
+};
+
+template <typename T>
+__global__ void k_vmod_pack_mfma(const T* W1, const T* b1, const T* W2, const T* b2, const T* gamma,
+                                 const T* beta, int d, unsigned char* __restrict__ out) {
+  // W1, W2 are [in][out] row-major
+  uint16_t* w1t = reinterpret_cast<uint16_t*>(out);
+  uint16_t* w2t = w1t + d * d;
+  float* vec = reinterpret_cast<float*>(w2t + d * d);
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < d * d; i += gridDim.x * blockDim.x) {
+    const int row = i / d, col = i % d;  // row = output of the layer, col = its input
+    w1t[i] = f32_to_bf16_bits(kHiddenScale * to_float(W1[col * d + row]));
+    w2t[i] = __builtin_bit_cast(uint16_t, static_cast<_Float16>(to_float(W2[col * d + row]) / kHiddenScale));
+    if (i < d) {
+      vec[i] = kHiddenScale * to_float(b1[i]);
+      vec[d + i] = to_float(b2[i]);
+      vec[2 * d + i] = to_float(gamma[i]);
+      vec[3 * d + i] = to_float(beta[i]);
+    }
+  }
+}
+
+// LDS: per map the two matrices row-major with swizzled 16-byte chunks (tile_off), then the four
+// vectors; after the maps one output tile per wave.
+template <int D>
+struct VSmem {
+  static constexpr int kRowB = D * 2;
+  static constexpr int kW1 = 0;
+  static constexpr int kW2 = D * D * 2;
+  static constexpr int kVec = 2 * D * D * 2;   // b1/4, b2, gamma, beta
+  static constexpr int kMap = kVec + 4 * D * 4;
+  static constexpr int total(int waves) { return 2 * kMap + waves * RowTile<D, kRowsOut>::kBytes; }
+};
+
+__host__ __device__ __forceinline__ int swap23(int r) { return (r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1); }
+
+template <int D, int THREADS>
+__device__ __forceinline__ void load_map(unsigned char* dst, const unsigned char* src) {
+  using SM = VSmem<D>;
+  constexpr int CH = D / 8;           // 16-byte chunks per matrix row
+  constexpr int NM = 2 * D * CH;      // chunks of both matrices
+  constexpr int IT = (NM + THREADS - 1) / THREADS;
+  static_assert(NM % THREADS == 0 && D * 4 * 4 / 16 <= THREADS, "copy loops assume whole rounds");
+  const int t = threadIdx.x;
+  u32x4 v[IT];
+#pragma unroll
+  for (int k = 0; k < IT; ++k) v[k] = *reinterpret_cast<const u32x4*>(src + (t + k * THREADS) * 16);
+  u32x4 vv;
+  if (t < D) vv = *reinterpret_cast<const u32x4*>(src + VPacked<D>::kB1 + t * 16);
+#pragma unroll
+  for (int k = 0; k < IT; ++k) {
+    const int i = t + k * THREADS;
+    const int mat = i / (D * CH), row = (i / CH) % D, chunk = i % CH;
+    *reinterpret_cast<u32x4*>(dst + mat * SM::kW2 + tile_off<SM::kRowB>(row, chunk)) = v[k];
+  }
+  if (t < D) *reinterpret_cast<u32x4*>(dst + SM::kVec + t * 16) = vv;
+}
+
+// the lane's share of a token row as B operands / in accumulator order: one 16-byte piece per
+// k-step, channels 16 ks + 8 gl .. + 7.  Rows at or beyond N read the last row.
+template <int D>
+__device__ __forceinline__ void load_row(const View& X, int b, int h, int n, int N, int gl,
+                                         u32x4 (&x)[D / 16]) {
+  const bf16_t* row = X.row<const bf16_t>(b, h, n < N ? n : N - 1);
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ++ks) x[ks] = *reinterpret_cast<const u32x4*>(row + 16 * ks + 8 * gl);
+}
+
+// 16 entries of an fp32 vector in LDS in accumulator order of row block rb
+__device__ __forceinline__ f32x16 vec_block(const float* v, int rb, int gl) {
+  f32x16 z;
+#pragma unroll
+  for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      const f32x4 t = *reinterpret_cast<const f32x4*>(v + 32 * rb + 16 * hf + 8 * gl + 4 * q);
+      z[8 * hf + 4 * q] = t[0];
+      z[8 * hf + 4 * q + 1] = t[1];
+      z[8 * hf + 4 * q + 2] = t[2];
+      z[8 * hf + 4 * q + 3] = t[3];
+    }
+  return z;
+}
+
+// entry i of a token row held as packed bf16 pieces (register i of block rb <-> piece 2 rb + i / 8)
+template <int D>
+__device__ __forceinline__ float row_entry(const u32x4 (&x)[D / 16], int rb, int i) {
+  const uint32_t p = x[2 * rb + i / 8][(i % 8) / 2];
+  return i % 2 ? bf16_hi(p) : bf16_lo(p);
+}
+
+// entry i of a vector held as packed fp16 pieces in the same order
+template <int D>
+__device__ __forceinline__ float half_entry(const u32x4 (&x)[D / 16], int rb, int i) {
+  const uint32_t w = x[2 * rb + i / 8][(i % 8) / 2];  // (a bit_cast applied to the element expression itself reads element 0)
+  const f16x2 p = __builtin_bit_cast(f16x2, w);
+  return static_cast<float>(p[i % 2]);
+}
+
+struct TileWalk {
+  int tiles_per_row, total, H;
+  __device__ __forceinline__ void decode(int t, int& b, int& h, int& n0) const {
+    const int row = t / tiles_per_row;
+    b = row / H;
+    h = row % H;
+    n0 = (t % tiles_per_row) * 32;
+  }
+};
+
+// First layer of one map for hidden block rb: y = h/4 of the 16 hidden units the lane holds
+template <int D>
+__device__ __forceinline__ f32x16 first_layer_block(const unsigned char* wm, const int (&a_off)[D / 16], int gl,
+                                                    const u32x4 (&x)[D / 16], int rb) {
+  using SM = VSmem<D>;
+  f32x16 hb = vec_block(reinterpret_cast<const float*>(wm + SM::kVec), rb, gl);
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ++ks)
+    hb = mfma32(*reinterpret_cast<const u32x4*>(wm + SM::kW1 + rb * 32 * SM::kRowB + a_off[ks]), x[ks], hb);
+  return hb;
+}
+
+// One map applied to the token rows in x: on return u holds u-hat (the LayerNorm's normalised
+// value, before gamma and beta) in accumulator order and rstd the token's 1/std.
+template <int D>
+__device__ __forceinline__ void map_forward(const unsigned char* wm, const int (&a_off)[D / 16], int gl,
+                                            const u32x4 (&x)[D / 16], float ln_eps,
+                                            f32x16 (&u)[D / 32], float& rstd) {
+  using SM = VSmem<D>;
+  constexpr int NRB = D / 32;
+  const float* vec = reinterpret_cast<const float*>(wm + SM::kVec);
+#pragma unroll
+  for (int ob = 0; ob < NRB; ++ob) u[ob] = vec_block(vec + D, ob, gl);
+#pragma unroll
+  for (int rb = 0; rb < NRB; ++rb) {
+    const f32x16 hb = first_layer_block<D>(wm, a_off, gl, x, rb);
+    f16x2 y[8];
+#pragma unroll
+    for (int p = 0; p < 8; ++p) y[p] = to_f16x2(hb[2 * p], hb[2 * p + 1]);
+    uint32_t gp[8];
+    gelu_y16<8>(y, gp);
+    u32x4 gb[2];
+#pragma unroll
+    for (int p = 0; p < 8; ++p) gb[p / 4][p % 4] = gp[p];
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+      for (int ob = 0; ob < NRB; ++ob)
+        u[ob] = mfma32_f16(*reinterpret_cast<const u32x4*>(wm + SM::kW2 + ob * 32 * SM::kRowB + a_off[2 * rb + hf]),
+                           gb[hf], u[ob]);
+    __builtin_amdgcn_sched_barrier(0);  // keeps the operand reads of later blocks from piling up in registers
+  }
+  // LayerNorm statistics of the token: this lane's D/2 channels and the partner lane's
+  float s = 0.0f;
+#pragma unroll
+  for (int ob = 0; ob < NRB; ++ob)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s += u[ob][i];
+  s += partner32(s);
+  const float mean = s * (1.0f / D);
+  float v = 0.0f;
+#pragma unroll
+  for (int ob = 0; ob < NRB; ++ob)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      u[ob][i] -= mean;
+      v = __builtin_fmaf(u[ob][i], u[ob][i], v);
+    }
+  v += partner32(v);
+  rstd = 1.0f / sqrtf(v * (1.0f / D) + ln_eps);
+#pragma unroll
+  for (int ob = 0; ob < NRB; ++ob)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) u[ob][i] *= rstd;
+}
+
+// 16 accumulator entries -> the two 16-byte bf16 pieces of the token row they stand for
+__device__ __forceinline__ void pack_block(const f32x16& a, u32x4 (&w)[2]) {
+#pragma unroll
+  for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+    for (int p = 0; p < 4; ++p) w[hf][p] = pack_bf16(a[8 * hf + 2 * p], a[8 * hf + 2 * p + 1]);
+}
+
+template <int D, class RowPtr>
+__device__ __forceinline__ void store_tile(const u32x4 (&w)[D / 32][2], int lane, unsigned char* lds,
+                                           RowPtr&& row_ptr) {
+#pragma unroll
+  for (int pass = 0; pass < 32 / kRowsOut; ++pass) {
+    put_rows<D, kRowsOut>(w, pass, lane, lds);
+    flush_rows<D, kRowsOut>(pass, lane, lds, row_ptr);
+  }
+}
+
+template <int D>
+__device__ __forceinline__ void first_layer_offsets(int lane, int (&a_off)[D / 16]) {
+  const int r = lane % 32, gl = lane / 32;
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ++ks) a_off[ks] = tile_off<D * 2>(swap23(r), 2 * ks + gl);
+}
+
+// grid: one workgroup per compute unit, block WAVES*64.  Tin holds T; O receives T + phi_v1(T) * phi_v2(V).
+template <int D, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void k_vmod_fwd_mfma(Geom g, const unsigned char* __restrict__ wpk,
+                                                              float ln_eps, View Tin, View V, View O) {
+  using SM = VSmem<D>;
+  constexpr int NRB = D / 32, NKS = D / 16;
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int lane = threadIdx.x % kWave, wave = wave_index();
+  const int r = lane % 32, gl = lane / 32;
+  load_map<D, WAVES * 64>(smem, wpk);
+  load_map<D, WAVES * 64>(smem + SM::kMap, wpk + VPacked<D>::kBytes);
+  __syncthreads();
+  unsigned char* otile = smem + 2 * SM::kMap + wave * RowTile<D, kRowsOut>::kBytes;
+  int a_off[NKS];
+  first_layer_offsets<D>(lane, a_off);
+  TileWalk tw;
+  tw.tiles_per_row = (g.N + 31) / 32;
+  tw.total = tw.tiles_per_row * g.B * g.H;
+  tw.H = g.H;
+  const int stride = gridDim.x * WAVES;
+  for (int tile = blockIdx.x * WAVES + wave; tile < tw.total; tile += stride) {
+    int b, h, n0;
+    tw.decode(tile, b, h, n0);
+    u32x4 xt[NKS];
+    load_row<D>(Tin, b, h, n0 + r, g.N, gl, xt);
+    f32x16 m1[NRB], m2[NRB];
+    float rstd;
+    map_forward<D>(smem, a_off, gl, xt, ln_eps, m1, rstd);
+    {
+      const float* vec = reinterpret_cast<const float*>(smem + SM::kVec);
+#pragma unroll
+      for (int ob = 0; ob < NRB; ++ob) {
+        const f32x16 ga = vec_block(vec + 2 * D, ob, gl), be = vec_block(vec + 3 * D, ob, gl);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) m1[ob][i] = __builtin_fmaf(m1[ob][i], ga[i], be[i]);
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    load_row<D>(V, b, h, n0 + r, g.N, gl, xt);
+    map_forward<D>(smem + SM::kMap, a_off, gl, xt, ln_eps, m2, rstd);
+    __builtin_amdgcn_sched_barrier(0);
+    load_row<D>(Tin, b, h, n0 + r, g.N, gl, xt);  // T again, for the sum (still in the caches)
+    u32x4 w[NRB][2];
+    {
+      const float* vec = reinterpret_cast<const float*>(smem + SM::kMap + SM::kVec);
+#pragma unroll
+      for (int ob = 0; ob < NRB; ++ob) {
+        const f32x16 ga = vec_block(vec + 2 * D, ob, gl), be = vec_block(vec + 3 * D, ob, gl);
+        f32x16 o;
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+          o[i] = __builtin_fmaf(m1[ob][i], __builtin_fmaf(m2[ob][i], ga[i], be[i]), row_entry<D>(xt, ob, i));
+        pack_block(o, w[ob]);
+      }
+    }
+    store_tile<D>(w, lane, otile, [&](int t) -> bf16_t* {
+      return n0 + t < g.N ? O.row<bf16_t>(b, h, n0 + t) : nullptr;
+    });
+  }
+}
+
+// LayerNorm backward of one map for the lane's token, ready for the matrix cores.  With
+// gg = dO * m_other * gamma (m_other = the other map's output) and means over the channels,
+//   du = rstd (gg - mean(gg) - u-hat mean(gg u-hat)).
+// Returns t = (gg - mean(gg) - u-hat mean(gg u-hat)) / |gg|_2 as packed fp16 B operands (k-slot =
+// channel) and the factor rstd |gg|_2 that dx must be multiplied with.  xd = dO (packed bf16),
+// us / uo = u-hat of this map / of the other one (packed fp16), all in token-row order.
+template <int D>
+__device__ __forceinline__ float norm_backward(const unsigned char* wm_self, const unsigned char* wm_other,
+                                               int gl, const u32x4 (&xd)[D / 16], const u32x4 (&us)[D / 16],
+                                               const u32x4 (&uo)[D / 16], float rstd, u32x4 (&dub)[D / 16]) {
+  using SM = VSmem<D>;
+  constexpr int NRB = D / 32;
+  const float* vs = reinterpret_cast<const float*>(wm_self + SM::kVec);
+  const float* vo = reinterpret_cast<const float*>(wm_other + SM::kVec);
+  // gg of the whole row is kept (fp32): it is needed again once its sums are known
+  f32x16 gg[NRB];
+  float sa = 0.0f, sb = 0.0f, sc = 0.0f;
+#pragma unroll
+  for (int ob = 0; ob < NRB; ++ob) {
+    const f32x16 gs = vec_block(vs + 2 * D, ob, gl);
+    const f32x16 go = vec_block(vo + 2 * D, ob, gl), bo = vec_block(vo + 3 * D, ob, gl);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const float mo = __builtin_fmaf(half_entry<D>(uo, ob, i), go[i], bo[i]);
+      gg[ob][i] = row_entry<D>(xd, ob, i) * mo * gs[i];
+      sa += gg[ob][i];
+      sb = __builtin_fmaf(gg[ob][i], half_entry<D>(us, ob, i), sb);
+      sc = __builtin_fmaf(gg[ob][i], gg[ob][i], sc);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  sa += partner32(sa);
+  sb += partner32(sb);
+  sc += partner32(sc);
+  const float nrm = sqrtf(sc);
+  const float inv = nrm > 0.0f ? 1.0f / nrm : 0.0f;
+  const float a = sa * (1.0f / D) * inv, bq = sb * (1.0f / D) * inv;
+#pragma unroll
+  for (int ob = 0; ob < NRB; ++ob)
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+      const float t0 = __builtin_fmaf(gg[ob][2 * p], inv, -a) - half_entry<D>(us, ob, 2 * p) * bq;
+      const float t1 = __builtin_fmaf(gg[ob][2 * p + 1], inv, -a) - half_entry<D>(us, ob, 2 * p + 1) * bq;
+      dub[2 * ob + p / 4][p % 4] = __builtin_bit_cast(uint32_t, to_f16x2(t0, t1));
+    }
+  return rstd * nrm;
+}
+
+// dx^T = W1 (GELU'(4y) * (W2 du^T)) for one map: dub = du as fp16 B operands, x = the map's input
+// rows (the first layer is computed again, block by block: keeping y of both maps across the
+// LayerNorm backward would not fit the registers of two waves per SIMD).
+template <int D>
+__device__ __forceinline__ void map_backward(const unsigned char* wm, const int (&a_off)[D / 16],
+                                             const int (&t_off)[2][D / 32], int gl,
+                                             const u32x4 (&x)[D / 16], const u32x4 (&dub)[D / 16],
+                                             f32x16 (&dx)[D / 32]) {
+  using SM = VSmem<D>;
+  constexpr int NRB = D / 32, NKS = D / 16;
+  auto tr_operand = [&](const unsigned char* mat, int blk, int ks) {
+    const u32x2 lo = lds_read_tr16(mat + ks * 16 * SM::kRowB + t_off[0][blk]);
+    const u32x2 hi = lds_read_tr16(mat + ks * 16 * SM::kRowB + t_off[1][blk]);
+    u32x4 a;
+    a[0] = lo[0];
+    a[1] = lo[1];
+    a[2] = hi[0];
+    a[3] = hi[1];
+    return a;
+  };
+#pragma unroll
+  for (int ib = 0; ib < NRB; ++ib)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) dx[ib][i] = 0.0f;
+#pragma unroll
+  for (int hb = 0; hb < NRB; ++hb) {
+    f32x16 dg;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) dg[i] = 0.0f;
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) dg = mfma32_f16(tr_operand(wm + SM::kW2, hb, ks), dub[ks], dg);
+    const f32x16 yb = first_layer_block<D>(wm, a_off, gl, x, hb);
+    f16x2 y[8], gp[8];
+#pragma unroll
+    for (int p = 0; p < 8; ++p) y[p] = to_f16x2(yb[2 * p], yb[2 * p + 1]);
+    gelu_grad_y16<8>(y, gp);
+    u32x4 dhb[2];
+#pragma unroll
+    for (int p = 0; p < 8; ++p)
+      dhb[p / 4][p % 4] = pack_bf16(static_cast<float>(gp[p][0]) * dg[2 * p], static_cast<float>(gp[p][1]) * dg[2 * p + 1]);
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+      for (int ib = 0; ib < NRB; ++ib) dx[ib] = mfma32(tr_operand(wm + SM::kW1, ib, 2 * hb + hf), dhb[hf], dx[ib]);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
+// grid: one workgroup per compute unit, block WAVES*64.
+//   dT  = dO + phi_v1'(T)^T (dO * phi_v2(V)),   dVm = phi_v2'(V)^T (dO * phi_v1(T));
+// both maps' forward values are recomputed.
+template <int D, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void k_vmod_bwd_mfma(Geom g, const unsigned char* __restrict__ wpk,
+                                                              float ln_eps, View Tin, View V, View dO,
+                                                              View dT, View dVm,
+                                                              unsigned char* stash) {
+  using SM = VSmem<D>;
+  constexpr int NRB = D / 32, NKS = D / 16;
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int lane = threadIdx.x % kWave, wave = wave_index();
+  const int r = lane % 32, gl = lane / 32;
+  const int L = lane % 16, q = lane / 16;
+  load_map<D, WAVES * 64>(smem, wpk);
+  load_map<D, WAVES * 64>(smem + SM::kMap, wpk + VPacked<D>::kBytes);
+  __syncthreads();
+  unsigned char* otile = smem + 2 * SM::kMap + wave * RowTile<D, kRowsOut>::kBytes;
+  int a_off[NKS];
+  first_layer_offsets<D>(lane, a_off);
+  // Transpose reads of a [k][m] matrix copy (row = contraction index, 16 per k-step: slot (gl, j)
+  // is row 8 gl + j) for the lane's A operand row: lanes 4j'..4j'+3 of a 16-lane group supply row
+  // j' of a 4 x 16 block, and lane L receives its column L, which is to be matrix column
+  // 32 blk + 16 (q % 2) + swap23(L): the lane that supplies block columns 4c..4c+3 therefore
+  // addresses the matrix columns of group c with its two bits exchanged.
+  int t_off[2][NRB];
+#pragma unroll
+  for (int hi = 0; hi < 2; ++hi)
+#pragma unroll
+    for (int blk = 0; blk < NRB; ++blk) {
+      const int c = L % 4, cs = ((c & 1) << 1) | (c >> 1);
+      const int row = 8 * gl + 4 * hi + L / 4;
+      const int col = 32 * blk + 16 * (q % 2) + 4 * cs;
+      t_off[hi][blk] = tile_off<SM::kRowB>(row, col >> 3) + ((col & 7) << 1);
+    }
+  TileWalk tw;
+  tw.tiles_per_row = (g.N + 31) / 32;
+  tw.total = tw.tiles_per_row * g.B * g.H;
+  tw.H = g.H;
+  const int stride = gridDim.x * WAVES;
+  // this wave's stash slot: [map][piece][lane] 16 bytes.  The read pointer is the same address
+  // behind an empty asm statement, so that the compiler treats the reads as real loads instead of
+  // keeping the stored registers alive.
+  unsigned char* slot_wr = stash + static_cast<size_t>(blockIdx.x * WAVES + wave) * (2 * NKS * 1024) + lane * 16;
+  const unsigned char* slot_rd = slot_wr;
+  asm volatile("" : "+v"(slot_rd));
+  auto put_stash = [&](int m, const f32x16 (&u)[NRB]) {
+#pragma unroll
+    for (int ob = 0; ob < NRB; ++ob)
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf) {
+        u32x4 v;
+#pragma unroll
+        for (int p = 0; p < 4; ++p)
+          v[p] = __builtin_bit_cast(uint32_t, to_f16x2(u[ob][8 * hf + 2 * p], u[ob][8 * hf + 2 * p + 1]));
+        *reinterpret_cast<u32x4*>(slot_wr + (m * NKS + 2 * ob + hf) * 1024) = v;
+      }
+  };
+  auto get_stash = [&](int m, u32x4 (&v)[NKS]) {
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) v[ks] = *reinterpret_cast<const u32x4*>(slot_rd + (m * NKS + ks) * 1024);
+  };
+  for (int tile = blockIdx.x * WAVES + wave; tile < tw.total; tile += stride) {
+    int b, h, n0;
+    tw.decode(tile, b, h, n0);
+    // Phase 1: both maps forward; their normalised outputs u-hat go, packed in fp16, to this
+    // wave's slot of the stash in global memory (lane-private 16-byte pieces, so a lane only ever
+    // reads back what it wrote itself) -- the registers of two waves per SIMD cannot hold them
+    // next to the accumulators of the products that follow.
+    float rstd1, rstd2;
+    {
+      u32x4 x[NKS];
+      f32x16 u[NRB];
+      load_row<D>(Tin, b, h, n0 + r, g.N, gl, x);
+      map_forward<D>(smem, a_off, gl, x, ln_eps, u, rstd1);
+      put_stash(0, u);
+      __builtin_amdgcn_sched_barrier(0);
+      load_row<D>(V, b, h, n0 + r, g.N, gl, x);
+      map_forward<D>(smem + SM::kMap, a_off, gl, x, ln_eps, u, rstd2);
+      put_stash(1, u);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    auto row_of = [&](const View& X) {
+      return [&X, b, h, n0, &g](int t) -> bf16_t* { return n0 + t < g.N ? X.row<bf16_t>(b, h, n0 + t) : nullptr; };
+    };
+    // Phase 2, per map: LayerNorm backward, then back through the two layers
+    {
+      u32x4 xd[NKS], du[NKS];
+      float s1;
+      {
+        u32x4 us[NKS], uo[NKS];
+        load_row<D>(dO, b, h, n0 + r, g.N, gl, xd);
+        get_stash(0, us);
+        get_stash(1, uo);
+        s1 = norm_backward<D>(smem, smem + SM::kMap, gl, xd, us, uo, rstd1, du);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      u32x4 x[NKS];  // read again: the rows are still in the caches
+      load_row<D>(Tin, b, h, n0 + r, g.N, gl, x);
+      f32x16 dx[NRB];
+      map_backward<D>(smem, a_off, t_off, gl, x, du, dx);
+      u32x4 w[NRB][2];
+#pragma unroll
+      for (int ib = 0; ib < NRB; ++ib) {
+        f32x16 o;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[i] = __builtin_fmaf(dx[ib][i], s1, row_entry<D>(xd, ib, i));
+        pack_block(o, w[ib]);
+      }
+      store_tile<D>(w, lane, otile, row_of(dT));
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    {
+      u32x4 du[NKS];
+      float s2;
+      {
+        u32x4 xd[NKS], us[NKS], uo[NKS];
+        load_row<D>(dO, b, h, n0 + r, g.N, gl, xd);
+        get_stash(1, us);
+        get_stash(0, uo);
+        s2 = norm_backward<D>(smem + SM::kMap, smem, gl, xd, us, uo, rstd2, du);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      u32x4 x[NKS];
+      load_row<D>(V, b, h, n0 + r, g.N, gl, x);
+      f32x16 dx[NRB];
+      map_backward<D>(smem + SM::kMap, a_off, t_off, gl, x, du, dx);
+      u32x4 w[NRB][2];
+#pragma unroll
+      for (int ib = 0; ib < NRB; ++ib) {
+        f32x16 o;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[i] = dx[ib][i] * s2;
+        pack_block(o, w[ib]);
+      }
+      store_tile<D>(w, lane, otile, row_of(dVm));
+    }
+  }
+}
+
+// dst += src over [B, H, N, D] bf16 rows, 16 bytes per thread (the modulation's share of dV joins
+// the operator's)
+template <int D>
+__global__ void k_add_rows16(Geom g, View dst, View src) {
+  constexpr int PIECES = D / 8;
+  const int64_t idx = blockIdx.x * static_cast<int64_t>(blockDim.x) + threadIdx.x;
+  const int64_t rows = static_cast<int64_t>(g.B) * g.H * g.N;
+  const int64_t rowi = idx / PIECES;
+  if (rowi >= rows) return;
+  const int piece = static_cast<int>(idx % PIECES);
+  const int n = static_cast<int>(rowi % g.N);
+  const int64_t bh = rowi / g.N;
+  const int h = static_cast<int>(bh % g.H), b = static_cast<int>(bh / g.H);
+  u32x4* p = reinterpret_cast<u32x4*>(dst.row<bf16_t>(b, h, n) + 8 * piece);
+  const u32x4 s = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src.row<const bf16_t>(b, h, n) + 8 * piece));
+  u32x4 v = *p;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) v[k] = pack_bf16(bf16_lo(v[k]) + bf16_lo(s[k]), bf16_hi(v[k]) + bf16_hi(s[k]));
+  *p = v;
+}
+
+template <int D>
+hla_status prepare_t() {
+  HLA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_vmod_fwd_mfma<D, kWavesV>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, VSmem<D>::total(kWavesV)));
+  HLA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_vmod_bwd_mfma<D, kWavesV>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, VSmem<D>::total(kWavesV)));
+  return HLA_OK;
+}
+
+int compute_units() {
+  int dev = 0, n = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 256;
+  if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return 256;
+  return n;
+}
+
+template <int D>
+hla_status forward_t(hla_handle* hd, const hla_call_args& a) {
+  const Geom& g = hd->g;
+  const int64_t tiles = static_cast<int64_t>((g.N + 31) / 32) * g.B * g.H;
+  const int grid = static_cast<int>(std::min<int64_t>(compute_units(), (tiles + kWavesV - 1) / kWavesV));
+  return launch(hd, "vmod_forward", k_vmod_fwd_mfma<D, kWavesV>, dim3(grid), dim3(kWavesV * 64),
+                VSmem<D>::total(kWavesV), a.stream, g, static_cast<const unsigned char*>(hd->vmod_wpk),
+                hd->vmod_ln_eps, vmod_view(hd->vmod_T, g), a.V, a.O);
+}
+
+template <int D>
+hla_status backward_t(hla_handle* hd, const hla_call_args& a) {
+  const Geom& g = hd->g;
+  const int64_t tiles = static_cast<int64_t>((g.N + 31) / 32) * g.B * g.H;
+  const int grid = static_cast<int>(std::min<int64_t>(compute_units(), (tiles + kWavesV - 1) / kWavesV));
+  return launch(hd, "vmod_backward", k_vmod_bwd_mfma<D, kWavesV>, dim3(grid), dim3(kWavesV * 64),
+                VSmem<D>::total(kWavesV), a.stream, g, static_cast<const unsigned char*>(hd->vmod_wpk),
+                hd->vmod_ln_eps, vmod_view(hd->vmod_T, g), a.V, a.dO, vmod_view(hd->vmod_dT, g),
+                vmod_view(hd->vmod_dV, g), hd->vmod_wpk + vmod_mfma_packed_bytes(hd));
+}
+
+template <int D>
+hla_status add_t(hla_handle* hd, const hla_call_args& a) {
+  const Geom& g = hd->g;
+  const int64_t total = static_cast<int64_t>(g.B) * g.H * g.N * (D / 8);
+  return launch(hd, "vmod_add_dv", k_add_rows16<D>, dim3(static_cast<unsigned>((total + 255) / 256)), dim3(256),
+                0, a.stream, g, a.dV, vmod_view(hd->vmod_dV, g));
+}
+
+}  // namespace
+
+bool vmod_mfma_supported(const hla_handle* hd) {
+  return hd->path == HLA_PATH_MFMA && hd->cfg.io_dtype == HLA_BF16 && (hd->g.d == 64 || hd->g.d == 128);
+}
+size_t vmod_mfma_packed_bytes(const hla_handle* hd) {
+  return 2 * static_cast<size_t>(hd->g.d == 64 ? VPacked<64>::kBytes : VPacked<128>::kBytes);
+}
+// packed weights, then the backward kernel's stash: one slot per wave of the largest grid
+size_t vmod_mfma_workspace_bytes(const hla_handle* hd) {
+  return vmod_mfma_packed_bytes(hd) + static_cast<size_t>(compute_units()) * kWavesV * 2 * (hd->g.d / 16) * 1024;
+}
+hla_status vmod_mfma_prepare_kernels(const hla_handle* hd) {
+  return hd->g.d == 64 ? prepare_t<64>() : prepare_t<128>();
+}
+hla_status vmod_mfma_set_weights(hla_handle* hd, const hla_vmod_weights* maps, hipStream_t s) {
+  const int d = hd->g.d;
+  const size_t per = vmod_mfma_packed_bytes(hd) / 2;
+  for (int m = 0; m < 2; ++m)
+    HLA_TRY(launch(hd, "vmod_pack", k_vmod_pack_mfma<bf16_t>, dim3(64), dim3(256), 0, s,
+                   static_cast<const bf16_t*>(maps[m].W1), static_cast<const bf16_t*>(maps[m].b1),
+                   static_cast<const bf16_t*>(maps[m].W2), static_cast<const bf16_t*>(maps[m].b2),
+                   static_cast<const bf16_t*>(maps[m].gamma), static_cast<const bf16_t*>(maps[m].beta), d,
+                   hd->vmod_wpk + m * per));
+  return HLA_OK;
+}
+hla_status vmod_mfma_forward(hla_handle* hd, const hla_call_args& a) {
+  return hd->g.d == 64 ? forward_t<64>(hd, a) : forward_t<128>(hd, a);
+}
+hla_status vmod_mfma_backward(hla_handle* hd, const hla_call_args& a) {
+  return hd->g.d == 64 ? backward_t<64>(hd, a) : backward_t<128>(hd, a);
+}
+hla_status vmod_mfma_add_value_grads(hla_handle* hd, const hla_call_args& a) {
+  return hd->g.d == 64 ? add_t<64>(hd, a) : add_t<128>(hd, a);
+}
+
+}  // namespace hla

@@ -1,6 +1,7 @@
 // Value modulation (paper Sec. 4.5):  O = T + phi_v1(T) * phi_v2(V), elementwise, with T the
 // normalised attention output and phi_v (App. A.1) = Linear d->d, GELU, Linear d->d, LayerNorm.
-// Forward and the backward to (dT, dV), as fp32 vector-ALU kernels for any I/O dtype and head dim.
+// Forward and the backward to (dT, dV), as fp32 vector-ALU kernels for any I/O dtype and head dim
+// (handles on the matrix-core path with bf16 I/O are served by hla_mfma_vmod.hip instead).
 // One workgroup of d threads serves a tile of tokens of one (batch row, head); thread j owns
 // hidden unit j of the first layer and channel j of everything after it.  The weights are read
 // through the caches ([in][out] order for the forward products, transposed copies for the
@@ -308,15 +309,19 @@ hla_status add_t(hla_handle* hd, const hla_call_args& a) {
 }  // namespace
 
 hla_status vmod_set_weights(hla_handle* hd, const hla_vmod_weights* maps, hipStream_t s) {
+  if (hd->vmod_wpk != nullptr) HLA_TRY(vmod_mfma_set_weights(hd, maps, s));
   return hd->cfg.io_dtype == HLA_F32 ? set_weights_t<float>(hd, maps, s) : set_weights_t<bf16_t>(hd, maps, s);
 }
 hla_status vmod_forward(hla_handle* hd, const hla_call_args& a) {
+  if (hd->vmod_wpk != nullptr) return vmod_mfma_forward(hd, a);
   return hd->cfg.io_dtype == HLA_F32 ? forward_t<float>(hd, a) : forward_t<bf16_t>(hd, a);
 }
 hla_status vmod_backward(hla_handle* hd, const hla_call_args& a) {
+  if (hd->vmod_wpk != nullptr) return vmod_mfma_backward(hd, a);
   return hd->cfg.io_dtype == HLA_F32 ? backward_t<float>(hd, a) : backward_t<bf16_t>(hd, a);
 }
 hla_status vmod_add_value_grads(hla_handle* hd, const hla_call_args& a) {
+  if (hd->vmod_wpk != nullptr) return vmod_mfma_add_value_grads(hd, a);
   return hd->cfg.io_dtype == HLA_F32 ? add_t<float>(hd, a) : add_t<bf16_t>(hd, a);
 }
 View vmod_view(void* p, const Geom& g) { return ws_view(p, g); }

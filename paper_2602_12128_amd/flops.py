@@ -109,10 +109,10 @@ def kernel_model(name: str, d: int, d_phi: int, F: int, e: int = 2):
         "mfma_bwd_query": (d * e + qf + 4 + qf, 4 * D * d, "hbm"),   # dO, features, den in; feature grads out
         "mfma_bwd_key": (d * e + kf + d * e + kf, 4 * D * d, "hbm"),
         "mfma_phi_backward": (4 * d * e + 2 * (qf + kf), (1 + F) * lin_b, "mfma"),
-        # value modulation (Sec. 4.5), fp32 vector ALU: two maps of two d x d layers; the backward
-        # recomputes them and goes back through both
-        "vmod_forward": (3 * d * e, 8 * d * d, "alu"),
-        "vmod_backward": (5 * d * e, 16 * d * d, "alu"),
+        # value modulation (Sec. 4.5): two maps of two d x d layers; the backward recomputes them
+        # and goes back through both (on the matrix cores for bf16 I/O, else fp32 vector ALU)
+        "vmod_forward": (3 * d * e, 8 * d * d, "mfma" if e == 2 else "alu"),
+        "vmod_backward": (5 * d * e, 16 * d * d, "mfma" if e == 2 else "alu"),
         "generic_phi_forward": (2 * d * e + qf + kf, phi_forward_flops(d, d_phi, F), "alu"),
         "generic_phi_backward": (2 * d * e + 2 * (qf + kf) + 2 * d * e, phi_backward_flops(d, d_phi, F), "alu"),
     }
