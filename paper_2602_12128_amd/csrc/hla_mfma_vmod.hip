@@ -29,8 +29,13 @@ namespace {
 
 using namespace mf;
 
-constexpr int kWavesV = 8;    // waves per workgroup (one workgroup per compute unit: LDS)
-constexpr int kRowsOut = 8;   // token rows of a wave's output tile in LDS (a tile leaves in 32/8 passes)
+// One workgroup per compute unit (both maps' weights fill most of its LDS) of four waves, one
+// per SIMD: a wave then has all 512 registers, which is what lets it keep a whole tile's
+// intermediate values and the next tile's inputs at once.  With two waves per SIMD (256 registers
+// each) the same work needed a round trip through memory for the normalised outputs and ran with
+// three quarters of its time in memory waits.
+constexpr int kWavesV = 4;
+constexpr int kRowsOut = 16;  // token rows of a wave's output tile in LDS (a tile leaves in 32/16 passes)
 
 // packed weights of one map in global memory
 template <int D>
@@ -141,6 +146,13 @@ __device__ __forceinline__ float half_entry(const u32x4 (&x)[D / 16], int rb, in
   return static_cast<float>(p[i % 2]);
 }
 
+// 16-byte load through a pointer known to be global memory (after a pointer has been passed
+// through an asm statement the compiler no longer knows, and would use the slower generic form)
+__device__ __forceinline__ u32x4 load_global16(const void* p) {
+  typedef const u32x4 __attribute__((address_space(1))) * gptr;
+  return *(gptr)(p);
+}
+
 struct TileWalk {
   int tiles_per_row, total, H;
   __device__ __forceinline__ void decode(int t, int& b, int& h, int& n0) const {
@@ -151,48 +163,107 @@ struct TileWalk {
   }
 };
 
-// First layer of one map for hidden block rb: y = h/4 of the 16 hidden units the lane holds
+// First layer of one map for hidden block rb: y = h/4 of the 16 hidden units the lane holds.
+// All LDS operands are read before the first MFMA is issued (one exposed LDS round trip per
+// block instead of one per MFMA).
 template <int D>
 __device__ __forceinline__ f32x16 first_layer_block(const unsigned char* wm, const int (&a_off)[D / 16], int gl,
                                                     const u32x4 (&x)[D / 16], int rb) {
   using SM = VSmem<D>;
-  f32x16 hb = vec_block(reinterpret_cast<const float*>(wm + SM::kVec), rb, gl);
+  constexpr int NKS = D / 16;
+  u32x4 a[NKS];
 #pragma unroll
-  for (int ks = 0; ks < D / 16; ++ks)
-    hb = mfma32(*reinterpret_cast<const u32x4*>(wm + SM::kW1 + rb * 32 * SM::kRowB + a_off[ks]), x[ks], hb);
+  for (int ks = 0; ks < NKS; ++ks)
+    a[ks] = *reinterpret_cast<const u32x4*>(wm + SM::kW1 + rb * 32 * SM::kRowB + a_off[ks]);
+  f32x16 hb = vec_block(reinterpret_cast<const float*>(wm + SM::kVec), rb, gl);
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int ks = 0; ks < NKS; ++ks) hb = mfma32(a[ks], x[ks], hb);
   return hb;
 }
 
 // One map applied to the token rows in x: on return u holds u-hat (the LayerNorm's normalised
-// value, before gamma and beta) in accumulator order and rstd the token's 1/std.
-template <int D>
+// value, before gamma and beta) in accumulator order, rstd the token's 1/std and, if KEEP, yk the
+// first layer's y = h/4 as packed fp16 pairs (pair p of block rb = registers 2p, 2p+1).
+// The two layers run as a software pipeline over the 32-row blocks of the hidden layer: in stage
+// s the vector ALU evaluates GELU on block s while the matrix cores compute the first layer of
+// block s + 1 and the second layer's share of block s - 1.  A wave issues in order and has its
+// SIMD to itself, so the overlap needs the two kinds of instructions to alternate in program
+// order: a stage is cut into four slices (scheduling barriers in between) of four MFMAs, the LDS
+// reads of the next slice's operands and a quarter of the block's GELU.
+template <int D, bool KEEP>
 __device__ __forceinline__ void map_forward(const unsigned char* wm, const int (&a_off)[D / 16], int gl,
                                             const u32x4 (&x)[D / 16], float ln_eps,
-                                            f32x16 (&u)[D / 32], float& rstd) {
+                                            f32x16 (&u)[D / 32], f16x2 (&yk)[KEEP ? D / 32 : 1][8],
+                                            float& rstd) {
   using SM = VSmem<D>;
-  constexpr int NRB = D / 32;
+  constexpr int NRB = D / 32, NKS = D / 16;
+  constexpr int P1 = NKS / 4;       // first-layer MFMAs per slice
+  constexpr int P2 = 2 * NRB / 4;   // second-layer MFMAs per slice
+  static_assert(NKS % 4 == 0 && (2 * NRB) % 4 == 0, "four slices per stage");
   const float* vec = reinterpret_cast<const float*>(wm + SM::kVec);
 #pragma unroll
   for (int ob = 0; ob < NRB; ++ob) u[ob] = vec_block(vec + D, ob, gl);
+  // operand of first-layer MFMA i of slice (s, j): block s + 1, k-step P1 j + i
+  auto a1 = [&](int s, int j, int i) {
+    return *reinterpret_cast<const u32x4*>(wm + SM::kW1 + (s + 1) * 32 * SM::kRowB + a_off[P1 * j + i]);
+  };
+  // second-layer MFMA i of slice (s, j) is number n = P2 j + i of block s - 1's 2 NRB products:
+  // k-step half n / NRB, output block n % NRB
+  auto a2 = [&](int s, int j, int i) {
+    const int n = P2 * j + i;
+    return *reinterpret_cast<const u32x4*>(wm + SM::kW2 + (n % NRB) * 32 * SM::kRowB + a_off[2 * (s - 1) + n / NRB]);
+  };
+  f32x16 hb[2];
+  hb[0] = first_layer_block<D>(wm, a_off, gl, x, 0);
+  u32x4 gprev[2], gcur[2], an1[P1], an2[P2];
 #pragma unroll
-  for (int rb = 0; rb < NRB; ++rb) {
-    const f32x16 hb = first_layer_block<D>(wm, a_off, gl, x, rb);
-    f16x2 y[8];
+  for (int i = 0; i < P1; ++i) an1[i] = a1(0, 0, i);
 #pragma unroll
-    for (int p = 0; p < 8; ++p) y[p] = to_f16x2(hb[2 * p], hb[2 * p + 1]);
-    uint32_t gp[8];
-    gelu_y16<8>(y, gp);
-    u32x4 gb[2];
+  for (int s = 0; s <= NRB; ++s) {
+    if (s + 1 < NRB) hb[(s + 1) % 2] = vec_block(vec, s + 1, gl);
 #pragma unroll
-    for (int p = 0; p < 8; ++p) gb[p / 4][p % 4] = gp[p];
+    for (int j = 0; j < 4; ++j) {
+      __builtin_amdgcn_sched_barrier(0);
+      if (s + 1 < NRB) {
 #pragma unroll
-    for (int hf = 0; hf < 2; ++hf)
+        for (int i = 0; i < P1; ++i) hb[(s + 1) % 2] = mfma32(an1[i], x[P1 * j + i], hb[(s + 1) % 2]);
+      }
+      if (s >= 1) {
 #pragma unroll
-      for (int ob = 0; ob < NRB; ++ob)
-        u[ob] = mfma32_f16(*reinterpret_cast<const u32x4*>(wm + SM::kW2 + ob * 32 * SM::kRowB + a_off[2 * rb + hf]),
-                           gb[hf], u[ob]);
-    __builtin_amdgcn_sched_barrier(0);  // keeps the operand reads of later blocks from piling up in registers
+        for (int i = 0; i < P2; ++i) {
+          const int n = P2 * j + i;
+          u[n % NRB] = mfma32_f16(an2[i], gprev[n / NRB], u[n % NRB]);
+        }
+      }
+      // operands of the next slice
+      const int sn = j < 3 ? s : s + 1, jn = j < 3 ? j + 1 : 0;
+      if (sn + 1 < NRB) {
+#pragma unroll
+        for (int i = 0; i < P1; ++i) an1[i] = a1(sn, jn, i);
+      }
+      if (sn >= 1 && sn <= NRB) {
+#pragma unroll
+        for (int i = 0; i < P2; ++i) an2[i] = a2(sn, jn, i);
+      }
+      if (s < NRB) {  // GELU of entries 4j .. 4j+3 of block s -> two dwords of the B operand
+        f16x2 y[2];
+        y[0] = to_f16x2(hb[s % 2][4 * j], hb[s % 2][4 * j + 1]);
+        y[1] = to_f16x2(hb[s % 2][4 * j + 2], hb[s % 2][4 * j + 3]);
+        if (KEEP) {
+          yk[s][2 * j] = y[0];
+          yk[s][2 * j + 1] = y[1];
+        }
+        uint32_t gp[2];
+        gelu_y16<2>(y, gp);
+        gcur[j / 2][2 * (j % 2)] = gp[0];
+        gcur[j / 2][2 * (j % 2) + 1] = gp[1];
+      }
+    }
+    gprev[0] = gcur[0];
+    gprev[1] = gcur[1];
   }
+  __builtin_amdgcn_sched_barrier(0);
   // LayerNorm statistics of the token: this lane's D/2 channels and the partner lane's
   float s = 0.0f;
 #pragma unroll
@@ -262,43 +333,65 @@ __global__ __launch_bounds__(WAVES * 64) void k_vmod_fwd_mfma(Geom g, const unsi
   tw.total = tw.tiles_per_row * g.B * g.H;
   tw.H = g.H;
   const int stride = gridDim.x * WAVES;
-  for (int tile = blockIdx.x * WAVES + wave; tile < tw.total; tile += stride) {
-    int b, h, n0;
+  // The value map runs first: its input rows were requested during the previous tile, the rows
+  // of T are requested at the top of the tile and needed only after it, and the next tile's V
+  // rows are requested once the value map is done with the registers -- no wait of the tile
+  // loop sits right behind its load, and the tile's stores have a whole map to complete before
+  // the next wait on the memory counter.
+  int tile = blockIdx.x * WAVES + wave;
+  int b = 0, h = 0, n0 = 0;
+  u32x4 xv[NKS];
+  if (tile < tw.total) {
     tw.decode(tile, b, h, n0);
+    load_row<D>(V, b, h, n0 + r, g.N, gl, xv);
+  }
+  for (; tile < tw.total; tile += stride) {
     u32x4 xt[NKS];
     load_row<D>(Tin, b, h, n0 + r, g.N, gl, xt);
-    f32x16 m1[NRB], m2[NRB];
-    float rstd;
-    map_forward<D>(smem, a_off, gl, xt, ln_eps, m1, rstd);
+    const int ob_ = b, oh_ = h, on0 = n0;
+    f16x2 none[1][8];
+    u32x4 m2p[NKS];  // phi_v2(V), packed bf16 in token-row order
     {
-      const float* vec = reinterpret_cast<const float*>(smem + SM::kVec);
-#pragma unroll
-      for (int ob = 0; ob < NRB; ++ob) {
-        const f32x16 ga = vec_block(vec + 2 * D, ob, gl), be = vec_block(vec + 3 * D, ob, gl);
-#pragma unroll
-        for (int i = 0; i < 16; ++i) m1[ob][i] = __builtin_fmaf(m1[ob][i], ga[i], be[i]);
-      }
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    load_row<D>(V, b, h, n0 + r, g.N, gl, xt);
-    map_forward<D>(smem + SM::kMap, a_off, gl, xt, ln_eps, m2, rstd);
-    __builtin_amdgcn_sched_barrier(0);
-    load_row<D>(Tin, b, h, n0 + r, g.N, gl, xt);  // T again, for the sum (still in the caches)
-    u32x4 w[NRB][2];
-    {
+      f32x16 m2[NRB];
+      float rstd;
+      map_forward<D, false>(smem + SM::kMap, a_off, gl, xv, ln_eps, m2, none, rstd);
       const float* vec = reinterpret_cast<const float*>(smem + SM::kMap + SM::kVec);
 #pragma unroll
       for (int ob = 0; ob < NRB; ++ob) {
         const f32x16 ga = vec_block(vec + 2 * D, ob, gl), be = vec_block(vec + 3 * D, ob, gl);
         f32x16 o;
 #pragma unroll
+        for (int i = 0; i < 16; ++i) o[i] = __builtin_fmaf(m2[ob][i], ga[i], be[i]);
+        u32x4 pk[2];
+        pack_block(o, pk);
+        m2p[2 * ob] = pk[0];
+        m2p[2 * ob + 1] = pk[1];
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    if (tile + stride < tw.total) {
+      tw.decode(tile + stride, b, h, n0);
+      load_row<D>(V, b, h, n0 + r, g.N, gl, xv);
+    }
+    f32x16 m1[NRB];
+    float rstd;
+    map_forward<D, false>(smem, a_off, gl, xt, ln_eps, m1, none, rstd);
+    __builtin_amdgcn_sched_barrier(0);
+    u32x4 w[NRB][2];
+    {
+      const float* vec = reinterpret_cast<const float*>(smem + SM::kVec);
+#pragma unroll
+      for (int ob = 0; ob < NRB; ++ob) {
+        const f32x16 ga = vec_block(vec + 2 * D, ob, gl), be = vec_block(vec + 3 * D, ob, gl);
+        f32x16 o;
+#pragma unroll
         for (int i = 0; i < 16; ++i)
-          o[i] = __builtin_fmaf(m1[ob][i], __builtin_fmaf(m2[ob][i], ga[i], be[i]), row_entry<D>(xt, ob, i));
+          o[i] = __builtin_fmaf(__builtin_fmaf(m1[ob][i], ga[i], be[i]), row_entry<D>(m2p, ob, i), row_entry<D>(xt, ob, i));
         pack_block(o, w[ob]);
       }
     }
     store_tile<D>(w, lane, otile, [&](int t) -> bf16_t* {
-      return n0 + t < g.N ? O.row<bf16_t>(b, h, n0 + t) : nullptr;
+      return on0 + t < g.N ? O.row<bf16_t>(ob_, oh_, on0 + t) : nullptr;
     });
   }
 }
@@ -307,32 +400,51 @@ __global__ __launch_bounds__(WAVES * 64) void k_vmod_fwd_mfma(Geom g, const unsi
 // gg = dO * m_other * gamma (m_other = the other map's output) and means over the channels,
 //   du = rstd (gg - mean(gg) - u-hat mean(gg u-hat)).
 // Returns t = (gg - mean(gg) - u-hat mean(gg u-hat)) / |gg|_2 as packed fp16 B operands (k-slot =
-// channel) and the factor rstd |gg|_2 that dx must be multiplied with.  xd = dO (packed bf16),
-// us / uo = u-hat of this map / of the other one (packed fp16), all in token-row order.
-template <int D>
+// channel) and the factor rstd |gg|_2 that dx must be multiplied with: scaled to unit Euclidean
+// norm per token, the operand's range does not depend on the size of dO or of 1/std.
+// The row is streamed twice, 16-byte piece by piece (first for the three sums, then for the
+// result), through `load(which, ks, pass)`: piece ks of dO (which = 0, packed bf16), of this map's
+// u-hat (1) and of the other map's (2, both packed fp16).  Only the result stays in registers; the
+// second pass must really load again (its loader is handed pass = 1 so that it can use an address
+// the compiler cannot match with the first pass's).
+template <int D, class Load>
 __device__ __forceinline__ float norm_backward(const unsigned char* wm_self, const unsigned char* wm_other,
-                                               int gl, const u32x4 (&xd)[D / 16], const u32x4 (&us)[D / 16],
-                                               const u32x4 (&uo)[D / 16], float rstd, u32x4 (&dub)[D / 16]) {
+                                               int gl, Load&& load, float rstd, u32x4 (&dub)[D / 16]) {
   using SM = VSmem<D>;
-  constexpr int NRB = D / 32;
-  const float* vs = reinterpret_cast<const float*>(wm_self + SM::kVec);
-  const float* vo = reinterpret_cast<const float*>(wm_other + SM::kVec);
-  // gg of the whole row is kept (fp32): it is needed again once its sums are known
-  f32x16 gg[NRB];
-  float sa = 0.0f, sb = 0.0f, sc = 0.0f;
+  constexpr int NKS = D / 16;
+  auto piece = [&](int ks, int pass, int opaque, float (&gg)[8], float (&uh)[8]) {
+    const u32x4 d = load(0, ks, pass), s = load(1, ks, pass), o = load(2, ks, pass);
+    const float* vs = reinterpret_cast<const float*>(wm_self + SM::kVec) + opaque + 16 * ks + 8 * gl;
+    const float* vo = reinterpret_cast<const float*>(wm_other + SM::kVec) + opaque + 16 * ks + 8 * gl;
 #pragma unroll
-  for (int ob = 0; ob < NRB; ++ob) {
-    const f32x16 gs = vec_block(vs + 2 * D, ob, gl);
-    const f32x16 go = vec_block(vo + 2 * D, ob, gl), bo = vec_block(vo + 3 * D, ob, gl);
+    for (int q = 0; q < 2; ++q) {
+      const f32x4 gs = *reinterpret_cast<const f32x4*>(vs + 2 * D + 4 * q);
+      const f32x4 go = *reinterpret_cast<const f32x4*>(vo + 2 * D + 4 * q);
+      const f32x4 bo = *reinterpret_cast<const f32x4*>(vo + 3 * D + 4 * q);
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const float mo = __builtin_fmaf(half_entry<D>(uo, ob, i), go[i], bo[i]);
-      gg[ob][i] = row_entry<D>(xd, ob, i) * mo * gs[i];
-      sa += gg[ob][i];
-      sb = __builtin_fmaf(gg[ob][i], half_entry<D>(us, ob, i), sb);
-      sc = __builtin_fmaf(gg[ob][i], gg[ob][i], sc);
+      for (int e = 0; e < 4; ++e) {
+        const int j = 4 * q + e;
+        const uint32_t dw = d[j / 2], sw = s[j / 2], ow = o[j / 2];
+        const f16x2 sp = __builtin_bit_cast(f16x2, sw), op = __builtin_bit_cast(f16x2, ow);
+        const float mo = __builtin_fmaf(static_cast<float>(op[j % 2]), go[e], bo[e]);
+        gg[j] = (j % 2 ? bf16_hi(dw) : bf16_lo(dw)) * mo * gs[e];
+        uh[j] = static_cast<float>(sp[j % 2]);
+      }
     }
-    __builtin_amdgcn_sched_barrier(0);
+  };
+  float sa = 0.0f, sb = 0.0f, sc = 0.0f;
+  int z1 = 0, z2 = 0;  // zeros the compiler cannot see through: the LDS vectors are read again, too
+  asm volatile("" : "+s"(z1));
+#pragma unroll
+  for (int ks = 0; ks < NKS; ++ks) {
+    float gg[8], uh[8];
+    piece(ks, 0, z1, gg, uh);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      sa += gg[j];
+      sb = __builtin_fmaf(gg[j], uh[j], sb);
+      sc = __builtin_fmaf(gg[j], gg[j], sc);
+    }
   }
   sa += partner32(sa);
   sb += partner32(sb);
@@ -340,20 +452,27 @@ __device__ __forceinline__ float norm_backward(const unsigned char* wm_self, con
   const float nrm = sqrtf(sc);
   const float inv = nrm > 0.0f ? 1.0f / nrm : 0.0f;
   const float a = sa * (1.0f / D) * inv, bq = sb * (1.0f / D) * inv;
+  asm volatile("" : "+s"(z2));
+  __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-  for (int ob = 0; ob < NRB; ++ob)
+  for (int ks = 0; ks < NKS; ++ks) {
+    float gg[8], uh[8];
+    piece(ks, 1, z2, gg, uh);
 #pragma unroll
-    for (int p = 0; p < 8; ++p) {
-      const float t0 = __builtin_fmaf(gg[ob][2 * p], inv, -a) - half_entry<D>(us, ob, 2 * p) * bq;
-      const float t1 = __builtin_fmaf(gg[ob][2 * p + 1], inv, -a) - half_entry<D>(us, ob, 2 * p + 1) * bq;
-      dub[2 * ob + p / 4][p % 4] = __builtin_bit_cast(uint32_t, to_f16x2(t0, t1));
+    for (int p = 0; p < 4; ++p) {
+      const float t0 = __builtin_fmaf(gg[2 * p], inv, -a) - uh[2 * p] * bq;
+      const float t1 = __builtin_fmaf(gg[2 * p + 1], inv, -a) - uh[2 * p + 1] * bq;
+      dub[ks][p] = __builtin_bit_cast(uint32_t, to_f16x2(t0, t1));
     }
+  }
   return rstd * nrm;
 }
 
 // dx^T = W1 (GELU'(4y) * (W2 du^T)) for one map: dub = du as fp16 B operands, x = the map's input
-// rows (the first layer is computed again, block by block: keeping y of both maps across the
-// LayerNorm backward would not fit the registers of two waves per SIMD).
+// rows (the first layer is computed again, block by block).
+// Per 32-row block of the hidden layer: y and dg (NKS MFMAs each, the operands of dg by transpose
+// reads, all requested up front), GELU' and the product on the vector ALU, then the block's share
+// of dx.
 template <int D>
 __device__ __forceinline__ void map_backward(const unsigned char* wm, const int (&a_off)[D / 16],
                                              const int (&t_off)[2][D / 32], int gl,
@@ -375,28 +494,44 @@ __device__ __forceinline__ void map_backward(const unsigned char* wm, const int 
   for (int ib = 0; ib < NRB; ++ib)
 #pragma unroll
     for (int i = 0; i < 16; ++i) dx[ib][i] = 0.0f;
+  u32x4 ag[NKS];
+#pragma unroll
+  for (int ks = 0; ks < NKS; ++ks) ag[ks] = tr_operand(wm + SM::kW2, 0, ks);
 #pragma unroll
   for (int hb = 0; hb < NRB; ++hb) {
+    __builtin_amdgcn_sched_barrier(0);
+    const f32x16 yb = first_layer_block<D>(wm, a_off, gl, x, hb);
     f32x16 dg;
 #pragma unroll
     for (int i = 0; i < 16; ++i) dg[i] = 0.0f;
 #pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) dg = mfma32_f16(tr_operand(wm + SM::kW2, hb, ks), dub[ks], dg);
-    const f32x16 yb = first_layer_block<D>(wm, a_off, gl, x, hb);
+    for (int ks = 0; ks < NKS; ++ks) dg = mfma32_f16(ag[ks], dub[ks], dg);
+    u32x4 ax[2][NRB];
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+      for (int ib = 0; ib < NRB; ++ib) ax[hf][ib] = tr_operand(wm + SM::kW1, ib, 2 * hb + hf);
+    __builtin_amdgcn_sched_barrier(0);
     f16x2 y[8], gp[8];
 #pragma unroll
     for (int p = 0; p < 8; ++p) y[p] = to_f16x2(yb[2 * p], yb[2 * p + 1]);
-    gelu_grad_y16<8>(y, gp);
+    gelu_grad_y16<4>(reinterpret_cast<const f16x2(&)[4]>(y[0]), reinterpret_cast<f16x2(&)[4]>(gp[0]));
+    gelu_grad_y16<4>(reinterpret_cast<const f16x2(&)[4]>(y[4]), reinterpret_cast<f16x2(&)[4]>(gp[4]));
     u32x4 dhb[2];
 #pragma unroll
     for (int p = 0; p < 8; ++p)
       dhb[p / 4][p % 4] = pack_bf16(static_cast<float>(gp[p][0]) * dg[2 * p], static_cast<float>(gp[p][1]) * dg[2 * p + 1]);
+    if (hb + 1 < NRB) {
+#pragma unroll
+      for (int ks = 0; ks < NKS; ++ks) ag[ks] = tr_operand(wm + SM::kW2, hb + 1, ks);
+    }
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
-      for (int ib = 0; ib < NRB; ++ib) dx[ib] = mfma32(tr_operand(wm + SM::kW1, ib, 2 * hb + hf), dhb[hf], dx[ib]);
-    __builtin_amdgcn_sched_barrier(0);
+      for (int ib = 0; ib < NRB; ++ib) dx[ib] = mfma32(ax[hf][ib], dhb[hf], dx[ib]);
   }
+  __builtin_amdgcn_sched_barrier(0);
 }
 
 // grid: one workgroup per compute unit, block WAVES*64.
@@ -405,8 +540,7 @@ __device__ __forceinline__ void map_backward(const unsigned char* wm, const int 
 template <int D, int WAVES>
 __global__ __launch_bounds__(WAVES * 64) void k_vmod_bwd_mfma(Geom g, const unsigned char* __restrict__ wpk,
                                                               float ln_eps, View Tin, View V, View dO,
-                                                              View dT, View dVm,
-                                                              unsigned char* stash) {
+                                                              View dT, View dVm, unsigned char* stash) {
   using SM = VSmem<D>;
   constexpr int NRB = D / 32, NKS = D / 16;
   extern __shared__ __align__(16) unsigned char smem[];
@@ -439,12 +573,15 @@ __global__ __launch_bounds__(WAVES * 64) void k_vmod_bwd_mfma(Geom g, const unsi
   tw.total = tw.tiles_per_row * g.B * g.H;
   tw.H = g.H;
   const int stride = gridDim.x * WAVES;
-  // this wave's stash slot: [map][piece][lane] 16 bytes.  The read pointer is the same address
-  // behind an empty asm statement, so that the compiler treats the reads as real loads instead of
-  // keeping the stored registers alive.
-  unsigned char* slot_wr = stash + static_cast<size_t>(blockIdx.x * WAVES + wave) * (2 * NKS * 1024) + lane * 16;
-  const unsigned char* slot_rd = slot_wr;
-  asm volatile("" : "+v"(slot_rd));
+  // this wave's stash slot: [map][piece][lane] 16 bytes, addressed as a scalar base plus the
+  // lane's offset.  The read bases are the same address behind empty asm statements, so that the
+  // compiler treats the reads as real loads instead of keeping the stored registers alive (and
+  // does not merge the reads of the two passes of norm_backward).
+  unsigned char* slot_wr = stash + static_cast<size_t>(blockIdx.x * WAVES + wave) * (2 * NKS * 1024);
+  const unsigned char* slot_rd[2] = {slot_wr, slot_wr};
+  asm volatile("" : "+s"(slot_rd[0]));
+  asm volatile("" : "+s"(slot_rd[1]));
+  const int lane16 = lane * 16;
   auto put_stash = [&](int m, const f32x16 (&u)[NRB]) {
 #pragma unroll
     for (int ob = 0; ob < NRB; ++ob)
@@ -454,30 +591,27 @@ __global__ __launch_bounds__(WAVES * 64) void k_vmod_bwd_mfma(Geom g, const unsi
 #pragma unroll
         for (int p = 0; p < 4; ++p)
           v[p] = __builtin_bit_cast(uint32_t, to_f16x2(u[ob][8 * hf + 2 * p], u[ob][8 * hf + 2 * p + 1]));
-        *reinterpret_cast<u32x4*>(slot_wr + (m * NKS + 2 * ob + hf) * 1024) = v;
+        *reinterpret_cast<u32x4*>(slot_wr + (m * NKS + 2 * ob + hf) * 1024 + lane16) = v;
       }
   };
-  auto get_stash = [&](int m, u32x4 (&v)[NKS]) {
-#pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) v[ks] = *reinterpret_cast<const u32x4*>(slot_rd + (m * NKS + ks) * 1024);
-  };
+  f16x2 none[1][8];
   for (int tile = blockIdx.x * WAVES + wave; tile < tw.total; tile += stride) {
     int b, h, n0;
     tw.decode(tile, b, h, n0);
     // Phase 1: both maps forward; their normalised outputs u-hat go, packed in fp16, to this
     // wave's slot of the stash in global memory (lane-private 16-byte pieces, so a lane only ever
-    // reads back what it wrote itself) -- the registers of two waves per SIMD cannot hold them
-    // next to the accumulators of the products that follow.
+    // reads back what it wrote itself): next to the accumulators of the products that follow
+    // they do not fit the register file.
     float rstd1, rstd2;
     {
-      u32x4 x[NKS];
+      u32x4 x[NKS], x2[NKS];
       f32x16 u[NRB];
       load_row<D>(Tin, b, h, n0 + r, g.N, gl, x);
-      map_forward<D>(smem, a_off, gl, x, ln_eps, u, rstd1);
+      load_row<D>(V, b, h, n0 + r, g.N, gl, x2);
+      map_forward<D, false>(smem, a_off, gl, x, ln_eps, u, none, rstd1);
       put_stash(0, u);
       __builtin_amdgcn_sched_barrier(0);
-      load_row<D>(V, b, h, n0 + r, g.N, gl, x);
-      map_forward<D>(smem + SM::kMap, a_off, gl, x, ln_eps, u, rstd2);
+      map_forward<D, false>(smem + SM::kMap, a_off, gl, x2, ln_eps, u, none, rstd2);
       put_stash(1, u);
     }
     __builtin_amdgcn_sched_barrier(0);
@@ -485,45 +619,43 @@ __global__ __launch_bounds__(WAVES * 64) void k_vmod_bwd_mfma(Geom g, const unsi
       return [&X, b, h, n0, &g](int t) -> bf16_t* { return n0 + t < g.N ? X.row<bf16_t>(b, h, n0 + t) : nullptr; };
     };
     // Phase 2, per map: LayerNorm backward, then back through the two layers
+    const bf16_t* drow[2] = {dO.row<const bf16_t>(b, h, n0 + r < g.N ? n0 + r : g.N - 1) + 8 * gl, nullptr};
+    drow[1] = drow[0];
+    asm volatile("" : "+v"(drow[1]));
+    auto loader = [&](int self) {
+      return [&, self](int which, int ks, int pass) -> u32x4 {
+        if (which == 0) return load_global16(drow[pass] + 16 * ks);
+        const int m = which == 1 ? self : 1 - self;
+        return load_global16(slot_rd[pass] + (m * NKS + ks) * 1024 + lane16);
+      };
+    };
     {
-      u32x4 xd[NKS], du[NKS];
-      float s1;
-      {
-        u32x4 us[NKS], uo[NKS];
-        load_row<D>(dO, b, h, n0 + r, g.N, gl, xd);
-        get_stash(0, us);
-        get_stash(1, uo);
-        s1 = norm_backward<D>(smem, smem + SM::kMap, gl, xd, us, uo, rstd1, du);
-      }
-      __builtin_amdgcn_sched_barrier(0);
       u32x4 x[NKS];  // read again: the rows are still in the caches
       load_row<D>(Tin, b, h, n0 + r, g.N, gl, x);
+      u32x4 du[NKS];
+      const float s1 = norm_backward<D>(smem, smem + SM::kMap, gl, loader(0), rstd1, du);
+      __builtin_amdgcn_sched_barrier(0);
       f32x16 dx[NRB];
       map_backward<D>(smem, a_off, t_off, gl, x, du, dx);
+      __builtin_amdgcn_sched_barrier(0);
+      load_row<D>(dO, b, h, n0 + r, g.N, gl, x);
       u32x4 w[NRB][2];
 #pragma unroll
       for (int ib = 0; ib < NRB; ++ib) {
         f32x16 o;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) o[i] = __builtin_fmaf(dx[ib][i], s1, row_entry<D>(xd, ib, i));
+        for (int i = 0; i < 16; ++i) o[i] = __builtin_fmaf(dx[ib][i], s1, row_entry<D>(x, ib, i));
         pack_block(o, w[ib]);
       }
       store_tile<D>(w, lane, otile, row_of(dT));
     }
     __builtin_amdgcn_sched_barrier(0);
     {
-      u32x4 du[NKS];
-      float s2;
-      {
-        u32x4 xd[NKS], us[NKS], uo[NKS];
-        load_row<D>(dO, b, h, n0 + r, g.N, gl, xd);
-        get_stash(1, us);
-        get_stash(0, uo);
-        s2 = norm_backward<D>(smem + SM::kMap, smem, gl, xd, us, uo, rstd2, du);
-      }
-      __builtin_amdgcn_sched_barrier(0);
       u32x4 x[NKS];
       load_row<D>(V, b, h, n0 + r, g.N, gl, x);
+      u32x4 du[NKS];
+      const float s2 = norm_backward<D>(smem + SM::kMap, smem, gl, loader(1), rstd2, du);
+      __builtin_amdgcn_sched_barrier(0);
       f32x16 dx[NRB];
       map_backward<D>(smem + SM::kMap, a_off, t_off, gl, x, du, dx);
       u32x4 w[NRB][2];
