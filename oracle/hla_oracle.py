@@ -382,6 +382,32 @@ def phi_v_backward(dm, x, W1, b1, W2, b2, gamma, beta, ln_eps: float):
     return dh @ np.asarray(W1, F64).T
 
 
+def phi_v_weight_grads(dm, x, W1, b1, W2, b2, gamma, beta, ln_eps: float):
+    """(dW1, db1, dW2, db2, dgamma, dbeta) of phi_v (App. A.1) for a loss with gradient dm w.r.t.
+    phi_v(x), summed over the rows of x: dgamma = sum dm * u-hat, dbeta = sum dm, then du as in
+    phi_v_backward, dW2 = GELU(h)^T du, db2 = sum du, dh = (du W2^T) * GELU'(h), dW1 = x^T dh,
+    db1 = sum dh."""
+    x = np.asarray(x, F64)
+    dm = np.asarray(dm, F64)
+    _, h, uhat, rstd = phi_v_forward(x, W1, b1, W2, b2, gamma, beta, ln_eps)
+    g = dm * np.asarray(gamma, F64)
+    du = rstd * (g - g.mean(axis=-1, keepdims=True) - uhat * (g * uhat).mean(axis=-1, keepdims=True))
+    dh = (du @ np.asarray(W2, F64).T) * gelu_erf_grad(h)
+    return (x.T @ dh, dh.sum(axis=0), gelu_erf(h).T @ du, du.sum(axis=0),
+            (dm * uhat).sum(axis=0), dm.sum(axis=0))
+
+
+def value_modulation_weight_grads(dout, t, v, pv1: PhiVWeights, pv2: PhiVWeights, ln_eps: float):
+    """Weight gradients of the two maps of value_modulation_forward for rows [N, d]: phi_v1 sees
+    the upstream gradient dOut * phi_v2(V), phi_v2 sees dOut * phi_v1(T).  Two tuples as
+    phi_v_weight_grads returns them."""
+    dout = np.asarray(dout, F64)
+    m1 = phi_v_forward(t, *pv1.astuple(), ln_eps)[0]
+    m2 = phi_v_forward(v, *pv2.astuple(), ln_eps)[0]
+    return (phi_v_weight_grads(dout * m2, t, *pv1.astuple(), ln_eps),
+            phi_v_weight_grads(dout * m1, v, *pv2.astuple(), ln_eps))
+
+
 def value_modulation_forward(t, v, pv1: PhiVWeights, pv2: PhiVWeights, ln_eps: float):
     """Sec. 4.5: T + phi_v1(T) * phi_v2(V) (elementwise), T = A V the normalised attention output,
     rows [N, d]."""
@@ -476,7 +502,7 @@ def hla_operator_backward(Q, K, V, dO, F: int, d_phi: int, eps: float,
                           phi: Optional[Sequence[PhiWeights]] = None,
                           cu_seqlens: Optional[Sequence[int]] = None,
                           route: str = "factorized", weight_grads: bool = False,
-                          feature_grads: bool = False, vmod=None):
+                          feature_grads: bool = False, vmod=None, vmod_weight_grads: bool = False):
     """(dQ, dK, dV) with the shapes of Q, K, V for L = sum(O * dO).  With feature maps, dK sums
     the contributions of the F key maps (they all read the same K).  With weight_grads (needs
     `phi`) a fourth result lists (dW1, db1, dW2, db2) for phi_q, phi_k1..phi_kF, each summed over
@@ -484,7 +510,9 @@ def hla_operator_backward(Q, K, V, dO, F: int, d_phi: int, eps: float,
     the gradient w.r.t. the features themselves, (dqf [B,H,N,d_phi], dkf [B,H,N,F*d_phi]), the
     intermediate that the feature maps' backward consumes.  vmod as in hla_operator_forward: dO
     is then the gradient w.r.t. the modulated output; it is first taken back through the
-    modulation (to the attention output T and to V), T's share then goes through the operator."""
+    modulation (to the attention output T and to V), T's share then goes through the operator.
+    With vmod_weight_grads (needs `vmod`) the last result lists (dW1, db1, dW2, db2, dgamma,
+    dbeta) for phi_v1 and phi_v2, summed over every sequence, head and token."""
     B, H, N = V.shape[:3]
     dQ = np.zeros(Q.shape, F64)
     dK = np.zeros(K.shape, F64)
@@ -496,6 +524,11 @@ def hla_operator_backward(Q, K, V, dO, F: int, d_phi: int, eps: float,
         if phi is None:
             raise ValueError("weight gradients need the feature maps")
         wg = [[np.zeros_like(a) for a in m.astuple()] for m in phi]
+    vwg = None
+    if vmod_weight_grads:
+        if vmod is None:
+            raise ValueError("the modulation's weight gradients need the modulation")
+        vwg = [[np.zeros_like(a) for a in m.astuple()] for m in vmod[:2]]
     bwd = hla_backward_factorized if route == "factorized" else hla_backward_bruteforce
     for (b, lo, hi) in _units(B, N, cu_seqlens):
         if hi == lo:
@@ -507,6 +540,10 @@ def hla_operator_backward(Q, K, V, dO, F: int, d_phi: int, eps: float,
             dv_mod = 0.0
             if vmod is not None:
                 t = (hla_factorized if route == "factorized" else hla_bruteforce)(qf, kfs, v, eps)[0]
+                if vwg is not None:
+                    for m, part in enumerate(value_modulation_weight_grads(do, t, v, vmod[0], vmod[1], vmod[2])):
+                        for a, da in zip(vwg[m], part):
+                            a += da
                 do, dv_mod = value_modulation_backward(do, t, v, vmod[0], vmod[1], vmod[2])
             dqf, dkfs, dv = bwd(qf, kfs, v, do, eps)
             dV[b, h, lo:hi] = dv + dv_mod
@@ -533,6 +570,8 @@ def hla_operator_backward(Q, K, V, dO, F: int, d_phi: int, eps: float,
         res += ([tuple(m) for m in wg],)
     if feature_grads:
         res += ((dQf, dKf),)
+    if vwg is not None:
+        res += ([tuple(m) for m in vwg],)
     return res
 
 

@@ -126,3 +126,47 @@ def test_operator_with_modulation_against_finite_differences(packed):
     zero = orc.PhiVWeights(np.zeros((d, d)), np.zeros(d), np.zeros((d, d)), np.zeros(d), np.ones(d), np.zeros(d))
     np.testing.assert_array_equal(
         orc.hla_operator_forward(Q, K, V, F, dp, eps, phi=phi, cu_seqlens=cu, vmod=(vmod[0], zero, 1e-5)), plain)
+
+
+def test_modulation_weight_gradients_against_finite_differences():
+    """Every weight array of both maps, perturbed entry by entry through the forward alone."""
+    rng = np.random.default_rng(75)
+    n, d, eps = 6, 5, 1e-5
+    t, v, dout = (rng.standard_normal((n, d)) for _ in range(3))
+    pv1, pv2 = _pv(rng, d, 2.0), _pv(rng, d)
+    f = lambda: float((orc.value_modulation_forward(t, v, pv1, pv2, eps) * dout).sum())
+    got = orc.value_modulation_weight_grads(dout, t, v, pv1, pv2, eps)
+    for pv, grads in zip((pv1, pv2), got):
+        assert len(grads) == 6
+        for arr, ga in zip(pv.astuple(), grads):
+            assert ga.shape == arr.shape
+            np.testing.assert_allclose(ga, _fd(f, arr), rtol=5e-6, atol=2e-8)
+    # closed forms that need no derivative of the network: d/dbeta_1 = sum_t dOut * phi_v2(V),
+    # d/dgamma_1 = sum_t dOut * phi_v2(V) * u-hat_1
+    m2 = orc.phi_v_forward(v, *pv2.astuple(), eps)[0]
+    uhat1 = orc.phi_v_forward(t, *pv1.astuple(), eps)[2]
+    np.testing.assert_allclose(got[0][5], (dout * m2).sum(axis=0), rtol=1e-13)
+    np.testing.assert_allclose(got[0][4], (dout * m2 * uhat1).sum(axis=0), rtol=1e-13)
+    # the second layer's bias cannot move a LayerNorm's output by a common shift: db2 sums to zero
+    assert abs(got[0][3].sum()) < 1e-12 * np.abs(got[0][3]).sum() + 1e-15
+
+
+def test_operator_modulation_weight_gradients_sum_over_heads_and_sequences():
+    rng = np.random.default_rng(76)
+    B, H, N, d, F, dp = 1, 2, 7, 4, 3, 3
+    cu = [0, 3, 7]
+    Q, K, V, dO = (rng.standard_normal((B, H, N, d)) for _ in range(4))
+    phi = [orc.PhiWeights(rng.standard_normal((d, d)), 0.3 * rng.standard_normal(d),
+                          rng.standard_normal((d, dp)), rng.standard_normal(dp) + 1.5)
+           for _ in range(1 + F)]
+    vmod = (_pv(rng, d, 3.0), _pv(rng, d), 1e-5)
+    eps = 1e-4
+    f = lambda: float((orc.hla_operator_forward(Q, K, V, F, dp, eps, phi=phi, cu_seqlens=cu,
+                                                route="bruteforce", vmod=vmod) * dO).sum())
+    res = orc.hla_operator_backward(Q, K, V, dO, F, dp, eps, phi=phi, cu_seqlens=cu, vmod=vmod,
+                                    vmod_weight_grads=True)
+    for pv, grads in zip(vmod[:2], res[-1]):
+        for arr, ga in zip(pv.astuple(), grads):
+            np.testing.assert_allclose(ga, _fd(f, arr), rtol=1e-5, atol=1e-7)
+    with pytest.raises(ValueError):
+        orc.hla_operator_backward(Q, K, V, dO, F, dp, eps, phi=phi, vmod_weight_grads=True)
