@@ -138,6 +138,10 @@ def main():
         wgrads = [{"d" + k: torch.empty(v.shape, dtype=torch.float32, device=dev) for k, v in m.items()}
                   for m in phi]
         h.set_phi_weight_grads(wgrads)
+        if args.value_modulation:  # the modulation's own weights, too
+            vwgrads = [{"d" + k: torch.empty(v.shape, dtype=torch.float32, device=dev) for k, v in m.items()}
+                       for m in vm]
+            h.set_value_modulation_grads(vwgrads)
 
     def step():
         h.forward(t["Q"], t["K"], t["V"], O, cu_seqlens=w.cu_seqlens)

@@ -184,7 +184,8 @@ hla_status hla_set_phi_weight_grads(hla_handle* h, const hla_phi_weight_grads* m
  * gradient w.r.t. the modulated O, carries it back through the modulation first (dV receives the
  * share that reaches V through phi_v2 as well) and must follow a forward made in the same mode.
  * The first registration allocates three [max_heads * max_tokens, d] arrays (synchronous;
- * HLA_ERR_ALLOC on failure).  Gradients of the modulation's own weights are not produced. */
+ * HLA_ERR_ALLOC on failure).  Gradients of the modulation's own weights: see
+ * hla_set_value_modulation_grads. */
 typedef struct {
   const void* W1;
   const void* b1;
@@ -195,6 +196,28 @@ typedef struct {
 } hla_vmod_weights;
 hla_status hla_set_value_modulation(hla_handle* h, const hla_vmod_weights* maps, float ln_eps,
                                     void* hip_stream);
+
+/* Optional outputs of hla_backward: gradients of the loss w.r.t. the weights of the two
+ * value-modulation maps (App. A.1, Sec. 4.5), summed over every token of every head and batch row
+ * (the maps are shared by all of them).  DEVICE pointers to fp32 arrays, caller-owned, shaped like
+ * the weights: dW1 [d, d], db1 [d], dW2 [d, d], db2 [d], dgamma [d], dbeta [d].
+ *
+ * maps = {phi_v1, phi_v2} registers them, maps = NULL clears the registration.  While registered,
+ * every hla_backward OVERWRITES them on its stream; they must stay valid until that work has
+ * completed.  Needs the modulation switched on (HLA_ERR_STATE otherwise); switching it off clears
+ * the registration.  A backward over no tokens writes zeros.  Head dims other than 32, 64, 128 are
+ * HLA_ERR_UNSUPPORTED.  The first registration allocates the workspace (three fp32
+ * [max_heads * max_tokens, d] arrays of per-token factors and the partial sums; synchronous;
+ * HLA_ERR_ALLOC on failure). */
+typedef struct {
+  float* dW1;
+  float* db1;
+  float* dW2;
+  float* db2;
+  float* dgamma;
+  float* dbeta;
+} hla_vmod_weight_grads;
+hla_status hla_set_value_modulation_grads(hla_handle* h, const hla_vmod_weight_grads* maps);
 
 /* hla_forward for callers that cannot allocate device memory: code under HIP graph capture, tight
  * serving loops, harnesses that forbid hipMalloc.  No handle: the workspace (features, chunk

@@ -23,7 +23,7 @@ EXPORTS = (
     "hla_create", "hla_set_phi_weights", "hla_forward", "hla_backward", "hla_destroy",
     "hla_status_string", "hla_active_path", "hla_profile_enable", "hla_profile_read",
     "hla_read_workspace", "hla_set_phi_weight_grads", "hla_forward_static",
-    "hla_set_value_modulation",
+    "hla_set_value_modulation", "hla_set_value_modulation_grads",
 )
 HLA_WS_FEATURES, HLA_WS_FEATURE_GRADS, HLA_WS_DENOMINATORS = 0, 1, 2
 
@@ -47,6 +47,10 @@ class hla_phi_weights(C.Structure):
 
 class hla_phi_weight_grads(C.Structure):
     _fields_ = [("dW1", C.c_void_p), ("db1", C.c_void_p), ("dW2", C.c_void_p), ("db2", C.c_void_p)]
+
+
+class hla_vmod_weight_grads(C.Structure):
+    _fields_ = [(k, C.c_void_p) for k in ("dW1", "db1", "dW2", "db2", "dgamma", "dbeta")]
 
 
 class hla_vmod_weights(C.Structure):
@@ -92,6 +96,8 @@ def load_library() -> C.CDLL:
                                  C.c_int32] + [hla_tensor] * 8 + [C.c_void_p]
     lib.hla_backward.restype = C.c_int
     lib.hla_set_value_modulation.argtypes = [H, C.POINTER(hla_vmod_weights), C.c_float, C.c_void_p]
+    lib.hla_set_value_modulation_grads.argtypes = [H, C.POINTER(hla_vmod_weight_grads)]
+    lib.hla_set_value_modulation_grads.restype = C.c_int
     lib.hla_set_value_modulation.restype = C.c_int
     lib.hla_forward_static.argtypes = [C.POINTER(hla_config), C.c_int32, C.c_int32, C.c_int32,
                                        hla_tensor, hla_tensor, hla_tensor, hla_tensor, C.c_void_p]
@@ -219,6 +225,26 @@ class HLA:
         self._keepalive_grads = list(maps)
         _check(self._lib.hla_set_phi_weight_grads(self._h, arr, len(maps)),
                "hla_set_phi_weight_grads")
+
+    # -- hla_set_value_modulation_grads
+    def set_value_modulation_grads(self, maps: Optional[Sequence[dict]]):
+        """maps: [phi_v1, phi_v2], each {'dW1','db1','dW2','db2','dgamma','dbeta'} contiguous fp32
+        device tensors shaped like the weights, overwritten by every following backward; None
+        switches the outputs off."""
+        import torch
+        if maps is None:
+            _check(self._lib.hla_set_value_modulation_grads(self._h, None), "hla_set_value_modulation_grads")
+            self._keepalive_vmod_grads = None
+            return
+        keys = ("dW1", "db1", "dW2", "db2", "dgamma", "dbeta")
+        arr = (hla_vmod_weight_grads * 2)()
+        for i, m in enumerate(maps):
+            for k in keys:
+                if m[k].dtype != torch.float32 or not m[k].is_contiguous():
+                    raise ValueError("weight gradients must be contiguous fp32 tensors")
+            arr[i] = hla_vmod_weight_grads(*(m[k].data_ptr() for k in keys))
+        self._keepalive_vmod_grads = list(maps)
+        _check(self._lib.hla_set_value_modulation_grads(self._h, arr), "hla_set_value_modulation_grads")
 
     # -- hla_set_value_modulation
     def set_value_modulation(self, maps: Optional[Sequence[dict]], ln_eps: float = 1e-5, stream=None):

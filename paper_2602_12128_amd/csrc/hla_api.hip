@@ -153,6 +153,8 @@ void free_all(hla_handle* hd) {
     (void)hipFree(hd->wg_partial);
     (void)hipFree(hd->vmod_w);
     (void)hipFree(hd->vmod_wpk);
+    (void)hipFree(hd->vmod_wg_partial);
+    (void)hipFree(hd->vmod_wg_rows);
     (void)hipFree(hd->vmod_T);
     (void)hipFree(hd->vmod_dT);
     (void)hipFree(hd->vmod_dV);
@@ -385,6 +387,7 @@ hla_status hla_set_value_modulation(hla_handle* hd, const hla_vmod_weights* maps
   hd->have_forward = false;
   if (maps == nullptr) {
     hd->vmod_on = false;
+    hd->vmod_wg_on = false;
     return HLA_OK;
   }
   if (!(ln_eps >= 0.0f)) return HLA_ERR_INVALID_ARG;
@@ -423,6 +426,36 @@ hla_status hla_set_value_modulation(hla_handle* hd, const hla_vmod_weights* maps
   HLA_TRY(vmod_set_weights(hd, maps, static_cast<hipStream_t>(hip_stream)));
   hd->vmod_ln_eps = ln_eps;
   hd->vmod_on = true;
+  return HLA_OK;
+}
+
+hla_status hla_set_value_modulation_grads(hla_handle* hd, const hla_vmod_weight_grads* maps) {
+  if (hd == nullptr) return HLA_ERR_INVALID_ARG;
+  if (maps == nullptr) {
+    hd->vmod_wg_on = false;
+    return HLA_OK;
+  }
+  if (!hd->vmod_on) return HLA_ERR_STATE;
+  const int d = hd->g.d;
+  if (d != 32 && d != 64 && d != 128) return HLA_ERR_UNSUPPORTED;
+  for (int m = 0; m < 2; ++m)
+    if (!maps[m].dW1 || !maps[m].db1 || !maps[m].dW2 || !maps[m].db2 || !maps[m].dgamma || !maps[m].dbeta)
+      return HLA_ERR_INVALID_ARG;
+  if (hd->vmod_wg_partial == nullptr) {
+    Arena arena;  // hipMalloc
+    float *part = nullptr, *rows = nullptr;
+    hla_status st = arena.alloc(&part, static_cast<size_t>(kVmodWgradParts) * vmod_wgrad_part_floats(d));
+    if (st == HLA_OK) st = arena.alloc(&rows, static_cast<size_t>(3) * hd->max_th * d);
+    if (st != HLA_OK) {
+      (void)hipFree(part);
+      (void)hipFree(rows);
+      return st;
+    }
+    hd->vmod_wg_partial = part;
+    hd->vmod_wg_rows = rows;
+  }
+  for (int m = 0; m < 2; ++m) hd->vmod_wg_out[m] = maps[m];
+  hd->vmod_wg_on = true;
   return HLA_OK;
 }
 
@@ -496,6 +529,11 @@ hla_status hla_backward(hla_handle* hd, int32_t B, int32_t H, int32_t N, const i
     if (hd->wg_on && H > 0)
       HLA_TRY(weight_grads_reduce(hd, 0, hd->phi.heads_w == 1 ? 1 : H, 0.0f, 0.0f, 0.0f, 0.0f,
                                   static_cast<hipStream_t>(hip_stream)));
+    if (hd->vmod_on && hd->vmod_wg_on) {
+      hla_call_args z{};
+      z.stream = static_cast<hipStream_t>(hip_stream);
+      HLA_TRY(vmod_weight_grads(hd, z, true));
+    }
     return HLA_OK;
   }
   if (bad_view(Q) || bad_view(K) || bad_view(V) || bad_view(O) || bad_view(dO) || bad_view(dQ) ||
@@ -520,6 +558,7 @@ hla_status hla_backward(hla_handle* hd, int32_t B, int32_t H, int32_t N, const i
     // back through the modulation first: the operator then sees dT as its upstream gradient and
     // T as its output; the modulation's share of dV is added once the operator has written dV
     HLA_TRY(vmod_backward(hd, a));
+    if (hd->vmod_wg_on) HLA_TRY(vmod_weight_grads(hd, a, false));
     a.dO = vmod_view(hd->vmod_dT, hd->g);
     a.O = vmod_view(hd->vmod_T, hd->g);
   }

@@ -19,6 +19,7 @@ struct hla_token_table {
   bool valid = false;
 };
 constexpr int kTableRoles = 3;
+constexpr int kVmodWgradParts = 1024;  // most partial sums (workgroups per map) of the modulation's weight gradients
 
 struct hla_call_args {
   int32_t B, H, N;
@@ -73,6 +74,11 @@ struct hla_handle {
   void* vmod_dT = nullptr;
   void* vmod_dV = nullptr;
   bool fw_vmod = false;            // mode of the last forward
+  // gradients of the modulation's own weights (optional): caller's fp32 arrays, per-workgroup partials
+  bool vmod_wg_on = false;
+  hla_vmod_weight_grads vmod_wg_out[2] = {};
+  float* vmod_wg_partial = nullptr;  // [kVmodWgradParts][d d + d]
+  float* vmod_wg_rows = nullptr;     // three [max_th][d] arrays of per-token factors
 
   // token tables, one per role (the path's workspace plan names the roles it uses)
   hla_token_table tables[kTableRoles];
@@ -139,6 +145,10 @@ hla_status vmod_forward(hla_handle* hd, const hla_call_args& a);
 hla_status vmod_backward(hla_handle* hd, const hla_call_args& a);
 hla_status vmod_add_value_grads(hla_handle* hd, const hla_call_args& a);
 View vmod_view(void* p, const Geom& g);  // contiguous [B, H, N, d] view of a workspace array
+// Gradients of the modulation's weights from (hd->vmod_T, a.V, a.dO = gradient w.r.t. the modulated
+// output) into the registered arrays; `empty`: no tokens, zeros are written.
+hla_status vmod_weight_grads(hla_handle* hd, const hla_call_args& a, bool empty);
+int64_t vmod_wgrad_part_floats(int d);
 // The same on the matrix cores (hla_mfma_vmod.hip), used by the functions above where supported.
 bool vmod_mfma_supported(const hla_handle* hd);
 size_t vmod_mfma_packed_bytes(const hla_handle* hd);

@@ -58,16 +58,19 @@ def make_handle(tensors, F, d_phi, eps, phi, cu_seqlens, path=hla.HLA_PATH_AUTO,
 
 
 WG_KEYS = ("dW1", "db1", "dW2", "db2")
+VWG_KEYS = ("dW1", "db1", "dW2", "db2", "dgamma", "dbeta")
 
 
 def run_gpu(tensors: Dict[str, torch.Tensor], F: int, d_phi: int, eps: float,
             phi=None, cu_seqlens=None, backward=True, path=hla.HLA_PATH_AUTO, handle=None,
-            weight_grads=False, per_head=False, features=False, vmod=None, ln_eps=1e-5):
+            weight_grads=False, per_head=False, features=False, vmod=None, ln_eps=1e-5,
+            vmod_weight_grads=False):
     """Returns dict of CPU tensors O (and dQ, dK, dV) computed by the HIP library; with
     weight_grads also 'wg': per map a dict of the fp32 weight gradients.  per_head: the weights
     carry a leading head dimension.  features: also '_features' [B,H,N,(1+F)*d_phi], the
     library's own feature workspace (an output to be compared, like the others).  vmod: the two
-    value-modulation maps (Sec. 4.5), switched on for the call."""
+    value-modulation maps (Sec. 4.5), switched on for the call; with vmod_weight_grads also
+    'vwg': per map a dict of the fp32 gradients of its weights."""
     dev = torch.device("cuda:0")
     t = {k: v.to(dev) for k, v in tensors.items()}
     h = handle or make_handle(tensors, F, d_phi, eps, phi, cu_seqlens, path)
@@ -81,6 +84,11 @@ def run_gpu(tensors: Dict[str, torch.Tensor], F: int, d_phi: int, eps: float,
             h.set_phi_weight_grads(wg)
     if vmod is not None:
         h.set_value_modulation([{k: v.to(dev) for k, v in m.items()} for m in vmod], ln_eps)
+    vwg = None
+    if vmod_weight_grads:
+        vwg = [{"d" + k: torch.full(v.shape, float("nan"), dtype=torch.float32, device=dev)
+                for k, v in m.items()} for m in vmod]
+        h.set_value_modulation_grads(vwg)
     out = {"O": torch.full_like(t["V"], float("nan"))}
     h.forward(t["Q"], t["K"], t["V"], out["O"], cu_seqlens=cu_seqlens)
     if backward:
@@ -92,6 +100,8 @@ def run_gpu(tensors: Dict[str, torch.Tensor], F: int, d_phi: int, eps: float,
     res = {k: v.cpu() for k, v in out.items()}
     if wg is not None:
         res["wg"] = [{k: v.cpu() for k, v in m.items()} for m in wg]
+    if vwg is not None:
+        res["vwg"] = [{k: v.cpu() for k, v in m.items()} for m in vwg]
     if features:
         B, H, N = t["V"].shape[:3]
         nfeat = (1 + F) * d_phi
@@ -110,7 +120,7 @@ def oracle_vmod(vmod, ln_eps):
 
 
 def run_oracle(tensors, F, d_phi, eps, phi=None, cu_seqlens=None, backward=True,
-               route="factorized", weight_grads=False, vmod=None, ln_eps=1e-5):
+               route="factorized", weight_grads=False, vmod=None, ln_eps=1e-5, vmod_weight_grads=False):
     """O (and dQ, dK, dV, 'wg') from the oracle; with feature maps and a backward also the
     feature gradients '_dqf', '_dkf' that the branch enumeration below starts from."""
     Q, K, V = (to_np(tensors[k]) for k in ("Q", "K", "V"))
@@ -121,10 +131,14 @@ def run_oracle(tensors, F, d_phi, eps, phi=None, cu_seqlens=None, backward=True,
     if backward:
         res = orc.hla_operator_backward(Q, K, V, to_np(tensors["dO"]), F, d_phi, eps,
                                         phi=ophi, cu_seqlens=cu_seqlens, route=route,
-                                        weight_grads=weight_grads, feature_grads=True, vmod=ovm)
+                                        weight_grads=weight_grads, feature_grads=True, vmod=ovm,
+                                        vmod_weight_grads=vmod_weight_grads)
         out.update(dQ=res[0], dK=res[1], dV=res[2])
         if weight_grads:
             out["wg"] = [dict(zip(WG_KEYS, m)) for m in res[3]]
+        if vmod_weight_grads:
+            out["vwg"] = [dict(zip(VWG_KEYS, m)) for m in res[-1]]
+            res = res[:-1]
         out["_dqf"], out["_dkf"] = res[-1]
     return out
 
@@ -223,6 +237,23 @@ def assert_parity(gpu, ref, tol, what="", kinks=None, row_scale=None):
     bad = {k: e for k, e in errs.items() if not e <= tol}
     assert not bad, f"{what}: max relative error above {tol:g}: {bad}"
     return errs
+
+
+def assert_vmod_weight_grad_parity(gpu_vwg, ref_vwg, tol, what=""):
+    """The six weight-gradient arrays of the two value-modulation maps against the oracle, each
+    with the build's error measure (max |diff| / max |ref| per array).  These maps have no ReLU:
+    nothing to enumerate."""
+    worst = {}
+    for m, (g, r) in enumerate(zip(gpu_vwg, ref_vwg)):
+        for k in VWG_KEYS:
+            got = to_np(g[k])
+            assert np.isfinite(got).all(), f"{what}: map {m} {k} has non-finite entries"
+            assert got.shape == r[k].shape
+            worst[f"{k}[{m}]"] = max_rel_err(got, r[k])
+    print(f"[parity] {what}: " + ", ".join(f"{k}={v:.2e}" for k, v in worst.items()) + f" (tol {tol:g})")
+    bad = {k: v for k, v in worst.items() if not v <= tol}
+    assert not bad, f"{what}: max relative error above {tol:g}: {bad}"
+    return worst
 
 
 def assert_weight_grad_parity(gpu_wg, ref_wg, tol, what="", branches=None):

@@ -73,3 +73,56 @@ def test_switching_the_modulation_off_and_on():
         h.set_value_modulation([{k: v.to(dev) for k, v in m.items()} for m in vm], ln_eps=-1.0)
     assert e.value.code == 1
     h.destroy()
+
+
+@pytest.mark.parametrize("dtype,path,F,dphi,d,B,H,N,tol", [
+    (torch.float32, hla.HLA_PATH_GENERIC, 3, 6, 32, 2, 2, 83, 1e-4),
+    (torch.float32, hla.HLA_PATH_GENERIC, 2, 12, 64, 1, 3, 150, 1e-4),
+    (torch.bfloat16, hla.HLA_PATH_MFMA, 3, 6, 128, 1, 2, 700, 2e-2),
+    (torch.bfloat16, hla.HLA_PATH_MFMA, 2, 12, 64, 2, 3, 333, 2e-2),
+])
+def test_modulation_weight_gradients(dtype, path, F, dphi, d, B, H, N, tol):
+    """Gradients of the two maps' own weights (summed over all tokens of all heads) next to the
+    input gradients, which registering them must not change."""
+    t, phi = wl.make_raw_inputs(1160 + N, B, H, N, d, F, dphi, dtype)
+    vm = _vmod(1161 + N, d, dtype)
+    gpu = pu.run_gpu(t, F, dphi, 1e-6, phi=phi, path=path, vmod=vm, vmod_weight_grads=True)
+    ref = pu.run_oracle(t, F, dphi, 1e-6, phi=phi, vmod=vm, vmod_weight_grads=True)
+    pu.assert_vmod_weight_grad_parity(gpu["vwg"], ref["vwg"], tol, f"modulation weight grads {dtype} d={d} N={N}")
+    plain = pu.run_gpu(t, F, dphi, 1e-6, phi=phi, path=path, vmod=vm)
+    for k in ("O", "dQ", "dK", "dV"):
+        assert torch.equal(gpu[k], plain[k]), k
+
+
+def test_modulation_weight_gradients_registration_rules():
+    dev = torch.device("cuda:0")
+    t = wl.make_feature_inputs(1170, 1, 2, 100, 64, 3, 6, torch.bfloat16)
+    vm = _vmod(1171, 64, torch.bfloat16)
+    td = {k: v.to(dev) for k, v in t.items()}
+    h = pu.make_handle(t, 3, 6, 1e-6, None, None)
+    grads = [{"d" + k: torch.full(v.shape, float("nan"), dtype=torch.float32, device=dev) for k, v in m.items()}
+             for m in vm]
+    with pytest.raises(hla.HLAError) as e:  # the modulation is off
+        h.set_value_modulation_grads(grads)
+    assert e.value.code == 5
+    h.set_value_modulation([{k: v.to(dev) for k, v in m.items()} for m in vm])
+    h.set_value_modulation_grads(grads)
+    O = torch.empty_like(td["V"])
+    g = [torch.empty_like(td[k]) for k in "QKV"]
+    h.forward(td["Q"], td["K"], td["V"], O)
+    h.backward(td["Q"], td["K"], td["V"], O, td["dO"], *g)
+    torch.cuda.synchronize()
+    assert all(torch.isfinite(a).all() for m in grads for a in m.values())
+    first = [{k: v.clone() for k, v in m.items()} for m in grads]
+    h.backward(td["Q"], td["K"], td["V"], O, td["dO"], *g)  # overwritten, not accumulated; deterministic
+    torch.cuda.synchronize()
+    assert all(torch.equal(a[k], b[k]) for a, b in zip(first, grads) for k in a)
+    h.set_value_modulation(None)  # clears the registration
+    for m in grads:
+        for a in m.values():
+            a.fill_(7.0)
+    h.forward(td["Q"], td["K"], td["V"], O)
+    h.backward(td["Q"], td["K"], td["V"], O, td["dO"], *g)
+    torch.cuda.synchronize()
+    assert all((a == 7.0).all() for m in grads for a in m.values())
+    h.destroy()
