@@ -217,25 +217,31 @@ def hla_sequential_state(kfs, v):
 # --------------------------------------------------------------------------------------------
 # Causal variant (Sec. 4.4): token i attends to tokens j <= i only
 # --------------------------------------------------------------------------------------------
-def hla_causal_bruteforce(qf, kfs, v, eps: float, rows=None):
+def hla_causal_bruteforce(qf, kfs, v, eps: float, rows=None, decay: float = 1.0):
     """Eq. 'hla' with the {0,1} causal mask of Sec. 4.4 on the N x N matrix: A_ij as before for
     j <= i, zero for j > i; eta_i = sum_{j<=i} A_ij; o_i = sum_{j<=i} A_ij v_j / (eta_i + eps).
-    rows: optional indices of the query rows to evaluate (against all their keys)."""
+    rows: optional indices of the query rows to evaluate (against all their keys).
+    decay: Sec. 4.4 lets the mask carry decay factors but gives no formula; the reading taken is
+    one scalar lambda in (0, 1] and mask entries lambda^(i - j) for j <= i (a token's
+    contribution fades geometrically with its distance), 1 = the plain {0,1} mask."""
     qf = np.asarray(qf, F64)
     v = np.asarray(v, F64)
     idx = np.arange(qf.shape[0]) if rows is None else np.asarray(rows)
     A = np.ones((len(idx), v.shape[0]), dtype=F64)
     for kf in kfs:
         A = A * (qf[idx] @ np.asarray(kf, F64).T)
-    A = A * (np.arange(v.shape[0])[None, :] <= idx[:, None])
+    dist = idx[:, None] - np.arange(v.shape[0])[None, :]
+    A = A * np.where(dist >= 0, float(decay) ** np.maximum(dist, 0), 0.0)
     eta = A.sum(axis=1)
     return (A @ v) / (eta + eps)[:, None]
 
 
-def hla_causal_sequential(qf, kfs, v, eps: float):
+def hla_causal_sequential(qf, kfs, v, eps: float, decay: float = 1.0):
     """The sequential updates of Sec. 4.4: the context tensor is the state, C^i = C^{i-1} +
     T_k,i (Kronecker) v_i (and z^i = z^{i-1} + T_k,i for the normaliser), and token i's output is
-    the contraction of T_q,i with C^i, divided by T_q,i . z^i + eps.  Python loop: small inputs."""
+    the contraction of T_q,i with C^i, divided by T_q,i . z^i + eps.  With a decay factor the old
+    state is multiplied by it before the new token is added: C^i = decay C^{i-1} + T_k,i (x) v_i.
+    Python loop: small inputs."""
     qf = np.asarray(qf, F64)
     kfs = [np.asarray(k, F64) for k in kfs]
     v = np.asarray(v, F64)
@@ -246,8 +252,8 @@ def hla_causal_sequential(qf, kfs, v, eps: float):
     out = np.zeros_like(v)
     for i in range(v.shape[0]):
         tk = outer_features([k[i:i + 1] for k in kfs])[0]
-        C += np.outer(tk, v[i])
-        z += tk
+        C = decay * C + np.outer(tk, v[i])
+        z = decay * z + tk
         tq = outer_features([qf[i:i + 1]] * F)[0]
         out[i] = (tq @ C) / (tq @ z + eps)
     return out
@@ -469,13 +475,14 @@ def _features(Q, K, lo, hi, b, h, F, d_phi, phi: Optional[Sequence[PhiWeights]])
 def hla_operator_forward(Q, K, V, F: int, d_phi: int, eps: float,
                          phi: Optional[Sequence[PhiWeights]] = None,
                          cu_seqlens: Optional[Sequence[int]] = None,
-                         route: str = "factorized", vmod=None, causal: bool = False) -> np.ndarray:
+                         route: str = "factorized", vmod=None, causal: bool = False,
+                         decay: float = 1.0) -> np.ndarray:
     """O [B,H,N,d] for Q,K,V [B,H,N,*].  `phi` = [phi_q, phi_k1..phi_kF] or None when Q and K
     already hold features.  Sequences (batch entries, or the packed ranges of cu_seqlens) never
     share state.  vmod = (phi_v1, phi_v2, ln_eps) applies the value modulation of Sec. 4.5 to the
     attention output, token by token (maps shared by all heads).  causal: the masked variant of
     Sec. 4.4 inside every sequence (route 'bruteforce' = masked N x N matrix, 'factorized' = the
-    sequential state updates)."""
+    sequential state updates), `decay` its decay factor (see hla_causal_bruteforce)."""
     B, H, N = V.shape[:3]
     O = np.zeros(V.shape, F64)
     for (b, lo, hi) in _units(B, N, cu_seqlens):
@@ -486,7 +493,7 @@ def hla_operator_forward(Q, K, V, F: int, d_phi: int, eps: float,
             v = np.asarray(V[b, h, lo:hi], F64)
             if causal:
                 O[b, h, lo:hi] = (hla_causal_sequential if route == "factorized" else
-                                  hla_causal_bruteforce)(qf, kfs, v, eps)
+                                  hla_causal_bruteforce)(qf, kfs, v, eps, decay=decay)
             elif route == "factorized":
                 O[b, h, lo:hi] = hla_factorized(qf, kfs, v, eps)[0]
             elif route == "bruteforce":

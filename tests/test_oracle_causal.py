@@ -84,3 +84,69 @@ def test_operator_level_causal_is_per_sequence():
         kf = [K[0, h, 5, f * dp:(f + 1) * dp] for f in range(F)]
         a55 = np.prod([Q[0, h, 5] @ k for k in kf])
         np.testing.assert_allclose(a[0, h, 5], V[0, h, 5] * a55 / (a55 + 1e-6), rtol=1e-12)
+
+
+# ---- decay factors (Sec. 4.4; reading: mask entries lambda^(i-j)) --------------------------------
+@pytest.mark.parametrize("F,dp,lam", [(1, 5, 0.9), (2, 4, 0.5), (3, 3, 0.97), (3, 6, 0.8)])
+def test_decayed_mask_equals_decayed_state_updates(F, dp, lam):
+    q, ks, v = _inputs(90 + F, 21, dp, 5, F)
+    a = orc.hla_causal_bruteforce(q, ks, v, 1e-6, decay=lam)
+    b = orc.hla_causal_sequential(q, ks, v, 1e-6, decay=lam)
+    np.testing.assert_allclose(a, b, rtol=1e-11, atol=1e-13)
+    # a subset of rows against all their keys is the same rows of the full result
+    rows = [0, 7, 20]
+    np.testing.assert_array_equal(orc.hla_causal_bruteforce(q, ks, v, 1e-6, rows=rows, decay=lam), a[rows])
+
+
+def test_decayed_mask_against_scalar_loops_and_limits():
+    q, ks, v = _inputs(95, 8, 3, 4, 2)
+    eps, lam = 1e-3, 0.7
+    got = orc.hla_causal_bruteforce(q, ks, v, eps, decay=lam)
+    for i in range(8):
+        num, eta = np.zeros(4), 0.0
+        for j in range(i + 1):
+            a = 1.0
+            for f in range(2):
+                a *= sum(q[i, c] * ks[f][j, c] for c in range(3))
+            a *= lam ** (i - j)          # the token's own position keeps weight 1
+            eta += a
+            num += a * v[j]
+        np.testing.assert_allclose(got[i], num / (eta + eps), rtol=1e-12, atol=1e-14)
+    # decay 1 is the plain causal mask (bit for bit); decay -> 0 leaves every token with itself
+    np.testing.assert_array_equal(orc.hla_causal_bruteforce(q, ks, v, eps, decay=1.0),
+                                  orc.hla_causal_bruteforce(q, ks, v, eps))
+    np.testing.assert_array_equal(orc.hla_causal_sequential(q, ks, v, eps, decay=1.0),
+                                  orc.hla_causal_sequential(q, ks, v, eps))
+    np.testing.assert_allclose(orc.hla_causal_bruteforce(q, ks, v, 0.0, decay=1e-200), v, rtol=1e-12)
+
+
+def test_identical_keys_give_the_geometrically_weighted_mean():
+    """With every key token equal, A_ij is the same for all j, so (eps = 0) o_i is the mean of
+    v_0..v_i with weights lambda^(i-j): a closed form that involves no feature arithmetic."""
+    rng = np.random.default_rng(96)
+    n, dp, d, lam = 12, 4, 3, 0.6
+    q = np.abs(rng.standard_normal((n, dp))) + 0.1
+    k1 = np.tile(np.abs(rng.standard_normal((1, dp))) + 0.1, (n, 1))
+    k2 = np.tile(np.abs(rng.standard_normal((1, dp))) + 0.1, (n, 1))
+    v = rng.standard_normal((n, d))
+    for fn in (orc.hla_causal_bruteforce, orc.hla_causal_sequential):
+        got = fn(q, [k1, k2], v, 0.0, decay=lam)
+        for i in range(n):
+            w = lam ** np.arange(i, -1, -1)
+            np.testing.assert_allclose(got[i], np.average(v[:i + 1], axis=0, weights=w), rtol=1e-11, atol=1e-13)
+
+
+def test_operator_level_decay_restarts_with_every_sequence():
+    rng = np.random.default_rng(97)
+    H, d, F, dp, lam = 2, 4, 2, 3, 0.85
+    cu = [0, 5, 5, 12]
+    Q = np.abs(rng.standard_normal((1, H, 12, dp)))
+    K = np.abs(rng.standard_normal((1, H, 12, F * dp)))
+    V = rng.standard_normal((1, H, 12, d))
+    for route in ("factorized", "bruteforce"):
+        O = orc.hla_operator_forward(Q, K, V, F, dp, 1e-6, cu_seqlens=cu, causal=True, decay=lam, route=route)
+        for (lo, hi) in ((0, 5), (5, 12)):
+            for h in range(H):
+                ref = orc.hla_causal_bruteforce(Q[0, h, lo:hi], [K[0, h, lo:hi, f * dp:(f + 1) * dp] for f in range(F)],
+                                                V[0, h, lo:hi], 1e-6, decay=lam)
+                np.testing.assert_allclose(O[0, h, lo:hi], ref, rtol=1e-11, atol=1e-13)
