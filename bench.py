@@ -43,6 +43,8 @@ def parse():
                     help="switch on the value modulation of Sec. 4.5 (a different workload: named in config)")
     ap.add_argument("--causal", action="store_true",
                     help="the causal variant of Sec. 4.4, forward only (a different workload: named in config)")
+    ap.add_argument("--decay", type=float, default=1.0,
+                    help="with --causal: decay factor of the mask (Sec. 4.4), 1 = none")
     return ap.parse_args()
 
 
@@ -122,7 +124,7 @@ def main():
     h = hla.HLA(head_dim=w.d, feature_dim=w.d_phi, degree=w.F, eps=w.eps,
                 io_dtype=hla.HLA_F32 if w.dtype == torch.float32 else hla.HLA_BF16,
                 phi_mode=hla.HLA_PHI_NONE if phi is None else hla.HLA_PHI_MLP, kernel_path=path,
-                max_heads=w.H, max_tokens=w.B * w.N, max_seqs=nseq, causal=args.causal)
+                max_heads=w.H, max_tokens=w.B * w.N, max_seqs=nseq, causal=args.causal, decay=args.decay if args.causal else 1.0)
     if phi is not None:
         h.set_phi_weights([{k: v.to(dev) for k, v in m.items()} for m in phi])
     if args.value_modulation:
@@ -229,7 +231,7 @@ def main():
                    "d_phi": w.d_phi, "phi": "mlp" if phi is not None else "none",
                    "packed_seqs": nseq if w.cu_seqlens else 0,
                    "path": "mfma" if h.active_path == hla.HLA_PATH_MFMA else "generic",
-                   "weight_grads": wgrads is not None, "value_modulation": args.value_modulation,
+                   "weight_grads": wgrads is not None, "value_modulation": args.value_modulation, "decay": args.decay if args.causal else None,
                    "causal": args.causal},
         "tflops_nominal": tflops,
         "mfma_peak_frac_nominal": tflops / 2500.0,

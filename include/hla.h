@@ -81,8 +81,13 @@ typedef struct {
                             is what the paper's sequential state update C^i = C^{i-1} + T_k,i (x) v_i
                             computes.  Forward only, MFMA path only: hla_create returns
                             HLA_ERR_UNSUPPORTED for a configuration without MFMA kernels,
-                            hla_backward and hla_forward_static return it for a causal handle.
-                            Decay factors are not implemented. */
+                            hla_backward and hla_forward_static return it for a causal handle. */
+  float decay;           /* causal handles only: decay factor lambda of Sec. 4.4.  The paper lets the
+                            mask carry decay factors without giving a formula; this library reads it
+                            as one scalar lambda in (0, 1] and mask entries lambda^(i-j) for j <= i
+                            (state update C^i = lambda C^{i-1} + T_k,i (x) v_i, the normaliser
+                            likewise).  0 and 1 both mean no decay.  Anything else than 0 or 1 on a
+                            non-causal handle, or a value outside [0, 1], is HLA_ERR_INVALID_ARG. */
 } hla_config;
 
 /* Weights of one feature map, device pointers in io_dtype, row-major, applied from the right:

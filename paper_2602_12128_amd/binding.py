@@ -33,7 +33,7 @@ class hla_config(C.Structure):
         ("head_dim", C.c_int32), ("feature_dim", C.c_int32), ("degree", C.c_int32),
         ("eps", C.c_float), ("io_dtype", C.c_int32), ("phi_mode", C.c_int32),
         ("kernel_path", C.c_int32), ("max_heads", C.c_int32), ("max_tokens", C.c_int64),
-        ("max_seqs", C.c_int32), ("causal", C.c_int32),
+        ("max_seqs", C.c_int32), ("causal", C.c_int32), ("decay", C.c_float),
     ]
 
 
@@ -163,10 +163,10 @@ class HLA:
     def __init__(self, head_dim: int, feature_dim: int = 6, degree: int = 3, eps: float = 1e-6,
                  io_dtype: int = HLA_BF16, phi_mode: int = HLA_PHI_MLP,
                  kernel_path: int = HLA_PATH_AUTO, max_heads: int = 1, max_tokens: int = 1,
-                 max_seqs: int = 1, causal: bool = False):
+                 max_seqs: int = 1, causal: bool = False, decay: float = 1.0):
         self._lib = load_library()
         self.config = hla_config(head_dim, feature_dim, degree, eps, io_dtype, phi_mode,
-                                 kernel_path, max_heads, max_tokens, max_seqs, int(causal))
+                                 kernel_path, max_heads, max_tokens, max_seqs, int(causal), float(decay))
         self._h = C.c_void_p()
         _check(self._lib.hla_create(C.byref(self.config), C.byref(self._h)), "hla_create")
         self._keepalive = None

@@ -221,6 +221,8 @@ hla_status validate_config(const hla_config* c) {
   if (c->kernel_path < HLA_PATH_AUTO || c->kernel_path > HLA_PATH_MFMA) return HLA_ERR_INVALID_ARG;
   if (!(c->eps >= 0.0f)) return HLA_ERR_INVALID_ARG;
   if (c->causal != 0 && c->causal != 1) return HLA_ERR_INVALID_ARG;
+  if (!(c->decay >= 0.0f && c->decay <= 1.0f)) return HLA_ERR_INVALID_ARG;
+  if (!c->causal && c->decay != 0.0f && c->decay != 1.0f) return HLA_ERR_INVALID_ARG;
   if (c->head_dim != 32 && c->head_dim != 64 && c->head_dim != 128) return HLA_ERR_UNSUPPORTED;
   if (c->degree < 1 || c->degree > 4 || c->feature_dim < 1) return HLA_ERR_UNSUPPORTED;
   if (c->feature_dim > 256 || ipow(c->feature_dim, c->degree) > 256) return HLA_ERR_UNSUPPORTED;
@@ -589,7 +591,7 @@ StaticSlot g_static[kMaxDevices];
 bool same_config(const hla_config& a, const hla_config& b) {
   return a.head_dim == b.head_dim && a.feature_dim == b.feature_dim && a.degree == b.degree &&
          a.eps == b.eps && a.io_dtype == b.io_dtype && a.phi_mode == b.phi_mode &&
-         a.kernel_path == b.kernel_path && a.causal == b.causal && a.max_heads == b.max_heads &&
+         a.kernel_path == b.kernel_path && a.causal == b.causal && a.decay == b.decay && a.max_heads == b.max_heads &&
          a.max_tokens == b.max_tokens && a.max_seqs == b.max_seqs;
 }
 

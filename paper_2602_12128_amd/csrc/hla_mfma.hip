@@ -22,6 +22,7 @@ constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
 constexpr int kQueryTarget = 496;  // workgroups aimed at by the query kernel: two per CU, one resident round
 constexpr int kMinChunk = 256;     // smallest chunk pick_chunk returns
+constexpr int kCausalChunk = 256;  // tokens per chunk of the causal scan
 constexpr int kMinQueryBlock = 128;  // smallest block pick_query_block returns
 constexpr int kChunkTarget = 256;  // workgroups aimed at by the chunked (token-contraction) kernels: one per CU
 constexpr int kChunkGrain = 64;    // chunk sizes are multiples of this many tokens (one wave step of k_state)
@@ -130,7 +131,7 @@ template <class SY, int D>
 __global__ __launch_bounds__(kThreads) void k_state(Geom g, const BlockEnt* __restrict__ chunks,
                                                     const float* __restrict__ feat, View V,
                                                     float* __restrict__ partial,
-                                                    int64_t partial_stride) {
+                                                    int64_t partial_stride, float log2_decay) {
   constexpr int DP = SY::DPHI, F = SY::F, MP = SY::MP;
   using SM = StateSmem<D, MP>;
   constexpr int NCB = D / 32;      // column blocks of the state
@@ -188,6 +189,14 @@ __global__ __launch_bounds__(kThreads) void k_state(Geom g, const BlockEnt* __re
       for (int f = 0; f < F; ++f)
 #pragma unroll
         for (int a = 0; a < DP; ++a) kk[f][a] = kf[f * DP + a];
+      if (log2_decay != 0.0f) {
+        // causal scan with a decay factor: the chunk's state is taken as seen from the first token
+        // behind the chunk, token n weighs decay^(t0 + chunk - n); the key tensor is linear in
+        // each factor, so the weight goes on the first one
+        const float wgt = __builtin_amdgcn_exp2f(log2_decay * static_cast<float>(e.t0 + kCausalChunk - (n0 + lane)));
+#pragma unroll
+        for (int a = 0; a < DP; ++a) kk[0][a] *= wgt;
+      }
       if (n0 + kWaves * 64 < e.t1) fetch(n0 + kWaves * 64);
       float sm[SY::NM];
       sym_key_monomials_all<SY>(kk, sm);
@@ -447,7 +456,6 @@ __global__ __launch_bounds__(kThreads) void k_query(Geom g, const BlockEnt* __re
 // BEFORE each chunk (exclusive running sum in chunk order, emitted as the query kernel's operand
 // image), and k_query_causal adds, for every query tile, the contribution of the earlier tiles of
 // its own chunk through the masked score tile  P^T = S Qm^T  (keys x queries) and  O^T += V^T P.
-constexpr int kCausalChunk = 256;
 
 template <class SY, int D>
 struct PrefixLayout {
@@ -472,11 +480,14 @@ CanonMap make_canon_map() {
 // column c (consecutive threads: consecutive floats), written for chunk ch -- before chunk ch's own
 // partial is added -- as the 16 bytes these eight slots occupy in the operand image (consecutive
 // threads of a 32-channel block: consecutive 16-byte pieces).  Padding slots are written as zeros.
+// With a decay factor the chunks' partials arrive weighted as seen from the first token behind
+// their chunk, and the running sum is multiplied by chunk_decay = decay^chunk from one chunk to the
+// next (1 without decay): the state before chunk ch as seen from its first token.
 template <class SY, int D>
 __global__ __launch_bounds__(256) void k_prefix(Geom g, const int32_t* __restrict__ seq_chunk_off,
                                                 const float* __restrict__ partial,
                                                 int64_t partial_stride, unsigned char* __restrict__ pfx,
-                                                CanonMap cm) {
+                                                CanonMap cm, float chunk_decay) {
   using PL = PrefixLayout<SY, D>;
   constexpr int MP = SY::MP, SP = SY::SP, NKS = MP / 16;
   const int s = blockIdx.x, h = blockIdx.y;
@@ -510,7 +521,7 @@ __global__ __launch_bounds__(256) void k_prefix(Geom g, const int32_t* __restric
       u32x4* opA = reinterpret_cast<u32x4*>(pfx + (static_cast<int64_t>(ch + k) * g.H + h) * PL::kBytes);
       opA[(rb * NKS + ks) * 64 + 32 * mg + r] = w;
 #pragma unroll
-      for (int j = 0; j < 8; ++j) acc[j] += ld[k][j];
+      for (int j = 0; j < 8; ++j) acc[j] = __builtin_fmaf(acc[j], chunk_decay, ld[k][j]);
     }
   }
   // the normaliser vector by slot, carried by the threads of channel 0; loads batched like the
@@ -543,7 +554,7 @@ __global__ __launch_bounds__(256) void k_prefix(Geom g, const int32_t* __restric
         *reinterpret_cast<f32x4*>(zslot + mg * SP + 8 * ks) = lo;
         *reinterpret_cast<f32x4*>(zslot + mg * SP + 8 * ks + 4) = hi;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) z[j] += ld[k][j];
+        for (int j = 0; j < 8; ++j) z[j] = __builtin_fmaf(z[j], chunk_decay, ld[k][j]);
       }
     }
   }
@@ -567,7 +578,7 @@ template <class SY, int D>
 __global__ __launch_bounds__(kThreads) void k_query_causal(Geom g, const BlockEnt* __restrict__ chunks,
                                                            const float* __restrict__ feat, View V,
                                                            const unsigned char* __restrict__ pfx, View O,
-                                                           float* __restrict__ den) {
+                                                           float* __restrict__ den, float log2_decay) {
   using SM = CausalSmem<SY, D>;
   using PL = PrefixLayout<SY, D>;
   constexpr int SP = SY::SP, MP = SY::MP, DP = SY::DPHI, F = SY::F;
@@ -670,6 +681,14 @@ __global__ __launch_bounds__(kThreads) void k_query_causal(Geom g, const BlockEn
 #pragma unroll
       for (int ks = 0; ks < NKS; ++ks) acc[rb] = mfma32(opA[(rb * NKS + ks) * 64 + lane], b[ks], acc[rb]);
     }
+    if (log2_decay != 0.0f) {  // the prefix state is as seen from the chunk's first token
+      const float wq = __builtin_amdgcn_exp2f(log2_decay * static_cast<float>(32 * qt + r));
+      eta *= wq;
+#pragma unroll
+      for (int rb = 0; rb < NRB; ++rb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[rb][i] *= wq;
+    }
     // the chunk's own tokens up to the query: key tiles 0 .. qt
 #pragma unroll 1
     for (int kt = 0; kt <= qt; ++kt) {
@@ -678,6 +697,14 @@ __global__ __launch_bounds__(kThreads) void k_query_causal(Geom g, const BlockEn
       for (int i = 0; i < 16; ++i) P[i] = 0.0f;
 #pragma unroll
       for (int ks = 0; ks < NKS; ++ks) P = mfma32(simg[(kt * NKS + ks) * 64 + lane], b[ks], P);
+      if (log2_decay != 0.0f) {  // decay^(query position - key position); masked entries get 0 below
+        const float base = static_cast<float>(32 * (qt - kt) + r);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const float dist = base - static_cast<float>(d_row(i, gl));
+          P[i] *= __builtin_amdgcn_exp2f(log2_decay * fmaxf(dist, 0.0f));
+        }
+      }
       if (kt == qt) {  // key d_row(i, gl) of the tile against query r: later keys are masked
 #pragma unroll
         for (int i = 0; i < 16; ++i)
@@ -1307,7 +1334,7 @@ hla_status forward_core(hla_handle* hd, const hla_call_args& a) {
   if (static_cast<int64_t>(chunks->count) * g.H > hd->max_chunks * hd->cfg.max_heads)
     return HLA_ERR_INVALID_ARG;
   HLA_TRY(launch(hd, "mfma_state", k_state<SY, D>, dim3(chunks->count, g.H), dim3(kThreads),
-                 SM::kTotal, s, g, chunks->dev, hd->feat, a.V, hd->partial, SL::kF32));
+                 SM::kTotal, s, g, chunks->dev, hd->feat, a.V, hd->partial, SL::kF32, 0.0f));
   const SlotMap sm = make_slot_map<SY>();
   unsigned char* ops = static_cast<unsigned char*>(hd->path_ws);
   HLA_TRY(launch(hd, "mfma_state_reduce", k_reduce<SY, D, false>, dim3(a.num_seqs, g.H, kReduceSlices),
@@ -1328,13 +1355,17 @@ hla_status forward_causal(hla_handle* hd, const hla_call_args& a) {
   HLA_TRY(get_table(hd, 2, kCausalChunk, s, &cch));
   if (static_cast<int64_t>(cch->count) * g.H > hd->max_chunks * hd->cfg.max_heads) return HLA_ERR_INVALID_ARG;
   unsigned char* pfx = static_cast<unsigned char*>(hd->path_ws) + hd->causal_off;
+  // decay factor: log2 for the per-token weights, its power over a whole chunk for the scan
+  const float dec = hd->cfg.decay > 0.0f && hd->cfg.decay < 1.0f ? hd->cfg.decay : 1.0f;
+  const float l2d = dec < 1.0f ? std::log2(dec) : 0.0f;
+  const float chunk_decay = dec < 1.0f ? std::pow(dec, static_cast<float>(kCausalChunk)) : 1.0f;
   HLA_TRY(launch(hd, "mfma_state", k_state<SY, D>, dim3(cch->count, g.H), dim3(kThreads), SM::kTotal, s,
-                 g, cch->dev, hd->feat, a.V, hd->partial, SL::kF32));
+                 g, cch->dev, hd->feat, a.V, hd->partial, SL::kF32, l2d));
   static_assert(2 * (SY::MP / 16) * D % 256 == 0, "whole workgroups of prefix items");
   HLA_TRY(launch(hd, "mfma_state_prefix", k_prefix<SY, D>, dim3(a.num_seqs, g.H, 2 * (SY::MP / 16) * D / 256),
-                 dim3(256), 0, s, g, cch->seq_off_dev, hd->partial, SL::kF32, pfx, make_canon_map<SY>()));
+                 dim3(256), 0, s, g, cch->seq_off_dev, hd->partial, SL::kF32, pfx, make_canon_map<SY>(), chunk_decay));
   HLA_TRY(launch(hd, "mfma_query_causal", k_query_causal<SY, D>, dim3(cch->count, g.H), dim3(kThreads),
-                 SC::kTotal, s, g, cch->dev, hd->feat, a.V, pfx, a.O, hd->den));
+                 SC::kTotal, s, g, cch->dev, hd->feat, a.V, pfx, a.O, hd->den, l2d));
   return HLA_OK;
 }
 

@@ -14,13 +14,13 @@ from tests import parity_utils as pu
 pytestmark = pytest.mark.gpu
 
 
-def _causal_gpu(t, F, dphi, phi=None, cu=None):
+def _causal_gpu(t, F, dphi, phi=None, cu=None, decay=1.0):
     dev = torch.device("cuda:0")
     B, H, N, d = t["V"].shape
     nseq = B if cu is None else len(cu) - 1
     h = hla.HLA(head_dim=d, feature_dim=dphi, degree=F, eps=1e-6, io_dtype=hla.HLA_BF16,
                 phi_mode=hla.HLA_PHI_NONE if phi is None else hla.HLA_PHI_MLP, max_heads=H,
-                max_tokens=B * N, max_seqs=max(nseq, 1), causal=True)
+                max_tokens=B * N, max_seqs=max(nseq, 1), causal=True, decay=decay)
     assert h.active_path == hla.HLA_PATH_MFMA
     if phi is not None:
         h.set_phi_weights([{k: v.to(dev) for k, v in m.items()} for m in phi])
@@ -31,10 +31,10 @@ def _causal_gpu(t, F, dphi, phi=None, cu=None):
     return h, O.cpu()
 
 
-def _causal_oracle(t, F, dphi, phi=None, cu=None):
+def _causal_oracle(t, F, dphi, phi=None, cu=None, decay=1.0):
     Q, K, V = (pu.to_np(t[k]) for k in ("Q", "K", "V"))
     return orc.hla_operator_forward(Q, K, V, F, dphi, 1e-6, phi=pu.oracle_phi(phi), cu_seqlens=cu,
-                                    route="bruteforce", causal=True)
+                                    route="bruteforce", causal=True, decay=decay)
 
 
 @pytest.mark.parametrize("F,dphi,d,B,H,N,kind", [
@@ -106,3 +106,44 @@ def test_causal_video_size_sampled_rows():
         worst = max(worst, float(np.abs(g - ref).max() / np.abs(ref).max()))
     print(f"[parity] causal 480p sampled rows: worst rel err {worst:.2e} (tol 0.02)", flush=True)
     assert worst <= 2e-2
+
+
+@pytest.mark.parametrize("F,dphi,d,B,H,N,lam", [
+    (3, 6, 128, 1, 2, 1000, 0.995),   # slow decay: earlier chunks still count
+    (3, 6, 64, 2, 2, 777, 0.9),       # a chunk's worth of distance is gone (0.9^256 = 2e-12)
+    (2, 12, 128, 1, 2, 600, 0.98),
+    (3, 6, 128, 1, 1, 300, 0.3),      # fast decay: almost only the token itself and its neighbours
+    (3, 6, 128, 1, 1, 33, 0.97),
+])
+def test_causal_decay_feature_level_bf16(F, dphi, d, B, H, N, lam):
+    """Decay factors in the causal mask (Sec. 4.4; entries decay^(i-j)) against the oracle's masked
+    matrix."""
+    t = wl.make_feature_inputs(1300 + N, B, H, N, d, F, dphi, torch.bfloat16, kind="halfnormal")
+    h, got = _causal_gpu(t, F, dphi, decay=lam)
+    h.destroy()
+    ref = _causal_oracle(t, F, dphi, decay=lam)
+    pu.assert_parity({"O": got}, {"O": ref}, 2e-2, f"causal decay {lam} F={F} d={d} N={N}")
+    nodecay = _causal_oracle(t, F, dphi)
+    assert np.abs(ref - nodecay).max() > 1e-2 * np.abs(nodecay).max()  # the factor does something
+
+
+def test_causal_decay_packed_through_the_maps_and_argument_checks():
+    cu = [0, 300, 300, 1324, 1325, 2600]
+    t, phi = wl.make_raw_inputs(1310, 1, 2, cu[-1], 128, 3, 6, torch.bfloat16)
+    h, got = _causal_gpu(t, 3, 6, phi=phi, cu=cu, decay=0.99)
+    h.destroy()
+    ref = _causal_oracle(t, 3, 6, phi=phi, cu=cu, decay=0.99)
+    pu.assert_parity({"O": got}, {"O": ref}, 2e-2, "causal decay packed through the maps")
+    # decay 0 and 1 both mean none: bit-identical outputs
+    t2 = wl.make_feature_inputs(1311, 1, 1, 500, 64, 3, 6, torch.bfloat16)
+    outs = []
+    for lam in (0.0, 1.0):
+        h, o = _causal_gpu(t2, 3, 6, decay=lam)
+        h.destroy()
+        outs.append(o)
+    assert torch.equal(outs[0], outs[1])
+    for kw in (dict(causal=True, decay=1.5), dict(causal=True, decay=-0.1), dict(causal=False, decay=0.5)):
+        with pytest.raises(hla.HLAError) as e:
+            hla.HLA(head_dim=128, feature_dim=6, degree=3, io_dtype=hla.HLA_BF16, phi_mode=hla.HLA_PHI_NONE,
+                    max_heads=1, max_tokens=8, max_seqs=1, **kw)
+        assert e.value.code == 1
