@@ -339,6 +339,85 @@ def hla_backward_bruteforce(qf, kfs, v, do, eps: float):
     return dqf, dkfs, dv
 
 
+def hla_causal_backward_bruteforce(qf, kfs, v, do, eps: float, decay: float = 1.0):
+    """Gradients of L = sum(O * dO) for the causal variant through the masked N x N matrix: with
+    M_ij = decay^(i-j) for j <= i (0 otherwise) and A = M * prod_f P^f, the steps of
+    hla_backward_bruteforce apply with every product carrying the mask:
+    dP^f = (<g_i, v_j> + s_i) * M * prod_{f' != f} P^f'.  Returns (dqf, [dkf_f], dv)."""
+    qf = np.asarray(qf, F64)
+    kfs = [np.asarray(k, F64) for k in kfs]
+    v = np.asarray(v, F64)
+    do = np.asarray(do, F64)
+    n = v.shape[0]
+    dist = np.arange(n)[:, None] - np.arange(n)[None, :]
+    M = np.where(dist >= 0, float(decay) ** np.maximum(dist, 0), 0.0)
+    P = [qf @ k.T for k in kfs]
+    A = M.copy()
+    for Pf in P:
+        A = A * Pf
+    eta = A.sum(axis=1)
+    den = eta + eps
+    o = (A @ v) / den[:, None]
+    g = do / den[:, None]
+    s = -(do * o).sum(axis=1) / den
+    dA = (g @ v.T + s[:, None]) * M
+    dqf = np.zeros_like(qf)
+    dkfs = []
+    for f in range(len(kfs)):
+        others = np.ones_like(A)
+        for f2 in range(len(kfs)):
+            if f2 != f:
+                others = others * P[f2]
+        dP = dA * others
+        dqf += dP @ kfs[f]
+        dkfs.append(dP.T @ qf)
+    return dqf, dkfs, A.T @ g
+
+
+def hla_causal_backward_sequential(qf, kfs, v, do, eps: float, decay: float = 1.0):
+    """The same gradients through the state recursions (independent route): forward in time the
+    states C^i, z^i of hla_causal_sequential give o_i and dT_q,i = C^i g_i + s_i z^i; backward in
+    time the gradient states dC^j = decay dC^{j+1} + T_q,j (x) g_j and dz^j = decay dz^{j+1} +
+    s_j T_q,j give dT_k,j = dC^j v_j + dz^j and dv_j = (dC^j)^T T_k,j.  Python loops: small inputs."""
+    qf = np.asarray(qf, F64)
+    kfs = [np.asarray(k, F64) for k in kfs]
+    v = np.asarray(v, F64)
+    do = np.asarray(do, F64)
+    F = len(kfs)
+    n, dp = qf.shape
+    Tq = outer_features([qf] * F)
+    Tk = outer_features(kfs)
+    D = Tq.shape[1]
+    C = np.zeros((D, v.shape[1]), F64)
+    z = np.zeros(D, F64)
+    g = np.zeros_like(v)
+    s = np.zeros(n, F64)
+    dTq = np.zeros((n, D), F64)
+    for i in range(n):
+        C = decay * C + np.outer(Tk[i], v[i])
+        z = decay * z + Tk[i]
+        den = Tq[i] @ z + eps
+        o = (Tq[i] @ C) / den
+        g[i] = do[i] / den
+        s[i] = -(do[i] @ o) / den
+        dTq[i] = C @ g[i] + s[i] * z
+    dC = np.zeros((D, v.shape[1]), F64)
+    dz = np.zeros(D, F64)
+    dTk = np.zeros((n, D), F64)
+    dv = np.zeros_like(v)
+    for j in range(n - 1, -1, -1):
+        dC = decay * dC + np.outer(Tq[j], g[j])
+        dz = decay * dz + s[j] * Tq[j]
+        dTk[j] = dC @ v[j] + dz
+        dv[j] = Tk[j] @ dC
+    shape = (n,) + (dp,) * F
+    dqf = np.zeros_like(qf)
+    for slot in range(F):
+        dqf += _slot_gradient(dTq.reshape(shape), [qf] * F, slot)
+    dkfs = [_slot_gradient(dTk.reshape(shape), kfs, slot) for slot in range(F)]
+    return dqf, dkfs, dv
+
+
 # --------------------------------------------------------------------------------------------
 # Value modulation (Sec. 4.5): T <- T + phi_v1(T) * phi_v2(V), elementwise product
 # --------------------------------------------------------------------------------------------
@@ -509,7 +588,8 @@ def hla_operator_backward(Q, K, V, dO, F: int, d_phi: int, eps: float,
                           phi: Optional[Sequence[PhiWeights]] = None,
                           cu_seqlens: Optional[Sequence[int]] = None,
                           route: str = "factorized", weight_grads: bool = False,
-                          feature_grads: bool = False, vmod=None, vmod_weight_grads: bool = False):
+                          feature_grads: bool = False, vmod=None, vmod_weight_grads: bool = False,
+                          causal: bool = False, decay: float = 1.0):
     """(dQ, dK, dV) with the shapes of Q, K, V for L = sum(O * dO).  With feature maps, dK sums
     the contributions of the F key maps (they all read the same K).  With weight_grads (needs
     `phi`) a fourth result lists (dW1, db1, dW2, db2) for phi_q, phi_k1..phi_kF, each summed over
@@ -519,7 +599,11 @@ def hla_operator_backward(Q, K, V, dO, F: int, d_phi: int, eps: float,
     is then the gradient w.r.t. the modulated output; it is first taken back through the
     modulation (to the attention output T and to V), T's share then goes through the operator.
     With vmod_weight_grads (needs `vmod`) the last result lists (dW1, db1, dW2, db2, dgamma,
-    dbeta) for phi_v1 and phi_v2, summed over every sequence, head and token."""
+    dbeta) for phi_v1 and phi_v2, summed over every sequence, head and token.
+    causal / decay: the masked variant of Sec. 4.4 (route 'bruteforce' = masked matrix,
+    'factorized' = the state recursions); not combined with vmod here."""
+    if causal and vmod is not None:
+        raise ValueError("the causal backward is not combined with the value modulation")
     B, H, N = V.shape[:3]
     dQ = np.zeros(Q.shape, F64)
     dK = np.zeros(K.shape, F64)
@@ -537,6 +621,9 @@ def hla_operator_backward(Q, K, V, dO, F: int, d_phi: int, eps: float,
             raise ValueError("the modulation's weight gradients need the modulation")
         vwg = [[np.zeros_like(a) for a in m.astuple()] for m in vmod[:2]]
     bwd = hla_backward_factorized if route == "factorized" else hla_backward_bruteforce
+    if causal:
+        cb = hla_causal_backward_sequential if route == "factorized" else hla_causal_backward_bruteforce
+        bwd = lambda qf, kfs, v, do, eps: cb(qf, kfs, v, do, eps, decay=decay)
     for (b, lo, hi) in _units(B, N, cu_seqlens):
         if hi == lo:
             continue

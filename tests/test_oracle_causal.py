@@ -150,3 +150,71 @@ def test_operator_level_decay_restarts_with_every_sequence():
                 ref = orc.hla_causal_bruteforce(Q[0, h, lo:hi], [K[0, h, lo:hi, f * dp:(f + 1) * dp] for f in range(F)],
                                                 V[0, h, lo:hi], 1e-6, decay=lam)
                 np.testing.assert_allclose(O[0, h, lo:hi], ref, rtol=1e-11, atol=1e-13)
+
+
+# ---- backward of the causal variant -------------------------------------------------------------
+def _fd(fun, x, h=1e-6):
+    g = np.zeros_like(x)
+    it = np.nditer(x, flags=["multi_index"])
+    for _ in it:
+        i = it.multi_index
+        old = x[i]
+        x[i] = old + h
+        fp = fun()
+        x[i] = old - h
+        fm = fun()
+        x[i] = old
+        g[i] = (fp - fm) / (2 * h)
+    return g
+
+
+@pytest.mark.parametrize("F,dp,lam", [(2, 3, 1.0), (3, 3, 0.8), (3, 2, 1.0), (1, 4, 0.6)])
+def test_causal_backward_routes_against_finite_differences(F, dp, lam):
+    """Both routes against central differences of the forward (masked matrix), and against each
+    other; the forward they differentiate is pinned above."""
+    q, ks, v = _inputs(100 + F, 9, dp, 4, F)
+    do = np.random.default_rng(101).standard_normal(v.shape)
+    eps = 1e-3
+    f = lambda: float((orc.hla_causal_bruteforce(q, ks, v, eps, decay=lam) * do).sum())
+    a = orc.hla_causal_backward_bruteforce(q, ks, v, do, eps, decay=lam)
+    b = orc.hla_causal_backward_sequential(q, ks, v, do, eps, decay=lam)
+    np.testing.assert_allclose(a[0], _fd(f, q), rtol=2e-6, atol=1e-8)
+    np.testing.assert_allclose(a[2], _fd(f, v), rtol=2e-6, atol=1e-8)
+    for fk in range(F):
+        np.testing.assert_allclose(a[1][fk], _fd(f, ks[fk]), rtol=2e-6, atol=1e-8)
+        np.testing.assert_allclose(a[1][fk], b[1][fk], rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(a[0], b[0], rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(a[2], b[2], rtol=1e-10, atol=1e-12)
+
+
+def test_causal_backward_known_rows():
+    """The last token is seen by itself only: its key-side gradients come from query N-1 alone;
+    the first query sees itself only, so dq_0 depends on token 0 alone (eps = 0: o_0 = v_0 exactly
+    and every gradient through row 0 vanishes)."""
+    q, ks, v = _inputs(105, 7, 3, 4, 2)
+    do = np.random.default_rng(106).standard_normal(v.shape)
+    dq, dks, dv = orc.hla_causal_backward_bruteforce(q, ks, v, do, 0.0, decay=0.9)
+    np.testing.assert_allclose(dq[0], 0.0, atol=1e-12)
+    # dv of the last token: A_{N-1,N-1} / eta_{N-1} * dO_{N-1}
+    a_last = np.prod([q[-1] @ k[-1] for k in ks])
+    eta_last = sum(0.9 ** (6 - j) * np.prod([q[-1] @ k[j] for k in ks]) for j in range(7))
+    np.testing.assert_allclose(dv[-1], a_last / eta_last * do[-1], rtol=1e-12)
+
+
+def test_operator_level_causal_backward_with_maps_and_packing():
+    rng = np.random.default_rng(107)
+    H, N, d, F, dp = 2, 8, 4, 2, 3
+    cu = [0, 3, 8]
+    Q, K, V, dO = (rng.standard_normal((1, H, N, d)) for _ in range(4))
+    phi = [orc.PhiWeights(rng.standard_normal((d, d)), 0.3 * rng.standard_normal(d),
+                          rng.standard_normal((d, dp)), rng.standard_normal(dp) + 1.5)
+           for _ in range(1 + F)]
+    eps, lam = 1e-4, 0.85
+    f = lambda: float((orc.hla_operator_forward(Q, K, V, F, dp, eps, phi=phi, cu_seqlens=cu, route="bruteforce",
+                                                causal=True, decay=lam) * dO).sum())
+    for route in ("factorized", "bruteforce"):
+        dQ, dK, dV = orc.hla_operator_backward(Q, K, V, dO, F, dp, eps, phi=phi, cu_seqlens=cu, route=route,
+                                               causal=True, decay=lam)
+        np.testing.assert_allclose(dQ, _fd(f, Q), rtol=5e-6, atol=5e-8)
+        np.testing.assert_allclose(dK, _fd(f, K), rtol=5e-6, atol=5e-8)
+        np.testing.assert_allclose(dV, _fd(f, V), rtol=5e-6, atol=5e-8)
