@@ -42,7 +42,7 @@ def parse():
     ap.add_argument("--value-modulation", action="store_true",
                     help="switch on the value modulation of Sec. 4.5 (a different workload: named in config)")
     ap.add_argument("--causal", action="store_true",
-                    help="the causal variant of Sec. 4.4, forward only (a different workload: named in config)")
+                    help="the causal variant of Sec. 4.4 (a different workload: named in config)")
     ap.add_argument("--decay", type=float, default=1.0,
                     help="with --causal: decay factor of the mask (Sec. 4.4), 1 = none")
     return ap.parse_args()
@@ -112,7 +112,7 @@ def main():
     hla.load_library()
     dev = torch.device("cuda:0")
     w = wl.make_workload(args.config)
-    backward = w.backward and not args.causal
+    backward = w.backward
     phi = w.phi
     if args.features:
         ft = wl.make_feature_inputs(w.seed, w.B, w.H, w.N, w.d, w.F, w.d_phi, w.dtype)

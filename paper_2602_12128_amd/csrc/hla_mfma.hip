@@ -127,11 +127,18 @@ struct StateSmem {
 // grid (chunks, H), block 256.  Each wave streams 64-token sub-tiles w, w+4, .. of the chunk
 // through its private LDS region; the four waves' accumulators are summed in wave order at the
 // end and written as one partial state.
-template <class SY, int D>
+// MODE 1 (backward of the causal variant): the same contraction for the gradient state of a chunk,
+//   sum_i w_i (Qm_i / den_i) (x) dO_i   and   sum_i w_i (s_i den_i) (Qm_i / den_i),
+// with the QUERY monomials of the tokens, V = the dO rows, den / sv the saved denominators and
+// the s_i of the query-side kernel, w_i = decay^(i - t0 + 1) (the chunk as seen from the token in
+// front of it).
+template <class SY, int D, int MODE = 0>
 __global__ __launch_bounds__(kThreads) void k_state(Geom g, const BlockEnt* __restrict__ chunks,
                                                     const float* __restrict__ feat, View V,
                                                     float* __restrict__ partial,
-                                                    int64_t partial_stride, float log2_decay) {
+                                                    int64_t partial_stride, float log2_decay,
+                                                    const float* __restrict__ den = nullptr,
+                                                    const float* __restrict__ sv = nullptr) {
   constexpr int DP = SY::DPHI, F = SY::F, MP = SY::MP;
   using SM = StateSmem<D, MP>;
   constexpr int NCB = D / 32;      // column blocks of the state
@@ -158,25 +165,35 @@ __global__ __launch_bounds__(kThreads) void k_state(Geom g, const BlockEnt* __re
   }
   u32x4 ones;
   ones[0] = ones[1] = ones[2] = ones[3] = 0x3f803f80u;  // bf16 1.0 pairs
+  u32x4 tws[MODE == 1 ? 4 : 1];  // MODE 1: per-token z weights in place of the ones
 
   // the next sub-tile's V rows and key features are fetched while the current one is consumed
   TileRegs<D, 64> vt;
+  constexpr int NFV = MODE == 0 ? F * DP : DP;  // feature values a token needs
   float kf[F * DP];
+  float dnf = 1.0f, svf = 0.0f;  // MODE 1: the token's denominator and s
   auto fetch = [&](int n0) {
     fetch_tile<D, 64>(V, e.b, h, n0, e.t1, lane, vt);
     const int n = n0 + lane;
     if (n < e.t1) {
       // pair p of the tile's 32 tokens is one 256-byte run: an 8-byte load per lane and pair
-      const f32x2* f = reinterpret_cast<const f32x2*>(feat + g.fidx(g.th(e.b, h, n), DP));
+      const int64_t th = g.th(e.b, h, n);
+      const f32x2* f = reinterpret_cast<const f32x2*>(feat + g.fidx(th, MODE == 0 ? DP : 0));
 #pragma unroll
-      for (int p = 0; p < F * DP / 2; ++p) {
+      for (int p = 0; p < NFV / 2; ++p) {
         const f32x2 v = f[32 * p];
         kf[2 * p] = v[0];
         kf[2 * p + 1] = v[1];
       }
+      if constexpr (MODE == 1) {
+        dnf = den[th];
+        svf = sv[th];
+      }
     } else {
 #pragma unroll
-      for (int a = 0; a < F * DP; ++a) kf[a] = 0.0f;
+      for (int a = 0; a < NFV; ++a) kf[a] = 0.0f;
+      dnf = 1.0f;
+      svf = 0.0f;
     }
   };
   if (e.t0 + wave * 64 < e.t1) fetch(e.t0 + wave * 64);
@@ -186,20 +203,39 @@ __global__ __launch_bounds__(kThreads) void k_state(Geom g, const BlockEnt* __re
     {
       float kk[F][DP];
 #pragma unroll
-      for (int f = 0; f < F; ++f)
+      for (int f = 0; f < (MODE == 0 ? F : 1); ++f)
 #pragma unroll
         for (int a = 0; a < DP; ++a) kk[f][a] = kf[f * DP + a];
-      if (log2_decay != 0.0f) {
-        // causal scan with a decay factor: the chunk's state is taken as seen from the first token
-        // behind the chunk, token n weighs decay^(t0 + chunk - n); the key tensor is linear in
-        // each factor, so the weight goes on the first one
-        const float wgt = __builtin_amdgcn_exp2f(log2_decay * static_cast<float>(e.t0 + kCausalChunk - (n0 + lane)));
+      float scale1 = 1.0f, tw = 0.0f;  // MODE 1: weight of the token's monomials, its z weight
+      if constexpr (MODE == 0) {
+        if (log2_decay != 0.0f) {
+          // causal scan with a decay factor: the chunk's state is taken as seen from the first token
+          // behind the chunk, token n weighs decay^(t0 + chunk - n); the key tensor is linear in
+          // each factor, so the weight goes on the first one
+          const float wgt = __builtin_amdgcn_exp2f(log2_decay * static_cast<float>(e.t0 + kCausalChunk - (n0 + lane)));
 #pragma unroll
-        for (int a = 0; a < DP; ++a) kk[0][a] *= wgt;
+          for (int a = 0; a < DP; ++a) kk[0][a] *= wgt;
+        }
+      } else {
+        scale1 = 1.0f / dnf;
+        if (log2_decay != 0.0f) scale1 *= __builtin_amdgcn_exp2f(log2_decay * static_cast<float>(n0 + lane - e.t0 + 1));
+        tw = svf * dnf;
       }
       if (n0 + kWaves * 64 < e.t1) fetch(n0 + kWaves * 64);
       float sm[SY::NM];
-      sym_key_monomials_all<SY>(kk, sm);
+      if constexpr (MODE == 0) {
+        sym_key_monomials_all<SY>(kk, sm);
+      } else {
+        sym_query_monomials_all<SY>(kk[0], sm);
+#pragma unroll
+        for (int m = 0; m < SY::NM; ++m) sm[m] *= scale1;
+        // the z weights of the sub-tile's tokens as B operands: k-slot (ks, gq, j) is token 16 ks + 8 gq + j
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+          for (int p = 0; p < 4; ++p)
+            tws[ks][p] = pack_bf16(__shfl(tw, 16 * ks + 8 * gq + 2 * p, 64), __shfl(tw, 16 * ks + 8 * gq + 2 * p + 1, 64));
+      }
       uint32_t packed[MP / 2];
 #pragma unroll
       for (int p = 0; p < MP / 2; ++p) {
@@ -247,7 +283,7 @@ __global__ __launch_bounds__(kThreads) void k_state(Geom g, const BlockEnt* __re
         for (int rb = 0; rb < NRM; ++rb) acc[rb][cb] = mfma32(a[rb], b, acc[rb][cb]);
       }
 #pragma unroll
-      for (int rb = 0; rb < NRM; ++rb) zacc[rb] = mfma32(a[rb], ones, zacc[rb]);
+      for (int rb = 0; rb < NRM; ++rb) zacc[rb] = mfma32(a[rb], MODE == 1 ? tws[ks] : ones, zacc[rb]);
     }
     wave_lds_sync();
   }
@@ -483,15 +519,19 @@ CanonMap make_canon_map() {
 // With a decay factor the chunks' partials arrive weighted as seen from the first token behind
 // their chunk, and the running sum is multiplied by chunk_decay = decay^chunk from one chunk to the
 // next (1 without decay): the state before chunk ch as seen from its first token.
-template <class SY, int D>
+// REVERSE: the running sum goes from the sequence's last chunk to its first, and chunk ch receives
+// the sum over the chunks behind it (the gradient states of the backward).  Images are written
+// `stride` bytes apart, the normaliser vector z_off bytes into an image.
+template <class SY, int D, bool REVERSE>
 __global__ __launch_bounds__(256) void k_prefix(Geom g, const int32_t* __restrict__ seq_chunk_off,
                                                 const float* __restrict__ partial,
                                                 int64_t partial_stride, unsigned char* __restrict__ pfx,
-                                                CanonMap cm, float chunk_decay) {
-  using PL = PrefixLayout<SY, D>;
+                                                CanonMap cm, float chunk_decay, int64_t stride,
+                                                int64_t z_off) {
   constexpr int MP = SY::MP, SP = SY::SP, NKS = MP / 16;
   const int s = blockIdx.x, h = blockIdx.y;
-  const int c0 = seq_chunk_off[s], c1 = seq_chunk_off[s + 1];
+  const int c0 = seq_chunk_off[s], c1 = seq_chunk_off[s + 1], nc = c1 - c0;
+  auto chunk_at = [&](int pos) { return REVERSE ? c1 - 1 - pos : c0 + pos; };  // pos-th chunk in scan order
   const int item = blockIdx.z * 256 + threadIdx.x;  // (mg, ks, c)
   const int c = item % D, ks = (item / D) % NKS, mg = item / (D * NKS);
   const float* base = partial + static_cast<int64_t>(h) * partial_stride + c;
@@ -504,21 +544,21 @@ __global__ __launch_bounds__(256) void k_prefix(Geom g, const int32_t* __restric
   for (int j = 0; j < 8; ++j) acc[j] = 0.0f;
   const int rb = c / 32, r = c % 32;
   constexpr int NB = 8;  // chunks in flight
-  for (int ch = c0; ch < c1; ch += NB) {
+  for (int pos = 0; pos < nc; pos += NB) {
     float ld[NB][8];
 #pragma unroll
     for (int k = 0; k < NB; ++k) {
-      const float* p = base + (ch + k < c1 ? ch + k : c1 - 1) * cstride;
+      const float* p = base + chunk_at(pos + k < nc ? pos + k : nc - 1) * cstride;
 #pragma unroll
       for (int j = 0; j < 8; ++j) ld[k][j] = row[j] >= 0 ? p[row[j] * D] : 0.0f;
     }
 #pragma unroll
     for (int k = 0; k < NB; ++k) {
-      if (ch + k >= c1) break;
+      if (pos + k >= nc) break;
       u32x4 w;
 #pragma unroll
       for (int p = 0; p < 4; ++p) w[p] = pack_bf16(acc[2 * p], acc[2 * p + 1]);
-      u32x4* opA = reinterpret_cast<u32x4*>(pfx + (static_cast<int64_t>(ch + k) * g.H + h) * PL::kBytes);
+      u32x4* opA = reinterpret_cast<u32x4*>(pfx + (static_cast<int64_t>(chunk_at(pos + k)) * g.H + h) * stride);
       opA[(rb * NKS + ks) * 64 + 32 * mg + r] = w;
 #pragma unroll
       for (int j = 0; j < 8; ++j) acc[j] = __builtin_fmaf(acc[j], chunk_decay, ld[k][j]);
@@ -533,18 +573,18 @@ __global__ __launch_bounds__(256) void k_prefix(Geom g, const int32_t* __restric
     for (int j = 0; j < 8; ++j) z[j] = 0.0f;
     const float* zb = partial + static_cast<int64_t>(h) * partial_stride + MP * D;
     constexpr int NZ = 16;
-    for (int ch = c0; ch < c1; ch += NZ) {
+    for (int pos = 0; pos < nc; pos += NZ) {
       float ld[NZ][8];
 #pragma unroll
       for (int k = 0; k < NZ; ++k) {
-        const float* p = zb + (ch + k < c1 ? ch + k : c1 - 1) * cstride;
+        const float* p = zb + chunk_at(pos + k < nc ? pos + k : nc - 1) * cstride;
 #pragma unroll
         for (int j = 0; j < 8; ++j) ld[k][j] = row[j] >= 0 ? p[row[j]] : 0.0f;
       }
 #pragma unroll
       for (int k = 0; k < NZ; ++k) {
-        if (ch + k >= c1) break;
-        float* zslot = reinterpret_cast<float*>(pfx + (static_cast<int64_t>(ch + k) * g.H + h) * PL::kBytes + PL::kOpElems * 2);
+        if (pos + k >= nc) break;
+        float* zslot = reinterpret_cast<float*>(pfx + (static_cast<int64_t>(chunk_at(pos + k)) * g.H + h) * stride + z_off);
         f32x4 lo, hi;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -555,6 +595,56 @@ __global__ __launch_bounds__(256) void k_prefix(Geom g, const int32_t* __restric
         *reinterpret_cast<f32x4*>(zslot + mg * SP + 8 * ks + 4) = hi;
 #pragma unroll
         for (int j = 0; j < 8; ++j) z[j] = __builtin_fmaf(z[j], chunk_decay, ld[k][j]);
+      }
+    }
+  }
+}
+
+// The same scan emitting the image whose rows are monomials (the A operand of products that
+// contract over the channels, used by the backward): image row rho = 32 rbm + r is slot
+// (g, s) = ((rho >> 2) & 1, 16 (rho >> 5) + 4 ((rho >> 3) & 3) + (rho & 3)), so that accumulator
+// register i of row block rbm on lane half gl is the lane's own slot 16 rbm + i.
+// grid (num_seqs, H, (MP / 32) * (D / 16) * 64 / 256), block 256; a thread owns eight consecutive
+// channels of one row; the image starts `img_off` bytes into a chunk's block.
+template <class SY, int D, bool REVERSE>
+__global__ __launch_bounds__(256) void k_prefix_rows(Geom g, const int32_t* __restrict__ seq_chunk_off,
+                                                     const float* __restrict__ partial,
+                                                     int64_t partial_stride, unsigned char* __restrict__ pfx,
+                                                     CanonMap cm, float chunk_decay, int64_t stride,
+                                                     int64_t img_off) {
+  constexpr int NKD = D / 16;
+  const int s = blockIdx.x, h = blockIdx.y;
+  const int c0 = seq_chunk_off[s], c1 = seq_chunk_off[s + 1], nc = c1 - c0;
+  auto chunk_at = [&](int pos) { return REVERSE ? c1 - 1 - pos : c0 + pos; };
+  const int item = blockIdx.z * 256 + threadIdx.x;  // (rbm, kd, lane)
+  const int lane = item % 64, kd = (item / 64) % NKD, rbm = item / (64 * NKD);
+  const int rho = 32 * rbm + lane % 32, gl = lane / 32;
+  const int m = cm.m[(rho >> 2) & 1][16 * (rho >> 5) + 4 * ((rho >> 3) & 3) + (rho & 3)];
+  const float* base = partial + static_cast<int64_t>(h) * partial_stride + (m >= 0 ? m : 0) * D + 16 * kd + 8 * gl;
+  const int64_t cstride = static_cast<int64_t>(g.H) * partial_stride;
+  float acc[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) acc[j] = 0.0f;
+  constexpr int NB = 8;
+  for (int pos = 0; pos < nc; pos += NB) {
+    f32x4 ld[NB][2];
+#pragma unroll
+    for (int k = 0; k < NB; ++k) {
+      const f32x4* p = reinterpret_cast<const f32x4*>(base + chunk_at(pos + k < nc ? pos + k : nc - 1) * cstride);
+      ld[k][0] = p[0];
+      ld[k][1] = p[1];
+    }
+#pragma unroll
+    for (int k = 0; k < NB; ++k) {
+      if (pos + k >= nc) break;
+      u32x4 w;
+#pragma unroll
+      for (int p = 0; p < 4; ++p) w[p] = pack_bf16(acc[2 * p], acc[2 * p + 1]);
+      u32x4* img = reinterpret_cast<u32x4*>(pfx + (static_cast<int64_t>(chunk_at(pos + k)) * g.H + h) * stride + img_off);
+      img[(rbm * NKD + kd) * 64 + lane] = w;
+      if (m >= 0) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] = __builtin_fmaf(acc[j], chunk_decay, ld[k][j / 4][j % 4]);
       }
     }
   }
@@ -1298,6 +1388,530 @@ hla_status allow_big_lds(K kernel, int bytes) {
              : HLA_ERR_HIP;
 }
 
+// ---- backward of the causal variant -----------------------------------------------------------------
+// With w_ij = decay^(i-j) for j <= i, den_i = eta_i + eps, Qm'_i = Qm_i / den_i, t_i = s_i den_i:
+//   query side  X_i = sum_{j<=i} w_ij <dO_i, v_j> S_j,   Z_i = sum_{j<=i} w_ij S_j,
+//               s_i = -<Qm_i, X_i> / den_i^2,            dQm_i = X_i / den_i + s_i Z_i
+//   key side    dS_j = sum_{i>=j} w_ij (<dO_i, v_j> + t_i) Qm'_i,
+//               dv_j = sum_{i>=j} w_ij <Qm'_i, S_j> dO_i
+// Each sum splits into the other chunks (a state: the prefix of sum S (x) v for the queries, the
+// suffix of sum w Qm' (x) dO for the keys, from the scans above as per-chunk operand images) and the
+// tokens of the own chunk, which go through 32 x 32 tiles E = (other rows) (own rows)^T masked and
+// weighted entry by entry, as in k_query_causal.  The two kernels below are mirror images: a
+// workgroup stages the rows and the monomials of the chunk's OTHER side in LDS, then each wave
+// serves two tiles of the OWN side, a token per MFMA column.
+// The monomial tile is [token][MP] bf16 with its columns in the row order rho of the operand images
+// (see k_prefix_rows), so that the accumulators of  X^T += M^T (W * E)  hold a lane's own slots.
+template <class SY, int D>
+struct CgSmem {
+  static constexpr int kTiles = kCausalChunk / 32;
+  static constexpr int kRStride = D * 2 + 32;          // bytes per token row of the row tile
+  static constexpr int kMStride = SY::MP * 2 + 32;     // bytes per token row of the monomial tile
+  static constexpr int kRBytes = kCausalChunk * kRStride;
+  static constexpr int kMBytes = kCausalChunk * kMStride;
+  static constexpr int kTBytes = kCausalChunk * 4;     // t_i of the chunk's queries (key side)
+  static constexpr int kTotalQ = kRBytes + kMBytes;
+  static constexpr int kTotalK = kRBytes + kMBytes + kTBytes + kWaves * RowTile<D, 16>::kBytes;
+};
+
+// column (in elements) of slot (g, s) in the monomial tile
+__device__ __forceinline__ int rho_of(int g, int s) { return 32 * (s / 16) + 8 * ((s % 16) / 4) + 4 * g + s % 4; }
+
+// this lane's SP monomials -> row `row` of the monomial tile (groups of four slots are four
+// consecutive columns)
+template <class SY>
+__device__ __forceinline__ void put_monomials(unsigned char* mt, int stride, int row, int gl,
+                                              const float (&m)[SY::SP], float scale) {
+#pragma unroll
+  for (int q4 = 0; q4 < SY::SP / 4; ++q4) {
+    u32x2 w;
+    w[0] = pack_bf16(m[4 * q4] * scale, m[4 * q4 + 1] * scale);
+    w[1] = pack_bf16(m[4 * q4 + 2] * scale, m[4 * q4 + 3] * scale);
+    *reinterpret_cast<u32x2*>(mt + row * stride + rho_of(gl, 4 * q4) * 2) = w;
+  }
+}
+
+// E[other token d_row(i, gl) of tile u][own token r] = <row_other, row_own>: A = plain 16-byte reads
+// of the row tile, B = the own rows in operand order
+template <int D>
+__device__ __forceinline__ f32x16 rows_product(const unsigned char* rt, int stride, int u, int lane,
+                                               const u32x4 (&bown)[D / 16]) {
+  const int r = lane % 32, gl = lane / 32;
+  f32x16 E;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) E[i] = 0.0f;
+#pragma unroll
+  for (int kd = 0; kd < D / 16; ++kd)
+    E = mfma32(*reinterpret_cast<const u32x4*>(rt + (32 * u + r) * stride + (16 * kd + 8 * gl) * 2), bown[kd], E);
+  return E;
+}
+
+// acc[blk]^T[32 blk + .. x own] += tile(u)^T B for the NB 32-column blocks of a [token][columns]
+// tile: k-slot (ks2, gl, j) of B is token 16 ks2 + 8 (j / 4) + 4 gl + j % 4 of tile u, the order
+// in which a product's accumulators hold its rows
+template <int NB>
+__device__ __forceinline__ void transposed_product(const unsigned char* tile, int stride, int u, int lane,
+                                                   const u32x4 (&b)[2], f32x16 (&acc)[NB]) {
+  const int gl = lane / 32, L = lane % 16, q = lane / 16;
+#pragma unroll
+  for (int ks2 = 0; ks2 < 2; ++ks2) {
+    const int krow = 32 * u + 16 * ks2 + 4 * gl + L / 4;
+#pragma unroll
+    for (int blk = 0; blk < NB; ++blk) {
+      const unsigned char* p = tile + krow * stride + (32 * blk + 16 * (q % 2) + 4 * (L % 4)) * 2;
+      const u32x2 lo = lds_read_tr16(p);
+      const u32x2 hi = lds_read_tr16(p + 8 * stride);
+      u32x4 a;
+      a[0] = lo[0];
+      a[1] = lo[1];
+      a[2] = hi[0];
+      a[3] = hi[1];
+      acc[blk] = mfma32(a, b[ks2], acc[blk]);
+    }
+  }
+}
+
+// grid (chunks of kCausalChunk tokens, H), block 256.  Query side: writes the query part of the
+// feature gradients and s_i (sv) for the key side.  ops: per (chunk, head) the images of the
+// state in front of the chunk (StateLayout: opA, opB, z by slot).
+template <class SY, int D>
+__global__ __launch_bounds__(kThreads) void k_cgrad_q(Geom g, const BlockEnt* __restrict__ chunks,
+                                                      const float* __restrict__ feat,
+                                                      const float* __restrict__ den, View V, View dO,
+                                                      const unsigned char* __restrict__ ops,
+                                                      float* __restrict__ dfeat, float* __restrict__ sv,
+                                                      float log2_decay, int relu_mask) {
+  using SM = CgSmem<SY, D>;
+  using SL = StateLayout<SY, D>;
+  constexpr int SP = SY::SP, MP = SY::MP, DP = SY::DPHI, F = SY::F;
+  constexpr int NKD = D / 16, NRM = MP / 32, NF = F * DP;
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int lane = threadIdx.x % kWave, wave = wave_index();
+  unsigned char* rt = smem;
+  unsigned char* mt = smem + SM::kRBytes;
+  const int r = lane % 32, gl = lane / 32;
+  const BlockEnt e = chunks[blockIdx.x];
+  const int h = blockIdx.y;
+  // ---- the chunk's V rows (64 per wave) and key monomials (two tiles per wave)
+  {
+    TileRegs<D, 64> vt;
+    fetch_tile<D, 64>(V, e.b, h, e.t0 + 64 * wave, e.t1, lane, vt);
+    put_tile<D, 64>(vt, lane, rt + 64 * wave * SM::kRStride, SM::kRStride);
+  }
+#pragma unroll 1
+  for (int tt = 0; tt < 2; ++tt) {
+    const int t = 2 * wave + tt;
+    const int n = e.t0 + 32 * t + r;
+    float kf[NF], kr[NF];
+    if (n < e.t1) {
+      const f32x2* f = reinterpret_cast<const f32x2*>(feat + g.fidx(g.th(e.b, h, n), DP));
+#pragma unroll
+      for (int p = 0; p < NF / 2; ++p) {
+        const f32x2 v = f[32 * p];
+        kf[2 * p] = v[0];
+        kf[2 * p + 1] = v[1];
+      }
+    } else {
+#pragma unroll
+      for (int a = 0; a < NF; ++a) kf[a] = 0.0f;
+    }
+    float kk[F][DP];
+#pragma unroll
+    for (int f = 0; f < F; ++f)
+#pragma unroll
+      for (int c = 0; c < DP; ++c) kr[f * DP + c] = kf[(f + 1) * DP - 1 - c];
+#pragma unroll
+    for (int f = 0; f < F; ++f)
+#pragma unroll
+      for (int c = 0; c < DP; ++c) kk[f][c] = gl ? kr[f * DP + c] : kf[f * DP + c];
+    float sm[SP];
+    sym_key_monomials_slots<SY>(kk, sm, gl);
+    put_monomials<SY>(mt, SM::kMStride, 32 * t + r, gl, sm, 1.0f);
+  }
+  __syncthreads();
+  const unsigned char* pu = ops + (static_cast<int64_t>(blockIdx.x) * g.H + h) * SL::kOpBytes;
+  const u32x4* opB = reinterpret_cast<const u32x4*>(pu + SL::kOpElems * 2);
+  const float* zslot = reinterpret_cast<const float*>(pu + 2 * SL::kOpElems * 2) + gl * SP;
+#pragma unroll 1
+  for (int qi = 0; qi < 2; ++qi) {
+    const int qt = qi == 0 ? wave : SM::kTiles - 1 - wave;
+    const int n0 = e.t0 + 32 * qt;
+    if (n0 >= e.t1) continue;
+    const int n = n0 + r;
+    const bool live = n < e.t1;
+    const int64_t th = g.th(e.b, h, live ? n : e.t1 - 1);
+    u32x4 bdo[NKD];
+    {
+      const bf16_t* row = dO.row<const bf16_t>(e.b, h, live ? n : e.t1 - 1);
+#pragma unroll
+      for (int kd = 0; kd < NKD; ++kd) {
+        bdo[kd] = *reinterpret_cast<const u32x4*>(row + 16 * kd + 8 * gl);
+        if (!live) bdo[kd][0] = bdo[kd][1] = bdo[kd][2] = bdo[kd][3] = 0u;
+      }
+    }
+    float fb[DP], qf[DP];
+    {
+      const f32x2* f = reinterpret_cast<const f32x2*>(feat + g.fidx(th, 0));
+#pragma unroll
+      for (int p = 0; p < DP / 2; ++p) {
+        const f32x2 v = f[32 * p];
+        fb[2 * p] = live ? v[0] : 0.0f;
+        fb[2 * p + 1] = live ? v[1] : 0.0f;
+      }
+      float fr[DP];
+#pragma unroll
+      for (int c = 0; c < DP; ++c) fr[c] = fb[DP - 1 - c];
+#pragma unroll
+      for (int c = 0; c < DP; ++c) qf[c] = gl ? fr[c] : fb[c];
+    }
+    const float inv = live ? 1.0f / den[th] : 0.0f;
+    float qm[SP];
+    sym_query_monomials<SY>(qf, qm, gl);
+    // the chunks in front: X = (state) dO^T, Z = its normaliser, both as seen from the chunk's
+    // first token
+    f32x16 X[NRM], Z[NRM];
+#pragma unroll
+    for (int rb = 0; rb < NRM; ++rb) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) X[rb][i] = 0.0f;
+#pragma unroll
+      for (int kd = 0; kd < NKD; ++kd) X[rb] = mfma32(opB[(rb * NKD + kd) * 64 + lane], bdo[kd], X[rb]);
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        const f32x4 z = *reinterpret_cast<const f32x4*>(zslot + 16 * rb + 4 * i4);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) Z[rb][4 * i4 + i] = z[i];
+      }
+    }
+    if (log2_decay != 0.0f) {
+      const float wq = __builtin_amdgcn_exp2f(log2_decay * static_cast<float>(32 * qt + r));
+#pragma unroll
+      for (int rb = 0; rb < NRM; ++rb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          X[rb][i] *= wq;
+          Z[rb][i] *= wq;
+        }
+    }
+    // the chunk's own keys up to the query: key tiles 0 .. qt
+#pragma unroll 1
+    for (int kt = 0; kt <= qt; ++kt) {
+      const f32x16 E = rows_product<D>(rt, SM::kRStride, kt, lane, bdo);
+      u32x4 bE[2], bW[2];
+      const float base = static_cast<float>(32 * (qt - kt) + r);
+#pragma unroll
+      for (int ks2 = 0; ks2 < 2; ++ks2)
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+          float wv[2];
+#pragma unroll
+          for (int x = 0; x < 2; ++x) {
+            const float dist = base - static_cast<float>(d_row(8 * ks2 + 2 * p + x, gl));
+            wv[x] = dist < 0.0f ? 0.0f : (log2_decay != 0.0f ? __builtin_amdgcn_exp2f(log2_decay * dist) : 1.0f);
+          }
+          bE[ks2][p] = pack_bf16(E[8 * ks2 + 2 * p] * wv[0], E[8 * ks2 + 2 * p + 1] * wv[1]);
+          bW[ks2][p] = pack_bf16(wv[0], wv[1]);
+        }
+      transposed_product<NRM>(mt, SM::kMStride, kt, lane, bE, X);
+      transposed_product<NRM>(mt, SM::kMStride, kt, lane, bW, Z);
+    }
+    // s_i from the same X that feeds dQm (the component along Qm cancels exactly), chain rule
+    float dot = 0.0f;
+#pragma unroll
+    for (int rb = 0; rb < NRM; ++rb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) dot += qm[16 * rb + i] * X[rb][i];
+    dot += partner32(dot);
+    const float si = -(inv * inv) * dot;
+    float dm[SP];
+#pragma unroll
+    for (int rb = 0; rb < NRM; ++rb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) dm[16 * rb + i] = inv * X[rb][i] + si * Z[rb][i];
+    float dq[DP];
+#pragma unroll
+    for (int c = 0; c < DP; ++c) dq[c] = 0.0f;
+    sym_query_monomials_grad<SY>(qf, dm, dq, gl);
+    float other[DP];
+#pragma unroll
+    for (int c = 0; c < DP; ++c) other[c] = partner32(dq[c]);
+    if (live && gl == 0) {
+      f32x2* df = reinterpret_cast<f32x2*>(dfeat + g.fidx(th, 0));
+#pragma unroll
+      for (int c = 0; c < DP; c += 2) {
+        f32x2 v;
+        v[0] = (!relu_mask || fb[c] > 0.0f) ? dq[c] + other[DP - 1 - c] : 0.0f;
+        v[1] = (!relu_mask || fb[c + 1] > 0.0f) ? dq[c + 1] + other[DP - 2 - c] : 0.0f;
+        df[32 * (c / 2)] = v;
+      }
+      sv[th] = si;
+    }
+  }
+}
+
+// grid (chunks of kCausalChunk tokens, H), block 256.  Key side: writes the key part of the feature
+// gradients and dV.  dops: per (chunk, head) the images of the gradient state behind the chunk.
+template <class SY, int D>
+__global__ __launch_bounds__(kThreads) void k_cgrad_k(Geom g, const BlockEnt* __restrict__ chunks,
+                                                      const float* __restrict__ feat,
+                                                      const float* __restrict__ den,
+                                                      const float* __restrict__ sv, View V, View dO,
+                                                      const unsigned char* __restrict__ dops,
+                                                      float* __restrict__ dfeat, View dV,
+                                                      float log2_decay, int relu_mask) {
+  using SM = CgSmem<SY, D>;
+  using SL = StateLayout<SY, D>;
+  constexpr int SP = SY::SP, MP = SY::MP, DP = SY::DPHI, F = SY::F;
+  constexpr int NRB = D / 32, NKD = D / 16, NRM = MP / 32, NKS = MP / 16, NF = F * DP;
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int lane = threadIdx.x % kWave, wave = wave_index();
+  unsigned char* rt = smem;
+  unsigned char* mt = smem + SM::kRBytes;
+  float* tq = reinterpret_cast<float*>(smem + SM::kRBytes + SM::kMBytes);
+  unsigned char* tile = smem + SM::kRBytes + SM::kMBytes + SM::kTBytes + wave * RowTile<D, 16>::kBytes;
+  const int r = lane % 32, gl = lane / 32;
+  const BlockEnt e = chunks[blockIdx.x];
+  const int h = blockIdx.y;
+  // ---- the chunk's dO rows (64 per wave), scaled query monomials Qm / den and t = s den
+  {
+    TileRegs<D, 64> vt;
+    fetch_tile<D, 64>(dO, e.b, h, e.t0 + 64 * wave, e.t1, lane, vt);
+    put_tile<D, 64>(vt, lane, rt + 64 * wave * SM::kRStride, SM::kRStride);
+  }
+#pragma unroll 1
+  for (int tt = 0; tt < 2; ++tt) {
+    const int t = 2 * wave + tt;
+    const int n = e.t0 + 32 * t + r;
+    const bool live = n < e.t1;
+    const int64_t th = g.th(e.b, h, live ? n : e.t1 - 1);
+    float qf[DP];
+    {
+      const f32x2* f = reinterpret_cast<const f32x2*>(feat + g.fidx(th, 0));
+#pragma unroll
+      for (int p = 0; p < DP / 2; ++p) {  // lane half 1 takes the pairs, and each pair, in reverse
+        const f32x2 v = f[32 * (gl ? DP / 2 - 1 - p : p)];
+        qf[2 * p] = live ? (gl ? v[1] : v[0]) : 0.0f;
+        qf[2 * p + 1] = live ? (gl ? v[0] : v[1]) : 0.0f;
+      }
+    }
+    const float dn = live ? den[th] : 1.0f;
+    float qm[SP];
+    sym_query_monomials<SY>(qf, qm, gl);
+    put_monomials<SY>(mt, SM::kMStride, 32 * t + r, gl, qm, live ? 1.0f / dn : 0.0f);
+    if (gl == 0) tq[32 * t + r] = live ? sv[th] * dn : 0.0f;
+  }
+  __syncthreads();
+  const unsigned char* pu = dops + (static_cast<int64_t>(blockIdx.x) * g.H + h) * SL::kOpBytes;
+  const u32x4* opA = reinterpret_cast<const u32x4*>(pu);
+  const u32x4* opB = reinterpret_cast<const u32x4*>(pu + SL::kOpElems * 2);
+  const float* dzslot = reinterpret_cast<const float*>(pu + 2 * SL::kOpElems * 2) + gl * SP;
+#pragma unroll 1
+  for (int ki = 0; ki < 2; ++ki) {
+    const int kt = ki == 0 ? wave : SM::kTiles - 1 - wave;
+    const int n0 = e.t0 + 32 * kt;
+    if (n0 >= e.t1) continue;
+    const int n = n0 + r;
+    const bool live = n < e.t1;
+    const int64_t th = g.th(e.b, h, live ? n : e.t1 - 1);
+    u32x4 bv[NKD];
+    {
+      const bf16_t* row = V.row<const bf16_t>(e.b, h, live ? n : e.t1 - 1);
+#pragma unroll
+      for (int kd = 0; kd < NKD; ++kd) {
+        bv[kd] = *reinterpret_cast<const u32x4*>(row + 16 * kd + 8 * gl);
+        if (!live) bv[kd][0] = bv[kd][1] = bv[kd][2] = bv[kd][3] = 0u;
+      }
+    }
+    float kb[NF];
+    float kk[F][DP];
+    {
+      const f32x2* f = reinterpret_cast<const f32x2*>(feat + g.fidx(th, DP));
+      float kr[NF];
+#pragma unroll
+      for (int p = 0; p < NF / 2; ++p) {
+        const f32x2 v = f[32 * p];
+        kb[2 * p] = live ? v[0] : 0.0f;
+        kb[2 * p + 1] = live ? v[1] : 0.0f;
+      }
+#pragma unroll
+      for (int f2 = 0; f2 < F; ++f2)
+#pragma unroll
+        for (int c = 0; c < DP; ++c) kr[f2 * DP + c] = kb[(f2 + 1) * DP - 1 - c];
+#pragma unroll
+      for (int f2 = 0; f2 < F; ++f2)
+#pragma unroll
+        for (int c = 0; c < DP; ++c) kk[f2][c] = gl ? kr[f2 * DP + c] : kb[f2 * DP + c];
+    }
+    float sm[SP];
+    sym_key_monomials_slots<SY>(kk, sm, gl);
+    u32x4 bS[NKS];
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks)
+#pragma unroll
+      for (int p = 0; p < 4; ++p) bS[ks][p] = pack_bf16(sm[8 * ks + 2 * p], sm[8 * ks + 2 * p + 1]);
+    // the chunks behind: dS = (gradient state) v + dz, dv = (gradient state)^T S, as seen from the
+    // chunk's last token
+    f32x16 Y[NRM], dvT[NRB];
+#pragma unroll
+    for (int rb = 0; rb < NRM; ++rb) {
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        const f32x4 z = *reinterpret_cast<const f32x4*>(dzslot + 16 * rb + 4 * i4);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) Y[rb][4 * i4 + i] = z[i];
+      }
+#pragma unroll
+      for (int kd = 0; kd < NKD; ++kd) Y[rb] = mfma32(opB[(rb * NKD + kd) * 64 + lane], bv[kd], Y[rb]);
+    }
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) dvT[rb][i] = 0.0f;
+#pragma unroll
+      for (int ks = 0; ks < NKS; ++ks) dvT[rb] = mfma32(opA[(rb * NKS + ks) * 64 + lane], bS[ks], dvT[rb]);
+    }
+    if (log2_decay != 0.0f) {
+      const float wk = __builtin_amdgcn_exp2f(log2_decay * static_cast<float>(kCausalChunk - 1 - (32 * kt + r)));
+#pragma unroll
+      for (int rb = 0; rb < NRM; ++rb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) Y[rb][i] *= wk;
+#pragma unroll
+      for (int rb = 0; rb < NRB; ++rb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) dvT[rb][i] *= wk;
+    }
+    // the chunk's own queries from the key on: query tiles kt .. last
+    const int last = (e.t1 - e.t0 + 31) / 32 - 1;
+#pragma unroll 1
+    for (int qt = kt; qt <= last; ++qt) {
+      const f32x16 E = rows_product<D>(rt, SM::kRStride, qt, lane, bv);  // <dO_i, v_j>
+      // <Qm'_i, S_j>: A = row reads of the monomial tile, the eight k-slots (g, 8 ks + j) of a
+      // k-step as two runs of four columns
+      f32x16 A;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) A[i] = 0.0f;
+#pragma unroll
+      for (int ks = 0; ks < NKS; ++ks) {
+        const unsigned char* p = mt + (32 * qt + r) * SM::kMStride + rho_of(gl, 8 * ks) * 2;
+        const u32x2 lo = *reinterpret_cast<const u32x2*>(p);
+        const u32x2 hi = *reinterpret_cast<const u32x2*>(p + 16);
+        u32x4 a;
+        a[0] = lo[0];
+        a[1] = lo[1];
+        a[2] = hi[0];
+        a[3] = hi[1];
+        A = mfma32(a, bS[ks], A);
+      }
+      u32x4 bE[2], bA[2];
+      const float base = static_cast<float>(32 * (qt - kt) - r);
+#pragma unroll
+      for (int ks2 = 0; ks2 < 2; ++ks2) {
+        const f32x4 t0 = *reinterpret_cast<const f32x4*>(tq + 32 * qt + 16 * ks2 + 4 * gl);
+        const f32x4 t1 = *reinterpret_cast<const f32x4*>(tq + 32 * qt + 16 * ks2 + 4 * gl + 8);
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+          float wv[2], tv[2];
+#pragma unroll
+          for (int x = 0; x < 2; ++x) {
+            const int i = 8 * ks2 + 2 * p + x;  // query d_row(i, gl) = 16 ks2 + 8 (p / 2) + 4 gl + (2 p + x) % 4
+            const float dist = base + static_cast<float>(d_row(i, gl));
+            wv[x] = dist < 0.0f ? 0.0f : (log2_decay != 0.0f ? __builtin_amdgcn_exp2f(log2_decay * dist) : 1.0f);
+            tv[x] = p < 2 ? t0[(2 * p + x) % 4] : t1[(2 * p + x) % 4];
+          }
+          bE[ks2][p] = pack_bf16((E[8 * ks2 + 2 * p] + tv[0]) * wv[0], (E[8 * ks2 + 2 * p + 1] + tv[1]) * wv[1]);
+          bA[ks2][p] = pack_bf16(A[8 * ks2 + 2 * p] * wv[0], A[8 * ks2 + 2 * p + 1] * wv[1]);
+        }
+      }
+      transposed_product<NRM>(mt, SM::kMStride, qt, lane, bE, Y);
+      transposed_product<NRB>(rt, SM::kRStride, qt, lane, bA, dvT);
+    }
+    // chain rule to the key features
+    float dk[F][DP];
+    {
+      float ds[SP];
+#pragma unroll
+      for (int rb = 0; rb < NRM; ++rb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) ds[16 * rb + i] = Y[rb][i];
+#pragma unroll
+      for (int f2 = 0; f2 < F; ++f2)
+#pragma unroll
+        for (int c = 0; c < DP; ++c) dk[f2][c] = 0.0f;
+      sym_key_monomials_grad_range<SY, 0, SY::NS>(kk, ds, dk, gl);
+    }
+    float other[F][DP];
+#pragma unroll
+    for (int f2 = 0; f2 < F; ++f2)
+#pragma unroll
+      for (int c = 0; c < DP; ++c) other[f2][c] = partner32(dk[f2][c]);
+    if (live && gl == 0) {
+      f32x2* df = reinterpret_cast<f32x2*>(dfeat + g.fidx(th, DP));
+#pragma unroll
+      for (int p = 0; p < NF / 2; ++p) {
+        f32x2 v;
+#pragma unroll
+        for (int x = 0; x < 2; ++x) {
+          const int a = 2 * p + x, f2 = a / DP, c = a % DP;
+          const float val = dk[f2][c] + other[f2][DP - 1 - c];
+          v[x] = (!relu_mask || kb[a] > 0.0f) ? val : 0.0f;
+        }
+        df[32 * p] = v;
+      }
+    }
+    store_rows_bf16<D, 16>(dvT, 1.0f, lane, tile, [&](int t) -> bf16_t* {
+      return n0 + t < e.t1 ? dV.row<bf16_t>(e.b, h, n0 + t) : nullptr;
+    });
+  }
+}
+
+template <class SY, int D>
+hla_status backward_causal(hla_handle* hd, const hla_call_args& a) {
+  using SL = StateLayout<SY, D>;
+  using SM = StateSmem<D, SY::MP>;
+  using SG = CgSmem<SY, D>;
+  Geom g = hd->g;
+  hipStream_t s = a.stream;
+  hla_token_table* cch = nullptr;
+  HLA_TRY(get_table(hd, 2, kCausalChunk, s, &cch));
+  if (static_cast<int64_t>(cch->count) * g.H > hd->max_chunks * hd->cfg.max_heads) return HLA_ERR_INVALID_ARG;
+  // images of the state in front of every chunk, then of the gradient state behind it
+  unsigned char* ops = static_cast<unsigned char*>(hd->path_ws) + hd->causal_bwd_off;
+  unsigned char* dops = ops + SL::kOpBytes * hd->max_chunks * hd->cfg.max_heads;
+  const float dec = hd->cfg.decay > 0.0f && hd->cfg.decay < 1.0f ? hd->cfg.decay : 1.0f;
+  const float l2d = dec < 1.0f ? std::log2(dec) : 0.0f;
+  const float chunk_decay = dec < 1.0f ? std::pow(dec, static_cast<float>(kCausalChunk)) : 1.0f;
+  const int relu_mask = hd->cfg.phi_mode == HLA_PHI_MLP ? 1 : 0;
+  const CanonMap cm = make_canon_map<SY>();
+  const int64_t stride = SL::kOpBytes, z_off = 2 * SL::kOpElems * 2, b_off = SL::kOpElems * 2;
+  const dim3 sgrid(a.num_seqs, g.H, 2 * (SY::MP / 16) * D / 256);
+  const dim3 rgrid(a.num_seqs, g.H, (SY::MP / 32) * (D / 16) * 64 / 256);
+  static_assert((SY::MP / 32) * (D / 16) * 64 % 256 == 0, "whole workgroups of row-image items");
+  const float* nof = nullptr;
+  // the chunks' own states again (the forward's partial buffer serves other kernels in between)
+  HLA_TRY(launch(hd, "mfma_state", k_state<SY, D>, dim3(cch->count, g.H), dim3(kThreads), SM::kTotal, s,
+                 g, cch->dev, hd->feat, a.V, hd->partial, SL::kF32, l2d, nof, nof));
+  HLA_TRY(launch(hd, "mfma_state_prefix", k_prefix<SY, D, false>, sgrid, dim3(256), 0, s, g, cch->seq_off_dev,
+                 hd->partial, SL::kF32, ops, cm, chunk_decay, stride, z_off));
+  HLA_TRY(launch(hd, "mfma_state_prefix_rows", k_prefix_rows<SY, D, false>, rgrid, dim3(256), 0, s, g,
+                 cch->seq_off_dev, hd->partial, SL::kF32, ops, cm, chunk_decay, stride, b_off));
+  HLA_TRY(launch(hd, "mfma_causal_grad_query", k_cgrad_q<SY, D>, dim3(cch->count, g.H), dim3(kThreads),
+                 SG::kTotalQ, s, g, cch->dev, hd->feat, hd->den, a.V, a.dO, ops, hd->dfeat, hd->yhat, l2d,
+                 relu_mask));
+  // gradient states of the chunks, summed from the back
+  HLA_TRY(launch(hd, "mfma_dstate", k_state<SY, D, 1>, dim3(cch->count, g.H), dim3(kThreads), SM::kTotal, s,
+                 g, cch->dev, hd->feat, a.dO, hd->partial, SL::kF32, l2d, static_cast<const float*>(hd->den),
+                 static_cast<const float*>(hd->yhat)));
+  HLA_TRY(launch(hd, "mfma_dstate_suffix", k_prefix<SY, D, true>, sgrid, dim3(256), 0, s, g, cch->seq_off_dev,
+                 hd->partial, SL::kF32, dops, cm, chunk_decay, stride, z_off));
+  HLA_TRY(launch(hd, "mfma_dstate_suffix_rows", k_prefix_rows<SY, D, true>, rgrid, dim3(256), 0, s, g,
+                 cch->seq_off_dev, hd->partial, SL::kF32, dops, cm, chunk_decay, stride, b_off));
+  HLA_TRY(launch(hd, "mfma_causal_grad_key", k_cgrad_k<SY, D>, dim3(cch->count, g.H), dim3(kThreads),
+                 SG::kTotalK, s, g, cch->dev, hd->feat, hd->den, static_cast<const float*>(hd->yhat), a.V, a.dO,
+                 dops, hd->dfeat, a.dV, l2d, relu_mask));
+  return HLA_OK;
+}
+
 template <class SY, int D>
 hla_status backward_core(hla_handle* hd, const hla_call_args& a) {
   using SL = StateLayout<SY, D>;
@@ -1334,7 +1948,7 @@ hla_status forward_core(hla_handle* hd, const hla_call_args& a) {
   if (static_cast<int64_t>(chunks->count) * g.H > hd->max_chunks * hd->cfg.max_heads)
     return HLA_ERR_INVALID_ARG;
   HLA_TRY(launch(hd, "mfma_state", k_state<SY, D>, dim3(chunks->count, g.H), dim3(kThreads),
-                 SM::kTotal, s, g, chunks->dev, hd->feat, a.V, hd->partial, SL::kF32, 0.0f));
+                 SM::kTotal, s, g, chunks->dev, hd->feat, a.V, hd->partial, SL::kF32, 0.0f, static_cast<const float*>(nullptr), static_cast<const float*>(nullptr)));
   const SlotMap sm = make_slot_map<SY>();
   unsigned char* ops = static_cast<unsigned char*>(hd->path_ws);
   HLA_TRY(launch(hd, "mfma_state_reduce", k_reduce<SY, D, false>, dim3(a.num_seqs, g.H, kReduceSlices),
@@ -1360,10 +1974,13 @@ hla_status forward_causal(hla_handle* hd, const hla_call_args& a) {
   const float l2d = dec < 1.0f ? std::log2(dec) : 0.0f;
   const float chunk_decay = dec < 1.0f ? std::pow(dec, static_cast<float>(kCausalChunk)) : 1.0f;
   HLA_TRY(launch(hd, "mfma_state", k_state<SY, D>, dim3(cch->count, g.H), dim3(kThreads), SM::kTotal, s,
-                 g, cch->dev, hd->feat, a.V, hd->partial, SL::kF32, l2d));
+                 g, cch->dev, hd->feat, a.V, hd->partial, SL::kF32, l2d, static_cast<const float*>(nullptr),
+                 static_cast<const float*>(nullptr)));
   static_assert(2 * (SY::MP / 16) * D % 256 == 0, "whole workgroups of prefix items");
-  HLA_TRY(launch(hd, "mfma_state_prefix", k_prefix<SY, D>, dim3(a.num_seqs, g.H, 2 * (SY::MP / 16) * D / 256),
-                 dim3(256), 0, s, g, cch->seq_off_dev, hd->partial, SL::kF32, pfx, make_canon_map<SY>(), chunk_decay));
+  using PL = PrefixLayout<SY, D>;
+  HLA_TRY(launch(hd, "mfma_state_prefix", k_prefix<SY, D, false>, dim3(a.num_seqs, g.H, 2 * (SY::MP / 16) * D / 256),
+                 dim3(256), 0, s, g, cch->seq_off_dev, hd->partial, SL::kF32, pfx, make_canon_map<SY>(), chunk_decay,
+                 static_cast<int64_t>(PL::kBytes), static_cast<int64_t>(PL::kOpElems * 2)));
   HLA_TRY(launch(hd, "mfma_query_causal", k_query_causal<SY, D>, dim3(cch->count, g.H), dim3(kThreads),
                  SC::kTotal, s, g, cch->dev, hd->feat, a.V, pfx, a.O, hd->den, l2d));
   return HLA_OK;
@@ -1372,6 +1989,9 @@ hla_status forward_causal(hla_handle* hd, const hla_call_args& a) {
 template <class SY, int D>
 hla_status prepare_core() {
   HLA_TRY(allow_big_lds(&k_query_causal<SY, D>, CausalSmem<SY, D>::kTotal));
+  HLA_TRY(allow_big_lds(&k_cgrad_q<SY, D>, CgSmem<SY, D>::kTotalQ));
+  HLA_TRY(allow_big_lds(&k_cgrad_k<SY, D>, CgSmem<SY, D>::kTotalK));
+  HLA_TRY(allow_big_lds(&k_state<SY, D, 1>, StateSmem<D, SY::MP>::kTotal));
   HLA_TRY(allow_big_lds(&k_state<SY, D>, StateSmem<D, SY::MP>::kTotal));
   return allow_big_lds(&k_bwd_query<SY, D>, BwdQSmem<D, SY::MP>::kTotal);
 }
@@ -1427,8 +2047,14 @@ hla_status mfma_workspace_plan(hla_handle* hd) {
   hd->w_packed_off = hd->path_ws_bytes;
   if (hd->cfg.phi_mode == HLA_PHI_MLP) hd->path_ws_bytes += mfma_phi_packed_bytes(hd);
   hd->causal_off = hd->path_ws_bytes;
-  if (hd->cfg.causal)
+  if (hd->cfg.causal) {
     hd->path_ws_bytes += static_cast<size_t>(hd->max_chunks * hd->cfg.max_heads * (MP * g.d * 2 + 2 * SP * 4));
+    // backward: per chunk the images (opA, opB, z) of the state in front and of the gradient state behind
+    hd->path_ws_bytes = (hd->path_ws_bytes + 255) / 256 * 256;
+    hd->causal_bwd_off = hd->path_ws_bytes;
+    hd->path_ws_bytes += static_cast<size_t>(2 * op_bytes * hd->max_chunks * hd->cfg.max_heads);
+    hd->yhat_floats = hd->max_th;  // s_i of the query-side kernel
+  }
   return HLA_OK;
 }
 
@@ -1449,6 +2075,7 @@ static hla_status forward_sym(hla_handle* hd, const hla_call_args& a) {
 }
 template <class SY>
 static hla_status backward_sym(hla_handle* hd, const hla_call_args& a) {
+  if (hd->cfg.causal) return hd->g.d == 128 ? backward_causal<SY, 128>(hd, a) : backward_causal<SY, 64>(hd, a);
   return hd->g.d == 128 ? backward_core<SY, 128>(hd, a) : backward_core<SY, 64>(hd, a);
 }
 

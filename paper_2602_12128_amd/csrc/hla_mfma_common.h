@@ -554,6 +554,21 @@ __device__ __forceinline__ void sym_query_monomials_grad(const float (&q)[SY::DP
     });
   }
 }
+// all NM query monomials in canonical order (one lane serves one token, features not reversed)
+template <class SY>
+__device__ __forceinline__ void sym_query_monomials_all(const float (&q)[SY::DPHI], float (&qm)[SY::NM]) {
+  constexpr int DP = SY::DPHI;
+  static_for<0, SY::NM>([&](auto M) {
+    constexpr int m = decltype(M)::value;
+    if constexpr (SY::F == 3) {
+      constexpr Tri t = sym3_mono(DP, m);
+      qm[m] = (q[t.x] * q[t.y]) * q[t.z];
+    } else {
+      constexpr Duo t = sym2_mono(DP, m);
+      qm[m] = q[t.x] * q[t.y];
+    }
+  });
+}
 // all NM key monomials in canonical order (one lane serves one token, features not reversed)
 template <class SY>
 __device__ __forceinline__ void sym_key_monomials_all(const float (&k)[SY::F][SY::DPHI],
