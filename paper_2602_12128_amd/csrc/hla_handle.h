@@ -51,6 +51,7 @@ struct hla_handle {
   size_t path_ws_bytes = 0;
   size_t w_packed_off = 0;         // byte offset of the MFMA path's packed feature-map weights in path_ws
   size_t causal_off = 0;           // byte offset of the per-chunk prefix-state images (causal handles)
+  bool causal_partials_valid = false;  // the partial buffer still holds the last causal forward's chunk states
   size_t causal_bwd_off = 0;       // byte offset of the per-chunk state / gradient-state images of the causal backward
 
   // feature-map weights, fp32 copies (both paths keep them; the MFMA path adds packed bf16)

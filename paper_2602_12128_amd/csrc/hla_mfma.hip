@@ -543,7 +543,7 @@ __global__ __launch_bounds__(256) void k_prefix(Geom g, const int32_t* __restric
 #pragma unroll
   for (int j = 0; j < 8; ++j) acc[j] = 0.0f;
   const int rb = c / 32, r = c % 32;
-  constexpr int NB = 8;  // chunks in flight
+  constexpr int NB = 16;  // chunks in flight (the scan is a chain of memory round trips: one per batch)
   for (int pos = 0; pos < nc; pos += NB) {
     float ld[NB][8];
 #pragma unroll
@@ -625,7 +625,7 @@ __global__ __launch_bounds__(256) void k_prefix_rows(Geom g, const int32_t* __re
   float acc[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) acc[j] = 0.0f;
-  constexpr int NB = 8;
+  constexpr int NB = 16;
   for (int pos = 0; pos < nc; pos += NB) {
     f32x4 ld[NB][2];
 #pragma unroll
@@ -1472,17 +1472,19 @@ __device__ __forceinline__ void transposed_product(const unsigned char* tile, in
 }
 
 // grid (chunks of kCausalChunk tokens, H), block 256.  Query side: writes the query part of the
-// feature gradients and s_i (sv) for the key side.  ops: per (chunk, head) the images of the
-// state in front of the chunk (StateLayout: opA, opB, z by slot).
+// feature gradients and s_i (sv) for the key side.  rows_img / z_img: per (chunk, head) the
+// monomial-row image of the state in front of the chunk and its normaliser by slot.
 template <class SY, int D>
 __global__ __launch_bounds__(kThreads) void k_cgrad_q(Geom g, const BlockEnt* __restrict__ chunks,
                                                       const float* __restrict__ feat,
                                                       const float* __restrict__ den, View V, View dO,
-                                                      const unsigned char* __restrict__ ops,
-                                                      float* __restrict__ dfeat, float* __restrict__ sv,
-                                                      float log2_decay, int relu_mask) {
+                                                      const unsigned char* __restrict__ rows_img,
+                                                      int64_t rows_stride,
+                                                      const unsigned char* __restrict__ z_img,
+                                                      int64_t z_stride, float* __restrict__ dfeat,
+                                                      float* __restrict__ sv, float log2_decay,
+                                                      int relu_mask) {
   using SM = CgSmem<SY, D>;
-  using SL = StateLayout<SY, D>;
   constexpr int SP = SY::SP, MP = SY::MP, DP = SY::DPHI, F = SY::F;
   constexpr int NKD = D / 16, NRM = MP / 32, NF = F * DP;
   extern __shared__ __align__(16) unsigned char smem[];
@@ -1529,9 +1531,9 @@ __global__ __launch_bounds__(kThreads) void k_cgrad_q(Geom g, const BlockEnt* __
     put_monomials<SY>(mt, SM::kMStride, 32 * t + r, gl, sm, 1.0f);
   }
   __syncthreads();
-  const unsigned char* pu = ops + (static_cast<int64_t>(blockIdx.x) * g.H + h) * SL::kOpBytes;
-  const u32x4* opB = reinterpret_cast<const u32x4*>(pu + SL::kOpElems * 2);
-  const float* zslot = reinterpret_cast<const float*>(pu + 2 * SL::kOpElems * 2) + gl * SP;
+  const int64_t ch_h = static_cast<int64_t>(blockIdx.x) * g.H + h;
+  const u32x4* opB = reinterpret_cast<const u32x4*>(rows_img + ch_h * rows_stride);
+  const float* zslot = reinterpret_cast<const float*>(z_img + ch_h * z_stride) + gl * SP;
 #pragma unroll 1
   for (int qi = 0; qi < 2; ++qi) {
     const int qt = qi == 0 ? wave : SM::kTiles - 1 - wave;
@@ -1888,16 +1890,22 @@ hla_status backward_causal(hla_handle* hd, const hla_call_args& a) {
   const dim3 rgrid(a.num_seqs, g.H, (SY::MP / 32) * (D / 16) * 64 / 256);
   static_assert((SY::MP / 32) * (D / 16) * 64 % 256 == 0, "whole workgroups of row-image items");
   const float* nof = nullptr;
-  // the chunks' own states again (the forward's partial buffer serves other kernels in between)
-  HLA_TRY(launch(hd, "mfma_state", k_state<SY, D>, dim3(cch->count, g.H), dim3(kThreads), SM::kTotal, s,
-                 g, cch->dev, hd->feat, a.V, hd->partial, SL::kF32, l2d, nof, nof));
-  HLA_TRY(launch(hd, "mfma_state_prefix", k_prefix<SY, D, false>, sgrid, dim3(256), 0, s, g, cch->seq_off_dev,
-                 hd->partial, SL::kF32, ops, cm, chunk_decay, stride, z_off));
+  using PL = PrefixLayout<SY, D>;
+  const unsigned char* pfx = static_cast<unsigned char*>(hd->path_ws) + hd->causal_off;
+  // The forward left the chunks' own states in the partial buffer and their running sum (operand
+  // image by channels, normaliser) in its prefix images; what the query side needs on top is the
+  // image by monomial rows.  A second backward after the same forward finds the partial buffer
+  // holding gradient states and computes the chunk states again.
+  if (!hd->causal_partials_valid)
+    HLA_TRY(launch(hd, "mfma_state", k_state<SY, D>, dim3(cch->count, g.H), dim3(kThreads), SM::kTotal, s,
+                   g, cch->dev, hd->feat, a.V, hd->partial, SL::kF32, l2d, nof, nof));
   HLA_TRY(launch(hd, "mfma_state_prefix_rows", k_prefix_rows<SY, D, false>, rgrid, dim3(256), 0, s, g,
                  cch->seq_off_dev, hd->partial, SL::kF32, ops, cm, chunk_decay, stride, b_off));
   HLA_TRY(launch(hd, "mfma_causal_grad_query", k_cgrad_q<SY, D>, dim3(cch->count, g.H), dim3(kThreads),
-                 SG::kTotalQ, s, g, cch->dev, hd->feat, hd->den, a.V, a.dO, ops, hd->dfeat, hd->yhat, l2d,
-                 relu_mask));
+                 SG::kTotalQ, s, g, cch->dev, hd->feat, hd->den, a.V, a.dO,
+                 static_cast<const unsigned char*>(ops + b_off), stride,
+                 pfx + PL::kOpElems * 2, static_cast<int64_t>(PL::kBytes), hd->dfeat, hd->yhat, l2d, relu_mask));
+  hd->causal_partials_valid = false;
   // gradient states of the chunks, summed from the back
   HLA_TRY(launch(hd, "mfma_dstate", k_state<SY, D, 1>, dim3(cch->count, g.H), dim3(kThreads), SM::kTotal, s,
                  g, cch->dev, hd->feat, a.dO, hd->partial, SL::kF32, l2d, static_cast<const float*>(hd->den),
@@ -1983,6 +1991,7 @@ hla_status forward_causal(hla_handle* hd, const hla_call_args& a) {
                  static_cast<int64_t>(PL::kBytes), static_cast<int64_t>(PL::kOpElems * 2)));
   HLA_TRY(launch(hd, "mfma_query_causal", k_query_causal<SY, D>, dim3(cch->count, g.H), dim3(kThreads),
                  SC::kTotal, s, g, cch->dev, hd->feat, a.V, pfx, a.O, hd->den, l2d));
+  hd->causal_partials_valid = true;  // the partial buffer holds this forward's chunk states
   return HLA_OK;
 }
 

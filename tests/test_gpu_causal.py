@@ -217,3 +217,24 @@ def test_causal_backward_through_feature_maps_packed():
         g2[k][:, :, 1324] = 0
         r2[k][:, :, 1324] = 0
     pu.assert_parity(g2, r2, 2e-2, "causal backward packed through the maps", kinks=kinks)
+
+
+def test_causal_backward_twice_after_one_forward_is_bit_identical():
+    """The first backward after a forward reuses the forward's chunk states, a second one has to
+    compute them again: the same bits either way."""
+    dev = torch.device("cuda:0")
+    t = wl.make_feature_inputs(1420, 1, 2, 900, 128, 3, 6, torch.bfloat16)
+    h = hla.HLA(head_dim=128, feature_dim=6, degree=3, eps=1e-6, io_dtype=hla.HLA_BF16,
+                phi_mode=hla.HLA_PHI_NONE, max_heads=2, max_tokens=900, max_seqs=1, causal=True, decay=0.98)
+    td = {k: v.to(dev) for k, v in t.items()}
+    O = torch.empty_like(td["V"])
+    h.forward(td["Q"], td["K"], td["V"], O)
+    runs = []
+    for _ in range(2):
+        g = [torch.full_like(td[k], float("nan")) for k in "QKV"]
+        h.backward(td["Q"], td["K"], td["V"], O, td["dO"], *g)
+        torch.cuda.synchronize()
+        runs.append([x.cpu() for x in g])
+    h.destroy()
+    for a, b in zip(*runs):
+        assert torch.equal(a, b)
