@@ -511,7 +511,7 @@ CanonMap make_canon_map() {
   return cm;
 }
 
-// grid (num_seqs, H, 2 * NKS * D / 256), block 256.  A thread owns the eight slots (g, 8 ks .. 8 ks + 7)
+// grid (num_seqs, H, 2 * NKS * D / kScanThreads + 1), block kScanThreads.  A thread owns the eight slots (g, 8 ks .. 8 ks + 7)
 // of one channel c: eight running sums, read from the eight partial rows of those monomials at
 // column c (consecutive threads: consecutive floats), written for chunk ch -- before chunk ch's own
 // partial is added -- as the 16 bytes these eight slots occupy in the operand image (consecutive
@@ -522,8 +522,9 @@ CanonMap make_canon_map() {
 // REVERSE: the running sum goes from the sequence's last chunk to its first, and chunk ch receives
 // the sum over the chunks behind it (the gradient states of the backward).  Images are written
 // `stride` bytes apart, the normaliser vector z_off bytes into an image.
+constexpr int kScanThreads = 64;  // one wave per workgroup: the scans are a few thousand threads in all, spread over as many compute units as possible
 template <class SY, int D, bool REVERSE>
-__global__ __launch_bounds__(256) void k_prefix(Geom g, const int32_t* __restrict__ seq_chunk_off,
+__global__ __launch_bounds__(kScanThreads) void k_prefix(Geom g, const int32_t* __restrict__ seq_chunk_off,
                                                 const float* __restrict__ partial,
                                                 int64_t partial_stride, unsigned char* __restrict__ pfx,
                                                 CanonMap cm, float chunk_decay, int64_t stride,
@@ -532,7 +533,11 @@ __global__ __launch_bounds__(256) void k_prefix(Geom g, const int32_t* __restric
   const int s = blockIdx.x, h = blockIdx.y;
   const int c0 = seq_chunk_off[s], c1 = seq_chunk_off[s + 1], nc = c1 - c0;
   auto chunk_at = [&](int pos) { return REVERSE ? c1 - 1 - pos : c0 + pos; };  // pos-th chunk in scan order
-  const int item = blockIdx.z * 256 + threadIdx.x;  // (mg, ks, c)
+  // the last workgroup in z carries the normaliser vector (one thread per eight slots), the others
+  // the operand image
+  const bool zblock = blockIdx.z == gridDim.z - 1;
+  if (zblock && threadIdx.x >= 2 * NKS) return;
+  const int item = zblock ? threadIdx.x * D : blockIdx.z * kScanThreads + threadIdx.x;  // (mg, ks, c)
   const int c = item % D, ks = (item / D) % NKS, mg = item / (D * NKS);
   const float* base = partial + static_cast<int64_t>(h) * partial_stride + c;
   const int64_t cstride = static_cast<int64_t>(g.H) * partial_stride;
@@ -544,7 +549,7 @@ __global__ __launch_bounds__(256) void k_prefix(Geom g, const int32_t* __restric
   for (int j = 0; j < 8; ++j) acc[j] = 0.0f;
   const int rb = c / 32, r = c % 32;
   constexpr int NB = 16;  // chunks in flight (the scan is a chain of memory round trips: one per batch)
-  for (int pos = 0; pos < nc; pos += NB) {
+  for (int pos = 0; pos < (zblock ? 0 : nc); pos += NB) {
     float ld[NB][8];
 #pragma unroll
     for (int k = 0; k < NB; ++k) {
@@ -567,7 +572,7 @@ __global__ __launch_bounds__(256) void k_prefix(Geom g, const int32_t* __restric
   // the normaliser vector by slot, carried by the threads of channel 0; loads batched like the
   // rows above (a load per chunk issued next to the store that needs it would cost one memory
   // round trip per chunk)
-  if (c == 0) {
+  if (zblock) {
     float z[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) z[j] = 0.0f;
@@ -604,10 +609,10 @@ __global__ __launch_bounds__(256) void k_prefix(Geom g, const int32_t* __restric
 // contract over the channels, used by the backward): image row rho = 32 rbm + r is slot
 // (g, s) = ((rho >> 2) & 1, 16 (rho >> 5) + 4 ((rho >> 3) & 3) + (rho & 3)), so that accumulator
 // register i of row block rbm on lane half gl is the lane's own slot 16 rbm + i.
-// grid (num_seqs, H, (MP / 32) * (D / 16) * 64 / 256), block 256; a thread owns eight consecutive
+// grid (num_seqs, H, (MP / 32) * (D / 16) * 64 / kScanThreads), block kScanThreads; a thread owns eight consecutive
 // channels of one row; the image starts `img_off` bytes into a chunk's block.
 template <class SY, int D, bool REVERSE>
-__global__ __launch_bounds__(256) void k_prefix_rows(Geom g, const int32_t* __restrict__ seq_chunk_off,
+__global__ __launch_bounds__(kScanThreads) void k_prefix_rows(Geom g, const int32_t* __restrict__ seq_chunk_off,
                                                      const float* __restrict__ partial,
                                                      int64_t partial_stride, unsigned char* __restrict__ pfx,
                                                      CanonMap cm, float chunk_decay, int64_t stride,
@@ -616,7 +621,7 @@ __global__ __launch_bounds__(256) void k_prefix_rows(Geom g, const int32_t* __re
   const int s = blockIdx.x, h = blockIdx.y;
   const int c0 = seq_chunk_off[s], c1 = seq_chunk_off[s + 1], nc = c1 - c0;
   auto chunk_at = [&](int pos) { return REVERSE ? c1 - 1 - pos : c0 + pos; };
-  const int item = blockIdx.z * 256 + threadIdx.x;  // (rbm, kd, lane)
+  const int item = blockIdx.z * kScanThreads + threadIdx.x;  // (rbm, kd, lane)
   const int lane = item % 64, kd = (item / 64) % NKD, rbm = item / (64 * NKD);
   const int rho = 32 * rbm + lane % 32, gl = lane / 32;
   const int m = cm.m[(rho >> 2) & 1][16 * (rho >> 5) + 4 * ((rho >> 3) & 3) + (rho & 3)];
@@ -1886,9 +1891,9 @@ hla_status backward_causal(hla_handle* hd, const hla_call_args& a) {
   const int relu_mask = hd->cfg.phi_mode == HLA_PHI_MLP ? 1 : 0;
   const CanonMap cm = make_canon_map<SY>();
   const int64_t stride = SL::kOpBytes, z_off = 2 * SL::kOpElems * 2, b_off = SL::kOpElems * 2;
-  const dim3 sgrid(a.num_seqs, g.H, 2 * (SY::MP / 16) * D / 256);
-  const dim3 rgrid(a.num_seqs, g.H, (SY::MP / 32) * (D / 16) * 64 / 256);
-  static_assert((SY::MP / 32) * (D / 16) * 64 % 256 == 0, "whole workgroups of row-image items");
+  const dim3 sgrid(a.num_seqs, g.H, 2 * (SY::MP / 16) * D / kScanThreads + 1);
+  const dim3 rgrid(a.num_seqs, g.H, (SY::MP / 32) * (D / 16) * 64 / kScanThreads);
+  static_assert((SY::MP / 32) * (D / 16) * 64 % kScanThreads == 0, "whole workgroups of row-image items");
   const float* nof = nullptr;
   using PL = PrefixLayout<SY, D>;
   const unsigned char* pfx = static_cast<unsigned char*>(hd->path_ws) + hd->causal_off;
@@ -1899,7 +1904,7 @@ hla_status backward_causal(hla_handle* hd, const hla_call_args& a) {
   if (!hd->causal_partials_valid)
     HLA_TRY(launch(hd, "mfma_state", k_state<SY, D>, dim3(cch->count, g.H), dim3(kThreads), SM::kTotal, s,
                    g, cch->dev, hd->feat, a.V, hd->partial, SL::kF32, l2d, nof, nof));
-  HLA_TRY(launch(hd, "mfma_state_prefix_rows", k_prefix_rows<SY, D, false>, rgrid, dim3(256), 0, s, g,
+  HLA_TRY(launch(hd, "mfma_state_prefix_rows", k_prefix_rows<SY, D, false>, rgrid, dim3(kScanThreads), 0, s, g,
                  cch->seq_off_dev, hd->partial, SL::kF32, ops, cm, chunk_decay, stride, b_off));
   HLA_TRY(launch(hd, "mfma_causal_grad_query", k_cgrad_q<SY, D>, dim3(cch->count, g.H), dim3(kThreads),
                  SG::kTotalQ, s, g, cch->dev, hd->feat, hd->den, a.V, a.dO,
@@ -1910,9 +1915,9 @@ hla_status backward_causal(hla_handle* hd, const hla_call_args& a) {
   HLA_TRY(launch(hd, "mfma_dstate", k_state<SY, D, 1>, dim3(cch->count, g.H), dim3(kThreads), SM::kTotal, s,
                  g, cch->dev, hd->feat, a.dO, hd->partial, SL::kF32, l2d, static_cast<const float*>(hd->den),
                  static_cast<const float*>(hd->yhat)));
-  HLA_TRY(launch(hd, "mfma_dstate_suffix", k_prefix<SY, D, true>, sgrid, dim3(256), 0, s, g, cch->seq_off_dev,
+  HLA_TRY(launch(hd, "mfma_dstate_suffix", k_prefix<SY, D, true>, sgrid, dim3(kScanThreads), 0, s, g, cch->seq_off_dev,
                  hd->partial, SL::kF32, dops, cm, chunk_decay, stride, z_off));
-  HLA_TRY(launch(hd, "mfma_dstate_suffix_rows", k_prefix_rows<SY, D, true>, rgrid, dim3(256), 0, s, g,
+  HLA_TRY(launch(hd, "mfma_dstate_suffix_rows", k_prefix_rows<SY, D, true>, rgrid, dim3(kScanThreads), 0, s, g,
                  cch->seq_off_dev, hd->partial, SL::kF32, dops, cm, chunk_decay, stride, b_off));
   HLA_TRY(launch(hd, "mfma_causal_grad_key", k_cgrad_k<SY, D>, dim3(cch->count, g.H), dim3(kThreads),
                  SG::kTotalK, s, g, cch->dev, hd->feat, hd->den, static_cast<const float*>(hd->yhat), a.V, a.dO,
@@ -1984,10 +1989,10 @@ hla_status forward_causal(hla_handle* hd, const hla_call_args& a) {
   HLA_TRY(launch(hd, "mfma_state", k_state<SY, D>, dim3(cch->count, g.H), dim3(kThreads), SM::kTotal, s,
                  g, cch->dev, hd->feat, a.V, hd->partial, SL::kF32, l2d, static_cast<const float*>(nullptr),
                  static_cast<const float*>(nullptr)));
-  static_assert(2 * (SY::MP / 16) * D % 256 == 0, "whole workgroups of prefix items");
+  static_assert(2 * (SY::MP / 16) * D % kScanThreads == 0, "whole workgroups of prefix items");
   using PL = PrefixLayout<SY, D>;
-  HLA_TRY(launch(hd, "mfma_state_prefix", k_prefix<SY, D, false>, dim3(a.num_seqs, g.H, 2 * (SY::MP / 16) * D / 256),
-                 dim3(256), 0, s, g, cch->seq_off_dev, hd->partial, SL::kF32, pfx, make_canon_map<SY>(), chunk_decay,
+  HLA_TRY(launch(hd, "mfma_state_prefix", k_prefix<SY, D, false>, dim3(a.num_seqs, g.H, 2 * (SY::MP / 16) * D / kScanThreads + 1),
+                 dim3(kScanThreads), 0, s, g, cch->seq_off_dev, hd->partial, SL::kF32, pfx, make_canon_map<SY>(), chunk_decay,
                  static_cast<int64_t>(PL::kBytes), static_cast<int64_t>(PL::kOpElems * 2)));
   HLA_TRY(launch(hd, "mfma_query_causal", k_query_causal<SY, D>, dim3(cch->count, g.H), dim3(kThreads),
                  SC::kTotal, s, g, cch->dev, hd->feat, a.V, pfx, a.O, hd->den, l2d));
