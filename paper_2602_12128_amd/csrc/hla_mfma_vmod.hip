@@ -153,6 +153,15 @@ __device__ __forceinline__ u32x4 load_global16(const void* p) {
   return *(gptr)(p);
 }
 
+// What the forward keeps of a 32-token tile for the backward: the normalised outputs u-hat of the
+// two maps in fp16, [map][piece][lane] 16 bytes (lane-private pieces: the backward's lane reads
+// what the forward's lane wrote), then the two 1/std per token, [map][lane] fp32.
+template <int D>
+struct SavedTile {
+  static constexpr int kUhat = 2 * (D / 16) * 1024;
+  static constexpr int kBytes = kUhat + 2 * 256;
+};
+
 struct TileWalk {
   int tiles_per_row, total, H;
   __device__ __forceinline__ void decode(int t, int& b, int& h, int& n0) const {
@@ -316,7 +325,8 @@ __device__ __forceinline__ void first_layer_offsets(int lane, int (&a_off)[D / 1
 // grid: one workgroup per compute unit, block WAVES*64.  Tin holds T; O receives T + phi_v1(T) * phi_v2(V).
 template <int D, int WAVES>
 __global__ __launch_bounds__(WAVES * 64) void k_vmod_fwd_mfma(Geom g, const unsigned char* __restrict__ wpk,
-                                                              float ln_eps, View Tin, View V, View O) {
+                                                              float ln_eps, View Tin, View V, View O,
+                                                              unsigned char* __restrict__ saved) {
   using SM = VSmem<D>;
   constexpr int NRB = D / 32, NKS = D / 16;
   extern __shared__ __align__(16) unsigned char smem[];
@@ -333,6 +343,21 @@ __global__ __launch_bounds__(WAVES * 64) void k_vmod_fwd_mfma(Geom g, const unsi
   tw.total = tw.tiles_per_row * g.B * g.H;
   tw.H = g.H;
   const int stride = gridDim.x * WAVES;
+  // u-hat and 1/std of map m for the backward (see SavedTile)
+  auto save = [&](int tile_index, int m, const f32x16 (&u)[NRB], float rstd) {
+    unsigned char* slot = saved + static_cast<int64_t>(tile_index) * SavedTile<D>::kBytes;
+#pragma unroll
+    for (int ob = 0; ob < NRB; ++ob)
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf) {
+        u32x4 v;
+#pragma unroll
+        for (int p = 0; p < 4; ++p)
+          v[p] = __builtin_bit_cast(uint32_t, to_f16x2(u[ob][8 * hf + 2 * p], u[ob][8 * hf + 2 * p + 1]));
+        __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(slot + (m * NKS + 2 * ob + hf) * 1024 + lane * 16));
+      }
+    *reinterpret_cast<float*>(slot + SavedTile<D>::kUhat + m * 256 + lane * 4) = rstd;
+  };
   // The value map runs first: its input rows were requested during the previous tile, the rows
   // of T are requested at the top of the tile and needed only after it, and the next tile's V
   // rows are requested once the value map is done with the registers -- no wait of the tile
@@ -355,6 +380,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_vmod_fwd_mfma(Geom g, const unsi
       f32x16 m2[NRB];
       float rstd;
       map_forward<D, false>(smem + SM::kMap, a_off, gl, xv, ln_eps, m2, none, rstd);
+      save(tile, 1, m2, rstd);
       const float* vec = reinterpret_cast<const float*>(smem + SM::kMap + SM::kVec);
 #pragma unroll
       for (int ob = 0; ob < NRB; ++ob) {
@@ -376,6 +402,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_vmod_fwd_mfma(Geom g, const unsi
     f32x16 m1[NRB];
     float rstd;
     map_forward<D, false>(smem, a_off, gl, xt, ln_eps, m1, none, rstd);
+    save(tile, 0, m1, rstd);
     __builtin_amdgcn_sched_barrier(0);
     u32x4 w[NRB][2];
     {
@@ -536,11 +563,13 @@ __device__ __forceinline__ void map_backward(const unsigned char* wm, const int 
 
 // grid: one workgroup per compute unit, block WAVES*64.
 //   dT  = dO + phi_v1'(T)^T (dO * phi_v2(V)),   dVm = phi_v2'(V)^T (dO * phi_v1(T));
-// both maps' forward values are recomputed.
+// the maps' normalised outputs come from the forward (SavedTile), the first layer is computed again
+// block by block for GELU'.
 template <int D, int WAVES>
 __global__ __launch_bounds__(WAVES * 64) void k_vmod_bwd_mfma(Geom g, const unsigned char* __restrict__ wpk,
                                                               float ln_eps, View Tin, View V, View dO,
-                                                              View dT, View dVm, unsigned char* stash) {
+                                                              View dT, View dVm,
+                                                              const unsigned char* __restrict__ saved) {
   using SM = VSmem<D>;
   constexpr int NRB = D / 32, NKS = D / 16;
   extern __shared__ __align__(16) unsigned char smem[];
@@ -573,48 +602,18 @@ __global__ __launch_bounds__(WAVES * 64) void k_vmod_bwd_mfma(Geom g, const unsi
   tw.total = tw.tiles_per_row * g.B * g.H;
   tw.H = g.H;
   const int stride = gridDim.x * WAVES;
-  // this wave's stash slot: [map][piece][lane] 16 bytes, addressed as a scalar base plus the
-  // lane's offset.  The read bases are the same address behind empty asm statements, so that the
-  // compiler treats the reads as real loads instead of keeping the stored registers alive (and
-  // does not merge the reads of the two passes of norm_backward).
-  unsigned char* slot_wr = stash + static_cast<size_t>(blockIdx.x * WAVES + wave) * (2 * NKS * 1024);
-  const unsigned char* slot_rd[2] = {slot_wr, slot_wr};
-  asm volatile("" : "+s"(slot_rd[0]));
-  asm volatile("" : "+s"(slot_rd[1]));
   const int lane16 = lane * 16;
-  auto put_stash = [&](int m, const f32x16 (&u)[NRB]) {
-#pragma unroll
-    for (int ob = 0; ob < NRB; ++ob)
-#pragma unroll
-      for (int hf = 0; hf < 2; ++hf) {
-        u32x4 v;
-#pragma unroll
-        for (int p = 0; p < 4; ++p)
-          v[p] = __builtin_bit_cast(uint32_t, to_f16x2(u[ob][8 * hf + 2 * p], u[ob][8 * hf + 2 * p + 1]));
-        *reinterpret_cast<u32x4*>(slot_wr + (m * NKS + 2 * ob + hf) * 1024 + lane16) = v;
-      }
-  };
-  f16x2 none[1][8];
   for (int tile = blockIdx.x * WAVES + wave; tile < tw.total; tile += stride) {
     int b, h, n0;
     tw.decode(tile, b, h, n0);
-    // Phase 1: both maps forward; their normalised outputs u-hat go, packed in fp16, to this
-    // wave's slot of the stash in global memory (lane-private 16-byte pieces, so a lane only ever
-    // reads back what it wrote itself): next to the accumulators of the products that follow
-    // they do not fit the register file.
-    float rstd1, rstd2;
-    {
-      u32x4 x[NKS], x2[NKS];
-      f32x16 u[NRB];
-      load_row<D>(Tin, b, h, n0 + r, g.N, gl, x);
-      load_row<D>(V, b, h, n0 + r, g.N, gl, x2);
-      map_forward<D, false>(smem, a_off, gl, x, ln_eps, u, none, rstd1);
-      put_stash(0, u);
-      __builtin_amdgcn_sched_barrier(0);
-      map_forward<D, false>(smem + SM::kMap, a_off, gl, x2, ln_eps, u, none, rstd2);
-      put_stash(1, u);
-    }
-    __builtin_amdgcn_sched_barrier(0);
+    // what the forward kept of this tile (SavedTile).  The two passes of norm_backward read through
+    // two copies of the address that the compiler cannot match, so that the second pass loads again
+    // instead of holding the first pass's registers.
+    const unsigned char* slot_rd[2] = {saved + static_cast<int64_t>(tile) * SavedTile<D>::kBytes, nullptr};
+    slot_rd[1] = slot_rd[0];
+    asm volatile("" : "+s"(slot_rd[1]));
+    const float rstd1 = *reinterpret_cast<const float*>(slot_rd[0] + SavedTile<D>::kUhat + lane * 4);
+    const float rstd2 = *reinterpret_cast<const float*>(slot_rd[0] + SavedTile<D>::kUhat + 256 + lane * 4);
     auto row_of = [&](const View& X) {
       return [&X, b, h, n0, &g](int t) -> bf16_t* { return n0 + t < g.N ? X.row<bf16_t>(b, h, n0 + t) : nullptr; };
     };
@@ -715,7 +714,7 @@ hla_status forward_t(hla_handle* hd, const hla_call_args& a) {
   const int grid = static_cast<int>(std::min<int64_t>(compute_units(), (tiles + kWavesV - 1) / kWavesV));
   return launch(hd, "vmod_forward", k_vmod_fwd_mfma<D, kWavesV>, dim3(grid), dim3(kWavesV * 64),
                 VSmem<D>::total(kWavesV), a.stream, g, static_cast<const unsigned char*>(hd->vmod_wpk),
-                hd->vmod_ln_eps, vmod_view(hd->vmod_T, g), a.V, a.O);
+                hd->vmod_ln_eps, vmod_view(hd->vmod_T, g), a.V, a.O, hd->vmod_wpk + vmod_mfma_packed_bytes(hd));
 }
 
 template <int D>
@@ -726,7 +725,8 @@ hla_status backward_t(hla_handle* hd, const hla_call_args& a) {
   return launch(hd, "vmod_backward", k_vmod_bwd_mfma<D, kWavesV>, dim3(grid), dim3(kWavesV * 64),
                 VSmem<D>::total(kWavesV), a.stream, g, static_cast<const unsigned char*>(hd->vmod_wpk),
                 hd->vmod_ln_eps, vmod_view(hd->vmod_T, g), a.V, a.dO, vmod_view(hd->vmod_dT, g),
-                vmod_view(hd->vmod_dV, g), hd->vmod_wpk + vmod_mfma_packed_bytes(hd));
+                vmod_view(hd->vmod_dV, g),
+                static_cast<const unsigned char*>(hd->vmod_wpk + vmod_mfma_packed_bytes(hd)));
 }
 
 template <int D>
@@ -745,9 +745,11 @@ bool vmod_mfma_supported(const hla_handle* hd) {
 size_t vmod_mfma_packed_bytes(const hla_handle* hd) {
   return 2 * static_cast<size_t>(hd->g.d == 64 ? VPacked<64>::kBytes : VPacked<128>::kBytes);
 }
-// packed weights, then the backward kernel's stash: one slot per wave of the largest grid
+// packed weights, then what the forward keeps for the backward: one SavedTile per 32-token tile
 size_t vmod_mfma_workspace_bytes(const hla_handle* hd) {
-  return vmod_mfma_packed_bytes(hd) + static_cast<size_t>(compute_units()) * kWavesV * 2 * (hd->g.d / 16) * 1024;
+  const int64_t tiles = hd->max_th / 32 + static_cast<int64_t>(hd->cfg.max_heads) * hd->cfg.max_seqs + 1;
+  const size_t per = hd->g.d == 64 ? SavedTile<64>::kBytes : SavedTile<128>::kBytes;
+  return vmod_mfma_packed_bytes(hd) + static_cast<size_t>(tiles) * per;
 }
 hla_status vmod_mfma_prepare_kernels(const hla_handle* hd) {
   return hd->g.d == 64 ? prepare_t<64>() : prepare_t<128>();
