@@ -439,8 +439,20 @@ __device__ __forceinline__ float norm_backward(const unsigned char* wm_self, con
                                                int gl, Load&& load, float rstd, u32x4 (&dub)[D / 16]) {
   using SM = VSmem<D>;
   constexpr int NKS = D / 16;
+  // a pass requests all its pieces before it looks at the first one: one memory round trip per
+  // pass instead of one per piece
+  u32x4 dd[NKS], ss[NKS], oo[NKS];
+  auto request = [&](int pass) {
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) {
+      dd[ks] = load(0, ks, pass);
+      ss[ks] = load(1, ks, pass);
+      oo[ks] = load(2, ks, pass);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  };
   auto piece = [&](int ks, int pass, int opaque, float (&gg)[8], float (&uh)[8]) {
-    const u32x4 d = load(0, ks, pass), s = load(1, ks, pass), o = load(2, ks, pass);
+    const u32x4 d = dd[ks], s = ss[ks], o = oo[ks];
     const float* vs = reinterpret_cast<const float*>(wm_self + SM::kVec) + opaque + 16 * ks + 8 * gl;
     const float* vo = reinterpret_cast<const float*>(wm_other + SM::kVec) + opaque + 16 * ks + 8 * gl;
 #pragma unroll
@@ -462,6 +474,7 @@ __device__ __forceinline__ float norm_backward(const unsigned char* wm_self, con
   float sa = 0.0f, sb = 0.0f, sc = 0.0f;
   int z1 = 0, z2 = 0;  // zeros the compiler cannot see through: the LDS vectors are read again, too
   asm volatile("" : "+s"(z1));
+  request(0);
 #pragma unroll
   for (int ks = 0; ks < NKS; ++ks) {
     float gg[8], uh[8];
@@ -481,6 +494,7 @@ __device__ __forceinline__ float norm_backward(const unsigned char* wm_self, con
   const float a = sa * (1.0f / D) * inv, bq = sb * (1.0f / D) * inv;
   asm volatile("" : "+s"(z2));
   __builtin_amdgcn_sched_barrier(0);
+  request(1);
 #pragma unroll
   for (int ks = 0; ks < NKS; ++ks) {
     float gg[8], uh[8];
