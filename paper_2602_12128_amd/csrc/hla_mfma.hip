@@ -1442,12 +1442,17 @@ template <int D>
 __device__ __forceinline__ f32x16 rows_product(const unsigned char* rt, int stride, int u, int lane,
                                                const u32x4 (&bown)[D / 16]) {
   const int r = lane % 32, gl = lane / 32;
+  // all operands are requested before the first MFMA: one exposed LDS round trip per product
+  u32x4 a[D / 16];
+#pragma unroll
+  for (int kd = 0; kd < D / 16; ++kd)
+    a[kd] = *reinterpret_cast<const u32x4*>(rt + (32 * u + r) * stride + (16 * kd + 8 * gl) * 2);
+  __builtin_amdgcn_sched_barrier(0);
   f32x16 E;
 #pragma unroll
   for (int i = 0; i < 16; ++i) E[i] = 0.0f;
 #pragma unroll
-  for (int kd = 0; kd < D / 16; ++kd)
-    E = mfma32(*reinterpret_cast<const u32x4*>(rt + (32 * u + r) * stride + (16 * kd + 8 * gl) * 2), bown[kd], E);
+  for (int kd = 0; kd < D / 16; ++kd) E = mfma32(a[kd], bown[kd], E);
   return E;
 }
 
@@ -1458,6 +1463,7 @@ template <int NB>
 __device__ __forceinline__ void transposed_product(const unsigned char* tile, int stride, int u, int lane,
                                                    const u32x4 (&b)[2], f32x16 (&acc)[NB]) {
   const int gl = lane / 32, L = lane % 16, q = lane / 16;
+  u32x4 a[2][NB];  // all operands are requested before the first MFMA
 #pragma unroll
   for (int ks2 = 0; ks2 < 2; ++ks2) {
     const int krow = 32 * u + 16 * ks2 + 4 * gl + L / 4;
@@ -1466,14 +1472,17 @@ __device__ __forceinline__ void transposed_product(const unsigned char* tile, in
       const unsigned char* p = tile + krow * stride + (32 * blk + 16 * (q % 2) + 4 * (L % 4)) * 2;
       const u32x2 lo = lds_read_tr16(p);
       const u32x2 hi = lds_read_tr16(p + 8 * stride);
-      u32x4 a;
-      a[0] = lo[0];
-      a[1] = lo[1];
-      a[2] = hi[0];
-      a[3] = hi[1];
-      acc[blk] = mfma32(a, b[ks2], acc[blk]);
+      a[ks2][blk][0] = lo[0];
+      a[ks2][blk][1] = lo[1];
+      a[ks2][blk][2] = hi[0];
+      a[ks2][blk][3] = hi[1];
     }
   }
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int ks2 = 0; ks2 < 2; ++ks2)
+#pragma unroll
+    for (int blk = 0; blk < NB; ++blk) acc[blk] = mfma32(a[ks2][blk], b[ks2], acc[blk]);
 }
 
 // grid (chunks of kCausalChunk tokens, H), block 256.  Query side: writes the query part of the
