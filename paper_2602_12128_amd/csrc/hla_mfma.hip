@@ -132,13 +132,16 @@ struct StateSmem {
 // with the QUERY monomials of the tokens, V = the dO rows, den / sv the saved denominators and
 // the s_i of the query-side kernel, w_i = decay^(i - t0 + 1) (the chunk as seen from the token in
 // front of it).
-template <class SY, int D, int MODE = 0>
+// PER_WAVE (the 256-token chunks of the causal scan): a wave serves a whole chunk of its own
+// (chunk blockIdx.x * 4 + wave of the `nchunks`) and writes its accumulators straight to the
+// chunk's partial, 128-byte runs per store: no sum over the waves, no barrier.
+template <class SY, int D, int MODE = 0, bool PER_WAVE = false>
 __global__ __launch_bounds__(kThreads) void k_state(Geom g, const BlockEnt* __restrict__ chunks,
                                                     const float* __restrict__ feat, View V,
                                                     float* __restrict__ partial,
                                                     int64_t partial_stride, float log2_decay,
-                                                    const float* __restrict__ den = nullptr,
-                                                    const float* __restrict__ sv = nullptr) {
+                                                    const float* __restrict__ den,
+                                                    const float* __restrict__ sv, int nchunks) {
   constexpr int DP = SY::DPHI, F = SY::F, MP = SY::MP;
   using SM = StateSmem<D, MP>;
   constexpr int NCB = D / 32;      // column blocks of the state
@@ -147,10 +150,13 @@ __global__ __launch_bounds__(kThreads) void k_state(Geom g, const BlockEnt* __re
   const int lane = threadIdx.x % kWave, wave = wave_index();
   unsigned char* vs = smem + wave * SM::kWaveBytes;
   unsigned char* ss = vs + SM::kVBytes;
-  const BlockEnt e = chunks[blockIdx.x];
+  const int chunk_index = PER_WAVE ? static_cast<int>(blockIdx.x) * kWaves + wave : static_cast<int>(blockIdx.x);
+  BlockEnt e = chunks[PER_WAVE && chunk_index >= nchunks ? 0 : chunk_index];
+  if (PER_WAVE && chunk_index >= nchunks) e.t1 = e.t0;  // no chunk for this wave
   const int h = blockIdx.y;
   const int gq = lane / 32;                   // MFMA operand coordinates
   const int L = lane % 16, q = lane / 16;
+  const int first = PER_WAVE ? e.t0 : e.t0 + wave * 64, step = PER_WAVE ? 64 : kWaves * 64;
 
   f32x16 acc[NRM][NCB];
   f32x16 zacc[NRM];
@@ -196,8 +202,8 @@ __global__ __launch_bounds__(kThreads) void k_state(Geom g, const BlockEnt* __re
       svf = 0.0f;
     }
   };
-  if (e.t0 + wave * 64 < e.t1) fetch(e.t0 + wave * 64);
-  for (int n0 = e.t0 + wave * 64; n0 < e.t1; n0 += kWaves * 64) {
+  if (first < e.t1) fetch(first);
+  for (int n0 = first; n0 < e.t1; n0 += step) {
     put_tile<D, 64>(vt, lane, vs, SM::kVStride);
     // ---- key monomials of token n0 + lane (all NM, canonical order), as bf16 row of the S tile
     {
@@ -221,7 +227,7 @@ __global__ __launch_bounds__(kThreads) void k_state(Geom g, const BlockEnt* __re
         if (log2_decay != 0.0f) scale1 *= __builtin_amdgcn_exp2f(log2_decay * static_cast<float>(n0 + lane - e.t0 + 1));
         tw = svf * dnf;
       }
-      if (n0 + kWaves * 64 < e.t1) fetch(n0 + kWaves * 64);
+      if (n0 + step < e.t1) fetch(n0 + step);
       float sm[SY::NM];
       if constexpr (MODE == 0) {
         sym_key_monomials_all<SY>(kk, sm);
@@ -286,6 +292,21 @@ __global__ __launch_bounds__(kThreads) void k_state(Geom g, const BlockEnt* __re
       for (int rb = 0; rb < NRM; ++rb) zacc[rb] = mfma32(a[rb], MODE == 1 ? tws[ks] : ones, zacc[rb]);
     }
     wave_lds_sync();
+  }
+  if constexpr (PER_WAVE) {
+    if (chunk_index >= nchunks) return;
+    float* out = partial + (static_cast<int64_t>(chunk_index) * g.H + h) * partial_stride;
+    const int r = lane % 32;
+#pragma unroll
+    for (int rb = 0; rb < NRM; ++rb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int row = 32 * rb + d_row(i, gq);
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb) out[row * D + 32 * cb + r] = acc[rb][cb][i];
+        if (r == 0) out[MP * D + row] = zacc[rb][i];
+      }
+    return;
   }
   // ---- sum the four waves through LDS, then write the partial state (rows = canonical monomials)
   float zl[MP / 2];
@@ -790,8 +811,14 @@ __global__ __launch_bounds__(kThreads) void k_query_causal(Geom g, const BlockEn
       f32x16 P;
 #pragma unroll
       for (int i = 0; i < 16; ++i) P[i] = 0.0f;
+      {
+        u32x4 sa[NKS];  // all operands requested before the first MFMA
 #pragma unroll
-      for (int ks = 0; ks < NKS; ++ks) P = mfma32(simg[(kt * NKS + ks) * 64 + lane], b[ks], P);
+        for (int ks = 0; ks < NKS; ++ks) sa[ks] = simg[(kt * NKS + ks) * 64 + lane];
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) P = mfma32(sa[ks], b[ks], P);
+      }
       if (log2_decay != 0.0f) {  // decay^(query position - key position); masked entries get 0 below
         const float base = static_cast<float>(32 * (qt - kt) + r);
 #pragma unroll
@@ -816,6 +843,7 @@ __global__ __launch_bounds__(kThreads) void k_query_causal(Geom g, const BlockEn
         }
       // O^T += V^T P: k-slot (ks2, gl, j) is key 16 ks2 + 8 (j / 4) + 4 gl + j % 4 of the tile, the
       // order in which the score accumulators hold the keys
+      u32x4 va[2][NRB];
 #pragma unroll
       for (int ks2 = 0; ks2 < 2; ++ks2) {
         const int krow = 32 * kt + 16 * ks2 + 4 * gl + L / 4;
@@ -824,14 +852,17 @@ __global__ __launch_bounds__(kThreads) void k_query_causal(Geom g, const BlockEn
           const unsigned char* p = vs + krow * SM::kVStride + (32 * rb + 16 * (q % 2) + 4 * (L % 4)) * 2;
           const u32x2 lo = lds_read_tr16(p);
           const u32x2 hi = lds_read_tr16(p + 8 * SM::kVStride);
-          u32x4 a;
-          a[0] = lo[0];
-          a[1] = lo[1];
-          a[2] = hi[0];
-          a[3] = hi[1];
-          acc[rb] = mfma32(a, pb[ks2], acc[rb]);
+          va[ks2][rb][0] = lo[0];
+          va[ks2][rb][1] = lo[1];
+          va[ks2][rb][2] = hi[0];
+          va[ks2][rb][3] = hi[1];
         }
       }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int ks2 = 0; ks2 < 2; ++ks2)
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb) acc[rb] = mfma32(va[ks2][rb], pb[ks2], acc[rb]);
     }
     eta += partner32(eta);
     const float dn = eta + g.eps;
@@ -1911,8 +1942,9 @@ hla_status backward_causal(hla_handle* hd, const hla_call_args& a) {
   // image by monomial rows.  A second backward after the same forward finds the partial buffer
   // holding gradient states and computes the chunk states again.
   if (!hd->causal_partials_valid)
-    HLA_TRY(launch(hd, "mfma_state", k_state<SY, D>, dim3(cch->count, g.H), dim3(kThreads), SM::kTotal, s,
-                   g, cch->dev, hd->feat, a.V, hd->partial, SL::kF32, l2d, nof, nof));
+    HLA_TRY(launch(hd, "mfma_state", k_state<SY, D, 0, true>, dim3((cch->count + kWaves - 1) / kWaves, g.H),
+                   dim3(kThreads), SM::kTotal, s, g, cch->dev, hd->feat, a.V, hd->partial, SL::kF32, l2d, nof, nof,
+                   cch->count));
   HLA_TRY(launch(hd, "mfma_state_prefix_rows", k_prefix_rows<SY, D, false>, rgrid, dim3(kScanThreads), 0, s, g,
                  cch->seq_off_dev, hd->partial, SL::kF32, ops, cm, chunk_decay, stride, b_off));
   HLA_TRY(launch(hd, "mfma_causal_grad_query", k_cgrad_q<SY, D>, dim3(cch->count, g.H), dim3(kThreads),
@@ -1921,9 +1953,9 @@ hla_status backward_causal(hla_handle* hd, const hla_call_args& a) {
                  pfx + PL::kOpElems * 2, static_cast<int64_t>(PL::kBytes), hd->dfeat, hd->yhat, l2d, relu_mask));
   hd->causal_partials_valid = false;
   // gradient states of the chunks, summed from the back
-  HLA_TRY(launch(hd, "mfma_dstate", k_state<SY, D, 1>, dim3(cch->count, g.H), dim3(kThreads), SM::kTotal, s,
-                 g, cch->dev, hd->feat, a.dO, hd->partial, SL::kF32, l2d, static_cast<const float*>(hd->den),
-                 static_cast<const float*>(hd->yhat)));
+  HLA_TRY(launch(hd, "mfma_dstate", k_state<SY, D, 1, true>, dim3((cch->count + kWaves - 1) / kWaves, g.H),
+                 dim3(kThreads), SM::kTotal, s, g, cch->dev, hd->feat, a.dO, hd->partial, SL::kF32, l2d,
+                 static_cast<const float*>(hd->den), static_cast<const float*>(hd->yhat), cch->count));
   HLA_TRY(launch(hd, "mfma_dstate_suffix", k_prefix<SY, D, true>, sgrid, dim3(kScanThreads), 0, s, g, cch->seq_off_dev,
                  hd->partial, SL::kF32, dops, cm, chunk_decay, stride, z_off));
   HLA_TRY(launch(hd, "mfma_dstate_suffix_rows", k_prefix_rows<SY, D, true>, rgrid, dim3(kScanThreads), 0, s, g,
@@ -1970,7 +2002,7 @@ hla_status forward_core(hla_handle* hd, const hla_call_args& a) {
   if (static_cast<int64_t>(chunks->count) * g.H > hd->max_chunks * hd->cfg.max_heads)
     return HLA_ERR_INVALID_ARG;
   HLA_TRY(launch(hd, "mfma_state", k_state<SY, D>, dim3(chunks->count, g.H), dim3(kThreads),
-                 SM::kTotal, s, g, chunks->dev, hd->feat, a.V, hd->partial, SL::kF32, 0.0f, static_cast<const float*>(nullptr), static_cast<const float*>(nullptr)));
+                 SM::kTotal, s, g, chunks->dev, hd->feat, a.V, hd->partial, SL::kF32, 0.0f, static_cast<const float*>(nullptr), static_cast<const float*>(nullptr), 0));
   const SlotMap sm = make_slot_map<SY>();
   unsigned char* ops = static_cast<unsigned char*>(hd->path_ws);
   HLA_TRY(launch(hd, "mfma_state_reduce", k_reduce<SY, D, false>, dim3(a.num_seqs, g.H, kReduceSlices),
@@ -1995,9 +2027,9 @@ hla_status forward_causal(hla_handle* hd, const hla_call_args& a) {
   const float dec = hd->cfg.decay > 0.0f && hd->cfg.decay < 1.0f ? hd->cfg.decay : 1.0f;
   const float l2d = dec < 1.0f ? std::log2(dec) : 0.0f;
   const float chunk_decay = dec < 1.0f ? std::pow(dec, static_cast<float>(kCausalChunk)) : 1.0f;
-  HLA_TRY(launch(hd, "mfma_state", k_state<SY, D>, dim3(cch->count, g.H), dim3(kThreads), SM::kTotal, s,
-                 g, cch->dev, hd->feat, a.V, hd->partial, SL::kF32, l2d, static_cast<const float*>(nullptr),
-                 static_cast<const float*>(nullptr)));
+  HLA_TRY(launch(hd, "mfma_state", k_state<SY, D, 0, true>, dim3((cch->count + kWaves - 1) / kWaves, g.H),
+                 dim3(kThreads), SM::kTotal, s, g, cch->dev, hd->feat, a.V, hd->partial, SL::kF32, l2d,
+                 static_cast<const float*>(nullptr), static_cast<const float*>(nullptr), cch->count));
   static_assert(2 * (SY::MP / 16) * D % kScanThreads == 0, "whole workgroups of prefix items");
   using PL = PrefixLayout<SY, D>;
   HLA_TRY(launch(hd, "mfma_state_prefix", k_prefix<SY, D, false>, dim3(a.num_seqs, g.H, 2 * (SY::MP / 16) * D / kScanThreads + 1),
@@ -2014,7 +2046,8 @@ hla_status prepare_core() {
   HLA_TRY(allow_big_lds(&k_query_causal<SY, D>, CausalSmem<SY, D>::kTotal));
   HLA_TRY(allow_big_lds(&k_cgrad_q<SY, D>, CgSmem<SY, D>::kTotalQ));
   HLA_TRY(allow_big_lds(&k_cgrad_k<SY, D>, CgSmem<SY, D>::kTotalK));
-  HLA_TRY(allow_big_lds(&k_state<SY, D, 1>, StateSmem<D, SY::MP>::kTotal));
+  HLA_TRY(allow_big_lds(&k_state<SY, D, 0, true>, StateSmem<D, SY::MP>::kTotal));
+  HLA_TRY(allow_big_lds(&k_state<SY, D, 1, true>, StateSmem<D, SY::MP>::kTotal));
   HLA_TRY(allow_big_lds(&k_state<SY, D>, StateSmem<D, SY::MP>::kTotal));
   return allow_big_lds(&k_bwd_query<SY, D>, BwdQSmem<D, SY::MP>::kTotal);
 }
