@@ -545,20 +545,20 @@ CanonMap make_canon_map() {
 // `stride` bytes apart, the normaliser vector z_off bytes into an image.
 constexpr int kScanThreads = 64;  // one wave per workgroup: the scans are a few thousand threads in all, spread over as many compute units as possible
 template <class SY, int D, bool REVERSE>
-__global__ __launch_bounds__(kScanThreads) void k_prefix(Geom g, const int32_t* __restrict__ seq_chunk_off,
-                                                const float* __restrict__ partial,
-                                                int64_t partial_stride, unsigned char* __restrict__ pfx,
-                                                CanonMap cm, float chunk_decay, int64_t stride,
-                                                int64_t z_off) {
+__device__ __forceinline__ void prefix_body(int zidx, int zcount, const Geom& g,
+                                            const int32_t* __restrict__ seq_chunk_off,
+                                            const float* __restrict__ partial, int64_t partial_stride,
+                                            unsigned char* __restrict__ pfx, const CanonMap& cm,
+                                            float chunk_decay, int64_t stride, int64_t z_off) {
   constexpr int MP = SY::MP, SP = SY::SP, NKS = MP / 16;
   const int s = blockIdx.x, h = blockIdx.y;
   const int c0 = seq_chunk_off[s], c1 = seq_chunk_off[s + 1], nc = c1 - c0;
   auto chunk_at = [&](int pos) { return REVERSE ? c1 - 1 - pos : c0 + pos; };  // pos-th chunk in scan order
   // the last workgroup in z carries the normaliser vector (one thread per eight slots), the others
   // the operand image
-  const bool zblock = blockIdx.z == gridDim.z - 1;
+  const bool zblock = zidx == zcount - 1;
   if (zblock && threadIdx.x >= 2 * NKS) return;
-  const int item = zblock ? threadIdx.x * D : blockIdx.z * kScanThreads + threadIdx.x;  // (mg, ks, c)
+  const int item = zblock ? threadIdx.x * D : zidx * kScanThreads + threadIdx.x;  // (mg, ks, c)
   const int c = item % D, ks = (item / D) % NKS, mg = item / (D * NKS);
   const float* base = partial + static_cast<int64_t>(h) * partial_stride + c;
   const int64_t cstride = static_cast<int64_t>(g.H) * partial_stride;
@@ -633,16 +633,16 @@ __global__ __launch_bounds__(kScanThreads) void k_prefix(Geom g, const int32_t* 
 // grid (num_seqs, H, (MP / 32) * (D / 16) * 64 / kScanThreads), block kScanThreads; a thread owns eight consecutive
 // channels of one row; the image starts `img_off` bytes into a chunk's block.
 template <class SY, int D, bool REVERSE>
-__global__ __launch_bounds__(kScanThreads) void k_prefix_rows(Geom g, const int32_t* __restrict__ seq_chunk_off,
-                                                     const float* __restrict__ partial,
-                                                     int64_t partial_stride, unsigned char* __restrict__ pfx,
-                                                     CanonMap cm, float chunk_decay, int64_t stride,
-                                                     int64_t img_off) {
+__device__ __forceinline__ void prefix_rows_body(int zidx, const Geom& g,
+                                                 const int32_t* __restrict__ seq_chunk_off,
+                                                 const float* __restrict__ partial, int64_t partial_stride,
+                                                 unsigned char* __restrict__ pfx, const CanonMap& cm,
+                                                 float chunk_decay, int64_t stride, int64_t img_off) {
   constexpr int NKD = D / 16;
   const int s = blockIdx.x, h = blockIdx.y;
   const int c0 = seq_chunk_off[s], c1 = seq_chunk_off[s + 1], nc = c1 - c0;
   auto chunk_at = [&](int pos) { return REVERSE ? c1 - 1 - pos : c0 + pos; };
-  const int item = blockIdx.z * kScanThreads + threadIdx.x;  // (rbm, kd, lane)
+  const int item = zidx * kScanThreads + threadIdx.x;  // (rbm, kd, lane)
   const int lane = item % 64, kd = (item / 64) % NKD, rbm = item / (64 * NKD);
   const int rho = 32 * rbm + lane % 32, gl = lane / 32;
   const int m = cm.m[(rho >> 2) & 1][16 * (rho >> 5) + 4 * ((rho >> 3) & 3) + (rho & 3)];
@@ -674,6 +674,40 @@ __global__ __launch_bounds__(kScanThreads) void k_prefix_rows(Geom g, const int3
       }
     }
   }
+}
+
+template <class SY, int D, bool REVERSE>
+__global__ __launch_bounds__(kScanThreads) void k_prefix(Geom g, const int32_t* __restrict__ seq_chunk_off,
+                                                         const float* __restrict__ partial,
+                                                         int64_t partial_stride, unsigned char* __restrict__ pfx,
+                                                         CanonMap cm, float chunk_decay, int64_t stride,
+                                                         int64_t z_off) {
+  prefix_body<SY, D, REVERSE>(blockIdx.z, gridDim.z, g, seq_chunk_off, partial, partial_stride, pfx, cm,
+                              chunk_decay, stride, z_off);
+}
+template <class SY, int D, bool REVERSE>
+__global__ __launch_bounds__(kScanThreads) void k_prefix_rows(Geom g, const int32_t* __restrict__ seq_chunk_off,
+                                                              const float* __restrict__ partial,
+                                                              int64_t partial_stride, unsigned char* __restrict__ pfx,
+                                                              CanonMap cm, float chunk_decay, int64_t stride,
+                                                              int64_t img_off) {
+  prefix_rows_body<SY, D, REVERSE>(blockIdx.z, g, seq_chunk_off, partial, partial_stride, pfx, cm, chunk_decay,
+                                   stride, img_off);
+}
+// both images in one launch: the first `za` workgroups in z carry the image by channels and the
+// normaliser, the rest the image by monomial rows
+template <class SY, int D, bool REVERSE>
+__global__ __launch_bounds__(kScanThreads) void k_prefix_both(Geom g, const int32_t* __restrict__ seq_chunk_off,
+                                                              const float* __restrict__ partial,
+                                                              int64_t partial_stride, unsigned char* __restrict__ pfx,
+                                                              CanonMap cm, float chunk_decay, int64_t stride,
+                                                              int64_t z_off, int64_t img_off, int za) {
+  if (static_cast<int>(blockIdx.z) < za)
+    prefix_body<SY, D, REVERSE>(blockIdx.z, za, g, seq_chunk_off, partial, partial_stride, pfx, cm, chunk_decay,
+                                stride, z_off);
+  else
+    prefix_rows_body<SY, D, REVERSE>(blockIdx.z - za, g, seq_chunk_off, partial, partial_stride, pfx, cm,
+                                     chunk_decay, stride, img_off);
 }
 
 template <class SY, int D>
@@ -1956,10 +1990,9 @@ hla_status backward_causal(hla_handle* hd, const hla_call_args& a) {
   HLA_TRY(launch(hd, "mfma_dstate", k_state<SY, D, 1, true>, dim3((cch->count + kWaves - 1) / kWaves, g.H),
                  dim3(kThreads), SM::kTotal, s, g, cch->dev, hd->feat, a.dO, hd->partial, SL::kF32, l2d,
                  static_cast<const float*>(hd->den), static_cast<const float*>(hd->yhat), cch->count));
-  HLA_TRY(launch(hd, "mfma_dstate_suffix", k_prefix<SY, D, true>, sgrid, dim3(kScanThreads), 0, s, g, cch->seq_off_dev,
-                 hd->partial, SL::kF32, dops, cm, chunk_decay, stride, z_off));
-  HLA_TRY(launch(hd, "mfma_dstate_suffix_rows", k_prefix_rows<SY, D, true>, rgrid, dim3(kScanThreads), 0, s, g,
-                 cch->seq_off_dev, hd->partial, SL::kF32, dops, cm, chunk_decay, stride, b_off));
+  HLA_TRY(launch(hd, "mfma_dstate_suffix", k_prefix_both<SY, D, true>, dim3(a.num_seqs, g.H, sgrid.z + rgrid.z),
+                 dim3(kScanThreads), 0, s, g, cch->seq_off_dev, hd->partial, SL::kF32, dops, cm, chunk_decay, stride,
+                 z_off, b_off, static_cast<int>(sgrid.z)));
   HLA_TRY(launch(hd, "mfma_causal_grad_key", k_cgrad_k<SY, D>, dim3(cch->count, g.H), dim3(kThreads),
                  SG::kTotalK, s, g, cch->dev, hd->feat, hd->den, static_cast<const float*>(hd->yhat), a.V, a.dO,
                  dops, hd->dfeat, a.dV, l2d, relu_mask));
