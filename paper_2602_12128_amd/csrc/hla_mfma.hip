@@ -785,6 +785,10 @@ __global__ __launch_bounds__(kThreads) void k_query_causal(Geom g, const BlockEn
     }
   }
   __syncthreads();
+  float rowfac[16];  // decay^(31 - key row of accumulator register i)
+#pragma unroll
+  for (int i = 0; i < 16; ++i)
+    rowfac[i] = log2_decay != 0.0f ? __builtin_amdgcn_exp2f(log2_decay * static_cast<float>(31 - d_row(i, gl))) : 1.0f;
   const unsigned char* pu = pfx + (static_cast<int64_t>(blockIdx.x) * g.H + h) * PL::kBytes;
   const u32x4* opA = reinterpret_cast<const u32x4*>(pu);
   const float* zslot = reinterpret_cast<const float*>(pu + PL::kOpElems * 2) + gl * SP;
@@ -854,11 +858,14 @@ __global__ __launch_bounds__(kThreads) void k_query_causal(Geom g, const BlockEn
         for (int ks = 0; ks < NKS; ++ks) P = mfma32(sa[ks], b[ks], P);
       }
       if (log2_decay != 0.0f) {  // decay^(query position - key position); masked entries get 0 below
-        const float base = static_cast<float>(32 * (qt - kt) + r);
+        if (kt < qt) {  // distance >= 1: a per-lane factor times a per-register one (both at most 1)
+          const float cw = __builtin_amdgcn_exp2f(log2_decay * static_cast<float>(32 * (qt - kt) + r - 31));
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const float dist = base - static_cast<float>(d_row(i, gl));
-          P[i] *= __builtin_amdgcn_exp2f(log2_decay * fmaxf(dist, 0.0f));
+          for (int i = 0; i < 16; ++i) P[i] *= cw * rowfac[i];
+        } else {
+#pragma unroll
+          for (int i = 0; i < 16; ++i)
+            P[i] *= __builtin_amdgcn_exp2f(log2_decay * fmaxf(static_cast<float>(r - d_row(i, gl)), 0.0f));
         }
       }
       if (kt == qt) {  // key d_row(i, gl) of the tile against query r: later keys are masked
@@ -1610,6 +1617,12 @@ __global__ __launch_bounds__(kThreads) void k_cgrad_q(Geom g, const BlockEnt* __
     put_monomials<SY>(mt, SM::kMStride, 32 * t + r, gl, sm, 1.0f);
   }
   __syncthreads();
+  // decay^(31 - key row of accumulator register i): the per-register part of an off-diagonal
+  // tile's weights (at most 1; 1 without decay)
+  float rowfac[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i)
+    rowfac[i] = log2_decay != 0.0f ? __builtin_amdgcn_exp2f(log2_decay * static_cast<float>(31 - d_row(i, gl))) : 1.0f;
   const int64_t ch_h = static_cast<int64_t>(blockIdx.x) * g.H + h;
   const u32x4* opB = reinterpret_cast<const u32x4*>(rows_img + ch_h * rows_stride);
   const float* zslot = reinterpret_cast<const float*>(z_img + ch_h * z_stride) + gl * SP;
@@ -1678,21 +1691,37 @@ __global__ __launch_bounds__(kThreads) void k_cgrad_q(Geom g, const BlockEnt* __
 #pragma unroll 1
     for (int kt = 0; kt <= qt; ++kt) {
       const f32x16 E = rows_product<D>(rt, SM::kRStride, kt, lane, bdo);
+      // weights of the tile's entries (key d_row(i, gl) of tile kt against query r): 1 in front of
+      // the diagonal tile, there 0 behind the query; with a decay factor decay^(distance), which
+      // in front of the diagonal tile (distance >= 1) factors into a per-lane and a per-register
+      // part
       u32x4 bE[2], bW[2];
-      const float base = static_cast<float>(32 * (qt - kt) + r);
+      if (kt < qt) {
+        const float cw = log2_decay != 0.0f ? __builtin_amdgcn_exp2f(log2_decay * static_cast<float>(32 * (qt - kt) + r - 31)) : 1.0f;
 #pragma unroll
-      for (int ks2 = 0; ks2 < 2; ++ks2)
+        for (int ks2 = 0; ks2 < 2; ++ks2)
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
-          float wv[2];
-#pragma unroll
-          for (int x = 0; x < 2; ++x) {
-            const float dist = base - static_cast<float>(d_row(8 * ks2 + 2 * p + x, gl));
-            wv[x] = dist < 0.0f ? 0.0f : (log2_decay != 0.0f ? __builtin_amdgcn_exp2f(log2_decay * dist) : 1.0f);
+          for (int p = 0; p < 4; ++p) {
+            const int i = 8 * ks2 + 2 * p;
+            const float w0 = cw * rowfac[i], w1 = cw * rowfac[i + 1];
+            bE[ks2][p] = pack_bf16(E[i] * w0, E[i + 1] * w1);
+            bW[ks2][p] = pack_bf16(w0, w1);
           }
-          bE[ks2][p] = pack_bf16(E[8 * ks2 + 2 * p] * wv[0], E[8 * ks2 + 2 * p + 1] * wv[1]);
-          bW[ks2][p] = pack_bf16(wv[0], wv[1]);
-        }
+      } else {
+#pragma unroll
+        for (int ks2 = 0; ks2 < 2; ++ks2)
+#pragma unroll
+          for (int p = 0; p < 4; ++p) {
+            float wv[2];
+#pragma unroll
+            for (int x = 0; x < 2; ++x) {
+              const float dist = static_cast<float>(r - d_row(8 * ks2 + 2 * p + x, gl));
+              wv[x] = dist < 0.0f ? 0.0f : (log2_decay != 0.0f ? __builtin_amdgcn_exp2f(log2_decay * dist) : 1.0f);
+            }
+            bE[ks2][p] = pack_bf16(E[8 * ks2 + 2 * p] * wv[0], E[8 * ks2 + 2 * p + 1] * wv[1]);
+            bW[ks2][p] = pack_bf16(wv[0], wv[1]);
+          }
+      }
       transposed_product<NRM>(mt, SM::kMStride, kt, lane, bE, X);
       transposed_product<NRM>(mt, SM::kMStride, kt, lane, bW, Z);
     }
@@ -1782,6 +1811,12 @@ __global__ __launch_bounds__(kThreads) void k_cgrad_k(Geom g, const BlockEnt* __
     if (gl == 0) tq[32 * t + r] = live ? sv[th] * dn : 0.0f;
   }
   __syncthreads();
+  // decay^(query row of accumulator register i): the per-register part of an off-diagonal tile's
+  // weights (1 without decay)
+  float rowfac[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i)
+    rowfac[i] = log2_decay != 0.0f ? __builtin_amdgcn_exp2f(log2_decay * static_cast<float>(d_row(i, gl))) : 1.0f;
   const unsigned char* pu = dops + (static_cast<int64_t>(blockIdx.x) * g.H + h) * SL::kOpBytes;
   const u32x4* opA = reinterpret_cast<const u32x4*>(pu);
   const u32x4* opB = reinterpret_cast<const u32x4*>(pu + SL::kOpElems * 2);
@@ -1884,20 +1919,27 @@ __global__ __launch_bounds__(kThreads) void k_cgrad_k(Geom g, const BlockEnt* __
         a[3] = hi[1];
         A = mfma32(a, bS[ks], A);
       }
+      // weights of the tile's entries (query d_row(i, gl) of tile qt against key r): 1 behind the
+      // diagonal tile, there 0 for queries in front of the key; with a decay factor
+      // decay^(distance), factored behind the diagonal tile (distance >= 1) as on the query side
       u32x4 bE[2], bA[2];
-      const float base = static_cast<float>(32 * (qt - kt) - r);
 #pragma unroll
       for (int ks2 = 0; ks2 < 2; ++ks2) {
         const f32x4 t0 = *reinterpret_cast<const f32x4*>(tq + 32 * qt + 16 * ks2 + 4 * gl);
         const f32x4 t1 = *reinterpret_cast<const f32x4*>(tq + 32 * qt + 16 * ks2 + 4 * gl + 8);
+        const float cw = qt > kt && log2_decay != 0.0f ? __builtin_amdgcn_exp2f(log2_decay * static_cast<float>(32 * (qt - kt) - r)) : 1.0f;
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
           float wv[2], tv[2];
 #pragma unroll
           for (int x = 0; x < 2; ++x) {
             const int i = 8 * ks2 + 2 * p + x;  // query d_row(i, gl) = 16 ks2 + 8 (p / 2) + 4 gl + (2 p + x) % 4
-            const float dist = base + static_cast<float>(d_row(i, gl));
-            wv[x] = dist < 0.0f ? 0.0f : (log2_decay != 0.0f ? __builtin_amdgcn_exp2f(log2_decay * dist) : 1.0f);
+            if (qt > kt) {
+              wv[x] = cw * rowfac[i];
+            } else {
+              const float dist = static_cast<float>(d_row(i, gl) - r);
+              wv[x] = dist < 0.0f ? 0.0f : (log2_decay != 0.0f ? __builtin_amdgcn_exp2f(log2_decay * dist) : 1.0f);
+            }
             tv[x] = p < 2 ? t0[(2 * p + x) % 4] : t1[(2 * p + x) % 4];
           }
           bE[ks2][p] = pack_bf16((E[8 * ks2 + 2 * p] + tv[0]) * wv[0], (E[8 * ks2 + 2 * p + 1] + tv[1]) * wv[1]);
