@@ -23,6 +23,17 @@ constexpr int kWaves = kThreads / kWave;
 constexpr int kQueryTarget = 496;  // workgroups aimed at by the query kernel: two per CU, one resident round
 constexpr int kMinChunk = 256;     // smallest chunk pick_chunk returns
 constexpr int kCausalChunk = 256;  // tokens per chunk of the causal scan
+// The chunk kernels give every wave kChunkTilesPerWave 32-token tiles of its own side.  (128-token
+// chunks, one tile per wave and two workgroups per compute unit, were measured: the tile kernels
+// gain 20-25 % -- a token meets 2.5 tiles of its chunk instead of 4.5 -- but the scans, serial in
+// the number of chunks, lose twice that.)
+constexpr int kChunkRowsPerWave = kCausalChunk / 4;
+constexpr int kChunkTilesPerWave = kCausalChunk / 32 / 4;
+static_assert(kChunkRowsPerWave == 32 || kChunkRowsPerWave == 64, "row staging covers 32 or 64 rows per wave");
+// tile `i` of wave `w`: with two tiles per wave, w and its mirror image (equal shares of the triangle)
+__device__ __forceinline__ int chunk_tile_of(int w, int i) {
+  return kChunkTilesPerWave == 1 ? w : (i == 0 ? w : kCausalChunk / 32 - 1 - w);
+}
 constexpr int kMinQueryBlock = 128;  // smallest block pick_query_block returns
 constexpr int kChunkTarget = 256;  // workgroups aimed at by the chunked (token-contraction) kernels: one per CU
 constexpr int kChunkGrain = 64;    // chunk sizes are multiples of this many tokens (one wave step of k_state)
@@ -717,7 +728,8 @@ struct CausalSmem {
   static constexpr int kVStride = D * 2 + 32;                  // bytes per token row of the V tile
   static constexpr int kVBytes = kCausalChunk * kVStride;
   static constexpr int kSBytes = kTiles * NKS * 64 * 16;       // key-monomial operand images of the chunk
-  static constexpr int kTotal = kVBytes + kSBytes + kWaves * RowTile<D>::kBytes;
+  static constexpr int kOutRows = kCausalChunk >= 256 ? 32 : 16;  // rows of a wave's store tile
+  static constexpr int kTotal = kVBytes + kSBytes + kWaves * RowTile<D, kOutRows>::kBytes;
 };
 
 // grid (chunks of kCausalChunk tokens, H), block 256.  The workgroup stages the chunk's V rows and
@@ -737,20 +749,20 @@ __global__ __launch_bounds__(kThreads) void k_query_causal(Geom g, const BlockEn
   const int lane = threadIdx.x % kWave, wave = wave_index();
   unsigned char* vs = smem;
   u32x4* simg = reinterpret_cast<u32x4*>(smem + SM::kVBytes);
-  unsigned char* tile = smem + SM::kVBytes + SM::kSBytes + wave * RowTile<D>::kBytes;
+  unsigned char* tile = smem + SM::kVBytes + SM::kSBytes + wave * RowTile<D, SM::kOutRows>::kBytes;
   const int r = lane % 32, gl = lane / 32;
   const int L = lane % 16, q = lane / 16;
   const BlockEnt e = chunks[blockIdx.x];
   const int h = blockIdx.y;
-  // ---- the chunk's V rows (64 per wave) and key-monomial images (two key tiles per wave)
+  // ---- the chunk's V rows and key-monomial images, an equal share per wave
   {
-    TileRegs<D, 64> vt;
-    fetch_tile<D, 64>(V, e.b, h, e.t0 + 64 * wave, e.t1, lane, vt);
-    put_tile<D, 64>(vt, lane, vs + 64 * wave * SM::kVStride, SM::kVStride);
+    TileRegs<D, kChunkRowsPerWave> vt;
+    fetch_tile<D, kChunkRowsPerWave>(V, e.b, h, e.t0 + kChunkRowsPerWave * wave, e.t1, lane, vt);
+    put_tile<D, kChunkRowsPerWave>(vt, lane, vs + kChunkRowsPerWave * wave * SM::kVStride, SM::kVStride);
   }
 #pragma unroll 1
-  for (int tt = 0; tt < 2; ++tt) {
-    const int t = 2 * wave + tt;
+  for (int tt = 0; tt < kChunkTilesPerWave; ++tt) {
+    const int t = kChunkTilesPerWave * wave + tt;
     const int n = e.t0 + 32 * t + r;
     float kf[NF], kr[NF];
     if (n < e.t1) {
@@ -793,8 +805,8 @@ __global__ __launch_bounds__(kThreads) void k_query_causal(Geom g, const BlockEn
   const u32x4* opA = reinterpret_cast<const u32x4*>(pu);
   const float* zslot = reinterpret_cast<const float*>(pu + PL::kOpElems * 2) + gl * SP;
 #pragma unroll 1
-  for (int qi = 0; qi < 2; ++qi) {
-    const int qt = qi == 0 ? wave : SM::kTiles - 1 - wave;
+  for (int qi = 0; qi < kChunkTilesPerWave; ++qi) {
+    const int qt = chunk_tile_of(wave, qi);
     const int n0 = e.t0 + 32 * qt;
     if (n0 >= e.t1) continue;
     const int n = n0 + r;
@@ -909,7 +921,7 @@ __global__ __launch_bounds__(kThreads) void k_query_causal(Geom g, const BlockEn
     const float dn = eta + g.eps;
     const float inv = 1.0f / dn;
     if (live && gl == 0) den[g.th(e.b, h, n)] = dn;
-    store_rows_bf16<D>(acc, inv, lane, tile, [&](int t) -> bf16_t* {
+    store_rows_bf16<D, SM::kOutRows>(acc, inv, lane, tile, [&](int t) -> bf16_t* {
       return n0 + t < e.t1 ? O.row<bf16_t>(e.b, h, n0 + t) : nullptr;
     });
   }
@@ -1582,13 +1594,13 @@ __global__ __launch_bounds__(kThreads) void k_cgrad_q(Geom g, const BlockEnt* __
   const int h = blockIdx.y;
   // ---- the chunk's V rows (64 per wave) and key monomials (two tiles per wave)
   {
-    TileRegs<D, 64> vt;
-    fetch_tile<D, 64>(V, e.b, h, e.t0 + 64 * wave, e.t1, lane, vt);
-    put_tile<D, 64>(vt, lane, rt + 64 * wave * SM::kRStride, SM::kRStride);
+    TileRegs<D, kChunkRowsPerWave> vt;
+    fetch_tile<D, kChunkRowsPerWave>(V, e.b, h, e.t0 + kChunkRowsPerWave * wave, e.t1, lane, vt);
+    put_tile<D, kChunkRowsPerWave>(vt, lane, rt + kChunkRowsPerWave * wave * SM::kRStride, SM::kRStride);
   }
 #pragma unroll 1
-  for (int tt = 0; tt < 2; ++tt) {
-    const int t = 2 * wave + tt;
+  for (int tt = 0; tt < kChunkTilesPerWave; ++tt) {
+    const int t = kChunkTilesPerWave * wave + tt;
     const int n = e.t0 + 32 * t + r;
     float kf[NF], kr[NF];
     if (n < e.t1) {
@@ -1627,8 +1639,8 @@ __global__ __launch_bounds__(kThreads) void k_cgrad_q(Geom g, const BlockEnt* __
   const u32x4* opB = reinterpret_cast<const u32x4*>(rows_img + ch_h * rows_stride);
   const float* zslot = reinterpret_cast<const float*>(z_img + ch_h * z_stride) + gl * SP;
 #pragma unroll 1
-  for (int qi = 0; qi < 2; ++qi) {
-    const int qt = qi == 0 ? wave : SM::kTiles - 1 - wave;
+  for (int qi = 0; qi < kChunkTilesPerWave; ++qi) {
+    const int qt = chunk_tile_of(wave, qi);
     const int n0 = e.t0 + 32 * qt;
     if (n0 >= e.t1) continue;
     const int n = n0 + r;
@@ -1784,13 +1796,13 @@ __global__ __launch_bounds__(kThreads) void k_cgrad_k(Geom g, const BlockEnt* __
   const int h = blockIdx.y;
   // ---- the chunk's dO rows (64 per wave), scaled query monomials Qm / den and t = s den
   {
-    TileRegs<D, 64> vt;
-    fetch_tile<D, 64>(dO, e.b, h, e.t0 + 64 * wave, e.t1, lane, vt);
-    put_tile<D, 64>(vt, lane, rt + 64 * wave * SM::kRStride, SM::kRStride);
+    TileRegs<D, kChunkRowsPerWave> vt;
+    fetch_tile<D, kChunkRowsPerWave>(dO, e.b, h, e.t0 + kChunkRowsPerWave * wave, e.t1, lane, vt);
+    put_tile<D, kChunkRowsPerWave>(vt, lane, rt + kChunkRowsPerWave * wave * SM::kRStride, SM::kRStride);
   }
 #pragma unroll 1
-  for (int tt = 0; tt < 2; ++tt) {
-    const int t = 2 * wave + tt;
+  for (int tt = 0; tt < kChunkTilesPerWave; ++tt) {
+    const int t = kChunkTilesPerWave * wave + tt;
     const int n = e.t0 + 32 * t + r;
     const bool live = n < e.t1;
     const int64_t th = g.th(e.b, h, live ? n : e.t1 - 1);
@@ -1822,8 +1834,8 @@ __global__ __launch_bounds__(kThreads) void k_cgrad_k(Geom g, const BlockEnt* __
   const u32x4* opB = reinterpret_cast<const u32x4*>(pu + SL::kOpElems * 2);
   const float* dzslot = reinterpret_cast<const float*>(pu + 2 * SL::kOpElems * 2) + gl * SP;
 #pragma unroll 1
-  for (int ki = 0; ki < 2; ++ki) {
-    const int kt = ki == 0 ? wave : SM::kTiles - 1 - wave;
+  for (int ki = 0; ki < kChunkTilesPerWave; ++ki) {
+    const int kt = chunk_tile_of(wave, ki);
     const int n0 = e.t0 + 32 * kt;
     if (n0 >= e.t1) continue;
     const int n = n0 + r;
