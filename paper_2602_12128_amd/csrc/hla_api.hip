@@ -446,8 +446,14 @@ hla_status hla_set_value_modulation_grads(hla_handle* hd, const hla_vmod_weight_
   if (hd->vmod_wg_partial == nullptr) {
     Arena arena;  // hipMalloc
     float *part = nullptr, *rows = nullptr;
-    hla_status st = arena.alloc(&part, static_cast<size_t>(kVmodWgradParts) * vmod_wgrad_part_floats(d));
-    if (st == HLA_OK) st = arena.alloc(&rows, static_cast<size_t>(3) * hd->max_th * d);
+    size_t part_floats = static_cast<size_t>(kVmodWgradParts) * vmod_wgrad_part_floats(d);
+    size_t row_floats = static_cast<size_t>(3) * hd->max_th * d;
+    if (hd->vmod_wpk != nullptr) {  // matrix-core handles: ten bf16 factor arrays, per-wave partials
+      part_floats = std::max(part_floats, static_cast<size_t>(vmod_mfma_partial_floats(hd)));
+      row_floats = std::max(row_floats, static_cast<size_t>(vmod_mfma_factor_floats(hd)));
+    }
+    hla_status st = arena.alloc(&part, part_floats);
+    if (st == HLA_OK) st = arena.alloc(&rows, row_floats);
     if (st != HLA_OK) {
       (void)hipFree(part);
       (void)hipFree(rows);

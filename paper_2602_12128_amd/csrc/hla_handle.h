@@ -160,6 +160,9 @@ hla_status vmod_mfma_set_weights(hla_handle* hd, const hla_vmod_weights* maps, h
 hla_status vmod_mfma_forward(hla_handle* hd, const hla_call_args& a);
 hla_status vmod_mfma_backward(hla_handle* hd, const hla_call_args& a);
 hla_status vmod_mfma_add_value_grads(hla_handle* hd, const hla_call_args& a);
+hla_status vmod_mfma_weight_grads(hla_handle* hd, const hla_call_args& a);
+int64_t vmod_mfma_factor_floats(const hla_handle* hd);
+int64_t vmod_mfma_partial_floats(const hla_handle* hd);
 
 // Shared helper kernels' host wrappers (hla_generic.hip).
 hla_status convert_weights_to_f32(hla_handle* hd, const hla_phi_weights* maps, hipStream_t s);

@@ -162,6 +162,25 @@ struct SavedTile {
   static constexpr int kBytes = kUhat + 2 * 256;
 };
 
+// Per-token factors of the maps' weight gradients, written by the backward kernel when they are
+// asked for: bf16 [token-heads][D] arrays per map m (nullptr: not wanted).  With them
+//   dW2 = G^T dU, db2 = sum dU;  dW1 = X^T dH, db1 = sum dH;  dgamma = diag(DM^T Uh), dbeta = sum DM.
+struct VmodFactors {
+  bf16_t* dU[2];   // gradient w.r.t. the second layer's output
+  bf16_t* dH[2];   // gradient w.r.t. the first layer's output
+  bf16_t* G[2];    // GELU(h)
+  bf16_t* DM[2];   // gradient w.r.t. the map's output
+  bf16_t* Uh[2];   // u-hat
+};
+
+// eight fp32 values -> a 16-byte piece of a bf16 row
+__device__ __forceinline__ u32x4 pack8(const float (&v)[8], float scale) {
+  u32x4 w;
+#pragma unroll
+  for (int p = 0; p < 4; ++p) w[p] = pack_bf16(v[2 * p] * scale, v[2 * p + 1] * scale);
+  return w;
+}
+
 struct TileWalk {
   int tiles_per_row, total, H;
   __device__ __forceinline__ void decode(int t, int& b, int& h, int& n0) const {
@@ -434,9 +453,13 @@ __global__ __launch_bounds__(WAVES * 64) void k_vmod_fwd_mfma(Geom g, const unsi
 // u-hat (1) and of the other map's (2, both packed fp16).  Only the result stays in registers; the
 // second pass must really load again (its loader is handed pass = 1 so that it can use an address
 // the compiler cannot match with the first pass's).
+// fDU / fDM / fUh: this lane's token rows of the factor arrays (see VmodFactors; + 8 gl already
+// applied), or nullptr.
 template <int D, class Load>
 __device__ __forceinline__ float norm_backward(const unsigned char* wm_self, const unsigned char* wm_other,
-                                               int gl, Load&& load, float rstd, u32x4 (&dub)[D / 16]) {
+                                               int gl, Load&& load, float rstd, u32x4 (&dub)[D / 16],
+                                               bf16_t* fDU = nullptr, bf16_t* fDM = nullptr,
+                                               bf16_t* fUh = nullptr) {
   using SM = VSmem<D>;
   constexpr int NKS = D / 16;
   // a pass requests all its pieces before it looks at the first one: one memory round trip per
@@ -451,7 +474,7 @@ __device__ __forceinline__ float norm_backward(const unsigned char* wm_self, con
     }
     __builtin_amdgcn_sched_barrier(0);
   };
-  auto piece = [&](int ks, int pass, int opaque, float (&gg)[8], float (&uh)[8]) {
+  auto piece = [&](int ks, int pass, int opaque, float (&gg)[8], float (&uh)[8], float (&dmv)[8]) {
     const u32x4 d = dd[ks], s = ss[ks], o = oo[ks];
     const float* vs = reinterpret_cast<const float*>(wm_self + SM::kVec) + opaque + 16 * ks + 8 * gl;
     const float* vo = reinterpret_cast<const float*>(wm_other + SM::kVec) + opaque + 16 * ks + 8 * gl;
@@ -466,7 +489,8 @@ __device__ __forceinline__ float norm_backward(const unsigned char* wm_self, con
         const uint32_t dw = d[j / 2], sw = s[j / 2], ow = o[j / 2];
         const f16x2 sp = __builtin_bit_cast(f16x2, sw), op = __builtin_bit_cast(f16x2, ow);
         const float mo = __builtin_fmaf(static_cast<float>(op[j % 2]), go[e], bo[e]);
-        gg[j] = (j % 2 ? bf16_hi(dw) : bf16_lo(dw)) * mo * gs[e];
+        dmv[j] = (j % 2 ? bf16_hi(dw) : bf16_lo(dw)) * mo;
+        gg[j] = dmv[j] * gs[e];
         uh[j] = static_cast<float>(sp[j % 2]);
       }
     }
@@ -477,8 +501,8 @@ __device__ __forceinline__ float norm_backward(const unsigned char* wm_self, con
   request(0);
 #pragma unroll
   for (int ks = 0; ks < NKS; ++ks) {
-    float gg[8], uh[8];
-    piece(ks, 0, z1, gg, uh);
+    float gg[8], uh[8], dmv[8];
+    piece(ks, 0, z1, gg, uh, dmv);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       sa += gg[j];
@@ -497,13 +521,16 @@ __device__ __forceinline__ float norm_backward(const unsigned char* wm_self, con
   request(1);
 #pragma unroll
   for (int ks = 0; ks < NKS; ++ks) {
-    float gg[8], uh[8];
-    piece(ks, 1, z2, gg, uh);
+    float gg[8], uh[8], dmv[8], tv[8];
+    piece(ks, 1, z2, gg, uh, dmv);
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      const float t0 = __builtin_fmaf(gg[2 * p], inv, -a) - uh[2 * p] * bq;
-      const float t1 = __builtin_fmaf(gg[2 * p + 1], inv, -a) - uh[2 * p + 1] * bq;
-      dub[ks][p] = __builtin_bit_cast(uint32_t, to_f16x2(t0, t1));
+    for (int j = 0; j < 8; ++j) tv[j] = __builtin_fmaf(gg[j], inv, -a) - uh[j] * bq;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) dub[ks][p] = __builtin_bit_cast(uint32_t, to_f16x2(tv[2 * p], tv[2 * p + 1]));
+    if (fDU != nullptr) {  // (all three or none)
+      *reinterpret_cast<u32x4*>(fDU + 16 * ks) = pack8(tv, rstd * nrm);
+      *reinterpret_cast<u32x4*>(fDM + 16 * ks) = pack8(dmv, 1.0f);
+      *reinterpret_cast<u32x4*>(fUh + 16 * ks) = pack8(uh, 1.0f);
     }
   }
   return rstd * nrm;
@@ -518,7 +545,10 @@ template <int D>
 __device__ __forceinline__ void map_backward(const unsigned char* wm, const int (&a_off)[D / 16],
                                              const int (&t_off)[2][D / 32], int gl,
                                              const u32x4 (&x)[D / 16], const u32x4 (&dub)[D / 16],
-                                             f32x16 (&dx)[D / 32]) {
+                                             f32x16 (&dx)[D / 32], bf16_t* fG = nullptr,
+                                             bf16_t* fDH = nullptr, float scale = 1.0f) {
+  // fG / fDH: this lane's token rows of the factor arrays (+ 8 gl applied) or nullptr; `scale` is
+  // the factor the normalised du (and with it dh) is short of
   using SM = VSmem<D>;
   constexpr int NRB = D / 32, NKS = D / 16;
   auto tr_operand = [&](const unsigned char* mat, int blk, int ks) {
@@ -562,6 +592,25 @@ __device__ __forceinline__ void map_backward(const unsigned char* wm, const int 
 #pragma unroll
     for (int p = 0; p < 8; ++p)
       dhb[p / 4][p % 4] = pack_bf16(static_cast<float>(gp[p][0]) * dg[2 * p], static_cast<float>(gp[p][1]) * dg[2 * p + 1]);
+    if (fG != nullptr) {  // registers 8 hf .. 8 hf + 7 of the block are channels 32 hb + 16 hf + 8 gl ..
+      uint32_t gq[8];
+      gelu_y16<4>(reinterpret_cast<const f16x2(&)[4]>(y[0]), reinterpret_cast<uint32_t(&)[4]>(gq[0]));
+      gelu_y16<4>(reinterpret_cast<const f16x2(&)[4]>(y[4]), reinterpret_cast<uint32_t(&)[4]>(gq[4]));
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf) {
+        float gv[8], hv[8];
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+          const f16x2 g2 = __builtin_bit_cast(f16x2, gq[4 * hf + p]);
+          gv[2 * p] = static_cast<float>(g2[0]);
+          gv[2 * p + 1] = static_cast<float>(g2[1]);
+          hv[2 * p] = static_cast<float>(gp[4 * hf + p][0]) * dg[8 * hf + 2 * p];
+          hv[2 * p + 1] = static_cast<float>(gp[4 * hf + p][1]) * dg[8 * hf + 2 * p + 1];
+        }
+        *reinterpret_cast<u32x4*>(fG + 32 * hb + 16 * hf) = pack8(gv, 1.0f / kHiddenScale);
+        *reinterpret_cast<u32x4*>(fDH + 32 * hb + 16 * hf) = pack8(hv, scale * kHiddenScale);  // dg carries the packed W2's factor 4
+      }
+    }
     if (hb + 1 < NRB) {
 #pragma unroll
       for (int ks = 0; ks < NKS; ++ks) ag[ks] = tr_operand(wm + SM::kW2, hb + 1, ks);
@@ -579,11 +628,13 @@ __device__ __forceinline__ void map_backward(const unsigned char* wm, const int 
 //   dT  = dO + phi_v1'(T)^T (dO * phi_v2(V)),   dVm = phi_v2'(V)^T (dO * phi_v1(T));
 // the maps' normalised outputs come from the forward (SavedTile), the first layer is computed again
 // block by block for GELU'.
-template <int D, int WAVES>
+// FACTORS: also writes the per-token factors of the maps' weight gradients (VmodFactors).
+template <int D, int WAVES, bool FACTORS>
 __global__ __launch_bounds__(WAVES * 64) void k_vmod_bwd_mfma(Geom g, const unsigned char* __restrict__ wpk,
                                                               float ln_eps, View Tin, View V, View dO,
                                                               View dT, View dVm,
-                                                              const unsigned char* __restrict__ saved) {
+                                                              const unsigned char* __restrict__ saved,
+                                                              VmodFactors fac) {
   using SM = VSmem<D>;
   constexpr int NRB = D / 32, NKS = D / 16;
   extern __shared__ __align__(16) unsigned char smem[];
@@ -642,14 +693,18 @@ __global__ __launch_bounds__(WAVES * 64) void k_vmod_bwd_mfma(Geom g, const unsi
         return load_global16(slot_rd[pass] + (m * NKS + ks) * 1024 + lane16);
       };
     };
+    // this lane's token row in the factor arrays (nullptr: none wanted, or a row past the end)
+    const int64_t frow = FACTORS && n0 + r < g.N ? g.th(b, h, n0 + r) * D + 8 * gl : -1;
+    auto frow_of = [&](bf16_t* base) -> bf16_t* { return FACTORS && frow >= 0 ? base + frow : nullptr; };
     {
       u32x4 x[NKS];  // read again: the rows are still in the caches
       load_row<D>(Tin, b, h, n0 + r, g.N, gl, x);
       u32x4 du[NKS];
-      const float s1 = norm_backward<D>(smem, smem + SM::kMap, gl, loader(0), rstd1, du);
+      const float s1 = norm_backward<D>(smem, smem + SM::kMap, gl, loader(0), rstd1, du, frow_of(fac.dU[0]),
+                                        frow_of(fac.DM[0]), frow_of(fac.Uh[0]));
       __builtin_amdgcn_sched_barrier(0);
       f32x16 dx[NRB];
-      map_backward<D>(smem, a_off, t_off, gl, x, du, dx);
+      map_backward<D>(smem, a_off, t_off, gl, x, du, dx, frow_of(fac.G[0]), frow_of(fac.dH[0]), s1);
       __builtin_amdgcn_sched_barrier(0);
       load_row<D>(dO, b, h, n0 + r, g.N, gl, x);
       u32x4 w[NRB][2];
@@ -667,10 +722,11 @@ __global__ __launch_bounds__(WAVES * 64) void k_vmod_bwd_mfma(Geom g, const unsi
       u32x4 x[NKS];
       load_row<D>(V, b, h, n0 + r, g.N, gl, x);
       u32x4 du[NKS];
-      const float s2 = norm_backward<D>(smem + SM::kMap, smem, gl, loader(1), rstd2, du);
+      const float s2 = norm_backward<D>(smem + SM::kMap, smem, gl, loader(1), rstd2, du, frow_of(fac.dU[1]),
+                                        frow_of(fac.DM[1]), frow_of(fac.Uh[1]));
       __builtin_amdgcn_sched_barrier(0);
       f32x16 dx[NRB];
-      map_backward<D>(smem + SM::kMap, a_off, t_off, gl, x, du, dx);
+      map_backward<D>(smem + SM::kMap, a_off, t_off, gl, x, du, dx, frow_of(fac.G[1]), frow_of(fac.dH[1]), s2);
       u32x4 w[NRB][2];
 #pragma unroll
       for (int ib = 0; ib < NRB; ++ib) {
@@ -681,6 +737,123 @@ __global__ __launch_bounds__(WAVES * 64) void k_vmod_bwd_mfma(Geom g, const unsi
       }
       store_tile<D>(w, lane, otile, row_of(dVm));
     }
+  }
+}
+
+// C[i][j] = sum over tokens of A[t][i] B[t][j] and z[i] = sum over tokens of A[t][i] for two bf16
+// [B, H, N, D] views, on the matrix cores.  grid (parts, D / 64), block 256: workgroup half
+// blockIdx.y owns rows 64 y .. 64 y + 63 of C; each wave streams 64-token sub-tiles (both row tiles
+// through its private LDS, both operands by transpose reads, k = token) of the flat list over all
+// (batch row, head) pairs and writes its accumulators straight to its own partial:
+//   part[(blockIdx.x * 4 + wave) * (D / 64) + y] = [C rows 64 x D | z 64] floats.
+template <int D>
+struct TnSmem {
+  static constexpr int kStride = D * 2 + 32;
+  static constexpr int kTile = 64 * kStride;
+  static constexpr int kTotal = 4 * 2 * kTile;
+};
+template <int D>
+__global__ __launch_bounds__(256) void k_tn_mfma(Geom g, View A, View Bv, float* __restrict__ part) {
+  using SM = TnSmem<D>;
+  constexpr int NCB = D / 32;
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int lane = threadIdx.x % kWave, wave = wave_index();
+  unsigned char* as = smem + wave * 2 * SM::kTile;
+  unsigned char* bs = as + SM::kTile;
+  const int r = lane % 32, gq = lane / 32, L = lane % 16, q = lane / 16;
+  const int half = blockIdx.y;
+  f32x16 acc[2][NCB], zacc[2];
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) zacc[rb][i] = 0.0f;
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[rb][cb][i] = 0.0f;
+  }
+  u32x4 ones;
+  ones[0] = ones[1] = ones[2] = ones[3] = 0x3f803f80u;  // bf16 1.0 pairs
+  const int per_row = (g.N + 63) / 64;
+  const int total = per_row * g.B * g.H;
+  const int stride = gridDim.x * 4;
+  TileRegs<D, 64> ta, tb;
+  auto fetch = [&](int st) {
+    const int row = st / per_row, n0 = (st % per_row) * 64;
+    fetch_tile<D, 64>(A, row / g.H, row % g.H, n0, g.N, lane, ta);
+    fetch_tile<D, 64>(Bv, row / g.H, row % g.H, n0, g.N, lane, tb);
+  };
+  int st = blockIdx.x * 4 + wave;
+  if (st < total) fetch(st);
+  for (; st < total; st += stride) {
+    put_tile<D, 64>(ta, lane, as, SM::kStride);
+    put_tile<D, 64>(tb, lane, bs, SM::kStride);
+    if (st + stride < total) fetch(st + stride);
+    wave_lds_sync();
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const int krow = 16 * ks + 8 * gq + L / 4;  // token row this lane addresses for the transpose reads
+      u32x4 a[2];
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb) {
+        const unsigned char* p = as + krow * SM::kStride + (64 * half + 32 * rb + 16 * (q % 2) + 4 * (L % 4)) * 2;
+        const u32x2 lo = lds_read_tr16(p);
+        const u32x2 hi = lds_read_tr16(p + 4 * SM::kStride);
+        a[rb][0] = lo[0];
+        a[rb][1] = lo[1];
+        a[rb][2] = hi[0];
+        a[rb][3] = hi[1];
+      }
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb) {
+        const unsigned char* p = bs + krow * SM::kStride + (32 * cb + 16 * (q % 2) + 4 * (L % 4)) * 2;
+        const u32x2 lo = lds_read_tr16(p);
+        const u32x2 hi = lds_read_tr16(p + 4 * SM::kStride);
+        u32x4 b;
+        b[0] = lo[0];
+        b[1] = lo[1];
+        b[2] = hi[0];
+        b[3] = hi[1];
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) acc[rb][cb] = mfma32(a[rb], b, acc[rb][cb]);
+      }
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb) zacc[rb] = mfma32(a[rb], ones, zacc[rb]);
+    }
+    wave_lds_sync();
+  }
+  float* out = part + (static_cast<int64_t>(blockIdx.x * 4 + wave) * gridDim.y + half) * (64 * D + 64);
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int row = 32 * rb + d_row(i, gq);
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb) out[row * D + 32 * cb + r] = acc[rb][cb][i];
+      if (r == 0) out[64 * D + row] = zacc[rb][i];
+    }
+}
+
+// Adds the `nparts` partials of k_tn_mfma in order.  diag = 0: M[j * D + i] = C[i][j] (the
+// transpose: the products are formed with the gradient as the A operand) and v[i] = z[i];
+// diag = 1: M[i] = C[i][i], v[i] = z[i].  grid (D * D / 256), block 256.
+template <int D>
+__global__ void k_tn_reduce(const float* __restrict__ part, int nparts, int diag, float* __restrict__ M,
+                            float* __restrict__ v) {
+  constexpr int HALVES = D / 64;
+  constexpr int64_t PW = 64 * D + 64;
+  const int idx = blockIdx.x * 256 + threadIdx.x;  // i * D + j
+  const int i = idx / D, j = idx % D;
+  const float* base = part + static_cast<int64_t>(i / 64) * PW;
+  if (!diag || i == j) {
+    float s = 0.0f;
+    for (int p = 0; p < nparts; ++p) s += base[static_cast<int64_t>(p) * HALVES * PW + (i % 64) * D + j];
+    if (diag) M[i] = s; else M[j * D + i] = s;
+  }
+  if (j == 0) {
+    float s = 0.0f;
+    for (int p = 0; p < nparts; ++p) s += base[static_cast<int64_t>(p) * HALVES * PW + 64 * D + i % 64];
+    v[i] = s;
   }
 }
 
@@ -709,8 +882,12 @@ template <int D>
 hla_status prepare_t() {
   HLA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_vmod_fwd_mfma<D, kWavesV>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, VSmem<D>::total(kWavesV)));
-  HLA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_vmod_bwd_mfma<D, kWavesV>),
+  HLA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_vmod_bwd_mfma<D, kWavesV, false>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, VSmem<D>::total(kWavesV)));
+  HLA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_vmod_bwd_mfma<D, kWavesV, true>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, VSmem<D>::total(kWavesV)));
+  HLA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_tn_mfma<D>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, TnSmem<D>::kTotal));
   return HLA_OK;
 }
 
@@ -731,16 +908,63 @@ hla_status forward_t(hla_handle* hd, const hla_call_args& a) {
                 hd->vmod_ln_eps, vmod_view(hd->vmod_T, g), a.V, a.O, hd->vmod_wpk + vmod_mfma_packed_bytes(hd));
 }
 
+// the ten factor arrays inside hd->vmod_wg_rows (bf16 [max_th][d] each)
+VmodFactors factor_arrays(const hla_handle* hd) {
+  VmodFactors f;
+  bf16_t* base = reinterpret_cast<bf16_t*>(hd->vmod_wg_rows);
+  const int64_t per = hd->max_th * hd->g.d;
+  for (int m = 0; m < 2; ++m) {
+    f.dU[m] = base + (5 * m + 0) * per;
+    f.dH[m] = base + (5 * m + 1) * per;
+    f.G[m] = base + (5 * m + 2) * per;
+    f.DM[m] = base + (5 * m + 3) * per;
+    f.Uh[m] = base + (5 * m + 4) * per;
+  }
+  return f;
+}
+
 template <int D>
 hla_status backward_t(hla_handle* hd, const hla_call_args& a) {
   const Geom& g = hd->g;
   const int64_t tiles = static_cast<int64_t>((g.N + 31) / 32) * g.B * g.H;
   const int grid = static_cast<int>(std::min<int64_t>(compute_units(), (tiles + kWavesV - 1) / kWavesV));
-  return launch(hd, "vmod_backward", k_vmod_bwd_mfma<D, kWavesV>, dim3(grid), dim3(kWavesV * 64),
+  const unsigned char* saved = hd->vmod_wpk + vmod_mfma_packed_bytes(hd);
+  if (hd->vmod_wg_on)
+    return launch(hd, "vmod_backward", k_vmod_bwd_mfma<D, kWavesV, true>, dim3(grid), dim3(kWavesV * 64),
+                  VSmem<D>::total(kWavesV), a.stream, g, static_cast<const unsigned char*>(hd->vmod_wpk),
+                  hd->vmod_ln_eps, vmod_view(hd->vmod_T, g), a.V, a.dO, vmod_view(hd->vmod_dT, g),
+                  vmod_view(hd->vmod_dV, g), saved, factor_arrays(hd));
+  return launch(hd, "vmod_backward", k_vmod_bwd_mfma<D, kWavesV, false>, dim3(grid), dim3(kWavesV * 64),
                 VSmem<D>::total(kWavesV), a.stream, g, static_cast<const unsigned char*>(hd->vmod_wpk),
                 hd->vmod_ln_eps, vmod_view(hd->vmod_T, g), a.V, a.dO, vmod_view(hd->vmod_dT, g),
-                vmod_view(hd->vmod_dV, g),
-                static_cast<const unsigned char*>(hd->vmod_wpk + vmod_mfma_packed_bytes(hd)));
+                vmod_view(hd->vmod_dV, g), saved, VmodFactors{});
+}
+
+constexpr int kTnBlocks = 64;  // workgroups per row half of a token contraction (x 4 waves = partials)
+
+// one contraction and its sums: M, v as k_tn_reduce writes them
+template <int D>
+hla_status tn_product(hla_handle* hd, hipStream_t s, View A, View Bv, int diag, float* M, float* v) {
+  const Geom& g = hd->g;
+  const int64_t subtiles = static_cast<int64_t>((g.N + 63) / 64) * g.B * g.H;
+  const int blocks = static_cast<int>(std::min<int64_t>(kTnBlocks, (subtiles + 3) / 4));
+  HLA_TRY(launch(hd, "vmod_weight_grads_gemm", k_tn_mfma<D>, dim3(blocks, D / 64), dim3(256), TnSmem<D>::kTotal, s,
+                 g, A, Bv, hd->vmod_wg_partial));
+  return launch(hd, "vmod_weight_grads_reduce", k_tn_reduce<D>, dim3(D * D / 256), dim3(256), 0, s,
+                static_cast<const float*>(hd->vmod_wg_partial), blocks * 4, diag, M, v);
+}
+
+template <int D>
+hla_status weight_grads_t(hla_handle* hd, const hla_call_args& a) {
+  const Geom& g = hd->g;
+  const VmodFactors f = factor_arrays(hd);
+  for (int m = 0; m < 2; ++m) {
+    const hla_vmod_weight_grads& o = hd->vmod_wg_out[m];
+    HLA_TRY(tn_product<D>(hd, a.stream, vmod_view(f.dU[m], g), vmod_view(f.G[m], g), 0, o.dW2, o.db2));
+    HLA_TRY(tn_product<D>(hd, a.stream, vmod_view(f.dH[m], g), m == 0 ? vmod_view(hd->vmod_T, g) : a.V, 0, o.dW1, o.db1));
+    HLA_TRY(tn_product<D>(hd, a.stream, vmod_view(f.DM[m], g), vmod_view(f.Uh[m], g), 1, o.dgamma, o.dbeta));
+  }
+  return HLA_OK;
 }
 
 template <int D>
@@ -784,6 +1008,16 @@ hla_status vmod_mfma_forward(hla_handle* hd, const hla_call_args& a) {
 }
 hla_status vmod_mfma_backward(hla_handle* hd, const hla_call_args& a) {
   return hd->g.d == 64 ? backward_t<64>(hd, a) : backward_t<128>(hd, a);
+}
+// the modulation's weight gradients from the factors the backward kernel left (it must have run
+// with hd->vmod_wg_on)
+hla_status vmod_mfma_weight_grads(hla_handle* hd, const hla_call_args& a) {
+  return hd->g.d == 64 ? weight_grads_t<64>(hd, a) : weight_grads_t<128>(hd, a);
+}
+// floats the factor arrays and the partials of the contractions need
+int64_t vmod_mfma_factor_floats(const hla_handle* hd) { return 5 * hd->max_th * hd->g.d; }  // ten bf16 arrays
+int64_t vmod_mfma_partial_floats(const hla_handle* hd) {
+  return static_cast<int64_t>(kTnBlocks) * 4 * (hd->g.d / 64) * (64 * hd->g.d + 64);
 }
 hla_status vmod_mfma_add_value_grads(hla_handle* hd, const hla_call_args& a) {
   return hd->g.d == 64 ? add_t<64>(hd, a) : add_t<128>(hd, a);

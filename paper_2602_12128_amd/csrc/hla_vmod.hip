@@ -551,6 +551,8 @@ int64_t vmod_wgrad_part_floats(int d) { return static_cast<int64_t>(d) * d + d; 
 
 hla_status vmod_weight_grads(hla_handle* hd, const hla_call_args& a, bool empty) {
   const Geom& g = hd->g;
+  // matrix-core handles: the backward kernel has left the per-token factors
+  if (!empty && hd->vmod_wpk != nullptr) return vmod_mfma_weight_grads(hd, a);
   int nparts = 0;
   if (!empty) {
     const int64_t tiles = static_cast<int64_t>((g.N + kBwdTile - 1) / kBwdTile) * g.B * g.H;
