@@ -744,8 +744,8 @@ __global__ __launch_bounds__(WAVES * 64) void k_vmod_bwd_mfma(Geom g, const unsi
 // [B, H, N, D] views, on the matrix cores.  grid (parts, D / 64), block 256: workgroup half
 // blockIdx.y owns rows 64 y .. 64 y + 63 of C; each wave streams 64-token sub-tiles (both row tiles
 // through its private LDS, both operands by transpose reads, k = token) of the flat list over all
-// (batch row, head) pairs and writes its accumulators straight to its own partial:
-//   part[(blockIdx.x * 4 + wave) * (D / 64) + y] = [C rows 64 x D | z 64] floats.
+// (batch row, head) pairs of the flat list; the workgroup writes one partial:
+//   part[blockIdx.x * (D / 64) + y] = [C rows 64 x D | z 64] floats (the four waves summed in order).
 template <int D>
 struct TnSmem {
   static constexpr int kStride = D * 2 + 32;
@@ -822,16 +822,25 @@ __global__ __launch_bounds__(256) void k_tn_mfma(Geom g, View A, View Bv, float*
     }
     wave_lds_sync();
   }
-  float* out = part + (static_cast<int64_t>(blockIdx.x * 4 + wave) * gridDim.y + half) * (64 * D + 64);
+  // the four waves' sums through LDS (the row tiles are done with), added in wave order, one
+  // partial per workgroup
+  constexpr int PW = 64 * D + 64;
+  static_assert(4 * PW * 4 <= SM::kTotal, "the waves' tiles fit the LDS the row tiles used");
+  __syncthreads();
+  float* mine = reinterpret_cast<float*>(smem) + wave * PW;
 #pragma unroll
   for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       const int row = 32 * rb + d_row(i, gq);
 #pragma unroll
-      for (int cb = 0; cb < NCB; ++cb) out[row * D + 32 * cb + r] = acc[rb][cb][i];
-      if (r == 0) out[64 * D + row] = zacc[rb][i];
+      for (int cb = 0; cb < NCB; ++cb) mine[row * D + 32 * cb + r] = acc[rb][cb][i];
+      if (r == 0) mine[64 * D + row] = zacc[rb][i];
     }
+  __syncthreads();
+  const float* all = reinterpret_cast<const float*>(smem);
+  float* out = part + (static_cast<int64_t>(blockIdx.x) * gridDim.y + half) * PW;
+  for (int k = threadIdx.x; k < PW; k += 256) out[k] = ((all[k] + all[PW + k]) + all[2 * PW + k]) + all[3 * PW + k];
 }
 
 // Adds the `nparts` partials of k_tn_mfma in order.  diag = 0: M[j * D + i] = C[i][j] (the
@@ -845,16 +854,23 @@ __global__ void k_tn_reduce(const float* __restrict__ part, int nparts, int diag
   const int idx = blockIdx.x * 256 + threadIdx.x;  // i * D + j
   const int i = idx / D, j = idx % D;
   const float* base = part + static_cast<int64_t>(i / 64) * PW;
-  if (!diag || i == j) {
+  // eight partials' loads in flight at a time, added in order
+  auto sum = [&](int64_t off) {
     float s = 0.0f;
-    for (int p = 0; p < nparts; ++p) s += base[static_cast<int64_t>(p) * HALVES * PW + (i % 64) * D + j];
+    for (int p = 0; p < nparts; p += 8) {
+      float ld[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) ld[k] = p + k < nparts ? base[static_cast<int64_t>(p + k) * HALVES * PW + off] : 0.0f;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) s += ld[k];
+    }
+    return s;
+  };
+  if (!diag || i == j) {
+    const float s = sum((i % 64) * D + j);
     if (diag) M[i] = s; else M[j * D + i] = s;
   }
-  if (j == 0) {
-    float s = 0.0f;
-    for (int p = 0; p < nparts; ++p) s += base[static_cast<int64_t>(p) * HALVES * PW + 64 * D + i % 64];
-    v[i] = s;
-  }
+  if (j == 0) v[i] = sum(64 * D + i % 64);
 }
 
 // dst += src over [B, H, N, D] bf16 rows, 16 bytes per thread (the modulation's share of dV joins
@@ -940,7 +956,7 @@ hla_status backward_t(hla_handle* hd, const hla_call_args& a) {
                 vmod_view(hd->vmod_dV, g), saved, VmodFactors{});
 }
 
-constexpr int kTnBlocks = 64;  // workgroups per row half of a token contraction (x 4 waves = partials)
+constexpr int kTnBlocks = 128;  // workgroups per row half of a token contraction (x 4 waves = partials)
 
 // one contraction and its sums: M, v as k_tn_reduce writes them
 template <int D>
@@ -951,7 +967,7 @@ hla_status tn_product(hla_handle* hd, hipStream_t s, View A, View Bv, int diag, 
   HLA_TRY(launch(hd, "vmod_weight_grads_gemm", k_tn_mfma<D>, dim3(blocks, D / 64), dim3(256), TnSmem<D>::kTotal, s,
                  g, A, Bv, hd->vmod_wg_partial));
   return launch(hd, "vmod_weight_grads_reduce", k_tn_reduce<D>, dim3(D * D / 256), dim3(256), 0, s,
-                static_cast<const float*>(hd->vmod_wg_partial), blocks * 4, diag, M, v);
+                static_cast<const float*>(hd->vmod_wg_partial), blocks, diag, M, v);
 }
 
 template <int D>
