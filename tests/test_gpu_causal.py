@@ -238,3 +238,25 @@ def test_causal_backward_twice_after_one_forward_is_bit_identical():
     h.destroy()
     for a, b in zip(*runs):
         assert torch.equal(a, b)
+
+
+def test_causal_video_size_forward_backward_two_heads():
+    """The 480p video shape as `bench.py --causal --decay` times it: two whole heads, forward and
+    backward, against the oracle's state recursions (the route that is linear in N)."""
+    w = wl.make_workload(3)
+    lam = 0.999
+    gpu = _causal_gpu_backward(w.tensors, w.F, w.d_phi, phi=w.phi, decay=lam)
+    for k in ("O", "dQ", "dK", "dV"):
+        assert torch.isfinite(gpu[k].float()).all(), k
+    heads = [2, 9]
+    sub = {k: v[:, heads].contiguous() for k, v in w.tensors.items()}
+    Q, K, V, dO = (pu.to_np(sub[k]) for k in ("Q", "K", "V", "dO"))
+    ophi = pu.oracle_phi(w.phi)
+    ref = {"O": orc.hla_operator_forward(Q, K, V, w.F, w.d_phi, w.eps, phi=ophi, causal=True, decay=lam)}
+    res = orc.hla_operator_backward(Q, K, V, dO, w.F, w.d_phi, w.eps, phi=ophi, causal=True, decay=lam,
+                                    feature_grads=True)
+    ref.update(dQ=res[0], dK=res[1], dV=res[2])
+    ref["_dqf"], ref["_dkf"] = res[-1]
+    got = {k: gpu[k][:, heads] for k in ("O", "dQ", "dK", "dV")}
+    pu.assert_parity(got, ref, 2e-2, f"causal 480p heads {heads}, decay {lam}",
+                     kinks=pu.oracle_kinks(sub, w.phi, w.F, w.d_phi, ref))

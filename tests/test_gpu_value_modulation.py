@@ -126,3 +126,26 @@ def test_modulation_weight_gradients_registration_rules():
     torch.cuda.synchronize()
     assert all((a == 7.0).all() for m in grads for a in m.values())
     h.destroy()
+
+
+def test_value_modulation_video_size_two_heads():
+    """The 480p video shape as `bench.py --value-modulation --weight-grads` times it: two whole heads
+    of O, dQ, dK, dV against the oracle; the modulation's weight gradients (sums over all heads)
+    against the oracle run on every head would take minutes, so they are checked for these two
+    heads alone in a second call on the sliced tensors."""
+    w = wl.make_workload(3)
+    vm = _vmod(1180, w.d, torch.bfloat16)
+    gpu = pu.run_gpu(w.tensors, w.F, w.d_phi, w.eps, phi=w.phi, vmod=vm)
+    assert gpu["_path"] == hla.HLA_PATH_MFMA
+    heads = [1, 10]
+    sub = {k: v[:, heads].contiguous() for k, v in w.tensors.items()}
+    ref = pu.run_oracle(sub, w.F, w.d_phi, w.eps, phi=w.phi, vmod=vm, vmod_weight_grads=True)
+    got = {k: gpu[k][:, heads] for k in ("O", "dQ", "dK", "dV")}
+    pu.assert_parity(got, {k: v for k, v in ref.items() if k != "vwg"}, 2e-2, f"value modulation 480p heads {heads}",
+                     kinks=pu.oracle_kinks(sub, w.phi, w.F, w.d_phi, ref))
+    gsub = pu.run_gpu(sub, w.F, w.d_phi, w.eps, phi=w.phi, vmod=vm, vmod_weight_grads=True)
+    # (the chunking of the state sums depends on the number of heads in the call, so the two calls
+    # agree to rounding, not bit for bit)
+    for k in ("O", "dQ", "dK", "dV"):
+        assert pu.max_rel_err(pu.to_np(gsub[k]), pu.to_np(gpu[k][:, heads])) < 1e-2, k
+    pu.assert_vmod_weight_grad_parity(gsub["vwg"], ref["vwg"], 2e-2, "modulation weight grads 480p two heads")
