@@ -62,8 +62,9 @@ def measured_traffic(workload: str, kernel: str):
         return None, None
 
 
-def cpu_baseline(w, phi, backward, features):
-    """Oracle (as it stands) on a bounded sample: the first heads of batch row / sequence 0."""
+def cpu_baseline(w, phi, backward, features, causal=False, decay=1.0, vmod=None):
+    """Oracle (as it stands) on a bounded sample: the first heads of batch row / sequence 0, in
+    the variant the run times (causal: the state recursions, about 10 s per 32760-token head)."""
     import numpy as np
     import torch
 
@@ -78,14 +79,16 @@ def cpu_baseline(w, phi, backward, features):
     H = w.H
     n_seq = w.N if w.cu_seqlens is None else w.cu_seqlens[1] - w.cu_seqlens[0]
     # about 1 s per 32760-token head (fwd+bwd) on 16 cores: take enough heads for 10 s or more
-    heads = max(1, min(H, int(round(12 * 32760 / max(n_seq, 1)))))
+    heads = max(1, min(H, int(round((2 if causal else 12) * 32760 / max(n_seq, 1)))))
     sl = (slice(0, 1), slice(0, heads), slice(0, n_seq))
     t = {k: pu.to_np(v[sl]) for k, v in w.tensors.items()}
     ophi = None if features else pu.oracle_phi(phi)
+    ovm = pu.oracle_vmod(vmod, 1e-5)
     t0 = time.perf_counter()
-    orc.hla_operator_forward(t["Q"], t["K"], t["V"], w.F, w.d_phi, w.eps, phi=ophi)
+    orc.hla_operator_forward(t["Q"], t["K"], t["V"], w.F, w.d_phi, w.eps, phi=ophi, vmod=ovm, causal=causal, decay=decay)
     if backward:
-        orc.hla_operator_backward(t["Q"], t["K"], t["V"], t["dO"], w.F, w.d_phi, w.eps, phi=ophi)
+        orc.hla_operator_backward(t["Q"], t["K"], t["V"], t["dO"], w.F, w.d_phi, w.eps, phi=ophi, vmod=ovm,
+                                  causal=causal, decay=decay)
     dt = time.perf_counter() - t0
     # whole-job rate: a token counts once all H heads are done
     value = n_seq / (dt * H / heads)
@@ -160,7 +163,8 @@ def main():
     # and the timed steps back to back: the first ~10 ms of load after an idle period run up to
     # 15 % slower (clock / power management settling: steps 6-30 of a cold start), and that
     # transient is not part of the steady-state step this line reports.
-    cpu = None if args.no_cpu else cpu_baseline(w, phi, backward, args.features)
+    cpu = None if args.no_cpu else cpu_baseline(w, phi, backward, args.features, args.causal, args.decay,
+                                                vm if args.value_modulation else None)
 
     # per-kernel durations: HIP event pairs inside the library around every launch
     prof_steps = max(args.steps, 60) if args.steps >= 10 else args.steps  # short runs: counter collection
