@@ -260,3 +260,33 @@ def test_causal_video_size_forward_backward_two_heads():
     got = {k: gpu[k][:, heads] for k in ("O", "dQ", "dK", "dV")}
     pu.assert_parity(got, ref, 2e-2, f"causal 480p heads {heads}, decay {lam}",
                      kinks=pu.oracle_kinks(sub, w.phi, w.F, w.d_phi, ref))
+
+
+def test_causal_backward_with_feature_map_weight_gradients():
+    """The feature maps' weight gradients (optional outputs of the backward) on a causal handle:
+    they are formed from the causal feature gradients."""
+    dev = torch.device("cuda:0")
+    B, H, N, d, F, dphi, lam = 1, 2, 700, 128, 3, 6, 0.99
+    t, phi = wl.make_raw_inputs(1430, B, H, N, d, F, dphi, torch.bfloat16)
+    h = hla.HLA(head_dim=d, feature_dim=dphi, degree=F, eps=1e-6, io_dtype=hla.HLA_BF16, phi_mode=hla.HLA_PHI_MLP,
+                max_heads=H, max_tokens=B * N, max_seqs=B, causal=True, decay=lam)
+    phi_dev = [{k: v.to(dev) for k, v in m.items()} for m in phi]
+    h.set_phi_weights(phi_dev)
+    wg = [{"d" + k: torch.full(v.shape, float("nan"), dtype=torch.float32, device=dev) for k, v in m.items()}
+          for m in phi_dev]
+    h.set_phi_weight_grads(wg)
+    td = {k: v.to(dev) for k, v in t.items()}
+    O = torch.empty_like(td["V"])
+    g = [torch.empty_like(td[k]) for k in "QKV"]
+    h.forward(td["Q"], td["K"], td["V"], O)
+    h.backward(td["Q"], td["K"], td["V"], O, td["dO"], *g)
+    torch.cuda.synchronize()
+    h.destroy()
+    Q, K, V, dO = (pu.to_np(t[k]) for k in ("Q", "K", "V", "dO"))
+    res = orc.hla_operator_backward(Q, K, V, dO, F, dphi, 1e-6, phi=pu.oracle_phi(phi), route="bruteforce",
+                                    causal=True, decay=lam, weight_grads=True, feature_grads=True)
+    ref = {"wg": [dict(zip(pu.WG_KEYS, m)) for m in res[3]]}
+    ref["_dqf"], ref["_dkf"] = res[-1]
+    br = pu.oracle_weight_grad_branches(t, phi, F, dphi, ref)
+    pu.assert_weight_grad_parity([{k: v.cpu() for k, v in m.items()} for m in wg], ref["wg"], 2e-2,
+                                 "causal weight gradients", branches=br)
