@@ -562,16 +562,23 @@ hla_status hla_backward(hla_handle* hd, int32_t B, int32_t H, int32_t N, const i
   a.dK = make_view(dK);
   a.dV = make_view(dV);
   a.stream = static_cast<hipStream_t>(hip_stream);
+  const hla::View dO_caller = a.dO, O_caller = a.O;
   if (hd->vmod_on) {
     // back through the modulation first: the operator then sees dT as its upstream gradient and
     // T as its output; the modulation's share of dV is added once the operator has written dV
+    // (from the caller's dO again), and the modulation's own weight gradients follow that
     HLA_TRY(vmod_backward(hd, a));
-    if (hd->vmod_wg_on) HLA_TRY(vmod_weight_grads(hd, a, false));
     a.dO = vmod_view(hd->vmod_dT, hd->g);
     a.O = vmod_view(hd->vmod_T, hd->g);
   }
   HLA_TRY(hd->path == HLA_PATH_MFMA ? mfma_backward(hd, a) : generic_backward(hd, a));
-  if (hd->vmod_on) HLA_TRY(vmod_add_value_grads(hd, a));
+  if (hd->vmod_on) {
+    hla_call_args m = a;
+    m.dO = dO_caller;
+    m.O = O_caller;
+    HLA_TRY(vmod_add_value_grads(hd, m));
+    if (hd->vmod_wg_on) HLA_TRY(vmod_weight_grads(hd, m, false));
+  }
   if (hd->wg_on) HLA_TRY(phi_weight_grads(hd, a));
   return HLA_OK;
 }

@@ -18,8 +18,9 @@
 // read from the same LDS copies by transpose reads.  du is handed to the matrix cores in fp16
 // scaled per token to unit Euclidean norm (the scale goes back on dx, which is linear in du), so
 // its range does not depend on the size of the upstream gradient or of 1/std.
-// The weights of both maps stay resident in LDS; each wave streams its own 32-token tiles and two
-// waves share a SIMD.
+// The forward keeps the weights of both maps resident in LDS (one workgroup of four waves per
+// compute unit); the backward runs one map per launch (two workgroups per unit).  Each wave streams
+// its own 32-token tiles.
 #include "hla_handle.h"
 #include "hla_mfma_common.h"
 #include "hla_mfma_gelu.h"
@@ -624,27 +625,36 @@ __device__ __forceinline__ void map_backward(const unsigned char* wm, const int 
   __builtin_amdgcn_sched_barrier(0);
 }
 
-// grid: one workgroup per compute unit, block WAVES*64.
-//   dT  = dO + phi_v1'(T)^T (dO * phi_v2(V)),   dVm = phi_v2'(V)^T (dO * phi_v1(T));
-// the maps' normalised outputs come from the forward (SavedTile), the first layer is computed again
-// block by block for GELU'.
-// FACTORS: also writes the per-token factors of the maps' weight gradients (VmodFactors).
-template <int D, int WAVES, bool FACTORS>
-__global__ __launch_bounds__(WAVES * 64) void k_vmod_bwd_mfma(Geom g, const unsigned char* __restrict__ wpk,
-                                                              float ln_eps, View Tin, View V, View dO,
-                                                              View dT, View dVm,
-                                                              const unsigned char* __restrict__ saved,
-                                                              VmodFactors fac) {
+// The backward of ONE map per launch (MAP 0: dT = dO + phi_v1'(T)^T (dO * phi_v2(V)), written to dT;
+// MAP 1: dV += phi_v2'(V)^T (dO * phi_v1(T)), added to the rows the operator's backward has written).
+// Only that map's matrices are in LDS (plus the other map's gamma, beta), so two workgroups share
+// a compute unit and one wave's memory and matrix-pipe waits are filled by another's arithmetic.
+constexpr int kRowsOutB = 8;
+template <int D>
+struct VSmemB {
+  static constexpr int kOtherVec = VSmem<D>::kMap;            // the other map's four vectors
+  static constexpr int kTiles = kOtherVec + 4 * D * 4;
+  static constexpr int total(int waves) { return kTiles + waves * RowTile<D, kRowsOutB>::kBytes; }
+};
+template <int D, int WAVES, bool FACTORS, int MAP>
+__global__ __launch_bounds__(WAVES * 64, FACTORS ? 1 : 2) void k_vmod_bwd_map(Geom g, const unsigned char* __restrict__ wpk,
+                                                             View Tin, View V, View dO, View out,
+                                                             const unsigned char* __restrict__ saved,
+                                                             VmodFactors fac) {
   using SM = VSmem<D>;
+  using SB = VSmemB<D>;
   constexpr int NRB = D / 32, NKS = D / 16;
   extern __shared__ __align__(16) unsigned char smem[];
   const int lane = threadIdx.x % kWave, wave = wave_index();
   const int r = lane % 32, gl = lane / 32;
   const int L = lane % 16, q = lane / 16;
-  load_map<D, WAVES * 64>(smem, wpk);
-  load_map<D, WAVES * 64>(smem + SM::kMap, wpk + VPacked<D>::kBytes);
+  load_map<D, WAVES * 64>(smem, wpk + MAP * VPacked<D>::kBytes);
+  if (threadIdx.x < D)
+    *reinterpret_cast<u32x4*>(smem + SB::kOtherVec + threadIdx.x * 16) =
+        *reinterpret_cast<const u32x4*>(wpk + (1 - MAP) * VPacked<D>::kBytes + VPacked<D>::kB1 + threadIdx.x * 16);
   __syncthreads();
-  unsigned char* otile = smem + 2 * SM::kMap + wave * RowTile<D, kRowsOut>::kBytes;
+  const unsigned char* wm_other = smem + SB::kOtherVec - SM::kVec;  // only its vectors are there
+  unsigned char* otile = smem + SB::kTiles + wave * RowTile<D, kRowsOutB>::kBytes;
   int a_off[NKS];
   first_layer_offsets<D>(lane, a_off);
   // Transpose reads of a [k][m] matrix copy (row = contraction index, 16 per k-step: slot (gl, j)
@@ -668,74 +678,49 @@ __global__ __launch_bounds__(WAVES * 64) void k_vmod_bwd_mfma(Geom g, const unsi
   tw.H = g.H;
   const int stride = gridDim.x * WAVES;
   const int lane16 = lane * 16;
+  const View& X = MAP == 0 ? Tin : V;
   for (int tile = blockIdx.x * WAVES + wave; tile < tw.total; tile += stride) {
     int b, h, n0;
     tw.decode(tile, b, h, n0);
-    // what the forward kept of this tile (SavedTile).  The two passes of norm_backward read through
-    // two copies of the address that the compiler cannot match, so that the second pass loads again
-    // instead of holding the first pass's registers.
     const unsigned char* slot_rd[2] = {saved + static_cast<int64_t>(tile) * SavedTile<D>::kBytes, nullptr};
     slot_rd[1] = slot_rd[0];
     asm volatile("" : "+s"(slot_rd[1]));
-    const float rstd1 = *reinterpret_cast<const float*>(slot_rd[0] + SavedTile<D>::kUhat + lane * 4);
-    const float rstd2 = *reinterpret_cast<const float*>(slot_rd[0] + SavedTile<D>::kUhat + 256 + lane * 4);
-    auto row_of = [&](const View& X) {
-      return [&X, b, h, n0, &g](int t) -> bf16_t* { return n0 + t < g.N ? X.row<bf16_t>(b, h, n0 + t) : nullptr; };
-    };
-    // Phase 2, per map: LayerNorm backward, then back through the two layers
+    const float rstd = *reinterpret_cast<const float*>(slot_rd[0] + SavedTile<D>::kUhat + MAP * 256 + lane * 4);
     const bf16_t* drow[2] = {dO.row<const bf16_t>(b, h, n0 + r < g.N ? n0 + r : g.N - 1) + 8 * gl, nullptr};
     drow[1] = drow[0];
     asm volatile("" : "+v"(drow[1]));
-    auto loader = [&](int self) {
-      return [&, self](int which, int ks, int pass) -> u32x4 {
-        if (which == 0) return load_global16(drow[pass] + 16 * ks);
-        const int m = which == 1 ? self : 1 - self;
-        return load_global16(slot_rd[pass] + (m * NKS + ks) * 1024 + lane16);
-      };
+    auto loader = [&](int which, int ks, int pass) -> u32x4 {
+      if (which == 0) return load_global16(drow[pass] + 16 * ks);
+      const int m = which == 1 ? MAP : 1 - MAP;
+      return load_global16(slot_rd[pass] + (m * NKS + ks) * 1024 + lane16);
     };
-    // this lane's token row in the factor arrays (nullptr: none wanted, or a row past the end)
     const int64_t frow = FACTORS && n0 + r < g.N ? g.th(b, h, n0 + r) * D + 8 * gl : -1;
     auto frow_of = [&](bf16_t* base) -> bf16_t* { return FACTORS && frow >= 0 ? base + frow : nullptr; };
-    {
-      u32x4 x[NKS];  // read again: the rows are still in the caches
-      load_row<D>(Tin, b, h, n0 + r, g.N, gl, x);
-      u32x4 du[NKS];
-      const float s1 = norm_backward<D>(smem, smem + SM::kMap, gl, loader(0), rstd1, du, frow_of(fac.dU[0]),
-                                        frow_of(fac.DM[0]), frow_of(fac.Uh[0]));
-      __builtin_amdgcn_sched_barrier(0);
-      f32x16 dx[NRB];
-      map_backward<D>(smem, a_off, t_off, gl, x, du, dx, frow_of(fac.G[0]), frow_of(fac.dH[0]), s1);
-      __builtin_amdgcn_sched_barrier(0);
-      load_row<D>(dO, b, h, n0 + r, g.N, gl, x);
-      u32x4 w[NRB][2];
-#pragma unroll
-      for (int ib = 0; ib < NRB; ++ib) {
-        f32x16 o;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) o[i] = __builtin_fmaf(dx[ib][i], s1, row_entry<D>(x, ib, i));
-        pack_block(o, w[ib]);
-      }
-      store_tile<D>(w, lane, otile, row_of(dT));
-    }
+    u32x4 x[NKS];  // the map's input rows, for the first layer's recomputation
+    load_row<D>(X, b, h, n0 + r, g.N, gl, x);
+    u32x4 du[NKS];
+    const float sc = norm_backward<D>(smem, wm_other, gl, loader, rstd, du, frow_of(fac.dU[MAP]),
+                                      frow_of(fac.DM[MAP]), frow_of(fac.Uh[MAP]));
     __builtin_amdgcn_sched_barrier(0);
-    {
-      u32x4 x[NKS];
-      load_row<D>(V, b, h, n0 + r, g.N, gl, x);
-      u32x4 du[NKS];
-      const float s2 = norm_backward<D>(smem + SM::kMap, smem, gl, loader(1), rstd2, du, frow_of(fac.dU[1]),
-                                        frow_of(fac.DM[1]), frow_of(fac.Uh[1]));
-      __builtin_amdgcn_sched_barrier(0);
-      f32x16 dx[NRB];
-      map_backward<D>(smem + SM::kMap, a_off, t_off, gl, x, du, dx, frow_of(fac.G[1]), frow_of(fac.dH[1]), s2);
-      u32x4 w[NRB][2];
+    f32x16 dx[NRB];
+    map_backward<D>(smem, a_off, t_off, gl, x, du, dx, frow_of(fac.G[MAP]), frow_of(fac.dH[MAP]), sc);
+    __builtin_amdgcn_sched_barrier(0);
+    // what the result is added to: dO (MAP 0) or the operator's own dV (MAP 1), this lane's row
+    load_row<D>(MAP == 0 ? dO : out, b, h, n0 + r, g.N, gl, x);
+    u32x4 w[NRB][2];
 #pragma unroll
-      for (int ib = 0; ib < NRB; ++ib) {
-        f32x16 o;
+    for (int ib = 0; ib < NRB; ++ib) {
+      f32x16 o;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) o[i] = dx[ib][i] * s2;
-        pack_block(o, w[ib]);
-      }
-      store_tile<D>(w, lane, otile, row_of(dVm));
+      for (int i = 0; i < 16; ++i) o[i] = __builtin_fmaf(dx[ib][i], sc, row_entry<D>(x, ib, i));
+      pack_block(o, w[ib]);
+    }
+#pragma unroll
+    for (int pass = 0; pass < 32 / kRowsOutB; ++pass) {
+      put_rows<D, kRowsOutB>(w, pass, lane, otile);
+      flush_rows<D, kRowsOutB>(pass, lane, otile, [&](int t) -> bf16_t* {
+        return n0 + t < g.N ? out.row<bf16_t>(b, h, n0 + t) : nullptr;
+      });
     }
   }
 }
@@ -873,35 +858,18 @@ __global__ void k_tn_reduce(const float* __restrict__ part, int nparts, int diag
   if (j == 0) v[i] = sum(64 * D + i % 64);
 }
 
-// dst += src over [B, H, N, D] bf16 rows, 16 bytes per thread (the modulation's share of dV joins
-// the operator's)
-template <int D>
-__global__ void k_add_rows16(Geom g, View dst, View src) {
-  constexpr int PIECES = D / 8;
-  const int64_t idx = blockIdx.x * static_cast<int64_t>(blockDim.x) + threadIdx.x;
-  const int64_t rows = static_cast<int64_t>(g.B) * g.H * g.N;
-  const int64_t rowi = idx / PIECES;
-  if (rowi >= rows) return;
-  const int piece = static_cast<int>(idx % PIECES);
-  const int n = static_cast<int>(rowi % g.N);
-  const int64_t bh = rowi / g.N;
-  const int h = static_cast<int>(bh % g.H), b = static_cast<int>(bh / g.H);
-  u32x4* p = reinterpret_cast<u32x4*>(dst.row<bf16_t>(b, h, n) + 8 * piece);
-  const u32x4 s = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src.row<const bf16_t>(b, h, n) + 8 * piece));
-  u32x4 v = *p;
-#pragma unroll
-  for (int k = 0; k < 4; ++k) v[k] = pack_bf16(bf16_lo(v[k]) + bf16_lo(s[k]), bf16_hi(v[k]) + bf16_hi(s[k]));
-  *p = v;
-}
-
 template <int D>
 hla_status prepare_t() {
   HLA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_vmod_fwd_mfma<D, kWavesV>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, VSmem<D>::total(kWavesV)));
-  HLA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_vmod_bwd_mfma<D, kWavesV, false>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, VSmem<D>::total(kWavesV)));
-  HLA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_vmod_bwd_mfma<D, kWavesV, true>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, VSmem<D>::total(kWavesV)));
+  HLA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_vmod_bwd_map<D, kWavesV, false, 0>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, VSmemB<D>::total(kWavesV)));
+  HLA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_vmod_bwd_map<D, kWavesV, false, 1>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, VSmemB<D>::total(kWavesV)));
+  HLA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_vmod_bwd_map<D, kWavesV, true, 0>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, VSmemB<D>::total(kWavesV)));
+  HLA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_vmod_bwd_map<D, kWavesV, true, 1>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, VSmemB<D>::total(kWavesV)));
   HLA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_tn_mfma<D>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, TnSmem<D>::kTotal));
   return HLA_OK;
@@ -939,21 +907,26 @@ VmodFactors factor_arrays(const hla_handle* hd) {
   return f;
 }
 
-template <int D>
-hla_status backward_t(hla_handle* hd, const hla_call_args& a) {
+// the backward of map MAP: MAP 0 writes dT (before the operator's backward), MAP 1 adds the
+// modulation's share to the dV the operator's backward has written
+template <int D, int MAP>
+hla_status backward_map_t(hla_handle* hd, const hla_call_args& a, View out) {
   const Geom& g = hd->g;
   const int64_t tiles = static_cast<int64_t>((g.N + 31) / 32) * g.B * g.H;
-  const int grid = static_cast<int>(std::min<int64_t>(compute_units(), (tiles + kWavesV - 1) / kWavesV));
+  const int grid = static_cast<int>(std::min<int64_t>(2 * compute_units(), (tiles + kWavesV - 1) / kWavesV));
   const unsigned char* saved = hd->vmod_wpk + vmod_mfma_packed_bytes(hd);
+  const char* name = MAP == 0 ? "vmod_backward" : "vmod_backward_value";
   if (hd->vmod_wg_on)
-    return launch(hd, "vmod_backward", k_vmod_bwd_mfma<D, kWavesV, true>, dim3(grid), dim3(kWavesV * 64),
-                  VSmem<D>::total(kWavesV), a.stream, g, static_cast<const unsigned char*>(hd->vmod_wpk),
-                  hd->vmod_ln_eps, vmod_view(hd->vmod_T, g), a.V, a.dO, vmod_view(hd->vmod_dT, g),
-                  vmod_view(hd->vmod_dV, g), saved, factor_arrays(hd));
-  return launch(hd, "vmod_backward", k_vmod_bwd_mfma<D, kWavesV, false>, dim3(grid), dim3(kWavesV * 64),
-                VSmem<D>::total(kWavesV), a.stream, g, static_cast<const unsigned char*>(hd->vmod_wpk),
-                hd->vmod_ln_eps, vmod_view(hd->vmod_T, g), a.V, a.dO, vmod_view(hd->vmod_dT, g),
-                vmod_view(hd->vmod_dV, g), saved, VmodFactors{});
+    return launch(hd, name, k_vmod_bwd_map<D, kWavesV, true, MAP>, dim3(grid), dim3(kWavesV * 64),
+                  VSmemB<D>::total(kWavesV), a.stream, g, static_cast<const unsigned char*>(hd->vmod_wpk),
+                  vmod_view(hd->vmod_T, g), a.V, a.dO, out, saved, factor_arrays(hd));
+  return launch(hd, name, k_vmod_bwd_map<D, kWavesV, false, MAP>, dim3(grid), dim3(kWavesV * 64),
+                VSmemB<D>::total(kWavesV), a.stream, g, static_cast<const unsigned char*>(hd->vmod_wpk),
+                vmod_view(hd->vmod_T, g), a.V, a.dO, out, saved, VmodFactors{});
+}
+template <int D>
+hla_status backward_t(hla_handle* hd, const hla_call_args& a) {
+  return backward_map_t<D, 0>(hd, a, vmod_view(hd->vmod_dT, hd->g));
 }
 
 constexpr int kTnBlocks = 128;  // workgroups per row half of a token contraction (x 4 waves = partials)
@@ -985,10 +958,7 @@ hla_status weight_grads_t(hla_handle* hd, const hla_call_args& a) {
 
 template <int D>
 hla_status add_t(hla_handle* hd, const hla_call_args& a) {
-  const Geom& g = hd->g;
-  const int64_t total = static_cast<int64_t>(g.B) * g.H * g.N * (D / 8);
-  return launch(hd, "vmod_add_dv", k_add_rows16<D>, dim3(static_cast<unsigned>((total + 255) / 256)), dim3(256),
-                0, a.stream, g, a.dV, vmod_view(hd->vmod_dV, g));
+  return backward_map_t<D, 1>(hd, a, a.dV);
 }
 
 }  // namespace

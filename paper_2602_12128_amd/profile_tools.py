@@ -31,7 +31,7 @@ LAUNCH_NAMES = {
     "k_wgrad_reduce": "phi_weight_grads_reduce",
     "k_query_causal<": "mfma_query_causal", "k_prefix<": "mfma_state_prefix",
     "k_vmod_forward<": "vmod_forward", "k_vmod_backward<": "vmod_backward", "k_add_rows<": "vmod_add_dv",
-    "k_vmod_fwd_mfma<": "vmod_forward", "k_vmod_bwd_mfma<": "vmod_backward", "k_add_rows16<": "vmod_add_dv",
+    "k_vmod_fwd_mfma<": "vmod_forward", "k_vmod_bwd_map<": "vmod_backward",
 }
 
 
