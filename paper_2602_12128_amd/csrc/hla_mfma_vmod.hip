@@ -572,12 +572,22 @@ __device__ __forceinline__ void map_backward(const unsigned char* wm, const int 
 #pragma unroll
   for (int hb = 0; hb < NRB; ++hb) {
     __builtin_amdgcn_sched_barrier(0);
-    const f32x16 yb = first_layer_block<D>(wm, a_off, gl, x, hb);
+    // y (first layer again) and dg are two chains of NKS dependent MFMAs each: issued alternately,
+    // one fills the other's latency
+    u32x4 a1[NKS];
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks)
+      a1[ks] = *reinterpret_cast<const u32x4*>(wm + SM::kW1 + hb * 32 * SM::kRowB + a_off[ks]);
+    f32x16 yb = vec_block(reinterpret_cast<const float*>(wm + SM::kVec), hb, gl);
     f32x16 dg;
 #pragma unroll
     for (int i = 0; i < 16; ++i) dg[i] = 0.0f;
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) dg = mfma32_f16(ag[ks], dub[ks], dg);
+    for (int ks = 0; ks < NKS; ++ks) {
+      yb = mfma32(a1[ks], x[ks], yb);
+      dg = mfma32_f16(ag[ks], dub[ks], dg);
+    }
     u32x4 ax[2][NRB];
 #pragma unroll
     for (int hf = 0; hf < 2; ++hf)
@@ -587,8 +597,7 @@ __device__ __forceinline__ void map_backward(const unsigned char* wm, const int 
     f16x2 y[8], gp[8];
 #pragma unroll
     for (int p = 0; p < 8; ++p) y[p] = to_f16x2(yb[2 * p], yb[2 * p + 1]);
-    gelu_grad_y16<4>(reinterpret_cast<const f16x2(&)[4]>(y[0]), reinterpret_cast<f16x2(&)[4]>(gp[0]));
-    gelu_grad_y16<4>(reinterpret_cast<const f16x2(&)[4]>(y[4]), reinterpret_cast<f16x2(&)[4]>(gp[4]));
+    gelu_grad_y16<8>(y, gp);  // eight independent chains in lockstep: no issue slot waits for its predecessor
     u32x4 dhb[2];
 #pragma unroll
     for (int p = 0; p < 8; ++p)
