@@ -189,9 +189,10 @@ hla_status hla_set_phi_weight_grads(hla_handle* h, const hla_phi_weight_grads* m
  * hla_forward writes the modulated O and keeps T in the handle; hla_backward takes dO as the
  * gradient w.r.t. the modulated O, carries it back through the modulation first (dV receives the
  * share that reaches V through phi_v2 as well) and must follow a forward made in the same mode.
- * The first registration allocates three [max_heads * max_tokens, d] arrays (synchronous;
- * HLA_ERR_ALLOC on failure).  Gradients of the modulation's own weights: see
- * hla_set_value_modulation_grads. */
+ * The first registration allocates three [max_heads * max_tokens, d] arrays and, on the
+ * matrix-core path, 512 bytes per token-head that the forward keeps for the backward (the maps'
+ * normalised outputs) (synchronous; HLA_ERR_ALLOC on failure).  Gradients of the modulation's own
+ * weights: see hla_set_value_modulation_grads. */
 typedef struct {
   const void* W1;
   const void* b1;
@@ -212,9 +213,9 @@ hla_status hla_set_value_modulation(hla_handle* h, const hla_vmod_weights* maps,
  * every hla_backward OVERWRITES them on its stream; they must stay valid until that work has
  * completed.  Needs the modulation switched on (HLA_ERR_STATE otherwise); switching it off clears
  * the registration.  A backward over no tokens writes zeros.  Head dims other than 32, 64, 128 are
- * HLA_ERR_UNSUPPORTED.  The first registration allocates the workspace (three fp32
- * [max_heads * max_tokens, d] arrays of per-token factors and the partial sums; synchronous;
- * HLA_ERR_ALLOC on failure). */
+ * HLA_ERR_UNSUPPORTED.  The first registration allocates the workspace (per-token factors, 20
+ * bytes per token-head and channel, and the partial sums; synchronous; HLA_ERR_ALLOC on
+ * failure). */
 typedef struct {
   float* dW1;
   float* db1;
