@@ -80,6 +80,10 @@ def load_library() -> C.CDLL:
     if not os.path.exists(LIB_PATH):
         raise FileNotFoundError(
             f"{LIB_PATH} not found: build it with `python -m paper_2602_12128_amd.build`")
+    # torch first: its wheel carries a HIP runtime of its own, and the tensors this binding is handed
+    # live in that runtime's context.  Loaded before torch, libhla.so would bring in the system's
+    # runtime instead and every allocation of the library would fail (HLA_ERR_ALLOC at hla_create).
+    import torch  # noqa: F401
     lib = C.CDLL(LIB_PATH)
     H = C.c_void_p
     lib.hla_create.argtypes = [C.POINTER(hla_config), C.POINTER(H)]
