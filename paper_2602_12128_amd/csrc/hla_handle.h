@@ -154,7 +154,7 @@ int64_t vmod_wgrad_part_floats(int d);
 // The same on the matrix cores (hla_mfma_vmod.hip), used by the functions above where supported.
 bool vmod_mfma_supported(const hla_handle* hd);
 size_t vmod_mfma_packed_bytes(const hla_handle* hd);
-size_t vmod_mfma_workspace_bytes(const hla_handle* hd);  // packed weights + the backward's stash
+size_t vmod_mfma_workspace_bytes(const hla_handle* hd);  // packed weights + what the forward keeps per tile for the backward
 hla_status vmod_mfma_prepare_kernels(const hla_handle* hd);
 hla_status vmod_mfma_set_weights(hla_handle* hd, const hla_vmod_weights* maps, hipStream_t s);
 hla_status vmod_mfma_forward(hla_handle* hd, const hla_call_args& a);

@@ -30,11 +30,10 @@ namespace {
 
 using namespace mf;
 
-// One workgroup per compute unit (both maps' weights fill most of its LDS) of four waves, one
-// per SIMD: a wave then has all 512 registers, which is what lets it keep a whole tile's
-// intermediate values and the next tile's inputs at once.  With two waves per SIMD (256 registers
-// each) the same work needed a round trip through memory for the normalised outputs and ran with
-// three quarters of its time in memory waits.
+// Workgroups of four waves.  The forward keeps both maps' weights in LDS, so one workgroup fits a
+// compute unit and a wave has its SIMD, and all 512 registers, to itself: that is what lets it
+// hold a tile's intermediate values and the next tile's inputs at once.  The backward runs one
+// map per launch, two workgroups per unit, 256 registers per wave.
 constexpr int kWavesV = 4;
 constexpr int kRowsOut = 16;  // token rows of a wave's output tile in LDS (a tile leaves in 32/16 passes)
 
