@@ -601,9 +601,8 @@ def hla_operator_backward(Q, K, V, dO, F: int, d_phi: int, eps: float,
     With vmod_weight_grads (needs `vmod`) the last result lists (dW1, db1, dW2, db2, dgamma,
     dbeta) for phi_v1 and phi_v2, summed over every sequence, head and token.
     causal / decay: the masked variant of Sec. 4.4 (route 'bruteforce' = masked matrix,
-    'factorized' = the state recursions); not combined with vmod here."""
-    if causal and vmod is not None:
-        raise ValueError("the causal backward is not combined with the value modulation")
+    'factorized' = the state recursions).  With vmod as well, T is the causal output: the
+    modulation acts token by token on (T, V), so the chain rule is the same composition."""
     B, H, N = V.shape[:3]
     dQ = np.zeros(Q.shape, F64)
     dK = np.zeros(K.shape, F64)
@@ -633,7 +632,11 @@ def hla_operator_backward(Q, K, V, dO, F: int, d_phi: int, eps: float,
             do = np.asarray(dO[b, h, lo:hi], F64)
             dv_mod = 0.0
             if vmod is not None:
-                t = (hla_factorized if route == "factorized" else hla_bruteforce)(qf, kfs, v, eps)[0]
+                if causal:
+                    t = (hla_causal_sequential if route == "factorized" else
+                         hla_causal_bruteforce)(qf, kfs, v, eps, decay=decay)
+                else:
+                    t = (hla_factorized if route == "factorized" else hla_bruteforce)(qf, kfs, v, eps)[0]
                 if vwg is not None:
                     for m, part in enumerate(value_modulation_weight_grads(do, t, v, vmod[0], vmod[1], vmod[2])):
                         for a, da in zip(vwg[m], part):

@@ -218,3 +218,40 @@ def test_operator_level_causal_backward_with_maps_and_packing():
         np.testing.assert_allclose(dQ, _fd(f, Q), rtol=5e-6, atol=5e-8)
         np.testing.assert_allclose(dK, _fd(f, K), rtol=5e-6, atol=5e-8)
         np.testing.assert_allclose(dV, _fd(f, V), rtol=5e-6, atol=5e-8)
+
+
+def test_operator_level_causal_backward_with_value_modulation():
+    """Causal variant followed by the value modulation (Secs. 4.4 and 4.5 composed): input and
+    modulation-weight gradients of both routes against central differences of the forward, and
+    the modulated causal output itself against the modulation applied by hand to the causal T."""
+    import math
+    rng = np.random.default_rng(108)
+    H, N, d, F, dp = 2, 7, 4, 2, 3
+    cu = [0, 3, 7]
+    Q, K, V, dO = (rng.standard_normal((1, H, N, d)) for _ in range(4))
+    phi = [orc.PhiWeights(rng.standard_normal((d, d)), 0.3 * rng.standard_normal(d),
+                          rng.standard_normal((d, dp)), rng.standard_normal(dp) + 1.5)
+           for _ in range(1 + F)]
+    pv = lambda scale: orc.PhiVWeights(scale * rng.standard_normal((d, d)), 0.3 * rng.standard_normal(d),
+                                       rng.standard_normal((d, d)) / math.sqrt(d), 0.3 * rng.standard_normal(d),
+                                       1.0 + 0.2 * rng.standard_normal(d), 0.2 * rng.standard_normal(d))
+    vmod = (pv(3.0), pv(1.0), 1e-5)
+    eps, lam = 1e-4, 0.9
+    fwd = lambda route: orc.hla_operator_forward(Q, K, V, F, dp, eps, phi=phi, cu_seqlens=cu, route=route,
+                                                 causal=True, decay=lam, vmod=vmod)
+    f = lambda: float((fwd("bruteforce") * dO).sum())
+    T = orc.hla_operator_forward(Q, K, V, F, dp, eps, phi=phi, cu_seqlens=cu, route="bruteforce",
+                                 causal=True, decay=lam)
+    for h in range(H):
+        want = orc.value_modulation_forward(T[0, h], V[0, h], *vmod)
+        np.testing.assert_allclose(fwd("factorized")[0, h], want, rtol=1e-10, atol=1e-12)
+    assert np.abs(fwd("bruteforce") - T).max() > 1e-3
+    for route in ("factorized", "bruteforce"):
+        dQ, dK, dV, vwg = orc.hla_operator_backward(Q, K, V, dO, F, dp, eps, phi=phi, cu_seqlens=cu, route=route,
+                                                    causal=True, decay=lam, vmod=vmod, vmod_weight_grads=True)
+        np.testing.assert_allclose(dQ, _fd(f, Q), rtol=5e-6, atol=5e-8)
+        np.testing.assert_allclose(dK, _fd(f, K), rtol=5e-6, atol=5e-8)
+        np.testing.assert_allclose(dV, _fd(f, V), rtol=5e-6, atol=5e-8)
+        for m, grads in zip(vmod[:2], vwg):
+            for arr, ga in zip(m.astuple(), grads):
+                np.testing.assert_allclose(ga, _fd(f, arr), rtol=1e-5, atol=1e-7)
