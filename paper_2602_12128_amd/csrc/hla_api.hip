@@ -518,7 +518,6 @@ hla_status hla_backward(hla_handle* hd, int32_t B, int32_t H, int32_t N, const i
   bool empty = false;
   int32_t nseq = 0;
   if (hd == nullptr) return HLA_ERR_INVALID_ARG;
-  if (hd->cfg.causal && hd->vmod_on) return HLA_ERR_UNSUPPORTED;  // not combined
   // The tables and the saved features belong to the last forward: check before touching them.
   {
     const bool packed = cu_seqlens != nullptr;

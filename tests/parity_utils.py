@@ -45,7 +45,8 @@ def oracle_phi(phi: Optional[Sequence[Dict[str, torch.Tensor]]]):
     return [orc.PhiWeights(*(to_np(m[k]) for k in ("W1", "b1", "W2", "b2"))) for m in phi]
 
 
-def make_handle(tensors, F, d_phi, eps, phi, cu_seqlens, path=hla.HLA_PATH_AUTO, max_scale=1):
+def make_handle(tensors, F, d_phi, eps, phi, cu_seqlens, path=hla.HLA_PATH_AUTO, max_scale=1,
+                causal=False, decay=1.0):
     V = tensors["V"]
     B, H, N, d = V.shape
     nseq = B if cu_seqlens is None else len(cu_seqlens) - 1
@@ -53,7 +54,7 @@ def make_handle(tensors, F, d_phi, eps, phi, cu_seqlens, path=hla.HLA_PATH_AUTO,
                 io_dtype=hla.HLA_F32 if V.dtype == torch.float32 else hla.HLA_BF16,
                 phi_mode=hla.HLA_PHI_NONE if phi is None else hla.HLA_PHI_MLP,
                 kernel_path=path, max_heads=max(H, 1), max_tokens=max(B * N, 1) * max_scale,
-                max_seqs=max(nseq, 1))
+                max_seqs=max(nseq, 1), causal=causal, decay=decay)
     return h
 
 
@@ -64,16 +65,17 @@ VWG_KEYS = ("dW1", "db1", "dW2", "db2", "dgamma", "dbeta")
 def run_gpu(tensors: Dict[str, torch.Tensor], F: int, d_phi: int, eps: float,
             phi=None, cu_seqlens=None, backward=True, path=hla.HLA_PATH_AUTO, handle=None,
             weight_grads=False, per_head=False, features=False, vmod=None, ln_eps=1e-5,
-            vmod_weight_grads=False):
+            vmod_weight_grads=False, causal=False, decay=1.0):
     """Returns dict of CPU tensors O (and dQ, dK, dV) computed by the HIP library; with
     weight_grads also 'wg': per map a dict of the fp32 weight gradients.  per_head: the weights
     carry a leading head dimension.  features: also '_features' [B,H,N,(1+F)*d_phi], the
     library's own feature workspace (an output to be compared, like the others).  vmod: the two
     value-modulation maps (Sec. 4.5), switched on for the call; with vmod_weight_grads also
-    'vwg': per map a dict of the fp32 gradients of its weights."""
+    'vwg': per map a dict of the fp32 gradients of its weights.  causal / decay: the masked
+    variant of Sec. 4.4 (a property of the handle)."""
     dev = torch.device("cuda:0")
     t = {k: v.to(dev) for k, v in tensors.items()}
-    h = handle or make_handle(tensors, F, d_phi, eps, phi, cu_seqlens, path)
+    h = handle or make_handle(tensors, F, d_phi, eps, phi, cu_seqlens, path, causal=causal, decay=decay)
     wg = None
     if phi is not None:
         phi_dev = [{k: v.to(dev) for k, v in m.items()} for m in phi]
@@ -120,19 +122,20 @@ def oracle_vmod(vmod, ln_eps):
 
 
 def run_oracle(tensors, F, d_phi, eps, phi=None, cu_seqlens=None, backward=True,
-               route="factorized", weight_grads=False, vmod=None, ln_eps=1e-5, vmod_weight_grads=False):
+               route="factorized", weight_grads=False, vmod=None, ln_eps=1e-5, vmod_weight_grads=False,
+               causal=False, decay=1.0):
     """O (and dQ, dK, dV, 'wg') from the oracle; with feature maps and a backward also the
     feature gradients '_dqf', '_dkf' that the branch enumeration below starts from."""
     Q, K, V = (to_np(tensors[k]) for k in ("Q", "K", "V"))
     ophi = oracle_phi(phi)
     ovm = oracle_vmod(vmod, ln_eps)
     out = {"O": orc.hla_operator_forward(Q, K, V, F, d_phi, eps, phi=ophi, cu_seqlens=cu_seqlens,
-                                         route=route, vmod=ovm)}
+                                         route=route, vmod=ovm, causal=causal, decay=decay)}
     if backward:
         res = orc.hla_operator_backward(Q, K, V, to_np(tensors["dO"]), F, d_phi, eps,
                                         phi=ophi, cu_seqlens=cu_seqlens, route=route,
                                         weight_grads=weight_grads, feature_grads=True, vmod=ovm,
-                                        vmod_weight_grads=vmod_weight_grads)
+                                        vmod_weight_grads=vmod_weight_grads, causal=causal, decay=decay)
         out.update(dQ=res[0], dK=res[1], dV=res[2])
         if weight_grads:
             out["wg"] = [dict(zip(WG_KEYS, m)) for m in res[3]]
@@ -371,3 +374,19 @@ def short_sequence_rows(tensors, ref, cu_seqlens, max_len=2):
             gain = 1.0
         out[k] = (mask, base * max(gain, 1.0))
     return out
+
+
+def causal_first_token_rows(tensors, ref, cu_seqlens=None):
+    """row_scale argument of assert_parity for dQ of the causal variant: the first token of every
+    sequence sees itself only, so its output does not depend on its query (up to eps) and its dQ
+    is what is left of two cancelling terms, exactly as for a one-token sequence (see
+    short_sequence_rows): measured on the same absolute scale."""
+    B, H, N = tensors["V"].shape[:3]
+    mask = np.zeros((B, H, N), bool)
+    starts = [0] if cu_seqlens is None else [lo for lo, hi in zip(cu_seqlens[:-1], cu_seqlens[1:]) if hi > lo]
+    mask[:, :, starts] = True
+    base = float(tensors["dO"].float().abs().max() * tensors["V"].float().abs().max())
+    gain = 1.0
+    if "_dqf" in ref and (~mask).any():
+        gain = np.abs(ref["dQ"][~mask]).max() / max(np.abs(ref["_dqf"][~mask]).max(), 1e-300)
+    return {"dQ": (mask, base * max(gain, 1.0))}

@@ -290,3 +290,37 @@ def test_causal_backward_with_feature_map_weight_gradients():
     br = pu.oracle_weight_grad_branches(t, phi, F, dphi, ref)
     pu.assert_weight_grad_parity([{k: v.cpu() for k, v in m.items()} for m in wg], ref["wg"], 2e-2,
                                  "causal weight gradients", branches=br)
+
+
+def _vmod(seed, d):
+    return wl.draw_vmod_weights(torch.Generator("cpu").manual_seed(seed), d, torch.bfloat16)
+
+
+@pytest.mark.parametrize("F,dphi,d,B,H,N,lam", [(3, 6, 128, 1, 2, 700, 0.99), (2, 12, 64, 2, 2, 333, 1.0)])
+def test_causal_with_value_modulation_forward_backward(F, dphi, d, B, H, N, lam):
+    """Sec. 4.5 on top of Sec. 4.4: the modulation acts on the causal output T; the backward takes
+    dO through the modulation first and hands dT to the causal operator."""
+    t, phi = wl.make_raw_inputs(1440 + N, B, H, N, d, F, dphi, torch.bfloat16)
+    vm = _vmod(1441 + N, d)
+    gpu = pu.run_gpu(t, F, dphi, 1e-6, phi=phi, path=hla.HLA_PATH_MFMA, vmod=vm, vmod_weight_grads=True,
+                     causal=True, decay=lam)
+    ref = pu.run_oracle(t, F, dphi, 1e-6, phi=phi, vmod=vm, vmod_weight_grads=True, route="bruteforce",
+                        causal=True, decay=lam)
+    what = f"causal + value modulation F={F} d={d} N={N} decay={lam}"
+    pu.assert_parity(gpu, {k: v for k, v in ref.items() if k != "vwg"}, 2e-2, what,
+                     kinks=pu.oracle_kinks(t, phi, F, dphi, ref), row_scale=pu.causal_first_token_rows(t, ref))
+    pu.assert_vmod_weight_grad_parity(gpu["vwg"], ref["vwg"], 2e-2, what)
+    # neither the unmodulated causal result nor the modulated non-causal one
+    plain = pu.run_oracle(t, F, dphi, 1e-6, phi=phi, backward=False, route="bruteforce", causal=True, decay=lam)
+    other = pu.run_oracle(t, F, dphi, 1e-6, phi=phi, vmod=vm, backward=False)
+    for o in (plain, other):
+        assert np.abs(ref["O"] - o["O"]).max() > 1e-2 * np.abs(ref["O"]).max()
+
+
+def test_causal_with_value_modulation_packed_feature_level():
+    cu = [0, 300, 300, 1324, 2600]
+    t = wl.make_feature_inputs(1450, 1, 2, cu[-1], 128, 3, 6, torch.bfloat16)
+    vm = _vmod(1451, 128)
+    gpu = pu.run_gpu(t, 3, 6, 1e-6, cu_seqlens=cu, vmod=vm, causal=True, decay=0.995)
+    ref = pu.run_oracle(t, 3, 6, 1e-6, cu_seqlens=cu, vmod=vm, route="bruteforce", causal=True, decay=0.995)
+    pu.assert_parity(gpu, ref, 2e-2, "causal + value modulation, packed features")
