@@ -79,10 +79,12 @@ typedef struct {
                             model); 1: the causal variant of Sec. 4.4, token i attends to tokens
                             j <= i of its sequence (the {0,1} mask; eta_i sums the same entries), which
                             is what the paper's sequential state update C^i = C^{i-1} + T_k,i (x) v_i
-                            computes.  Forward and backward, MFMA path only: hla_create returns
-                            HLA_ERR_UNSUPPORTED for a configuration without MFMA kernels, and so
-                            does hla_forward_static for a causal configuration.  The value
-                            modulation of Sec. 4.5 then acts on the causal output. */
+                            computes.  Forward and backward on both kernel paths (chunked scans on
+                            the MFMA path; on the generic path one workgroup walks a (sequence,
+                            head) token tile by token tile: exact in fp32, slow).
+                            hla_forward_static returns HLA_ERR_UNSUPPORTED for a causal
+                            configuration.  The value modulation of Sec. 4.5 then acts on the
+                            causal output. */
   float decay;           /* causal handles only: decay factor lambda of Sec. 4.4.  The paper lets the
                             mask carry decay factors without giving a formula; this library reads it
                             as one scalar lambda in (0, 1] and mask entries lambda^(i-j) for j <= i

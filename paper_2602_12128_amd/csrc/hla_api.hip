@@ -245,7 +245,6 @@ hla_status plan_handle(hla_handle* hd, const hla_config& c) {
   const bool mfma_ok = mfma_supported(c);
   if (c.kernel_path == HLA_PATH_MFMA && !mfma_ok) return HLA_ERR_UNSUPPORTED;
   hd->path = (c.kernel_path == HLA_PATH_GENERIC || !mfma_ok) ? HLA_PATH_GENERIC : HLA_PATH_MFMA;
-  if (c.causal && hd->path != HLA_PATH_MFMA) return HLA_ERR_UNSUPPORTED;  // only the MFMA path has the scan
   hd->g.feat_tiled = hd->path == HLA_PATH_MFMA ? 1 : 0;
   for (hla_token_table& t : hd->tables) t = hla_token_table{};
   return hd->path == HLA_PATH_MFMA ? mfma_workspace_plan(hd) : generic_workspace_plan(hd);

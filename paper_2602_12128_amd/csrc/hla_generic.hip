@@ -558,6 +558,54 @@ __global__ void k_backward_prep(Geom g, View dO, View O, const float* __restrict
   }
 }
 
+// Chain rule from dT [tile][D] (LDS) through the outer product to the feature gradients of the
+// tile's tokens: the gradient of slot s, coordinate a, token t is the sum over the entries whose
+// digit s equals a of dT[entry] times the product of the other slots' features.  QUERY: all F
+// slots hold phi_q and their gradients are summed into dfeat[.., 0:dphi]; otherwise slot f goes
+// to dfeat[.., (1+f)*dphi : ..].  Called by all threads of the block; fs = features [tile][nfeat].
+template <bool QUERY>
+__device__ __forceinline__ void slot_gradients(const Geom& g, const float* fs, const float* dts,
+                                               int tile, int nt, int b, int h, int t0,
+                                               float* __restrict__ dfeat) {
+  const int D = g.D, dphi = g.dphi, F = g.F;
+  const int nout = QUERY ? tile * dphi : tile * F * dphi;
+  for (int idx = threadIdx.x; idx < nout; idx += blockDim.x) {
+    int t, s_lo, s_hi, a;
+    if (QUERY) {
+      t = idx / dphi;
+      a = idx % dphi;
+      s_lo = 0;
+      s_hi = F;
+    } else {
+      t = idx / (F * dphi);
+      s_lo = (idx / dphi) % F;
+      s_hi = s_lo + 1;
+      a = idx % dphi;
+    }
+    if (t >= nt) continue;
+    const float* frow = fs + t * g.nfeat;
+    float grad = 0.0f;
+    for (int s = s_lo; s < s_hi; ++s) {
+      for (int Di = 0; Di < D; ++Di) {
+        int rem = Di;
+        float p = 1.0f;
+        bool hit = false;
+        for (int sl = F - 1; sl >= 0; --sl) {
+          const int dig = rem % dphi;
+          rem /= dphi;
+          if (sl == s)
+            hit = dig == a;
+          else
+            p *= frow[slot_offset(QUERY, sl, dphi) + dig];
+        }
+        if (hit) grad += dts[t * D + Di] * p;
+      }
+    }
+    const int col = QUERY ? a : (1 + s_lo) * dphi + a;
+    dfeat[g.fidx(g.th(b, h, t0 + t), col)] = grad;
+  }
+}
+
 // ---- dtensor: dT_i = M yhat_i, then gradients of the outer-product slots -----------------------
 // QUERY = true : M = Chat, yhat = ghat (dense scratch), slots all phi_q -> dfeat[.., 0:dphi] (summed)
 // QUERY = false: M = dChat, yhat = [V | 1] (caller's V), slot f -> dfeat[.., (1+f)*dphi : ..]
@@ -568,7 +616,7 @@ __global__ void k_dtensor(Geom g, const BlockEnt* __restrict__ tiles,
                           int64_t state_stride, View Y, const float* __restrict__ ydense,
                           float* __restrict__ dfeat) {
   extern __shared__ float smem[];
-  const int d = g.d, D = g.D, dphi = g.dphi, F = g.F;
+  const int d = g.d, D = g.D;
   float* ys = smem;                       // [kDtTile][d+1]
   float* fs = ys + kDtTile * (d + 1);     // [kDtTile][nfeat]
   float* dts = fs + kDtTile * g.nfeat;    // [kDtTile][D]
@@ -607,43 +655,163 @@ __global__ void k_dtensor(Geom g, const BlockEnt* __restrict__ tiles,
     for (int t = 0; t < kDtTile; ++t) dts[t * D + tid] = dt[t];
   }
   __syncthreads();
-  // gradient of slot s, coordinate a, token t: sum over entries whose digit s equals a of
-  // dT[entry] * product of the other slots' features
-  const int nout = QUERY ? kDtTile * dphi : kDtTile * F * dphi;
-  for (int idx = tid; idx < nout; idx += kThreads) {
-    int t, s_lo, s_hi, a;
-    if (QUERY) {
-      t = idx / dphi;
-      a = idx % dphi;
-      s_lo = 0;
-      s_hi = F;
-    } else {
-      t = idx / (F * dphi);
-      s_lo = (idx / dphi) % F;
-      s_hi = s_lo + 1;
-      a = idx % dphi;
+  slot_gradients<QUERY>(g, fs, dts, kDtTile, nt, e.b, h, e.t0, dfeat);
+}
+
+// ---- causal variant (Sec. 4.4): one scan over the tokens of a (sequence, head) ------------------
+// The sequential state update  Chat^i = decay Chat^{i-1} + T_k,i (x) vhat_i  (and, for the gradient
+// of the key side, its mirror image from the back,  dChat^j = decay dChat^{j+1} + T_q,j (x) ghat_j)
+// carried through the sequence by ONE workgroup, TT tokens at a time, with the running state in
+// LDS.  With a = the tensor that builds the state and ya its augmented rows, b = the tensor that
+// reads it and yb its rows, m_tj = decay^|t-j| on the visible side of the mask (j <= t going
+// forward, j >= t going back) and c_t the decay of the carried state C as seen from token t:
+//   out_t = c_t b_t . C  + sum_j m_tj <b_t, a_j> ya_j          (contract)
+//   db_t  = c_t C yb_t   + sum_j m_tj <yb_t, ya_j> a_j         (dtensor, then the chain rule)
+//   C    <- decay^TT C   + sum_j u_j a_j (x) ya_j              (u_j: decay from token j to the carry's reference)
+// MODE 0: a = T_k, ya = vhat, b = T_q:            O = out[0:d] / (out[d] + eps), den
+// MODE 1: same state, yb = ghat:                  d(phi_q) from db
+// MODE 2: a = T_q, ya = ghat, b = T_k, yb = vhat, from the back:  dV = out[0:d], d(phi_k) from db
+// grid (num_seqs, H), block 256.  Throughput is not a goal: this is the fp32 cross-check of the scan.
+template <int TT>
+__host__ __device__ constexpr size_t causal_scan_floats(int D, int d, int nfeat) {
+  return static_cast<size_t>(D) * (d + 1) + 3 * static_cast<size_t>(TT) * D + 2 * static_cast<size_t>(TT) * (d + 1) +
+         static_cast<size_t>(TT) * nfeat + 2 * TT * TT + 3 * TT;
+}
+
+template <typename T, int MODE, int TT>
+__global__ __launch_bounds__(kThreads) void k_causal_scan(
+    Geom g, const BlockEnt* __restrict__ chunks, const int32_t* __restrict__ seq_chunk_off,
+    const float* __restrict__ feat, View V, const float* __restrict__ ghat, float decay, View Out,
+    float* __restrict__ den, float* __restrict__ dfeat) {
+  extern __shared__ float smem[];
+  constexpr bool BACK = MODE == 2;
+  const int d = g.d, D = g.D, d1 = g.d + 1;
+  const int R = kThreads / d;
+  float* C = smem;                 // [D][d+1] carried state
+  float* A = C + D * d1;           // [TT][D]  state-building tensor
+  float* Bt = A + TT * D;          // [TT][D]  reading tensor
+  float* dts = Bt + TT * D;        // [TT][D]  db
+  float* ya = dts + TT * D;        // [TT][d+1]
+  float* yb = ya + TT * d1;        // [TT][d+1]
+  float* fs = yb + TT * d1;        // [TT][nfeat]
+  float* mp = fs + TT * g.nfeat;   // [TT][TT] m_tj <b_t, a_j>
+  float* mw = mp + TT * TT;        // [TT][TT] m_tj <yb_t, ya_j>
+  float* cf = mw + TT * TT;        // [TT] c_t
+  float* uf = cf + TT;             // [TT] u_j
+  float* etas = uf + TT;           // [TT]
+  const int s = blockIdx.x, h = blockIdx.y;
+  const int tid = threadIdx.x;
+  const int c0 = seq_chunk_off[s], c1 = seq_chunk_off[s + 1];
+  if (c0 == c1) return;  // empty sequence (uniform over the block)
+  const int b = chunks[c0].b, lo = chunks[c0].t0, hi = chunks[c1 - 1].t1;
+  const int ntiles = (hi - lo + TT - 1) / TT;
+  for (int idx = tid; idx < D * d1; idx += kThreads) C[idx] = 0.0f;
+  if (tid < TT) {
+    // forward: C is the state at the last token before the tile; back: at the first token behind it
+    cf[tid] = powf(decay, static_cast<float>(BACK ? TT - tid : tid + 1));
+    uf[tid] = powf(decay, static_cast<float>(BACK ? tid : TT - 1 - tid));
+  }
+  const float tile_decay = powf(decay, static_cast<float>(TT));
+  for (int ti = 0; ti < ntiles; ++ti) {
+    const int t0 = lo + (BACK ? ntiles - 1 - ti : ti) * TT;
+    const int nt = min(TT, hi - t0);
+    __syncthreads();  // the previous tile's readers of fs, A, ya, dts are done; C is up to date
+    for (int idx = tid; idx < TT * g.nfeat; idx += kThreads) {
+      const int t = idx / g.nfeat;
+      fs[idx] = t < nt ? feat[g.fidx(g.th(b, h, t0 + t), idx % g.nfeat)] : 0.0f;
     }
-    if (t >= nt) continue;
-    const float* frow = fs + t * g.nfeat;
-    float grad = 0.0f;
-    for (int s = s_lo; s < s_hi; ++s) {
-      for (int Di = 0; Di < D; ++Di) {
-        int rem = Di;
-        float p = 1.0f;
-        bool hit = false;
-        for (int sl = F - 1; sl >= 0; --sl) {
-          const int dig = rem % dphi;
-          rem /= dphi;
-          if (sl == s)
-            hit = dig == a;
-          else
-            p *= frow[slot_offset(QUERY, sl, dphi) + dig];
+    for (int idx = tid; idx < TT * d1; idx += kThreads) {
+      const int t = idx / d1, cc = idx % d1;
+      float v = 0.0f, gh = 0.0f;  // rows of tokens beyond the sequence are zero, the 1 included
+      if (t < nt) {
+        v = cc < d ? to_float(V.row<const T>(b, h, t0 + t)[cc]) : 1.0f;
+        if (MODE != 0) gh = ghat[g.th(b, h, t0 + t) * d1 + cc];
+      }
+      (BACK ? yb : ya)[idx] = v;
+      if (MODE != 0) (BACK ? ya : yb)[idx] = gh;
+    }
+    __syncthreads();
+    for (int idx = tid; idx < TT * D; idx += kThreads) {
+      const int t = idx / D, Di = idx % D;
+      const float tq = outer_entry(fs + t * g.nfeat, true, Di, g.F, g.dphi);
+      const float tk = outer_entry(fs + t * g.nfeat, false, Di, g.F, g.dphi);
+      A[idx] = BACK ? tq : tk;
+      Bt[idx] = BACK ? tk : tq;
+    }
+    __syncthreads();
+    for (int idx = tid; idx < (MODE == 0 ? 1 : 2) * TT * TT; idx += kThreads) {
+      const int w = idx / (TT * TT), t = (idx / TT) % TT, j = idx % TT;
+      const bool visible = BACK ? j >= t : j <= t;
+      float acc = 0.0f;
+      if (visible) {
+        if (w == 0) {
+          for (int Di = 0; Di < D; ++Di) acc += Bt[t * D + Di] * A[j * D + Di];
+        } else {
+          for (int cc = 0; cc < d1; ++cc) acc += yb[t * d1 + cc] * ya[j * d1 + cc];
         }
-        if (hit) grad += dts[t * D + Di] * p;
+        acc *= powf(decay, static_cast<float>(BACK ? j - t : t - j));
+      }
+      (w == 0 ? mp : mw)[t * TT + j] = acc;
+    }
+    __syncthreads();
+    // contract: thread (r, c) owns column c of tokens r, r + R, ..
+    float out[TT];
+    if (MODE != 1) {
+      const int c = tid % d, r = tid / d;
+#pragma unroll
+      for (int k = 0; k < TT; ++k) {
+        const int t = r + k * R;
+        float acc = 0.0f;
+        if (t < TT) {
+          for (int Di = 0; Di < D; ++Di) acc += Bt[t * D + Di] * C[Di * d1 + c];
+          acc *= cf[t];
+          for (int j = 0; j < TT; ++j) acc += mp[t * TT + j] * ya[j * d1 + c];
+        }
+        out[k] = acc;
+      }
+      if (MODE == 0 && tid < TT) {
+        float eta = 0.0f;
+        for (int Di = 0; Di < D; ++Di) eta += Bt[tid * D + Di] * C[Di * d1 + d];
+        eta *= cf[tid];
+        for (int j = 0; j < TT; ++j) eta += mp[tid * TT + j] * ya[j * d1 + d];
+        etas[tid] = eta + g.eps;
+        if (tid < nt) den[g.th(b, h, t0 + tid)] = eta + g.eps;
       }
     }
-    const int col = QUERY ? a : (1 + s_lo) * dphi + a;
-    dfeat[g.th(e.b, h, e.t0 + t) * g.nfeat + col] = grad;
+    // dtensor: thread Di owns row Di of the state
+    if (MODE != 0 && tid < D) {
+      float dt[TT];
+#pragma unroll
+      for (int t = 0; t < TT; ++t) dt[t] = 0.0f;
+      for (int cc = 0; cc < d1; ++cc) {
+        const float cv = C[tid * d1 + cc];
+#pragma unroll
+        for (int t = 0; t < TT; ++t) dt[t] += cv * yb[t * d1 + cc];
+      }
+#pragma unroll
+      for (int t = 0; t < TT; ++t) {
+        float acc = dt[t] * cf[t];
+        for (int j = 0; j < TT; ++j) acc += mw[t * TT + j] * A[j * D + tid];
+        dts[t * D + tid] = acc;
+      }
+    }
+    __syncthreads();  // every read of C is done; etas and dts are visible
+    if (MODE != 1) {
+      const int c = tid % d, r = tid / d;
+#pragma unroll
+      for (int k = 0; k < TT; ++k) {
+        const int t = r + k * R;
+        if (t < nt) Out.row<T>(b, h, t0 + t)[c] = from_float<T>(MODE == 0 ? out[k] / etas[t] : out[k]);
+      }
+    }
+    if (MODE == 1) slot_gradients<true>(g, fs, dts, TT, nt, b, h, t0, dfeat);
+    if (MODE == 2) slot_gradients<false>(g, fs, dts, TT, nt, b, h, t0, dfeat);
+    for (int idx = tid; idx < D * d1; idx += kThreads) {
+      const int Di = idx / d1, cc = idx % d1;
+      float acc = C[idx] * tile_decay;
+      for (int j = 0; j < TT; ++j) acc += uf[j] * A[j * D + Di] * ya[j * d1 + cc];
+      C[idx] = acc;
+    }
   }
 }
 
@@ -679,6 +847,39 @@ hla_status features_out_t(hla_handle* hd, const hla_call_args& a) {
                 hd->feat, hd->dfeat, a.dQ, a.dK);
 }
 
+// The causal scan in one of its three modes; TT = 8 tokens per step where the LDS allows, else 4.
+constexpr size_t kLdsLimit = 160 * 1024;
+inline int causal_scan_tile(const Geom& g) {
+  if (causal_scan_floats<8>(g.D, g.d, g.nfeat) * sizeof(float) <= kLdsLimit) return 8;
+  if (causal_scan_floats<4>(g.D, g.d, g.nfeat) * sizeof(float) <= kLdsLimit) return 4;
+  return 0;
+}
+
+template <typename T, int MODE, int TT>
+hla_status causal_scan_launch(hla_handle* hd, const hla_call_args& a, const char* name, View out) {
+  const Geom& g = hd->g;
+  hla_token_table* chunks = nullptr;
+  HLA_TRY(get_table(hd, 0, kChunk, a.stream, &chunks));
+  const size_t sh = causal_scan_floats<TT>(g.D, g.d, g.nfeat) * sizeof(float);
+  auto kernel = &k_causal_scan<T, MODE, TT>;
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                          static_cast<int>(sh)) != hipSuccess)
+    return HLA_ERR_HIP;
+  const float dec = hd->cfg.decay > 0.0f && hd->cfg.decay < 1.0f ? hd->cfg.decay : 1.0f;
+  return launch(hd, name, kernel, dim3(a.num_seqs, g.H), dim3(kThreads), sh, a.stream, g, chunks->dev,
+                chunks->seq_off_dev, static_cast<const float*>(hd->feat), a.V,
+                static_cast<const float*>(hd->yhat), dec, out, hd->den, hd->dfeat);
+}
+
+template <typename T, int MODE>
+hla_status causal_scan(hla_handle* hd, const hla_call_args& a, const char* name, View out) {
+  switch (causal_scan_tile(hd->g)) {
+    case 8: return causal_scan_launch<T, MODE, 8>(hd, a, name, out);
+    case 4: return causal_scan_launch<T, MODE, 4>(hd, a, name, out);
+    default: return HLA_ERR_UNSUPPORTED;
+  }
+}
+
 template <typename T>
 hla_status forward_t(hla_handle* hd, const hla_call_args& a) {
   Geom g = hd->g;
@@ -686,6 +887,7 @@ hla_status forward_t(hla_handle* hd, const hla_call_args& a) {
   const int d = g.d;
   const int R = kThreads / d;
   HLA_TRY(features_in_t<T>(hd, a));
+  if (hd->cfg.causal) return causal_scan<T, 0>(hd, a, "generic_causal_forward", a.O);
   hla_token_table *chunks = nullptr, *tiles = nullptr;
   HLA_TRY(get_table(hd, 0, kChunk, s, &chunks));
   HLA_TRY(get_table(hd, 1, kTokPerThread * R, s, &tiles));
@@ -716,6 +918,13 @@ hla_status backward_t(hla_handle* hd, const hla_call_args& a) {
   HLA_TRY(get_table(hd, 2, kDtTile, s, &dtt));
   HLA_TRY(launch(hd, "generic_backward_prep", k_backward_prep<T>, dim3((g.N + R - 1) / R, g.H, g.B),
                  dim3(kThreads), 0, s, g, a.dO, a.O, hd->den, hd->yhat));
+  if (hd->cfg.causal) {
+    // the same state recurrence once more for d(phi_q), its mirror image from the back for
+    // d(phi_k) and dV
+    HLA_TRY((causal_scan<T, 1>(hd, a, "generic_causal_dquery", a.dV)));
+    HLA_TRY((causal_scan<T, 2>(hd, a, "generic_causal_dkey", a.dV)));
+    return features_out_t<T>(hd, a);
+  }
   const int nrows = (g.D + R - 1) / R;
   const size_t sh_acc = (kAccTile * nrows * R + kAccTile * (d + 1) + kAccTile * g.nfeat) * sizeof(float);
   HLA_TRY(launch(hd, "generic_dstate_accumulate", k_accumulate<T, false>, dim3(chunks->count, g.H),
@@ -756,6 +965,7 @@ hla_status generic_workspace_plan(hla_handle* hd) {
   const size_t tile = kTokPerThread * R;
   const size_t sh_c = (tile * g.D + tile * g.nfeat + tile) * sizeof(float);
   if (sh_c > 64 * 1024) return HLA_ERR_UNSUPPORTED;
+  if (hd->cfg.causal && causal_scan_tile(g) == 0) return HLA_ERR_UNSUPPORTED;  // the scan's state does not fit LDS
   return HLA_OK;
 }
 

@@ -1,7 +1,9 @@
 """GPU parity of the causal variant (Sec. 4.4: token i attends to tokens j <= i) through the C ABI,
-forward only: full comparison with the oracle's masked N x N matrix at sizes that span several
-chunks of the scan with ragged tails, sampled rows at the video-DiT size, packed sequences
-without leaks, both forms, through the feature maps, and the error codes."""
+forward and backward: full comparison with the oracle's masked N x N matrix at sizes that span
+several chunks of the scan with ragged tails, sampled rows at the video-DiT size, packed sequences
+without leaks, both forms, through the feature maps, with decay factors, with the value
+modulation on top, on the matrix-core kernels (bf16, 2e-2) and on the fp32 kernels (1e-4), and
+the error codes."""
 import numpy as np
 import pytest
 import torch
@@ -75,10 +77,6 @@ def test_causal_through_feature_maps_packed_no_leak():
     assert torch.equal(got[:, :, :2000], O2.cpu()[:, :, :2000])
     assert not torch.equal(got[:, :, 2000:], O2.cpu()[:, :, 2000:])
     h.destroy()
-    with pytest.raises(hla.HLAError) as e:  # no scan on the fp32 kernels
-        hla.HLA(head_dim=32, feature_dim=6, degree=3, io_dtype=hla.HLA_F32, phi_mode=hla.HLA_PHI_NONE,
-                max_heads=1, max_tokens=8, max_seqs=1, causal=True)
-    assert e.value.code == 2
 
 
 def test_causal_video_size_sampled_rows():
@@ -324,3 +322,71 @@ def test_causal_with_value_modulation_packed_feature_level():
     gpu = pu.run_gpu(t, 3, 6, 1e-6, cu_seqlens=cu, vmod=vm, causal=True, decay=0.995)
     ref = pu.run_oracle(t, 3, 6, 1e-6, cu_seqlens=cu, vmod=vm, route="bruteforce", causal=True, decay=0.995)
     pu.assert_parity(gpu, ref, 2e-2, "causal + value modulation, packed features")
+
+
+# ---- the fp32 kernels: the same scan, token tile by token tile, at the fp32 tolerance ------------
+@pytest.mark.parametrize("F,dphi,d,B,H,N,lam,kind", [
+    (3, 6, 32, 2, 2, 83, 1.0, "halfnormal"),      # ragged last tile of the scan
+    (3, 6, 128, 1, 2, 300, 0.97, "lognormal"),
+    (2, 12, 64, 1, 3, 1100, 0.995, "halfnormal"),  # crosses a chunk boundary of the token table
+    (1, 16, 64, 2, 1, 64, 0.9, "halfnormal"),     # one factor: causal linear attention
+    (4, 4, 128, 1, 1, 40, 1.0, "halfnormal"),     # 256 state rows: the scan steps by four tokens
+    (3, 6, 64, 2, 2, 1, 1.0, "halfnormal"),       # one token
+])
+def test_causal_fp32_kernels_feature_level(F, dphi, d, B, H, N, lam, kind):
+    t = wl.make_feature_inputs(1500 + N, B, H, N, d, F, dphi, torch.float32, kind=kind)
+    gpu = pu.run_gpu(t, F, dphi, 1e-6, path=hla.HLA_PATH_GENERIC, causal=True, decay=lam)
+    assert gpu["_path"] == hla.HLA_PATH_GENERIC
+    ref = pu.run_oracle(t, F, dphi, 1e-6, route="bruteforce", causal=True, decay=lam)
+    what = f"causal fp32 features F={F} dphi={dphi} d={d} N={N} decay={lam}"
+    if N == 1:
+        pu.assert_parity({k: gpu[k] for k in ("O", "dV")}, {k: ref[k] for k in ("O", "dV")}, 1e-4, what)
+        return
+    pu.assert_parity(gpu, ref, 1e-4, what, row_scale=pu.causal_first_token_rows(t, ref))
+    seq = pu.run_oracle(t, F, dphi, 1e-6, route="factorized", causal=True, decay=lam)  # the state recursions
+    pu.assert_parity(gpu, seq, 1e-4, what + " (sequential route)", row_scale=pu.causal_first_token_rows(t, seq))
+
+
+def test_causal_fp32_kernels_through_the_maps_packed_with_weight_gradients():
+    cu = [0, 37, 37, 38, 500, 1300]
+    F, dphi, d, H, lam = 3, 6, 64, 2, 0.99
+    t, phi = wl.make_raw_inputs(1520, 1, H, cu[-1], d, F, dphi, torch.float32)
+    gpu = pu.run_gpu(t, F, dphi, 1e-6, phi=phi, cu_seqlens=cu, path=hla.HLA_PATH_GENERIC, weight_grads=True,
+                     causal=True, decay=lam)
+    ref = pu.run_oracle(t, F, dphi, 1e-6, phi=phi, cu_seqlens=cu, route="bruteforce", weight_grads=True,
+                        causal=True, decay=lam)
+    what = "causal fp32 packed through the maps"
+    pu.assert_parity(gpu, ref, 1e-4, what, kinks=pu.oracle_kinks(t, phi, F, dphi, ref),
+                     row_scale=pu.causal_first_token_rows(t, ref, cu))
+    pu.assert_weight_grad_parity(gpu["wg"], ref["wg"], 1e-4, what,
+                                 branches=pu.oracle_weight_grad_branches(t, phi, F, dphi, ref, cu_seqlens=cu))
+
+
+def test_causal_fp32_kernels_with_value_modulation():
+    F, dphi, d, B, H, N, lam = 3, 6, 32, 2, 2, 150, 0.98
+    t, phi = wl.make_raw_inputs(1530, B, H, N, d, F, dphi, torch.float32)
+    vm = wl.draw_vmod_weights(torch.Generator("cpu").manual_seed(1531), d, torch.float32)
+    gpu = pu.run_gpu(t, F, dphi, 1e-6, phi=phi, path=hla.HLA_PATH_GENERIC, vmod=vm, vmod_weight_grads=True,
+                     causal=True, decay=lam)
+    ref = pu.run_oracle(t, F, dphi, 1e-6, phi=phi, vmod=vm, vmod_weight_grads=True, route="bruteforce",
+                        causal=True, decay=lam)
+    what = "causal fp32 with the value modulation"
+    pu.assert_parity(gpu, {k: v for k, v in ref.items() if k != "vwg"}, 1e-4, what,
+                     kinks=pu.oracle_kinks(t, phi, F, dphi, ref), row_scale=pu.causal_first_token_rows(t, ref))
+    pu.assert_vmod_weight_grad_parity(gpu["vwg"], ref["vwg"], 1e-4, what)
+
+
+def test_causal_fp32_kernels_against_the_matrix_core_kernels_bf16():
+    """Two independent implementations of the scan on the GPU: bf16 inputs through the fp32
+    vector-ALU kernels and through the matrix-core kernels agree with each other as both do with the
+    oracle."""
+    F, dphi, d, B, H, N, lam = 3, 6, 128, 1, 2, 700, 0.99
+    t, phi = wl.make_raw_inputs(1540, B, H, N, d, F, dphi, torch.bfloat16)
+    a = pu.run_gpu(t, F, dphi, 1e-6, phi=phi, path=hla.HLA_PATH_GENERIC, causal=True, decay=lam)
+    b = pu.run_gpu(t, F, dphi, 1e-6, phi=phi, path=hla.HLA_PATH_MFMA, causal=True, decay=lam)
+    assert a["_path"] == hla.HLA_PATH_GENERIC and b["_path"] == hla.HLA_PATH_MFMA
+    ref = pu.run_oracle(t, F, dphi, 1e-6, phi=phi, route="bruteforce", causal=True, decay=lam)
+    kinks = pu.oracle_kinks(t, phi, F, dphi, ref)
+    for name, got in (("fp32 kernels", a), ("matrix cores", b)):
+        pu.assert_parity(got, ref, 2e-2, f"causal bf16 I/O, {name}", kinks=kinks,
+                         row_scale=pu.causal_first_token_rows(t, ref))
