@@ -721,23 +721,45 @@ __global__ __launch_bounds__(kScanThreads) void k_prefix_both(Geom g, const int3
                                      chunk_decay, stride, img_off);
 }
 
+// copies `bytes` (a multiple of 16) from global memory to LDS with all threads of the block
+template <int THREADS>
+__device__ __forceinline__ void stage_image(unsigned char* dst, const unsigned char* src, int bytes) {
+  for (int i = threadIdx.x; i < bytes / 16; i += THREADS)
+    reinterpret_cast<u32x4*>(dst)[i] = reinterpret_cast<const u32x4*>(src)[i];
+}
+
+// Waves per workgroup of k_query_causal: eight (two per SIMD, 256 registers each) where the live
+// set allows it, one query tile per wave; else four with two tiles each.
+template <class SY>
+constexpr int causal_query_waves() {
+  return SY::MP <= 64 && kCausalChunk == 256 ? 8 : 4;
+}
+
 template <class SY, int D>
 struct CausalSmem {
   static constexpr int kTiles = kCausalChunk / 32;
   static constexpr int NKS = SY::MP / 16;
+  static constexpr int kWavesQ = causal_query_waves<SY>();
   static constexpr int kVStride = D * 2 + 32;                  // bytes per token row of the V tile
   static constexpr int kVBytes = kCausalChunk * kVStride;
   static constexpr int kSBytes = kTiles * NKS * 64 * 16;       // key-monomial operand images of the chunk
-  static constexpr int kOutRows = kCausalChunk >= 256 ? 32 : 16;  // rows of a wave's store tile
-  static constexpr int kTotal = kVBytes + kSBytes + kWaves * RowTile<D, kOutRows>::kBytes;
+  static constexpr int kOutRows = kCausalChunk >= 256 && kWavesQ == 4 ? 32 : 16;  // rows of a wave's store tile
+  static constexpr int kBase = kVBytes + kSBytes + kWavesQ * RowTile<D, kOutRows>::kBytes;
+  // the operand image of the state in front of the chunk, read by every wave: an LDS copy where
+  // it fits, each wave's own loads from memory otherwise
+  static constexpr int kImgBytes = SY::MP * D * 2;
+  static constexpr bool kImgLds = kBase + kImgBytes <= 160 * 1024;
+  static constexpr int kTotal = kBase + (kImgLds ? kImgBytes : 0);
 };
 
-// grid (chunks of kCausalChunk tokens, H), block 256.  The workgroup stages the chunk's V rows and
-// the key monomials of its tokens (as MFMA A-operand images, one per 32-key tile) in LDS; wave w
-// then serves query tiles w and 7 - w (equal numbers of key tiles per wave).  Lane (r, gl): query
-// r of the tile, slot half gl, as in k_query.
+// grid (chunks of kCausalChunk tokens, H), block of 4 or 8 waves.  The workgroup stages the chunk's
+// V rows and the key monomials of its tokens (as MFMA A-operand images, one per 32-key tile) in
+// LDS; with four waves, wave w then serves query tiles w and 7 - w (equal numbers of key tiles per
+// wave); with eight, waves w and w + 4 (which share a SIMD) serve tiles w and 7 - w, so that every
+// SIMD still sees nine key tiles but has a second wave to run while one waits.  Lane (r, gl):
+// query r of the tile, slot half gl, as in k_query.
 template <class SY, int D>
-__global__ __launch_bounds__(kThreads) void k_query_causal(Geom g, const BlockEnt* __restrict__ chunks,
+__global__ __launch_bounds__(causal_query_waves<SY>() * 64) void k_query_causal(Geom g, const BlockEnt* __restrict__ chunks,
                                                            const float* __restrict__ feat, View V,
                                                            const unsigned char* __restrict__ pfx, View O,
                                                            float* __restrict__ den, float log2_decay) {
@@ -745,6 +767,9 @@ __global__ __launch_bounds__(kThreads) void k_query_causal(Geom g, const BlockEn
   using PL = PrefixLayout<SY, D>;
   constexpr int SP = SY::SP, MP = SY::MP, DP = SY::DPHI, F = SY::F;
   constexpr int NRB = D / 32, NKS = MP / 16, NF = F * DP;
+  constexpr int WAVES = SM::kWavesQ;
+  constexpr int kRowsPW = kCausalChunk / WAVES;       // rows a wave stages
+  constexpr int kTilesPW = kCausalChunk / 32 / WAVES;  // tiles a wave stages and serves
   extern __shared__ __align__(16) unsigned char smem[];
   const int lane = threadIdx.x % kWave, wave = wave_index();
   unsigned char* vs = smem;
@@ -754,15 +779,17 @@ __global__ __launch_bounds__(kThreads) void k_query_causal(Geom g, const BlockEn
   const int L = lane % 16, q = lane / 16;
   const BlockEnt e = chunks[blockIdx.x];
   const int h = blockIdx.y;
+  const unsigned char* pu = pfx + (static_cast<int64_t>(blockIdx.x) * g.H + h) * PL::kBytes;
+  if constexpr (SM::kImgLds) stage_image<WAVES * 64>(smem + SM::kBase, pu, SM::kImgBytes);
   // ---- the chunk's V rows and key-monomial images, an equal share per wave
   {
-    TileRegs<D, kChunkRowsPerWave> vt;
-    fetch_tile<D, kChunkRowsPerWave>(V, e.b, h, e.t0 + kChunkRowsPerWave * wave, e.t1, lane, vt);
-    put_tile<D, kChunkRowsPerWave>(vt, lane, vs + kChunkRowsPerWave * wave * SM::kVStride, SM::kVStride);
+    TileRegs<D, kRowsPW> vt;
+    fetch_tile<D, kRowsPW>(V, e.b, h, e.t0 + kRowsPW * wave, e.t1, lane, vt);
+    put_tile<D, kRowsPW>(vt, lane, vs + kRowsPW * wave * SM::kVStride, SM::kVStride);
   }
 #pragma unroll 1
-  for (int tt = 0; tt < kChunkTilesPerWave; ++tt) {
-    const int t = kChunkTilesPerWave * wave + tt;
+  for (int tt = 0; tt < kTilesPW; ++tt) {
+    const int t = kTilesPW * wave + tt;
     const int n = e.t0 + 32 * t + r;
     float kf[NF], kr[NF];
     if (n < e.t1) {
@@ -801,12 +828,11 @@ __global__ __launch_bounds__(kThreads) void k_query_causal(Geom g, const BlockEn
 #pragma unroll
   for (int i = 0; i < 16; ++i)
     rowfac[i] = log2_decay != 0.0f ? __builtin_amdgcn_exp2f(log2_decay * static_cast<float>(31 - d_row(i, gl))) : 1.0f;
-  const unsigned char* pu = pfx + (static_cast<int64_t>(blockIdx.x) * g.H + h) * PL::kBytes;
-  const u32x4* opA = reinterpret_cast<const u32x4*>(pu);
+  const u32x4* opA = reinterpret_cast<const u32x4*>(SM::kImgLds ? smem + SM::kBase : pu);
   const float* zslot = reinterpret_cast<const float*>(pu + PL::kOpElems * 2) + gl * SP;
 #pragma unroll 1
-  for (int qi = 0; qi < kChunkTilesPerWave; ++qi) {
-    const int qt = chunk_tile_of(wave, qi);
+  for (int qi = 0; qi < kTilesPW; ++qi) {
+    const int qt = WAVES == 8 ? (wave < 4 ? wave : 11 - wave) : chunk_tile_of(wave, qi);
     const int n0 = e.t0 + 32 * qt;
     if (n0 >= e.t1) continue;
     const int n = n0 + r;
@@ -1495,13 +1521,25 @@ template <class SY, int D>
 struct CgSmem {
   static constexpr int kTiles = kCausalChunk / 32;
   static constexpr int kRStride = D * 2 + 32;          // bytes per token row of the row tile
-  static constexpr int kMStride = SY::MP * 2 + 32;     // bytes per token row of the monomial tile
+  // bytes per token row of the monomial tile: rows 36 (52) dwords apart keep both its 8-byte row
+  // reads and its transpose reads (four rows of 32 bytes per 16 lanes) off each other's banks
+  static constexpr int kMStride = SY::MP * 2 + 16;
   static constexpr int kRBytes = kCausalChunk * kRStride;
   static constexpr int kMBytes = kCausalChunk * kMStride;
   static constexpr int kTBytes = kCausalChunk * 4;     // t_i of the chunk's queries (key side)
-  static constexpr int kTotalQ = kRBytes + kMBytes;
-  static constexpr int kTotalK = kRBytes + kMBytes + kTBytes + kWaves * RowTile<D, 16>::kBytes;
+  static constexpr int kImgBytes = SY::MP * D * 2;     // one operand image of a state
+  static constexpr int kLdsLimit = 160 * 1024;
+  // The images of the state in front of / behind the chunk are read by every wave, for each of
+  // its tiles: from an LDS copy where that fits, from memory otherwise (each wave's own loads:
+  // eight times the traffic, and measured at a third of the key-side kernel's time).
+  static constexpr int kBaseQ = kRBytes + kMBytes;
+  static constexpr bool kImgLdsQ = kBaseQ + kImgBytes <= kLdsLimit;
+  static constexpr int kTotalQ = kBaseQ + (kImgLdsQ ? kImgBytes : 0);
+  static constexpr int kBaseK = kRBytes + kMBytes + kTBytes + kWaves * RowTile<D, 16>::kBytes;
+  static constexpr bool kImgLdsK = kBaseK + 2 * kImgBytes <= kLdsLimit;
+  static constexpr int kTotalK = kBaseK + (kImgLdsK ? 2 * kImgBytes : 0);
 };
+
 
 // column (in elements) of slot (g, s) in the monomial tile
 __device__ __forceinline__ int rho_of(int g, int s) { return 32 * (s / 16) + 8 * ((s % 16) / 4) + 4 * g + s % 4; }
@@ -1573,7 +1611,7 @@ __device__ __forceinline__ void transposed_product(const unsigned char* tile, in
 // feature gradients and s_i (sv) for the key side.  rows_img / z_img: per (chunk, head) the
 // monomial-row image of the state in front of the chunk and its normaliser by slot.
 template <class SY, int D>
-__global__ __launch_bounds__(kThreads) void k_cgrad_q(Geom g, const BlockEnt* __restrict__ chunks,
+__global__ __launch_bounds__(causal_query_waves<SY>() * 64) void k_cgrad_q(Geom g, const BlockEnt* __restrict__ chunks,
                                                       const float* __restrict__ feat,
                                                       const float* __restrict__ den, View V, View dO,
                                                       const unsigned char* __restrict__ rows_img,
@@ -1585,6 +1623,9 @@ __global__ __launch_bounds__(kThreads) void k_cgrad_q(Geom g, const BlockEnt* __
   using SM = CgSmem<SY, D>;
   constexpr int SP = SY::SP, MP = SY::MP, DP = SY::DPHI, F = SY::F;
   constexpr int NKD = D / 16, NRM = MP / 32, NF = F * DP;
+  constexpr int WAVES = causal_query_waves<SY>();      // see k_query_causal
+  constexpr int kRowsPW = kCausalChunk / WAVES;        // rows a wave stages
+  constexpr int kTilesPW = kCausalChunk / 32 / WAVES;  // tiles a wave stages and serves
   extern __shared__ __align__(16) unsigned char smem[];
   const int lane = threadIdx.x % kWave, wave = wave_index();
   unsigned char* rt = smem;
@@ -1592,15 +1633,18 @@ __global__ __launch_bounds__(kThreads) void k_cgrad_q(Geom g, const BlockEnt* __
   const int r = lane % 32, gl = lane / 32;
   const BlockEnt e = chunks[blockIdx.x];
   const int h = blockIdx.y;
-  // ---- the chunk's V rows (64 per wave) and key monomials (two tiles per wave)
+  const int64_t ch_h = static_cast<int64_t>(blockIdx.x) * g.H + h;
+  // the monomial-row image of the state in front of the chunk: an LDS copy where it fits
+  if constexpr (SM::kImgLdsQ) stage_image<WAVES * 64>(smem + SM::kBaseQ, rows_img + ch_h * rows_stride, SM::kImgBytes);
+  // ---- the chunk's V rows and key monomials, an equal share per wave
   {
-    TileRegs<D, kChunkRowsPerWave> vt;
-    fetch_tile<D, kChunkRowsPerWave>(V, e.b, h, e.t0 + kChunkRowsPerWave * wave, e.t1, lane, vt);
-    put_tile<D, kChunkRowsPerWave>(vt, lane, rt + kChunkRowsPerWave * wave * SM::kRStride, SM::kRStride);
+    TileRegs<D, kRowsPW> vt;
+    fetch_tile<D, kRowsPW>(V, e.b, h, e.t0 + kRowsPW * wave, e.t1, lane, vt);
+    put_tile<D, kRowsPW>(vt, lane, rt + kRowsPW * wave * SM::kRStride, SM::kRStride);
   }
 #pragma unroll 1
-  for (int tt = 0; tt < kChunkTilesPerWave; ++tt) {
-    const int t = kChunkTilesPerWave * wave + tt;
+  for (int tt = 0; tt < kTilesPW; ++tt) {
+    const int t = kTilesPW * wave + tt;
     const int n = e.t0 + 32 * t + r;
     float kf[NF], kr[NF];
     if (n < e.t1) {
@@ -1635,12 +1679,11 @@ __global__ __launch_bounds__(kThreads) void k_cgrad_q(Geom g, const BlockEnt* __
 #pragma unroll
   for (int i = 0; i < 16; ++i)
     rowfac[i] = log2_decay != 0.0f ? __builtin_amdgcn_exp2f(log2_decay * static_cast<float>(31 - d_row(i, gl))) : 1.0f;
-  const int64_t ch_h = static_cast<int64_t>(blockIdx.x) * g.H + h;
-  const u32x4* opB = reinterpret_cast<const u32x4*>(rows_img + ch_h * rows_stride);
+  const u32x4* opB = reinterpret_cast<const u32x4*>(SM::kImgLdsQ ? smem + SM::kBaseQ : rows_img + ch_h * rows_stride);
   const float* zslot = reinterpret_cast<const float*>(z_img + ch_h * z_stride) + gl * SP;
 #pragma unroll 1
-  for (int qi = 0; qi < kChunkTilesPerWave; ++qi) {
-    const int qt = chunk_tile_of(wave, qi);
+  for (int qi = 0; qi < kTilesPW; ++qi) {
+    const int qt = WAVES == 8 ? (wave < 4 ? wave : 11 - wave) : chunk_tile_of(wave, qi);
     const int n0 = e.t0 + 32 * qt;
     if (n0 >= e.t1) continue;
     const int n = n0 + r;
@@ -1771,38 +1814,69 @@ __global__ __launch_bounds__(kThreads) void k_cgrad_q(Geom g, const BlockEnt* __
   }
 }
 
-// grid (chunks of kCausalChunk tokens, H), block 256.  Key side: writes the key part of the feature
-// gradients and dV.  dops: per (chunk, head) the images of the gradient state behind the chunk.
+// grid (chunks of kCausalChunk tokens, H), block of eight waves.  Key side: writes the key part of
+// the feature gradients and dV.  dops: per (chunk, head) the images of the gradient state behind
+// the chunk.  A key tile has two results, dS (-> the feature gradients) and dv, which share nothing
+// but the tile's weights: wave w < 4 computes dS and wave w + 4 (same SIMD) dv of key tiles w and
+// 7 - w, twelve MFMAs per query tile each, so that a SIMD always has a second wave to run while one
+// waits for LDS, and each role's live set fits the 256 registers a wave then has.
+constexpr int kWavesCK = 8;
+static_assert(kCausalChunk / 32 == kWavesCK, "one staged tile per wave, two key tiles per wave pair");
+
+// weights of a tile's entries (query d_row(i, gl) of tile qt against key r of tile kt): 1 behind
+// the diagonal tile, there 0 for queries in front of the key; with a decay factor
+// decay^(distance), factored behind the diagonal tile (distance >= 1) into a per-lane and a
+// per-register part (rowfac[i] = decay^d_row(i, gl))
+__device__ __forceinline__ void key_tile_weights(int qt, int kt, int r, int gl, float log2_decay,
+                                                 const float (&rowfac)[16], float (&wv)[16]) {
+  const float cw = qt > kt && log2_decay != 0.0f
+                       ? __builtin_amdgcn_exp2f(log2_decay * static_cast<float>(32 * (qt - kt) - r))
+                       : 1.0f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    if (qt > kt) {
+      wv[i] = cw * rowfac[i];
+    } else {
+      const float dist = static_cast<float>(d_row(i, gl) - r);
+      wv[i] = dist < 0.0f ? 0.0f : (log2_decay != 0.0f ? __builtin_amdgcn_exp2f(log2_decay * dist) : 1.0f);
+    }
+  }
+}
+
 template <class SY, int D>
-__global__ __launch_bounds__(kThreads) void k_cgrad_k(Geom g, const BlockEnt* __restrict__ chunks,
-                                                      const float* __restrict__ feat,
-                                                      const float* __restrict__ den,
-                                                      const float* __restrict__ sv, View V, View dO,
-                                                      const unsigned char* __restrict__ dops,
-                                                      float* __restrict__ dfeat, View dV,
-                                                      float log2_decay, int relu_mask) {
+__global__ __launch_bounds__(kWavesCK * 64) void k_cgrad_k(
+    Geom g, const BlockEnt* __restrict__ chunks, const float* __restrict__ feat,
+    const float* __restrict__ den, const float* __restrict__ sv, View V, View dO,
+    const unsigned char* __restrict__ dops, float* __restrict__ dfeat, View dV, float log2_decay,
+    int relu_mask) {
   using SM = CgSmem<SY, D>;
   using SL = StateLayout<SY, D>;
   constexpr int SP = SY::SP, MP = SY::MP, DP = SY::DPHI, F = SY::F;
   constexpr int NRB = D / 32, NKD = D / 16, NRM = MP / 32, NKS = MP / 16, NF = F * DP;
+  constexpr int kRowsPW = kCausalChunk / kWavesCK;  // rows a wave stages
   extern __shared__ __align__(16) unsigned char smem[];
   const int lane = threadIdx.x % kWave, wave = wave_index();
+  const int wt = wave % 4;  // this wave's share of the key tiles: wt and 7 - wt
   unsigned char* rt = smem;
   unsigned char* mt = smem + SM::kRBytes;
   float* tq = reinterpret_cast<float*>(smem + SM::kRBytes + SM::kMBytes);
-  unsigned char* tile = smem + SM::kRBytes + SM::kMBytes + SM::kTBytes + wave * RowTile<D, 16>::kBytes;
+  unsigned char* tile = smem + SM::kRBytes + SM::kMBytes + SM::kTBytes + wt * RowTile<D, 16>::kBytes;
   const int r = lane % 32, gl = lane / 32;
   const BlockEnt e = chunks[blockIdx.x];
   const int h = blockIdx.y;
-  // ---- the chunk's dO rows (64 per wave), scaled query monomials Qm / den and t = s den
+  const unsigned char* pu = dops + (static_cast<int64_t>(blockIdx.x) * g.H + h) * SL::kOpBytes;
+  // the two images of the gradient state behind the chunk (channel rows for dv, monomial rows for dS)
+  if constexpr (SM::kImgLdsK) stage_image<kWavesCK * 64>(smem + SM::kBaseK, pu, 2 * SM::kImgBytes);
+  const u32x4* opA = reinterpret_cast<const u32x4*>(SM::kImgLdsK ? smem + SM::kBaseK : pu);
+  const u32x4* opB = reinterpret_cast<const u32x4*>(SM::kImgLdsK ? smem + SM::kBaseK + SM::kImgBytes : pu + SL::kOpElems * 2);
+  // ---- the chunk's dO rows, scaled query monomials Qm / den and t = s den: 32 tokens per wave
   {
-    TileRegs<D, kChunkRowsPerWave> vt;
-    fetch_tile<D, kChunkRowsPerWave>(dO, e.b, h, e.t0 + kChunkRowsPerWave * wave, e.t1, lane, vt);
-    put_tile<D, kChunkRowsPerWave>(vt, lane, rt + kChunkRowsPerWave * wave * SM::kRStride, SM::kRStride);
+    TileRegs<D, kRowsPW> vt;
+    fetch_tile<D, kRowsPW>(dO, e.b, h, e.t0 + kRowsPW * wave, e.t1, lane, vt);
+    put_tile<D, kRowsPW>(vt, lane, rt + kRowsPW * wave * SM::kRStride, SM::kRStride);
   }
-#pragma unroll 1
-  for (int tt = 0; tt < kChunkTilesPerWave; ++tt) {
-    const int t = kChunkTilesPerWave * wave + tt;
+  {
+    const int t = wave;
     const int n = e.t0 + 32 * t + r;
     const bool live = n < e.t1;
     const int64_t th = g.th(e.b, h, live ? n : e.t1 - 1);
@@ -1823,38 +1897,24 @@ __global__ __launch_bounds__(kThreads) void k_cgrad_k(Geom g, const BlockEnt* __
     if (gl == 0) tq[32 * t + r] = live ? sv[th] * dn : 0.0f;
   }
   __syncthreads();
-  // decay^(query row of accumulator register i): the per-register part of an off-diagonal tile's
-  // weights (1 without decay)
   float rowfac[16];
 #pragma unroll
   for (int i = 0; i < 16; ++i)
     rowfac[i] = log2_decay != 0.0f ? __builtin_amdgcn_exp2f(log2_decay * static_cast<float>(d_row(i, gl))) : 1.0f;
-  const unsigned char* pu = dops + (static_cast<int64_t>(blockIdx.x) * g.H + h) * SL::kOpBytes;
-  const u32x4* opA = reinterpret_cast<const u32x4*>(pu);
-  const u32x4* opB = reinterpret_cast<const u32x4*>(pu + SL::kOpElems * 2);
-  const float* dzslot = reinterpret_cast<const float*>(pu + 2 * SL::kOpElems * 2) + gl * SP;
+  const int last = (e.t1 - e.t0 + 31) / 32 - 1;  // the chunk's last query tile
 #pragma unroll 1
-  for (int ki = 0; ki < kChunkTilesPerWave; ++ki) {
-    const int kt = chunk_tile_of(wave, ki);
+  for (int ki = 0; ki < 2; ++ki) {
+    const int kt = ki == 0 ? wt : kCausalChunk / 32 - 1 - wt;
     const int n0 = e.t0 + 32 * kt;
     if (n0 >= e.t1) continue;
     const int n = n0 + r;
     const bool live = n < e.t1;
     const int64_t th = g.th(e.b, h, live ? n : e.t1 - 1);
-    u32x4 bv[NKD];
-    {
-      const bf16_t* row = V.row<const bf16_t>(e.b, h, live ? n : e.t1 - 1);
-#pragma unroll
-      for (int kd = 0; kd < NKD; ++kd) {
-        bv[kd] = *reinterpret_cast<const u32x4*>(row + 16 * kd + 8 * gl);
-        if (!live) bv[kd][0] = bv[kd][1] = bv[kd][2] = bv[kd][3] = 0u;
-      }
-    }
-    float kb[NF];
+    // the key's features: lane half 1 holds every map's reversed
     float kk[F][DP];
     {
       const f32x2* f = reinterpret_cast<const f32x2*>(feat + g.fidx(th, DP));
-      float kr[NF];
+      float kb[NF], kr[NF];
 #pragma unroll
       for (int p = 0; p < NF / 2; ++p) {
         const f32x2 v = f[32 * p];
@@ -1870,133 +1930,159 @@ __global__ __launch_bounds__(kThreads) void k_cgrad_k(Geom g, const BlockEnt* __
 #pragma unroll
         for (int c = 0; c < DP; ++c) kk[f2][c] = gl ? kr[f2 * DP + c] : kb[f2 * DP + c];
     }
-    float sm[SP];
-    sym_key_monomials_slots<SY>(kk, sm, gl);
-    u32x4 bS[NKS];
+    // the chunks behind enter as seen from the chunk's last token
+    const float wk = log2_decay != 0.0f
+                         ? __builtin_amdgcn_exp2f(log2_decay * static_cast<float>(kCausalChunk - 1 - (32 * kt + r)))
+                         : 1.0f;
+    if (wave < 4) {
+      // ---- dS^T = (gradient state) v + dz  +  sum over the chunk's queries, then the chain rule
+      const float* dzslot = reinterpret_cast<const float*>(pu + 2 * SL::kOpElems * 2) + gl * SP;
+      u32x4 bv[NKD];
+      {
+        const bf16_t* row = V.row<const bf16_t>(e.b, h, live ? n : e.t1 - 1);
 #pragma unroll
-    for (int ks = 0; ks < NKS; ++ks)
-#pragma unroll
-      for (int p = 0; p < 4; ++p) bS[ks][p] = pack_bf16(sm[8 * ks + 2 * p], sm[8 * ks + 2 * p + 1]);
-    // the chunks behind: dS = (gradient state) v + dz, dv = (gradient state)^T S, as seen from the
-    // chunk's last token
-    f32x16 Y[NRM], dvT[NRB];
-#pragma unroll
-    for (int rb = 0; rb < NRM; ++rb) {
-#pragma unroll
-      for (int i4 = 0; i4 < 4; ++i4) {
-        const f32x4 z = *reinterpret_cast<const f32x4*>(dzslot + 16 * rb + 4 * i4);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) Y[rb][4 * i4 + i] = z[i];
-      }
-#pragma unroll
-      for (int kd = 0; kd < NKD; ++kd) Y[rb] = mfma32(opB[(rb * NKD + kd) * 64 + lane], bv[kd], Y[rb]);
-    }
-#pragma unroll
-    for (int rb = 0; rb < NRB; ++rb) {
-#pragma unroll
-      for (int i = 0; i < 16; ++i) dvT[rb][i] = 0.0f;
-#pragma unroll
-      for (int ks = 0; ks < NKS; ++ks) dvT[rb] = mfma32(opA[(rb * NKS + ks) * 64 + lane], bS[ks], dvT[rb]);
-    }
-    if (log2_decay != 0.0f) {
-      const float wk = __builtin_amdgcn_exp2f(log2_decay * static_cast<float>(kCausalChunk - 1 - (32 * kt + r)));
-#pragma unroll
-      for (int rb = 0; rb < NRM; ++rb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) Y[rb][i] *= wk;
-#pragma unroll
-      for (int rb = 0; rb < NRB; ++rb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) dvT[rb][i] *= wk;
-    }
-    // the chunk's own queries from the key on: query tiles kt .. last
-    const int last = (e.t1 - e.t0 + 31) / 32 - 1;
-#pragma unroll 1
-    for (int qt = kt; qt <= last; ++qt) {
-      const f32x16 E = rows_product<D>(rt, SM::kRStride, qt, lane, bv);  // <dO_i, v_j>
-      // <Qm'_i, S_j>: A = row reads of the monomial tile, the eight k-slots (g, 8 ks + j) of a
-      // k-step as two runs of four columns
-      f32x16 A;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) A[i] = 0.0f;
-#pragma unroll
-      for (int ks = 0; ks < NKS; ++ks) {
-        const unsigned char* p = mt + (32 * qt + r) * SM::kMStride + rho_of(gl, 8 * ks) * 2;
-        const u32x2 lo = *reinterpret_cast<const u32x2*>(p);
-        const u32x2 hi = *reinterpret_cast<const u32x2*>(p + 16);
-        u32x4 a;
-        a[0] = lo[0];
-        a[1] = lo[1];
-        a[2] = hi[0];
-        a[3] = hi[1];
-        A = mfma32(a, bS[ks], A);
-      }
-      // weights of the tile's entries (query d_row(i, gl) of tile qt against key r): 1 behind the
-      // diagonal tile, there 0 for queries in front of the key; with a decay factor
-      // decay^(distance), factored behind the diagonal tile (distance >= 1) as on the query side
-      u32x4 bE[2], bA[2];
-#pragma unroll
-      for (int ks2 = 0; ks2 < 2; ++ks2) {
-        const f32x4 t0 = *reinterpret_cast<const f32x4*>(tq + 32 * qt + 16 * ks2 + 4 * gl);
-        const f32x4 t1 = *reinterpret_cast<const f32x4*>(tq + 32 * qt + 16 * ks2 + 4 * gl + 8);
-        const float cw = qt > kt && log2_decay != 0.0f ? __builtin_amdgcn_exp2f(log2_decay * static_cast<float>(32 * (qt - kt) - r)) : 1.0f;
-#pragma unroll
-        for (int p = 0; p < 4; ++p) {
-          float wv[2], tv[2];
-#pragma unroll
-          for (int x = 0; x < 2; ++x) {
-            const int i = 8 * ks2 + 2 * p + x;  // query d_row(i, gl) = 16 ks2 + 8 (p / 2) + 4 gl + (2 p + x) % 4
-            if (qt > kt) {
-              wv[x] = cw * rowfac[i];
-            } else {
-              const float dist = static_cast<float>(d_row(i, gl) - r);
-              wv[x] = dist < 0.0f ? 0.0f : (log2_decay != 0.0f ? __builtin_amdgcn_exp2f(log2_decay * dist) : 1.0f);
-            }
-            tv[x] = p < 2 ? t0[(2 * p + x) % 4] : t1[(2 * p + x) % 4];
-          }
-          bE[ks2][p] = pack_bf16((E[8 * ks2 + 2 * p] + tv[0]) * wv[0], (E[8 * ks2 + 2 * p + 1] + tv[1]) * wv[1]);
-          bA[ks2][p] = pack_bf16(A[8 * ks2 + 2 * p] * wv[0], A[8 * ks2 + 2 * p + 1] * wv[1]);
+        for (int kd = 0; kd < NKD; ++kd) {
+          bv[kd] = *reinterpret_cast<const u32x4*>(row + 16 * kd + 8 * gl);
+          if (!live) bv[kd][0] = bv[kd][1] = bv[kd][2] = bv[kd][3] = 0u;
         }
       }
-      transposed_product<NRM>(mt, SM::kMStride, qt, lane, bE, Y);
-      transposed_product<NRB>(rt, SM::kRStride, qt, lane, bA, dvT);
-    }
-    // chain rule to the key features
-    float dk[F][DP];
-    {
-      float ds[SP];
+      f32x16 Y[NRM];
 #pragma unroll
-      for (int rb = 0; rb < NRM; ++rb)
+      for (int rb = 0; rb < NRM; ++rb) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) ds[16 * rb + i] = Y[rb][i];
+        for (int i4 = 0; i4 < 4; ++i4) {
+          const f32x4 z = *reinterpret_cast<const f32x4*>(dzslot + 16 * rb + 4 * i4);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) Y[rb][4 * i4 + i] = z[i];
+        }
+#pragma unroll
+        for (int kd = 0; kd < NKD; ++kd) Y[rb] = mfma32(opB[(rb * NKD + kd) * 64 + lane], bv[kd], Y[rb]);
+      }
+
+      if (log2_decay != 0.0f) {
+#pragma unroll
+        for (int rb = 0; rb < NRM; ++rb)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) Y[rb][i] *= wk;
+      }
+#pragma unroll 1
+      for (int qt = kt; qt <= last; ++qt) {
+        float wv[16];
+        key_tile_weights(qt, kt, r, gl, log2_decay, rowfac, wv);
+        const f32x16 E = rows_product<D>(rt, SM::kRStride, qt, lane, bv);  // <dO_i, v_j>
+        u32x4 bE[2];
+#pragma unroll
+        for (int ks2 = 0; ks2 < 2; ++ks2) {
+          // t of query d_row(i, gl) = 16 ks2 + 8 (p / 2) + 4 gl + (2 p + x) % 4, i = 8 ks2 + 2 p + x
+          const f32x4 t0 = *reinterpret_cast<const f32x4*>(tq + 32 * qt + 16 * ks2 + 4 * gl);
+          const f32x4 t1 = *reinterpret_cast<const f32x4*>(tq + 32 * qt + 16 * ks2 + 4 * gl + 8);
+#pragma unroll
+          for (int p = 0; p < 4; ++p) {
+            const int i = 8 * ks2 + 2 * p;
+            const float ta = p < 2 ? t0[(2 * p) % 4] : t1[(2 * p) % 4];
+            const float tb = p < 2 ? t0[(2 * p + 1) % 4] : t1[(2 * p + 1) % 4];
+            bE[ks2][p] = pack_bf16((E[i] + ta) * wv[i], (E[i + 1] + tb) * wv[i + 1]);
+          }
+        }
+        transposed_product<NRM>(mt, SM::kMStride, qt, lane, bE, Y);
+      }
+      float dk[F][DP];
+      {
+        float ds[SP];
+#pragma unroll
+        for (int rb = 0; rb < NRM; ++rb)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) ds[16 * rb + i] = Y[rb][i];
+#pragma unroll
+        for (int f2 = 0; f2 < F; ++f2)
+#pragma unroll
+          for (int c = 0; c < DP; ++c) dk[f2][c] = 0.0f;
+        sym_key_monomials_grad_range<SY, 0, SY::NS>(kk, ds, dk, gl);
+      }
+      float other[F][DP];
 #pragma unroll
       for (int f2 = 0; f2 < F; ++f2)
 #pragma unroll
-        for (int c = 0; c < DP; ++c) dk[f2][c] = 0.0f;
-      sym_key_monomials_grad_range<SY, 0, SY::NS>(kk, ds, dk, gl);
-    }
-    float other[F][DP];
+        for (int c = 0; c < DP; ++c) other[f2][c] = partner32(dk[f2][c]);
+      if (live && gl == 0) {
+        f32x2* df = reinterpret_cast<f32x2*>(dfeat + g.fidx(th, DP));
 #pragma unroll
-    for (int f2 = 0; f2 < F; ++f2)
+        for (int p = 0; p < NF / 2; ++p) {
+          f32x2 v;
 #pragma unroll
-      for (int c = 0; c < DP; ++c) other[f2][c] = partner32(dk[f2][c]);
-    if (live && gl == 0) {
-      f32x2* df = reinterpret_cast<f32x2*>(dfeat + g.fidx(th, DP));
-#pragma unroll
-      for (int p = 0; p < NF / 2; ++p) {
-        f32x2 v;
-#pragma unroll
-        for (int x = 0; x < 2; ++x) {
-          const int a = 2 * p + x, f2 = a / DP, c = a % DP;
-          const float val = dk[f2][c] + other[f2][DP - 1 - c];
-          v[x] = (!relu_mask || kb[a] > 0.0f) ? val : 0.0f;
+          for (int x = 0; x < 2; ++x) {
+            const int a = 2 * p + x, f2 = a / DP, c = a % DP;
+            const float val = dk[f2][c] + other[f2][DP - 1 - c];
+            v[x] = (!relu_mask || kk[f2][c] > 0.0f) ? val : 0.0f;  // gl == 0: the features in order
+          }
+          df[32 * p] = v;
         }
-        df[32 * p] = v;
       }
+    } else {
+      // ---- dv^T = (gradient state)^T S  +  sum over the chunk's queries of w <Qm'_i, S_j> dO_i
+      u32x4 bS[NKS];
+      {
+        float sm[SP];
+        sym_key_monomials_slots<SY>(kk, sm, gl);
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks)
+#pragma unroll
+          for (int p = 0; p < 4; ++p) bS[ks][p] = pack_bf16(sm[8 * ks + 2 * p], sm[8 * ks + 2 * p + 1]);
+      }
+      f32x16 dvT[NRB];
+#pragma unroll
+      for (int rb = 0; rb < NRB; ++rb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) dvT[rb][i] = 0.0f;
+#pragma unroll 1
+      for (int qt = kt; qt <= last; ++qt) {
+        float wv[16];
+        key_tile_weights(qt, kt, r, gl, log2_decay, rowfac, wv);
+        // <Qm'_i, S_j>: A = row reads of the monomial tile, the eight k-slots (g, 8 ks + j) of a
+        // k-step as two runs of four columns
+        u32x4 am[NKS];
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+          const unsigned char* p = mt + (32 * qt + r) * SM::kMStride + rho_of(gl, 8 * ks) * 2;
+          const u32x2 lo = *reinterpret_cast<const u32x2*>(p);
+          const u32x2 hi = *reinterpret_cast<const u32x2*>(p + 16);
+          am[ks][0] = lo[0];
+          am[ks][1] = lo[1];
+          am[ks][2] = hi[0];
+          am[ks][3] = hi[1];
+        }
+        f32x16 A;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) A[i] = 0.0f;
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) A = mfma32(am[ks], bS[ks], A);
+        u32x4 bA[2];
+#pragma unroll
+        for (int ks2 = 0; ks2 < 2; ++ks2)
+#pragma unroll
+          for (int p = 0; p < 4; ++p) {
+            const int i = 8 * ks2 + 2 * p;
+            bA[ks2][p] = pack_bf16(A[i] * wv[i], A[i + 1] * wv[i + 1]);
+          }
+        transposed_product<NRB>(rt, SM::kRStride, qt, lane, bA, dvT);
+      }
+      // the chunks behind (the key's weight wk goes into the B operand)
+      {
+        u32x4 bSw[NKS];
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks)
+#pragma unroll
+          for (int p = 0; p < 4; ++p)
+            bSw[ks][p] = log2_decay != 0.0f ? pack_bf16(bf16_lo(bS[ks][p]) * wk, bf16_hi(bS[ks][p]) * wk) : bS[ks][p];
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb)
+#pragma unroll
+          for (int ks = 0; ks < NKS; ++ks) dvT[rb] = mfma32(opA[(rb * NKS + ks) * 64 + lane], bSw[ks], dvT[rb]);
+      }
+      store_rows_bf16<D, 16>(dvT, 1.0f, lane, tile, [&](int t) -> bf16_t* {
+        return n0 + t < e.t1 ? dV.row<bf16_t>(e.b, h, n0 + t) : nullptr;
+      });
     }
-    store_rows_bf16<D, 16>(dvT, 1.0f, lane, tile, [&](int t) -> bf16_t* {
-      return n0 + t < e.t1 ? dV.row<bf16_t>(e.b, h, n0 + t) : nullptr;
-    });
   }
 }
 
@@ -2035,7 +2121,7 @@ hla_status backward_causal(hla_handle* hd, const hla_call_args& a) {
                    cch->count));
   HLA_TRY(launch(hd, "mfma_state_prefix_rows", k_prefix_rows<SY, D, false>, rgrid, dim3(kScanThreads), 0, s, g,
                  cch->seq_off_dev, hd->partial, SL::kF32, ops, cm, chunk_decay, stride, b_off));
-  HLA_TRY(launch(hd, "mfma_causal_grad_query", k_cgrad_q<SY, D>, dim3(cch->count, g.H), dim3(kThreads),
+  HLA_TRY(launch(hd, "mfma_causal_grad_query", k_cgrad_q<SY, D>, dim3(cch->count, g.H), dim3(causal_query_waves<SY>() * 64),
                  SG::kTotalQ, s, g, cch->dev, hd->feat, hd->den, a.V, a.dO,
                  static_cast<const unsigned char*>(ops + b_off), stride,
                  pfx + PL::kOpElems * 2, static_cast<int64_t>(PL::kBytes), hd->dfeat, hd->yhat, l2d, relu_mask));
@@ -2047,7 +2133,7 @@ hla_status backward_causal(hla_handle* hd, const hla_call_args& a) {
   HLA_TRY(launch(hd, "mfma_dstate_suffix", k_prefix_both<SY, D, true>, dim3(a.num_seqs, g.H, sgrid.z + rgrid.z),
                  dim3(kScanThreads), 0, s, g, cch->seq_off_dev, hd->partial, SL::kF32, dops, cm, chunk_decay, stride,
                  z_off, b_off, static_cast<int>(sgrid.z)));
-  HLA_TRY(launch(hd, "mfma_causal_grad_key", k_cgrad_k<SY, D>, dim3(cch->count, g.H), dim3(kThreads),
+  HLA_TRY(launch(hd, "mfma_causal_grad_key", k_cgrad_k<SY, D>, dim3(cch->count, g.H), dim3(kWavesCK * 64),
                  SG::kTotalK, s, g, cch->dev, hd->feat, hd->den, static_cast<const float*>(hd->yhat), a.V, a.dO,
                  dops, hd->dfeat, a.dV, l2d, relu_mask));
   return HLA_OK;
@@ -2122,7 +2208,7 @@ hla_status forward_causal(hla_handle* hd, const hla_call_args& a) {
   HLA_TRY(launch(hd, "mfma_state_prefix", k_prefix<SY, D, false>, dim3(a.num_seqs, g.H, 2 * (SY::MP / 16) * D / kScanThreads + 1),
                  dim3(kScanThreads), 0, s, g, cch->seq_off_dev, hd->partial, SL::kF32, pfx, make_canon_map<SY>(), chunk_decay,
                  static_cast<int64_t>(PL::kBytes), static_cast<int64_t>(PL::kOpElems * 2)));
-  HLA_TRY(launch(hd, "mfma_query_causal", k_query_causal<SY, D>, dim3(cch->count, g.H), dim3(kThreads),
+  HLA_TRY(launch(hd, "mfma_query_causal", k_query_causal<SY, D>, dim3(cch->count, g.H), dim3(SC::kWavesQ * 64),
                  SC::kTotal, s, g, cch->dev, hd->feat, a.V, pfx, a.O, hd->den, l2d));
   hd->causal_partials_valid = true;  // the partial buffer holds this forward's chunk states
   return HLA_OK;
