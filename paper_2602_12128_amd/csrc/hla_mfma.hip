@@ -6,6 +6,8 @@
 //   k_query   : O^T = Csym^T Qm^T, eta = Qm . zsym, O = num / (eta + eps)
 // Lanes serve tokens: in every token-parallel kernel a token is the MFMA *column*, so per-token
 // scalars (eta, den, s) live in one lane pair and never need a cross-lane broadcast.
+#include <type_traits>
+
 #include "hla_handle.h"
 #include "hla_mfma_common.h"
 
@@ -721,12 +723,29 @@ __global__ __launch_bounds__(kScanThreads) void k_prefix_both(Geom g, const int3
                                      chunk_decay, stride, img_off);
 }
 
-// copies `bytes` (a multiple of 16) from global memory to LDS with all threads of the block
-template <int THREADS>
-__device__ __forceinline__ void stage_image(unsigned char* dst, const unsigned char* src, int bytes) {
-  for (int i = threadIdx.x; i < bytes / 16; i += THREADS)
-    reinterpret_cast<u32x4*>(dst)[i] = reinterpret_cast<const u32x4*>(src)[i];
-}
+// A block-wide copy of BYTES (a multiple of 16) from global memory to LDS in two halves: request()
+// puts the loads in flight, commit() writes what arrived to LDS.  Kernels request everything their
+// start-up needs from memory in one go and only then consume it, so that the start-up costs one
+// round trip to memory instead of one per item.
+template <int BYTES, int THREADS>
+struct ImageCopy {
+  static constexpr int N16 = BYTES / 16, N = (N16 + THREADS - 1) / THREADS;
+  u32x4 v[N];
+  __device__ __forceinline__ void request(const unsigned char* src) {
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+      const int i = threadIdx.x + k * THREADS;
+      if (N16 % THREADS == 0 || i < N16) v[k] = reinterpret_cast<const u32x4*>(src)[i];
+    }
+  }
+  __device__ __forceinline__ void commit(unsigned char* dst) const {
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+      const int i = threadIdx.x + k * THREADS;
+      if (N16 % THREADS == 0 || i < N16) reinterpret_cast<u32x4*>(dst)[i] = v[k];
+    }
+  }
+};
 
 // Waves per workgroup of k_query_causal: eight (two per SIMD, 256 registers each) where the live
 // set allows it, one query tile per wave; else four with two tiles each.
@@ -747,7 +766,7 @@ struct CausalSmem {
   static constexpr int kBase = kVBytes + kSBytes + kWavesQ * RowTile<D, kOutRows>::kBytes;
   // the operand image of the state in front of the chunk, read by every wave: an LDS copy where
   // it fits, each wave's own loads from memory otherwise
-  static constexpr int kImgBytes = SY::MP * D * 2;
+  static constexpr int kImgBytes = SY::MP * D * 2 + 2 * SY::SP * 4;  // with the normaliser by slot behind it
   static constexpr bool kImgLds = kBase + kImgBytes <= 160 * 1024;
   static constexpr int kTotal = kBase + (kImgLds ? kImgBytes : 0);
 };
@@ -780,29 +799,44 @@ __global__ __launch_bounds__(causal_query_waves<SY>() * 64) void k_query_causal(
   const BlockEnt e = chunks[blockIdx.x];
   const int h = blockIdx.y;
   const unsigned char* pu = pfx + (static_cast<int64_t>(blockIdx.x) * g.H + h) * PL::kBytes;
-  if constexpr (SM::kImgLds) stage_image<WAVES * 64>(smem + SM::kBase, pu, SM::kImgBytes);
-  // ---- the chunk's V rows and key-monomial images, an equal share per wave
-  {
-    TileRegs<D, kRowsPW> vt;
-    fetch_tile<D, kRowsPW>(V, e.b, h, e.t0 + kRowsPW * wave, e.t1, lane, vt);
-    put_tile<D, kRowsPW>(vt, lane, vs + kRowsPW * wave * SM::kVStride, SM::kVStride);
+  static_assert(SM::kImgBytes == PL::kBytes, "the staged image is the prefix record of the chunk");
+  // a query tile's features (tokens beyond the chunk read its last token and are zeroed when used)
+  auto request_query = [&](int qt, f32x2 (&qraw)[DP / 2]) {
+    const int n = e.t0 + 32 * qt + r;
+    const f32x2* f = reinterpret_cast<const f32x2*>(feat + g.fidx(g.th(e.b, h, n < e.t1 ? n : e.t1 - 1), 0));
+#pragma unroll
+    for (int p = 0; p < DP / 2; ++p) qraw[p] = f[32 * (gl ? DP / 2 - 1 - p : p)];  // lane half 1: pairs in reverse
+  };
+  const int qt_first = WAVES == 8 ? (wave < 4 ? wave : 11 - wave) : chunk_tile_of(wave, 0);
+  // ---- everything the start needs from memory, requested at once: the image of the state in front
+  // of the chunk with its normaliser, the chunk's V rows and the key features of the tiles this wave
+  // stages (an equal share per wave), the features of its first query tile
+  ImageCopy<SM::kImgLds ? SM::kImgBytes : 16, WAVES * 64> image;
+  if constexpr (SM::kImgLds) image.request(pu);
+  TileRegs<D, kRowsPW> vt;
+  fetch_tile<D, kRowsPW>(V, e.b, h, e.t0 + kRowsPW * wave, e.t1, lane, vt);
+  f32x2 kraw[kTilesPW][NF / 2];
+#pragma unroll
+  for (int tt = 0; tt < kTilesPW; ++tt) {
+    const int n = e.t0 + 32 * (kTilesPW * wave + tt) + r;
+    const f32x2* f = reinterpret_cast<const f32x2*>(feat + g.fidx(g.th(e.b, h, n < e.t1 ? n : e.t1 - 1), DP));
+#pragma unroll
+    for (int p = 0; p < NF / 2; ++p) kraw[tt][p] = f[32 * p];
   }
-#pragma unroll 1
+  f32x2 qraw0[DP / 2];
+  request_query(qt_first, qraw0);
+  // ---- the staged tiles: V rows and key-monomial images
+  if constexpr (SM::kImgLds) image.commit(smem + SM::kBase);
+  put_tile<D, kRowsPW>(vt, lane, vs + kRowsPW * wave * SM::kVStride, SM::kVStride);
+#pragma unroll
   for (int tt = 0; tt < kTilesPW; ++tt) {
     const int t = kTilesPW * wave + tt;
-    const int n = e.t0 + 32 * t + r;
+    const bool live_k = e.t0 + 32 * t + r < e.t1;
     float kf[NF], kr[NF];
-    if (n < e.t1) {
-      const f32x2* f = reinterpret_cast<const f32x2*>(feat + g.fidx(g.th(e.b, h, n), DP));
 #pragma unroll
-      for (int p = 0; p < NF / 2; ++p) {
-        const f32x2 v = f[32 * p];
-        kf[2 * p] = v[0];
-        kf[2 * p + 1] = v[1];
-      }
-    } else {
-#pragma unroll
-      for (int a = 0; a < NF; ++a) kf[a] = 0.0f;
+    for (int p = 0; p < NF / 2; ++p) {
+      kf[2 * p] = live_k ? kraw[tt][p][0] : 0.0f;
+      kf[2 * p + 1] = live_k ? kraw[tt][p][1] : 0.0f;
     }
     float kk[F][DP];
 #pragma unroll
@@ -829,7 +863,7 @@ __global__ __launch_bounds__(causal_query_waves<SY>() * 64) void k_query_causal(
   for (int i = 0; i < 16; ++i)
     rowfac[i] = log2_decay != 0.0f ? __builtin_amdgcn_exp2f(log2_decay * static_cast<float>(31 - d_row(i, gl))) : 1.0f;
   const u32x4* opA = reinterpret_cast<const u32x4*>(SM::kImgLds ? smem + SM::kBase : pu);
-  const float* zslot = reinterpret_cast<const float*>(pu + PL::kOpElems * 2) + gl * SP;
+  const float* zslot = reinterpret_cast<const float*>((SM::kImgLds ? smem + SM::kBase : pu) + PL::kOpElems * 2) + gl * SP;
 #pragma unroll 1
   for (int qi = 0; qi < kTilesPW; ++qi) {
     const int qt = WAVES == 8 ? (wave < 4 ? wave : 11 - wave) : chunk_tile_of(wave, qi);
@@ -839,12 +873,17 @@ __global__ __launch_bounds__(causal_query_waves<SY>() * 64) void k_query_causal(
     const bool live = n < e.t1;
     float qf[DP];
     {
-      const f32x2* f = reinterpret_cast<const f32x2*>(feat + g.fidx(g.th(e.b, h, live ? n : e.t1 - 1), 0));
+      f32x2 qraw[DP / 2];
+      if (qi == 0) {
 #pragma unroll
-      for (int p = 0; p < DP / 2; ++p) {  // lane half 1 takes the pairs, and each pair, in reverse
-        const f32x2 v = f[32 * (gl ? DP / 2 - 1 - p : p)];
-        qf[2 * p] = live ? (gl ? v[1] : v[0]) : 0.0f;
-        qf[2 * p + 1] = live ? (gl ? v[0] : v[1]) : 0.0f;
+        for (int p = 0; p < DP / 2; ++p) qraw[p] = qraw0[p];
+      } else {
+        request_query(qt, qraw);
+      }
+#pragma unroll
+      for (int p = 0; p < DP / 2; ++p) {  // and each pair in reverse
+        qf[2 * p] = live ? (gl ? qraw[p][1] : qraw[p][0]) : 0.0f;
+        qf[2 * p + 1] = live ? (gl ? qraw[p][0] : qraw[p][1]) : 0.0f;
       }
     }
     float qm[SP];
@@ -1635,29 +1674,52 @@ __global__ __launch_bounds__(causal_query_waves<SY>() * 64) void k_cgrad_q(Geom 
   const int h = blockIdx.y;
   const int64_t ch_h = static_cast<int64_t>(blockIdx.x) * g.H + h;
   // the monomial-row image of the state in front of the chunk: an LDS copy where it fits
-  if constexpr (SM::kImgLdsQ) stage_image<WAVES * 64>(smem + SM::kBaseQ, rows_img + ch_h * rows_stride, SM::kImgBytes);
-  // ---- the chunk's V rows and key monomials, an equal share per wave
-  {
-    TileRegs<D, kRowsPW> vt;
-    fetch_tile<D, kRowsPW>(V, e.b, h, e.t0 + kRowsPW * wave, e.t1, lane, vt);
-    put_tile<D, kRowsPW>(vt, lane, rt + kRowsPW * wave * SM::kRStride, SM::kRStride);
+  // a query tile's inputs: its dO row in operand order, its features and den (tokens beyond the
+  // chunk read its last token and are zeroed when used)
+  auto request_query = [&](int qt, u32x4 (&bdo)[NKD], f32x2 (&fraw)[DP / 2], float& dn) {
+    const int n = e.t0 + 32 * qt + r;
+    const int nc = n < e.t1 ? n : e.t1 - 1;
+    const bf16_t* row = dO.row<const bf16_t>(e.b, h, nc);
+#pragma unroll
+    for (int kd = 0; kd < NKD; ++kd) bdo[kd] = *reinterpret_cast<const u32x4*>(row + 16 * kd + 8 * gl);
+    const int64_t th = g.th(e.b, h, nc);
+    const f32x2* f = reinterpret_cast<const f32x2*>(feat + g.fidx(th, 0));
+#pragma unroll
+    for (int p = 0; p < DP / 2; ++p) fraw[p] = f[32 * p];
+    dn = den[th];
+  };
+  const int qt_first = WAVES == 8 ? (wave < 4 ? wave : 11 - wave) : chunk_tile_of(wave, 0);
+  // ---- everything the start needs from memory, requested at once: the monomial-row image of the
+  // state in front of the chunk (an LDS copy where it fits), the chunk's V rows and the key features
+  // of the tiles this wave stages (an equal share per wave), the inputs of its first query tile
+  ImageCopy<SM::kImgLdsQ ? SM::kImgBytes : 16, WAVES * 64> image;
+  if constexpr (SM::kImgLdsQ) image.request(rows_img + ch_h * rows_stride);
+  TileRegs<D, kRowsPW> vt;
+  fetch_tile<D, kRowsPW>(V, e.b, h, e.t0 + kRowsPW * wave, e.t1, lane, vt);
+  f32x2 kraw[kTilesPW][NF / 2];
+#pragma unroll
+  for (int tt = 0; tt < kTilesPW; ++tt) {
+    const int n = e.t0 + 32 * (kTilesPW * wave + tt) + r;
+    const f32x2* f = reinterpret_cast<const f32x2*>(feat + g.fidx(g.th(e.b, h, n < e.t1 ? n : e.t1 - 1), DP));
+#pragma unroll
+    for (int p = 0; p < NF / 2; ++p) kraw[tt][p] = f[32 * p];
   }
-#pragma unroll 1
+  u32x4 bdo0[NKD];
+  f32x2 fraw0[DP / 2];
+  float dn0;
+  request_query(qt_first, bdo0, fraw0, dn0);
+  // ---- the staged tiles: V rows and key monomials
+  if constexpr (SM::kImgLdsQ) image.commit(smem + SM::kBaseQ);
+  put_tile<D, kRowsPW>(vt, lane, rt + kRowsPW * wave * SM::kRStride, SM::kRStride);
+#pragma unroll
   for (int tt = 0; tt < kTilesPW; ++tt) {
     const int t = kTilesPW * wave + tt;
-    const int n = e.t0 + 32 * t + r;
+    const bool live_k = e.t0 + 32 * t + r < e.t1;
     float kf[NF], kr[NF];
-    if (n < e.t1) {
-      const f32x2* f = reinterpret_cast<const f32x2*>(feat + g.fidx(g.th(e.b, h, n), DP));
 #pragma unroll
-      for (int p = 0; p < NF / 2; ++p) {
-        const f32x2 v = f[32 * p];
-        kf[2 * p] = v[0];
-        kf[2 * p + 1] = v[1];
-      }
-    } else {
-#pragma unroll
-      for (int a = 0; a < NF; ++a) kf[a] = 0.0f;
+    for (int p = 0; p < NF / 2; ++p) {
+      kf[2 * p] = live_k ? kraw[tt][p][0] : 0.0f;
+      kf[2 * p + 1] = live_k ? kraw[tt][p][1] : 0.0f;
     }
     float kk[F][DP];
 #pragma unroll
@@ -1690,22 +1752,27 @@ __global__ __launch_bounds__(causal_query_waves<SY>() * 64) void k_cgrad_q(Geom 
     const bool live = n < e.t1;
     const int64_t th = g.th(e.b, h, live ? n : e.t1 - 1);
     u32x4 bdo[NKD];
-    {
-      const bf16_t* row = dO.row<const bf16_t>(e.b, h, live ? n : e.t1 - 1);
+    f32x2 fraw[DP / 2];
+    float dn;
+    if (qi == 0) {  // requested before the staging
 #pragma unroll
-      for (int kd = 0; kd < NKD; ++kd) {
-        bdo[kd] = *reinterpret_cast<const u32x4*>(row + 16 * kd + 8 * gl);
-        if (!live) bdo[kd][0] = bdo[kd][1] = bdo[kd][2] = bdo[kd][3] = 0u;
-      }
+      for (int kd = 0; kd < NKD; ++kd) bdo[kd] = bdo0[kd];
+#pragma unroll
+      for (int p = 0; p < DP / 2; ++p) fraw[p] = fraw0[p];
+      dn = dn0;
+    } else {
+      request_query(qt, bdo, fraw, dn);
+    }
+    if (!live) {
+#pragma unroll
+      for (int kd = 0; kd < NKD; ++kd) bdo[kd][0] = bdo[kd][1] = bdo[kd][2] = bdo[kd][3] = 0u;
     }
     float fb[DP], qf[DP];
     {
-      const f32x2* f = reinterpret_cast<const f32x2*>(feat + g.fidx(th, 0));
 #pragma unroll
       for (int p = 0; p < DP / 2; ++p) {
-        const f32x2 v = f[32 * p];
-        fb[2 * p] = live ? v[0] : 0.0f;
-        fb[2 * p + 1] = live ? v[1] : 0.0f;
+        fb[2 * p] = live ? fraw[p][0] : 0.0f;
+        fb[2 * p + 1] = live ? fraw[p][1] : 0.0f;
       }
       float fr[DP];
 #pragma unroll
@@ -1713,7 +1780,7 @@ __global__ __launch_bounds__(causal_query_waves<SY>() * 64) void k_cgrad_q(Geom 
 #pragma unroll
       for (int c = 0; c < DP; ++c) qf[c] = gl ? fr[c] : fb[c];
     }
-    const float inv = live ? 1.0f / den[th] : 0.0f;
+    const float inv = live ? 1.0f / dn : 0.0f;
     float qm[SP];
     sym_query_monomials<SY>(qf, qm, gl);
     // the chunks in front: X = (state) dO^T, Z = its normaliser, both as seen from the chunk's
@@ -1865,36 +1932,56 @@ __global__ __launch_bounds__(kWavesCK * 64) void k_cgrad_k(
   const BlockEnt e = chunks[blockIdx.x];
   const int h = blockIdx.y;
   const unsigned char* pu = dops + (static_cast<int64_t>(blockIdx.x) * g.H + h) * SL::kOpBytes;
-  // the two images of the gradient state behind the chunk (channel rows for dv, monomial rows for dS)
-  if constexpr (SM::kImgLdsK) stage_image<kWavesCK * 64>(smem + SM::kBaseK, pu, 2 * SM::kImgBytes);
   const u32x4* opA = reinterpret_cast<const u32x4*>(SM::kImgLdsK ? smem + SM::kBaseK : pu);
   const u32x4* opB = reinterpret_cast<const u32x4*>(SM::kImgLdsK ? smem + SM::kBaseK + SM::kImgBytes : pu + SL::kOpElems * 2);
-  // ---- the chunk's dO rows, scaled query monomials Qm / den and t = s den: 32 tokens per wave
-  {
-    TileRegs<D, kRowsPW> vt;
-    fetch_tile<D, kRowsPW>(dO, e.b, h, e.t0 + kRowsPW * wave, e.t1, lane, vt);
-    put_tile<D, kRowsPW>(vt, lane, rt + kRowsPW * wave * SM::kRStride, SM::kRStride);
-  }
-  {
-    const int t = wave;
-    const int n = e.t0 + 32 * t + r;
-    const bool live = n < e.t1;
-    const int64_t th = g.th(e.b, h, live ? n : e.t1 - 1);
-    float qf[DP];
-    {
-      const f32x2* f = reinterpret_cast<const f32x2*>(feat + g.fidx(th, 0));
+  // a key tile's inputs: its key features and, for the dS role, its V row in operand order
+  // (tokens beyond the chunk read the chunk's last token and are zeroed when used)
+  auto request_key = [&](int kt, f32x2 (&kraw)[NF / 2], u32x4 (&bv)[NKD]) {
+    const int n = e.t0 + 32 * kt + r;
+    const int nc = n < e.t1 ? n : e.t1 - 1;
+    const f32x2* f = reinterpret_cast<const f32x2*>(feat + g.fidx(g.th(e.b, h, nc), DP));
 #pragma unroll
-      for (int p = 0; p < DP / 2; ++p) {  // lane half 1 takes the pairs, and each pair, in reverse
-        const f32x2 v = f[32 * (gl ? DP / 2 - 1 - p : p)];
-        qf[2 * p] = live ? (gl ? v[1] : v[0]) : 0.0f;
-        qf[2 * p + 1] = live ? (gl ? v[0] : v[1]) : 0.0f;
-      }
+    for (int p = 0; p < NF / 2; ++p) kraw[p] = f[32 * p];
+    if (wave < 4) {
+      const bf16_t* row = V.row<const bf16_t>(e.b, h, nc);
+#pragma unroll
+      for (int kd = 0; kd < NKD; ++kd) bv[kd] = *reinterpret_cast<const u32x4*>(row + 16 * kd + 8 * gl);
     }
-    const float dn = live ? den[th] : 1.0f;
+  };
+  // ---- everything the start needs from memory, requested at once: the two images of the gradient
+  // state behind the chunk (channel rows for dv, monomial rows for dS), the chunk's dO rows, the
+  // query features, den and s of the 32 tokens this wave stages, the first key tile's inputs
+  ImageCopy<SM::kImgLdsK ? 2 * SM::kImgBytes : 16, kWavesCK * 64> images;
+  if constexpr (SM::kImgLdsK) images.request(pu);
+  TileRegs<D, kRowsPW> vt;
+  fetch_tile<D, kRowsPW>(dO, e.b, h, e.t0 + kRowsPW * wave, e.t1, lane, vt);
+  const int ns = e.t0 + 32 * wave + r;  // the token whose monomials this lane stages
+  const bool live_s = ns < e.t1;
+  const int64_t th_s = g.th(e.b, h, live_s ? ns : e.t1 - 1);
+  f32x2 qraw[DP / 2];
+  {
+    const f32x2* f = reinterpret_cast<const f32x2*>(feat + g.fidx(th_s, 0));
+#pragma unroll
+    for (int p = 0; p < DP / 2; ++p) qraw[p] = f[32 * (gl ? DP / 2 - 1 - p : p)];  // lane half 1: pairs in reverse
+  }
+  const float dn_s = den[th_s], sv_s = sv[th_s];
+  f32x2 kraw0[NF / 2];
+  u32x4 bv0[NKD];
+  request_key(wt, kraw0, bv0);
+  // ---- the staged tiles: dO rows, scaled query monomials Qm / den and t = s den
+  if constexpr (SM::kImgLdsK) images.commit(smem + SM::kBaseK);
+  put_tile<D, kRowsPW>(vt, lane, rt + kRowsPW * wave * SM::kRStride, SM::kRStride);
+  {
+    float qf[DP];
+#pragma unroll
+    for (int p = 0; p < DP / 2; ++p) {  // and each pair in reverse
+      qf[2 * p] = live_s ? (gl ? qraw[p][1] : qraw[p][0]) : 0.0f;
+      qf[2 * p + 1] = live_s ? (gl ? qraw[p][0] : qraw[p][1]) : 0.0f;
+    }
     float qm[SP];
     sym_query_monomials<SY>(qf, qm, gl);
-    put_monomials<SY>(mt, SM::kMStride, 32 * t + r, gl, qm, live ? 1.0f / dn : 0.0f);
-    if (gl == 0) tq[32 * t + r] = live ? sv[th] * dn : 0.0f;
+    put_monomials<SY>(mt, SM::kMStride, 32 * wave + r, gl, qm, live_s ? 1.0f / dn_s : 0.0f);
+    if (gl == 0) tq[32 * wave + r] = live_s ? sv_s * dn_s : 0.0f;
   }
   __syncthreads();
   float rowfac[16];
@@ -1902,24 +1989,32 @@ __global__ __launch_bounds__(kWavesCK * 64) void k_cgrad_k(
   for (int i = 0; i < 16; ++i)
     rowfac[i] = log2_decay != 0.0f ? __builtin_amdgcn_exp2f(log2_decay * static_cast<float>(d_row(i, gl))) : 1.0f;
   const int last = (e.t1 - e.t0 + 31) / 32 - 1;  // the chunk's last query tile
-#pragma unroll 1
-  for (int ki = 0; ki < 2; ++ki) {
-    const int kt = ki == 0 ? wt : kCausalChunk / 32 - 1 - wt;
+  // one key tile; FIRST: the wave's first, whose inputs were requested before the staging
+  auto key_tile = [&](int kt, auto first_tag) {
+    constexpr bool FIRST = decltype(first_tag)::value;
     const int n0 = e.t0 + 32 * kt;
-    if (n0 >= e.t1) continue;
+    if (n0 >= e.t1) return;
     const int n = n0 + r;
     const bool live = n < e.t1;
     const int64_t th = g.th(e.b, h, live ? n : e.t1 - 1);
+    f32x2 kraw[NF / 2];
+    u32x4 bv[NKD];
+    if constexpr (FIRST) {
+#pragma unroll
+      for (int p = 0; p < NF / 2; ++p) kraw[p] = kraw0[p];
+#pragma unroll
+      for (int kd = 0; kd < NKD; ++kd) bv[kd] = bv0[kd];
+    } else {
+      request_key(kt, kraw, bv);
+    }
     // the key's features: lane half 1 holds every map's reversed
     float kk[F][DP];
     {
-      const f32x2* f = reinterpret_cast<const f32x2*>(feat + g.fidx(th, DP));
       float kb[NF], kr[NF];
 #pragma unroll
       for (int p = 0; p < NF / 2; ++p) {
-        const f32x2 v = f[32 * p];
-        kb[2 * p] = live ? v[0] : 0.0f;
-        kb[2 * p + 1] = live ? v[1] : 0.0f;
+        kb[2 * p] = live ? kraw[p][0] : 0.0f;
+        kb[2 * p + 1] = live ? kraw[p][1] : 0.0f;
       }
 #pragma unroll
       for (int f2 = 0; f2 < F; ++f2)
@@ -1937,14 +2032,9 @@ __global__ __launch_bounds__(kWavesCK * 64) void k_cgrad_k(
     if (wave < 4) {
       // ---- dS^T = (gradient state) v + dz  +  sum over the chunk's queries, then the chain rule
       const float* dzslot = reinterpret_cast<const float*>(pu + 2 * SL::kOpElems * 2) + gl * SP;
-      u32x4 bv[NKD];
-      {
-        const bf16_t* row = V.row<const bf16_t>(e.b, h, live ? n : e.t1 - 1);
+      if (!live) {
 #pragma unroll
-        for (int kd = 0; kd < NKD; ++kd) {
-          bv[kd] = *reinterpret_cast<const u32x4*>(row + 16 * kd + 8 * gl);
-          if (!live) bv[kd][0] = bv[kd][1] = bv[kd][2] = bv[kd][3] = 0u;
-        }
+        for (int kd = 0; kd < NKD; ++kd) bv[kd][0] = bv[kd][1] = bv[kd][2] = bv[kd][3] = 0u;
       }
       f32x16 Y[NRM];
 #pragma unroll
@@ -2083,7 +2173,9 @@ __global__ __launch_bounds__(kWavesCK * 64) void k_cgrad_k(
         return n0 + t < e.t1 ? dV.row<bf16_t>(e.b, h, n0 + t) : nullptr;
       });
     }
-  }
+  };
+  key_tile(wt, std::true_type{});
+  key_tile(kCausalChunk / 32 - 1 - wt, std::false_type{});
 }
 
 template <class SY, int D>
