@@ -24,18 +24,15 @@ constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
 constexpr int kQueryTarget = 496;  // workgroups aimed at by the query kernel: two per CU, one resident round
 constexpr int kMinChunk = 256;     // smallest chunk pick_chunk returns
-constexpr int kCausalChunk = 256;  // tokens per chunk of the causal scan
-// The chunk kernels give every wave kChunkTilesPerWave 32-token tiles of its own side.  (128-token
-// chunks, one tile per wave and two workgroups per compute unit, were measured: the tile kernels
-// gain 20-25 % -- a token meets 2.5 tiles of its chunk instead of 4.5 -- but the scans, serial in
-// the number of chunks, lose twice that.)
-constexpr int kChunkRowsPerWave = kCausalChunk / 4;
-constexpr int kChunkTilesPerWave = kCausalChunk / 32 / 4;
-static_assert(kChunkRowsPerWave == 32 || kChunkRowsPerWave == 64, "row staging covers 32 or 64 rows per wave");
-// tile `i` of wave `w`: with two tiles per wave, w and its mirror image (equal shares of the triangle)
-__device__ __forceinline__ int chunk_tile_of(int w, int i) {
-  return kChunkTilesPerWave == 1 ? w : (i == 0 ? w : kCausalChunk / 32 - 1 - w);
-}
+constexpr int kCausalChunk = 256;  // tokens per chunk of the causal scan: eight 32-token tiles
+// (128-token chunks, one tile per wave of a four-wave workgroup and two workgroups per compute
+// unit, were measured: the tile kernels gain 20-25 % -- a token meets 2.5 tiles of its chunk instead
+// of 4.5 -- but the scans, serial in the number of chunks, lose twice that.)
+static_assert(kCausalChunk == 256, "the tile kernels' wave-to-tile maps assume eight tiles per chunk");
+// Tile `i` (0 or 1) of wave `w` of a four-wave workgroup: w and its mirror image 7 - w, equal
+// shares of the triangle of tile pairs.  Eight-wave workgroups give the same two tiles to the two
+// waves of a SIMD, w and w + 4.
+__device__ __forceinline__ int chunk_tile_of(int w, int i) { return i == 0 ? w : kCausalChunk / 32 - 1 - w; }
 constexpr int kMinQueryBlock = 128;  // smallest block pick_query_block returns
 constexpr int kChunkTarget = 256;  // workgroups aimed at by the chunked (token-contraction) kernels: one per CU
 constexpr int kChunkGrain = 64;    // chunk sizes are multiples of this many tokens (one wave step of k_state)
@@ -751,7 +748,7 @@ struct ImageCopy {
 // set allows it, one query tile per wave; else four with two tiles each.
 template <class SY>
 constexpr int causal_query_waves() {
-  return SY::MP <= 64 && kCausalChunk == 256 ? 8 : 4;
+  return SY::MP <= 64 ? 8 : 4;
 }
 
 template <class SY, int D>
@@ -762,7 +759,7 @@ struct CausalSmem {
   static constexpr int kVStride = D * 2 + 32;                  // bytes per token row of the V tile
   static constexpr int kVBytes = kCausalChunk * kVStride;
   static constexpr int kSBytes = kTiles * NKS * 64 * 16;       // key-monomial operand images of the chunk
-  static constexpr int kOutRows = kCausalChunk >= 256 && kWavesQ == 4 ? 32 : 16;  // rows of a wave's store tile
+  static constexpr int kOutRows = kWavesQ == 4 ? 32 : 16;  // rows of a wave's store tile
   static constexpr int kBase = kVBytes + kSBytes + kWavesQ * RowTile<D, kOutRows>::kBytes;
   // the operand image of the state in front of the chunk, read by every wave: an LDS copy where
   // it fits, each wave's own loads from memory otherwise
