@@ -316,7 +316,7 @@ hla_status hla_create(const hla_config* c, hla_handle** out) {
   // padding entries of packed operands are never written afterwards and must read as zero
   if (st == HLA_OK && hd->path_ws_bytes > 0 && hipMemset(hd->path_ws, 0, hd->path_ws_bytes) != hipSuccess)
     st = HLA_ERR_HIP;
-  if (st == HLA_OK && hd->path == HLA_PATH_MFMA) st = mfma_prepare_kernels(hd);
+  if (st == HLA_OK) st = hd->path == HLA_PATH_MFMA ? mfma_prepare_kernels(hd) : generic_prepare_kernels(hd);
   if (st == HLA_OK && hipDeviceSynchronize() != hipSuccess) st = HLA_ERR_HIP;
   if (st != HLA_OK) {
     free_all(hd);

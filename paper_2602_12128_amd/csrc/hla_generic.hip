@@ -862,13 +862,23 @@ hla_status causal_scan_launch(hla_handle* hd, const hla_call_args& a, const char
   HLA_TRY(get_table(hd, 0, kChunk, a.stream, &chunks));
   const size_t sh = causal_scan_floats<TT>(g.D, g.d, g.nfeat) * sizeof(float);
   auto kernel = &k_causal_scan<T, MODE, TT>;
-  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                          static_cast<int>(sh)) != hipSuccess)
-    return HLA_ERR_HIP;
   const float dec = hd->cfg.decay > 0.0f && hd->cfg.decay < 1.0f ? hd->cfg.decay : 1.0f;
   return launch(hd, name, kernel, dim3(a.num_seqs, g.H), dim3(kThreads), sh, a.stream, g, chunks->dev,
                 chunks->seq_off_dev, static_cast<const float*>(hd->feat), a.V,
                 static_cast<const float*>(hd->yhat), dec, out, hd->den, hd->dfeat);
+}
+
+// The scan's LDS exceeds the 64 KB a kernel gets without asking: the three modes of a handle's
+// dtype and tile are given their size once, when the handle is planned.
+template <typename T, int TT>
+hla_status causal_scan_allow_lds(const Geom& g) {
+  const int sh = static_cast<int>(causal_scan_floats<TT>(g.D, g.d, g.nfeat) * sizeof(float));
+  const void* kernels[3] = {reinterpret_cast<const void*>(&k_causal_scan<T, 0, TT>),
+                            reinterpret_cast<const void*>(&k_causal_scan<T, 1, TT>),
+                            reinterpret_cast<const void*>(&k_causal_scan<T, 2, TT>)};
+  for (const void* k : kernels)
+    if (hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, sh) != hipSuccess) return HLA_ERR_HIP;
+  return HLA_OK;
 }
 
 template <typename T, int MODE>
@@ -967,6 +977,18 @@ hla_status generic_workspace_plan(hla_handle* hd) {
   if (sh_c > 64 * 1024) return HLA_ERR_UNSUPPORTED;
   if (hd->cfg.causal && causal_scan_tile(g) == 0) return HLA_ERR_UNSUPPORTED;  // the scan's state does not fit LDS
   return HLA_OK;
+}
+
+// Kernel attributes a handle on this path needs (once per handle, at creation).
+hla_status generic_prepare_kernels(const hla_handle* hd) {
+  if (!hd->cfg.causal) return HLA_OK;
+  const Geom& g = hd->g;
+  const bool f32 = hd->cfg.io_dtype == HLA_F32;
+  switch (causal_scan_tile(g)) {
+    case 8: return f32 ? causal_scan_allow_lds<float, 8>(g) : causal_scan_allow_lds<bf16_t, 8>(g);
+    case 4: return f32 ? causal_scan_allow_lds<float, 4>(g) : causal_scan_allow_lds<bf16_t, 4>(g);
+    default: return HLA_ERR_UNSUPPORTED;
+  }
 }
 
 hla_status convert_weights_to_f32(hla_handle* hd, const hla_phi_weights* maps, hipStream_t s) {

@@ -129,6 +129,7 @@ hla_status mfma_workspace_plan(hla_handle* hd);
 // Launch attributes (LDS sizes above the default limit) of the kernels this handle will launch,
 // on the current device.
 hla_status mfma_prepare_kernels(const hla_handle* hd);
+hla_status generic_prepare_kernels(const hla_handle* hd);
 hla_status mfma_phi_prepare_kernels(const hla_handle* hd);
 hla_status mfma_set_weights(hla_handle* hd, hipStream_t s);
 hla_status mfma_forward(hla_handle* hd, const hla_call_args& a);
