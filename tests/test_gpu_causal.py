@@ -390,3 +390,41 @@ def test_causal_fp32_kernels_against_the_matrix_core_kernels_bf16():
     for name, got in (("fp32 kernels", a), ("matrix cores", b)):
         pu.assert_parity(got, ref, 2e-2, f"causal bf16 I/O, {name}", kinks=kinks,
                          row_scale=pu.causal_first_token_rows(t, ref))
+
+
+def test_causal_packed_video_sizes_one_head_of_two_sequences():
+    """The packed configuration (four sequences of 8190 to 32760 tokens in one row) on a causal
+    handle with decay, as `bench.py --config 5 --causal` runs it: every sequence starts its own
+    scan.  One head of the first two sequences is compared in full (forward and backward) with the
+    oracle's state recursions run on each sequence alone; sampled rows of the last sequence with
+    the masked definition."""
+    w = wl.make_workload(5)
+    cu, lam, hh = w.cu_seqlens, 0.9995, 7
+    gpu = _causal_gpu_backward(w.tensors, w.F, w.d_phi, phi=w.phi, cu=cu, decay=lam)
+    for k in ("O", "dQ", "dK", "dV"):
+        assert torch.isfinite(gpu[k].float()).all(), k
+    ophi = pu.oracle_phi(w.phi)
+    for sq in (0, 1):
+        lo, hi = cu[sq], cu[sq + 1]
+        sub = {k: v[:, hh:hh + 1, lo:hi].contiguous() for k, v in w.tensors.items()}
+        Q, K, V, dO = (pu.to_np(sub[k]) for k in ("Q", "K", "V", "dO"))
+        ref = {"O": orc.hla_operator_forward(Q, K, V, w.F, w.d_phi, w.eps, phi=ophi, causal=True, decay=lam)}
+        res = orc.hla_operator_backward(Q, K, V, dO, w.F, w.d_phi, w.eps, phi=ophi, causal=True, decay=lam,
+                                        feature_grads=True)
+        ref.update(dQ=res[0], dK=res[1], dV=res[2])
+        ref["_dqf"], ref["_dkf"] = res[-1]
+        got = {k: gpu[k][:, hh:hh + 1, lo:hi] for k in ("O", "dQ", "dK", "dV")}
+        pu.assert_parity(got, ref, 2e-2, f"causal packed config, sequence {sq} head {hh}",
+                         kinks=pu.oracle_kinks(sub, w.phi, w.F, w.d_phi, ref),
+                         row_scale=pu.causal_first_token_rows(sub, ref))
+    lo, hi = cu[3], cu[4]
+    rng = np.random.default_rng(8)
+    rows = np.sort(np.concatenate([[0, 1, 255, 256, hi - lo - 1], rng.choice(hi - lo, 27, replace=False)]))
+    K = pu.to_np(w.tensors["K"][0, hh, lo:hi])
+    kfs = [orc.phi_forward(K, *ophi[1 + f].astuple())[0] for f in range(w.F)]
+    qf = orc.phi_forward(pu.to_np(w.tensors["Q"][0, hh, lo:hi]), *ophi[0].astuple())[0]
+    ref = orc.hla_causal_bruteforce(qf, kfs, pu.to_np(w.tensors["V"][0, hh, lo:hi]), w.eps, rows=rows, decay=lam)
+    g = pu.to_np(gpu["O"][0, hh, lo:hi][rows])
+    err = float(np.abs(g - ref).max() / np.abs(ref).max())
+    print(f"[parity] causal packed config, sampled rows of the last sequence: {err:.2e} (tol 0.02)", flush=True)
+    assert err <= 2e-2
