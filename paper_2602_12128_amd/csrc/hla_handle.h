@@ -52,6 +52,8 @@ struct hla_handle {
   size_t w_packed_off = 0;         // byte offset of the MFMA path's packed feature-map weights in path_ws
   size_t causal_off = 0;           // byte offset of the per-chunk prefix-state images (causal handles)
   bool causal_partials_valid = false;  // the partial buffer still holds the last causal forward's chunk states
+  bool causal_rows_valid = false;      // the monomial-row image of the running state belongs to the last forward
+  bool causal_seen_backward = false;   // a backward has run on this handle: forwards prepare that image too
   size_t causal_bwd_off = 0;       // byte offset of the per-chunk state / gradient-state images of the causal backward
 
   // feature-map weights, fp32 copies (both paths keep them; the MFMA path adds packed bf16)

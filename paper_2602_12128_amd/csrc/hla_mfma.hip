@@ -705,19 +705,21 @@ __global__ __launch_bounds__(kScanThreads) void k_prefix_rows(Geom g, const int3
                                    stride, img_off);
 }
 // both images in one launch: the first `za` workgroups in z carry the image by channels and the
-// normaliser, the rest the image by monomial rows
+// normaliser (into `pfx`), the rest the image by monomial rows (into `rows`, img_off bytes into a
+// chunk's block there)
 template <class SY, int D, bool REVERSE>
 __global__ __launch_bounds__(kScanThreads) void k_prefix_both(Geom g, const int32_t* __restrict__ seq_chunk_off,
                                                               const float* __restrict__ partial,
                                                               int64_t partial_stride, unsigned char* __restrict__ pfx,
                                                               CanonMap cm, float chunk_decay, int64_t stride,
-                                                              int64_t z_off, int64_t img_off, int za) {
+                                                              int64_t z_off, unsigned char* __restrict__ rows,
+                                                              int64_t rows_stride, int64_t img_off, int za) {
   if (static_cast<int>(blockIdx.z) < za)
     prefix_body<SY, D, REVERSE>(blockIdx.z, za, g, seq_chunk_off, partial, partial_stride, pfx, cm, chunk_decay,
                                 stride, z_off);
   else
-    prefix_rows_body<SY, D, REVERSE>(blockIdx.z - za, g, seq_chunk_off, partial, partial_stride, pfx, cm,
-                                     chunk_decay, stride, img_off);
+    prefix_rows_body<SY, D, REVERSE>(blockIdx.z - za, g, seq_chunk_off, partial, partial_stride, rows, cm,
+                                     chunk_decay, rows_stride, img_off);
 }
 
 // A block-wide copy of BYTES (a multiple of 16) from global memory to LDS in two halves: request()
@@ -2204,12 +2206,18 @@ hla_status backward_causal(hla_handle* hd, const hla_call_args& a) {
   // image by channels, normaliser) in its prefix images; what the query side needs on top is the
   // image by monomial rows.  A second backward after the same forward finds the partial buffer
   // holding gradient states and computes the chunk states again.
-  if (!hd->causal_partials_valid)
-    HLA_TRY(launch(hd, "mfma_state", k_state<SY, D, 0, true>, dim3((cch->count + kWaves - 1) / kWaves, g.H),
-                   dim3(kThreads), SM::kTotal, s, g, cch->dev, hd->feat, a.V, hd->partial, SL::kF32, l2d, nof, nof,
-                   cch->count));
-  HLA_TRY(launch(hd, "mfma_state_prefix_rows", k_prefix_rows<SY, D, false>, rgrid, dim3(kScanThreads), 0, s, g,
-                 cch->seq_off_dev, hd->partial, SL::kF32, ops, cm, chunk_decay, stride, b_off));
+  // A handle that has run a backward before has its forwards write that image too (one scan
+  // launch for both, see forward_causal), and it stays valid until the next forward.
+  if (!hd->causal_rows_valid) {
+    if (!hd->causal_partials_valid)
+      HLA_TRY(launch(hd, "mfma_state", k_state<SY, D, 0, true>, dim3((cch->count + kWaves - 1) / kWaves, g.H),
+                     dim3(kThreads), SM::kTotal, s, g, cch->dev, hd->feat, a.V, hd->partial, SL::kF32, l2d, nof, nof,
+                     cch->count));
+    HLA_TRY(launch(hd, "mfma_state_prefix_rows", k_prefix_rows<SY, D, false>, rgrid, dim3(kScanThreads), 0, s, g,
+                   cch->seq_off_dev, hd->partial, SL::kF32, ops, cm, chunk_decay, stride, b_off));
+    hd->causal_rows_valid = true;
+  }
+  hd->causal_seen_backward = true;
   HLA_TRY(launch(hd, "mfma_causal_grad_query", k_cgrad_q<SY, D>, dim3(cch->count, g.H), dim3(causal_query_waves<SY>() * 64),
                  SG::kTotalQ, s, g, cch->dev, hd->feat, hd->den, a.V, a.dO,
                  static_cast<const unsigned char*>(ops + b_off), stride,
@@ -2221,7 +2229,7 @@ hla_status backward_causal(hla_handle* hd, const hla_call_args& a) {
                  static_cast<const float*>(hd->den), static_cast<const float*>(hd->yhat), cch->count));
   HLA_TRY(launch(hd, "mfma_dstate_suffix", k_prefix_both<SY, D, true>, dim3(a.num_seqs, g.H, sgrid.z + rgrid.z),
                  dim3(kScanThreads), 0, s, g, cch->seq_off_dev, hd->partial, SL::kF32, dops, cm, chunk_decay, stride,
-                 z_off, b_off, static_cast<int>(sgrid.z)));
+                 z_off, dops, stride, b_off, static_cast<int>(sgrid.z)));
   HLA_TRY(launch(hd, "mfma_causal_grad_key", k_cgrad_k<SY, D>, dim3(cch->count, g.H), dim3(kWavesCK * 64),
                  SG::kTotalK, s, g, cch->dev, hd->feat, hd->den, static_cast<const float*>(hd->yhat), a.V, a.dO,
                  dops, hd->dfeat, a.dV, l2d, relu_mask));
@@ -2294,9 +2302,22 @@ hla_status forward_causal(hla_handle* hd, const hla_call_args& a) {
                  static_cast<const float*>(nullptr), static_cast<const float*>(nullptr), cch->count));
   static_assert(2 * (SY::MP / 16) * D % kScanThreads == 0, "whole workgroups of prefix items");
   using PL = PrefixLayout<SY, D>;
-  HLA_TRY(launch(hd, "mfma_state_prefix", k_prefix<SY, D, false>, dim3(a.num_seqs, g.H, 2 * (SY::MP / 16) * D / kScanThreads + 1),
-                 dim3(kScanThreads), 0, s, g, cch->seq_off_dev, hd->partial, SL::kF32, pfx, make_canon_map<SY>(), chunk_decay,
-                 static_cast<int64_t>(PL::kBytes), static_cast<int64_t>(PL::kOpElems * 2)));
+  const int za = 2 * (SY::MP / 16) * D / kScanThreads + 1;
+  if (hd->causal_seen_backward) {
+    // a handle in training use: the backward's image of the same running sum (rows = monomials)
+    // comes out of the same launch, which spares the backward a scan of its own
+    unsigned char* ops = static_cast<unsigned char*>(hd->path_ws) + hd->causal_bwd_off;
+    const int zr = (SY::MP / 32) * (D / 16) * 64 / kScanThreads;
+    HLA_TRY(launch(hd, "mfma_state_prefix", k_prefix_both<SY, D, false>, dim3(a.num_seqs, g.H, za + zr),
+                   dim3(kScanThreads), 0, s, g, cch->seq_off_dev, hd->partial, SL::kF32, pfx, make_canon_map<SY>(),
+                   chunk_decay, static_cast<int64_t>(PL::kBytes), static_cast<int64_t>(PL::kOpElems * 2), ops,
+                   static_cast<int64_t>(SL::kOpBytes), static_cast<int64_t>(SL::kOpElems * 2), za));
+  } else {
+    HLA_TRY(launch(hd, "mfma_state_prefix", k_prefix<SY, D, false>, dim3(a.num_seqs, g.H, za),
+                   dim3(kScanThreads), 0, s, g, cch->seq_off_dev, hd->partial, SL::kF32, pfx, make_canon_map<SY>(), chunk_decay,
+                   static_cast<int64_t>(PL::kBytes), static_cast<int64_t>(PL::kOpElems * 2)));
+  }
+  hd->causal_rows_valid = hd->causal_seen_backward;
   HLA_TRY(launch(hd, "mfma_query_causal", k_query_causal<SY, D>, dim3(cch->count, g.H), dim3(SC::kWavesQ * 64),
                  SC::kTotal, s, g, cch->dev, hd->feat, a.V, pfx, a.O, hd->den, l2d));
   hd->causal_partials_valid = true;  // the partial buffer holds this forward's chunk states

@@ -428,3 +428,44 @@ def test_causal_packed_video_sizes_one_head_of_two_sequences():
     err = float(np.abs(g - ref).max() / np.abs(ref).max())
     print(f"[parity] causal packed config, sampled rows of the last sequence: {err:.2e} (tol 0.02)", flush=True)
     assert err <= 2e-2
+
+
+def test_causal_steps_after_the_first_reuse_the_forward_scan_bit_identically():
+    """Once a handle has run a backward, its forwards write the backward's image of the running
+    state in the same scan launch: the second and third step on a handle give the bits a fresh
+    handle gives, also when the inputs change in between and when a forward is repeated without a
+    backward."""
+    dev = torch.device("cuda:0")
+    kw = dict(head_dim=128, feature_dim=6, degree=3, eps=1e-6, io_dtype=hla.HLA_BF16, phi_mode=hla.HLA_PHI_NONE,
+              max_heads=2, max_tokens=900, max_seqs=1, causal=True, decay=0.99)
+    ta = wl.make_feature_inputs(1460, 1, 2, 900, 128, 3, 6, torch.bfloat16)
+    tb = wl.make_feature_inputs(1461, 1, 2, 700, 128, 3, 6, torch.bfloat16, kind="lognormal")
+
+    def step(h, t):
+        td = {k: v.to(dev) for k, v in t.items()}
+        out = [torch.full_like(td["V"], float("nan"))] + [torch.full_like(td[k], float("nan")) for k in "QKV"]
+        h.forward(td["Q"], td["K"], td["V"], out[0])
+        h.backward(td["Q"], td["K"], td["V"], out[0], td["dO"], *out[1:])
+        torch.cuda.synchronize()
+        return [x.cpu() for x in out]
+
+    fresh = {}
+    for name, t in (("a", ta), ("b", tb)):
+        h = hla.HLA(**kw)
+        fresh[name] = step(h, t)
+        h.destroy()
+    h = hla.HLA(**kw)
+    first = step(h, ta)       # scan without the backward's image, the backward makes its own
+    second = step(h, ta)      # the forward's scan writes it
+    third = step(h, tb)       # other inputs, another length
+    td = {k: v.to(dev) for k, v in ta.items()}
+    O = torch.empty_like(td["V"])
+    h.forward(td["Q"], td["K"], td["V"], O)   # a forward that no backward follows
+    fourth = step(h, ta)
+    h.destroy()
+    for got, want in ((first, fresh["a"]), (second, fresh["a"]), (third, fresh["b"]), (fourth, fresh["a"])):
+        for x, y in zip(got, want):
+            assert torch.equal(x, y)
+    ref = _causal_oracle_backward(ta, 3, 6, decay=0.99)
+    pu.assert_parity(dict(zip(("O", "dQ", "dK", "dV"), second)), ref, 2e-2, "causal, second step on a handle",
+                     row_scale=pu.causal_first_token_rows(ta, ref))
