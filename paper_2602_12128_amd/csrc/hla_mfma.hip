@@ -542,8 +542,8 @@ CanonMap make_canon_map() {
   return cm;
 }
 
-// grid (num_seqs, H, 2 * NKS * D / kScanThreads + 1), block kScanThreads.  A thread owns the eight slots (g, 8 ks .. 8 ks + 7)
-// of one channel c: eight running sums, read from the eight partial rows of those monomials at
+// grid (num_seqs, H, kScanParts * 2 * NKS * D / kScanThreads + 1), block kScanThreads.  A piece is the eight slots (g, 8 ks .. 8 ks + 7)
+// of one channel c, shared by kScanParts threads (see there): eight running sums, read from the eight partial rows of those monomials at
 // column c (consecutive threads: consecutive floats), written for chunk ch -- before chunk ch's own
 // partial is added -- as the 16 bytes these eight slots occupy in the operand image (consecutive
 // threads of a 32-channel block: consecutive 16-byte pieces).  Padding slots are written as zeros.
@@ -554,6 +554,15 @@ CanonMap make_canon_map() {
 // the sum over the chunks behind it (the gradient states of the backward).  Images are written
 // `stride` bytes apart, the normaliser vector z_off bytes into an image.
 constexpr int kScanThreads = 64;  // one wave per workgroup: the scans are a few thousand threads in all, spread over as many compute units as possible
+// A scan is a chain of memory round trips, one per batch of chunks, and a wave can have only 63
+// loads outstanding: the eight values of a 16-byte piece of the image by channels (eight scalar
+// loads per chunk) are shared by two neighbouring threads, whose stores still fall side by side, so
+// that a batch of sixteen chunks is one round trip (measured: 41 / 40 us for the two scans against
+// 43 / 45; four threads per piece 58; the image by monomial rows, two 16-byte loads per chunk, is
+// best left with one thread per piece and sixteen chunks per batch: 50 and 46 us otherwise).
+constexpr int kScanParts = 2;      // image by channels: threads per piece (four slots each)
+constexpr int kScanPartsRows = 1;  // image by monomial rows: threads per piece
+constexpr int kScanBatchRows = 16; // its chunks in flight
 template <class SY, int D, bool REVERSE>
 __device__ __forceinline__ void prefix_body(int zidx, int zcount, const Geom& g,
                                             const int32_t* __restrict__ seq_chunk_off,
@@ -561,77 +570,94 @@ __device__ __forceinline__ void prefix_body(int zidx, int zcount, const Geom& g,
                                             unsigned char* __restrict__ pfx, const CanonMap& cm,
                                             float chunk_decay, int64_t stride, int64_t z_off) {
   constexpr int MP = SY::MP, SP = SY::SP, NKS = MP / 16;
+  constexpr int NV = 8 / kScanParts;  // slots per thread
   const int s = blockIdx.x, h = blockIdx.y;
   const int c0 = seq_chunk_off[s], c1 = seq_chunk_off[s + 1], nc = c1 - c0;
   auto chunk_at = [&](int pos) { return REVERSE ? c1 - 1 - pos : c0 + pos; };  // pos-th chunk in scan order
+  const int64_t cstride = static_cast<int64_t>(g.H) * partial_stride;
   // the last workgroup in z carries the normaliser vector (one thread per eight slots), the others
   // the operand image
   const bool zblock = zidx == zcount - 1;
-  if (zblock && threadIdx.x >= 2 * NKS) return;
-  const int item = zblock ? threadIdx.x * D : zidx * kScanThreads + threadIdx.x;  // (mg, ks, c)
-  const int c = item % D, ks = (item / D) % NKS, mg = item / (D * NKS);
-  const float* base = partial + static_cast<int64_t>(h) * partial_stride + c;
-  const int64_t cstride = static_cast<int64_t>(g.H) * partial_stride;
+  if (!zblock) {
+    const int item = zidx * kScanThreads + threadIdx.x;  // (mg, ks, c, part)
+    const int part = item % kScanParts, rest = item / kScanParts;
+    const int c = rest % D, ks = (rest / D) % NKS, mg = rest / (D * NKS);
+    const float* base = partial + static_cast<int64_t>(h) * partial_stride + c;
+    int row[NV];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) row[j] = cm.m[mg][8 * ks + NV * part + j];
+    float acc[NV];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) acc[j] = 0.0f;
+    const int rb = c / 32, r = c % 32;
+    constexpr int NB = 16;  // chunks in flight (one memory round trip per batch)
+    for (int pos = 0; pos < nc; pos += NB) {
+      float ld[NB][NV];
+#pragma unroll
+      for (int k = 0; k < NB; ++k) {
+        const float* p = base + chunk_at(pos + k < nc ? pos + k : nc - 1) * cstride;
+#pragma unroll
+        for (int j = 0; j < NV; ++j) ld[k][j] = row[j] >= 0 ? p[row[j] * D] : 0.0f;
+      }
+#pragma unroll
+      for (int k = 0; k < NB; ++k) {
+        if (pos + k >= nc) break;
+        u32x4* opA = reinterpret_cast<u32x4*>(pfx + (static_cast<int64_t>(chunk_at(pos + k)) * g.H + h) * stride);
+        uint32_t* piece = reinterpret_cast<uint32_t*>(opA + (rb * NKS + ks) * 64 + 32 * mg + r) + (NV / 2) * part;
+        if constexpr (NV == 8) {
+          u32x4 w;
+#pragma unroll
+          for (int p = 0; p < 4; ++p) w[p] = pack_bf16(acc[2 * p], acc[2 * p + 1]);
+          *reinterpret_cast<u32x4*>(piece) = w;
+        } else if constexpr (NV == 4) {
+          u32x2 w;
+          w[0] = pack_bf16(acc[0], acc[1]);
+          w[1] = pack_bf16(acc[2], acc[3]);
+          *reinterpret_cast<u32x2*>(piece) = w;
+        } else {
+          piece[0] = pack_bf16(acc[0], acc[1]);
+        }
+#pragma unroll
+        for (int j = 0; j < NV; ++j) acc[j] = __builtin_fmaf(acc[j], chunk_decay, ld[k][j]);
+      }
+    }
+    return;
+  }
+  // the normaliser vector by slot: thread (mg, ks) carries eight slots; loads batched like the
+  // rows above (a load per chunk issued next to the store that needs it would cost one memory
+  // round trip per chunk)
+  if (threadIdx.x >= 2 * NKS) return;
+  const int ks = threadIdx.x % NKS, mg = threadIdx.x / NKS;
   int row[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) row[j] = cm.m[mg][8 * ks + j];
-  float acc[8];
+  float z[8];
 #pragma unroll
-  for (int j = 0; j < 8; ++j) acc[j] = 0.0f;
-  const int rb = c / 32, r = c % 32;
-  constexpr int NB = 16;  // chunks in flight (the scan is a chain of memory round trips: one per batch)
-  for (int pos = 0; pos < (zblock ? 0 : nc); pos += NB) {
-    float ld[NB][8];
+  for (int j = 0; j < 8; ++j) z[j] = 0.0f;
+  const float* zb = partial + static_cast<int64_t>(h) * partial_stride + MP * D;
+  constexpr int NZ = 16;
+  for (int pos = 0; pos < nc; pos += NZ) {
+    float ld[NZ][8];
 #pragma unroll
-    for (int k = 0; k < NB; ++k) {
-      const float* p = base + chunk_at(pos + k < nc ? pos + k : nc - 1) * cstride;
+    for (int k = 0; k < NZ; ++k) {
+      const float* p = zb + chunk_at(pos + k < nc ? pos + k : nc - 1) * cstride;
 #pragma unroll
-      for (int j = 0; j < 8; ++j) ld[k][j] = row[j] >= 0 ? p[row[j] * D] : 0.0f;
+      for (int j = 0; j < 8; ++j) ld[k][j] = row[j] >= 0 ? p[row[j]] : 0.0f;
     }
 #pragma unroll
-    for (int k = 0; k < NB; ++k) {
+    for (int k = 0; k < NZ; ++k) {
       if (pos + k >= nc) break;
-      u32x4 w;
+      float* zslot = reinterpret_cast<float*>(pfx + (static_cast<int64_t>(chunk_at(pos + k)) * g.H + h) * stride + z_off);
+      f32x4 lo, hi;
 #pragma unroll
-      for (int p = 0; p < 4; ++p) w[p] = pack_bf16(acc[2 * p], acc[2 * p + 1]);
-      u32x4* opA = reinterpret_cast<u32x4*>(pfx + (static_cast<int64_t>(chunk_at(pos + k)) * g.H + h) * stride);
-      opA[(rb * NKS + ks) * 64 + 32 * mg + r] = w;
-#pragma unroll
-      for (int j = 0; j < 8; ++j) acc[j] = __builtin_fmaf(acc[j], chunk_decay, ld[k][j]);
-    }
-  }
-  // the normaliser vector by slot, carried by the threads of channel 0; loads batched like the
-  // rows above (a load per chunk issued next to the store that needs it would cost one memory
-  // round trip per chunk)
-  if (zblock) {
-    float z[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) z[j] = 0.0f;
-    const float* zb = partial + static_cast<int64_t>(h) * partial_stride + MP * D;
-    constexpr int NZ = 16;
-    for (int pos = 0; pos < nc; pos += NZ) {
-      float ld[NZ][8];
-#pragma unroll
-      for (int k = 0; k < NZ; ++k) {
-        const float* p = zb + chunk_at(pos + k < nc ? pos + k : nc - 1) * cstride;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) ld[k][j] = row[j] >= 0 ? p[row[j]] : 0.0f;
+      for (int j = 0; j < 4; ++j) {
+        lo[j] = z[j];
+        hi[j] = z[4 + j];
       }
+      *reinterpret_cast<f32x4*>(zslot + mg * SP + 8 * ks) = lo;
+      *reinterpret_cast<f32x4*>(zslot + mg * SP + 8 * ks + 4) = hi;
 #pragma unroll
-      for (int k = 0; k < NZ; ++k) {
-        if (pos + k >= nc) break;
-        float* zslot = reinterpret_cast<float*>(pfx + (static_cast<int64_t>(chunk_at(pos + k)) * g.H + h) * stride + z_off);
-        f32x4 lo, hi;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          lo[j] = z[j];
-          hi[j] = z[4 + j];
-        }
-        *reinterpret_cast<f32x4*>(zslot + mg * SP + 8 * ks) = lo;
-        *reinterpret_cast<f32x4*>(zslot + mg * SP + 8 * ks + 4) = hi;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) z[j] = __builtin_fmaf(z[j], chunk_decay, ld[k][j]);
-      }
+      for (int j = 0; j < 8; ++j) z[j] = __builtin_fmaf(z[j], chunk_decay, ld[k][j]);
     }
   }
 }
@@ -640,8 +666,8 @@ __device__ __forceinline__ void prefix_body(int zidx, int zcount, const Geom& g,
 // contract over the channels, used by the backward): image row rho = 32 rbm + r is slot
 // (g, s) = ((rho >> 2) & 1, 16 (rho >> 5) + 4 ((rho >> 3) & 3) + (rho & 3)), so that accumulator
 // register i of row block rbm on lane half gl is the lane's own slot 16 rbm + i.
-// grid (num_seqs, H, (MP / 32) * (D / 16) * 64 / kScanThreads), block kScanThreads; a thread owns eight consecutive
-// channels of one row; the image starts `img_off` bytes into a chunk's block.
+// grid (num_seqs, H, kScanPartsRows * (MP / 32) * (D / 16) * 64 / kScanThreads), block kScanThreads; a
+// piece is eight consecutive channels of one row; the image starts `img_off` bytes into a chunk's block.
 template <class SY, int D, bool REVERSE>
 __device__ __forceinline__ void prefix_rows_body(int zidx, const Geom& g,
                                                  const int32_t* __restrict__ seq_chunk_off,
@@ -649,38 +675,49 @@ __device__ __forceinline__ void prefix_rows_body(int zidx, const Geom& g,
                                                  unsigned char* __restrict__ pfx, const CanonMap& cm,
                                                  float chunk_decay, int64_t stride, int64_t img_off) {
   constexpr int NKD = D / 16;
+  constexpr int PR = kScanPartsRows, NQ = 2 / PR;  // threads per piece, 16-byte loads per thread and chunk
+  static_assert(PR == 1 || PR == 2, "a thread carries eight or four channels of a piece");
   const int s = blockIdx.x, h = blockIdx.y;
   const int c0 = seq_chunk_off[s], c1 = seq_chunk_off[s + 1], nc = c1 - c0;
   auto chunk_at = [&](int pos) { return REVERSE ? c1 - 1 - pos : c0 + pos; };
-  const int item = zidx * kScanThreads + threadIdx.x;  // (rbm, kd, lane)
-  const int lane = item % 64, kd = (item / 64) % NKD, rbm = item / (64 * NKD);
+  const int item = zidx * kScanThreads + threadIdx.x;  // (rbm, kd, lane, part)
+  const int part = item % PR, rest = item / PR;
+  const int lane = rest % 64, kd = (rest / 64) % NKD, rbm = rest / (64 * NKD);
   const int rho = 32 * rbm + lane % 32, gl = lane / 32;
   const int m = cm.m[(rho >> 2) & 1][16 * (rho >> 5) + 4 * ((rho >> 3) & 3) + (rho & 3)];
-  const float* base = partial + static_cast<int64_t>(h) * partial_stride + (m >= 0 ? m : 0) * D + 16 * kd + 8 * gl;
+  const float* base = partial + static_cast<int64_t>(h) * partial_stride + (m >= 0 ? m : 0) * D + 16 * kd + 8 * gl + 4 * NQ * part;
   const int64_t cstride = static_cast<int64_t>(g.H) * partial_stride;
-  float acc[8];
+  float acc[4 * NQ];
 #pragma unroll
-  for (int j = 0; j < 8; ++j) acc[j] = 0.0f;
-  constexpr int NB = 16;
+  for (int j = 0; j < 4 * NQ; ++j) acc[j] = 0.0f;
+  constexpr int NB = kScanBatchRows;
   for (int pos = 0; pos < nc; pos += NB) {
-    f32x4 ld[NB][2];
+    f32x4 ld[NB][NQ];
 #pragma unroll
     for (int k = 0; k < NB; ++k) {
       const f32x4* p = reinterpret_cast<const f32x4*>(base + chunk_at(pos + k < nc ? pos + k : nc - 1) * cstride);
-      ld[k][0] = p[0];
-      ld[k][1] = p[1];
+#pragma unroll
+      for (int x = 0; x < NQ; ++x) ld[k][x] = p[x];
     }
 #pragma unroll
     for (int k = 0; k < NB; ++k) {
       if (pos + k >= nc) break;
-      u32x4 w;
-#pragma unroll
-      for (int p = 0; p < 4; ++p) w[p] = pack_bf16(acc[2 * p], acc[2 * p + 1]);
       u32x4* img = reinterpret_cast<u32x4*>(pfx + (static_cast<int64_t>(chunk_at(pos + k)) * g.H + h) * stride + img_off);
-      img[(rbm * NKD + kd) * 64 + lane] = w;
+      uint32_t* piece = reinterpret_cast<uint32_t*>(img + (rbm * NKD + kd) * 64 + lane) + 2 * NQ * part;
+      if constexpr (NQ == 2) {
+        u32x4 w;
+#pragma unroll
+        for (int p = 0; p < 4; ++p) w[p] = pack_bf16(acc[2 * p], acc[2 * p + 1]);
+        *reinterpret_cast<u32x4*>(piece) = w;
+      } else {
+        u32x2 w;
+        w[0] = pack_bf16(acc[0], acc[1]);
+        w[1] = pack_bf16(acc[2], acc[3]);
+        *reinterpret_cast<u32x2*>(piece) = w;
+      }
       if (m >= 0) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) acc[j] = __builtin_fmaf(acc[j], chunk_decay, ld[k][j / 4][j % 4]);
+        for (int j = 0; j < 4 * NQ; ++j) acc[j] = __builtin_fmaf(acc[j], chunk_decay, ld[k][j / 4][j % 4]);
       }
     }
   }
@@ -2196,8 +2233,8 @@ hla_status backward_causal(hla_handle* hd, const hla_call_args& a) {
   const int relu_mask = hd->cfg.phi_mode == HLA_PHI_MLP ? 1 : 0;
   const CanonMap cm = make_canon_map<SY>();
   const int64_t stride = SL::kOpBytes, z_off = 2 * SL::kOpElems * 2, b_off = SL::kOpElems * 2;
-  const dim3 sgrid(a.num_seqs, g.H, 2 * (SY::MP / 16) * D / kScanThreads + 1);
-  const dim3 rgrid(a.num_seqs, g.H, (SY::MP / 32) * (D / 16) * 64 / kScanThreads);
+  const dim3 sgrid(a.num_seqs, g.H, kScanParts * 2 * (SY::MP / 16) * D / kScanThreads + 1);
+  const dim3 rgrid(a.num_seqs, g.H, kScanPartsRows * (SY::MP / 32) * (D / 16) * 64 / kScanThreads);
   static_assert((SY::MP / 32) * (D / 16) * 64 % kScanThreads == 0, "whole workgroups of row-image items");
   const float* nof = nullptr;
   using PL = PrefixLayout<SY, D>;
@@ -2302,12 +2339,12 @@ hla_status forward_causal(hla_handle* hd, const hla_call_args& a) {
                  static_cast<const float*>(nullptr), static_cast<const float*>(nullptr), cch->count));
   static_assert(2 * (SY::MP / 16) * D % kScanThreads == 0, "whole workgroups of prefix items");
   using PL = PrefixLayout<SY, D>;
-  const int za = 2 * (SY::MP / 16) * D / kScanThreads + 1;
+  const int za = kScanParts * 2 * (SY::MP / 16) * D / kScanThreads + 1;
   if (hd->causal_seen_backward) {
     // a handle in training use: the backward's image of the same running sum (rows = monomials)
     // comes out of the same launch, which spares the backward a scan of its own
     unsigned char* ops = static_cast<unsigned char*>(hd->path_ws) + hd->causal_bwd_off;
-    const int zr = (SY::MP / 32) * (D / 16) * 64 / kScanThreads;
+    const int zr = kScanPartsRows * (SY::MP / 32) * (D / 16) * 64 / kScanThreads;
     HLA_TRY(launch(hd, "mfma_state_prefix", k_prefix_both<SY, D, false>, dim3(a.num_seqs, g.H, za + zr),
                    dim3(kScanThreads), 0, s, g, cch->seq_off_dev, hd->partial, SL::kF32, pfx, make_canon_map<SY>(),
                    chunk_decay, static_cast<int64_t>(PL::kBytes), static_cast<int64_t>(PL::kOpElems * 2), ops,
