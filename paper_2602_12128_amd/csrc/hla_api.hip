@@ -371,9 +371,11 @@ hla_status hla_set_phi_weight_grads(hla_handle* hd, const hla_phi_weight_grads* 
   if (hd->wg_partial == nullptr) {
     const Geom& g = hd->g;
     hd->wg_part_floats = static_cast<int64_t>(g.d) * g.d + g.d + static_cast<int64_t>(g.d) * g.dphi + g.dphi;
-    // at most about 512 partial sums are ever in flight (a few per workgroup of one full grid),
-    // and never fewer than one per (map, head)
-    hd->wg_parts_cap = 512 + 2 * static_cast<int64_t>(num_maps) * hd->cfg.max_heads;
+    // one partial sum per wave group of a grid of at most 256 workgroups (eight waves, a group per
+    // d / 32 hidden blocks: two groups at d = 128, four at d = 64), and never fewer than one per
+    // (map, head)
+    const int64_t groups = g.d >= 32 ? 8 * 32 / g.d : 8;
+    hd->wg_parts_cap = 256 * (groups < 2 ? 2 : groups) + 2 * static_cast<int64_t>(num_maps) * hd->cfg.max_heads;
     Arena arena;  // hipMalloc
     HLA_TRY(arena.alloc(&hd->wg_partial, hd->wg_parts_cap * hd->wg_part_floats));
   }

@@ -29,7 +29,9 @@ def test_weight_grads_fp32_generic_path(F, dphi, d, B, H, N):
     pu.assert_weight_grad_parity(gpu["wg"], ref["wg"], 1e-4, f"generic fp32 F={F} d={d} N={N}")
 
 
-@pytest.mark.parametrize("d,B,H,N", [(128, 1, 2, 700), (64, 2, 3, 333), (128, 2, 1, 95), (64, 1, 1, 33)])
+@pytest.mark.parametrize("d,B,H,N", [(128, 1, 2, 700), (64, 2, 3, 333), (128, 2, 1, 95), (64, 1, 1, 33),
+                                     (64, 1, 4, 4100),    # enough tiles for a full grid of partial sums at d = 64
+                                     (128, 1, 2, 8200)])  # and at d = 128
 def test_weight_grads_bf16_mfma_path(d, B, H, N):
     t, phi = wl.make_raw_inputs(720 + N, B, H, N, d, 3, 6, torch.bfloat16)
     gpu = pu.run_gpu(t, 3, 6, 1e-6, phi=phi, path=hla.HLA_PATH_MFMA, weight_grads=True)
