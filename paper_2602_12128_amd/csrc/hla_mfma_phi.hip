@@ -645,315 +645,22 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_bwd(Geom g, View Q, View K,
 // columns of partial number blockIdx.x * T + th of this (map, head):
 //   [dW1 D*D | db1 D | dW2 D*d_phi | db2 d_phi] floats, scaled by the packing factors
 // (dW1, db1 four times too large, dW2 four times too small); a second kernel adds the partials.
-// A workgroup has four waves, one per SIMD: accumulators, resident operands and two tiles of
-// prefetched inputs need more than the 256 registers a wave gets when two share a SIMD, so the
-// overlap of vector and matrix work comes from a software pipeline inside the wave instead.
+// A workgroup has eight waves, two per SIMD (the live set is kept to 256 registers), and a wave
+// takes one tile per iteration, its steps one after the other: what hides the LDS round trip
+// between writing a tile and reading it back transposed is the other wave of the SIMD.  (A
+// four-wave form with a software pipeline inside the wave -- first layer of tile t+1 and
+// contractions of tile t-1 under the vector work of tile t, two sets of LDS tiles, 352 registers --
+// took 335 us where this one takes 270, 274 against 235 for twelve features per map.)
 template <int D>
 struct WgSmem {
   static constexpr int kXStride = (D + 32) * 2 + 32;  // bytes per token row: channels, 32 du columns, pad
   static constexpr int kGStride = 64 * 2 + 32;        // dh (32 columns), GELU(h) (32 columns), pad
   static constexpr int kXBytes = 32 * kXStride;
-  static constexpr int kWaveBytes = kXBytes + 32 * kGStride;
+  static constexpr int kWaveBytes = kXBytes + 32 * kGStride;  // a wave's two tiles
 };
 
 template <int D, int WAVES, int DPH>
 __global__ __launch_bounds__(WAVES * 64) void k_phi_wgrad(Geom g, View Q, View K,
-                                                          const unsigned char* __restrict__ wpk,
-                                                          int heads_w,
-                                                          const float* __restrict__ feat,
-                                                          const float* __restrict__ dfeat,
-                                                          float* __restrict__ partial) {
-  using SM = WgSmem<D>;
-  using PK = Packed<D>;
-  constexpr int NRB = D / 32, NKS = D / 16, TH = WAVES / NRB;
-  static_assert(WAVES % NRB == 0, "whole groups of hidden blocks");
-  extern __shared__ __align__(16) unsigned char smem[];
-  const int lane = threadIdx.x % kWave, wave = wave_index();
-  const int r = lane % 32, gl = lane / 32;
-  const int L = lane % 16, q = lane / 16;
-  const int hb = wave % NRB, th = wave / NRB;
-  const int m = blockIdx.y, hw = blockIdx.z;
-  unsigned char* xt = smem + wave * 2 * SM::kWaveBytes;  // two sets of (X tile, G tile)
-  unsigned char* gt = xt + SM::kXBytes;
-  const unsigned char* wm = wpk + (static_cast<int64_t>(m) * heads_w + hw) * PK::kBytes;
-  const View& X = m == 0 ? Q : K;
-  // this wave's first-layer operands: rows 32 hb + r of W1^T, k-slot (ks, gl, j) = channel 16ks + 8gl + j
-  u32x4 w1a[NKS];
-#pragma unroll
-  for (int ks = 0; ks < NKS; ++ks)
-    w1a[ks] = *reinterpret_cast<const u32x4*>(wm + PK::kW1T + ((32 * hb + r) * D + 16 * ks + 8 * gl) * 2);
-  const u32x4 w2b = *reinterpret_cast<const u32x4*>(wm + PK::kW2B + (hb * 64 + lane) * 16);
-  f32x16 bias;  // first-layer bias of the block in accumulator order
-  {
-    const float* b1 = reinterpret_cast<const float*>(wm + PK::kB1) + 32 * hb + 4 * gl;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const f32x4 bv = *reinterpret_cast<const f32x4*>(b1 + 8 * i);
-      bias[4 * i] = bv[0];
-      bias[4 * i + 1] = bv[1];
-      bias[4 * i + 2] = bv[2];
-      bias[4 * i + 3] = bv[3];
-    }
-  }
-  // token tiles: one list over all (batch row, head) pairs when the weights are shared
-  const bool shared = heads_w == 1;
-  const int tpr = (g.N + 31) / 32;
-  const int total = (shared ? g.B * g.H : g.B) * tpr;
-  f32x16 acc[NRB];   // dW1 rows 32 ib + d_row(i, gl), column 32 hb + r
-  f32x16 acc2;       // dW2^T rows = features d_row(i, gl), column 32 hb + r
-  float db1[16];     // per-lane (token r) sums of dh for hidden 32 hb + d_row(i, gl)
-  float db2[DPH];    // per-lane sums of du (read from the lanes gl == 0)
-#pragma unroll
-  for (int i = 0; i < 16; ++i) {
-#pragma unroll
-    for (int ib = 0; ib < NRB; ++ib) acc[ib][i] = 0.0f;
-    acc2[i] = 0.0f;
-    db1[i] = 0.0f;
-  }
-#pragma unroll
-  for (int a = 0; a < DPH; ++a) db2[a] = 0.0f;
-  // The next tile's inputs are loaded as soon as the current tile's have been consumed (the
-  // input rows after the copy to LDS, the features once du is formed).  These loads are
-  // unconditional with clamped addresses, so that the same number is outstanding on every path;
-  // the last tile is simply fetched twice.
-  const int step = gridDim.x * TH;
-  int tile = blockIdx.x * TH + th;
-  u32x4 xb[NKS], xn[NKS];  // input rows of the next tile and of the one after
-  float fv[DPH], dv[DPH];
-  auto coords = [&](int t, int& b, int& h, int& n0) {
-    const int row = t / tpr;
-    n0 = (t % tpr) * 32;
-    b = shared ? row / g.H : row;
-    h = shared ? row % g.H : hw;
-  };
-  auto fetch_features = [&](int b, int h, int n0) {
-    const int n = n0 + r;
-    const int64_t o = g.fidx(g.th(b, h, n < g.N ? n : g.N - 1), m * DPH);
-    const f32x2* fp = reinterpret_cast<const f32x2*>(feat + o);
-    const f32x2* dp = reinterpret_cast<const f32x2*>(dfeat + o);
-#pragma unroll
-    for (int p = 0; p < DPH / 2; ++p) {
-      const f32x2 f2 = fp[32 * p], d2 = dp[32 * p];
-      fv[2 * p] = f2[0];
-      fv[2 * p + 1] = f2[1];
-      dv[2 * p] = d2[0];
-      dv[2 * p + 1] = d2[1];
-    }
-  };
-  // Two sets of LDS tiles: while the vector ALU turns tile t's hidden block into dh and GELU(h)
-  // (set t % 2), the matrix pipe runs the first layer of tile t+1 and the contractions of tile
-  // t-1 (set (t-1) % 2), a few MFMAs between the quarters of the vector work.  The sets start as
-  // zeros, so the contraction "of the tile before the first" adds nothing.
-  // (set s of this wave: X tile at xt + s * kWaveBytes, G tile at gt + s * kWaveBytes)
-  {
-    u32x4 z4;
-    z4[0] = z4[1] = z4[2] = z4[3] = 0u;
-    for (int o = lane * 16; o < 2 * SM::kWaveBytes; o += 64 * 16) *reinterpret_cast<u32x4*>(xt + o) = z4;
-  }
-  // du of the token: zero where the ReLU was closed, and for tokens past the end (whose clamped
-  // input row then adds nothing to any sum).  As the B operand of dg = W2 du^T, slot (gl, j) is
-  // feature 8 gl + j: with d_phi <= 8 the lanes gl = 1 hold zeros throughout (db2 included), with
-  // more features they hold the ninth feature on.
-  auto make_du = [&](bool live, u32x4& dub) {
-    float du[DPH];
-#pragma unroll
-    for (int a = 0; a < DPH; ++a) du[a] = live && (DPH > 8 || gl == 0) && fv[a] > 0.0f ? dv[a] : 0.0f;
-#pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      const float lo0 = 2 * p < DPH ? du[2 * p < DPH ? 2 * p : 0] : 0.0f;
-      const float hi0 = 2 * p + 1 < DPH ? du[2 * p + 1 < DPH ? 2 * p + 1 : 0] : 0.0f;
-      const float lo1 = 8 + 2 * p < DPH ? du[8 + 2 * p < DPH ? 8 + 2 * p : 0] : 0.0f;
-      const float hi1 = 9 + 2 * p < DPH ? du[9 + 2 * p < DPH ? 9 + 2 * p : 0] : 0.0f;
-      dub[p] = DPH > 8 ? pack_bf16(gl ? lo1 : lo0, gl ? hi1 : hi0) : pack_bf16(lo0, hi0);
-    }
-#pragma unroll
-    for (int a = 0; a < DPH; ++a) db2[a] += du[a];
-  };
-  auto put_x_tile = [&](unsigned char* xdst, const u32x4 (&xr)[NKS], const u32x4& dub) {  // [token][channels | du]
-#pragma unroll
-    for (int ks = 0; ks < NKS; ++ks)
-      *reinterpret_cast<u32x4*>(xdst + r * SM::kXStride + (16 * ks + 8 * gl) * 2) = xr[ks];
-    u32x4 z4;
-    z4[0] = z4[1] = z4[2] = z4[3] = 0u;
-    // du columns D + 8 gl .. + 7 are this lane's operand slots; columns D + 16 .. D + 31 are zero
-    *reinterpret_cast<u32x4*>(xdst + r * SM::kXStride + (D + 8 * gl) * 2) = dub;
-    *reinterpret_cast<u32x4*>(xdst + r * SM::kXStride + (D + 16 + 8 * gl) * 2) = z4;
-  };
-  // transpose-read operand: tokens 16 ks + 8 gl + {0..7} of 32 columns starting at col0
-  auto operand = [&](const unsigned char* tl, int stride, int ks, int col0) {
-    const int krow = 16 * ks + 8 * gl + L / 4;
-    const unsigned char* p = tl + krow * stride + (col0 + 16 * (q % 2) + 4 * (L % 4)) * 2;
-    const u32x2 lo = lds_read_tr16(p);
-    const u32x2 hi = lds_read_tr16(p + 4 * stride);
-    u32x4 o;
-    o[0] = lo[0];
-    o[1] = lo[1];
-    o[2] = hi[0];
-    o[3] = hi[1];
-    return o;
-  };
-  f32x16 zero;
-#pragma unroll
-  for (int i = 0; i < 16; ++i) zero[i] = 0.0f;
-  f32x16 cur = bias, dg = zero;
-  int buf = 0;
-  if (tile < total) {
-    // first tile: inputs, first layer, dg, [token][channels | du] tile; then the second tile's loads
-    int b, h, n0;
-    coords(tile, b, h, n0);
-    load_x<D>(X, b, h, n0 + r, g.N, gl, xb);
-    fetch_features(b, h, n0);
-    u32x4 dub;
-    make_du(n0 + r < g.N, dub);
-#pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) cur = mfma32(w1a[ks], xb[ks], cur);
-    dg = mfma32(w2b, dub, zero);
-    wave_lds_sync();  // the zero fill is complete
-    put_x_tile(xt, xb, dub);
-    coords(tile + step < total ? tile + step : tile, b, h, n0);
-    load_x<D>(X, b, h, n0 + r, g.N, gl, xb);
-    fetch_features(b, h, n0);
-  }
-  // One stage per tile t: its vector work, the first layer of tile t+1 (input rows in xb) and the
-  // contractions of tile t-1; tile t+2's input rows are loaded into xn and move to xb at the end.
-  for (; tile < total; tile += step) {
-    // xb, fv, dv hold tile t+1 (the last tile again when there is none); cur, dg belong to tile t
-    const int tn = tile + step < total ? tile + step : tile;
-    int b, h, n0;
-    coords(tn, b, h, n0);
-    // tile t+2's input rows: issued first, a whole stage ahead of their use
-    {
-      int b2, h2, n02;
-      coords(tile + 2 * step < total ? tile + 2 * step : tn, b2, h2, n02);
-      load_x<D>(X, b2, h2, n02 + r, g.N, gl, xn);
-    }
-    u32x4 dubn;
-    {
-      // the next tile's du; a repeated last tile counts as past the end, so that db2 is not
-      // touched twice
-      make_du(n0 + r < g.N && tile + step < total, dubn);
-    }
-    {
-      int b2, h2, n02;
-      coords(tile + 2 * step < total ? tile + 2 * step : tn, b2, h2, n02);
-      fetch_features(b2, h2, n02);
-    }
-    const unsigned char* xp = xt + (buf ^ 1) * SM::kWaveBytes;  // tiles of tile t-1
-    const unsigned char* gp_ = gt + (buf ^ 1) * SM::kWaveBytes;
-    unsigned char* gcur = gt + buf * SM::kWaveBytes;
-    f32x16 nxt = bias;
-    // Operands of the contractions are read one slice ahead, before that slice's LDS writes: a
-    // read cannot be moved above an earlier write to the same memory, so a read placed at its
-    // use would wait out its whole latency there.  Slice j = 2 ks + half uses the token step ks
-    // and the input-channel blocks of its half (the du block rides with the first half).
-    constexpr int NH = NRB / 2;
-    auto read_ops = [&](int j, u32x4 (&ops)[NH + 1], u32x4& bdh_, u32x4& bg_) {
-      const int ks = j / 2, half = j % 2;
-#pragma unroll
-      for (int x = 0; x < NH; ++x) ops[x] = operand(xp, SM::kXStride, ks, 32 * (half * NH + x));
-      if (half == 0) {
-        ops[NH] = operand(xp, SM::kXStride, ks, D);
-        bdh_ = operand(gp_, SM::kGStride, ks, 0);
-        bg_ = operand(gp_, SM::kGStride, ks, 32);
-      }
-    };
-    u32x4 ops[NH + 1], bdh, bg;
-    read_ops(0, ops, bdh, bg);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      // matrix pipe: a quarter of tile t+1's first layer and of tile t-1's contractions
-      constexpr int kPer = NKS / 4;
-#pragma unroll
-      for (int t = 0; t < kPer; ++t) nxt = mfma32(w1a[j * kPer + t], xb[j * kPer + t], nxt);
-#pragma unroll
-      for (int x = 0; x < NH; ++x) acc[(j % 2) * NH + x] = mfma32(ops[x], bdh, acc[(j % 2) * NH + x]);
-      if (j % 2 == 0) acc2 = mfma32(ops[NH], bg, acc2);
-      if (j < 3) {
-        if (j % 2 == 0) {
-          u32x4 unused0, unused1;
-          read_ops(j + 1, ops, unused0, unused1);
-        } else {
-          read_ops(j + 1, ops, bdh, bg);
-        }
-      }
-      // vector ALU: slice j of tile t covers hidden 8j + 4gl .. +3 of the block
-      const float in[4] = {cur[4 * j], cur[4 * j + 1], cur[4 * j + 2], cur[4 * j + 3]};
-      f16x2 gv[2], gp[2];
-      gelu_both_f16<2>(in, gv, gp);
-      const float d0 = __builtin_fmaf(static_cast<float>(gp[0][0]), dg[4 * j], 0.0f);
-      const float d1 = __builtin_fmaf(static_cast<float>(gp[0][1]), dg[4 * j + 1], 0.0f);
-      const float d2 = __builtin_fmaf(static_cast<float>(gp[1][0]), dg[4 * j + 2], 0.0f);
-      const float d3 = __builtin_fmaf(static_cast<float>(gp[1][1]), dg[4 * j + 3], 0.0f);
-      db1[4 * j] += d0;
-      db1[4 * j + 1] += d1;
-      db1[4 * j + 2] += d2;
-      db1[4 * j + 3] += d3;
-      u32x2 dh2, g2;
-      dh2[0] = pack_bf16(d0, d1);
-      dh2[1] = pack_bf16(d2, d3);
-      g2[0] = pack_bf16(static_cast<float>(gv[0][0]), static_cast<float>(gv[0][1]));
-      g2[1] = pack_bf16(static_cast<float>(gv[1][0]), static_cast<float>(gv[1][1]));
-      *reinterpret_cast<u32x2*>(gcur + r * SM::kGStride + (8 * j + 4 * gl) * 2) = dh2;
-      *reinterpret_cast<u32x2*>(gcur + r * SM::kGStride + (32 + 8 * j + 4 * gl) * 2) = g2;
-    }
-    const f32x16 dgn = mfma32(w2b, dubn, zero);
-    // tile t+1's [token][channels | du] tile takes the set tile t-1 has just been read from
-    put_x_tile(xt + (buf ^ 1) * SM::kWaveBytes, xb, dubn);
-#pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) xb[ks] = xn[ks];
-    wave_lds_sync();
-    cur = nxt;
-    dg = dgn;
-    buf ^= 1;
-  }
-  // contractions of the last tile (set buf ^ 1 after the final swap)
-  if (static_cast<int>(blockIdx.x) * TH + th < total) {
-    const unsigned char* xp = xt + (buf ^ 1) * SM::kWaveBytes;
-    const unsigned char* gp_ = gt + (buf ^ 1) * SM::kWaveBytes;
-#pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-      const u32x4 bdh = operand(gp_, SM::kGStride, ks, 0);
-      const u32x4 bg = operand(gp_, SM::kGStride, ks, 32);
-#pragma unroll
-      for (int ib = 0; ib < NRB; ++ib) acc[ib] = mfma32(operand(xp, SM::kXStride, ks, 32 * ib), bdh, acc[ib]);
-      acc2 = mfma32(operand(xp, SM::kXStride, ks, D), bg, acc2);
-    }
-  }
-  // ---- this wave's share of the partial
-  const int nparts = gridDim.x * TH;
-  const int64_t floats = static_cast<int64_t>(D) * D + D + D * DPH + DPH;
-  float* out = partial + ((static_cast<int64_t>(m) * gridDim.z + hw) * nparts + blockIdx.x * TH + th) * floats;
-#pragma unroll
-  for (int ib = 0; ib < NRB; ++ib)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) out[(32 * ib + d_row(i, gl)) * D + 32 * hb + r] = acc[ib][i];
-#pragma unroll
-  for (int i = 0; i < (DPH > 8 ? 8 : 4); ++i) {
-    const int a = d_row(i, gl);
-    if (a < DPH) out[D * D + D + (32 * hb + r) * DPH + a] = acc2[i];
-  }
-  // sums over the 32 tokens of a half-wave (xor offsets below 32 stay inside it)
-#pragma unroll
-  for (int i = 0; i < 16; ++i) {
-    float v = db1[i];
-#pragma unroll
-    for (int off = 16; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
-    if (r == 0) out[D * D + 32 * hb + d_row(i, gl)] = v;
-  }
-  if (hb == 0) {
-#pragma unroll
-    for (int a = 0; a < DPH; ++a) {
-      float v = db2[a];
-#pragma unroll
-      for (int off = 16; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
-      if (lane == 0) out[D * D + D + D * DPH + a] = v;
-    }
-  }
-}
-
-// The same sums with eight waves, two per SIMD, and one tile per iteration (see the loop).
-template <int D, int WAVES, int DPH>
-__global__ __launch_bounds__(WAVES * 64) void k_phi_wgrad_s(Geom g, View Q, View K,
                                                           const unsigned char* __restrict__ wpk,
                                                           int heads_w,
                                                           const float* __restrict__ feat,
@@ -1084,15 +791,19 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_wgrad_s(Geom g, View Q, View
   // One tile per iteration, its steps one after the other (first layer, dg, the two LDS tiles,
   // GELU and GELU', the contractions over its tokens): the second wave of the SIMD runs while this
   // one waits.  xb, fv, dv always hold the coming tile, loaded as soon as the current tile has used them.
+  // (with more than eight features per map the feature loads are not run ahead: their registers
+  // are what makes the difference between fitting 256 and spilling)
+  constexpr bool kFeatAhead = DPH <= 8;
   if (tile < total) {
     int b, h, n0;
     coords(tile, b, h, n0);
     load_x<D>(X, b, h, n0 + r, g.N, gl, xb);
-    fetch_features(b, h, n0);
+    if (kFeatAhead) fetch_features(b, h, n0);
   }
   for (; tile < total; tile += step) {
     int b, h, n0;
     coords(tile, b, h, n0);
+    if (!kFeatAhead) fetch_features(b, h, n0);
     u32x4 dub;
     make_du(n0 + r < g.N, dub);
     f32x16 cur = bias;
@@ -1104,7 +815,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_phi_wgrad_s(Geom g, View Q, View
       const int tn = tile + step < total ? tile + step : tile;
       coords(tn, b, h, n0);
       load_x<D>(X, b, h, n0 + r, g.N, gl, xb);
-      fetch_features(b, h, n0);
+      if (kFeatAhead) fetch_features(b, h, n0);
     }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {  // slice j covers hidden 8j + 4gl .. +3 of the block
@@ -1227,22 +938,13 @@ hla_status backward_t(hla_handle* hd, const hla_call_args& a) {
   return HLA_OK;
 }
 
-// The weight-gradient sums run as eight waves, two per SIMD, one tile per iteration
-// (k_phi_wgrad_s) where that form fits 256 registers (d_phi <= 8: 272 us against 338 at the 480p
-// shape); with more features it spills and the four-wave kernel with its software pipeline
-// (k_phi_wgrad) is the faster one (278 us against 333 for the two-factor form).
-template <int DPH>
-constexpr int wgrad_waves() {
-  return DPH <= 8 ? 8 : 4;
-}
+constexpr int kWavesW = 8;  // two waves per SIMD
 
 template <int D, int DPH>
 hla_status weight_grads_t(hla_handle* hd, const hla_call_args& a) {
   using SM = WgSmem<D>;
-  constexpr int kWavesW = wgrad_waves<DPH>();
-  constexpr bool kSimple = kWavesW == 8;
   constexpr int TH = kWavesW / (D / 32);
-  constexpr int lds = (kSimple ? 1 : 2) * kWavesW * SM::kWaveBytes;  // one or two sets of tiles per wave
+  constexpr int lds = kWavesW * SM::kWaveBytes;  // a set of tiles per wave
   Geom g = hd->g;
   const unsigned char* wpk = static_cast<const unsigned char*>(hd->path_ws) + hd->w_packed_off;
   const int nm = 1 + g.F;
@@ -1255,8 +957,7 @@ hla_status weight_grads_t(hla_handle* hd, const hla_call_args& a) {
   if (nblk < 1) nblk = 1;
   const int64_t nparts = nblk * TH;
   if (nm * heads * nparts > hd->wg_parts_cap) return HLA_ERR_STATE;
-  auto kernel = kSimple ? &k_phi_wgrad_s<D, kWavesW, DPH> : &k_phi_wgrad<D, kWavesW, DPH>;
-  HLA_TRY(launch(hd, "mfma_phi_weight_grads", kernel,
+  HLA_TRY(launch(hd, "mfma_phi_weight_grads", k_phi_wgrad<D, kWavesW, DPH>,
                  dim3(static_cast<unsigned>(nblk), nm, heads), dim3(kWavesW * 64), lds, a.stream, g, a.Q, a.K,
                  wpk, hd->phi.heads_w, static_cast<const float*>(hd->feat),
                  static_cast<const float*>(hd->dfeat), hd->wg_partial));
@@ -1269,11 +970,7 @@ template <int D, int F, int DPH>
 hla_status prepare_t() {
   HLA_TRY(allow_lds(&k_phi_fwd<D, F, kWavesF, DPH>, PhiSmem<D>::total(F, kWavesF)));
   HLA_TRY(allow_lds(&k_phi_bwd<D, F, kWavesB, DPH>, PhiSmem<D, true>::total(F, kWavesB)));
-  constexpr int kWavesW = wgrad_waves<DPH>();
-  if constexpr (kWavesW == 8)
-    return allow_lds(&k_phi_wgrad_s<D, kWavesW, DPH>, kWavesW * WgSmem<D>::kWaveBytes);
-  else
-    return allow_lds(&k_phi_wgrad<D, kWavesW, DPH>, 2 * kWavesW * WgSmem<D>::kWaveBytes);
+  return allow_lds(&k_phi_wgrad<D, kWavesW, DPH>, kWavesW * WgSmem<D>::kWaveBytes);
 }
 
 }  // namespace
