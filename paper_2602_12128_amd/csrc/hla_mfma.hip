@@ -817,7 +817,8 @@ template <class SY, int D>
 __global__ __launch_bounds__(causal_query_waves<SY>() * 64) void k_query_causal(Geom g, const BlockEnt* __restrict__ chunks,
                                                            const float* __restrict__ feat, View V,
                                                            const unsigned char* __restrict__ pfx, View O,
-                                                           float* __restrict__ den, float log2_decay) {
+                                                           float* __restrict__ den, float log2_decay,
+                                                           int nchunks) {
   using SM = CausalSmem<SY, D>;
   using PL = PrefixLayout<SY, D>;
   constexpr int SP = SY::SP, MP = SY::MP, DP = SY::DPHI, F = SY::F;
@@ -832,199 +833,229 @@ __global__ __launch_bounds__(causal_query_waves<SY>() * 64) void k_query_causal(
   unsigned char* tile = smem + SM::kVBytes + SM::kSBytes + wave * RowTile<D, SM::kOutRows>::kBytes;
   const int r = lane % 32, gl = lane / 32;
   const int L = lane % 16, q = lane / 16;
-  const BlockEnt e = chunks[blockIdx.x];
-  const int h = blockIdx.y;
-  const unsigned char* pu = pfx + (static_cast<int64_t>(blockIdx.x) * g.H + h) * PL::kBytes;
   static_assert(SM::kImgBytes == PL::kBytes, "the staged image is the prefix record of the chunk");
+  // A workgroup walks the (chunk, head) items blockIdx.x, blockIdx.x + gridDim.x, .. (item = head *
+  // nchunks + chunk): what the next item's start needs from memory is requested while the current
+  // one is worked on (and its table entry an item earlier still), so that only the copy into LDS
+  // stands between two items.
+  struct Staged {  // an item's start as it arrives from memory
+    ImageCopy<SM::kImgLds ? SM::kImgBytes : 16, WAVES * 64> image;  // state in front of the chunk, its normaliser
+    TileRegs<D, kRowsPW> vt;                                        // this wave's share of the V rows
+    f32x2 kraw[kTilesPW][NF / 2];                                   // key features of the tiles it stages
+    f32x2 qraw0[DP / 2];                                            // features of its first query tile
+  };
+  const int qt_first = WAVES == 8 ? (wave < 4 ? wave : 11 - wave) : chunk_tile_of(wave, 0);
   // a query tile's features (tokens beyond the chunk read its last token and are zeroed when used)
-  auto request_query = [&](int qt, f32x2 (&qraw)[DP / 2]) {
+  auto request_query = [&](const BlockEnt& e, int h, int qt, f32x2 (&qraw)[DP / 2]) {
     const int n = e.t0 + 32 * qt + r;
     const f32x2* f = reinterpret_cast<const f32x2*>(feat + g.fidx(g.th(e.b, h, n < e.t1 ? n : e.t1 - 1), 0));
 #pragma unroll
     for (int p = 0; p < DP / 2; ++p) qraw[p] = f[32 * (gl ? DP / 2 - 1 - p : p)];  // lane half 1: pairs in reverse
   };
-  const int qt_first = WAVES == 8 ? (wave < 4 ? wave : 11 - wave) : chunk_tile_of(wave, 0);
-  // ---- everything the start needs from memory, requested at once: the image of the state in front
-  // of the chunk with its normaliser, the chunk's V rows and the key features of the tiles this wave
-  // stages (an equal share per wave), the features of its first query tile
-  ImageCopy<SM::kImgLds ? SM::kImgBytes : 16, WAVES * 64> image;
-  if constexpr (SM::kImgLds) image.request(pu);
-  TileRegs<D, kRowsPW> vt;
-  fetch_tile<D, kRowsPW>(V, e.b, h, e.t0 + kRowsPW * wave, e.t1, lane, vt);
-  f32x2 kraw[kTilesPW][NF / 2];
+  auto request = [&](const BlockEnt& e, int ci, int h, Staged& st) {
+    if constexpr (SM::kImgLds) st.image.request(pfx + (static_cast<int64_t>(ci) * g.H + h) * PL::kBytes);
+    fetch_tile<D, kRowsPW>(V, e.b, h, e.t0 + kRowsPW * wave, e.t1, lane, st.vt);
 #pragma unroll
-  for (int tt = 0; tt < kTilesPW; ++tt) {
-    const int n = e.t0 + 32 * (kTilesPW * wave + tt) + r;
-    const f32x2* f = reinterpret_cast<const f32x2*>(feat + g.fidx(g.th(e.b, h, n < e.t1 ? n : e.t1 - 1), DP));
+    for (int tt = 0; tt < kTilesPW; ++tt) {
+      const int n = e.t0 + 32 * (kTilesPW * wave + tt) + r;
+      const f32x2* f = reinterpret_cast<const f32x2*>(feat + g.fidx(g.th(e.b, h, n < e.t1 ? n : e.t1 - 1), DP));
 #pragma unroll
-    for (int p = 0; p < NF / 2; ++p) kraw[tt][p] = f[32 * p];
-  }
-  f32x2 qraw0[DP / 2];
-  request_query(qt_first, qraw0);
-  // ---- the staged tiles: V rows and key-monomial images
-  if constexpr (SM::kImgLds) image.commit(smem + SM::kBase);
-  put_tile<D, kRowsPW>(vt, lane, vs + kRowsPW * wave * SM::kVStride, SM::kVStride);
-#pragma unroll
-  for (int tt = 0; tt < kTilesPW; ++tt) {
-    const int t = kTilesPW * wave + tt;
-    const bool live_k = e.t0 + 32 * t + r < e.t1;
-    float kf[NF], kr[NF];
-#pragma unroll
-    for (int p = 0; p < NF / 2; ++p) {
-      kf[2 * p] = live_k ? kraw[tt][p][0] : 0.0f;
-      kf[2 * p + 1] = live_k ? kraw[tt][p][1] : 0.0f;
+      for (int p = 0; p < NF / 2; ++p) st.kraw[tt][p] = f[32 * p];
     }
-    float kk[F][DP];
+    request_query(e, h, qt_first, st.qraw0);
+  };
+  // the staged tiles: state image, V rows, key-monomial images
+  auto commit = [&](const BlockEnt& e, const Staged& st) {
+    if constexpr (SM::kImgLds) st.image.commit(smem + SM::kBase);
+    put_tile<D, kRowsPW>(st.vt, lane, vs + kRowsPW * wave * SM::kVStride, SM::kVStride);
 #pragma unroll
-    for (int f = 0; f < F; ++f)
+    for (int tt = 0; tt < kTilesPW; ++tt) {
+      const int t = kTilesPW * wave + tt;
+      const bool live_k = e.t0 + 32 * t + r < e.t1;
+      float kf[NF], kr[NF];
 #pragma unroll
-      for (int c = 0; c < DP; ++c) kr[f * DP + c] = kf[(f + 1) * DP - 1 - c];
+      for (int p = 0; p < NF / 2; ++p) {
+        kf[2 * p] = live_k ? st.kraw[tt][p][0] : 0.0f;
+        kf[2 * p + 1] = live_k ? st.kraw[tt][p][1] : 0.0f;
+      }
+      float kk[F][DP];
 #pragma unroll
-    for (int f = 0; f < F; ++f)
+      for (int f = 0; f < F; ++f)
 #pragma unroll
-      for (int c = 0; c < DP; ++c) kk[f][c] = gl ? kr[f * DP + c] : kf[f * DP + c];
-    float sm[SP];
-    sym_key_monomials_slots<SY>(kk, sm, gl);
+        for (int c = 0; c < DP; ++c) kr[f * DP + c] = kf[(f + 1) * DP - 1 - c];
 #pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) {
-      u32x4 w;
+      for (int f = 0; f < F; ++f)
 #pragma unroll
-      for (int p = 0; p < 4; ++p) w[p] = pack_bf16(sm[8 * ks + 2 * p], sm[8 * ks + 2 * p + 1]);
-      simg[(t * NKS + ks) * 64 + lane] = w;
+        for (int c = 0; c < DP; ++c) kk[f][c] = gl ? kr[f * DP + c] : kf[f * DP + c];
+      float sm[SP];
+      sym_key_monomials_slots<SY>(kk, sm, gl);
+#pragma unroll
+      for (int ks = 0; ks < NKS; ++ks) {
+        u32x4 w;
+#pragma unroll
+        for (int p = 0; p < 4; ++p) w[p] = pack_bf16(sm[8 * ks + 2 * p], sm[8 * ks + 2 * p + 1]);
+        simg[(t * NKS + ks) * 64 + lane] = w;
+      }
     }
-  }
-  __syncthreads();
+  };
   float rowfac[16];  // decay^(31 - key row of accumulator register i)
 #pragma unroll
   for (int i = 0; i < 16; ++i)
     rowfac[i] = log2_decay != 0.0f ? __builtin_amdgcn_exp2f(log2_decay * static_cast<float>(31 - d_row(i, gl))) : 1.0f;
-  const u32x4* opA = reinterpret_cast<const u32x4*>(SM::kImgLds ? smem + SM::kBase : pu);
-  const float* zslot = reinterpret_cast<const float*>((SM::kImgLds ? smem + SM::kBase : pu) + PL::kOpElems * 2) + gl * SP;
-#pragma unroll 1
-  for (int qi = 0; qi < kTilesPW; ++qi) {
-    const int qt = WAVES == 8 ? (wave < 4 ? wave : 11 - wave) : chunk_tile_of(wave, qi);
-    const int n0 = e.t0 + 32 * qt;
-    if (n0 >= e.t1) continue;
-    const int n = n0 + r;
-    const bool live = n < e.t1;
-    float qf[DP];
-    {
-      f32x2 qraw[DP / 2];
-      if (qi == 0) {
+  const int nitems = nchunks * g.H, stride_i = gridDim.x;
+  int item = blockIdx.x;  // < nitems: the grid is never larger
+  int ci = item % nchunks, h = item / nchunks;
+  BlockEnt e = chunks[ci];
+  BlockEnt e_next = chunks[(item + stride_i < nitems ? item + stride_i : item) % nchunks];
+  Staged st;
+  request(e, ci, h, st);
+  while (true) {
+    f32x2 qraw0[DP / 2];
 #pragma unroll
-        for (int p = 0; p < DP / 2; ++p) qraw[p] = qraw0[p];
-      } else {
-        request_query(qt, qraw);
-      }
-#pragma unroll
-      for (int p = 0; p < DP / 2; ++p) {  // and each pair in reverse
-        qf[2 * p] = live ? (gl ? qraw[p][1] : qraw[p][0]) : 0.0f;
-        qf[2 * p + 1] = live ? (gl ? qraw[p][0] : qraw[p][1]) : 0.0f;
-      }
-    }
-    float qm[SP];
-    sym_query_monomials<SY>(qf, qm, gl);
-    u32x4 b[NKS];
-    float eta = 0.0f;
-#pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) {
-      const f32x4 z0 = *reinterpret_cast<const f32x4*>(zslot + 8 * ks);
-      const f32x4 z1 = *reinterpret_cast<const f32x4*>(zslot + 8 * ks + 4);
-#pragma unroll
-      for (int p = 0; p < 4; ++p) {
-        const int s = 8 * ks + 2 * p;
-        const uint32_t pk = pack_bf16(qm[s], qm[s + 1]);
-        b[ks][p] = pk;
-        const float za = p < 2 ? z0[2 * p] : z1[2 * p - 4], zb = p < 2 ? z0[2 * p + 1] : z1[2 * p - 3];
-        eta += bf16_lo(pk) * za + bf16_hi(pk) * zb;  // the same rounded values the MFMA sees
-      }
-    }
-    // everything before the chunk: the prefix state
-    f32x16 acc[NRB];
-#pragma unroll
-    for (int rb = 0; rb < NRB; ++rb) {
-#pragma unroll
-      for (int i = 0; i < 16; ++i) acc[rb][i] = 0.0f;
-#pragma unroll
-      for (int ks = 0; ks < NKS; ++ks) acc[rb] = mfma32(opA[(rb * NKS + ks) * 64 + lane], b[ks], acc[rb]);
-    }
-    if (log2_decay != 0.0f) {  // the prefix state is as seen from the chunk's first token
-      const float wq = __builtin_amdgcn_exp2f(log2_decay * static_cast<float>(32 * qt + r));
-      eta *= wq;
-#pragma unroll
-      for (int rb = 0; rb < NRB; ++rb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) acc[rb][i] *= wq;
-    }
-    // the chunk's own tokens up to the query: key tiles 0 .. qt
-#pragma unroll 1
-    for (int kt = 0; kt <= qt; ++kt) {
-      f32x16 P;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) P[i] = 0.0f;
+    for (int p = 0; p < DP / 2; ++p) qraw0[p] = st.qraw0[p];
+    commit(e, st);
+    __syncthreads();
+    const int item_n = item + stride_i;
+    const bool more = item_n < nitems;  // the same for the whole workgroup
+    const int cn = item_n % nchunks, hn = item_n / nchunks;
+    if (more) request(e_next, cn, hn, st);
+    const BlockEnt e_next2 = chunks[(item_n + stride_i < nitems ? item_n + stride_i : item) % nchunks];
+    const unsigned char* pu = pfx + (static_cast<int64_t>(ci) * g.H + h) * PL::kBytes;
+    const u32x4* opA = reinterpret_cast<const u32x4*>(SM::kImgLds ? smem + SM::kBase : pu);
+    const float* zslot = reinterpret_cast<const float*>((SM::kImgLds ? smem + SM::kBase : pu) + PL::kOpElems * 2) + gl * SP;
+  #pragma unroll 1
+    for (int qi = 0; qi < kTilesPW; ++qi) {
+      const int qt = WAVES == 8 ? (wave < 4 ? wave : 11 - wave) : chunk_tile_of(wave, qi);
+      const int n0 = e.t0 + 32 * qt;
+      if (n0 >= e.t1) continue;
+      const int n = n0 + r;
+      const bool live = n < e.t1;
+      float qf[DP];
       {
-        u32x4 sa[NKS];  // all operands requested before the first MFMA
-#pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) sa[ks] = simg[(kt * NKS + ks) * 64 + lane];
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) P = mfma32(sa[ks], b[ks], P);
-      }
-      if (log2_decay != 0.0f) {  // decay^(query position - key position); masked entries get 0 below
-        if (kt < qt) {  // distance >= 1: a per-lane factor times a per-register one (both at most 1)
-          const float cw = __builtin_amdgcn_exp2f(log2_decay * static_cast<float>(32 * (qt - kt) + r - 31));
-#pragma unroll
-          for (int i = 0; i < 16; ++i) P[i] *= cw * rowfac[i];
+        f32x2 qraw[DP / 2];
+        if (qi == 0) {
+  #pragma unroll
+          for (int p = 0; p < DP / 2; ++p) qraw[p] = qraw0[p];
         } else {
-#pragma unroll
-          for (int i = 0; i < 16; ++i)
-            P[i] *= __builtin_amdgcn_exp2f(log2_decay * fmaxf(static_cast<float>(r - d_row(i, gl)), 0.0f));
+          request_query(e, h, qt, qraw);
+        }
+  #pragma unroll
+        for (int p = 0; p < DP / 2; ++p) {  // and each pair in reverse
+          qf[2 * p] = live ? (gl ? qraw[p][1] : qraw[p][0]) : 0.0f;
+          qf[2 * p + 1] = live ? (gl ? qraw[p][0] : qraw[p][1]) : 0.0f;
         }
       }
-      if (kt == qt) {  // key d_row(i, gl) of the tile against query r: later keys are masked
-#pragma unroll
-        for (int i = 0; i < 16; ++i)
-          if (d_row(i, gl) > r) P[i] = 0.0f;
-      }
-      u32x4 pb[2];
-#pragma unroll
-      for (int ks2 = 0; ks2 < 2; ++ks2)
-#pragma unroll
+      float qm[SP];
+      sym_query_monomials<SY>(qf, qm, gl);
+      u32x4 b[NKS];
+      float eta = 0.0f;
+  #pragma unroll
+      for (int ks = 0; ks < NKS; ++ks) {
+        const f32x4 z0 = *reinterpret_cast<const f32x4*>(zslot + 8 * ks);
+        const f32x4 z1 = *reinterpret_cast<const f32x4*>(zslot + 8 * ks + 4);
+  #pragma unroll
         for (int p = 0; p < 4; ++p) {
-          const uint32_t pk = pack_bf16(P[8 * ks2 + 2 * p], P[8 * ks2 + 2 * p + 1]);
-          pb[ks2][p] = pk;
-          eta += bf16_lo(pk) + bf16_hi(pk);
-        }
-      // O^T += V^T P: k-slot (ks2, gl, j) is key 16 ks2 + 8 (j / 4) + 4 gl + j % 4 of the tile, the
-      // order in which the score accumulators hold the keys
-      u32x4 va[2][NRB];
-#pragma unroll
-      for (int ks2 = 0; ks2 < 2; ++ks2) {
-        const int krow = 32 * kt + 16 * ks2 + 4 * gl + L / 4;
-#pragma unroll
-        for (int rb = 0; rb < NRB; ++rb) {
-          const unsigned char* p = vs + krow * SM::kVStride + (32 * rb + 16 * (q % 2) + 4 * (L % 4)) * 2;
-          const u32x2 lo = lds_read_tr16(p);
-          const u32x2 hi = lds_read_tr16(p + 8 * SM::kVStride);
-          va[ks2][rb][0] = lo[0];
-          va[ks2][rb][1] = lo[1];
-          va[ks2][rb][2] = hi[0];
-          va[ks2][rb][3] = hi[1];
+          const int s = 8 * ks + 2 * p;
+          const uint32_t pk = pack_bf16(qm[s], qm[s + 1]);
+          b[ks][p] = pk;
+          const float za = p < 2 ? z0[2 * p] : z1[2 * p - 4], zb = p < 2 ? z0[2 * p + 1] : z1[2 * p - 3];
+          eta += bf16_lo(pk) * za + bf16_hi(pk) * zb;  // the same rounded values the MFMA sees
         }
       }
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int ks2 = 0; ks2 < 2; ++ks2)
-#pragma unroll
-        for (int rb = 0; rb < NRB; ++rb) acc[rb] = mfma32(va[ks2][rb], pb[ks2], acc[rb]);
+      // everything before the chunk: the prefix state
+      f32x16 acc[NRB];
+  #pragma unroll
+      for (int rb = 0; rb < NRB; ++rb) {
+  #pragma unroll
+        for (int i = 0; i < 16; ++i) acc[rb][i] = 0.0f;
+  #pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) acc[rb] = mfma32(opA[(rb * NKS + ks) * 64 + lane], b[ks], acc[rb]);
+      }
+      if (log2_decay != 0.0f) {  // the prefix state is as seen from the chunk's first token
+        const float wq = __builtin_amdgcn_exp2f(log2_decay * static_cast<float>(32 * qt + r));
+        eta *= wq;
+  #pragma unroll
+        for (int rb = 0; rb < NRB; ++rb)
+  #pragma unroll
+          for (int i = 0; i < 16; ++i) acc[rb][i] *= wq;
+      }
+      // the chunk's own tokens up to the query: key tiles 0 .. qt
+  #pragma unroll 1
+      for (int kt = 0; kt <= qt; ++kt) {
+        f32x16 P;
+  #pragma unroll
+        for (int i = 0; i < 16; ++i) P[i] = 0.0f;
+        {
+          u32x4 sa[NKS];  // all operands requested before the first MFMA
+  #pragma unroll
+          for (int ks = 0; ks < NKS; ++ks) sa[ks] = simg[(kt * NKS + ks) * 64 + lane];
+          __builtin_amdgcn_sched_barrier(0);
+  #pragma unroll
+          for (int ks = 0; ks < NKS; ++ks) P = mfma32(sa[ks], b[ks], P);
+        }
+        if (log2_decay != 0.0f) {  // decay^(query position - key position); masked entries get 0 below
+          if (kt < qt) {  // distance >= 1: a per-lane factor times a per-register one (both at most 1)
+            const float cw = __builtin_amdgcn_exp2f(log2_decay * static_cast<float>(32 * (qt - kt) + r - 31));
+  #pragma unroll
+            for (int i = 0; i < 16; ++i) P[i] *= cw * rowfac[i];
+          } else {
+  #pragma unroll
+            for (int i = 0; i < 16; ++i)
+              P[i] *= __builtin_amdgcn_exp2f(log2_decay * fmaxf(static_cast<float>(r - d_row(i, gl)), 0.0f));
+          }
+        }
+        if (kt == qt) {  // key d_row(i, gl) of the tile against query r: later keys are masked
+  #pragma unroll
+          for (int i = 0; i < 16; ++i)
+            if (d_row(i, gl) > r) P[i] = 0.0f;
+        }
+        u32x4 pb[2];
+  #pragma unroll
+        for (int ks2 = 0; ks2 < 2; ++ks2)
+  #pragma unroll
+          for (int p = 0; p < 4; ++p) {
+            const uint32_t pk = pack_bf16(P[8 * ks2 + 2 * p], P[8 * ks2 + 2 * p + 1]);
+            pb[ks2][p] = pk;
+            eta += bf16_lo(pk) + bf16_hi(pk);
+          }
+        // O^T += V^T P: k-slot (ks2, gl, j) is key 16 ks2 + 8 (j / 4) + 4 gl + j % 4 of the tile, the
+        // order in which the score accumulators hold the keys
+        u32x4 va[2][NRB];
+  #pragma unroll
+        for (int ks2 = 0; ks2 < 2; ++ks2) {
+          const int krow = 32 * kt + 16 * ks2 + 4 * gl + L / 4;
+  #pragma unroll
+          for (int rb = 0; rb < NRB; ++rb) {
+            const unsigned char* p = vs + krow * SM::kVStride + (32 * rb + 16 * (q % 2) + 4 * (L % 4)) * 2;
+            const u32x2 lo = lds_read_tr16(p);
+            const u32x2 hi = lds_read_tr16(p + 8 * SM::kVStride);
+            va[ks2][rb][0] = lo[0];
+            va[ks2][rb][1] = lo[1];
+            va[ks2][rb][2] = hi[0];
+            va[ks2][rb][3] = hi[1];
+          }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+  #pragma unroll
+        for (int ks2 = 0; ks2 < 2; ++ks2)
+  #pragma unroll
+          for (int rb = 0; rb < NRB; ++rb) acc[rb] = mfma32(va[ks2][rb], pb[ks2], acc[rb]);
+      }
+      eta += partner32(eta);
+      const float dn = eta + g.eps;
+      const float inv = 1.0f / dn;
+      if (live && gl == 0) den[g.th(e.b, h, n)] = dn;
+      store_rows_bf16<D, SM::kOutRows>(acc, inv, lane, tile, [&](int t) -> bf16_t* {
+        return n0 + t < e.t1 ? O.row<bf16_t>(e.b, h, n0 + t) : nullptr;
+      });
     }
-    eta += partner32(eta);
-    const float dn = eta + g.eps;
-    const float inv = 1.0f / dn;
-    if (live && gl == 0) den[g.th(e.b, h, n)] = dn;
-    store_rows_bf16<D, SM::kOutRows>(acc, inv, lane, tile, [&](int t) -> bf16_t* {
-      return n0 + t < e.t1 ? O.row<bf16_t>(e.b, h, n0 + t) : nullptr;
-    });
+    if (!more) break;
+    __syncthreads();  // every wave is done with this item's tiles
+    item = item_n;
+    ci = cn;
+    h = hn;
+    e = e_next;
+    e_next = e_next2;
   }
 }
 
@@ -2355,8 +2386,11 @@ hla_status forward_causal(hla_handle* hd, const hla_call_args& a) {
                    static_cast<int64_t>(PL::kBytes), static_cast<int64_t>(PL::kOpElems * 2)));
   }
   hd->causal_rows_valid = hd->causal_seen_backward;
-  HLA_TRY(launch(hd, "mfma_query_causal", k_query_causal<SY, D>, dim3(cch->count, g.H), dim3(SC::kWavesQ * 64),
-                 SC::kTotal, s, g, cch->dev, hd->feat, a.V, pfx, a.O, hd->den, l2d));
+  // one resident workgroup per compute unit, each walking its share of the (chunk, head) items
+  const int64_t items = static_cast<int64_t>(cch->count) * g.H;
+  HLA_TRY(launch(hd, "mfma_query_causal", k_query_causal<SY, D>, dim3(static_cast<unsigned>(items < kChunkTarget ? items : kChunkTarget)),
+                 dim3(SC::kWavesQ * 64), SC::kTotal, s, g, cch->dev, hd->feat, a.V, pfx, a.O, hd->den, l2d,
+                 static_cast<int>(cch->count)));
   hd->causal_partials_valid = true;  // the partial buffer holds this forward's chunk states
   return HLA_OK;
 }
