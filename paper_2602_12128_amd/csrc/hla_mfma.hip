@@ -72,18 +72,22 @@ struct StateLayout {
 // ---- sum of per-wave accumulator tiles over the four waves of a workgroup ------------------------
 // Every wave holds a [MP rows x D] fp32 tile in MFMA accumulator layout (acc[rb][cb][i]: row
 // 32rb + d_row(i, gl), column 32cb + r) and an MP-vector zl (element (MP/2) gl + k, replicated
-// over r).  Fixed order (w0 + w1) + (w2 + w3), two LDS regions of (MP D + MP) floats, four barriers;
+// over r).  Fixed order (w0 + w1) + (w2 + w3), LDS regions of (MP D + MP) floats;
 // the sum ends in region 0 with tile row `row` at floats [row * D, row * D + D) and the vector at
 // MP D.
 template <int D, int MP>
 struct WaveSum {
   static constexpr int kRegion = MP * D + MP;          // floats
-  static constexpr int kBytes = 2 * kRegion * 4;
+  // a region per wave where LDS has room for four (one pass, everybody adds); else two regions
+  // and the waves add pairwise through their registers
+  static constexpr bool kFlat = 4 * kRegion * 4 <= 160 * 1024;
+  static constexpr int kBytes = (kFlat ? 4 : 2) * kRegion * 4;
 };
 template <int D, int MP>
 __device__ __forceinline__ void sum_over_waves(f32x16 (&acc)[MP / 32][D / 32], float (&zl)[MP / 2],
                                                float* lds, int wave, int lane) {
   constexpr int NCB = D / 32, NRM = MP / 32, HALF = MP / 2;
+  using WS = WaveSum<D, MP>;
   const int r = lane % 32, gl = lane / 32;
   auto put = [&](float* reg) {
 #pragma unroll
@@ -97,6 +101,25 @@ __device__ __forceinline__ void sum_over_waves(f32x16 (&acc)[MP / 32][D / 32], f
       for (int k = 0; k < HALF; ++k) reg[MP * D + HALF * gl + k] = zl[k];
     }
   };
+  if constexpr (WS::kFlat) {
+    // the same sum, (w0 + w1) + (w2 + w3) entry by entry, formed by all threads at once
+    __syncthreads();
+    put(lds + wave * WS::kRegion);
+    __syncthreads();
+    static_assert(WS::kRegion % 4 == 0, "16-byte pieces");
+    for (int i = threadIdx.x; i < WS::kRegion / 4; i += kThreads) {
+      const f32x4 a = reinterpret_cast<const f32x4*>(lds)[i];
+      const f32x4 b = reinterpret_cast<const f32x4*>(lds + WS::kRegion)[i];
+      const f32x4 c = reinterpret_cast<const f32x4*>(lds + 2 * WS::kRegion)[i];
+      const f32x4 d = reinterpret_cast<const f32x4*>(lds + 3 * WS::kRegion)[i];
+      f32x4 v;
+#pragma unroll
+      for (int x = 0; x < 4; ++x) v[x] = (a[x] + b[x]) + (c[x] + d[x]);
+      reinterpret_cast<f32x4*>(lds)[i] = v;
+    }
+    __syncthreads();
+    return;
+  }
   auto add = [&](const float* reg) {
 #pragma unroll
     for (int rb = 0; rb < NRM; ++rb)
@@ -107,7 +130,7 @@ __device__ __forceinline__ void sum_over_waves(f32x16 (&acc)[MP / 32][D / 32], f
 #pragma unroll
     for (int k = 0; k < HALF; ++k) zl[k] += reg[MP * D + HALF * gl + k];
   };
-  float* reg = lds + (wave / 2) * WaveSum<D, MP>::kRegion;
+  float* reg = lds + (wave / 2) * WS::kRegion;
   __syncthreads();
   if (wave % 2 == 1) put(reg);
   __syncthreads();
