@@ -73,8 +73,8 @@ struct StateLayout {
 // Every wave holds a [MP rows x D] fp32 tile in MFMA accumulator layout (acc[rb][cb][i]: row
 // 32rb + d_row(i, gl), column 32cb + r) and an MP-vector zl (element (MP/2) gl + k, replicated
 // over r).  Fixed order (w0 + w1) + (w2 + w3), LDS regions of (MP D + MP) floats;
-// the sum ends in region 0 with tile row `row` at floats [row * D, row * D + D) and the vector at
-// MP D.
+// the sum (read through summed4 / summed1) has tile row `row` at floats [row * D, row * D + D) and
+// the vector at MP D.
 template <int D, int MP>
 struct WaveSum {
   static constexpr int kRegion = MP * D + MP;          // floats
@@ -102,21 +102,9 @@ __device__ __forceinline__ void sum_over_waves(f32x16 (&acc)[MP / 32][D / 32], f
     }
   };
   if constexpr (WS::kFlat) {
-    // the same sum, (w0 + w1) + (w2 + w3) entry by entry, formed by all threads at once
+    // every wave leaves its tile in a region of its own; summed4 / summed1 below form the sum
     __syncthreads();
     put(lds + wave * WS::kRegion);
-    __syncthreads();
-    static_assert(WS::kRegion % 4 == 0, "16-byte pieces");
-    for (int i = threadIdx.x; i < WS::kRegion / 4; i += kThreads) {
-      const f32x4 a = reinterpret_cast<const f32x4*>(lds)[i];
-      const f32x4 b = reinterpret_cast<const f32x4*>(lds + WS::kRegion)[i];
-      const f32x4 c = reinterpret_cast<const f32x4*>(lds + 2 * WS::kRegion)[i];
-      const f32x4 d = reinterpret_cast<const f32x4*>(lds + 3 * WS::kRegion)[i];
-      f32x4 v;
-#pragma unroll
-      for (int x = 0; x < 4; ++x) v[x] = (a[x] + b[x]) + (c[x] + d[x]);
-      reinterpret_cast<f32x4*>(lds)[i] = v;
-    }
     __syncthreads();
     return;
   }
@@ -143,6 +131,28 @@ __device__ __forceinline__ void sum_over_waves(f32x16 (&acc)[MP / 32][D / 32], f
     put(lds);
   }
   __syncthreads();
+}
+
+// Entries of the sum after sum_over_waves: floats [4i, 4i + 4) and float i of the summed region.
+template <int D, int MP>
+__device__ __forceinline__ f32x4 summed4(const float* lds, int i) {
+  using WS = WaveSum<D, MP>;
+  static_assert(WS::kRegion % 4 == 0, "16-byte pieces");
+  const f32x4 a = reinterpret_cast<const f32x4*>(lds)[i];
+  if constexpr (!WS::kFlat) return a;
+  const f32x4 b = reinterpret_cast<const f32x4*>(lds + WS::kRegion)[i];
+  const f32x4 c = reinterpret_cast<const f32x4*>(lds + 2 * WS::kRegion)[i];
+  const f32x4 d = reinterpret_cast<const f32x4*>(lds + 3 * WS::kRegion)[i];
+  f32x4 v;
+#pragma unroll
+  for (int x = 0; x < 4; ++x) v[x] = (a[x] + b[x]) + (c[x] + d[x]);
+  return v;
+}
+template <int D, int MP>
+__device__ __forceinline__ float summed1(const float* lds, int i) {
+  using WS = WaveSum<D, MP>;
+  if constexpr (!WS::kFlat) return lds[i];
+  return (lds[i] + lds[WS::kRegion + i]) + (lds[2 * WS::kRegion + i] + lds[3 * WS::kRegion + i]);
 }
 
 // ---- k_state ----------------------------------------------------------------------------------
@@ -351,11 +361,11 @@ __global__ __launch_bounds__(kThreads) void k_state(Geom g, const BlockEnt* __re
   sum_over_waves<D, MP>(acc, zl, red, wave, lane);
   float* out = partial + (static_cast<int64_t>(blockIdx.x) * g.H + h) * partial_stride;
   for (int i = threadIdx.x; i < MP * D / 4; i += kThreads)
-    reinterpret_cast<f32x4*>(out)[i] = reinterpret_cast<const f32x4*>(red)[i];
+    reinterpret_cast<f32x4*>(out)[i] = summed4<D, MP>(red, i);
   // vector element (MP/2) gl + 16 rb + i is state row 32 rb + d_row(i, gl)
   if (threadIdx.x < MP) {
     const int gg = threadIdx.x / (MP / 2), k = threadIdx.x % (MP / 2);
-    out[MP * D + 32 * (k / 16) + d_row(k % 16, gg)] = red[MP * D + threadIdx.x];
+    out[MP * D + 32 * (k / 16) + d_row(k % 16, gg)] = summed1<D, MP>(red, MP * D + threadIdx.x);
   }
 }
 
@@ -1356,7 +1366,7 @@ __global__ __launch_bounds__(kThreads) void k_bwd_query(
   float* red = reinterpret_cast<float*>(smem);
   sum_over_waves<D, MP>(dC, dzacc, red, wave, lane);
   f32x4* out = reinterpret_cast<f32x4*>(partial + (static_cast<int64_t>(blockIdx.x) * g.H + h) * partial_stride);
-  for (int i = threadIdx.x; i < (MP * D + MP) / 4; i += kThreads) out[i] = reinterpret_cast<const f32x4*>(red)[i];
+  for (int i = threadIdx.x; i < (MP * D + MP) / 4; i += kThreads) out[i] = summed4<D, MP>(red, i);
 }
 
 // ---- k_bwd_key --------------------------------------------------------------------------------
