@@ -469,3 +469,34 @@ def test_causal_steps_after_the_first_reuse_the_forward_scan_bit_identically():
     ref = _causal_oracle_backward(ta, 3, 6, decay=0.99)
     pu.assert_parity(dict(zip(("O", "dQ", "dK", "dV"), second)), ref, 2e-2, "causal, second step on a handle",
                      row_scale=pu.causal_first_token_rows(ta, ref))
+
+
+def test_causal_dense_batch_of_longer_sequences_and_later_steps():
+    """A dense batch of two sequences of 20 chunks each (more than one batch of the scans' loads, the
+    last one ragged), with decay, the two-factor form: forward and backward against the oracle's
+    state recursions, and the second step on the handle (forward scan writing both images) gives
+    the bits of the first."""
+    dev = torch.device("cuda:0")
+    F, dphi, d, B, H, N, lam = 2, 12, 64, 2, 2, 4900, 0.9993
+    t = wl.make_feature_inputs(1470, B, H, N, d, F, dphi, torch.bfloat16)
+    h = hla.HLA(head_dim=d, feature_dim=dphi, degree=F, eps=1e-6, io_dtype=hla.HLA_BF16, phi_mode=hla.HLA_PHI_NONE,
+                max_heads=H, max_tokens=B * N, max_seqs=B, causal=True, decay=lam)
+    td = {k: v.to(dev) for k, v in t.items()}
+
+    def step():
+        out = [torch.full_like(td["V"], float("nan"))] + [torch.full_like(td[k], float("nan")) for k in "QKV"]
+        h.forward(td["Q"], td["K"], td["V"], out[0])
+        h.backward(td["Q"], td["K"], td["V"], out[0], td["dO"], *out[1:])
+        torch.cuda.synchronize()
+        return [x.cpu() for x in out]
+
+    first, second = step(), step()
+    h.destroy()
+    for x, y in zip(first, second):
+        assert torch.equal(x, y)
+    Q, K, V, dO = (pu.to_np(t[k]) for k in ("Q", "K", "V", "dO"))
+    ref = {"O": orc.hla_operator_forward(Q, K, V, F, dphi, 1e-6, causal=True, decay=lam)}
+    res = orc.hla_operator_backward(Q, K, V, dO, F, dphi, 1e-6, causal=True, decay=lam)
+    ref.update(dQ=res[0], dK=res[1], dV=res[2])
+    pu.assert_parity(dict(zip(("O", "dQ", "dK", "dV"), first)), ref, 2e-2, "causal, dense batch of 4900-token sequences",
+                     row_scale=pu.causal_first_token_rows(t, ref))
