@@ -734,20 +734,34 @@ __global__ __launch_bounds__(WAVES * 64, FACTORS ? 1 : 2) void k_vmod_bwd_map(Ge
 }
 
 // C[i][j] = sum over tokens of A[t][i] B[t][j] and z[i] = sum over tokens of A[t][i] for two bf16
-// [B, H, N, D] views, on the matrix cores.  grid (parts, D / 64), block 256: workgroup half
+// [B, H, N, D] views, on the matrix cores.  grid (parts, D / 64, jobs), block 256: workgroup half
 // blockIdx.y owns rows 64 y .. 64 y + 63 of C; each wave streams 64-token sub-tiles (both row tiles
 // through its private LDS, both operands by transpose reads, k = token) of the flat list over all
-// (batch row, head) pairs of the flat list; the workgroup writes one partial:
-//   part[blockIdx.x * (D / 64) + y] = [C rows 64 x D | z 64] floats (the four waves summed in order).
+// (batch row, head) pairs; the workgroup writes one partial:
+//   part[(job * parts + blockIdx.x) * (D / 64) + y] = [C rows 64 x D | z 64] floats (the four waves
+//   summed in order).  grid.z = jobs: the (A, B) pairs of the list.
 template <int D>
 struct TnSmem {
   static constexpr int kStride = D * 2 + 32;
   static constexpr int kTile = 64 * kStride;
   static constexpr int kTotal = 4 * 2 * kTile;
 };
+// The token contractions of one backward as a list: one launch forms them all (blockIdx.z picks
+// the job), a second one adds up the partials of each.
+constexpr int kTnJobs = 6;
+struct TnJob {
+  View A, Bv;
+  float* M;
+  float* v;
+  int diag;
+};
+struct TnJobs {
+  TnJob j[kTnJobs];
+};
 template <int D>
-__global__ __launch_bounds__(256) void k_tn_mfma(Geom g, View A, View Bv, float* __restrict__ part) {
+__global__ __launch_bounds__(256) void k_tn_mfma(Geom g, TnJobs jobs, float* __restrict__ part) {
   using SM = TnSmem<D>;
+  const View A = jobs.j[blockIdx.z].A, Bv = jobs.j[blockIdx.z].Bv;
   constexpr int NCB = D / 32;
   extern __shared__ __align__(16) unsigned char smem[];
   const int lane = threadIdx.x % kWave, wave = wave_index();
@@ -832,21 +846,23 @@ __global__ __launch_bounds__(256) void k_tn_mfma(Geom g, View A, View Bv, float*
     }
   __syncthreads();
   const float* all = reinterpret_cast<const float*>(smem);
-  float* out = part + (static_cast<int64_t>(blockIdx.x) * gridDim.y + half) * PW;
+  float* out = part + ((static_cast<int64_t>(blockIdx.z) * gridDim.x + blockIdx.x) * gridDim.y + half) * PW;
   for (int k = threadIdx.x; k < PW; k += 256) out[k] = ((all[k] + all[PW + k]) + all[2 * PW + k]) + all[3 * PW + k];
 }
 
 // Adds the `nparts` partials of k_tn_mfma in order.  diag = 0: M[j * D + i] = C[i][j] (the
 // transpose: the products are formed with the gradient as the A operand) and v[i] = z[i];
-// diag = 1: M[i] = C[i][i], v[i] = z[i].  grid (D * D / 256), block 256.
+// diag = 1: M[i] = C[i][i], v[i] = z[i].  grid (D * D / 256, jobs), block 256.
 template <int D>
-__global__ void k_tn_reduce(const float* __restrict__ part, int nparts, int diag, float* __restrict__ M,
-                            float* __restrict__ v) {
+__global__ void k_tn_reduce(const float* __restrict__ part, int nparts, TnJobs jobs) {
   constexpr int HALVES = D / 64;
   constexpr int64_t PW = 64 * D + 64;
+  const int diag = jobs.j[blockIdx.y].diag;
+  float* __restrict__ M = jobs.j[blockIdx.y].M;
+  float* __restrict__ v = jobs.j[blockIdx.y].v;
   const int idx = blockIdx.x * 256 + threadIdx.x;  // i * D + j
   const int i = idx / D, j = idx % D;
-  const float* base = part + static_cast<int64_t>(i / 64) * PW;
+  const float* base = part + (static_cast<int64_t>(blockIdx.y) * nparts * HALVES + i / 64) * PW;
   // eight partials' loads in flight at a time, added in order
   auto sum = [&](int64_t off) {
     float s = 0.0f;
@@ -937,31 +953,25 @@ hla_status backward_t(hla_handle* hd, const hla_call_args& a) {
   return backward_map_t<D, 0>(hd, a, vmod_view(hd->vmod_dT, hd->g));
 }
 
-constexpr int kTnBlocks = 128;  // workgroups per row half of a token contraction (x 4 waves = partials)
-
-// one contraction and its sums: M, v as k_tn_reduce writes them
-template <int D>
-hla_status tn_product(hla_handle* hd, hipStream_t s, View A, View Bv, int diag, float* M, float* v) {
-  const Geom& g = hd->g;
-  const int64_t subtiles = static_cast<int64_t>((g.N + 63) / 64) * g.B * g.H;
-  const int blocks = static_cast<int>(std::min<int64_t>(kTnBlocks, (subtiles + 3) / 4));
-  HLA_TRY(launch(hd, "vmod_weight_grads_gemm", k_tn_mfma<D>, dim3(blocks, D / 64), dim3(256), TnSmem<D>::kTotal, s,
-                 g, A, Bv, hd->vmod_wg_partial));
-  return launch(hd, "vmod_weight_grads_reduce", k_tn_reduce<D>, dim3(D * D / 256), dim3(256), 0, s,
-                static_cast<const float*>(hd->vmod_wg_partial), blocks, diag, M, v);
-}
+constexpr int kTnBlocks = 128;  // workgroups (and partials) per row half of a token contraction
 
 template <int D>
 hla_status weight_grads_t(hla_handle* hd, const hla_call_args& a) {
   const Geom& g = hd->g;
   const VmodFactors f = factor_arrays(hd);
+  TnJobs jobs;
   for (int m = 0; m < 2; ++m) {
     const hla_vmod_weight_grads& o = hd->vmod_wg_out[m];
-    HLA_TRY(tn_product<D>(hd, a.stream, vmod_view(f.dU[m], g), vmod_view(f.G[m], g), 0, o.dW2, o.db2));
-    HLA_TRY(tn_product<D>(hd, a.stream, vmod_view(f.dH[m], g), m == 0 ? vmod_view(hd->vmod_T, g) : a.V, 0, o.dW1, o.db1));
-    HLA_TRY(tn_product<D>(hd, a.stream, vmod_view(f.DM[m], g), vmod_view(f.Uh[m], g), 1, o.dgamma, o.dbeta));
+    jobs.j[3 * m + 0] = TnJob{vmod_view(f.dU[m], g), vmod_view(f.G[m], g), o.dW2, o.db2, 0};
+    jobs.j[3 * m + 1] = TnJob{vmod_view(f.dH[m], g), m == 0 ? vmod_view(hd->vmod_T, g) : a.V, o.dW1, o.db1, 0};
+    jobs.j[3 * m + 2] = TnJob{vmod_view(f.DM[m], g), vmod_view(f.Uh[m], g), o.dgamma, o.dbeta, 1};
   }
-  return HLA_OK;
+  const int64_t subtiles = static_cast<int64_t>((g.N + 63) / 64) * g.B * g.H;
+  const int blocks = static_cast<int>(std::min<int64_t>(kTnBlocks, (subtiles + 3) / 4));
+  HLA_TRY(launch(hd, "vmod_weight_grads_gemm", k_tn_mfma<D>, dim3(blocks, D / 64, kTnJobs), dim3(256),
+                 TnSmem<D>::kTotal, a.stream, g, jobs, hd->vmod_wg_partial));
+  return launch(hd, "vmod_weight_grads_reduce", k_tn_reduce<D>, dim3(D * D / 256, kTnJobs), dim3(256), 0, a.stream,
+                static_cast<const float*>(hd->vmod_wg_partial), blocks, jobs);
 }
 
 template <int D>
@@ -1011,7 +1021,7 @@ hla_status vmod_mfma_weight_grads(hla_handle* hd, const hla_call_args& a) {
 // floats the factor arrays and the partials of the contractions need
 int64_t vmod_mfma_factor_floats(const hla_handle* hd) { return 5 * hd->max_th * hd->g.d; }  // ten bf16 arrays
 int64_t vmod_mfma_partial_floats(const hla_handle* hd) {
-  return static_cast<int64_t>(kTnBlocks) * 4 * (hd->g.d / 64) * (64 * hd->g.d + 64);
+  return static_cast<int64_t>(kTnJobs) * kTnBlocks * (hd->g.d / 64) * (64 * hd->g.d + 64);
 }
 hla_status vmod_mfma_add_value_grads(hla_handle* hd, const hla_call_args& a) {
   return hd->g.d == 64 ? add_t<64>(hd, a) : add_t<128>(hd, a);
