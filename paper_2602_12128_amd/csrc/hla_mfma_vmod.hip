@@ -164,13 +164,15 @@ struct SavedTile {
 
 // Per-token factors of the maps' weight gradients, written by the backward kernel when they are
 // asked for: bf16 [token-heads][D] arrays per map m (nullptr: not wanted).  With them
-//   dW2 = G^T dU, db2 = sum dU;  dW1 = X^T dH, db1 = sum dH;  dgamma = diag(DM^T Uh), dbeta = sum DM.
+//   dW2 = G^T dU, db2 = sum dU;  dW1 = X^T dH, db1 = sum dH.
+// The LayerNorm's dgamma = sum over tokens of dm * u-hat and dbeta = sum of dm (dm: gradient w.r.t.
+// the map's output) need no arrays: the backward kernel adds them up per lane as it goes and
+// leaves one partial per workgroup in gb_part ([workgroup][dgamma | dbeta][D] floats).
 struct VmodFactors {
   bf16_t* dU[2];   // gradient w.r.t. the second layer's output
   bf16_t* dH[2];   // gradient w.r.t. the first layer's output
   bf16_t* G[2];    // GELU(h)
-  bf16_t* DM[2];   // gradient w.r.t. the map's output
-  bf16_t* Uh[2];   // u-hat
+  float* gb_part;
 };
 
 // eight fp32 values -> a 16-byte piece of a bf16 row
@@ -453,13 +455,15 @@ __global__ __launch_bounds__(WAVES * 64) void k_vmod_fwd_mfma(Geom g, const unsi
 // u-hat (1) and of the other map's (2, both packed fp16).  Only the result stays in registers; the
 // second pass must really load again (its loader is handed pass = 1 so that it can use an address
 // the compiler cannot match with the first pass's).
-// fDU / fDM / fUh: this lane's token rows of the factor arrays (see VmodFactors; + 8 gl already
-// applied), or nullptr.
-template <int D, class Load>
+// fDU: this lane's token row of that factor array (see VmodFactors; + 8 gl already applied), or
+// nullptr.  ag / ab (D / 2 entries; 1 entry: no sums wanted): the lane's running sums of dm * u-hat and of dm over its
+// tokens, entry 8 ks + j for channel 16 ks + 8 gl + j; `live` is 1 for a token of the sequence
+// and 0 for the padding of a ragged tile, whose rows must not be counted.
+template <int D, int NA, class Load>
 __device__ __forceinline__ float norm_backward(const unsigned char* wm_self, const unsigned char* wm_other,
                                                int gl, Load&& load, float rstd, u32x4 (&dub)[D / 16],
-                                               bf16_t* fDU = nullptr, bf16_t* fDM = nullptr,
-                                               bf16_t* fUh = nullptr) {
+                                               bf16_t* fDU, float (&ag)[NA], float (&ab)[NA], float live) {
+  static_assert(NA == D / 2 || NA == 1, "the lane's 64 channels, or no sums wanted");
   using SM = VSmem<D>;
   constexpr int NKS = D / 16;
   // a pass requests all its pieces before it looks at the first one: one memory round trip per
@@ -527,10 +531,14 @@ __device__ __forceinline__ float norm_backward(const unsigned char* wm_self, con
     for (int j = 0; j < 8; ++j) tv[j] = __builtin_fmaf(gg[j], inv, -a) - uh[j] * bq;
 #pragma unroll
     for (int p = 0; p < 4; ++p) dub[ks][p] = __builtin_bit_cast(uint32_t, to_f16x2(tv[2 * p], tv[2 * p + 1]));
-    if (fDU != nullptr) {  // (all three or none)
-      *reinterpret_cast<u32x4*>(fDU + 16 * ks) = pack8(tv, rstd * nrm);
-      *reinterpret_cast<u32x4*>(fDM + 16 * ks) = pack8(dmv, 1.0f);
-      *reinterpret_cast<u32x4*>(fUh + 16 * ks) = pack8(uh, 1.0f);
+    if (fDU != nullptr) *reinterpret_cast<u32x4*>(fDU + 16 * ks) = pack8(tv, rstd * nrm);
+    if constexpr (NA == D / 2) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const float dl = dmv[j] * live;
+        ab[8 * ks + j] += dl;
+        ag[8 * ks + j] = __builtin_fmaf(dl, uh[j], ag[8 * ks + j]);
+      }
     }
   }
   return rstd * nrm;
@@ -643,6 +651,13 @@ struct VSmemB {
   static constexpr int kOtherVec = VSmem<D>::kMap;            // the other map's four vectors
   static constexpr int kTiles = kOtherVec + 4 * D * 4;
   static constexpr int total(int waves) { return kTiles + waves * RowTile<D, kRowsOutB>::kBytes; }
+  // the factor-writing form ends with the sums of dgamma and dbeta over lanes and waves: a
+  // [D][33] float tile per wave and 2 x D floats per wave (one workgroup per compute unit)
+  static constexpr int kSumTile = D * 33;
+  static constexpr int total_factors(int waves) {
+    const int sums = (waves * kSumTile + 2 * waves * D) * 4;
+    return sums > total(waves) ? sums : total(waves);
+  }
 };
 template <int D, int WAVES, bool FACTORS, int MAP>
 __global__ __launch_bounds__(WAVES * 64, FACTORS ? 1 : 2) void k_vmod_bwd_map(Geom g, const unsigned char* __restrict__ wpk,
@@ -687,6 +702,10 @@ __global__ __launch_bounds__(WAVES * 64, FACTORS ? 1 : 2) void k_vmod_bwd_map(Ge
   const int stride = gridDim.x * WAVES;
   const int lane16 = lane * 16;
   const View& X = MAP == 0 ? Tin : V;
+  // FACTORS: the lane's sums of dm * u-hat and of dm over its tokens (see norm_backward)
+  float ag[FACTORS ? D / 2 : 1], ab[FACTORS ? D / 2 : 1];
+#pragma unroll
+  for (int i = 0; i < (FACTORS ? D / 2 : 1); ++i) ag[i] = ab[i] = 0.0f;
   for (int tile = blockIdx.x * WAVES + wave; tile < tw.total; tile += stride) {
     int b, h, n0;
     tw.decode(tile, b, h, n0);
@@ -707,8 +726,8 @@ __global__ __launch_bounds__(WAVES * 64, FACTORS ? 1 : 2) void k_vmod_bwd_map(Ge
     u32x4 x[NKS];  // the map's input rows, for the first layer's recomputation
     load_row<D>(X, b, h, n0 + r, g.N, gl, x);
     u32x4 du[NKS];
-    const float sc = norm_backward<D>(smem, wm_other, gl, loader, rstd, du, frow_of(fac.dU[MAP]),
-                                      frow_of(fac.DM[MAP]), frow_of(fac.Uh[MAP]));
+    const float sc = norm_backward<D>(smem, wm_other, gl, loader, rstd, du, frow_of(fac.dU[MAP]), ag, ab,
+                                      frow >= 0 ? 1.0f : 0.0f);
     __builtin_amdgcn_sched_barrier(0);
     f32x16 dx[NRB];
     map_backward<D>(smem, a_off, t_off, gl, x, du, dx, frow_of(fac.G[MAP]), frow_of(fac.dH[MAP]), sc);
@@ -731,6 +750,64 @@ __global__ __launch_bounds__(WAVES * 64, FACTORS ? 1 : 2) void k_vmod_bwd_map(Ge
       });
     }
   }
+  if constexpr (FACTORS) {
+    // The workgroup's share of dgamma and dbeta: per wave the 32 token lanes of a channel are added
+    // in lane order through a [channel][33] LDS tile (the weights are done with), then the four
+    // waves in wave order; one partial per workgroup.
+    constexpr int kTile = SB::kSumTile;
+    __syncthreads();
+    float* red = reinterpret_cast<float*>(smem) + wave * kTile;
+    float* wsum = reinterpret_cast<float*>(smem) + WAVES * kTile;  // [2][WAVES][D]
+    auto wave_sum = [&](const float (&src)[FACTORS ? D / 2 : 1], int which) {
+#pragma unroll
+      for (int i = 0; i < D / 2; ++i) red[(16 * (i / 8) + 8 * gl + i % 8) * 33 + r] = src[i];
+      wave_lds_sync();
+      for (int c = lane; c < D; c += kWave) {
+        float sum = 0.0f;
+#pragma unroll
+        for (int k = 0; k < 32; ++k) sum += red[c * 33 + k];
+        wsum[(which * WAVES + wave) * D + c] = sum;
+      }
+      wave_lds_sync();
+    };
+    wave_sum(ag, 0);
+    wave_sum(ab, 1);
+    __syncthreads();
+    for (int i = threadIdx.x; i < 2 * D; i += WAVES * 64) {
+      const int which = i / D, c = i % D;
+      float sum = wsum[(which * WAVES) * D + c];
+#pragma unroll
+      for (int w = 1; w < WAVES; ++w) sum += wsum[(which * WAVES + w) * D + c];
+      fac.gb_part[(static_cast<int64_t>(blockIdx.x) * 2 + which) * D + c] = sum;
+    }
+  }
+}
+
+// Adds the `nparts` per-workgroup partials of dgamma and dbeta (see VmodFactors) in order: eight
+// slices of the partials per output, each with sixteen loads in flight, then the slices in order.
+// grid (2 D / 32), block 256.
+__global__ __launch_bounds__(256) void k_vmod_gb_reduce(const float* __restrict__ part, int nparts, int D,
+                                                        float* __restrict__ dgamma, float* __restrict__ dbeta) {
+  __shared__ float sh[8][32];
+  const int o = blockIdx.x * 32 + threadIdx.x % 32, slice = threadIdx.x / 32;  // o = which * D + c
+  const int per = (nparts + 7) / 8;
+  const int p0 = slice * per, p1 = p0 + per < nparts ? p0 + per : nparts;
+  float sum = 0.0f;
+  for (int p = p0; p < p1; p += 16) {
+    float ld[16];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) ld[k] = p + k < p1 ? part[static_cast<int64_t>(p + k) * 2 * D + o] : 0.0f;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) sum += ld[k];
+  }
+  sh[slice][threadIdx.x % 32] = sum;
+  __syncthreads();
+  if (slice == 0) {
+    float t = sh[0][threadIdx.x];
+#pragma unroll
+    for (int k = 1; k < 8; ++k) t += sh[k][threadIdx.x];
+    (o < D ? dgamma : dbeta)[o % D] = t;
+  }
 }
 
 // C[i][j] = sum over tokens of A[t][i] B[t][j] and z[i] = sum over tokens of A[t][i] for two bf16
@@ -748,12 +825,11 @@ struct TnSmem {
 };
 // The token contractions of one backward as a list: one launch forms them all (blockIdx.z picks
 // the job), a second one adds up the partials of each.
-constexpr int kTnJobs = 6;
+constexpr int kTnJobs = 4;
 struct TnJob {
   View A, Bv;
   float* M;
   float* v;
-  int diag;
 };
 struct TnJobs {
   TnJob j[kTnJobs];
@@ -850,14 +926,13 @@ __global__ __launch_bounds__(256) void k_tn_mfma(Geom g, TnJobs jobs, float* __r
   for (int k = threadIdx.x; k < PW; k += 256) out[k] = ((all[k] + all[PW + k]) + all[2 * PW + k]) + all[3 * PW + k];
 }
 
-// Adds the `nparts` partials of k_tn_mfma in order.  diag = 0: M[j * D + i] = C[i][j] (the
-// transpose: the products are formed with the gradient as the A operand) and v[i] = z[i];
-// diag = 1: M[i] = C[i][i], v[i] = z[i].  grid (D * D / 256, jobs), block 256.
+// Adds the `nparts` partials of k_tn_mfma in order: M[j * D + i] = C[i][j] (the transpose: the
+// products are formed with the gradient as the A operand) and v[i] = z[i].
+// grid (D * D / 256, jobs), block 256.
 template <int D>
 __global__ void k_tn_reduce(const float* __restrict__ part, int nparts, TnJobs jobs) {
   constexpr int HALVES = D / 64;
   constexpr int64_t PW = 64 * D + 64;
-  const int diag = jobs.j[blockIdx.y].diag;
   float* __restrict__ M = jobs.j[blockIdx.y].M;
   float* __restrict__ v = jobs.j[blockIdx.y].v;
   const int idx = blockIdx.x * 256 + threadIdx.x;  // i * D + j
@@ -875,10 +950,7 @@ __global__ void k_tn_reduce(const float* __restrict__ part, int nparts, TnJobs j
     }
     return s;
   };
-  if (!diag || i == j) {
-    const float s = sum((i % 64) * D + j);
-    if (diag) M[i] = s; else M[j * D + i] = s;
-  }
+  M[j * D + i] = sum((i % 64) * D + j);
   if (j == 0) v[i] = sum(64 * D + i % 64);
 }
 
@@ -891,9 +963,9 @@ hla_status prepare_t() {
   HLA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_vmod_bwd_map<D, kWavesV, false, 1>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, VSmemB<D>::total(kWavesV)));
   HLA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_vmod_bwd_map<D, kWavesV, true, 0>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, VSmemB<D>::total(kWavesV)));
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, VSmemB<D>::total_factors(kWavesV)));
   HLA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_vmod_bwd_map<D, kWavesV, true, 1>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, VSmemB<D>::total(kWavesV)));
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, VSmemB<D>::total_factors(kWavesV)));
   HLA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_tn_mfma<D>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, TnSmem<D>::kTotal));
   return HLA_OK;
@@ -916,18 +988,19 @@ hla_status forward_t(hla_handle* hd, const hla_call_args& a) {
                 hd->vmod_ln_eps, vmod_view(hd->vmod_T, g), a.V, a.O, hd->vmod_wpk + vmod_mfma_packed_bytes(hd));
 }
 
-// the ten factor arrays inside hd->vmod_wg_rows (bf16 [max_th][d] each)
+// the six factor arrays inside hd->vmod_wg_rows (bf16 [max_th][d] each); the workgroups' partial
+// sums of dgamma and dbeta go to the head of the contractions' partial buffer, which is free while
+// the backward kernels run
 VmodFactors factor_arrays(const hla_handle* hd) {
   VmodFactors f;
   bf16_t* base = reinterpret_cast<bf16_t*>(hd->vmod_wg_rows);
   const int64_t per = hd->max_th * hd->g.d;
   for (int m = 0; m < 2; ++m) {
-    f.dU[m] = base + (5 * m + 0) * per;
-    f.dH[m] = base + (5 * m + 1) * per;
-    f.G[m] = base + (5 * m + 2) * per;
-    f.DM[m] = base + (5 * m + 3) * per;
-    f.Uh[m] = base + (5 * m + 4) * per;
+    f.dU[m] = base + (3 * m + 0) * per;
+    f.dH[m] = base + (3 * m + 1) * per;
+    f.G[m] = base + (3 * m + 2) * per;
   }
+  f.gb_part = hd->vmod_wg_partial;
   return f;
 }
 
@@ -940,10 +1013,14 @@ hla_status backward_map_t(hla_handle* hd, const hla_call_args& a, View out) {
   const int grid = static_cast<int>(std::min<int64_t>(2 * compute_units(), (tiles + kWavesV - 1) / kWavesV));
   const unsigned char* saved = hd->vmod_wpk + vmod_mfma_packed_bytes(hd);
   const char* name = MAP == 0 ? "vmod_backward" : "vmod_backward_value";
-  if (hd->vmod_wg_on)
-    return launch(hd, name, k_vmod_bwd_map<D, kWavesV, true, MAP>, dim3(grid), dim3(kWavesV * 64),
-                  VSmemB<D>::total(kWavesV), a.stream, g, static_cast<const unsigned char*>(hd->vmod_wpk),
-                  vmod_view(hd->vmod_T, g), a.V, a.dO, out, saved, factor_arrays(hd));
+  if (hd->vmod_wg_on) {
+    HLA_TRY(launch(hd, name, k_vmod_bwd_map<D, kWavesV, true, MAP>, dim3(grid), dim3(kWavesV * 64),
+                   VSmemB<D>::total_factors(kWavesV), a.stream, g, static_cast<const unsigned char*>(hd->vmod_wpk),
+                   vmod_view(hd->vmod_T, g), a.V, a.dO, out, saved, factor_arrays(hd)));
+    const hla_vmod_weight_grads& o = hd->vmod_wg_out[MAP];
+    return launch(hd, "vmod_weight_grads_norm", k_vmod_gb_reduce, dim3(2 * D / 32), dim3(256), 0, a.stream,
+                  static_cast<const float*>(hd->vmod_wg_partial), grid, D, o.dgamma, o.dbeta);
+  }
   return launch(hd, name, k_vmod_bwd_map<D, kWavesV, false, MAP>, dim3(grid), dim3(kWavesV * 64),
                 VSmemB<D>::total(kWavesV), a.stream, g, static_cast<const unsigned char*>(hd->vmod_wpk),
                 vmod_view(hd->vmod_T, g), a.V, a.dO, out, saved, VmodFactors{});
@@ -962,9 +1039,8 @@ hla_status weight_grads_t(hla_handle* hd, const hla_call_args& a) {
   TnJobs jobs;
   for (int m = 0; m < 2; ++m) {
     const hla_vmod_weight_grads& o = hd->vmod_wg_out[m];
-    jobs.j[3 * m + 0] = TnJob{vmod_view(f.dU[m], g), vmod_view(f.G[m], g), o.dW2, o.db2, 0};
-    jobs.j[3 * m + 1] = TnJob{vmod_view(f.dH[m], g), m == 0 ? vmod_view(hd->vmod_T, g) : a.V, o.dW1, o.db1, 0};
-    jobs.j[3 * m + 2] = TnJob{vmod_view(f.DM[m], g), vmod_view(f.Uh[m], g), o.dgamma, o.dbeta, 1};
+    jobs.j[2 * m + 0] = TnJob{vmod_view(f.dU[m], g), vmod_view(f.G[m], g), o.dW2, o.db2};
+    jobs.j[2 * m + 1] = TnJob{vmod_view(f.dH[m], g), m == 0 ? vmod_view(hd->vmod_T, g) : a.V, o.dW1, o.db1};
   }
   const int64_t subtiles = static_cast<int64_t>((g.N + 63) / 64) * g.B * g.H;
   const int blocks = static_cast<int>(std::min<int64_t>(kTnBlocks, (subtiles + 3) / 4));
@@ -1019,7 +1095,7 @@ hla_status vmod_mfma_weight_grads(hla_handle* hd, const hla_call_args& a) {
   return hd->g.d == 64 ? weight_grads_t<64>(hd, a) : weight_grads_t<128>(hd, a);
 }
 // floats the factor arrays and the partials of the contractions need
-int64_t vmod_mfma_factor_floats(const hla_handle* hd) { return 5 * hd->max_th * hd->g.d; }  // ten bf16 arrays
+int64_t vmod_mfma_factor_floats(const hla_handle* hd) { return 3 * hd->max_th * hd->g.d; }  // six bf16 arrays
 int64_t vmod_mfma_partial_floats(const hla_handle* hd) {
   return static_cast<int64_t>(kTnJobs) * kTnBlocks * (hd->g.d / 64) * (64 * hd->g.d + 64);
 }

@@ -80,6 +80,9 @@ def test_switching_the_modulation_off_and_on():
     (torch.float32, hla.HLA_PATH_GENERIC, 2, 12, 64, 1, 3, 150, 1e-4),
     (torch.bfloat16, hla.HLA_PATH_MFMA, 3, 6, 128, 1, 2, 700, 2e-2),
     (torch.bfloat16, hla.HLA_PATH_MFMA, 2, 12, 64, 2, 3, 333, 2e-2),
+    # mostly padding in the last tile: rows that are not tokens must not reach the sums over tokens
+    (torch.bfloat16, hla.HLA_PATH_MFMA, 3, 6, 128, 1, 2, 40, 2e-2),
+    (torch.bfloat16, hla.HLA_PATH_MFMA, 3, 6, 64, 2, 1, 33, 2e-2),
 ])
 def test_modulation_weight_gradients(dtype, path, F, dphi, d, B, H, N, tol):
     """Gradients of the two maps' own weights (summed over all tokens of all heads) next to the
