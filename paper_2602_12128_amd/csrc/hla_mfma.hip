@@ -22,7 +22,17 @@ using namespace mf;
 constexpr int kStaggerCore = 5;    // start-up stagger unit of the two core backward kernels (see stagger_start)
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
-constexpr int kQueryTarget = 496;  // workgroups aimed at by the query kernel: two per CU, one resident round
+// k_query: with a state of 64 rows the workgroup keeps the state's operand image in LDS and three
+// workgroups share a compute unit; with more rows the image stays in registers (an LDS copy would
+// not buy a third wave per SIMD) and two do.  The grid aims at one resident round.
+template <class SY>
+constexpr bool query_image_in_lds() {
+  return SY::MP <= 64;
+}
+template <class SY>
+constexpr int query_target() {
+  return query_image_in_lds<SY>() ? 768 : 496;
+}
 constexpr int kMinChunk = 256;     // smallest chunk pick_chunk returns
 constexpr int kCausalChunk = 256;  // tokens per chunk of the causal scan: eight 32-token tiles
 // (128-token chunks, one tile per wave of a four-wave workgroup and two workgroups per compute
@@ -452,31 +462,71 @@ __global__ __launch_bounds__(256) void k_reduce(Geom g, const int32_t* __restric
   }
 }
 
+// A block-wide copy of BYTES (a multiple of 16) from global memory to LDS in two halves: request()
+// puts the loads in flight, commit() writes what arrived to LDS.  Kernels request everything their
+// start-up needs from memory in one go and only then consume it, so that the start-up costs one
+// round trip to memory instead of one per item.
+template <int BYTES, int THREADS>
+struct ImageCopy {
+  static constexpr int N16 = BYTES / 16, N = (N16 + THREADS - 1) / THREADS;
+  u32x4 v[N];
+  __device__ __forceinline__ void request(const unsigned char* src) {
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+      const int i = threadIdx.x + k * THREADS;
+      if (N16 % THREADS == 0 || i < N16) v[k] = reinterpret_cast<const u32x4*>(src)[i];
+    }
+  }
+  __device__ __forceinline__ void commit(unsigned char* dst) const {
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+      const int i = threadIdx.x + k * THREADS;
+      if (N16 % THREADS == 0 || i < N16) reinterpret_cast<u32x4*>(dst)[i] = v[k];
+    }
+  }
+};
+
 // ---- k_query ----------------------------------------------------------------------------------
 // grid (blocks of pick_query_block tokens, H), block 256.  Wave w serves 32-token tiles w, w+4, ..;
 // lane (r, gl): token r of the tile, slot half gl (gl = 1 works on the reversed feature vector).
 template <class SY, int D>
-__global__ __launch_bounds__(kThreads) void k_query(Geom g, const BlockEnt* __restrict__ blocks,
+__global__ __launch_bounds__(kThreads, query_image_in_lds<SY>() ? 3 : 2) void k_query(Geom g, const BlockEnt* __restrict__ blocks,
                                                     const float* __restrict__ feat,
                                                     const unsigned char* __restrict__ ops, View O,
                                                     float* __restrict__ den) {
   using SL = StateLayout<SY, D>;
   constexpr int SP = SY::SP, MP = SY::MP, DP = SY::DPHI;
   constexpr int NRB = D / 32, NKS = MP / 16;
-  __shared__ __align__(16) unsigned char smem[kWaves * RowTile<D>::kBytes];
+  // The operand image of the state (rows = channels): shared by the workgroup's waves through LDS
+  // and read per product (in registers it would cost 64 of them per lane and one of the three
+  // waves a SIMD holds of this kernel), or in registers (see query_image_in_lds).
+  constexpr bool kImgLds = query_image_in_lds<SY>();
+  constexpr int kImgBytes = kImgLds ? NRB * NKS * 64 * 16 : 0;
+  __shared__ __align__(16) unsigned char smem[kImgBytes + kWaves * RowTile<D>::kBytes];
   const int lane = threadIdx.x % kWave, wave = wave_index();
-  unsigned char* tile = smem + wave * RowTile<D>::kBytes;
+  unsigned char* tile = smem + kImgBytes + wave * RowTile<D>::kBytes;
   const int r = lane % 32, gl = lane / 32;
   const BlockEnt e = blocks[blockIdx.x];
   const int h = blockIdx.y;
   const int64_t u = static_cast<int64_t>(e.seq) * g.H + h;
   const u32x4* opA = reinterpret_cast<const u32x4*>(ops + u * SL::kOpBytes);
   const float* zslot = reinterpret_cast<const float*>(ops + u * SL::kOpBytes + 2 * SL::kOpElems * 2) + gl * SP;
-  u32x4 a[NRB][NKS];
+  u32x4 areg[kImgLds ? 1 : NRB * NKS];
+  if constexpr (kImgLds) {
+    ImageCopy<NRB * NKS * 64 * 16, kThreads> img;
+    img.request(reinterpret_cast<const unsigned char*>(opA));
+    img.commit(smem);
+    __syncthreads();
+  } else {
 #pragma unroll
-  for (int rb = 0; rb < NRB; ++rb)
-#pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) a[rb][ks] = opA[(rb * NKS + ks) * 64 + lane];
+    for (int k = 0; k < NRB * NKS; ++k) areg[k] = opA[k * 64 + lane];
+  }
+  auto state_op = [&](int rb, int ks) -> u32x4 {
+    if constexpr (kImgLds)
+      return reinterpret_cast<const u32x4*>(smem)[(rb * NKS + ks) * 64 + lane];
+    else
+      return areg[rb * NKS + ks];
+  };
   // The normaliser vector of this lane's half: in registers, or -- when the state has more than 64
   // rows and the registers would no longer allow two waves per SIMD -- in LDS, read per tile.
   constexpr bool kZInLds = SP > 32;
@@ -541,7 +591,7 @@ __global__ __launch_bounds__(kThreads) void k_query(Geom g, const BlockEnt* __re
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[rb][i] = 0.0f;
 #pragma unroll
-      for (int ks = 0; ks < NKS; ++ks) acc[rb] = mfma32(a[rb][ks], b[ks], acc[rb]);
+      for (int ks = 0; ks < NKS; ++ks) acc[rb] = mfma32(state_op(rb, ks), b[ks], acc[rb]);
     }
     store_rows_bf16<D>(acc, inv, lane, tile, [&](int t) -> bf16_t* {
       return n0 + t < e.t1 ? O.row<bf16_t>(e.b, h, n0 + t) : nullptr;
@@ -791,30 +841,6 @@ __global__ __launch_bounds__(kScanThreads) void k_prefix_both(Geom g, const int3
     prefix_rows_body<SY, D, REVERSE>(blockIdx.z - za, g, seq_chunk_off, partial, partial_stride, rows, cm,
                                      chunk_decay, rows_stride, img_off);
 }
-
-// A block-wide copy of BYTES (a multiple of 16) from global memory to LDS in two halves: request()
-// puts the loads in flight, commit() writes what arrived to LDS.  Kernels request everything their
-// start-up needs from memory in one go and only then consume it, so that the start-up costs one
-// round trip to memory instead of one per item.
-template <int BYTES, int THREADS>
-struct ImageCopy {
-  static constexpr int N16 = BYTES / 16, N = (N16 + THREADS - 1) / THREADS;
-  u32x4 v[N];
-  __device__ __forceinline__ void request(const unsigned char* src) {
-#pragma unroll
-    for (int k = 0; k < N; ++k) {
-      const int i = threadIdx.x + k * THREADS;
-      if (N16 % THREADS == 0 || i < N16) v[k] = reinterpret_cast<const u32x4*>(src)[i];
-    }
-  }
-  __device__ __forceinline__ void commit(unsigned char* dst) const {
-#pragma unroll
-    for (int k = 0; k < N; ++k) {
-      const int i = threadIdx.x + k * THREADS;
-      if (N16 % THREADS == 0 || i < N16) reinterpret_cast<u32x4*>(dst)[i] = v[k];
-    }
-  }
-};
 
 // Waves per workgroup of k_query_causal: eight (two per SIMD, 256 registers each) where the live
 // set allows it, one query tile per wave; else four with two tiles each.
@@ -1624,11 +1650,11 @@ inline int pick_chunk(const hla_handle* hd, const Geom& g, int num_seqs) {
   return static_cast<int>(chunk);
 }
 
-inline int pick_query_block(const Geom& g, int num_seqs) {
-  // The query kernel keeps two workgroups per compute unit: aim at one resident round of them,
-  // in multiples of the 128 tokens a workgroup consumes per step.
+inline int pick_query_block(const Geom& g, int num_seqs, int target) {
+  // The query kernel keeps two or three workgroups per compute unit (`target` in all): aim at one
+  // resident round of them, in multiples of the 128 tokens a workgroup consumes per step.
   const int units = num_seqs * g.H > 0 ? num_seqs * g.H : 1;
-  const int per_unit = kQueryTarget / units > 0 ? kQueryTarget / units : 1;
+  const int per_unit = target / units > 0 ? target / units : 1;
   const int64_t mean_len = (static_cast<int64_t>(g.B) * g.N + num_seqs - 1) / (num_seqs > 0 ? num_seqs : 1);
   const int64_t blk = ((mean_len + per_unit - 1) / per_unit + 127) / 128 * 128;
   return static_cast<int>(blk < kMinQueryBlock ? kMinQueryBlock : blk);
@@ -2369,7 +2395,7 @@ hla_status forward_core(hla_handle* hd, const hla_call_args& a) {
   const int chunk = pick_chunk(hd, g, a.num_seqs);
   hla_token_table *chunks = nullptr, *qblocks = nullptr;
   HLA_TRY(get_table(hd, 0, chunk, s, &chunks));
-  HLA_TRY(get_table(hd, 1, pick_query_block(g, a.num_seqs), s, &qblocks));
+  HLA_TRY(get_table(hd, 1, pick_query_block(g, a.num_seqs, query_target<SY>()), s, &qblocks));
   if (static_cast<int64_t>(chunks->count) * g.H > hd->max_chunks * hd->cfg.max_heads)
     return HLA_ERR_INVALID_ARG;
   HLA_TRY(launch(hd, "mfma_state", k_state<SY, D>, dim3(chunks->count, g.H), dim3(kThreads),
