@@ -1584,10 +1584,13 @@ __global__ __launch_bounds__(kThreads) void k_bwd_key(Geom g, const BlockEnt* __
 #pragma unroll
         for (int c = 0; c < DP; ++c) dk[f][c] = 0.0f;
       // chain rule in four quarters, the previous tile's outputs leaving in between
+      KeyGradAcc<SY> kacc;
+      kacc.clear();
       static_for<0, 4>([&](auto Q) {
         constexpr int qd = decltype(Q)::value;
         constexpr int NS = SY::NS, S0 = qd * ((NS + 3) / 4), S1 = (qd + 1) * ((NS + 3) / 4);
-        sym_key_monomials_grad_range<SY, S0, S1>(kk, ds, dk, gl);
+        sym_key_monomials_grad_range<SY, S0, S1>(kk, ds, dk, kacc, gl);
+        if constexpr (qd == 3) sym_key_monomials_grad_finish<SY>(kk, dk, kacc);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = qd * NST / 4; i < (qd + 1) * NST / 4; ++i) flush_piece(i);
@@ -2213,7 +2216,10 @@ __global__ __launch_bounds__(kWavesCK * 64) void k_cgrad_k(
         for (int f2 = 0; f2 < F; ++f2)
 #pragma unroll
           for (int c = 0; c < DP; ++c) dk[f2][c] = 0.0f;
-        sym_key_monomials_grad_range<SY, 0, SY::NS>(kk, ds, dk, gl);
+        KeyGradAcc<SY> kacc;
+        kacc.clear();
+        sym_key_monomials_grad_range<SY, 0, SY::NS>(kk, ds, dk, kacc, gl);
+        sym_key_monomials_grad_finish<SY>(kk, dk, kacc);
       }
       float other[F][DP];
 #pragma unroll

@@ -410,23 +410,46 @@ __device__ __forceinline__ void key_monomials_slots(const float (&k1)[DP], const
 
 // Chain rule of key_monomials_slots: every distinct ordering (a,b,c) of slot s feeds
 // dk1[a] += ds * k2_b k3_c, dk2[b] += ds * k1_a k3_c, dk3[c] += ds * k1_a k2_b.
-// Slots S0 .. S1-1 only, so that callers can interleave other work between ranges.
+// Evaluated through U[a][b] = sum over the orderings of ds * k3_c, which serves two of the three:
+//   dk1[a] = sum_b U[a][b] k2_b,   dk2[b] = sum_a U[a][b] k1_a,   dk3[c] += ds * (k1_a k2_b),
+// two multiply-adds per ordering plus 2 DP^2 at the end instead of three and three products.
+// Slots S0 .. S1-1 per call, so that callers can interleave other work between ranges; U is
+// cleared by the caller before the first range and folded in by key_monomials_grad_finish after
+// the last.
+constexpr bool sym3_pair_used(int dp, int a, int b) {  // does any slot have an ordering (a, b, .)?
+  for (int s = 0; s < sym3_num_mono(dp) / 2; ++s) {
+    const Perm3 p = sym3_perms(sym3_slot(dp, s));
+    for (int e = 0; e < p.n; ++e)
+      if (p.a[e] == a && p.b[e] == b) return true;
+  }
+  return false;
+}
 template <int DP, int S0, int S1>
 __device__ __forceinline__ void key_monomials_grad_range(const float (&k1)[DP], const float (&k2)[DP],
                                                          const float (&k3)[DP],
                                                          const float (&ds)[Sym3<DP>::SP],
-                                                         float (&dk1)[DP], float (&dk2)[DP],
-                                                         float (&dk3)[DP]) {
+                                                         float (&U)[DP][DP], float (&dk3)[DP]) {
   static_for<S0, (S1 < Sym3<DP>::NS ? S1 : Sym3<DP>::NS)>([&](auto S) {
     constexpr int s = decltype(S)::value;
     constexpr Tri t = sym3_slot(DP, s);
     constexpr Perm3 p = sym3_perms(t);
     static_for<0, p.n>([&](auto E) {
       constexpr int e = decltype(E)::value;
-      dk1[p.a[e]] += ds[s] * (k2[p.b[e]] * k3[p.c[e]]);
-      dk2[p.b[e]] += ds[s] * (k1[p.a[e]] * k3[p.c[e]]);
+      U[p.a[e]][p.b[e]] += ds[s] * k3[p.c[e]];
       dk3[p.c[e]] += ds[s] * (k1[p.a[e]] * k2[p.b[e]]);
     });
+  });
+}
+template <int DP>
+__device__ __forceinline__ void key_monomials_grad_finish(const float (&k1)[DP], const float (&k2)[DP],
+                                                          const float (&U)[DP][DP], float (&dk1)[DP],
+                                                          float (&dk2)[DP]) {
+  static_for<0, DP * DP>([&](auto AB) {
+    constexpr int a = decltype(AB)::value / DP, b = decltype(AB)::value % DP;
+    if constexpr (sym3_pair_used(DP, a, b)) {
+      dk1[a] += U[a][b] * k2[b];
+      dk2[b] += U[a][b] * k1[a];
+    }
   });
 }
 template <int DP>
@@ -435,7 +458,13 @@ __device__ __forceinline__ void key_monomials_grad(const float (&k1)[DP], const 
                                                    const float (&ds)[Sym3<DP>::SP],
                                                    float (&dk1)[DP], float (&dk2)[DP],
                                                    float (&dk3)[DP]) {
-  key_monomials_grad_range<DP, 0, Sym3<DP>::NS>(k1, k2, k3, ds, dk1, dk2, dk3);
+  float U[DP][DP];
+#pragma unroll
+  for (int a = 0; a < DP; ++a)
+#pragma unroll
+    for (int b = 0; b < DP; ++b) U[a][b] = 0.0f;
+  key_monomials_grad_range<DP, 0, Sym3<DP>::NS>(k1, k2, k3, ds, U, dk3);
+  key_monomials_grad_finish<DP>(k1, k2, U, dk1, dk2);
 }
 
 
@@ -610,14 +639,28 @@ __device__ __forceinline__ void sym_key_monomials_slots(const float (&k)[SY::F][
     });
   }
 }
-// chain rule of sym_key_monomials_slots over slots S0 .. S1-1
+// chain rule of sym_key_monomials_slots over slots S0 .. S1-1: clear a KeyGradAcc, call the ranges
+// in any split, then sym_key_monomials_grad_finish (three factors: see key_monomials_grad_range;
+// two factors: nothing is carried between the calls)
+template <class SY>
+struct KeyGradAcc {
+  static constexpr int N = SY::F == 3 ? SY::DPHI : 1;
+  float U[N][N];
+  __device__ __forceinline__ void clear() {
+#pragma unroll
+    for (int a = 0; a < N; ++a)
+#pragma unroll
+      for (int b = 0; b < N; ++b) U[a][b] = 0.0f;
+  }
+};
 template <class SY, int S0, int S1>
 __device__ __forceinline__ void sym_key_monomials_grad_range(const float (&k)[SY::F][SY::DPHI],
                                                              const float (&ds)[SY::SP],
-                                                             float (&dk)[SY::F][SY::DPHI], int gl) {
+                                                             float (&dk)[SY::F][SY::DPHI],
+                                                             KeyGradAcc<SY>& acc, int gl) {
   constexpr int DP = SY::DPHI;
   if constexpr (SY::F == 3) {
-    key_monomials_grad_range<DP, S0, S1>(k[0], k[1], k[2], ds, dk[0], dk[1], dk[2]);
+    key_monomials_grad_range<DP, S0, S1>(k[0], k[1], k[2], ds, acc.U, dk[2]);
   } else {
     const float fx = gl ? 0.0f : 1.0f;
     static_for<S0, (S1 < SY::NS ? S1 : SY::NS)>([&](auto S) {
@@ -632,6 +675,12 @@ __device__ __forceinline__ void sym_key_monomials_grad_range(const float (&k)[SY
       }
     });
   }
+}
+template <class SY>
+__device__ __forceinline__ void sym_key_monomials_grad_finish(const float (&k)[SY::F][SY::DPHI],
+                                                              float (&dk)[SY::F][SY::DPHI],
+                                                              const KeyGradAcc<SY>& acc) {
+  if constexpr (SY::F == 3) key_monomials_grad_finish<SY::DPHI>(k[0], k[1], acc.U, dk[0], dk[1]);
 }
 
 }  // namespace mf
