@@ -72,6 +72,38 @@ __global__ void k_feat_import(Geom g, View Q, View K, float* __restrict__ feat) 
   const int h = static_cast<int>(bh % g.H), b = static_cast<int>(bh / g.H);
   const T* q = Q.row<const T>(b, h, n);
   const T* k = K.row<const T>(b, h, n);
+  if constexpr (sizeof(T) == 2) {
+    // a pair of bf16 features per load and an 8-byte store per pair where the rows allow it: a
+    // pair is adjacent in both layouts of the workspace (see fidx), pair p + 1 sits `step` floats on
+    const bool pairs = g.dphi % 2 == 0 && ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k)) & 3) == 0;
+    if (pairs) {
+      const uint32_t* q2 = reinterpret_cast<const uint32_t*>(q);
+      const uint32_t* k2 = reinterpret_cast<const uint32_t*>(k);
+      float* dst = feat + g.fidx(th, 0);
+      const int step = g.feat_tiled ? 64 : 2, nq = g.dphi / 2, np = g.nfeat / 2;
+      // eight pairs' loads in flight before the first store (a load next to the store that needs
+      // it would cost a memory round trip per pair)
+      for (int p0 = 0; p0 < np; p0 += 8) {
+        uint32_t w[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const int p = p0 + i < np ? p0 + i : np - 1;
+          w[i] = p < nq ? q2[p] : k2[p - nq];
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) asm volatile("" : "+v"(w[i]));  // all eight are loaded here: the compiler may not sink a load to its store
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          if (p0 + i >= np) break;
+          float2 v;
+          v.x = __uint_as_float(w[i] << 16);
+          v.y = __uint_as_float(w[i] & 0xffff0000u);
+          *reinterpret_cast<float2*>(dst + static_cast<int64_t>(p0 + i) * step) = v;
+        }
+      }
+      return;
+    }
+  }
   for (int j = 0; j < g.dphi; ++j) feat[g.fidx(th, j)] = to_float(q[j]);
   for (int j = g.dphi; j < g.nfeat; ++j) feat[g.fidx(th, j)] = to_float(k[j - g.dphi]);
 }
@@ -92,12 +124,23 @@ __global__ void k_dfeat_export(Geom g, const float* __restrict__ dfeat, View dQ,
     if (pairs) {
       uint32_t* q2 = reinterpret_cast<uint32_t*>(q);
       uint32_t* k2 = reinterpret_cast<uint32_t*>(k);
-      for (int j = 0; j < g.dphi; j += 2)
-        q2[j / 2] = static_cast<uint32_t>(f32_to_bf16_bits(dfeat[g.fidx(th, j)])) |
-                    (static_cast<uint32_t>(f32_to_bf16_bits(dfeat[g.fidx(th, j + 1)])) << 16);
-      for (int j = g.dphi; j < g.nfeat; j += 2)
-        k2[(j - g.dphi) / 2] = static_cast<uint32_t>(f32_to_bf16_bits(dfeat[g.fidx(th, j)])) |
-                               (static_cast<uint32_t>(f32_to_bf16_bits(dfeat[g.fidx(th, j + 1)])) << 16);
+      const float* src = dfeat + g.fidx(th, 0);  // pair p: 8 bytes at src + p * step (see fidx)
+      const int step = g.feat_tiled ? 64 : 2, nq = g.dphi / 2, np = g.nfeat / 2;
+      for (int p0 = 0; p0 < np; p0 += 8) {  // eight pairs' loads in flight before the first store
+        float2 v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+          v[i] = *reinterpret_cast<const float2*>(src + static_cast<int64_t>(p0 + i < np ? p0 + i : np - 1) * step);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) asm volatile("" : "+v"(v[i].x), "+v"(v[i].y));  // as in k_feat_import
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          if (p0 + i >= np) break;
+          const uint32_t w = static_cast<uint32_t>(f32_to_bf16_bits(v[i].x)) |
+                             (static_cast<uint32_t>(f32_to_bf16_bits(v[i].y)) << 16);
+          if (p0 + i < nq) q2[p0 + i] = w; else k2[p0 + i - nq] = w;
+        }
+      }
       return;
     }
   }
